@@ -1,0 +1,483 @@
+/*
+ * dbp_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * Plain, slow, obviously-correct CPU oracle for the dithered-backprop hot path
+ * (Wiedemann et al., "Dithered backprop", arXiv 2004.04729).  It exists so that the
+ * HIP kernels can be checked element by element.  Only the tests, the smoke check and
+ * the benchmark's cpu_baseline leg may call it; it shares no code, header, table or
+ * helper with the GPU library and neither includes the other.
+ *
+ * What it computes, and where the paper defines it:
+ *   - NSD quantiser  q = Delta * floor((x + nu)/Delta + 1/2),  nu ~ U(-Delta/2, Delta/2)
+ *     on the open interval                                  (Sec. "Non-subtractive dithered
+ *     quantization", Eq. (nsd); applied to delta_z in Eq. (qdz)).
+ *   - the two backward products that consume q              (Eqs. (qda), (qdw)):
+ *         delta_a = W^T . q          delta_W = q . a^T
+ *     for fully connected layers, and their convolutional analogues ("analogous for
+ *     convolutional layers", Sec. "Dithered backpropagation").
+ *   - 8-bit mode: integer codes times int8 activations, exact int32 weight gradient
+ *     (Sec. "Quantizing forward pass": everything but the weight update in 8 bit).
+ *
+ * The paper fixes no random generator, no code width, no storage layout and no sparse
+ * format.  Those readings are stated where they are used below; they are spec decisions
+ * of this repository ("parity unpinned" against the paper: the hash constants, the
+ * 16-bit dither resolution, the multiply-by-reciprocal, the +-127 saturation and the
+ * tile layout are pinned only by frozen test vectors and by the statistical laws the
+ * paper does state).
+ *
+ * Precision: the quantiser's decision is taken in fp32 exactly as specified (one fused
+ * multiply-add, one floor) because it decides an integer; every product is accumulated
+ * in fp64 in natural index order; integer mode accumulates in int64 and checks int32.
+ *
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -fPIC -shared.  The OpenMP pragmas
+ * only distribute independent output rows over threads; no sum is reordered.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------------------
+ * Dither generator (spec decision; the paper only hints at a cheap congruential-style
+ * generator in Sec. "Computational complexity", item 2).
+ *
+ * Counter based: the dither of element g of a tensor depends only on (seed, g), so any
+ * traversal order, any sharding and any hardware give the same draw.
+ *
+ *   mix(x):   x ^= x>>16; x *= A; x ^= x>>15; x *= C; x ^= x>>16
+ *   k0 = mix(lo32(seed) ^ G);  k1 = mix(hi32(seed) + k0 + A)
+ *   H(seed,c): h = (lo32(c) ^ k0) * G;  h ^= h>>16;
+ *              h = (h + k1 + hi32(c)*C) * A;  h ^= h>>15;  h *= C;  h ^= h>>16
+ *   G = floor(2^32/phi), A = frac(sqrt 2)*2^32, C = frac(sqrt 3)*2^32  (all odd)
+ *
+ * One hash word serves two neighbouring elements: element g uses word H(seed, g>>1),
+ * the low 16 bits when g is even and the high 16 bits when g is odd.  With m those 16
+ * bits, u = (2m+1) * 2^-17 lies in [2^-17, 1-2^-17], is symmetric about 1/2 and never
+ * touches 0 or 1: u - 1/2 is nu/Delta on the OPEN interval (-1/2, 1/2) of Eq. (nsd).
+ * ---------------------------------------------------------------------------------- */
+#define DBP_G 0x9E3779B9u
+#define DBP_A 0x6A09E667u
+#define DBP_C 0xBB67AE85u
+
+static uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= DBP_A; x ^= x >> 15; x *= DBP_C; x ^= x >> 16;
+    return x;
+}
+
+uint32_t dbp_oracle_hash(uint64_t seed, uint64_t counter)
+{
+    uint32_t k0 = mix32((uint32_t)seed ^ DBP_G);
+    uint32_t k1 = mix32((uint32_t)(seed >> 32) + k0 + DBP_A);
+    uint32_t h = ((uint32_t)counter ^ k0) * DBP_G;
+    h ^= h >> 16;
+    h = (h + k1 + (uint32_t)(counter >> 32) * DBP_C) * DBP_A;
+    h ^= h >> 15;
+    h *= DBP_C;
+    h ^= h >> 16;
+    return h;
+}
+
+void dbp_oracle_keys(uint64_t seed, uint32_t *k0, uint32_t *k1)
+{
+    *k0 = mix32((uint32_t)seed ^ DBP_G);
+    *k1 = mix32((uint32_t)(seed >> 32) + *k0 + DBP_A);
+}
+
+/* u = nu/Delta + 1/2 for global element index g. */
+float dbp_oracle_dither_u(uint64_t seed, uint64_t g)
+{
+    uint32_t h = dbp_oracle_hash(seed, g >> 1);
+    uint32_t m = (g & 1u) ? (h >> 16) : (h & 0xFFFFu);
+    return (float)(2u * m + 1u) * 0x1p-17f;      /* exact: a 17-bit odd integer scaled */
+}
+
+/* ------------------------------------------------------------------------------------
+ * NSD quantiser, Eq. (nsd) / Eq. (qdz).
+ *
+ *   floor((x + nu)/Delta + 1/2) = floor(x/Delta + u),   u = nu/Delta + 1/2.
+ *
+ * Readings (the paper is silent): x/Delta is x * inv with inv = 1.0f/Delta rounded once;
+ * t = fma(x, inv, u) is ONE fp32 operation (single rounding), k = floor(t); k saturates
+ * to [-127, 127] (the paper reports <= 8 bit codes in all experiments, Sec. "Accuracy &
+ * Induced Sparsity"); a NaN t gives code 0.  q = k * Delta is never materialised.
+ * Algorithm 1 prints Q(delta_z) without the dither; Eq. (qdz) has it, and is followed.
+ * ---------------------------------------------------------------------------------- */
+typedef struct {
+    uint64_t nnz;            /* codes != 0                                   */
+    uint64_t n_saturated;    /* |floor(t)| > 127 before clamping (incl. Inf) */
+    uint64_t n_nonfinite;    /* inputs that are NaN or +-Inf                 */
+    int32_t  max_abs_code;   /* max |k| after clamping                       */
+    int32_t  pad_;
+} dbp_oracle_stats;
+
+void dbp_oracle_nsd(const float *delta, int64_t n, float step, uint64_t seed,
+                    uint64_t idx_base, int8_t *codes, dbp_oracle_stats *st)
+{
+    const float inv = 1.0f / step;
+    dbp_oracle_stats s;
+    memset(&s, 0, sizeof s);
+    for (int64_t j = 0; j < n; ++j) {
+        float x = delta[j];
+        float u = dbp_oracle_dither_u(seed, idx_base + (uint64_t)j);
+        float t = fmaf(x, inv, u);
+        float kf = floorf(t);
+        int k;
+        if (!isfinite(x)) s.n_nonfinite++;
+        if (isnan(t)) {
+            k = 0;
+        } else if (kf > 127.0f) {
+            k = 127;  s.n_saturated++;
+        } else if (kf < -127.0f) {
+            k = -127; s.n_saturated++;
+        } else {
+            k = (int)kf;
+        }
+        if (k != 0) s.nnz++;
+        int a = k < 0 ? -k : k;
+        if (a > s.max_abs_code) s.max_abs_code = a;
+        codes[j] = (int8_t)k;
+    }
+    if (st) *st = s;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Tile-sparse format (this repository's design; the paper only says "sparse tensors
+ * with low precision non-zero values").  The code plane [rows x cols] is cut, row by
+ * row, into tiles of 256 consecutive columns (the last tile of a row may be short);
+ * tiles_per_row = ceil(cols/256), tile t = row*tiles_per_row + col/256.  Per tile:
+ *   bitmap[4t + w]   bit b set  <=>  code at in-tile column 64w+b is nonzero
+ *   tile_nnz[t]      number of nonzero codes in the tile
+ *   entries[256t+i]  i < tile_nnz[t]: (in-tile column << 8) | (code & 0xFF), columns
+ *                    ascending.  Slots at and beyond tile_nnz[t] are left untouched.
+ * ---------------------------------------------------------------------------------- */
+void dbp_oracle_tile_format(const int8_t *codes, int64_t rows, int64_t cols,
+                            uint64_t *bitmap, uint16_t *tile_nnz, uint16_t *entries)
+{
+    int64_t tpr = (cols + 255) / 256;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t s = 0; s < tpr; ++s) {
+            int64_t t = r * tpr + s;
+            uint64_t w[4] = {0, 0, 0, 0};
+            int cnt = 0;
+            for (int c = 0; c < 256; ++c) {
+                int64_t col = s * 256 + c;
+                if (col >= cols) break;
+                int8_t k = codes[r * cols + col];
+                if (k != 0) {
+                    w[c >> 6] |= (uint64_t)1 << (c & 63);
+                    entries[t * 256 + cnt] = (uint16_t)((c << 8) | (uint8_t)k);
+                    cnt++;
+                }
+            }
+            for (int i = 0; i < 4; ++i) bitmap[t * 4 + i] = w[i];
+            tile_nnz[t] = (uint16_t)cnt;
+        }
+}
+
+/* Value of the quantised gradient element j: k*Delta from the codes, or (for the dense,
+ * undithered comparison of Eqs. (da),(dw)) the raw fp32 gradient. */
+static inline double qval(const int8_t *codes, const float *dense, double step, int64_t j)
+{
+    return codes ? (double)codes[j] * step : (double)dense[j];
+}
+
+/* ------------------------------------------------------------------------------------
+ * Fully connected layer, Eqs. (qda), (qdw).  Storage is batch-row-major:
+ *   Q [B x out],  W [out x in],  X [B x in]   (the paper's column-vector z = W a).
+ *   dX[b,i] = sum_o Q[b,o] W[o,i]          (delta_a = W^T . q)
+ *   dW[o,i] = sum_b Q[b,o] X[b,i]          (delta_W = q . a^T ; no 1/B factor)
+ * Zero q terms are skipped (they add exactly 0).  Either output may be NULL.
+ * Pass codes (+step) for the dithered path or dense for the plain backward pass.
+ * macs (nullable) returns the number of multiply-adds performed, the p_nz*m*k*n of
+ * Sec. "Computational complexity".
+ * ---------------------------------------------------------------------------------- */
+void dbp_oracle_linear_backward(const int8_t *codes, const float *dense, double step,
+                                const float *W, const float *X,
+                                int64_t B, int64_t in, int64_t out,
+                                double *dX, double *dW, int threads, uint64_t *macs)
+{
+    uint64_t n_mac = 0;
+    if (threads < 1) threads = 1;
+    if (dX) {
+        #pragma omp parallel for num_threads(threads) schedule(static) reduction(+:n_mac)
+        for (int64_t b = 0; b < B; ++b) {
+            double *row = dX + b * in;
+            for (int64_t i = 0; i < in; ++i) row[i] = 0.0;
+            for (int64_t o = 0; o < out; ++o) {
+                double q = qval(codes, dense, step, b * out + o);
+                if (q == 0.0) continue;
+                const float *w = W + o * in;
+                for (int64_t i = 0; i < in; ++i) row[i] += q * (double)w[i];
+                n_mac += (uint64_t)in;
+            }
+        }
+    }
+    if (dW) {
+        #pragma omp parallel for num_threads(threads) schedule(static) reduction(+:n_mac)
+        for (int64_t o = 0; o < out; ++o) {
+            double *row = dW + o * in;
+            for (int64_t i = 0; i < in; ++i) row[i] = 0.0;
+            for (int64_t b = 0; b < B; ++b) {
+                double q = qval(codes, dense, step, b * out + o);
+                if (q == 0.0) continue;
+                const float *x = X + b * in;
+                for (int64_t i = 0; i < in; ++i) row[i] += q * (double)x[i];
+                n_mac += (uint64_t)in;
+            }
+        }
+    }
+    if (macs) *macs = n_mac;
+}
+
+/* 8-bit mode weight gradient: dW32[o,i] = sum_b k[b,o] * x8[b,i], exact.  Returns the
+ * number of outputs that do not fit int32 (they are stored wrapped; callers treat a
+ * non-zero return as an error). */
+int64_t dbp_oracle_linear_dw_i8(const int8_t *codes, const int8_t *X8,
+                                int64_t B, int64_t in, int64_t out, int32_t *dW32, int threads)
+{
+    int64_t bad = 0;
+    if (threads < 1) threads = 1;
+    #pragma omp parallel for num_threads(threads) schedule(static) reduction(+:bad)
+    for (int64_t o = 0; o < out; ++o) {
+        int64_t *acc = (int64_t *)calloc((size_t)in, sizeof(int64_t));
+        for (int64_t b = 0; b < B; ++b) {
+            int64_t k = codes[b * out + o];
+            if (k == 0) continue;
+            const int8_t *x = X8 + b * in;
+            for (int64_t i = 0; i < in; ++i) acc[i] += k * (int64_t)x[i];
+        }
+        for (int64_t i = 0; i < in; ++i) {
+            if (acc[i] > INT32_MAX || acc[i] < INT32_MIN) bad++;
+            dW32[o * in + i] = (int32_t)acc[i];
+        }
+        free(acc);
+    }
+    return bad;
+}
+
+/* ------------------------------------------------------------------------------------
+ * 2-D convolution.  The paper gives no formula ("analogous"); this is the standard
+ * cross-correlation layer with zero padding:
+ *   Y[n,k,p,q] = sum_{c,r,s} W[k,c,r,s] * X[n,c, p*st + r - pad, q*st + s - pad]
+ * X [N,C,H,Wd], W [K,C,R,S], Y and its gradient Q [N,K,P,Q'],  P = (H+2pad-R)/st + 1.
+ * The backward products are the adjoints of that map (Eqs. (qda),(qdw) carried over):
+ *   dX[n,c,h,w]   = sum_{k,r,s} Q[n,k,p,q] W[k,c,r,s]   with h = p*st+r-pad, w = q*st+s-pad
+ *   dW[k,c,r,s]   = sum_{n,p,q} Q[n,k,p,q] X[n,c,p*st+r-pad,q*st+s-pad]   (zero outside)
+ * ---------------------------------------------------------------------------------- */
+void dbp_oracle_conv2d_forward(const float *X, const float *W, int64_t N, int64_t C,
+                               int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                               int64_t st, int64_t pad, double *Y)
+{
+    int64_t P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
+    for (int64_t n = 0; n < N; ++n)
+      for (int64_t k = 0; k < K; ++k)
+        for (int64_t p = 0; p < P; ++p)
+          for (int64_t q = 0; q < Q; ++q) {
+              double acc = 0.0;
+              for (int64_t c = 0; c < C; ++c)
+                for (int64_t r = 0; r < R; ++r)
+                  for (int64_t s = 0; s < S; ++s) {
+                      int64_t h = p * st + r - pad, w = q * st + s - pad;
+                      if (h < 0 || h >= H || w < 0 || w >= Wd) continue;
+                      acc += (double)W[((k * C + c) * R + r) * S + s] *
+                             (double)X[((n * C + c) * H + h) * Wd + w];
+                  }
+              Y[((n * K + k) * P + p) * Q + q] = acc;
+          }
+}
+
+void dbp_oracle_conv2d_backward(const int8_t *codes, const float *dense, double step,
+                                const float *W, const float *X,
+                                int64_t N, int64_t C, int64_t H, int64_t Wd,
+                                int64_t K, int64_t R, int64_t S, int64_t st, int64_t pad,
+                                double *dX, double *dW, int threads, uint64_t *macs)
+{
+    int64_t P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
+    uint64_t n_mac = 0;
+    if (threads < 1) threads = 1;
+    if (dX) {
+        #pragma omp parallel for num_threads(threads) schedule(dynamic, 1) reduction(+:n_mac)
+        for (int64_t n = 0; n < N; ++n) {
+            double *img = dX + n * C * H * Wd;
+            for (int64_t i = 0; i < C * H * Wd; ++i) img[i] = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+              for (int64_t p = 0; p < P; ++p)
+                for (int64_t q = 0; q < Q; ++q) {
+                    double g = qval(codes, dense, step, ((n * K + k) * P + p) * Q + q);
+                    if (g == 0.0) continue;
+                    for (int64_t c = 0; c < C; ++c)
+                      for (int64_t r = 0; r < R; ++r)
+                        for (int64_t s = 0; s < S; ++s) {
+                            int64_t h = p * st + r - pad, w = q * st + s - pad;
+                            if (h < 0 || h >= H || w < 0 || w >= Wd) continue;
+                            img[(c * H + h) * Wd + w] +=
+                                g * (double)W[((k * C + c) * R + r) * S + s];
+                        }
+                    n_mac += (uint64_t)(C * R * S);
+                }
+        }
+    }
+    if (dW) {
+        #pragma omp parallel for num_threads(threads) schedule(dynamic, 1) reduction(+:n_mac)
+        for (int64_t k = 0; k < K; ++k) {
+            double *flt = dW + k * C * R * S;
+            for (int64_t i = 0; i < C * R * S; ++i) flt[i] = 0.0;
+            for (int64_t n = 0; n < N; ++n)
+              for (int64_t p = 0; p < P; ++p)
+                for (int64_t q = 0; q < Q; ++q) {
+                    double g = qval(codes, dense, step, ((n * K + k) * P + p) * Q + q);
+                    if (g == 0.0) continue;
+                    for (int64_t c = 0; c < C; ++c)
+                      for (int64_t r = 0; r < R; ++r)
+                        for (int64_t s = 0; s < S; ++s) {
+                            int64_t h = p * st + r - pad, w = q * st + s - pad;
+                            if (h < 0 || h >= H || w < 0 || w >= Wd) continue;
+                            flt[(c * R + r) * S + s] +=
+                                g * (double)X[((n * C + c) * H + h) * Wd + w];
+                        }
+                    n_mac += (uint64_t)(C * R * S);
+                }
+        }
+    }
+    if (macs) *macs = n_mac;
+}
+
+/* 8-bit mode conv weight gradient, exact; same contract as dbp_oracle_linear_dw_i8. */
+int64_t dbp_oracle_conv2d_dw_i8(const int8_t *codes, const int8_t *X8,
+                                int64_t N, int64_t C, int64_t H, int64_t Wd,
+                                int64_t K, int64_t R, int64_t S, int64_t st, int64_t pad,
+                                int32_t *dW32, int threads)
+{
+    int64_t P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
+    int64_t bad = 0;
+    if (threads < 1) threads = 1;
+    #pragma omp parallel for num_threads(threads) schedule(dynamic, 1) reduction(+:bad)
+    for (int64_t k = 0; k < K; ++k) {
+        int64_t *acc = (int64_t *)calloc((size_t)(C * R * S), sizeof(int64_t));
+        for (int64_t n = 0; n < N; ++n)
+          for (int64_t p = 0; p < P; ++p)
+            for (int64_t q = 0; q < Q; ++q) {
+                int64_t g = codes[((n * K + k) * P + p) * Q + q];
+                if (g == 0) continue;
+                for (int64_t c = 0; c < C; ++c)
+                  for (int64_t r = 0; r < R; ++r)
+                    for (int64_t s = 0; s < S; ++s) {
+                        int64_t h = p * st + r - pad, w = q * st + s - pad;
+                        if (h < 0 || h >= H || w < 0 || w >= Wd) continue;
+                        acc[(c * R + r) * S + s] +=
+                            g * (int64_t)X8[((n * C + c) * H + h) * Wd + w];
+                    }
+            }
+        for (int64_t i = 0; i < C * R * S; ++i) {
+            if (acc[i] > INT32_MAX || acc[i] < INT32_MIN) bad++;
+            dW32[k * C * R * S + i] = (int32_t)acc[i];
+        }
+        free(acc);
+    }
+    return bad;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Single-output versions, for checking sampled outputs of problems too large to run in
+ * full.  Each is the defining sum of one output element, written in gather form
+ * (independently of the scatter loops above, which the tests compare them with).
+ * idx holds flat output indices; X8 non-NULL selects the integer weight gradient.
+ * ---------------------------------------------------------------------------------- */
+void dbp_oracle_linear_dx_at(const int8_t *codes, const float *dense, double step,
+                             const float *W, int64_t B, int64_t in, int64_t out,
+                             const int64_t *idx, int64_t n_idx, double *val)
+{
+    (void)B;
+    for (int64_t t = 0; t < n_idx; ++t) {
+        int64_t b = idx[t] / in, i = idx[t] % in;
+        double acc = 0.0;
+        for (int64_t o = 0; o < out; ++o)
+            acc += qval(codes, dense, step, b * out + o) * (double)W[o * in + i];
+        val[t] = acc;
+    }
+}
+
+void dbp_oracle_linear_dw_at(const int8_t *codes, const float *dense, double step,
+                             const float *X, const int8_t *X8, int64_t B, int64_t in, int64_t out,
+                             const int64_t *idx, int64_t n_idx, double *val)
+{
+    for (int64_t t = 0; t < n_idx; ++t) {
+        int64_t o = idx[t] / in, i = idx[t] % in;
+        double acc = 0.0;
+        for (int64_t b = 0; b < B; ++b) {
+            double x = X8 ? (double)X8[b * in + i] : (double)X[b * in + i];
+            double q = X8 ? (double)codes[b * out + o] : qval(codes, dense, step, b * out + o);
+            acc += q * x;
+        }
+        val[t] = acc;
+    }
+}
+
+void dbp_oracle_conv2d_dx_at(const int8_t *codes, const float *dense, double step,
+                             const float *W, int64_t N, int64_t C, int64_t H, int64_t Wd,
+                             int64_t K, int64_t R, int64_t S, int64_t st, int64_t pad,
+                             const int64_t *idx, int64_t n_idx, double *val)
+{
+    (void)N;
+    int64_t P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
+    for (int64_t t = 0; t < n_idx; ++t) {
+        int64_t f = idx[t];
+        int64_t w = f % Wd; f /= Wd;
+        int64_t h = f % H;  f /= H;
+        int64_t c = f % C;  int64_t n = f / C;
+        double acc = 0.0;
+        for (int64_t k = 0; k < K; ++k)
+          for (int64_t r = 0; r < R; ++r)
+            for (int64_t s = 0; s < S; ++s) {
+                int64_t hp = h + pad - r, wq = w + pad - s;
+                if (hp < 0 || wq < 0 || hp % st || wq % st) continue;
+                int64_t p = hp / st, q = wq / st;
+                if (p >= P || q >= Q) continue;
+                acc += qval(codes, dense, step, ((n * K + k) * P + p) * Q + q) *
+                       (double)W[((k * C + c) * R + r) * S + s];
+            }
+        val[t] = acc;
+    }
+}
+
+void dbp_oracle_conv2d_dw_at(const int8_t *codes, const float *dense, double step,
+                             const float *X, const int8_t *X8,
+                             int64_t N, int64_t C, int64_t H, int64_t Wd,
+                             int64_t K, int64_t R, int64_t S, int64_t st, int64_t pad,
+                             const int64_t *idx, int64_t n_idx, double *val)
+{
+    int64_t P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
+    for (int64_t t = 0; t < n_idx; ++t) {
+        int64_t f = idx[t];
+        int64_t s = f % S; f /= S;
+        int64_t r = f % R; f /= R;
+        int64_t c = f % C; int64_t k = f / C;
+        double acc = 0.0;
+        for (int64_t n = 0; n < N; ++n)
+          for (int64_t p = 0; p < P; ++p) {
+              int64_t h = p * st + r - pad;
+              if (h < 0 || h >= H) continue;
+              for (int64_t q = 0; q < Q; ++q) {
+                  int64_t w = q * st + s - pad;
+                  if (w < 0 || w >= Wd) continue;
+                  int64_t j = ((n * K + k) * P + p) * Q + q;
+                  int64_t xi = ((n * C + c) * H + h) * Wd + w;
+                  double x = X8 ? (double)X8[xi] : (double)X[xi];
+                  double g = X8 ? (double)codes[j] : qval(codes, dense, step, j);
+                  acc += g * x;
+              }
+          }
+        val[t] = acc;
+    }
+}
+
+int dbp_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
