@@ -1,0 +1,202 @@
+/*
+ * dbp.h -- C ABI of the MI355X (gfx950) dithered-backprop library.
+ *
+ * Method: Wiedemann, Mehari, Kepp, Samek, "Dithered backprop: a sparse and quantized
+ * backpropagation algorithm for more efficient deep neural network training"
+ * (arXiv 2004.04729).  The library implements the per-layer backward hot path:
+ *
+ *   1. NSD quantisation of the preactivation gradient delta_z        (Eq. (nsd), Eq. (qdz))
+ *          k = floor(delta/Delta + u),  u = nu/Delta + 1/2,  nu ~ U(-Delta/2, Delta/2) open
+ *          quantised gradient q = k * Delta, kept as int8 codes k plus a tile-sparse format
+ *   2. the two backward products that consume q                      (Eqs. (qda), (qdw))
+ *          delta_a = W^T . q        delta_W = q . a^T
+ *      for fully connected layers and, "analogously" (Sec. "Dithered backpropagation"),
+ *      for 2-D convolutions lowered to an implicit-im2col GEMM
+ *   3. the 8-bit mode of Sec. "Quantizing forward pass": int8 activations, int8 codes,
+ *      weight gradient accumulated exactly in int32.
+ *
+ * Conventions that hold for EVERY entry point
+ *   - All tensor pointers are DEVICE pointers (HBM) unless a comment says "host".
+ *     The caller owns every buffer; the library never allocates, frees or synchronises.
+ *     Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream).
+ *   - Tensors are dense, contiguous, row-major: FC  delta/codes [B,out], W [out,in],
+ *     X [B,in], dX [B,in], dW [out,in];  conv  delta/codes [N,K,P,Q], W [K,C,R,S],
+ *     X [N,C,H,Wd], dX [N,C,H,Wd], dW [K,C,R,S]  (P = (H+2pad-R)/stride+1, likewise Q).
+ *     With W stored [out,in] the paper's W^T.q is  dX[b,i] = sum_o q[b,o] W[o,i]  and
+ *     q.a^T is  dW[o,i] = sum_b q[b,o] X[b,i]  (no 1/B factor).
+ *   - Outputs are overwritten (beta = 0).  fp32 outputs are in real units (Delta applied);
+ *     the int32 weight gradient is the raw sum  k * x8  (the caller scales it).
+ *   - Arguments are validated on the host BEFORE any HIP call, so every status except
+ *     DBP_ERR_DEVICE can be produced on a machine without a GPU.  Nothing aborts or throws.
+ *   - `workspace` is device scratch of at least the size the matching *_workspace_bytes
+ *     function returns, 256-byte aligned.  Its contents need not be initialised and are
+ *     undefined afterwards, except for the tile-sparse format (see below) which stays valid.
+ *   - The dither of element j of delta is a pure function of (seed, idx_base + j), where j is
+ *     the row-major flat index; a shard of a larger tensor passes its offset as idx_base and
+ *     obtains bit-identical codes.
+ */
+#ifndef DBP_H_
+#define DBP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DBP_ABI_VERSION 1u
+#define DBP_TILE 256                     /* columns per tile of the tile-sparse format */
+
+typedef enum {
+    DBP_OK = 0,
+    DBP_ERR_NULL = 1,          /* a required pointer is NULL                                   */
+    DBP_ERR_SHAPE = 2,         /* a dimension is <= 0, too large, or inconsistent              */
+    DBP_ERR_STEP = 3,          /* Delta is <= 0, NaN, Inf, or 1/Delta is not finite            */
+    DBP_ERR_DTYPE = 4,         /* unknown dbp_dtype                                            */
+    DBP_ERR_WORKSPACE = 5,     /* workspace NULL/too small/misaligned                          */
+    DBP_ERR_UNSUPPORTED = 6,   /* valid request this build does not implement (e.g. stride>1)  */
+    DBP_ERR_OVERFLOW = 7,      /* int32 weight gradient could overflow: reduction*127*127>=2^31 */
+    DBP_ERR_DEVICE = 8         /* a HIP call failed (launch error, wrong device, ...)          */
+} dbp_status;
+
+typedef enum { DBP_F32 = 0, DBP_I8 = 1 } dbp_dtype;
+
+/* Which kernels compute the two products.  AUTO picks by problem size and, for GATHER,
+ * requires the density threshold measured on MI355X. */
+typedef enum {
+    DBP_PATH_AUTO = 0,
+    DBP_PATH_MFMA = 1,         /* codes as exact bf16 (or int8) operands of matrix-core tiles,
+                                  all-zero code fragments skipped                              */
+    DBP_PATH_GATHER = 2        /* walk the nonzero entries of the tile-sparse format           */
+} dbp_path;
+
+/* Per-call statistics, device resident (the paper's reported quantities: sparsity and the
+ * width of the non-zero codes, Sec. "Accuracy & Induced Sparsity").  Written by the NSD pass. */
+typedef struct {
+    uint64_t nnz;              /* codes != 0                                                   */
+    uint64_t n_saturated;      /* |floor(t)| > 127 before clamping to [-127,127] (incl. +-Inf) */
+    uint64_t n_nonfinite;      /* inputs that were NaN or +-Inf (NaN quantises to code 0)      */
+    int32_t  max_abs_code;     /* max |k| after clamping                                       */
+    int32_t  reserved;
+} dbp_stats;
+
+/*
+ * Tile-sparse format written by the NSD pass (this library's design; the paper asks only for
+ * "sparse tensors with low precision non-zero values").  The code plane [rows x cols] is cut,
+ * row by row, into tiles of DBP_TILE consecutive columns (a row's last tile may be short):
+ * tiles_per_row = ceil(cols/256), tile t = row*tiles_per_row + col/256.  Per tile
+ *   bitmap  [4t + w]     uint64: bit b set <=> code at in-tile column 64w+b is nonzero
+ *   tile_nnz[t]          uint16: number of nonzero codes of the tile
+ *   entries [256t + i]   uint16, i < tile_nnz[t]: (in-tile column << 8) | (code & 0xFF),
+ *                        columns ascending; later slots are not written.
+ * All three arrays live in one caller-provided buffer at the byte offsets given here.
+ */
+typedef struct {
+    int64_t tiles_per_row;
+    int64_t n_tiles;
+    size_t  bitmap_offset;     /* uint64[4*n_tiles]  */
+    size_t  tile_nnz_offset;   /* uint16[n_tiles]    */
+    size_t  entries_offset;    /* uint16[256*n_tiles]*/
+    size_t  total_bytes;
+} dbp_format_layout;
+
+uint32_t    dbp_abi_version(void);
+const char *dbp_status_string(dbp_status s);
+
+/* Layout/size of the tile-sparse format for a [rows x cols] code plane (host computation). */
+dbp_status  dbp_format_layout_of(int64_t rows, int64_t cols, dbp_format_layout *layout /*host*/);
+
+/* Bytes of workspace the backward entry points need (format + partial sums + staging);
+ * 0 on invalid arguments. */
+size_t dbp_linear_workspace_bytes(int64_t B, int64_t in, int64_t out, dbp_dtype x_dtype);
+size_t dbp_conv2d_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                                  int64_t R, int64_t S, int64_t stride, int64_t pad,
+                                  dbp_dtype x_dtype);
+
+/*
+ * NSD pass, Eq. (nsd) applied elementwise as in Eq. (qdz) (Algorithm 1, step 4, with the
+ * dither the algorithm listing omits).  One fused kernel: counter-based dither, quantise,
+ * int8 codes, per-tile nonzero counts (wavefront ballot + popcount), bitmap, compaction.
+ *   delta   [rows*cols] fp32, in.      rows/cols only shape the tile-sparse format; the
+ *                                      codes themselves depend on the flat index alone.
+ *   step    Delta > 0 (the caller's s*sigma of Algorithm 1, steps 2-3).
+ *   codes   [rows*cols] int8, out.
+ *   format  buffer of dbp_format_layout.total_bytes, 256-byte aligned, out; NULL = codes only.
+ *   stats   out, nullable.
+ * Errors: NULL delta/codes -> DBP_ERR_NULL; rows/cols <= 0 or rows*cols >= 2^40 -> SHAPE;
+ * bad step -> STEP; format too small/misaligned -> WORKSPACE.
+ */
+dbp_status nsd_quantize(const float *delta, int64_t rows, int64_t cols, float step,
+                        uint64_t seed, uint64_t idx_base, int8_t *codes,
+                        void *format, size_t format_bytes, dbp_stats *stats, void *stream);
+
+/*
+ * Dithered backward pass of a fully connected layer, Eqs. (qdz), (qda), (qdw):
+ * NSD of delta, then dX = q.W and dW = q^T.X  (storage form of W^T.q and q.a^T).
+ *   X, dW   fp32 when x_dtype == DBP_F32; int8 X and int32 dW when x_dtype == DBP_I8
+ *           (8-bit mode, Sec. "Quantizing forward pass"; dW32 = sum_b k[b,o]*x8[b,i], exact).
+ *   codes   out, nullable (then kept inside the workspace).
+ *   dX, dW  nullable = skip that product (not both).
+ * Errors as nsd_quantize, plus DBP_ERR_DTYPE, DBP_ERR_OVERFLOW (8-bit mode, B*127*127 >= 2^31).
+ */
+dbp_status dithered_linear_backward(const float *delta, const float *W, const void *X,
+                                    dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out,
+                                    float step, uint64_t seed, uint64_t idx_base,
+                                    int8_t *codes, float *dX, void *dW,
+                                    void *workspace, size_t workspace_bytes,
+                                    dbp_stats *stats, dbp_path path, void *stream);
+
+/*
+ * Dithered backward pass of a 2-D convolution (cross-correlation, zero padding, groups = 1,
+ * dilation = 1), the convolutional analogue of Eqs. (qdz), (qda), (qdw):
+ *   dX[n,c,h,w] = Delta * sum_{k,r,s} code[n,k,p,q] W[k,c,r,s],  h = p*stride+r-pad, w = q*stride+s-pad
+ *   dW[k,c,r,s] = Delta * sum_{n,p,q} code[n,k,p,q] X[n,c,p*stride+r-pad,q*stride+s-pad]
+ * computed as implicit-im2col GEMMs (no im2col buffer is materialised).  x_dtype as above.
+ * Errors as above; stride != 1 -> DBP_ERR_UNSUPPORTED in this build.
+ */
+dbp_status dithered_conv2d_backward(const float *delta, const float *W, const void *X,
+                                    dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H,
+                                    int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                    int64_t stride, int64_t pad,
+                                    float step, uint64_t seed, uint64_t idx_base,
+                                    int8_t *codes, float *dX, void *dW,
+                                    void *workspace, size_t workspace_bytes,
+                                    dbp_stats *stats, dbp_path path, void *stream);
+
+/*
+ * Same-library dense baselines: the undithered backward pass, Eqs. (da), (dw), on fp32 matrix
+ * cores (x_dtype == DBP_F32) -- the line the dithered path is measured against.  In 8-bit
+ * mode (DBP_I8) `delta` is instead a dense int8 gradient [..] and dW is int32.
+ */
+dbp_status dense_linear_backward(const void *delta, const float *W, const void *X,
+                                 dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out,
+                                 float *dX, void *dW, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *X,
+                                 dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd,
+                                 int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
+                                 float *dX, void *dW, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
+/*
+ * The products alone, from codes already quantised (e.g. by nsd_quantize): the second half of
+ * dithered_*_backward, exposed so that each kernel can be timed and tested on its own.
+ * `format` is the buffer nsd_quantize filled for (rows=B, cols=out) resp. (rows=N*K, cols=P*Q);
+ * it may be NULL when path == DBP_PATH_MFMA.
+ */
+dbp_status dbp_linear_products(const int8_t *codes, const void *format, float step,
+                               const float *W, const void *X, dbp_dtype x_dtype,
+                               int64_t B, int64_t in, int64_t out, float *dX, void *dW,
+                               void *workspace, size_t workspace_bytes, dbp_path path, void *stream);
+dbp_status dbp_conv2d_products(const int8_t *codes, const void *format, float step,
+                               const float *W, const void *X, dbp_dtype x_dtype,
+                               int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                               int64_t R, int64_t S, int64_t stride, int64_t pad,
+                               float *dX, void *dW, void *workspace, size_t workspace_bytes,
+                               dbp_path path, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBP_H_ */

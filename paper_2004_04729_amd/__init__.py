@@ -1,0 +1,13 @@
+"""MI355X-native dithered backprop (arXiv 2004.04729): NSD quantisation of the preactivation
+gradient and the two sparse backward products, as hand-written gfx950 HIP kernels behind a C ABI.
+
+The Python layer only marshals arguments; every step runs in the HIP library.  There is no CPU
+fallback: importing :mod:`paper_2004_04729_amd.binding` fails loudly when the library is missing.
+"""
+from .binding import (  # noqa: F401
+    DbpError, Stats, PATH_AUTO, PATH_MFMA, PATH_GATHER, F32, I8,
+    abi_version, status_string, format_layout, linear_workspace_bytes, conv2d_workspace_bytes,
+    nsd_quantize, dithered_linear_backward, dithered_conv2d_backward,
+    dense_linear_backward, dense_conv2d_backward, linear_products, conv2d_products,
+    lib, lib_path,
+)

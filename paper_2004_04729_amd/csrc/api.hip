@@ -1,0 +1,291 @@
+// C ABI of the library (include/dbp.h): argument validation on the host, workspace carving, launches.
+// Every check happens before the first HIP call so that all statuses but DBP_ERR_DEVICE are
+// reachable on a machine without a GPU.
+#include <cmath>
+#include <cstring>
+#include "common.h"
+
+using namespace dbp;
+
+namespace {
+
+constexpr int64_t kMaxElems = (int64_t)1 << 40;
+constexpr int64_t kMaxDim = (int64_t)1 << 30;          // GEMM indices are 32-bit
+
+bool step_ok(float step)
+{
+    if (!(step > 0.0f) || !std::isfinite(step)) return false;
+    const float inv = 1.0f / step;
+    return std::isfinite(inv) && inv >= 1.17549435e-38f && step >= 1.17549435e-38f;
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+dbp_status format_layout(int64_t rows, int64_t cols, dbp_format_layout *L)
+{
+    if (!L) return DBP_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || rows > kMaxElems / cols) return DBP_ERR_SHAPE;
+    const int64_t tpr = (cols + DBP_TILE - 1) / DBP_TILE;
+    const int64_t nt = rows * tpr;
+    L->tiles_per_row = tpr;
+    L->n_tiles = nt;
+    L->bitmap_offset = 0;
+    L->tile_nnz_offset = align_up((size_t)nt * 4 * sizeof(uint64_t), 256);
+    L->entries_offset = L->tile_nnz_offset + align_up((size_t)nt * sizeof(uint16_t), 256);
+    L->total_bytes = L->entries_offset + align_up((size_t)nt * DBP_TILE * sizeof(uint16_t), 256);
+    return DBP_OK;
+}
+
+struct Carve {                      // pieces of a backward workspace
+    dbp_format_layout fmt;
+    size_t codes_offset, scratch_offset, total;
+};
+
+Carve carve(int64_t rows, int64_t cols, size_t scratch_bytes)
+{
+    Carve c;
+    format_layout(rows, cols, &c.fmt);
+    c.codes_offset = c.fmt.total_bytes;
+    c.scratch_offset = c.codes_offset + align_up((size_t)(rows * cols), 256);
+    c.total = c.scratch_offset + scratch_bytes;
+    return c;
+}
+
+dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
+                   int8_t *codes, char *fmt_base, const dbp_format_layout *L, dbp_stats *stats, hipStream_t s)
+{
+    NsdArgs a;
+    a.delta = delta; a.codes = codes; a.stats = stats;
+    a.bitmap = fmt_base ? (uint64_t *)(fmt_base + L->bitmap_offset) : nullptr;
+    a.tile_nnz = fmt_base ? (uint16_t *)(fmt_base + L->tile_nnz_offset) : nullptr;
+    a.entries = fmt_base ? (uint16_t *)(fmt_base + L->entries_offset) : nullptr;
+    a.rows = rows; a.cols = cols; a.tiles_per_row = L->tiles_per_row; a.n_tiles = L->n_tiles;
+    a.inv_step = 1.0f / step;
+    const DitherKeys k = make_dither_keys(seed);
+    a.k0 = k.k0; a.k1 = k.k1; a.idx_base = idx_base;
+    return launch_nsd(a, s) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+dbp_status check_linear_dims(int64_t B, int64_t in, int64_t out)
+{
+    if (B <= 0 || in <= 0 || out <= 0 || B > kMaxDim || in > kMaxDim || out > kMaxDim) return DBP_ERR_SHAPE;
+    if (B > kMaxElems / out || B > kMaxElems / in || out > kMaxElems / in) return DBP_ERR_SHAPE;
+    return DBP_OK;
+}
+
+dbp_status check_conv_dims(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                           int64_t stride, int64_t pad, int64_t *P, int64_t *Q)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || Wd <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return DBP_ERR_SHAPE;
+    if (N > 65535 || C > 65535 || K > 65535 || H > 65535 || Wd > 65535 || R > 255 || S > 255 || pad > 255) return DBP_ERR_SHAPE;
+    if (H + 2 * pad < R || Wd + 2 * pad < S) return DBP_ERR_SHAPE;
+    *P = (H + 2 * pad - R) / stride + 1;
+    *Q = (Wd + 2 * pad - S) / stride + 1;
+    // every GEMM index (rows, cols, padded reductions) must fit 31 bits
+    const int64_t lim = ((int64_t)1 << 31) - 4096;
+    if (N * H * Wd >= lim || N * (*P * *Q + 64) >= lim || C * R * S >= lim || R * S * (K + 16) >= lim) return DBP_ERR_SHAPE;
+    if (N * K * *P * *Q >= kMaxElems || N * C * H * Wd >= kMaxElems) return DBP_ERR_SHAPE;
+    return DBP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t dbp_abi_version(void) { return DBP_ABI_VERSION; }
+
+const char *dbp_status_string(dbp_status s)
+{
+    switch (s) {
+    case DBP_OK: return "ok";
+    case DBP_ERR_NULL: return "required pointer is NULL";
+    case DBP_ERR_SHAPE: return "invalid or unsupported shape";
+    case DBP_ERR_STEP: return "step size must be positive, finite and invertible in fp32";
+    case DBP_ERR_DTYPE: return "unknown dtype";
+    case DBP_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case DBP_ERR_UNSUPPORTED: return "not implemented in this build";
+    case DBP_ERR_OVERFLOW: return "int32 weight gradient could overflow";
+    case DBP_ERR_DEVICE: return "HIP error";
+    }
+    return "unknown status";
+}
+
+dbp_status dbp_format_layout_of(int64_t rows, int64_t cols, dbp_format_layout *layout)
+{
+    return format_layout(rows, cols, layout);
+}
+
+size_t dbp_linear_workspace_bytes(int64_t B, int64_t in, int64_t out, dbp_dtype x_dtype)
+{
+    if (check_linear_dims(B, in, out) != DBP_OK || (x_dtype != DBP_F32 && x_dtype != DBP_I8)) return 0;
+    return carve(B, out, linear_scratch_bytes(B, in, out)).total;
+}
+
+size_t dbp_conv2d_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                  int64_t stride, int64_t pad, dbp_dtype x_dtype)
+{
+    int64_t P, Q;
+    if (check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q) != DBP_OK) return 0;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return 0;
+    if (stride != 1) return 0;
+    return carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad)).total;
+}
+
+dbp_status nsd_quantize(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
+                        int8_t *codes, void *format, size_t format_bytes, dbp_stats *stats, void *stream)
+{
+    if (!delta || !codes) return DBP_ERR_NULL;
+    dbp_format_layout L;
+    dbp_status st = format_layout(rows, cols, &L);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (format && (format_bytes < L.total_bytes || !aligned(format, 256))) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    return run_nsd(delta, rows, cols, step, seed, idx_base, codes, (char *)format, &L, stats, (hipStream_t)stream);
+}
+
+dbp_status dbp_linear_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
+                               dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX, void *dW,
+                               void *workspace, size_t workspace_bytes, dbp_path path, void *stream)
+{
+    if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    dbp_status st = check_linear_dims(B, in, out);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    LinearArgs a;
+    a.codes = codes; a.dense = nullptr; a.step = step; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW;
+    if (path == DBP_PATH_GATHER) {
+        if (!format) return DBP_ERR_NULL;
+        if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
+        dbp_format_layout L;
+        format_layout(B, out, &L);
+        const char *fb = (const char *)format;
+        FormatView f{(const uint64_t *)(fb + L.bitmap_offset), (const uint16_t *)(fb + L.tile_nnz_offset),
+                     (const uint16_t *)(fb + L.entries_offset), L.tiles_per_row};
+        a.scratch = nullptr; a.scratch_bytes = 0;
+        return launch_linear_gather(a, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+    }
+    const size_t need = linear_scratch_bytes(B, in, out);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+dbp_status dithered_linear_backward(const float *delta, const float *W, const void *X, dbp_dtype x_dtype,
+                                    int64_t B, int64_t in, int64_t out, float step, uint64_t seed, uint64_t idx_base,
+                                    int8_t *codes, float *dX, void *dW, void *workspace, size_t workspace_bytes,
+                                    dbp_stats *stats, dbp_path path, void *stream)
+{
+    if (!delta || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    dbp_status st = check_linear_dims(B, in, out);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const Carve c = carve(B, out, linear_scratch_bytes(B, in, out));
+    if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    char *ws = (char *)workspace;
+    int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
+    st = run_nsd(delta, B, out, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream);
+    if (st != DBP_OK) return st;
+    return dbp_linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset,
+                               workspace_bytes - c.scratch_offset, path, stream);
+}
+
+dbp_status dbp_conv2d_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
+                               dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                               int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW,
+                               void *workspace, size_t workspace_bytes, dbp_path path, void *stream)
+{
+    (void)format;
+    if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    int64_t P, Q;
+    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (stride != 1 || path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    ConvArgs a;
+    a.codes = codes; a.dense = nullptr; a.step = step; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
+    a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+dbp_status dithered_conv2d_backward(const float *delta, const float *W, const void *X, dbp_dtype x_dtype,
+                                    int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                    int64_t stride, int64_t pad, float step, uint64_t seed, uint64_t idx_base,
+                                    int8_t *codes, float *dX, void *dW, void *workspace, size_t workspace_bytes,
+                                    dbp_stats *stats, dbp_path path, void *stream)
+{
+    if (!delta || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    int64_t P, Q;
+    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (stride != 1 || path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad));
+    if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    char *ws = (char *)workspace;
+    int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream);
+    if (st != DBP_OK) return st;
+    return dbp_conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
+                               ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path, stream);
+}
+
+dbp_status dense_linear_backward(const void *delta, const float *W, const void *X, dbp_dtype x_dtype,
+                                 int64_t B, int64_t in, int64_t out, float *dX, void *dW,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!delta || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    dbp_status st = check_linear_dims(B, in, out);
+    if (st != DBP_OK) return st;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (x_dtype == DBP_I8 && dX) return DBP_ERR_UNSUPPORTED;          // int8 gradient with fp32 weights
+    if (x_dtype == DBP_I8 && dW && B * 128 * 128 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const size_t need = linear_scratch_bytes(B, in, out);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    LinearArgs a;
+    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *X, dbp_dtype x_dtype,
+                                 int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                 int64_t stride, int64_t pad, float *dX, void *dW,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!delta || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    int64_t P, Q;
+    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
+    if (st != DBP_OK) return st;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (stride != 1) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dX) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && N * P * Q * 128 * 128 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    ConvArgs a;
+    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
+    a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,78 @@
+// Shared declarations of the gfx950 dithered-backprop library (internal; the public C ABI is include/dbp.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "dbp.h"
+
+namespace dbp {
+
+typedef float    f32x4  __attribute__((ext_vector_type(4)));
+typedef float    f32x16 __attribute__((ext_vector_type(16)));
+typedef int32_t  i32x4  __attribute__((ext_vector_type(4)));
+typedef int32_t  i32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4  __attribute__((ext_vector_type(4)));
+typedef __bf16   bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kWave = 64;
+
+// Dither keys derived from the 64-bit seed on the host (constants: golden ratio, frac sqrt2, frac sqrt3).
+struct DitherKeys { uint32_t k0, k1; };
+DitherKeys make_dither_keys(uint64_t seed);
+
+struct NsdArgs {
+    const float *delta;
+    int8_t      *codes;
+    uint64_t    *bitmap;      // nullable (codes only)
+    uint16_t    *tile_nnz;
+    uint16_t    *entries;
+    dbp_stats   *stats;       // nullable
+    int64_t      rows, cols, tiles_per_row, n_tiles;
+    float        inv_step;
+    uint32_t     k0, k1;
+    uint64_t     idx_base;
+};
+hipError_t launch_nsd(const NsdArgs &a, hipStream_t s);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace dbp
+
+namespace dbp {
+
+// ---- products (products.hip) -----------------------------------------------------------------
+struct LinearArgs {
+    const int8_t *codes;       // dithered path: int8 codes [B,out]
+    const void   *dense;       // dense baseline: fp32 (or int8 in 8-bit mode) gradient [B,out]
+    float         step;        // Delta (dithered); ignored for dense
+    const float  *W;           // [out,in]
+    const void   *X;           // [B,in] fp32 or int8
+    dbp_dtype     x_dtype;
+    int64_t       B, in, out;
+    float        *dX;          // nullable
+    void         *dW;          // nullable
+    void         *scratch;     // split-K partials
+    size_t        scratch_bytes;
+};
+struct ConvArgs {
+    const int8_t *codes;
+    const void   *dense;
+    float         step;
+    const float  *W;           // [K,C,R,S]
+    const void   *X;           // [N,C,H,Wd]
+    dbp_dtype     x_dtype;
+    int64_t       N, C, H, Wd, K, R, S, pad;
+    float        *dX;
+    void         *dW;
+    void         *scratch;
+    size_t        scratch_bytes;
+};
+size_t     linear_scratch_bytes(int64_t B, int64_t in, int64_t out);
+size_t     conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad);
+hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s);
+hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s);
+
+// ---- gather path (gather.hip) ------------------------------------------------------------------
+struct FormatView { const uint64_t *bitmap; const uint16_t *tile_nnz; const uint16_t *entries; int64_t tiles_per_row; };
+hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s);
+
+}  // namespace dbp

@@ -1,0 +1,128 @@
+"""GPU parity of the fully connected backward products (Eqs. (qda),(qdw)) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import workloads
+from workloads import LinearProblem
+
+pytestmark = pytest.mark.gpu
+
+
+def _problem(B, in_, out, c=4.0, seed=0, x_zero_frac=0.5):
+    rng = np.random.default_rng(seed + B * 31 + in_ * 7 + out)
+    X = np.maximum(rng.standard_normal((B, in_)), 0).astype(np.float32) if x_zero_frac else \
+        rng.standard_normal((B, in_)).astype(np.float32)
+    W = (rng.standard_normal((out, in_)) / np.sqrt(in_)).astype(np.float32)
+    d = rng.laplace(0, 1e-3, size=(B, out)).astype(np.float32)
+    return LinearProblem("t_%dx%dx%d" % (B, in_, out), d, W, X, float(np.float32(c * 1.4142e-3)))
+
+
+def _check_fp32(p, res):
+    from gpu_util import check_products
+    from oracle import oracle as O
+    k_ref, _ = O.nsd(p.delta, p.step, p.seed)
+    assert np.array_equal(res["codes"], k_ref)
+    rX, rW, _ = O.linear_backward(p.W, p.X, codes=k_ref, step=p.step)
+    aX, aW, _ = O.linear_backward(np.abs(p.W), np.abs(p.X), codes=np.abs(k_ref), step=p.step)
+    e1 = check_products(res["dX"], rX, aX, p.name + " dX") if res["dX"] is not None else 0
+    e2 = check_products(res["dW"], rW, aW, p.name + " dW") if res["dW"] is not None else 0
+    return max(e1, e2)
+
+
+SHAPES = [(1, 1, 1), (5, 3, 2), (37, 301, 129), (64, 784, 300), (300, 520, 1030), (256, 1024, 1000), (257, 130, 33),
+          (8, 2000, 515)]
+
+
+@pytest.mark.parametrize("B,in_,out", SHAPES)
+@pytest.mark.parametrize("path", ["mfma", "gather"])
+def test_fc_products_match_oracle(B, in_, out, path):
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_linear
+    p = _problem(B, in_, out)
+    res = run_linear(p, path=dbp.PATH_MFMA if path == "mfma" else dbp.PATH_GATHER)
+    worst = _check_fp32(p, res)
+    assert worst < 1e-4
+
+
+@pytest.mark.parametrize("path", ["mfma", "gather"])
+def test_fc_dense_codes_and_extreme_values(path):
+    # small step: dense codes up to +-127, so every bf16 plane and every code magnitude is exercised
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_linear
+    p = _problem(96, 200, 260, c=0.02, x_zero_frac=0)
+    p.W[::3] *= 1e4
+    p.W[1::3] *= 1e-6
+    res = run_linear(p, path=dbp.PATH_MFMA if path == "mfma" else dbp.PATH_GATHER)
+    assert np.abs(res["codes"]).max() == 127
+    _check_fp32(p, res)
+
+
+@pytest.mark.parametrize("path", ["mfma", "gather"])
+def test_fc_all_zero_codes_and_single_products(path):
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_linear
+    pp = dbp.PATH_MFMA if path == "mfma" else dbp.PATH_GATHER
+    p = _problem(40, 96, 300)
+    p.delta[:] = 0
+    res = run_linear(p, path=pp)
+    assert not res["codes"].any() and not res["dX"].any() and not res["dW"].any()
+    p = _problem(70, 260, 300, c=8.0)
+    p.delta[10:50] = 0                       # structured: whole rows of zeros
+    p.delta[:, 100:228] = 0                  # and whole column blocks
+    _check_fp32(p, run_linear(p, path=pp, want_dw=False))
+    _check_fp32(p, run_linear(p, path=pp, want_dx=False))
+
+
+@pytest.mark.parametrize("B,in_,out", [(5, 3, 2), (37, 301, 129), (256, 520, 300), (1000, 64, 70)])
+@pytest.mark.parametrize("path", ["mfma", "gather"])
+def test_fc_int8_mode_is_bit_exact(B, in_, out, path):
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_linear
+    from oracle import oracle as O
+    p = _problem(B, in_, out, c=1.0)
+    X8 = workloads.int8_relu_uniform(np.random.default_rng(B), (B, in_))
+    res = run_linear(p, path=dbp.PATH_MFMA if path == "mfma" else dbp.PATH_GATHER, x_i8=X8)
+    k_ref, _ = O.nsd(p.delta, p.step, p.seed)
+    assert np.array_equal(res["codes"], k_ref)
+    assert np.array_equal(res["dW"], O.linear_dw_i8(k_ref, X8))
+    # dX stays fp32 (weights are fp32)
+    from gpu_util import check_products
+    rX, _, _ = O.linear_backward(p.W, p.X, codes=k_ref, step=p.step, want_dw=False)
+    aX, _, _ = O.linear_backward(np.abs(p.W), p.X, codes=np.abs(k_ref), step=p.step, want_dw=False)
+    check_products(res["dX"], rX, aX, "int8-mode dX")
+
+
+def test_fc_results_are_deterministic_and_paths_agree_on_codes():
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_linear
+    p = _problem(256, 1024, 1000, c=8.0)
+    a = run_linear(p, path=dbp.PATH_MFMA)
+    b = run_linear(p, path=dbp.PATH_MFMA)
+    assert a["dX"].tobytes() == b["dX"].tobytes() and a["dW"].tobytes() == b["dW"].tobytes()
+    g = run_linear(p, path=dbp.PATH_GATHER, fused=False)
+    assert np.array_equal(g["codes"], a["codes"])
+
+
+@pytest.mark.parametrize("B,in_,out", [(5, 3, 2), (37, 301, 129), (256, 520, 300)])
+def test_dense_baseline_matches_oracle(B, in_, out):
+    import torch
+    import paper_2004_04729_amd as dbp
+    from gpu_util import dev, stream, check_products
+    from oracle import oracle as O
+    p = _problem(B, in_, out)
+    dX = torch.empty((B, in_), dtype=torch.float32, device="cuda:0")
+    dW = torch.empty((out, in_), dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(dbp.linear_workspace_bytes(B, in_, out), dtype=torch.uint8, device="cuda:0")
+    dbp.dense_linear_backward(dev(p.delta), dev(p.W), dev(p.X), dbp.F32, B, in_, out, dX, dW, ws, stream())
+    torch.cuda.synchronize()
+    rX, rW, _ = O.linear_backward(p.W, p.X, dense=p.delta)
+    aX, aW, _ = O.linear_backward(np.abs(p.W), np.abs(p.X), dense=np.abs(p.delta))
+    check_products(dX.cpu().numpy(), rX, aX, "dense dX")
+    check_products(dW.cpu().numpy(), rW, aW, "dense dW")
+
+
+def test_config1_and_config2_full_size():
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_linear
+    for p in [workloads.config1()] + workloads.config2(8.0):
+        _check_fp32(p, run_linear(p, path=dbp.PATH_AUTO))
