@@ -1,0 +1,120 @@
+"""CPU-only checks of the C ABI: the library loads, exports every function include/dbp.h declares,
+and rejects bad arguments before touching the GPU (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2004_04729_amd as dbp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, NULL, SHAPE, STEP, DTYPE, WORKSPACE, UNSUPPORTED, OVERFLOW, DEVICE = range(9)
+FAKE = 0x10000       # a non-NULL, 256-aligned address that is never dereferenced by the checks under test
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "dbp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
+    return sorted({n for n in names if n.startswith(("dbp_", "nsd_", "dithered_", "dense_"))})
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert {"nsd_quantize", "dithered_linear_backward", "dithered_conv2d_backward", "dense_linear_backward",
+            "dense_conv2d_backward", "dbp_linear_products", "dbp_conv2d_products", "dbp_format_layout_of",
+            "dbp_linear_workspace_bytes", "dbp_conv2d_workspace_bytes", "dbp_status_string",
+            "dbp_abi_version"} <= set(names)
+    raw = C.CDLL(dbp.lib_path())
+    for n in names:
+        assert hasattr(raw, n), n
+
+
+def test_version_and_status_strings():
+    assert dbp.abi_version() == 1
+    seen = {dbp.status_string(c) for c in range(9)}
+    assert len(seen) == 9 and dbp.status_string(99) == "unknown status"
+
+
+def test_format_layout():
+    L = dbp.format_layout(64, 300)
+    assert L["tiles_per_row"] == 2 and L["n_tiles"] == 128
+    assert L["bitmap_offset"] == 0 and L["tile_nnz_offset"] >= 128 * 32
+    assert L["entries_offset"] >= L["tile_nnz_offset"] + 128 * 2
+    assert L["total_bytes"] >= L["entries_offset"] + 128 * 512
+    assert all(L[k] % 256 == 0 for k in ("tile_nnz_offset", "entries_offset", "total_bytes"))
+    with pytest.raises(dbp.DbpError) as e:
+        dbp.format_layout(0, 5)
+    assert e.value.code == SHAPE
+
+
+def test_workspace_sizes():
+    assert dbp.linear_workspace_bytes(64, 784, 300) > 64 * 300
+    assert dbp.linear_workspace_bytes(0, 784, 300) == 0 and dbp.linear_workspace_bytes(64, 784, 300, 7) == 0
+    assert dbp.conv2d_workspace_bytes(128, 64, 32, 32, 64, 3, 3, 1, 1) > 128 * 64 * 32 * 32
+    assert dbp.conv2d_workspace_bytes(128, 64, 32, 32, 64, 3, 3, 2, 1) == 0       # stride 2 not in this build
+    assert dbp.conv2d_workspace_bytes(1, 1, 2, 2, 1, 5, 5, 1, 0) == 0             # kernel larger than input
+
+
+def _code(fn, *a, **k):
+    with pytest.raises(dbp.DbpError) as e:
+        fn(*a, **k)
+    return e.value.code
+
+
+def test_nsd_argument_errors():
+    q = dbp.nsd_quantize
+    assert _code(q, None, 4, 4, 1.0, 1, 0, FAKE) == NULL
+    assert _code(q, FAKE, 4, 4, 1.0, 1, 0, None) == NULL
+    assert _code(q, FAKE, 0, 4, 1.0, 1, 0, FAKE) == SHAPE
+    assert _code(q, FAKE, 4, -1, 1.0, 1, 0, FAKE) == SHAPE
+    assert _code(q, FAKE, 1 << 30, 1 << 30, 1.0, 1, 0, FAKE) == SHAPE
+    for bad in (0.0, -1.0, float("nan"), float("inf"), 1e-45, 3.4e38):
+        assert _code(q, FAKE, 4, 4, bad, 1, 0, FAKE) == STEP
+    raw = dbp.lib()
+    assert raw.nsd_quantize(FAKE, 4, 4, 1.0, 1, 0, FAKE, FAKE, 16, None, None) == WORKSPACE     # too small
+    assert raw.nsd_quantize(FAKE, 4, 4, 1.0, 1, 0, FAKE, FAKE + 8, 1 << 20, None, None) == WORKSPACE  # misaligned
+
+
+def test_linear_argument_errors():
+    f = dbp.lib().dithered_linear_backward
+    big = 1 << 30
+
+    def call(delta=FAKE, W=FAKE, X=FAKE, xd=0, B=8, i=8, o=8, step=1.0, dX=FAKE, dW=FAKE, ws=FAKE, wsb=big, path=0):
+        return f(delta, W, X, xd, B, i, o, step, 1, 0, None, dX, dW, ws, wsb, None, path, None)
+
+    assert call(delta=None) == NULL and call(W=None) == NULL and call(X=None) == NULL
+    assert call(dX=None, dW=None) == NULL
+    assert call(B=0) == SHAPE and call(i=-3) == SHAPE and call(o=1 << 31) == SHAPE
+    assert call(step=0.0) == STEP
+    assert call(xd=5) == DTYPE
+    assert call(path=9) == UNSUPPORTED
+    assert call(ws=None) == WORKSPACE and call(wsb=100) == WORKSPACE and call(ws=FAKE + 4) == WORKSPACE
+    assert call(xd=1, B=140000) == OVERFLOW
+    g = dbp.lib().dense_linear_backward
+    assert g(None, FAKE, FAKE, 0, 8, 8, 8, FAKE, FAKE, FAKE, big, None) == NULL
+    assert g(FAKE, FAKE, FAKE, 1, 8, 8, 8, FAKE, FAKE, FAKE, big, None) == UNSUPPORTED
+    assert g(FAKE, FAKE, FAKE, 0, 8, 8, 8, FAKE, FAKE, FAKE, 10, None) == WORKSPACE
+    h = dbp.lib().dbp_linear_products
+    assert h(FAKE, None, 1.0, FAKE, FAKE, 0, 8, 8, 8, FAKE, FAKE, FAKE, big, 2, None) == NULL    # gather needs the format
+    assert h(None, None, 1.0, FAKE, FAKE, 0, 8, 8, 8, FAKE, FAKE, FAKE, big, 1, None) == NULL
+
+
+def test_conv_argument_errors():
+    f = dbp.lib().dithered_conv2d_backward
+    big = 1 << 34
+
+    def call(delta=FAKE, W=FAKE, X=FAKE, xd=0, N=2, Cc=3, H=8, Wd=8, K=4, R=3, S=3, stride=1, pad=1, step=1.0,
+             dX=FAKE, dW=FAKE, ws=FAKE, wsb=big, path=0):
+        return f(delta, W, X, xd, N, Cc, H, Wd, K, R, S, stride, pad, step, 1, 0, None, dX, dW, ws, wsb, None, path, None)
+
+    assert call(delta=None) == NULL and call(dX=None, dW=None) == NULL
+    assert call(N=0) == SHAPE and call(R=9, pad=0, H=4) == SHAPE and call(pad=-1) == SHAPE
+    assert call(step=float("nan")) == STEP and call(xd=3) == DTYPE
+    assert call(stride=2) == UNSUPPORTED and call(path=2) == UNSUPPORTED
+    assert call(wsb=1000) == WORKSPACE
+    assert call(xd=1, N=64, H=64, Wd=64) == OVERFLOW
+    g = dbp.lib().dense_conv2d_backward
+    assert g(FAKE, FAKE, FAKE, 0, 2, 3, 8, 8, 4, 3, 3, 2, 1, FAKE, FAKE, FAKE, big, None) == UNSUPPORTED
+    assert g(FAKE, FAKE, None, 0, 2, 3, 8, 8, 4, 3, 3, 1, 1, FAKE, FAKE, FAKE, big, None) == NULL

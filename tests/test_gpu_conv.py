@@ -1,0 +1,155 @@
+"""GPU parity of the convolutional backward products (implicit-im2col GEMMs) against the CPU oracle."""
+import numpy as np
+import pytest
+
+import workloads
+from workloads import ConvProblem
+
+pytestmark = pytest.mark.gpu
+
+
+def _problem(N, C, H, Wd, K, R, S, pad, c=4.0, seed=0, i8=False):
+    rng = np.random.default_rng(seed + N * 131 + C * 17 + H * 5 + K)
+    P, Q = H + 2 * pad - R + 1, Wd + 2 * pad - S + 1
+    X = workloads.int8_relu_uniform(rng, (N, C, H, Wd)) if i8 else workloads.relu_normal(rng, (N, C, H, Wd))
+    W = (rng.standard_normal((K, C, R, S)) * np.sqrt(2.0 / (C * R * S))).astype(np.float32)
+    d = rng.laplace(0, 5e-4, size=(N, K, P, Q)).astype(np.float32)
+    return ConvProblem("t_n%d_c%d_%dx%d_k%d_%dx%d_p%d" % (N, C, H, Wd, K, R, S, pad), d, W, X,
+                       float(np.float32(c * 7.071e-4)), 1, pad)
+
+
+def _check(p, res, sample=None):
+    """Full comparison, or (sample = (idx_dx, idx_dw)) sampled outputs for problems too big for a full oracle run."""
+    from gpu_util import check_products
+    from oracle import oracle as O
+    k_ref, st = O.nsd(p.delta, p.step, p.seed)
+    assert np.array_equal(res["codes"], k_ref)
+    assert res["stats"].nnz == st.nnz and res["stats"].max_abs_code == st.max_abs_code
+    i8 = p.X.dtype == np.int8
+    Xf = p.X.astype(np.float32)
+    kw = dict(stride=p.stride, pad=p.pad)
+    if sample is None:
+        rX, rW, _ = O.conv2d_backward(p.W, Xf, codes=k_ref, step=p.step, **kw)
+        aX, aW, _ = O.conv2d_backward(np.abs(p.W), np.abs(Xf), codes=np.abs(k_ref), step=p.step, **kw)
+        if res["dX"] is not None:
+            check_products(res["dX"], rX, aX, p.name + " dX")
+        if res["dW"] is not None:
+            if i8:
+                assert np.array_equal(res["dW"], O.conv2d_dw_i8(k_ref, p.X, p.W.shape[2], p.W.shape[3], p.stride, p.pad))
+            else:
+                check_products(res["dW"], rW, aW, p.name + " dW")
+    else:
+        ix, iw = sample
+        if res["dX"] is not None:
+            r = O.conv2d_dx_at(p.W, p.X.shape, ix, codes=k_ref, step=p.step, **kw)
+            a = O.conv2d_dx_at(np.abs(p.W), p.X.shape, ix, codes=np.abs(k_ref), step=p.step, **kw)
+            check_products(res["dX"].ravel()[ix], r, a, p.name + " dX (sampled)")
+        if res["dW"] is not None:
+            if i8:
+                r = O.conv2d_dw_at(p.X, p.W.shape, iw, codes=k_ref, **kw)
+                assert np.array_equal(res["dW"].ravel()[iw].astype(np.float64), r)
+            else:
+                r = O.conv2d_dw_at(p.X, p.W.shape, iw, codes=k_ref, step=p.step, **kw)
+                a = O.conv2d_dw_at(np.abs(p.X), p.W.shape, iw, codes=np.abs(k_ref), step=p.step, **kw)
+                check_products(res["dW"].ravel()[iw], r, a, p.name + " dW (sampled)")
+
+
+CASES = [  # N, C, H, Wd, K, R, S, pad
+    (1, 1, 1, 1, 1, 1, 1, 0),
+    (2, 5, 9, 7, 6, 3, 3, 1),
+    (3, 16, 14, 14, 24, 3, 3, 1),
+    (2, 33, 14, 14, 20, 1, 1, 0),
+    (2, 3, 11, 8, 4, 5, 3, 2),
+    (2, 8, 10, 10, 9, 3, 3, 0),
+    (5, 40, 12, 20, 70, 3, 3, 1),
+    (1, 130, 6, 6, 260, 3, 3, 1),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_conv_products_match_oracle(case):
+    from gpu_util import run_conv
+    p = _problem(*case)
+    _check(p, run_conv(p))
+
+
+@pytest.mark.parametrize("case", CASES[1:6])
+def test_conv_int8_mode_is_bit_exact(case):
+    from gpu_util import run_conv
+    p = _problem(*case, c=1.0, i8=True)
+    _check(p, run_conv(p))
+
+
+def test_conv_dense_codes_and_structured_zeros():
+    from gpu_util import run_conv
+    p = _problem(2, 12, 10, 10, 40, 3, 3, 1, c=0.02)
+    res = run_conv(p)
+    assert np.abs(res["codes"]).max() == 127
+    _check(p, res)
+    p = _problem(4, 12, 16, 16, 40, 3, 3, 1, c=8.0)
+    p.delta[:] = workloads.structured_planes(p.delta, 0.5)
+    _check(p, run_conv(p))
+    p.delta[:] = 0
+    res = run_conv(p)
+    assert not res["dX"].any() and not res["dW"].any()
+
+
+def test_conv_single_products_and_determinism():
+    from gpu_util import run_conv
+    p = _problem(3, 16, 14, 14, 24, 3, 3, 1)
+    a = run_conv(p)
+    b = run_conv(p)
+    assert a["dX"].tobytes() == b["dX"].tobytes() and a["dW"].tobytes() == b["dW"].tobytes()
+    only_dx = run_conv(p, want_dw=False)
+    only_dw = run_conv(p, want_dx=False)
+    assert only_dx["dX"].tobytes() == a["dX"].tobytes() and only_dw["dW"].tobytes() == a["dW"].tobytes()
+
+
+def test_dense_conv_baseline_matches_oracle():
+    import torch
+    import paper_2004_04729_amd as dbp
+    from gpu_util import dev, stream, check_products, conv_dims
+    from oracle import oracle as O
+    for case in (CASES[1], CASES[2], CASES[3]):
+        p = _problem(*case)
+        N, Cc, H, Wd, K, R, S = conv_dims(p)
+        dX = torch.empty(p.X.shape, dtype=torch.float32, device="cuda:0")
+        dW = torch.empty(p.W.shape, dtype=torch.float32, device="cuda:0")
+        ws = torch.empty(dbp.conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, 1, p.pad), dtype=torch.uint8, device="cuda:0")
+        dbp.dense_conv2d_backward(dev(p.delta), dev(p.W), dev(p.X), dbp.F32, N, Cc, H, Wd, K, R, S, 1, p.pad, dX, dW, ws, stream())
+        torch.cuda.synchronize()
+        rX, rW, _ = O.conv2d_backward(p.W, p.X, dense=p.delta, pad=p.pad)
+        aX, aW, _ = O.conv2d_backward(np.abs(p.W), np.abs(p.X), dense=np.abs(p.delta), pad=p.pad)
+        check_products(dX.cpu().numpy(), rX, aX, "dense conv dX")
+        check_products(dW.cpu().numpy(), rW, aW, "dense conv dW")
+
+
+def _samples(p, n=300, seed=3):
+    rng = np.random.default_rng(seed)
+    return rng.integers(0, p.X.size, size=n), rng.integers(0, p.W.size, size=n)
+
+
+def test_config3_reduced_batch_in_full():
+    from gpu_util import run_conv
+    p = workloads.config3(N=4)
+    _check(p, run_conv(p))
+
+
+@pytest.mark.parametrize("make", [workloads.config3, workloads.config4a, workloads.config4b])
+def test_fp32_conv_configs_full_size_sampled(make):
+    from gpu_util import run_conv
+    p = make()
+    res = run_conv(p)
+    assert abs(1 - res["stats"].nnz / p.delta.size - p.predicted_sparsity) < 5e-3
+    assert res["stats"].n_saturated == 0
+    _check(p, res, sample=_samples(p))
+
+
+@pytest.mark.parametrize("target", [0.5, 0.9, 0.99])
+def test_config5_int8_full_size_sampled(target):
+    from gpu_util import run_conv
+    p = workloads.config5(target)
+    res = run_conv(p)
+    assert abs(1 - res["stats"].nnz / p.delta.size - target) < 5e-3
+    assert res["stats"].n_saturated == 0
+    _check(p, res, sample=_samples(p, n=200))

@@ -38,7 +38,7 @@ def step_for_sparsity(delta: np.ndarray, target: float) -> float:
     if sample.size > (1 << 22):
         sample = sample[:: sample.size // (1 << 22)]
     lo, hi = 1e-12, float(np.max(np.abs(sample))) * 1e4 + 1e-6
-    for _ in range(200):
+    for _ in range(100):
         mid = np.sqrt(lo * hi)
         if expected_sparsity(sample, mid) < target:
             lo = mid
