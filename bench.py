@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the dithered-backprop hot path on one MI355X.
+
+One "step" = the whole hot path on the benchmark's configs[1]: the three-layer MLP backward chain
+(batch 256, 1024->4096->4096->1000, Delta = 8*std -> ~91% zero codes), i.e. per layer one NSD pass
+(Eq. (qdz)) and the two products dX = q.W, dW = q^T.X (Eqs. (qda),(qdw)), through the C ABI entry point
+dithered_linear_backward.  Inputs are synthetic (workloads.py), resident in HBM before the timed
+region, and three buffer sets are rotated so that the 256 MB Infinity Cache cannot stand in for HBM.
+
+Prints ONE JSON line: whole-job dense-equivalent TFLOP/s, plus `roofline` for the dominant kernel
+(timed alone with events on the launch stream), `cpu_baseline` (the CPU oracle on the host cores) and
+context numbers (NSD bandwidth on a 2^28-element tensor, the library's own dense fp32 backward and
+torch's dense matmul on the same shapes).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_BF16_TFLOPS = 2500.0
+PEAK_I8_TOPS = 5000.0
+PEAK_F32_MFMA_TFLOPS = 157.3
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--c", type=float, default=8.0, help="step-size multiple: Delta = c*std(delta)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--all", action="store_true", help="also time the conv / 8-bit configs (slower)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives are part of the hot path); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2004_04729_amd as dbp
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, iters, warm=3):
+        for _ in range(warm):
+            fn(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e-3          # seconds per call
+
+    # ------------------------------------------------------------------ workload: configs[1]
+    layers = workloads.config2(args.c)
+    NSETS = 3
+    sets = []
+    for s in range(NSETS):
+        bufs = []
+        for p in layers:
+            B, in_, out = p.dims
+            rng = np.random.default_rng(4242 + s)
+            perm = rng.permutation(B) if s else np.arange(B)       # same law, different bytes per set
+            d = torch.from_numpy(p.delta[perm]).to(dev)
+            W = torch.from_numpy(p.W).to(dev).clone()
+            X = torch.from_numpy(p.X[perm]).to(dev)
+            bufs.append(dict(p=p, d=d, W=W, X=X,
+                             codes=torch.empty((B, out), dtype=torch.int8, device=dev),
+                             dX=torch.empty((B, in_), dtype=torch.float32, device=dev),
+                             dW=torch.empty((out, in_), dtype=torch.float32, device=dev),
+                             ws=torch.empty(dbp.linear_workspace_bytes(B, in_, out), dtype=torch.uint8, device=dev),
+                             stats=torch.zeros(32, dtype=torch.uint8, device=dev)))
+        sets.append(bufs)
+
+    def step(i, path=dbp.PATH_AUTO):
+        for b in sets[i % NSETS]:
+            p = b["p"]
+            B, in_, out = p.dims
+            dbp.dithered_linear_backward(b["d"], b["W"], b["X"], dbp.F32, B, in_, out, p.step, p.seed, 0,
+                                         b["codes"], b["dX"], b["dW"], b["ws"], b["stats"], path, stream)
+
+    dense_flops = sum(2 * 2 * p.dims[0] * p.dims[1] * p.dims[2] for p in layers)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(args.steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / args.steps
+    t_step = max(e0.elapsed_time(e1) * 1e-3 / args.steps, 0.0)
+    t_step = max(t_step, 1e-9)
+    sparsity = []
+    nnz_total = 0
+    for b in sets[0]:
+        st = dbp.Stats.from_tensor(b["stats"])
+        sparsity.append(1 - st.nnz / b["d"].numel())
+        nnz_total += st.nnz
+    value = dense_flops / t_step / 1e12
+
+    # ------------------------------------------------------------------ per-kernel timings (L2 layer)
+    b2 = [s[1] for s in sets]                      # the 4096x4096 layer of each set
+    p2 = b2[0]["p"]
+    B, in_, out = p2.dims
+    fmts = [torch.empty(dbp.format_layout(B, out)["total_bytes"], dtype=torch.uint8, device=dev) for _ in b2]
+    for b, f in zip(b2, fmts):
+        dbp.nsd_quantize(b["d"], B, out, p2.step, p2.seed, 0, b["codes"], f, b["stats"], stream)
+
+    def k_dx(i, path=dbp.PATH_MFMA):
+        b = b2[i % NSETS]
+        dbp.linear_products(b["codes"], fmts[i % NSETS], p2.step, b["W"], b["X"], dbp.F32, B, in_, out, b["dX"], None, b["ws"], path, stream)
+
+    def k_dw(i, path=dbp.PATH_MFMA):
+        b = b2[i % NSETS]
+        dbp.linear_products(b["codes"], fmts[i % NSETS], p2.step, b["W"], b["X"], dbp.F32, B, in_, out, None, b["dW"], b["ws"], path, stream)
+
+    def k_nsd(i):
+        b = b2[i % NSETS]
+        dbp.nsd_quantize(b["d"], B, out, p2.step, p2.seed, 0, b["codes"], fmts[i % NSETS], b["stats"], stream)
+
+    iters = max(20, args.steps)
+    t_dx, t_dw, t_nsd_small = timed(k_dx, iters), timed(k_dw, iters), timed(k_nsd, iters)
+    t_dx_g = timed(lambda i: k_dx(i, dbp.PATH_GATHER), max(5, iters // 4))
+    t_dw_g = timed(lambda i: k_dw(i, dbp.PATH_GATHER), max(5, iters // 4))
+    mnk = 2.0 * B * in_ * out
+    # dominant kernel: the larger of the two matrix-core products of the 4096x4096 layer
+    dom_name, t_dom = ("gemm_kernel<bf16x3> dW (codes^T . X), 4096x4096x256", t_dw) if t_dw >= t_dx else \
+                      ("gemm_kernel<bf16x3> dX (codes . W), 256x4096x4096 split-K", t_dx)
+    alg_flops = 3 * mnk                            # three exact bf16 planes per fp32 operand element
+    roofline = {"bound": "mfma", "kernel": dom_name, "achieved": alg_flops / t_dom / 1e12, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": alg_flops / t_dom / 1e12 / PEAK_BF16_TFLOPS, "traffic": None,
+                "flops_counted": "3 bf16 planes x 2*M*N*K per launch", "us_per_launch": t_dom * 1e6,
+                "dense_equiv_tflops": mnk / t_dom / 1e12,
+                "hbm_bytes_algorithmic": 4 * (B * in_ + out * in_) + B * out,
+                "hbm_frac_if_memory_bound": (4 * (B * in_ + out * in_) + B * out) / t_dom / 1e9 / PEAK_HBM_GBS}
+
+    # ------------------------------------------------------------------ dense baselines on the same shapes
+    def dense_step(i):
+        for b in sets[i % NSETS]:
+            p = b["p"]
+            Bq, iq, oq = p.dims
+            dbp.dense_linear_backward(b["d"], b["W"], b["X"], dbp.F32, Bq, iq, oq, b["dX"], b["dW"], b["ws"], stream)
+
+    def torch_step(i):
+        for b in sets[i % NSETS]:
+            torch.matmul(b["d"], b["W"], out=b["dX"])
+            torch.matmul(b["d"].t(), b["X"], out=b["dW"])
+
+    t_dense = timed(dense_step, max(5, args.steps // 4))
+    torch.backends.cuda.matmul.allow_tf32 = False
+    t_torch = timed(torch_step, max(5, args.steps // 4))
+
+    # ------------------------------------------------------------------ NSD bandwidth on a 2^28-element tensor
+    n_big = 1 << 28
+    rows_b, cols_b = 1 << 16, 1 << 12
+    g = torch.Generator(device=dev)
+    g.manual_seed(1234)
+    big = torch.empty(n_big, dtype=torch.float32, device=dev)
+    big.exponential_(1.0 / 1e-3, generator=g)                      # |Laplace(0, 1e-3)|
+    sign = torch.empty(n_big, dtype=torch.float32, device=dev).uniform_(-1, 1, generator=g).sign_()
+    big.mul_(sign)
+    del sign
+    step_big = float(np.float32(8 * 1e-3 * np.sqrt(2.0)))
+    codes_big = torch.empty(n_big, dtype=torch.int8, device=dev)
+    fmt_big = torch.empty(dbp.format_layout(rows_b, cols_b)["total_bytes"], dtype=torch.uint8, device=dev)
+    st_big = torch.zeros(32, dtype=torch.uint8, device=dev)
+    t_nsd = timed(lambda i: dbp.nsd_quantize(big, rows_b, cols_b, step_big, 1, 0, codes_big, fmt_big, st_big, stream), 10)
+    nnz_big = dbp.Stats.from_tensor(st_big).nnz
+    nsd_bytes = n_big * (4 + 1 + 0.125 + 2.0 / 256) + 2.0 * nnz_big
+    nsd = {"elements": n_big, "sparsity": 1 - nnz_big / n_big, "ms": t_nsd * 1e3, "GBps": nsd_bytes / t_nsd / 1e9,
+           "frac_of_8TBps": nsd_bytes / t_nsd / 1e9 / PEAK_HBM_GBS, "bytes_per_element": nsd_bytes / n_big}
+    t_nsd_codes = timed(lambda i: dbp.nsd_quantize(big, rows_b, cols_b, step_big, 1, 0, codes_big, None, st_big, stream), 10)
+    nsd["codes_only_GBps"] = n_big * 5.0 / t_nsd_codes / 1e9
+    del big, codes_big, fmt_big
+
+    extra = {}
+    if args.all:
+        extra = bench_conv_configs(dbp, workloads, torch, np, timed, stream)
+
+    # ------------------------------------------------------------------ CPU oracle baseline
+    cpu = None
+    if not args.no_cpu:
+        from oracle import oracle as O
+        threads = O.max_threads()
+        t0 = time.perf_counter()
+        for p in layers:
+            k, _ = O.nsd(p.delta, p.step, p.seed)
+            O.linear_backward(p.W, p.X, codes=k, step=p.step, threads=threads)
+        t_cpu = time.perf_counter() - t0
+        cpu = {"value": dense_flops / t_cpu / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+               "sample": "one full step (3 layers: NSD + dX + dW, zero codes skipped, fp64 accumulate), %.2f s" % t_cpu}
+
+    out_line = {
+        "metric": "dithered backward dense-equiv TFLOP/s (NSD + dX + dW, 3-layer MLP chain)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16x3 MFMA (exact int8 codes x 3-plane split of fp32), fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: MLP backward chain, batch 256, 1024-4096-4096-1000, Delta=%g*std" % args.c,
+                   "sparsity_per_layer": [round(s, 4) for s in sparsity], "path": "AUTO (matrix cores)"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "host_wall_ms_per_step": wall * 1e3,
+        "vs_dense": {"same_library_fp32_mfma_ms": t_dense * 1e3, "torch_matmul_fp32_ms": t_torch * 1e3,
+                     "speedup_vs_same_library": t_dense / t_step, "speedup_vs_torch": t_torch / t_step},
+        "kernels_L2_us": {"nsd_1M_elements": t_nsd_small * 1e6, "dX_mfma": t_dx * 1e6, "dW_mfma": t_dw * 1e6,
+                          "dX_gather": t_dx_g * 1e6, "dW_gather": t_dw_g * 1e6},
+        "nsd_2^28": nsd,
+    }
+    if extra:
+        out_line["other_configs"] = extra
+    print(json.dumps(out_line))
+
+
+def bench_conv_configs(dbp, workloads, torch, np, timed, stream):
+    """Context lines for the conv / 8-bit configs: dithered vs the same library's dense backward."""
+    dev = torch.device("cuda:0")
+    res = {}
+    problems = [("cfg3", workloads.config3()), ("cfg4a", workloads.config4a()), ("cfg4b", workloads.config4b())]
+    problems += [("cfg5_s%g" % s, workloads.config5(s)) for s in (0.5, 0.9, 0.99)]
+    for name, p in problems:
+        N, Cc, H, Wd = p.X.shape
+        K, _, R, S = p.W.shape
+        i8 = p.X.dtype == np.int8
+        xd = dbp.I8 if i8 else dbp.F32
+        d, W, X = (torch.from_numpy(a).to(dev) for a in (p.delta, p.W, p.X))
+        codes = torch.empty(p.delta.shape, dtype=torch.int8, device=dev)
+        dX = torch.empty(p.X.shape, dtype=torch.float32, device=dev)
+        dW = torch.empty(p.W.shape, dtype=torch.int32 if i8 else torch.float32, device=dev)
+        ws = torch.empty(dbp.conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, 1, p.pad, xd), dtype=torch.uint8, device=dev)
+        st = torch.zeros(32, dtype=torch.uint8, device=dev)
+        t = timed(lambda i: dbp.dithered_conv2d_backward(d, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, p.step, p.seed, 0,
+                                                         codes, dX, dW, ws, st, dbp.PATH_AUTO, stream), 5, warm=1)
+        P, Q = p.delta.shape[2:]
+        flops = 2 * 2.0 * N * K * P * Q * Cc * R * S
+        row = {"ms": t * 1e3, "dense_equiv_tflops": flops / t / 1e12, "sparsity": 1 - dbp.Stats.from_tensor(st).nnz / p.delta.size}
+        if not i8:
+            t_d = timed(lambda i: dbp.dense_conv2d_backward(d, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, dX, dW, ws, stream), 3, warm=1)
+            row["same_library_dense_ms"] = t_d * 1e3
+        res[name] = row
+        del d, W, X, codes, dX, dW, ws
+    return res
+
+
+if __name__ == "__main__":
+    main()

@@ -86,10 +86,11 @@ typedef struct {
  * "sparse tensors with low precision non-zero values").  The code plane [rows x cols] is cut,
  * row by row, into tiles of DBP_TILE consecutive columns (a row's last tile may be short):
  * tiles_per_row = ceil(cols/256), tile t = row*tiles_per_row + col/256.  Per tile
- *   bitmap  [4t + w]     uint64: bit b set <=> code at in-tile column 64w+b is nonzero
+ *   bitmap  [4t + j]     uint64, j = 0..3: bit l set <=> code at in-tile column 4l+j is nonzero
+ *                        (column c is bit c/4 of word c%4: the wavefront ballots of the NSD kernel)
  *   tile_nnz[t]          uint16: number of nonzero codes of the tile
  *   entries [256t + i]   uint16, i < tile_nnz[t]: (in-tile column << 8) | (code & 0xFF),
- *                        columns ascending; later slots are not written.
+ *                        columns ascending; the contents of later slots are undefined.
  * All three arrays live in one caller-provided buffer at the byte offsets given here.
  */
 typedef struct {
@@ -98,6 +99,7 @@ typedef struct {
     size_t  bitmap_offset;     /* uint64[4*n_tiles]  */
     size_t  tile_nnz_offset;   /* uint16[n_tiles]    */
     size_t  entries_offset;    /* uint16[256*n_tiles]*/
+    size_t  scratch_offset;    /* 256 KiB used by the NSD pass itself (per-workgroup statistics) */
     size_t  total_bytes;
 } dbp_format_layout;
 
@@ -123,7 +125,9 @@ size_t dbp_conv2d_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, i
  *   step    Delta > 0 (the caller's s*sigma of Algorithm 1, steps 2-3).
  *   codes   [rows*cols] int8, out.
  *   format  buffer of dbp_format_layout.total_bytes, 256-byte aligned, out; NULL = codes only.
- *   stats   out, nullable.
+ *   stats   out, nullable.  With a format buffer the statistics are reduced without atomics (per-workgroup
+ *           partial sums in the buffer's scratch region, then one small kernel); without one they are
+ *           accumulated with device atomics from fewer workgroups, which is slower on large tensors.
  * Errors: NULL delta/codes -> DBP_ERR_NULL; rows/cols <= 0 or rows*cols >= 2^40 -> SHAPE;
  * bad step -> STEP; format too small/misaligned -> WORKSPACE.
  */

@@ -146,10 +146,11 @@ void dbp_oracle_nsd(const float *delta, int64_t n, float step, uint64_t seed,
  * with low precision non-zero values").  The code plane [rows x cols] is cut, row by
  * row, into tiles of 256 consecutive columns (the last tile of a row may be short);
  * tiles_per_row = ceil(cols/256), tile t = row*tiles_per_row + col/256.  Per tile:
- *   bitmap[4t + w]   bit b set  <=>  code at in-tile column 64w+b is nonzero
+ *   bitmap[4t + j]   bit l set  <=>  code at in-tile column 4l+j is nonzero (j = 0..3)
  *   tile_nnz[t]      number of nonzero codes in the tile
  *   entries[256t+i]  i < tile_nnz[t]: (in-tile column << 8) | (code & 0xFF), columns
- *                    ascending.  Slots at and beyond tile_nnz[t] are left untouched.
+ *                    ascending.  Slots at and beyond tile_nnz[t] are left untouched here
+ *                    (their contents are unspecified in the format).
  * ---------------------------------------------------------------------------------- */
 void dbp_oracle_tile_format(const int8_t *codes, int64_t rows, int64_t cols,
                             uint64_t *bitmap, uint16_t *tile_nnz, uint16_t *entries)
@@ -165,7 +166,7 @@ void dbp_oracle_tile_format(const int8_t *codes, int64_t rows, int64_t cols,
                 if (col >= cols) break;
                 int8_t k = codes[r * cols + col];
                 if (k != 0) {
-                    w[c >> 6] |= (uint64_t)1 << (c & 63);
+                    w[c & 3] |= (uint64_t)1 << (c >> 2);
                     entries[t * 256 + cnt] = (uint16_t)((c << 8) | (uint8_t)k);
                     cnt++;
                 }

@@ -25,7 +25,8 @@ class DbpError(RuntimeError):
 
 class _Layout(C.Structure):
     _fields_ = [("tiles_per_row", C.c_int64), ("n_tiles", C.c_int64), ("bitmap_offset", C.c_size_t),
-                ("tile_nnz_offset", C.c_size_t), ("entries_offset", C.c_size_t), ("total_bytes", C.c_size_t)]
+                ("tile_nnz_offset", C.c_size_t), ("entries_offset", C.c_size_t), ("scratch_offset", C.c_size_t),
+                ("total_bytes", C.c_size_t)]
 
 
 @dataclass

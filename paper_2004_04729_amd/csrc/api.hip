@@ -32,7 +32,8 @@ dbp_status format_layout(int64_t rows, int64_t cols, dbp_format_layout *L)
     L->bitmap_offset = 0;
     L->tile_nnz_offset = align_up((size_t)nt * 4 * sizeof(uint64_t), 256);
     L->entries_offset = L->tile_nnz_offset + align_up((size_t)nt * sizeof(uint16_t), 256);
-    L->total_bytes = L->entries_offset + align_up((size_t)nt * DBP_TILE * sizeof(uint16_t), 256);
+    L->scratch_offset = L->entries_offset + align_up((size_t)nt * DBP_TILE * sizeof(uint16_t), 256);
+    L->total_bytes = L->scratch_offset + kNsdScratchBytes;
     return DBP_OK;
 }
 
@@ -59,6 +60,7 @@ dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, u
     a.bitmap = fmt_base ? (uint64_t *)(fmt_base + L->bitmap_offset) : nullptr;
     a.tile_nnz = fmt_base ? (uint16_t *)(fmt_base + L->tile_nnz_offset) : nullptr;
     a.entries = fmt_base ? (uint16_t *)(fmt_base + L->entries_offset) : nullptr;
+    a.partials = fmt_base ? (u32x4 *)(fmt_base + L->scratch_offset) : nullptr;
     a.rows = rows; a.cols = cols; a.tiles_per_row = L->tiles_per_row; a.n_tiles = L->n_tiles;
     a.inv_step = 1.0f / step;
     const DitherKeys k = make_dither_keys(seed);

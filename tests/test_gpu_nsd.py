@@ -60,8 +60,9 @@ def test_codes_only_mode_and_determinism():
     c = run_nsd(d, 10, 3000, 4e-3, 1)
     k_ref, _ = O.nsd(d.ravel(), 4e-3, 1)
     assert np.array_equal(a["codes"].ravel(), k_ref) and np.array_equal(b["codes"], a["codes"])
-    assert np.array_equal(b["bitmap"], c["bitmap"]) and np.array_equal(b["entries"], c["entries"])
-    assert np.array_equal(b["tile_nnz"], c["tile_nnz"])
+    assert np.array_equal(b["bitmap"], c["bitmap"]) and np.array_equal(b["tile_nnz"], c["tile_nnz"])
+    used = np.arange(256)[None, :] < b["tile_nnz"][:, None].astype(np.int64)      # later slots are undefined
+    assert np.array_equal(b["entries"][used], c["entries"][used])
 
 
 def test_observed_sparsity_matches_prediction_on_the_configs():

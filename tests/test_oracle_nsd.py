@@ -229,7 +229,7 @@ def test_tile_format_decodes_back_to_the_code_plane(rows, cols):
             for i in range(int(tile_nnz[t])):
                 e = int(entries[t, i])
                 c, v = e >> 8, np.int8(np.uint8(e & 0xFF))
-                assert c > prev and (int(bitmap[t, c >> 6]) >> (c & 63)) & 1
+                assert c > prev and (int(bitmap[t, c & 3]) >> (c >> 2)) & 1
                 prev = c
                 dec[r, s * 256 + c] = v
             assert np.all(entries[t, int(tile_nnz[t]):] == 0xFFFF)          # untouched slots
