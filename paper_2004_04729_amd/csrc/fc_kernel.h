@@ -1,29 +1,43 @@
 // Fast matrix-core kernel for the two fully connected products, Eqs. (qda)/(qdw) (internal header).
 //
-//   dX[b,i] = Delta * sum_o code[b,o] W[o,i]      A = codes, reduction index contiguous  (A_KFAST)
-//   dW[o,i] = Delta * sum_b code[b,o] X[b,i]      A = codes^T, reduction index strided    (!A_KFAST)
+//   dX[b,i] = Delta * sum_o code[b,o] W[o,i]      A = codes, reduction index contiguous  (a_kfast)
+//   dW[o,i] = Delta * sum_b code[b,o] X[b,i]      A = codes^T, reduction index strided    (!a_kfast)
 //
 // In both products the fp32 operand is stored [reduction][column] with columns contiguous, so one B
 // path serves both: 16-byte loads along the columns, a 3-way exact bf16 split in registers, and
 // 8-byte LDS writes that assemble the [chunk][column] cells the MFMA fragments read.  Codes are
-// widened to bf16 (exact) on the way into LDS.  Arithmetic, tile shape and LDS cell layout are those
-// of gemm_core.h; what differs is the data movement: no per-element predicates in the main loop
-// (rows/columns outside the matrix are clamped to valid addresses and discarded at the store, only
-// the last K step masks), and a column/row permutation inside the tile that makes every LDS write
-// and read conflict-free and gives each lane adjacent output columns (8-byte stores).
+// widened to bf16 (exact) on the way into LDS.  Arithmetic and LDS cell layout are those of
+// gemm_core.h; what differs is the data movement (no per-element predicates in the main loop: rows and
+// columns outside the matrix are clamped to valid addresses and discarded at the store, only the last
+// K step masks; a column/row permutation inside the tile makes every LDS access conflict-free) and
+// the schedule:
+//
+//   * 128x128 tiles, 64 accumulator registers per wavefront, 32 KiB LDS per workgroup: three to four
+//     workgroups share a CU and fill each other's wait states.
+//   * ONE launch computes BOTH products.  Work items (tile, K-split) of the two products are dealt
+//     alternately to persistent workgroups; a workgroup's stores of one item drain while it loads the
+//     next.  dX streams W from HBM and writes little, dW reads little and writes its whole output,
+//     so mixing the two keeps loads, matrix cores and stores busy at the same time instead of in
+//     three chip-wide bursts.
+//   * Split-K partials are written in thread order and summed in split order by one small second
+//     launch for both products (deterministic).
 #pragma once
 #include "gemm_core.h"
 
 namespace dbp {
 
-struct FcArgs {
-    const int8_t *A; int64_t lda;     // A_KFAST: A[m*lda + k]   else: A[k*lda + m]
+constexpr int FC_TM = 128, FC_TN = 128, FC_KT = 32;
+
+struct FcProblem {
+    const int8_t *A; int64_t lda;     // a_kfast: A[m*lda + k]   else: A[k*lda + m]
     const float  *B; int64_t ldb;     // B[k*ldb + n]
     float *out; int64_t ldc;          // out[m*ldc + n]
-    float *partial;                   // split-K partials [z][M][N]
-    int M, N, K, k_per_split, tiles_m;
+    float *partial;                   // [tile][split][128*128] in thread order (n_split > 1)
+    int M, N, K, k_per_split, n_split, tiles_m, n_items;
     float scale;
+    int a_kfast;
 };
+struct FcPairArgs { FcProblem prob[2]; };
 
 __device__ __forceinline__ uint32_t bf16x2_from_codes(int a, int b)
 {
@@ -36,53 +50,44 @@ __device__ __forceinline__ uint32_t upper_halves(uint32_t hi_word, uint32_t lo_w
     return __builtin_amdgcn_perm(hi_word, lo_word, 0x07060302u);    // {hi_word[31:16], lo_word[31:16]}
 }
 
-template <bool A_KFAST, int AVEC>
-__global__ __launch_bounds__(256, 2) void fc_bf16_kernel(FcArgs p)
-{
-    constexpr int KT = 32;
-    __shared__ u32x4 sA[NCHUNK][TM];               // [chunk][row position]          16 KiB
-    __shared__ uint2 sB[3][NCHUNK][TN][2];         // [plane][chunk][col position][half]  24 KiB
+struct FcSmem {
+    uint2 a[NCHUNK][FC_TM][2];        // [chunk][row position][half]          8 KiB
+    uint2 b[3][NCHUNK][FC_TN][2];     // [plane][chunk][col position][half]  24 KiB
+};
 
+template <bool A_KFAST>
+__device__ __forceinline__ void fc_item(const FcProblem &p, int item, FcSmem &sm)
+{
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1;
-    const int tile_m = (blockIdx.x % p.tiles_m) * TM;
-    const int tile_n = (blockIdx.x / p.tiles_m) * TN;
-    const int k_begin = blockIdx.z * p.k_per_split;
+    const int tile = item / p.n_split, z = item - tile * p.n_split;
+    const int tile_m = (tile % p.tiles_m) * FC_TM;
+    const int tile_n = (tile / p.tiles_m) * FC_TN;
+    const int k_begin = z * p.k_per_split;
     const int k_end = min(p.K, k_begin + p.k_per_split);
 
-    // ---- B staging: thread owns columns 4*nq..4*nq+3 and reduction rows 4*kq..4*kq+3 of each step
+    // B staging: thread owns columns 4*nq..4*nq+3 and reduction rows 4*kq..4*kq+3 of each step
     const int nq = tid & 31, kq = tid >> 5;
     const float *b_ptr = p.B + min(tile_n + 4 * nq, p.N - 4) + (int64_t)(4 * kq) * p.ldb;
-    // ---- A staging
-    //   A_KFAST: thread owns row tid, all 32 reduction indices (32 contiguous bytes)
-    //   else   : thread owns rows 4*mq..4*mq+3 and reduction rows 8*wave..8*wave+7 (8 dwords)
-    const int mq = tid & 63;
-    const int8_t *a_ptr = A_KFAST ? p.A + (int64_t)min(tile_m + tid, p.M - 1) * p.lda
-                                  : p.A + min(tile_m + 4 * mq, p.M - 4) + (int64_t)(8 * wave) * p.lda;
+    // A staging
+    //   A_KFAST: thread owns row tid/2 and reduction indices 16*(tid&1) .. +15 (16 contiguous bytes)
+    //   else   : thread owns rows 4*nq..4*nq+3 and reduction rows 4*kq..4*kq+3 (4 dwords), like B
+    const int8_t *a_ptr = A_KFAST ? p.A + (int64_t)min(tile_m + (tid >> 1), p.M - 1) * p.lda + 16 * (tid & 1)
+                                  : p.A + min(tile_m + 4 * nq, p.M - 4) + (int64_t)(4 * kq) * p.lda;
 
     f32x4 b_raw[4];
-    uint32_t a_raw[8];
+    uint32_t a_raw[4];
 
     auto prefetch = [&](int k0) {
-        if (k0 + KT <= k_end) {
+        if (k0 + FC_KT <= k_end) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) b_raw[r] = *(const f32x4 *)(b_ptr + (int64_t)(k0 + r) * p.ldb);
             if (A_KFAST) {
-                const int8_t *q = a_ptr + k0;
-                if (AVEC == 16) {
-                    const u32x4 v0 = *(const u32x4 *)q, v1 = *(const u32x4 *)(q + 16);
-                    a_raw[0] = v0.x; a_raw[1] = v0.y; a_raw[2] = v0.z; a_raw[3] = v0.w;
-                    a_raw[4] = v1.x; a_raw[5] = v1.y; a_raw[6] = v1.z; a_raw[7] = v1.w;
-                } else if (AVEC == 8) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) { const uint2 v = *(const uint2 *)(q + 8 * r); a_raw[2 * r] = v.x; a_raw[2 * r + 1] = v.y; }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) a_raw[r] = *(const uint32_t *)(q + 4 * r);
-                }
+                for (int r = 0; r < 4; ++r) a_raw[r] = *(const uint32_t *)(a_ptr + k0 + 4 * r);
             } else {
 #pragma unroll
-                for (int r = 0; r < 8; ++r) a_raw[r] = *(const uint32_t *)(a_ptr + (int64_t)(k0 + r) * p.lda);
+                for (int r = 0; r < 4; ++r) a_raw[r] = *(const uint32_t *)(a_ptr + (int64_t)(k0 + r) * p.lda);
             }
         } else {
             // last, partial K step: mask by reduction index (zero codes and zero weights add exactly 0)
@@ -93,129 +98,169 @@ __global__ __launch_bounds__(256, 2) void fc_bf16_kernel(FcArgs p)
             }
             if (A_KFAST) {
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
+                for (int r = 0; r < 4; ++r) {
                     uint32_t w = 0;
 #pragma unroll
                     for (int b = 0; b < 4; ++b)
-                        if (k0 + 4 * r + b < k_end) w |= (uint32_t)(uint8_t)a_ptr[k0 + 4 * r + b] << (8 * b);
+                        if (k0 + 16 * (tid & 1) + 4 * r + b < k_end) w |= (uint32_t)(uint8_t)a_ptr[k0 + 4 * r + b] << (8 * b);
                     a_raw[r] = w;
                 }
             } else {
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
+                for (int r = 0; r < 4; ++r) {
                     a_raw[r] = 0u;
-                    if (k0 + 8 * wave + r < k_end) a_raw[r] = *(const uint32_t *)(a_ptr + (int64_t)(k0 + r) * p.lda);
+                    if (k0 + 4 * kq + r < k_end) a_raw[r] = *(const uint32_t *)(a_ptr + (int64_t)(k0 + r) * p.lda);
                 }
             }
         }
     };
 
     auto stage = [&]() {
-        // ---- codes -> bf16 cells
         if (A_KFAST) {
+            // 16 codes = chunks 2*(tid&1), 2*(tid&1)+1 of row tid/2
 #pragma unroll
-            for (int c = 0; c < NCHUNK; ++c) {
+            for (int c = 0; c < 2; ++c) {
                 const uint32_t w0 = a_raw[2 * c], w1 = a_raw[2 * c + 1];
-                u32x4 cell;
-                cell.x = bf16x2_from_codes((int8_t)w0, (int8_t)(w0 >> 8));
-                cell.y = bf16x2_from_codes((int8_t)(w0 >> 16), (int8_t)(w0 >> 24));
-                cell.z = bf16x2_from_codes((int8_t)w1, (int8_t)(w1 >> 8));
-                cell.w = bf16x2_from_codes((int8_t)(w1 >> 16), (int8_t)(w1 >> 24));
-                sA[c][tid] = cell;
+                sm.a[2 * (tid & 1) + c][tid >> 1][0] = uint2{bf16x2_from_codes((int8_t)w0, (int8_t)(w0 >> 8)),
+                                                             bf16x2_from_codes((int8_t)(w0 >> 16), (int8_t)(w0 >> 24))};
+                sm.a[2 * (tid & 1) + c][tid >> 1][1] = uint2{bf16x2_from_codes((int8_t)w1, (int8_t)(w1 >> 8)),
+                                                             bf16x2_from_codes((int8_t)(w1 >> 16), (int8_t)(w1 >> 24))};
             }
         } else {
-            // byte j of the 8 dwords = 8 consecutive reduction indices of row 4*mq+j -> position j*64+mq
+            // byte j of the 4 dwords = 4 consecutive reduction indices of row 4*nq+j -> position j*32+nq
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                u32x4 cell;
-                cell.x = bf16x2_from_codes((int8_t)(a_raw[0] >> (8 * j)), (int8_t)(a_raw[1] >> (8 * j)));
-                cell.y = bf16x2_from_codes((int8_t)(a_raw[2] >> (8 * j)), (int8_t)(a_raw[3] >> (8 * j)));
-                cell.z = bf16x2_from_codes((int8_t)(a_raw[4] >> (8 * j)), (int8_t)(a_raw[5] >> (8 * j)));
-                cell.w = bf16x2_from_codes((int8_t)(a_raw[6] >> (8 * j)), (int8_t)(a_raw[7] >> (8 * j)));
-                sA[wave][j * 64 + mq] = cell;
-            }
+            for (int j = 0; j < 4; ++j)
+                sm.a[kq >> 1][j * 32 + nq][kq & 1] =
+                    uint2{bf16x2_from_codes((int8_t)(a_raw[0] >> (8 * j)), (int8_t)(a_raw[1] >> (8 * j))),
+                          bf16x2_from_codes((int8_t)(a_raw[2] >> (8 * j)), (int8_t)(a_raw[3] >> (8 * j)))};
         }
-        // ---- fp32 -> three exact bf16 planes; column 4*nq+j -> position j*32+nq
+        // fp32 -> three exact bf16 planes; column 4*nq+j -> position j*32+nq
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             uint32_t h[4], m[4], l[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) split3(b_raw[r][j], h[r], m[r], l[r]);
             const int pos = j * 32 + nq;
-            sB[0][kq >> 1][pos][kq & 1] = uint2{upper_halves(l[1], l[0]), upper_halves(l[3], l[2])};
-            sB[1][kq >> 1][pos][kq & 1] = uint2{upper_halves(m[1], m[0]), upper_halves(m[3], m[2])};
-            sB[2][kq >> 1][pos][kq & 1] = uint2{upper_halves(h[1], h[0]), upper_halves(h[3], h[2])};
+            sm.b[0][kq >> 1][pos][kq & 1] = uint2{upper_halves(l[1], l[0]), upper_halves(l[3], l[2])};
+            sm.b[1][kq >> 1][pos][kq & 1] = uint2{upper_halves(m[1], m[0]), upper_halves(m[3], m[2])};
+            sm.b[2][kq >> 1][pos][kq & 1] = uint2{upper_halves(h[1], h[0]), upper_halves(h[3], h[2])};
         }
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[2][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     if (k_begin < k_end) prefetch(k_begin);
-    for (int k0 = k_begin; k0 < k_end; k0 += KT) {
+    for (int k0 = k_begin; k0 < k_end; k0 += FC_KT) {
         stage();
         __syncthreads();
-        if (k0 + KT < k_end) prefetch(k0 + KT);
+        if (k0 + FC_KT < k_end) prefetch(k0 + FC_KT);
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int ch = 2 * kk + (lane >> 5);
-            u32x4 bf[3][2];
+            u32x4 bf[3][2], af[2];
 #pragma unroll
             for (int pl = 0; pl < 3; ++pl)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    bf[pl][j] = *(const u32x4 *)&sB[pl][ch][wc * 64 + j * 32 + (lane & 31)][0];
+                    bf[pl][j] = *(const u32x4 *)&sm.b[pl][ch][wc * 64 + j * 32 + (lane & 31)][0];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const u32x4 af = sA[ch][wr * 128 + i * 32 + (lane & 31)];
-                // 32 rows x 16 reduction indices of codes all zero: nothing to add (structured sparsity)
-                if (__builtin_amdgcn_ballot_w64((af.x | af.y | af.z | af.w) != 0u) == 0ull) continue;
+            for (int i = 0; i < 2; ++i) af[i] = *(const u32x4 *)&sm.a[ch][wr * 64 + i * 32 + (lane & 31)][0];
+            // planes outermost: consecutive MFMAs accumulate into different blocks
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+            for (int pl = 0; pl < 3; ++pl)
 #pragma unroll
-                    for (int pl = 0; pl < 3; ++pl) Mma<MODE_BF16>::run(af, bf[pl][j], acc[i][j]);
-            }
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) Mma<MODE_BF16>::run(af[i], bf[pl][j], acc[i][j]);
         }
         __syncthreads();
     }
 
-    // ---- epilogue.  Block (i,j) of this wavefront covers row positions (4*wr+i)*32.. and column
-    // positions (2*wc+j)*32..; D[ii][jj] of a block sits in lane (jj, ii%8/4), register 4*(ii/8)+ii%4.
-    const bool direct = gridDim.z == 1;
+    // ---- split-K: park the partial tile in thread order; fc_reduce_kernel sums the splits in a fixed
+    // order.  (Summing in the last workgroup to arrive was tried: it needs device-scope fences, and on
+    // this multi-XCD part each such fence writes back a whole L2 -- 10x slower than a second launch.)
+    if (p.n_split > 1) {
+        float2 *mine = (float2 *)(p.partial + ((int64_t)tile * p.n_split + z) * (FC_TM * FC_TN));
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mine[(i * 16 + v) * 256 + tid] = float2{acc[i][0][v], acc[i][1][v]};
+        return;
+    }
+
+    // ---- epilogue: block (i,j) covers row positions (2*wr+i)*32.. and column positions (2*wc+j)*32..;
+    // D[ii][jj] of a block sits in lane (jj, ii%8/4), register 4*(ii/8)+ii%4.
     const int col = tile_n + 4 * (lane & 31) + 2 * wc;          // columns col, col+1 (j = 0, 1)
     if (col < p.N) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int mbg = wr * 4 + i;
+        for (int i = 0; i < 2; ++i) {
+            const int mbg = wr * 2 + i;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                const int row = A_KFAST ? tile_m + mbg * 32 + ii : tile_m + 128 * (mbg & 1) + 4 * ii + (mbg >> 1);
-                if (row >= p.M) continue;
-                if (direct) {
+                const int row = A_KFAST ? tile_m + mbg * 32 + ii : tile_m + 4 * ii + mbg;
+                if (row < p.M)
                     *(float2 *)(p.out + (int64_t)row * p.ldc + col) = float2{p.scale * acc[i][0][v], p.scale * acc[i][1][v]};
-                } else {
-                    *(float2 *)(p.partial + ((int64_t)blockIdx.z * p.M + row) * p.N + col) = float2{acc[i][0][v], acc[i][1][v]};
-                }
             }
         }
     }
 }
 
-// float4 reduction of split-K partials for plain row-major outputs (N % 4 == 0, ldc % 4 == 0)
-__global__ __launch_bounds__(256) void reduce4_kernel(const f32x4 *partial, float *out, int64_t ldc, int M, int N4, int nsplit, float scale)
+// Persistent workgroups; items of the two problems alternate (even = problem 0, odd = problem 1) for as
+// long as both have items left, so that neighbouring workgroups work on different products.
+__global__ __launch_bounds__(256, 3) void fc_pair_kernel(FcPairArgs a)
 {
-    const int64_t total = (int64_t)M * N4;
-    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
-        f32x4 s = partial[idx];
-        for (int z = 1; z < nsplit; ++z) s += partial[(int64_t)z * total + idx];
-        const int row = (int)(idx / N4), c4 = (int)(idx - (int64_t)row * N4);
-        *(f32x4 *)(out + (int64_t)row * ldc + 4 * c4) = s * scale;
+    __shared__ FcSmem sm;
+    const int n0 = a.prob[0].n_items, n1 = a.prob[1].n_items;
+    const int both = 2 * min(n0, n1), total = n0 + n1;
+    for (int t = blockIdx.x; t < total; t += gridDim.x) {
+        int which, item;
+        if (t < both) { which = t & 1; item = t >> 1; }
+        else { which = n0 > n1 ? 0 : 1; item = t - both + (both >> 1); }
+        const FcProblem &p = a.prob[which];
+        if (p.a_kfast) fc_item<true>(p, item, sm);
+        else fc_item<false>(p, item, sm);
+        __syncthreads();                                    // LDS is reused by the next item
+    }
+}
+
+// Second launch of a split-K run: workgroup (tile, quarter) sums the partials of 8 of the tile's 32
+// accumulator slots over the splits, in split order, and writes the output with the item's own mapping.
+__global__ __launch_bounds__(256) void fc_reduce_kernel(FcPairArgs a, int tiles0)
+{
+    const int which = (int)(blockIdx.x >> 2) < tiles0 ? 0 : 1;
+    const FcProblem &p = a.prob[which];
+    const int tile = (int)(blockIdx.x >> 2) - (which ? tiles0 : 0), quarter = blockIdx.x & 3;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int tile_m = (tile % p.tiles_m) * FC_TM;
+    const int tile_n = (tile / p.tiles_m) * FC_TN;
+    const float2 *all = (const float2 *)(p.partial + (int64_t)tile * p.n_split * (FC_TM * FC_TN));
+    const int col = tile_n + 4 * (lane & 31) + 2 * wc;
+    float2 sum[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) sum[u] = float2{0.f, 0.f};
+    for (int q = 0; q < p.n_split; ++q) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float2 t = all[(int64_t)q * (FC_TM * FC_TN / 2) + (quarter * 8 + u) * 256 + tid];
+            sum[u].x += t.x; sum[u].y += t.y;
+        }
+    }
+    if (col >= p.N) return;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int slot = quarter * 8 + u, i = slot >> 4, v = slot & 15;
+        const int mbg = wr * 2 + i;
+        const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int row = p.a_kfast ? tile_m + mbg * 32 + ii : tile_m + 4 * ii + mbg;
+        if (row < p.M) *(float2 *)(p.out + (int64_t)row * p.ldc + col) = float2{p.scale * sum[u].x, p.scale * sum[u].y};
     }
 }
 

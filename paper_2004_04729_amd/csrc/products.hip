@@ -88,61 +88,65 @@ size_t relayout_bytes(int64_t K, int64_t C, int64_t R, int64_t S)
     return align_up((size_t)(R * S * Kp * C) * sizeof(float), 256);
 }
 
-// Fast fully connected kernel (fc_kernel.h) when the layout allows 16-byte column loads; returns false
-// when the shape needs the generic kernel instead.
-template <bool A_KFAST>
-bool run_fc_fast(const int8_t *A, int64_t lda, const float *B, int64_t ldb, int M, int N, int K, float scale,
-                 float *out, void *scratch, size_t scratch_bytes, hipStream_t s, hipError_t *err)
+// ---- fast fully connected path (fc_kernel.h) -------------------------------------------------------
+struct FcPlan { int tiles_m, tiles_n, n_split, k_per_split; int64_t tiles; size_t partial_bytes; };
+
+// Aim at ~2 items per CU and product; never split below 4 K steps per item.
+FcPlan fc_plan(int64_t M, int64_t N, int64_t K)
 {
-    if (N < 4 || N % 4 || ldb % 4 || ((uintptr_t)B % 16) || ((uintptr_t)out % 16)) return false;
-    int avec = 0;
-    if (A_KFAST) {
-        avec = (lda % 16 == 0 && (uintptr_t)A % 16 == 0) ? 16 : (lda % 8 == 0 && (uintptr_t)A % 8 == 0) ? 8 :
-               (lda % 4 == 0 && (uintptr_t)A % 4 == 0) ? 4 : 0;
-        if (!avec) return false;
-    } else {
-        if (M < 4 || M % 4 || lda % 4 || ((uintptr_t)A % 4)) return false;
-    }
-    FcArgs p;
-    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.out = out; p.ldc = N; p.partial = (float *)scratch;
-    p.M = M; p.N = N; p.K = K; p.scale = scale;
-    p.tiles_m = (M + TM - 1) / TM;
-    const int tiles_n = (N + TN - 1) / TN;
-    const int64_t tiles = (int64_t)p.tiles_m * tiles_n;
-    Split sp = choose_split(tiles, K, 32);
-    while (sp.n > 1 && (size_t)sp.n * M * N * sizeof(float) > scratch_bytes) {
-        int64_t units = (K + 31) / 32, n = sp.n - 1;
-        sp.k_per = (int)((units + n - 1) / n * 32);
-        sp.n = (int)((K + sp.k_per - 1) / sp.k_per);
-    }
-    p.k_per_split = sp.n == 1 ? (K + 31) / 32 * 32 : sp.k_per;
-    const dim3 grid((unsigned)tiles, 1, (unsigned)sp.n), block(256);
-    if (!A_KFAST)         hipLaunchKernelGGL((fc_bf16_kernel<false, 4>), grid, block, 0, s, p);
-    else if (avec == 16)  hipLaunchKernelGGL((fc_bf16_kernel<true, 16>), grid, block, 0, s, p);
-    else if (avec == 8)   hipLaunchKernelGGL((fc_bf16_kernel<true, 8>), grid, block, 0, s, p);
-    else                  hipLaunchKernelGGL((fc_bf16_kernel<true, 4>), grid, block, 0, s, p);
-    *err = hipGetLastError();
-    if (*err == hipSuccess && sp.n > 1) {
-        const int64_t total4 = (int64_t)M * (N / 4);
-        const int blocks = (int)((total4 + 255) / 256 < 2048 ? (total4 + 255) / 256 : 2048);
-        hipLaunchKernelGGL(reduce4_kernel, dim3(blocks), dim3(256), 0, s, (const f32x4 *)scratch, out, (int64_t)N, M, N / 4, sp.n, scale);
-        *err = hipGetLastError();
-    }
+    FcPlan pl;
+    pl.tiles_m = (int)((M + FC_TM - 1) / FC_TM);
+    pl.tiles_n = (int)((N + FC_TN - 1) / FC_TN);
+    pl.tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+    const int64_t steps = (K + FC_KT - 1) / FC_KT;
+    int64_t want = (512 + pl.tiles - 1) / pl.tiles;
+    const int64_t max_n = steps / 4 > 0 ? steps / 4 : 1;
+    if (want > max_n) want = max_n;
+    if (want < 1) want = 1;
+    const int64_t per = (steps + want - 1) / want;
+    pl.k_per_split = (int)(per * FC_KT);
+    pl.n_split = (int)((steps + per - 1) / per);
+    pl.partial_bytes = pl.n_split > 1 ? (size_t)pl.tiles * pl.n_split * FC_TM * FC_TN * sizeof(float) : 0;
+    return pl;
+}
+
+bool fc_fast_ok(bool a_kfast, const int8_t *A, int64_t lda, const float *B, int64_t ldb, int64_t M, int64_t N, const float *out)
+{
+    if (N < 4 || N % 4 || ldb % 4 || ((uintptr_t)B % 16) || ((uintptr_t)out % 8)) return false;
+    if (lda % 4 || ((uintptr_t)A % 4)) return false;
+    if (!a_kfast && (M < 4 || M % 4)) return false;
     return true;
+}
+
+FcProblem fc_problem(bool a_kfast, const int8_t *A, int64_t lda, const float *B, int64_t ldb, int M, int N, int K,
+                     float scale, float *out, const FcPlan &pl, char *&scratch)
+{
+    FcProblem p;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.out = out; p.ldc = N;
+    p.M = M; p.N = N; p.K = K; p.scale = scale; p.a_kfast = a_kfast ? 1 : 0;
+    p.tiles_m = pl.tiles_m; p.n_split = pl.n_split; p.k_per_split = pl.k_per_split;
+    p.n_items = (int)(pl.tiles * pl.n_split);
+    p.partial = (float *)scratch;
+    scratch += align_up(pl.partial_bytes, 256);
+    return p;
 }
 
 }  // namespace
 
 size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
 {
-    // split-K partials of the larger of the two products, at the split the launcher would choose
+    // generic kernel: split-K partials of the larger of the two products, at the split the launcher would choose
     auto part = [](int64_t M, int64_t N, int64_t K) {
         int64_t tiles = ((M + TM - 1) / TM) * ((N + TN - 1) / TN);
         Split sp = choose_split(tiles, K, 16);          // smallest K step (fp32 mode) gives the largest split
         return sp.n > 1 ? (size_t)sp.n * M * N * 4 : (size_t)0;
     };
     size_t a = part(B, in, out), b = part(out, in, B);
-    return align_up(a > b ? a : b, 256) + 256;
+    const size_t generic = align_up(a > b ? a : b, 256);
+    // fast path: both products in one launch, each with its own partials
+    const FcPlan dx = fc_plan(B, in, out), dw = fc_plan(out, in, B);
+    const size_t fast = align_up(dx.partial_bytes, 256) + align_up(dw.partial_bytes, 256);
+    return (generic > fast ? generic : fast) + 256;
 }
 
 size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad)
@@ -168,23 +172,47 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
     hipError_t e = hipSuccess;
     RowMajorOut om{a.in};
     if (a.codes) {
-        if (a.dX && run_fc_fast<true>(a.codes, a.out, a.W, a.in, B, in, out, a.step, a.dX, a.scratch, a.scratch_bytes, s, &e)) {
+        // fast path: one launch for every product whose layout allows it
+        const bool dx_fast = a.dX && fc_fast_ok(true, a.codes, a.out, a.W, a.in, B, in, a.dX);
+        const bool dw_fast = a.dW && a.x_dtype == DBP_F32 &&
+                             fc_fast_ok(false, a.codes, a.out, (const float *)a.X, a.in, out, in, (const float *)a.dW);
+        if (dx_fast || dw_fast) {
+            char *scratch = (char *)a.scratch;
+            FcPairArgs pa;
+            const FcPlan none = {0, 0, 1, FC_KT, 0, 0};
+            const FcPlan pdx = dx_fast ? fc_plan(B, in, out) : none, pdw = dw_fast ? fc_plan(out, in, B) : none;
+            pa.prob[0] = fc_problem(true, a.codes, a.out, a.W, a.in, B, in, out, a.step, a.dX, pdx, scratch);
+            pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, a.step, (float *)a.dW, pdw, scratch);
+            if (!dx_fast) pa.prob[0].n_items = 0;
+            if (!dw_fast) pa.prob[1].n_items = 0;
+            if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
+            const int total = pa.prob[0].n_items + pa.prob[1].n_items;
+            // odd grid: a persistent workgroup then alternates between the two products
+            int grid = total < 767 ? total : 767;          // 3 resident workgroups on each of 256 CUs
+            hipLaunchKernelGGL(fc_pair_kernel, dim3(grid), dim3(256), 0, s, pa);
+            e = hipGetLastError();
             if (e != hipSuccess) return e;
-        } else if (a.dX) {
+            // split-K: one reduction launch for both products (a problem without splits gets no workgroups)
+            const bool r0 = dx_fast && pdx.n_split > 1, r1 = dw_fast && pdw.n_split > 1;
+            if (r0 || r1) {
+                FcPairArgs ra = pa;
+                int tiles0 = r0 ? (int)pdx.tiles : 0, tiles1 = r1 ? (int)pdw.tiles : 0;
+                hipLaunchKernelGGL(fc_reduce_kernel, dim3(4 * (tiles0 + tiles1)), dim3(256), 0, s, ra, tiles0);
+                e = hipGetLastError();
+                if (e != hipSuccess) return e;
+            }
+        }
+        if (a.dX && !dx_fast) {
             MatrixLoader<MODE_BF16, true, true>   al{a.codes, a.out, B, out};
             MatrixLoader<MODE_BF16, false, false> bl{a.W, a.in, in, out};
             e = run_gemm<MODE_BF16>(al, bl, om, B, in, out, k_step<MODE_BF16>(), a.step, a.dX, a.scratch, a.scratch_bytes, s);
             if (e != hipSuccess) return e;
         }
-        if (a.dW && a.x_dtype == DBP_F32 &&
-            run_fc_fast<false>(a.codes, a.out, (const float *)a.X, a.in, out, in, B, a.step, (float *)a.dW, a.scratch, a.scratch_bytes, s, &e)) {
-            return e;
-        }
-        if (a.dW && a.x_dtype == DBP_F32) {
+        if (a.dW && a.x_dtype == DBP_F32 && !dw_fast) {
             MatrixLoader<MODE_BF16, true, false>  al{a.codes, a.out, out, B};
             MatrixLoader<MODE_BF16, false, false> bl{(const float *)a.X, a.in, in, B};
             e = run_gemm<MODE_BF16>(al, bl, om, out, in, B, k_step<MODE_BF16>(), a.step, (float *)a.dW, a.scratch, a.scratch_bytes, s);
-        } else if (a.dW) {
+        } else if (a.dW && a.x_dtype != DBP_F32) {
             MatrixLoader<MODE_I8, true, false>  al{a.codes, a.out, out, B};
             MatrixLoader<MODE_I8, false, false> bl{(const int8_t *)a.X, a.in, in, B};
             e = run_gemm<MODE_I8>(al, bl, om, out, in, B, k_step<MODE_I8>(), 1.0f, (int32_t *)a.dW, a.scratch, a.scratch_bytes, s);
