@@ -35,6 +35,9 @@ def main():
     ap.add_argument("--c", type=float, default=8.0, help="step-size multiple: Delta = c*std(delta)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--all", action="store_true", help="also time the conv / 8-bit configs (slower)")
+    ap.add_argument("--probe", action="store_true",
+                    help="counter probe: one 1 GiB device copy of known size, then only the dominant kernel "
+                         "(for `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives are part of the hot path); use --gpus 1")
@@ -80,6 +83,25 @@ def main():
                              ws=torch.empty(dbp.linear_workspace_bytes(B, in_, out), dtype=torch.uint8, device=dev),
                              stats=torch.zeros(32, dtype=torch.uint8, device=dev)))
         sets.append(bufs)
+
+    if args.probe:
+        # counter probe: an elementwise kernel of known traffic (1 GiB read + 1 GiB written), then the dominant kernel
+        b = sets[0][1]
+        p2 = b["p"]
+        B, in_, out = p2.dims
+        fmt = torch.empty(dbp.format_layout(B, out)["total_bytes"], dtype=torch.uint8, device=dev)
+        dbp.nsd_quantize(b["d"], B, out, p2.step, p2.seed, 0, b["codes"], fmt, None, stream)
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.mul(src, 2.0, out=dst)
+        torch.cuda.synchronize()
+        for i in range(6):
+            dbp.linear_products(b["codes"], fmt, p2.step, b["W"], b["X"], dbp.F32, B, in_, out, b["dX"], b["dW"], b["ws"],
+                                dbp.PATH_MFMA, stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "torch.mul on 2^28 floats (1 GiB read, 1 GiB written) + 6 launches of fc_pair_kernel "
+                                   "and fc_reduce_kernel on the 256x4096x4096 layer"}))
+        return
 
     def step(i, path=dbp.PATH_AUTO):
         for b in sets[i % NSETS]:
@@ -127,25 +149,37 @@ def main():
         b = b2[i % NSETS]
         dbp.linear_products(b["codes"], fmts[i % NSETS], p2.step, b["W"], b["X"], dbp.F32, B, in_, out, None, b["dW"], b["ws"], path, stream)
 
+    def k_both(i, path=dbp.PATH_MFMA):
+        b = b2[i % NSETS]
+        dbp.linear_products(b["codes"], fmts[i % NSETS], p2.step, b["W"], b["X"], dbp.F32, B, in_, out, b["dX"], b["dW"], b["ws"], path, stream)
+
     def k_nsd(i):
         b = b2[i % NSETS]
         dbp.nsd_quantize(b["d"], B, out, p2.step, p2.seed, 0, b["codes"], fmts[i % NSETS], b["stats"], stream)
 
     iters = max(20, args.steps)
-    t_dx, t_dw, t_nsd_small = timed(k_dx, iters), timed(k_dw, iters), timed(k_nsd, iters)
+    t_dx, t_dw, t_both, t_nsd_small = timed(k_dx, iters), timed(k_dw, iters), timed(k_both, iters), timed(k_nsd, iters)
     t_dx_g = timed(lambda i: k_dx(i, dbp.PATH_GATHER), max(5, iters // 4))
     t_dw_g = timed(lambda i: k_dw(i, dbp.PATH_GATHER), max(5, iters // 4))
     mnk = 2.0 * B * in_ * out
-    # dominant kernel: the larger of the two matrix-core products of the 4096x4096 layer
-    dom_name, t_dom = ("gemm_kernel<bf16x3> dW (codes^T . X), 4096x4096x256", t_dw) if t_dw >= t_dx else \
-                      ("gemm_kernel<bf16x3> dX (codes . W), 256x4096x4096 split-K", t_dx)
-    alg_flops = 3 * mnk                            # three exact bf16 planes per fp32 operand element
-    roofline = {"bound": "mfma", "kernel": dom_name, "achieved": alg_flops / t_dom / 1e12, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": alg_flops / t_dom / 1e12 / PEAK_BF16_TFLOPS, "traffic": None,
-                "flops_counted": "3 bf16 planes x 2*M*N*K per launch", "us_per_launch": t_dom * 1e6,
-                "dense_equiv_tflops": mnk / t_dom / 1e12,
-                "hbm_bytes_algorithmic": 4 * (B * in_ + out * in_) + B * out,
-                "hbm_frac_if_memory_bound": (4 * (B * in_ + out * in_) + B * out) / t_dom / 1e9 / PEAK_HBM_GBS}
+    # Dominant kernel: fc_pair_kernel, both products of the 4096x4096 layer in one launch (its split-K
+    # reduction launch is included in the time).  Algorithmic work per launch:
+    # flops = 2 products x 3 exact bf16 planes x 2*B*in*out; HBM bytes = W + X + codes read, dX + dW written.
+    alg_flops = 2 * 3 * mnk
+    alg_bytes = 4.0 * (out * in_ + B * in_) + B * out + 4.0 * (B * in_ + out * in_)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "fc_pair_kernel_cfg2_L2_pmc.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
+    roofline = {"bound": "mfma", "kernel": "fc_pair_kernel (dX and dW of the 256x4096x4096 layer, one launch) + fc_reduce_kernel",
+                "achieved": alg_flops / t_both / 1e12, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": alg_flops / t_both / 1e12 / PEAK_BF16_TFLOPS, "traffic": traffic,
+                "flops_counted": "2 products x 3 bf16 planes x 2*M*N*K per launch", "us_per_launch": t_both * 1e6,
+                "dense_equiv_tflops": 2 * mnk / t_both / 1e12,
+                "hbm_bytes_algorithmic": alg_bytes,
+                "hbm_frac_of_8TBps": alg_bytes / t_both / 1e9 / PEAK_HBM_GBS}
 
     # ------------------------------------------------------------------ dense baselines on the same shapes
     def dense_step(i):
@@ -182,7 +216,7 @@ def main():
     nsd_bytes = n_big * (4 + 1 + 0.125 + 2.0 / 256) + 2.0 * nnz_big
     nsd = {"elements": n_big, "sparsity": 1 - nnz_big / n_big, "ms": t_nsd * 1e3, "GBps": nsd_bytes / t_nsd / 1e9,
            "frac_of_8TBps": nsd_bytes / t_nsd / 1e9 / PEAK_HBM_GBS, "bytes_per_element": nsd_bytes / n_big}
-    t_nsd_codes = timed(lambda i: dbp.nsd_quantize(big, rows_b, cols_b, step_big, 1, 0, codes_big, None, st_big, stream), 10)
+    t_nsd_codes = timed(lambda i: dbp.nsd_quantize(big, rows_b, cols_b, step_big, 1, 0, codes_big, None, None, stream), 10)
     nsd["codes_only_GBps"] = n_big * 5.0 / t_nsd_codes / 1e9
     del big, codes_big, fmt_big
 
@@ -195,13 +229,17 @@ def main():
     if not args.no_cpu:
         from oracle import oracle as O
         threads = O.max_threads()
+        reps, t_cpu = 0, 0.0
         t0 = time.perf_counter()
-        for p in layers:
-            k, _ = O.nsd(p.delta, p.step, p.seed)
-            O.linear_backward(p.W, p.X, codes=k, step=p.step, threads=threads)
-        t_cpu = time.perf_counter() - t0
+        while reps < 3 or (t_cpu < 5.0 and reps < 200):          # bounded sample: a few seconds of whole steps
+            for p in layers:
+                k, _ = O.nsd(p.delta, p.step, p.seed)
+                O.linear_backward(p.W, p.X, codes=k, step=p.step, threads=threads)
+            reps += 1
+            t_cpu = time.perf_counter() - t0
+        t_cpu /= reps
         cpu = {"value": dense_flops / t_cpu / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-               "sample": "one full step (3 layers: NSD + dX + dW, zero codes skipped, fp64 accumulate), %.2f s" % t_cpu}
+               "sample": "%d whole steps (3 layers: NSD + dX + dW, zero codes skipped, fp64 accumulate), %.3f s each" % (reps, t_cpu)}
 
     out_line = {
         "metric": "dithered backward dense-equiv TFLOP/s (NSD + dX + dW, 3-layer MLP chain)",
@@ -217,6 +255,7 @@ def main():
         "vs_dense": {"same_library_fp32_mfma_ms": t_dense * 1e3, "torch_matmul_fp32_ms": t_torch * 1e3,
                      "speedup_vs_same_library": t_dense / t_step, "speedup_vs_torch": t_torch / t_step},
         "kernels_L2_us": {"nsd_1M_elements": t_nsd_small * 1e6, "dX_mfma": t_dx * 1e6, "dW_mfma": t_dw * 1e6,
+                          "dX_and_dW_one_launch": t_both * 1e6,
                           "dX_gather": t_dx_g * 1e6, "dW_gather": t_dw_g * 1e6},
         "nsd_2^28": nsd,
     }

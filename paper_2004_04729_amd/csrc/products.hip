@@ -91,7 +91,9 @@ size_t relayout_bytes(int64_t K, int64_t C, int64_t R, int64_t S)
 // ---- fast fully connected path (fc_kernel.h) -------------------------------------------------------
 struct FcPlan { int tiles_m, tiles_n, n_split, k_per_split; int64_t tiles; size_t partial_bytes; };
 
-// Aim at ~2 items per CU and product; never split below 4 K steps per item.
+// Split the reduction of a product with few tiles into about two items per CU, never below 8 K steps per
+// item (the length of a dW item at batch 256, so the persistent workgroups stay balanced).  Every split
+// costs a partial write + read.
 FcPlan fc_plan(int64_t M, int64_t N, int64_t K)
 {
     FcPlan pl;
@@ -100,7 +102,7 @@ FcPlan fc_plan(int64_t M, int64_t N, int64_t K)
     pl.tiles = (int64_t)pl.tiles_m * pl.tiles_n;
     const int64_t steps = (K + FC_KT - 1) / FC_KT;
     int64_t want = (512 + pl.tiles - 1) / pl.tiles;
-    const int64_t max_n = steps / 4 > 0 ? steps / 4 : 1;
+    const int64_t max_n = steps / 8 > 0 ? steps / 8 : 1;
     if (want > max_n) want = max_n;
     if (want < 1) want = 1;
     const int64_t per = (steps + want - 1) / want;
