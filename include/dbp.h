@@ -30,7 +30,10 @@
  *     DBP_ERR_DEVICE can be produced on a machine without a GPU.  Nothing aborts or throws.
  *   - `workspace` is device scratch of at least the size the matching *_workspace_bytes
  *     function returns, 256-byte aligned.  Its contents need not be initialised and are
- *     undefined afterwards, except for the tile-sparse format (see below) which stays valid.
+ *     undefined afterwards, except that dithered_linear_backward with path == DBP_PATH_GATHER
+ *     leaves the tile-sparse format (see below) at the start of the workspace.  The other
+ *     paths do not read that format and do not spend bandwidth writing it; nsd_quantize
+ *     produces it on request.
  *   - The dither of element j of delta is a pure function of (seed, idx_base + j), where j is
  *     the row-major flat index; a shard of a larger tensor passes its offset as idx_base and
  *     obtains bit-identical codes.

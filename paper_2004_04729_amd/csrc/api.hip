@@ -52,20 +52,24 @@ Carve carve(int64_t rows, int64_t cols, size_t scratch_bytes)
     return c;
 }
 
+// `fmt_base` is a buffer with layout *L; the tile-sparse arrays are written only if `want_format`
+// (its statistics records are used either way).
 dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
-                   int8_t *codes, char *fmt_base, const dbp_format_layout *L, dbp_stats *stats, hipStream_t s)
+                   int8_t *codes, char *fmt_base, const dbp_format_layout *L, dbp_stats *stats, hipStream_t s,
+                   bool want_format = true, StatsJob *defer = nullptr)
 {
     NsdArgs a;
     a.delta = delta; a.codes = codes; a.stats = stats;
-    a.bitmap = fmt_base ? (uint64_t *)(fmt_base + L->bitmap_offset) : nullptr;
-    a.tile_nnz = fmt_base ? (uint16_t *)(fmt_base + L->tile_nnz_offset) : nullptr;
-    a.entries = fmt_base ? (uint16_t *)(fmt_base + L->entries_offset) : nullptr;
+    const bool fmt = fmt_base && want_format;
+    a.bitmap = fmt ? (uint64_t *)(fmt_base + L->bitmap_offset) : nullptr;
+    a.tile_nnz = fmt ? (uint16_t *)(fmt_base + L->tile_nnz_offset) : nullptr;
+    a.entries = fmt ? (uint16_t *)(fmt_base + L->entries_offset) : nullptr;
     a.partials = fmt_base ? (u32x4 *)(fmt_base + L->scratch_offset) : nullptr;
     a.rows = rows; a.cols = cols; a.tiles_per_row = L->tiles_per_row; a.n_tiles = L->n_tiles;
     a.inv_step = 1.0f / step;
     const DitherKeys k = make_dither_keys(seed);
     a.k0 = k.k0; a.k1 = k.k1; a.idx_base = idx_base;
-    return launch_nsd(a, s) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+    return launch_nsd(a, s, defer) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
 dbp_status check_linear_dims(int64_t B, int64_t in, int64_t out)
@@ -88,6 +92,38 @@ dbp_status check_conv_dims(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t 
     if (N * H * Wd >= lim || N * (*P * *Q + 64) >= lim || C * R * S >= lim || R * S * (K + 16) >= lim) return DBP_ERR_SHAPE;
     if (N * K * *P * *Q >= kMaxElems || N * C * H * Wd >= kMaxElems) return DBP_ERR_SHAPE;
     return DBP_OK;
+}
+
+dbp_status linear_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
+                           dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX, void *dW,
+                           void *workspace, size_t workspace_bytes, dbp_path path, void *stream, StatsJob job)
+{
+    if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    dbp_status st = check_linear_dims(B, in, out);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    LinearArgs a;
+    a.codes = codes; a.dense = nullptr; a.step = step; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.stats_job = job;
+    if (path == DBP_PATH_GATHER) {
+        if (!format) return DBP_ERR_NULL;
+        if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
+        dbp_format_layout L;
+        format_layout(B, out, &L);
+        const char *fb = (const char *)format;
+        FormatView f{(const uint64_t *)(fb + L.bitmap_offset), (const uint16_t *)(fb + L.tile_nnz_offset),
+                     (const uint16_t *)(fb + L.entries_offset), L.tiles_per_row};
+        a.scratch = nullptr; a.scratch_bytes = 0;
+        if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
+        return launch_linear_gather(a, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+    }
+    const size_t need = linear_scratch_bytes(B, in, out);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
 }  // namespace
@@ -150,31 +186,8 @@ dbp_status dbp_linear_products(const int8_t *codes, const void *format, float st
                                dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX, void *dW,
                                void *workspace, size_t workspace_bytes, dbp_path path, void *stream)
 {
-    if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
-    dbp_status st = check_linear_dims(B, in, out);
-    if (st != DBP_OK) return st;
-    if (!step_ok(step)) return DBP_ERR_STEP;
-    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    LinearArgs a;
-    a.codes = codes; a.dense = nullptr; a.step = step; a.W = W; a.X = X; a.x_dtype = x_dtype;
-    a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW;
-    if (path == DBP_PATH_GATHER) {
-        if (!format) return DBP_ERR_NULL;
-        if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
-        dbp_format_layout L;
-        format_layout(B, out, &L);
-        const char *fb = (const char *)format;
-        FormatView f{(const uint64_t *)(fb + L.bitmap_offset), (const uint16_t *)(fb + L.tile_nnz_offset),
-                     (const uint16_t *)(fb + L.entries_offset), L.tiles_per_row};
-        a.scratch = nullptr; a.scratch_bytes = 0;
-        return launch_linear_gather(a, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
-    }
-    const size_t need = linear_scratch_bytes(B, in, out);
-    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
-    a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+    return linear_products(codes, format, step, W, X, x_dtype, B, in, out, dX, dW, workspace, workspace_bytes, path,
+                           stream, StatsJob{nullptr, 0, nullptr});
 }
 
 dbp_status dithered_linear_backward(const float *delta, const float *W, const void *X, dbp_dtype x_dtype,
@@ -194,10 +207,13 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    st = run_nsd(delta, B, out, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream);
+    // only the gather kernels read the tile-sparse arrays; the statistics are summed by the products' launch
+    StatsJob job;
+    st = run_nsd(delta, B, out, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream,
+                 path == DBP_PATH_GATHER, &job);
     if (st != DBP_OK) return st;
-    return dbp_linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset,
-                               workspace_bytes - c.scratch_offset, path, stream);
+    return linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset,
+                           workspace_bytes - c.scratch_offset, path, stream, job);
 }
 
 dbp_status dbp_conv2d_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
@@ -221,6 +237,7 @@ dbp_status dbp_conv2d_products(const int8_t *codes, const void *format, float st
     a.codes = codes; a.dense = nullptr; a.step = step; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    a.stats_job = StatsJob{nullptr, 0, nullptr};
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -244,7 +261,7 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream);
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, false);
     if (st != DBP_OK) return st;
     return dbp_conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
                                ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path, stream);
@@ -265,6 +282,7 @@ dbp_status dense_linear_backward(const void *delta, const float *W, const void *
     LinearArgs a;
     a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    a.stats_job = StatsJob{nullptr, 0, nullptr};
     return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -287,6 +305,7 @@ dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *
     a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    a.stats_job = StatsJob{nullptr, 0, nullptr};
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 

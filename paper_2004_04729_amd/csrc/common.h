@@ -36,7 +36,13 @@ struct NsdArgs {
     int          run;                                  // consecutive tiles per wavefront run (set by launch_nsd)
     int64_t      wave_stride_rows, wave_stride_segs;   // grid stride in tiles = rows*tiles_per_row + segs (set by launch_nsd)
 };
-hipError_t launch_nsd(const NsdArgs &a, hipStream_t s);
+// Pending reduction of the per-workgroup statistics records into one dbp_stats (n == 0: nothing pending).
+struct StatsJob { const u32x4 *partials; int n; dbp_stats *out; };
+// Launches the quantiser.  With `defer` non-null and statistics kept in records, the final sum is not
+// launched: *defer describes it, and the caller either folds it into a later kernel of the same stream
+// or calls launch_stats_job.
+hipError_t launch_nsd(const NsdArgs &a, hipStream_t s, StatsJob *defer = nullptr);
+hipError_t launch_stats_job(const StatsJob &j, hipStream_t s);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -57,6 +63,7 @@ struct LinearArgs {
     void         *dW;          // nullable
     void         *scratch;     // split-K partials
     size_t        scratch_bytes;
+    StatsJob      stats_job;   // statistics sum still to be done on this stream (n == 0: none)
 };
 struct ConvArgs {
     const int8_t *codes;
@@ -70,6 +77,7 @@ struct ConvArgs {
     void         *dW;
     void         *scratch;
     size_t        scratch_bytes;
+    StatsJob      stats_job;
 };
 size_t     linear_scratch_bytes(int64_t B, int64_t in, int64_t out);
 size_t     conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad);

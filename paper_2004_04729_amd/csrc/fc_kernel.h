@@ -37,7 +37,7 @@ struct FcProblem {
     float scale;
     int a_kfast;
 };
-struct FcPairArgs { FcProblem prob[2]; };
+struct FcPairArgs { FcProblem prob[2]; StatsJob stats; };
 
 __device__ __forceinline__ uint32_t bf16x2_from_codes(int a, int b)
 {
@@ -214,9 +214,41 @@ __device__ __forceinline__ void fc_item(const FcProblem &p, int item, FcSmem &sm
 
 // Persistent workgroups; items of the two problems alternate (even = problem 0, odd = problem 1) for as
 // long as both have items left, so that neighbouring workgroups work on different products.
+// Sum of the quantiser's per-workgroup statistics records by one workgroup of 256 threads (integer
+// sums and a maximum: the result does not depend on the order).
+__device__ __forceinline__ void fc_sum_stats(const StatsJob &j, uint64_t *lds)
+{
+    uint64_t nnz = 0, sat = 0, nf = 0, mx = 0;
+    for (int i = threadIdx.x; i < j.n; i += 256) {
+        const u32x4 q = j.partials[i];
+        nnz += q.x; sat += q.y; nf += q.z; mx = mx > q.w ? mx : q.w;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        nnz += __shfl_xor((unsigned long long)nnz, off); sat += __shfl_xor((unsigned long long)sat, off);
+        nf += __shfl_xor((unsigned long long)nf, off);
+        const uint64_t o = __shfl_xor((unsigned long long)mx, off);
+        mx = mx > o ? mx : o;
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { lds[4 * wave] = nnz; lds[4 * wave + 1] = sat; lds[4 * wave + 2] = nf; lds[4 * wave + 3] = mx; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t m = 0;
+        for (int w = 0; w < 4; ++w) m = m > lds[4 * w + 3] ? m : lds[4 * w + 3];
+        j.out->nnz = lds[0] + lds[4] + lds[8] + lds[12];
+        j.out->n_saturated = lds[1] + lds[5] + lds[9] + lds[13];
+        j.out->n_nonfinite = lds[2] + lds[6] + lds[10] + lds[14];
+        j.out->max_abs_code = (int32_t)m; j.out->reserved = 0;
+    }
+    __syncthreads();                                        // the items reuse this LDS
+}
+
 __global__ __launch_bounds__(256, 3) void fc_pair_kernel(FcPairArgs a)
 {
     __shared__ FcSmem sm;
+    // the last workgroup has the fewest items: it also finishes the quantiser's statistics
+    if (a.stats.n > 0 && blockIdx.x == gridDim.x - 1) fc_sum_stats(a.stats, (uint64_t *)&sm);
     const int n0 = a.prob[0].n_items, n1 = a.prob[1].n_items;
     const int both = 2 * min(n0, n1), total = n0 + n1;
     for (int t = blockIdx.x; t < total; t += gridDim.x) {

@@ -303,8 +303,16 @@ DitherKeys make_dither_keys(uint64_t seed)
     return k;
 }
 
-hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s)
+hipError_t launch_stats_job(const StatsJob &j, hipStream_t s)
 {
+    if (j.n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(finalize_stats_kernel, dim3(1), dim3(1024), 0, s, j.partials, j.n, j.out);
+    return hipGetLastError();
+}
+
+hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s, StatsJob *defer)
+{
+    if (defer) *defer = StatsJob{nullptr, 0, nullptr};
     NsdArgs a = a_in;
     if (!a.stats) a.partials = nullptr;
     const bool use_atomics = a.stats && !a.partials;
@@ -328,8 +336,11 @@ hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s)
     else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false>), grid, block, 0, s, a);
     else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true>), grid, block, 0, s, a);
     else                       hipLaunchKernelGGL((nsd_kernel<false, false>), grid, block, 0, s, a);
-    if (a.partials)
-        hipLaunchKernelGGL(finalize_stats_kernel, dim3(1), dim3(1024), 0, s, (const u32x4 *)a.partials, (int)blocks, a.stats);
+    if (a.partials) {
+        const StatsJob j{(const u32x4 *)a.partials, (int)blocks, a.stats};
+        if (defer) *defer = j;
+        else return launch_stats_job(j, s);
+    }
     return hipGetLastError();
 }
 

@@ -173,6 +173,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
     const int B = (int)a.B, in = (int)a.in, out = (int)a.out;
     hipError_t e = hipSuccess;
     RowMajorOut om{a.in};
+    StatsJob pending = a.stats_job;
     if (a.codes) {
         // fast path: one launch for every product whose layout allows it
         const bool dx_fast = a.dX && fc_fast_ok(true, a.codes, a.out, a.W, a.in, B, in, a.dX);
@@ -187,6 +188,8 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, a.step, (float *)a.dW, pdw, scratch);
             if (!dx_fast) pa.prob[0].n_items = 0;
             if (!dw_fast) pa.prob[1].n_items = 0;
+            pa.stats = pending;                            // summed by the last workgroup of the launch
+            pending.n = 0;
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
             // odd grid: a persistent workgroup then alternates between the two products
@@ -204,6 +207,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
                 if (e != hipSuccess) return e;
             }
         }
+        if (pending.n) { e = launch_stats_job(pending, s); if (e != hipSuccess) return e; }
         if (a.dX && !dx_fast) {
             MatrixLoader<MODE_BF16, true, true>   al{a.codes, a.out, B, out};
             MatrixLoader<MODE_BF16, false, false> bl{a.W, a.in, in, out};
@@ -222,6 +226,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
         return e;
     }
     // dense baseline
+    if (pending.n) { e = launch_stats_job(pending, s); if (e != hipSuccess) return e; }
     if (a.dX) {
         MatrixLoader<MODE_F32, false, true>  al{(const float *)a.dense, a.out, B, out};
         MatrixLoader<MODE_F32, false, false> bl{a.W, a.in, in, out};

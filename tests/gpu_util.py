@@ -94,8 +94,10 @@ def run_linear(p, path=dbp.PATH_MFMA, x_i8=None, want_dx=True, want_dw=True, fus
           torch.full((out, in_), float("nan"), dtype=torch.float32, device=DEV)) if want_dw else None
     xd = dbp.I8 if i8 else dbp.F32
     ws = torch.empty(dbp.linear_workspace_bytes(B, in_, out, xd), dtype=torch.uint8, device=DEV)
+    st = None
     if fused:
-        dbp.dithered_linear_backward(d, W, X, xd, B, in_, out, p.step, p.seed, 0, codes, dX, dW, ws, None, path, stream())
+        st = torch.full((32,), 0xEE, dtype=torch.uint8, device=DEV)
+        dbp.dithered_linear_backward(d, W, X, xd, B, in_, out, p.step, p.seed, 0, codes, dX, dW, ws, st, path, stream())
     else:
         L = dbp.format_layout(B, out)
         fmt = torch.empty(L["total_bytes"], dtype=torch.uint8, device=DEV)
@@ -107,7 +109,7 @@ def run_linear(p, path=dbp.PATH_MFMA, x_i8=None, want_dx=True, want_dw=True, fus
         dbp.linear_products(codes, fmt, p.step, W, X, xd, B, in_, out, dX, dW, ws, path, stream())
     torch.cuda.synchronize()
     return {"codes": codes.cpu().numpy(), "dX": None if dX is None else dX.cpu().numpy(),
-            "dW": None if dW is None else dW.cpu().numpy()}
+            "dW": None if dW is None else dW.cpu().numpy(), "stats": None if st is None else dbp.Stats.from_tensor(st)}
 
 
 def conv_dims(p):

@@ -20,8 +20,12 @@ def _problem(B, in_, out, c=4.0, seed=0, x_zero_frac=0.5):
 def _check_fp32(p, res):
     from gpu_util import check_products
     from oracle import oracle as O
-    k_ref, _ = O.nsd(p.delta, p.step, p.seed)
+    k_ref, st = O.nsd(p.delta, p.step, p.seed)
     assert np.array_equal(res["codes"], k_ref)
+    if res.get("stats") is not None:          # the fused entry point sums the statistics in the products' launch
+        got = res["stats"]
+        assert (got.nnz, got.n_saturated, got.n_nonfinite, got.max_abs_code) == \
+               (st.nnz, st.n_saturated, st.n_nonfinite, st.max_abs_code)
     rX, rW, _ = O.linear_backward(p.W, p.X, codes=k_ref, step=p.step)
     aX, aW, _ = O.linear_backward(np.abs(p.W), np.abs(p.X), codes=np.abs(k_ref), step=p.step)
     e1 = check_products(res["dX"], rX, aX, p.name + " dX") if res["dX"] is not None else 0
@@ -126,3 +130,22 @@ def test_config1_and_config2_full_size():
     from gpu_util import run_linear
     for p in [workloads.config1()] + workloads.config2(8.0):
         _check_fp32(p, run_linear(p, path=dbp.PATH_AUTO))
+
+
+@pytest.mark.parametrize("B,in_,out", [(64, 512, 384), (300, 520, 1030), (33, 70, 129)])
+def test_fc_fused_call_reports_statistics(B, in_, out):
+    # saturating and non-finite gradients, through the single-call entry point (its statistics are summed
+    # inside the products' launch on the fast path, by a launch of their own otherwise)
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_linear
+    from oracle import oracle as O
+    p = _problem(B, in_, out, c=2.0)
+    flat = p.delta.reshape(-1)
+    flat[::97] = 10.0
+    flat[5::211] = -10.0
+    flat[7::1013] = np.nan
+    flat[11::1999] = np.inf
+    res = run_linear(p, path=dbp.PATH_MFMA)
+    _, st = O.nsd(p.delta, p.step, p.seed)
+    assert st.n_saturated > 0 and st.n_nonfinite > 0 and st.max_abs_code == 127
+    _check_fp32(p, res)
