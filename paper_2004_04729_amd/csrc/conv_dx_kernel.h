@@ -1,0 +1,240 @@
+// Input-gradient product of a stride-1 convolution from int8 codes, the convolutional analogue of Eq. (qda):
+//   dX[n,c,h,w] = Delta * sum_{k,r,s} code[n,k,h+pad-r,w+pad-s] * W[k,c,r,s]
+// on bf16 matrix cores with the bf16x3 weight split (exact codes x three-plane weights, fp32 accumulate).
+//
+// Orientation: D[c][pixel] = sum_kk Wp[c][kk] * code[kk][pixel], kk = (tap, k).  Output pixels are the
+// matrix-core columns, so every store instruction writes runs of 32 consecutive pixels of one channel.
+//
+//   * A workgroup owns a run of consecutive output pixels of ONE image and up to four 32-channel blocks.
+//     Its code patch (the pixels' rows plus the kernel halo, zero outside the image) lives in LDS as bf16
+//     cells [k-group][patch pixel][8 k]: one 16-byte cell is exactly the matrix-core fragment of a lane.
+//     All R*S taps read the same patch at a per-tap cell offset, so codes are fetched, transposed and
+//     converted once per 32 reduction channels instead of once per tap.
+//   * Weights are split into bf16 planes and re-laid once per call (conv_dx_weight_prep_kernel) into
+//     fragment order [tap][k-group][plane][c][8 k]; a lane then loads its weight fragment with one
+//     16-byte global load (L2-resident: every workgroup streams the same few MB in the same order).
+//   * The patch is double buffered over 32-channel reduction chunks: one barrier per chunk; the next
+//     chunk's codes are in flight as global loads during the current chunk's matrix-core phase.
+//   * The whole reduction stays inside the workgroup: no split-K, no second launch.
+#pragma once
+#include "gemm_core.h"
+
+namespace dbp {
+
+constexpr int CDX_KGC = 4;            // k-groups (of 8 channels) per reduction chunk
+constexpr int CDX_ITMAX = 2;          // patch-fill items per thread and chunk, at most
+constexpr int CDX_MAX_LDS = 64 * 1024;   // dynamic LDS a launch may ask for without raising the function attribute
+
+struct ConvDxArgs {
+    const int8_t *codes;      // [N][K][P][Q]
+    const uint4  *wp;         // prepared weights, cell ((tap*KG + kg)*3 + plane)*Cp + c
+    float        *dX;         // [N][C][H][Wd]
+    int N, C, H, Wd, K, R, S, pad, P, Q;
+    int PI, PQ;               // H*Wd, P*Q
+    int Cp, KG, n_chunks;     // C rounded to 32; k-groups in total (K rounded to 32, over 8); chunks of 32 channels
+    int wc, wpx;              // waves along channels x waves along pixels (wc * wpx == 4)
+    int cgroups;              // ceil(C / (32*wc))
+    int tiles;                // pixel tiles per image
+    int prow, pw, patch_cells;// patch rows (maximum over tiles), patch width Wd+S-1 ... cells per k-group
+    float scale;
+};
+
+// fp32 weights [K][C][R][S] -> bf16 planes in fragment order (plane 0 = lo, 1 = mid, 2 = hi), zero padded.
+__global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W, uint4 *wp, int K, int C, int RS, int KG, int Cp)
+{
+    const int64_t total = (int64_t)RS * KG * Cp;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int c = (int)(i % Cp);
+        const int64_t t = i / Cp;
+        const int kg = (int)(t % KG), tap = (int)(t / KG);
+        uint32_t h[8], m[8], l[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int k = kg * 8 + j;
+            const float w = (k < K && c < C) ? W[((int64_t)k * C + c) * RS + tap] : 0.0f;
+            split3(w, h[j], m[j], l[j]);
+        }
+        uint4 *dst = wp + ((int64_t)tap * KG + kg) * 3 * Cp + c;
+        dst[0]      = uint4{(l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]};
+        dst[Cp]     = uint4{(m[0] >> 16) | m[1], (m[2] >> 16) | m[3], (m[4] >> 16) | m[5], (m[6] >> 16) | m[7]};
+        dst[2 * Cp] = uint4{(h[0] >> 16) | h[1], (h[2] >> 16) | h[3], (h[4] >> 16) | h[5], (h[6] >> 16) | h[7]};
+    }
+}
+
+__device__ __forceinline__ uint32_t cdx_bf16_pair(uint32_t wa, uint32_t wb, int e)
+{
+    // bytes e of words wa, wb as signed codes -> two bf16 (exact), wa's in the low half
+    const float fa = (float)((int)(wa << (24 - 8 * e)) >> 24), fb = (float)((int)(wb << (24 - 8 * e)) >> 24);
+    return __builtin_amdgcn_perm(__float_as_uint(fb), __float_as_uint(fa), 0x07060302u);
+}
+
+template <int NB>
+__global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
+{
+    extern __shared__ uint4 cdx_lds[];                       // [2][CDX_KGC][patch_cells]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lcol = lane & 31, lhalf = lane >> 5;
+
+    // ---- which tile ------------------------------------------------------------------------------
+    int b = blockIdx.x;
+    const int cg = b % a.cgroups; b /= a.cgroups;
+    const int tile = b % a.tiles, n = b / a.tiles;
+    const int wave_c = wave % a.wc, wave_p = wave / a.wc;
+    const int cb = cg * a.wc + wave_c;                       // 32-channel block of this wave
+    const int tile_px = a.wpx * 32 * NB;
+    const int j0 = tile * tile_px;                           // first flat pixel of the workgroup
+    const int j_end = min(j0 + tile_px, a.PI);               // one past its last pixel
+    const int jw0 = j0 + wave_p * 32 * NB;                   // first pixel of this wave
+
+    // patch geometry: code rows p_lo..p_hi, columns q_lo..q_lo+pw-1
+    const int h_first = j0 / a.Wd, h_last = (j_end - 1) / a.Wd;
+    const int p_lo = h_first + a.pad - (a.R - 1), q_lo = a.pad - (a.S - 1);
+    const int p_a = max(p_lo, 0), p_b = min(h_last + a.pad, a.P - 1);   // rows that exist in the code image
+    const int buf_cells = CDX_KGC * a.patch_cells;
+
+    // ---- zero both buffers (halo and out-of-image cells stay zero for good) -----------------------
+    for (int i = tid; i < 2 * buf_cells; i += 256) cdx_lds[i] = uint4{0u, 0u, 0u, 0u};
+
+    // ---- patch-fill items of this thread: (k-group, aligned dword of the rows' flat byte range) ----
+    const int f_a = (p_a * a.Q) & ~3;
+    const int n_dw = p_b >= p_a ? ((p_b + 1) * a.Q - f_a + 3) >> 2 : 0;
+    const int n_items = n_dw * CDX_KGC;
+    int      item_goff[CDX_ITMAX];                           // byte offset inside the chunk's first code plane
+    int      item_k[CDX_ITMAX];                              // first channel of the item's k-group inside the chunk
+    uint32_t item_cell[CDX_ITMAX][2];                        // four 16-bit cell indices (0xFFFF = skip)
+#pragma unroll
+    for (int i = 0; i < CDX_ITMAX; ++i) {
+        const int it = tid + 256 * i;
+        item_goff[i] = -1; item_k[i] = 0;
+        item_cell[i][0] = item_cell[i][1] = 0xFFFFFFFFu;
+        if (it < n_items) {
+            const int kgl = it / n_dw, f = it - kgl * n_dw;
+            const int pix0 = f_a + 4 * f;
+            item_goff[i] = kgl * 8 * a.PQ + pix0; item_k[i] = kgl * 8;
+            uint32_t cells[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int pix = pix0 + e, p = pix / a.Q, q = pix - p * a.Q;
+                const bool need = p >= p_a && p <= p_b && q >= q_lo && q - q_lo < a.pw;
+                cells[e] = need ? (uint32_t)(kgl * a.patch_cells + (p - p_lo) * a.pw + (q - q_lo)) : 0xFFFFu;
+            }
+            item_cell[i][0] = cells[0] | (cells[1] << 16);
+            item_cell[i][1] = cells[2] | (cells[3] << 16);
+        }
+    }
+    uint32_t raw[CDX_ITMAX][8];
+    const int8_t *img = a.codes + (int64_t)n * a.K * a.PQ;
+    auto fetch_chunk = [&](int chunk) {
+#pragma unroll
+        for (int i = 0; i < CDX_ITMAX; ++i) {
+#pragma unroll
+            for (int kq = 0; kq < 8; ++kq) raw[i][kq] = 0u;
+            if (item_goff[i] >= 0) {
+                const int k0 = chunk * (8 * CDX_KGC) + item_k[i];
+                const int8_t *src = img + (int64_t)chunk * (8 * CDX_KGC) * a.PQ + item_goff[i];
+#pragma unroll
+                for (int kq = 0; kq < 8; ++kq)
+                    if (k0 + kq < a.K) raw[i][kq] = *(const uint32_t *)(src + (int64_t)kq * a.PQ);
+            }
+        }
+    };
+    auto store_chunk = [&](int buf) {
+        uint4 *dst = cdx_lds + buf * buf_cells;
+#pragma unroll
+        for (int i = 0; i < CDX_ITMAX; ++i) {
+            if (item_goff[i] < 0) continue;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t cell = (item_cell[i][e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                if (cell == 0xFFFFu) continue;
+                dst[cell] = uint4{cdx_bf16_pair(raw[i][0], raw[i][1], e), cdx_bf16_pair(raw[i][2], raw[i][3], e),
+                                  cdx_bf16_pair(raw[i][4], raw[i][5], e), cdx_bf16_pair(raw[i][6], raw[i][7], e)};
+            }
+        }
+    };
+
+    // ---- per-lane patch cell of each owned pixel (tap (0,0) position; a tap subtracts r*pw + s) ----
+    int lane_cell[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        int j = jw0 + 32 * nb + lcol;
+        j = min(j, a.PI - 1);                                 // tail lanes compute a valid pixel again; not stored
+        const int h = j / a.Wd, w = j - h * a.Wd;
+        lane_cell[nb] = (h - h_first + a.R - 1) * a.pw + (w + a.S - 1) + lhalf * a.patch_cells;
+    }
+
+    f32x16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+
+    const bool wave_active = cb * 32 < a.C && jw0 < j_end;   // uniform per wave
+    const int RS = a.R * a.S;
+    const uint4 *wlane = a.wp + (int64_t)lhalf * 3 * a.Cp + cb * 32 + lcol;
+    const int64_t kg_stride = (int64_t)3 * a.Cp;             // cells per k-group
+    auto load_a = [&](int chunk, int tap, int kk, u32x4 (&dst)[3]) {
+        const uint4 *p = wlane + ((int64_t)tap * a.KG + chunk * CDX_KGC + 2 * kk) * kg_stride;
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) { const uint4 t = p[(int64_t)pl * a.Cp]; dst[pl] = u32x4{t.x, t.y, t.z, t.w}; }
+    };
+
+    fetch_chunk(0);
+    u32x4 a0[3], a1[3];                                       // weight fragments of kk = 0 / kk = 1 (ping-pong)
+    if (wave_active) load_a(0, 0, 0, a0);
+    __syncthreads();                                          // zero fill done before the first patch writes
+
+    auto multiply = [&](const uint4 *pb, int off, const u32x4 (&af)[3]) {
+        u32x4 bfrag[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const uint4 t = pb[lane_cell[nb] + off];
+            bfrag[nb] = u32x4{t.x, t.y, t.z, t.w};
+        }
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) Mma<MODE_BF16>::run(af[pl], bfrag[nb], acc[nb]);
+    };
+
+    for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+        const int buf = chunk & 1;
+        store_chunk(buf);
+        __syncthreads();
+        if (chunk + 1 < a.n_chunks) fetch_chunk(chunk + 1);   // in flight during the matrix-core phase
+        if (wave_active) {
+            const uint4 *pb = cdx_lds + buf * buf_cells;
+            int r = 0, s = 0;
+            for (int tap = 0; tap < RS; ++tap) {
+                const int tapoff = r * a.pw + s;
+                // the next weight fragment is loaded while the current one is multiplied
+                load_a(chunk, tap, 1, a1);
+                multiply(pb, -tapoff, a0);
+                if (tap + 1 < RS) load_a(chunk, tap + 1, 0, a0);
+                else if (chunk + 1 < a.n_chunks) load_a(chunk + 1, 0, 0, a0);
+                multiply(pb, 2 * a.patch_cells - tapoff, a1);
+                if (++s == a.S) { s = 0; ++r; }
+            }
+        }
+    }
+
+    // ---- store: lane holds pixel column lcol, channel rows 8*(v/4) + 4*lhalf + v%4 of its block ----
+    if (wave_active) {
+        float *out = a.dX + (int64_t)n * a.C * a.PI;          // offsets inside one image fit 31 bits (host check)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int j = jw0 + 32 * nb + lcol;
+            if (j >= j_end) continue;
+            const int c0 = cb * 32 + 4 * lhalf;
+            int off = c0 * a.PI + j;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int c = c0 + 8 * (v >> 2) + (v & 3);
+                if (c < a.C) out[off] = acc[nb][v] * a.scale;
+                off += (v & 3) == 3 ? 5 * a.PI : a.PI;
+            }
+        }
+    }
+}
+
+}  // namespace dbp

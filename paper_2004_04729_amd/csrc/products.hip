@@ -2,6 +2,7 @@
 // dithered (bf16x3 / int8) and dense (fp32) variants, with deterministic split-K.
 #include "conv_loaders.h"
 #include "fc_kernel.h"
+#include "conv_dx_kernel.h"
 
 namespace dbp {
 
@@ -85,7 +86,67 @@ ConvGeom make_geom(const ConvArgs &a, int kch, int kstep)
 size_t relayout_bytes(int64_t K, int64_t C, int64_t R, int64_t S)
 {
     int64_t Kp = (K + 7) / 8 * 8;                       // multiple of every chunk length in use (4, 8)
-    return align_up((size_t)(R * S * Kp * C) * sizeof(float), 256);
+    const size_t generic = (size_t)(R * S * Kp * C) * sizeof(float);
+    // fast dX kernel: three bf16 planes, channels rounded to 32 on both sides
+    const size_t fast = (size_t)(R * S) * ((K + 31) / 32 * 32) * ((C + 31) / 32 * 32) * 6;
+    return align_up(generic > fast ? generic : fast, 256);
+}
+
+// Geometry of the fast dX kernel for one problem, or ok == false when the generic kernel has to serve.
+struct ConvDxPlan { bool ok; int nb; ConvDxArgs args; size_t lds_bytes; int grid; };
+
+ConvDxPlan conv_dx_plan(const ConvArgs &a)
+{
+    ConvDxPlan pl;
+    pl.ok = false;
+    ConvDxArgs &k = pl.args;
+    k.N = (int)a.N; k.C = (int)a.C; k.H = (int)a.H; k.Wd = (int)a.Wd; k.K = (int)a.K; k.R = (int)a.R; k.S = (int)a.S;
+    k.pad = (int)a.pad;
+    k.P = k.H + 2 * k.pad - k.R + 1; k.Q = k.Wd + 2 * k.pad - k.S + 1;
+    k.PI = k.H * k.Wd; k.PQ = k.P * k.Q;
+    if (k.PQ % 4 || ((uintptr_t)a.codes % 4)) return pl;         // the patch fill reads aligned dwords of a code plane
+    if ((int64_t)(k.C + 32) * k.PI >= ((int64_t)1 << 31)) return pl;   // 32-bit offsets inside one image
+    k.Cp = (k.C + 31) / 32 * 32;
+    k.KG = (k.K + 31) / 32 * 4;
+    k.n_chunks = k.KG / CDX_KGC;
+    const int ncb = k.Cp / 32;
+    k.wc = ncb >= 3 ? 4 : ncb;
+    k.wpx = 4 / k.wc;
+    k.cgroups = (ncb + k.wc - 1) / k.wc;
+    k.pw = k.Wd + k.S - 1;
+    double best = -1.0;
+    const int cand[2] = {7, 4};
+    for (int ci = 0; ci < 2; ++ci) {
+        const int nb = cand[ci], tile_px = k.wpx * 32 * nb;
+        const int tiles = (k.PI + tile_px - 1) / tile_px;
+        int prow = 0, n_dw = 0;
+        for (int t = 0; t < tiles; ++t) {
+            const int j0 = t * tile_px, j_end = j0 + tile_px < k.PI ? j0 + tile_px : k.PI;
+            const int h_first = j0 / k.Wd, h_last = (j_end - 1) / k.Wd;
+            const int p_lo = h_first + k.pad - (k.R - 1);
+            const int p_a = p_lo > 0 ? p_lo : 0, p_b = h_last + k.pad < k.P - 1 ? h_last + k.pad : k.P - 1;
+            if (h_last - h_first + k.R > prow) prow = h_last - h_first + k.R;
+            if (p_b >= p_a) {
+                const int f_a = (p_a * k.Q) & ~3, d = ((p_b + 1) * k.Q - f_a + 3) >> 2;
+                if (d > n_dw) n_dw = d;
+            }
+        }
+        const int64_t cells = (int64_t)prow * k.pw;
+        const size_t lds = (size_t)2 * CDX_KGC * cells * 16;
+        if (lds > (size_t)CDX_MAX_LDS || (int64_t)n_dw * CDX_KGC > 256 * CDX_ITMAX) continue;
+        // time ~ rounds of workgroups over the chip (two resident per CU) x work per workgroup
+        const int64_t grid = (int64_t)k.N * tiles * k.cgroups;
+        const double cost = (double)nb * (double)((grid + 511) / 512);
+        if (best < 0.0 || cost < best) {
+            best = cost; pl.ok = true; pl.nb = nb; pl.lds_bytes = lds;
+            k.tiles = tiles; k.prow = prow; k.patch_cells = (int)cells;
+        }
+    }
+    if (!pl.ok) return pl;
+    const int64_t grid = (int64_t)k.N * k.tiles * k.cgroups;
+    if (grid > 0x7FFFFFFF) { pl.ok = false; return pl; }
+    pl.grid = (int)grid;
+    return pl;
 }
 
 // ---- fast fully connected path (fc_kernel.h) -------------------------------------------------------
@@ -252,6 +313,20 @@ template <int MODE_G>
 static hipError_t conv_dx(const ConvArgs &a, const void *grad, float scale, hipStream_t s)
 {
     // MODE_G: MODE_BF16 (codes) or MODE_F32 (dense).  Weights are fp32 in every mode.
+    if constexpr (MODE_G == MODE_BF16) {
+        ConvDxPlan pl = conv_dx_plan(a);
+        if (pl.ok) {
+            ConvDxArgs &k = pl.args;
+            k.codes = (const int8_t *)grad; k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale;
+            const int64_t cells = (int64_t)k.R * k.S * k.KG * k.Cp;
+            const int pb = (int)((cells + 255) / 256 < 4096 ? (cells + 255) / 256 : 4096);
+            hipLaunchKernelGGL(conv_dx_weight_prep_kernel, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch,
+                               k.K, k.C, k.R * k.S, k.KG, k.Cp);
+            if (pl.nb == 7) hipLaunchKernelGGL(conv_dx_kernel<7>, dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
+            else            hipLaunchKernelGGL(conv_dx_kernel<4>, dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
+            return hipGetLastError();
+        }
+    }
     ConvGeom g = make_geom(a, ModeTraits<MODE_G>::KCH, k_step<MODE_G>());
     float *Wt = (float *)a.scratch;
     const size_t rb = relayout_bytes(a.K, a.C, a.R, a.S);

@@ -63,6 +63,9 @@ CASES = [  # N, C, H, Wd, K, R, S, pad
     (2, 8, 10, 10, 9, 3, 3, 0),
     (5, 40, 12, 20, 70, 3, 3, 1),
     (1, 130, 6, 6, 260, 3, 3, 1),
+    (2, 7, 12, 9, 5, 5, 3, 2),          # R != S, wide padding
+    (1, 4, 6, 6, 3, 3, 3, 3),           # padding beyond the kernel extent
+    (2, 64, 30, 30, 40, 3, 3, 1),       # several pixel tiles per image, tile borders inside a row
 ]
 
 
