@@ -3,6 +3,7 @@
 #include "conv_loaders.h"
 #include "fc_kernel.h"
 #include "conv_dx_kernel.h"
+#include "conv_dw_kernel.h"
 
 namespace dbp {
 
@@ -149,6 +150,94 @@ ConvDxPlan conv_dx_plan(const ConvArgs &a)
     return pl;
 }
 
+
+// Geometry of the fast dW kernel (conv_dw_kernel.h), or ok == false when the generic kernel has to serve.
+struct ConvDwPlan { bool ok; int mb; ConvDwArgs args; size_t lds_bytes, partial_bytes; int grid, reduce_grid; };
+
+ConvDwPlan conv_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, bool i8)
+{
+    ConvDwPlan pl;
+    pl.ok = false; pl.partial_bytes = 0; pl.lds_bytes = 0;
+    ConvDwArgs &k = pl.args;
+    const bool one = R == 1 && S == 1;
+    // one accumulator per tap: compiled tap counts only.  (The 1x1 instantiation exists and is correct, but a
+    // single tap leaves the stagers far behind the matrix cores: the generic kernel is faster there.)
+    if (!(R == 3 && S == 3)) return pl;
+    if (pad > 1 || (one && pad != 0)) return pl;                     // compiled paddings: 0 and 1 (3x3), 0 (1x1)
+    const int64_t P = H + 2 * pad - R + 1, Q = Wd + 2 * pad - S + 1;
+    if ((H * Wd) % 4 || (P * Q) % 4) return pl;                     // rows are fetched as aligned 4-element pieces
+    if (C * H * Wd >= ((int64_t)1 << 29) || K * P * Q >= ((int64_t)1 << 29) || K * C * R * S >= ((int64_t)1 << 31)) return pl;
+    k.N = (int)N; k.C = (int)C; k.H = (int)H; k.Wd = (int)Wd; k.K = (int)K; k.P = (int)P; k.Q = (int)Q; k.pad = (int)pad;
+    const int FRAG = i8 ? 16 : 8, KSTEP = 2 * FRAG, ESZ = i8 ? 1 : 2, PL = i8 ? 1 : 3, CQL = 128, XQL = 64;
+    int64_t pw = Wd + pad;
+    const int64_t over = S - 1 - pad > 0 ? S - 1 - pad : 0;
+    if (Q + over > pw) pw = Q + over;
+    pw = (pw + FRAG - 1) / FRAG * FRAG;
+    if (pw > 256) return pl;
+    k.PW = (int)pw;
+    const int t_max = CDW_M8 + (int)((R - 1) * pw + pad);
+    double best = -1.0;
+    for (int mb = 1; mb >= 1 && !pl.ok; --mb) {
+        const int TK = 64 * mb, TC = 64;
+        for (int ru = 1; ru <= H && ru * Wd <= 4 * XQL - 9 && ru * pw <= 320; ++ru) {
+            const int tpc = (int)(ru * pw);
+            if (tpc % KSTEP) continue;
+            const int len = (tpc + t_max + FRAG + 3) / 4 * 4;
+            const int nr = (int)((len - CDW_M8 - 1) / pw) + 2;
+            const int nqc = (int)((nr * Q + 9) / 4), nqx = (int)((ru * Wd + 9) / 4);
+            if (nqc > CQL || nqx > XQL) continue;
+            int xc = tpc / FRAG; if (xc % 2 == 0) ++xc;              // odd cell counts spread a fragment read over the banks
+            int cc = (len + FRAG - 1) / FRAG; if (cc % 2 == 0) ++cc;
+            const size_t lds = 2 * ((size_t)PL * TC * xc * FRAG * ESZ + (size_t)TK * cc * FRAG * ESZ);   // double buffered
+            if (lds > (size_t)CDW_MAX_LDS) continue;
+            const int chunks = (int)((H + ru - 1) / ru);
+            const double cost = (double)chunks * (tpc + 64.0);      // matrix-core steps plus a fixed cost per unit
+            if (best < 0.0 || cost < best) {
+                best = cost; pl.ok = true; pl.mb = mb; pl.lds_bytes = lds;
+                k.RU = ru; k.TPc = tpc; k.chunks = chunks; k.lenC = len; k.pitchX = xc * FRAG; k.pitchC = cc * FRAG;
+                k.NR = nr; k.nqx = nqx; k.nqc = nqc; k.lds_cells = (int)(lds / 16);
+            }
+        }
+    }
+    if (!pl.ok) return pl;
+    k.row4x = Wd % 4 == 0; k.row4c = Q % 4 == 0;
+    k.row2x = Wd % 2 == 0; k.row2c = Q % 2 == 0;
+    k.xshift = k.nqx <= 16 ? 4 : k.nqx <= 32 ? 5 : 6;
+    k.cshift = k.nqc <= 32 ? 5 : k.nqc <= 64 ? 6 : 7;
+    const int TK = 64 * pl.mb;
+    k.tiles_k = (int)((K + TK - 1) / TK); k.tiles_c = (int)((C + 63) / 64);
+    const int64_t tiles = (int64_t)k.tiles_k * k.tiles_c;
+    const int64_t units = N * k.chunks;
+    if (units >= ((int64_t)1 << 31) || tiles > 65535) { pl.ok = false; return pl; }
+    k.units = (int)units;
+    int64_t want = tiles >= 256 ? 1 : 256 / tiles;                   // one workgroup per CU
+    if (want > units) want = units;
+    k.units_per_split = (int)((units + want - 1) / want);
+    k.n_split = (int)((units + k.units_per_split - 1) / k.units_per_split);
+    const int64_t ne = R * S * pl.mb * 16;
+    pl.partial_bytes = k.n_split > 1 ? (size_t)tiles * k.n_split * ne * 256 * 4 : 0;
+    pl.grid = (int)(tiles * k.n_split);
+    pl.reduce_grid = (int)(tiles * (ne / 4) * 16);                  // (tile, group of 4 elements, 16 of the 256 slots)
+    return pl;
+}
+
+template <int MODE, int R, int S, int PAD, int MB>
+hipError_t launch_conv_dw_fast(const ConvDwPlan &pl, hipStream_t s)
+{
+    // more than 64 KiB of dynamic LDS has to be allowed per kernel, once
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dw_kernel<MODE, R, S, PAD, MB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, CDW_MAX_LDS);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((conv_dw_kernel<MODE, R, S, PAD, MB>), dim3(pl.grid), dim3(512), pl.lds_bytes, s, pl.args);
+    if (pl.args.n_split > 1)
+        hipLaunchKernelGGL((conv_dw_reduce_kernel<MODE, R, S, MB>), dim3(pl.reduce_grid), dim3(256), 0, s, pl.args);
+    return hipGetLastError();
+}
+
 // ---- fast fully connected path (fc_kernel.h) -------------------------------------------------------
 struct FcPlan { int tiles_m, tiles_n, n_split, k_per_split; int64_t tiles; size_t partial_bytes; };
 
@@ -223,7 +312,12 @@ size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K
     size_t dx = part(N * H * Wd, C, R * S * ((K + 7) / 8 * 8), 16);
     const int64_t PQp16 = (P * Q + 15) / 16 * 16;
     size_t dw = part(K, C * R * S, N * PQp16, 16);
-    return relayout_bytes(K, C, R, S) + align_up(dx > dw ? dx : dw, 256) + 256;
+    size_t big = dx > dw ? dx : dw;
+    for (int i8 = 0; i8 < 2; ++i8) {                                 // fast dW kernel, either X type
+        const ConvDwPlan pl = conv_dw_plan(N, C, H, Wd, K, R, S, pad, i8 != 0);
+        if (pl.ok && pl.partial_bytes > big) big = pl.partial_bytes;
+    }
+    return relayout_bytes(K, C, R, S) + align_up(big, 256) + 256;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -347,8 +441,18 @@ template <int MODE>
 static hipError_t conv_dw(const ConvArgs &a, const void *grad, float scale, hipStream_t s)
 {
     using Acc = typename ModeTraits<MODE>::Acc;
-    ConvGeom g = make_geom(a, ModeTraits<MODE>::KCH, k_step<MODE>());
     const size_t rb = relayout_bytes(a.K, a.C, a.R, a.S);
+    if constexpr (MODE != MODE_F32) {
+        ConvDwPlan pl = conv_dw_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad, MODE == MODE_I8);
+        const size_t xal = MODE == MODE_I8 ? 4 : 16;                 // aligned 4-element loads of both operands
+        if (pl.ok && rb + pl.partial_bytes <= a.scratch_bytes && (uintptr_t)a.X % xal == 0 && (uintptr_t)grad % 4 == 0) {
+            ConvDwArgs &k = pl.args;
+            k.codes = (const int8_t *)grad; k.X = a.X; k.dW = a.dW; k.partial = (char *)a.scratch + rb; k.scale = scale;
+            if (a.R == 3) return a.pad == 1 ? launch_conv_dw_fast<MODE, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE, 3, 3, 0, 1>(pl, s);
+            return launch_conv_dw_fast<MODE, 1, 1, 0, 1>(pl, s);
+        }
+    }
+    ConvGeom g = make_geom(a, ModeTraits<MODE>::KCH, k_step<MODE>());
     const int CRS = g.C * g.R * g.S, Kred = g.N * g.PQp;
     ConvDwGradLoader<MODE> al{(const typename GradElem<MODE>::T *)grad, g};
     ConvDwActLoader<MODE>  bl{(const decltype(ConvDwActLoader<MODE>::base))a.X, g};
