@@ -2,6 +2,7 @@
 // dithered (bf16x3 / int8) and dense (fp32) variants, with deterministic split-K.
 #include "conv_loaders.h"
 #include "fc_kernel.h"
+#include "fc2_kernel.h"
 #include "conv_dx_kernel.h"
 #include "conv_dw_kernel.h"
 
@@ -244,11 +245,11 @@ struct FcPlan { int tiles_m, tiles_n, n_split, k_per_split; int64_t tiles; size_
 // Split the reduction of a product with few tiles into about two items per CU, never below 8 K steps per
 // item (the length of a dW item at batch 256, so the persistent workgroups stay balanced).  Every split
 // costs a partial write + read.
-FcPlan fc_plan(int64_t M, int64_t N, int64_t K)
+FcPlan fc_plan(int64_t M, int64_t N, int64_t K, int tm = FC_TM, int tn = FC_TN)
 {
     FcPlan pl;
-    pl.tiles_m = (int)((M + FC_TM - 1) / FC_TM);
-    pl.tiles_n = (int)((N + FC_TN - 1) / FC_TN);
+    pl.tiles_m = (int)((M + tm - 1) / tm);
+    pl.tiles_n = (int)((N + tn - 1) / tn);
     pl.tiles = (int64_t)pl.tiles_m * pl.tiles_n;
     const int64_t steps = (K + FC_KT - 1) / FC_KT;
     int64_t want = (512 + pl.tiles - 1) / pl.tiles;
@@ -258,8 +259,33 @@ FcPlan fc_plan(int64_t M, int64_t N, int64_t K)
     const int64_t per = (steps + want - 1) / want;
     pl.k_per_split = (int)(per * FC_KT);
     pl.n_split = (int)((steps + per - 1) / per);
-    pl.partial_bytes = pl.n_split > 1 ? (size_t)pl.tiles * pl.n_split * FC_TM * FC_TN * sizeof(float) : 0;
+    pl.partial_bytes = pl.n_split > 1 ? (size_t)pl.tiles * pl.n_split * tm * tn * sizeof(float) : 0;
     return pl;
+}
+
+// Plans of the two products for the kernel with staging and multiplying wavefronts: reductions are split
+// into items of about half a workgroup's share of all K steps (one workgroup per CU), at least 8 steps.
+void fc2_plans(int64_t B, int64_t in, int64_t out, bool want_dx, bool want_dw, FcPlan &dx, FcPlan &dw)
+{
+    auto base = [](int64_t M, int64_t N, int64_t K, FcPlan &pl) {
+        pl.tiles_m = (int)((M + FC2_TM - 1) / FC2_TM);
+        pl.tiles_n = (int)((N + FC2_TN - 1) / FC2_TN);
+        pl.tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+        return (K + FC2_KT - 1) / FC2_KT;
+    };
+    const int64_t sx = base(B, in, out, dx), sw = base(out, in, B, dw);
+    const int64_t all = (want_dx ? dx.tiles * sx : 0) + (want_dw ? dw.tiles * sw : 0);
+    int64_t len = all / 512;
+    if (len < 8) len = 8;
+    auto split = [len](int64_t steps, FcPlan &pl) {
+        int64_t n = (steps + len / 2) / len;
+        if (n < 1) n = 1;
+        const int64_t per = (steps + n - 1) / n;
+        pl.k_per_split = (int)(per * FC2_KT);
+        pl.n_split = (int)((steps + per - 1) / per);
+        pl.partial_bytes = pl.n_split > 1 ? (size_t)pl.tiles * pl.n_split * FC2_TM * FC2_TN * sizeof(float) : 0;
+    };
+    split(sx, dx); split(sw, dw);
 }
 
 bool fc_fast_ok(bool a_kfast, const int8_t *A, int64_t lda, const float *B, int64_t ldb, int64_t M, int64_t N, const float *out)
@@ -297,7 +323,13 @@ size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
     const size_t generic = align_up(a > b ? a : b, 256);
     // fast path: both products in one launch, each with its own partials
     const FcPlan dx = fc_plan(B, in, out), dw = fc_plan(out, in, B);
-    const size_t fast = align_up(dx.partial_bytes, 256) + align_up(dw.partial_bytes, 256);
+    size_t fast = align_up(dx.partial_bytes, 256) + align_up(dw.partial_bytes, 256);
+    for (int m = 1; m < 4; ++m) {                               // every combination of products a call can ask for
+        FcPlan dx2, dw2;
+        fc2_plans(B, in, out, (m & 1) != 0, (m & 2) != 0, dx2, dw2);
+        const size_t fast2 = ((m & 1) ? align_up(dx2.partial_bytes, 256) : 0) + ((m & 2) ? align_up(dw2.partial_bytes, 256) : 0);
+        if (fast2 > fast) fast = fast2;
+    }
     return (generic > fast ? generic : fast) + 256;
 }
 
@@ -334,7 +366,43 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
         const bool dx_fast = a.dX && fc_fast_ok(true, a.codes, a.out, a.W, a.in, B, in, a.dX);
         const bool dw_fast = a.dW && a.x_dtype == DBP_F32 &&
                              fc_fast_ok(false, a.codes, a.out, (const float *)a.X, a.in, out, in, (const float *)a.dW);
-        if (dx_fast || dw_fast) {
+        // Large products: the kernel with separate staging and multiplying wavefronts (256x128 tiles, one
+        // workgroup per CU); small ones (less than half such a tile of rows): the 128x128 kernel.
+        const bool big = (!dx_fast || B > FC2_TM / 2) && (!dw_fast || out > FC2_TM / 2);
+        if ((dx_fast || dw_fast) && big) {
+            static bool raised = false;
+            if (!raised) {
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, FC2_LDS_BYTES);
+                if (e != hipSuccess) return e;
+                raised = true;
+            }
+            char *scratch = (char *)a.scratch;
+            FcPairArgs pa;
+            FcPlan pdx, pdw;
+            fc2_plans(B, in, out, dx_fast, dw_fast, pdx, pdw);
+            if (!dx_fast) { pdx.n_split = 1; pdx.partial_bytes = 0; }
+            if (!dw_fast) { pdw.n_split = 1; pdw.partial_bytes = 0; }
+            pa.prob[0] = fc_problem(true, a.codes, a.out, a.W, a.in, B, in, out, a.step, a.dX, pdx, scratch);
+            pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, a.step, (float *)a.dW, pdw, scratch);
+            if (!dx_fast) pa.prob[0].n_items = 0;
+            if (!dw_fast) pa.prob[1].n_items = 0;
+            if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
+            pa.stats = pending;                            // summed by a stager wavefront of the last workgroup
+            pending.n = 0;
+            const int total = pa.prob[0].n_items + pa.prob[1].n_items;
+            const int grid = total < 256 ? total : 256;    // persistent: one workgroup per CU
+            hipLaunchKernelGGL(fc2_pair_kernel, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            const bool r0 = dx_fast && pdx.n_split > 1, r1 = dw_fast && pdw.n_split > 1;
+            if (r0 || r1) {
+                const int tiles0 = r0 ? (int)pdx.tiles : 0, tiles1 = r1 ? (int)pdw.tiles : 0;
+                hipLaunchKernelGGL(fc2_reduce_kernel, dim3(8 * (tiles0 + tiles1)), dim3(256), 0, s, pa, tiles0);
+                e = hipGetLastError();
+                if (e != hipSuccess) return e;
+            }
+        } else if (dx_fast || dw_fast) {
             char *scratch = (char *)a.scratch;
             FcPairArgs pa;
             const FcPlan none = {0, 0, 1, FC_KT, 0, 0};
