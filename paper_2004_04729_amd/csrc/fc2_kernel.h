@@ -295,38 +295,28 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
     }
 }
 
-// Second launch of a split-K run: workgroup (tile, eighth) sums the partials of 4 of the tile's 32
-// accumulator slots (four columns each) over the splits, in split order, and writes the output with the
-// item's own mapping.
+// Second launch of a split-K run: workgroup (tile, slot) sums one of the tile's 32 accumulator slots (four
+// columns per thread) over the splits, in split order, and writes the output with the item's own mapping.
 __global__ __launch_bounds__(256) void fc2_reduce_kernel(FcPairArgs a, int tiles0)
 {
-    const int which = (int)(blockIdx.x >> 3) < tiles0 ? 0 : 1;
+    const int which = (int)(blockIdx.x >> 5) < tiles0 ? 0 : 1;
     const FcProblem &p = a.prob[which];
-    const int tile = (int)(blockIdx.x >> 3) - (which ? tiles0 : 0), eighth = blockIdx.x & 7;
+    const int tile = (int)(blockIdx.x >> 5) - (which ? tiles0 : 0), slot = blockIdx.x & 31;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tile_m = (tile % p.tiles_m) * FC2_TM;
     const int tile_n = (tile / p.tiles_m) * FC2_TN;
-    const float4 *all = (const float4 *)(p.partial + (int64_t)tile * p.n_split * (FC2_TM * FC2_TN));
+    const float4 *all = (const float4 *)(p.partial + (int64_t)tile * p.n_split * (FC2_TM * FC2_TN)) + slot * 256 + tid;
     const int col = tile_n + 4 * (lane & 31);
-    float4 sum[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) sum[u] = float4{0.f, 0.f, 0.f, 0.f};
+    float4 sum = float4{0.f, 0.f, 0.f, 0.f};
     for (int q = 0; q < p.n_split; ++q) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float4 t = all[(int64_t)q * (FC2_TM * FC2_TN / 4) + (eighth * 4 + u) * 256 + tid];
-            sum[u].x += t.x; sum[u].y += t.y; sum[u].z += t.z; sum[u].w += t.w;
-        }
+        const float4 t = all[(int64_t)q * (FC2_TM * FC2_TN / 4)];
+        sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
     }
-    if (col >= p.N) return;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int slot = eighth * 4 + u, i = slot >> 4, v = slot & 15;
-        const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int row = fc2_row(p.a_kfast, tile_m, wave, i, ii);
-        if (row < p.M)
-            *(float4 *)(p.out + (int64_t)row * p.ldc + col) = float4{p.scale * sum[u].x, p.scale * sum[u].y, p.scale * sum[u].z, p.scale * sum[u].w};
-    }
+    const int i = slot >> 4, v = slot & 15;
+    const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    const int row = fc2_row(p.a_kfast, tile_m, wave, i, ii);
+    if (col < p.N && row < p.M)
+        *(float4 *)(p.out + (int64_t)row * p.ldc + col) = float4{p.scale * sum.x, p.scale * sum.y, p.scale * sum.z, p.scale * sum.w};
 }
 
 }  // namespace dbp

@@ -398,7 +398,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             const bool r0 = dx_fast && pdx.n_split > 1, r1 = dw_fast && pdw.n_split > 1;
             if (r0 || r1) {
                 const int tiles0 = r0 ? (int)pdx.tiles : 0, tiles1 = r1 ? (int)pdw.tiles : 0;
-                hipLaunchKernelGGL(fc2_reduce_kernel, dim3(8 * (tiles0 + tiles1)), dim3(256), 0, s, pa, tiles0);
+                hipLaunchKernelGGL(fc2_reduce_kernel, dim3(32 * (tiles0 + tiles1)), dim3(256), 0, s, pa, tiles0);
                 e = hipGetLastError();
                 if (e != hipSuccess) return e;
             }
