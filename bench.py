@@ -99,8 +99,8 @@ def main():
             dbp.linear_products(b["codes"], fmt, p2.step, b["W"], b["X"], dbp.F32, B, in_, out, b["dX"], b["dW"], b["ws"],
                                 dbp.PATH_MFMA, stream)
         torch.cuda.synchronize()
-        print(json.dumps({"probe": "torch.mul on 2^28 floats (1 GiB read, 1 GiB written) + 6 launches of fc_pair_kernel "
-                                   "and fc_reduce_kernel on the 256x4096x4096 layer"}))
+        print(json.dumps({"probe": "torch.mul on 2^28 floats (1 GiB read, 1 GiB written) + 6 launches of fc2_pair_kernel "
+                                   "and fc2_reduce_kernel on the 256x4096x4096 layer"}))
         return
 
     def step(i, path=dbp.PATH_AUTO):
@@ -162,18 +162,18 @@ def main():
     t_dx_g = timed(lambda i: k_dx(i, dbp.PATH_GATHER), max(5, iters // 4))
     t_dw_g = timed(lambda i: k_dw(i, dbp.PATH_GATHER), max(5, iters // 4))
     mnk = 2.0 * B * in_ * out
-    # Dominant kernel: fc_pair_kernel, both products of the 4096x4096 layer in one launch (its split-K
+    # Dominant kernel: fc2_pair_kernel, both products of the 4096x4096 layer in one launch (its split-K
     # reduction launch is included in the time).  Algorithmic work per launch:
     # flops = 2 products x 3 exact bf16 planes x 2*B*in*out; HBM bytes = W + X + codes read, dX + dW written.
     alg_flops = 2 * 3 * mnk
     alg_bytes = 4.0 * (out * in_ + B * in_) + B * out + 4.0 * (B * in_ + out * in_)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "fc_pair_kernel_cfg2_L2_pmc.txt")
+    tpath = os.path.join(ROOT, "profiles", "fc2_pair_kernel_cfg2_L2_pmc.txt")
     if os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
-    roofline = {"bound": "mfma", "kernel": "fc_pair_kernel (dX and dW of the 256x4096x4096 layer, one launch) + fc_reduce_kernel",
+    roofline = {"bound": "mfma", "kernel": "fc2_pair_kernel (dX and dW of the 256x4096x4096 layer, one launch) + fc2_reduce_kernel",
                 "achieved": alg_flops / t_both / 1e12, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": alg_flops / t_both / 1e12 / PEAK_BF16_TFLOPS, "traffic": traffic,
                 "flops_counted": "2 products x 3 bf16 planes x 2*M*N*K per launch", "us_per_launch": t_both * 1e6,
@@ -286,9 +286,24 @@ def bench_conv_configs(dbp, workloads, torch, np, timed, stream):
         P, Q = p.delta.shape[2:]
         flops = 2 * 2.0 * N * K * P * Q * Cc * R * S
         row = {"ms": t * 1e3, "dense_equiv_tflops": flops / t / 1e12, "sparsity": 1 - dbp.Stats.from_tensor(st).nnz / p.delta.size}
+        t_x = timed(lambda i: dbp.conv2d_products(codes, None, p.step, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, dX, None, ws,
+                                                  dbp.PATH_MFMA, stream), 5, warm=1)
+        t_w = timed(lambda i: dbp.conv2d_products(codes, None, p.step, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, None, dW, ws,
+                                                  dbp.PATH_MFMA, stream), 5, warm=1)
+        row["dX_us"], row["dW_us"], row["nsd_us"] = t_x * 1e6, t_w * 1e6, max(t - t_x - t_w, 0.0) * 1e6
         if not i8:
             t_d = timed(lambda i: dbp.dense_conv2d_backward(d, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, dX, dW, ws, stream), 3, warm=1)
             row["same_library_dense_ms"] = t_d * 1e3
+            # context only: the vendor library's fp32 convolution backward on the same shapes (dense gradient)
+            dt = torch.from_numpy(p.delta).to(dev)
+            torch.backends.cudnn.allow_tf32 = False
+            f = lambda i: torch.ops.aten.convolution_backward(dt, X, W, None, [1, 1], [p.pad, p.pad], [1, 1], False, [0, 0], 1,
+                                                              [True, True, False])
+            try:
+                row["torch_conv_backward_fp32_ms"] = timed(f, 3, warm=2) * 1e3
+            except Exception as e:                                   # context line: never fail the run over it
+                row["torch_conv_backward_fp32_ms"] = None
+            del dt
         res[name] = row
         del d, W, X, codes, dX, dW, ws
     return res
