@@ -212,8 +212,6 @@ __device__ __forceinline__ void fc_item(const FcProblem &p, int item, FcSmem &sm
     }
 }
 
-// Persistent workgroups; items of the two problems alternate (even = problem 0, odd = problem 1) for as
-// long as both have items left, so that neighbouring workgroups work on different products.
 // Sum of the quantiser's per-workgroup statistics records by one workgroup of 256 threads (integer
 // sums and a maximum: the result does not depend on the order).
 __device__ __forceinline__ void fc_sum_stats(const StatsJob &j, uint64_t *lds)
@@ -244,6 +242,8 @@ __device__ __forceinline__ void fc_sum_stats(const StatsJob &j, uint64_t *lds)
     __syncthreads();                                        // the items reuse this LDS
 }
 
+// Persistent workgroups; items of the two problems alternate (even = problem 0, odd = problem 1) for as
+// long as both have items left, so that neighbouring workgroups work on different products.
 __global__ __launch_bounds__(256, 3) void fc_pair_kernel(FcPairArgs a)
 {
     __shared__ FcSmem sm;

@@ -160,11 +160,10 @@ ConvDwPlan conv_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, 
     ConvDwPlan pl;
     pl.ok = false; pl.partial_bytes = 0; pl.lds_bytes = 0;
     ConvDwArgs &k = pl.args;
-    const bool one = R == 1 && S == 1;
-    // one accumulator per tap: compiled tap counts only.  (The 1x1 instantiation exists and is correct, but a
-    // single tap leaves the stagers far behind the matrix cores: the generic kernel is faster there.)
+    // one accumulator per tap: compiled tap counts only.  (A 1x1 instantiation was measured: a single tap
+    // leaves the stagers far behind the matrix cores, and the generic kernel is faster there.)
     if (!(R == 3 && S == 3)) return pl;
-    if (pad > 1 || (one && pad != 0)) return pl;                     // compiled paddings: 0 and 1 (3x3), 0 (1x1)
+    if (pad > 1) return pl;                                          // compiled paddings: 0 and 1
     const int64_t P = H + 2 * pad - R + 1, Q = Wd + 2 * pad - S + 1;
     if ((H * Wd) % 4 || (P * Q) % 4) return pl;                     // rows are fetched as aligned 4-element pieces
     if (C * H * Wd >= ((int64_t)1 << 29) || K * P * Q >= ((int64_t)1 << 29) || K * C * R * S >= ((int64_t)1 << 31)) return pl;
@@ -516,8 +515,7 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, float scale, hipS
         if (pl.ok && rb + pl.partial_bytes <= a.scratch_bytes && (uintptr_t)a.X % xal == 0 && (uintptr_t)grad % 4 == 0) {
             ConvDwArgs &k = pl.args;
             k.codes = (const int8_t *)grad; k.X = a.X; k.dW = a.dW; k.partial = (char *)a.scratch + rb; k.scale = scale;
-            if (a.R == 3) return a.pad == 1 ? launch_conv_dw_fast<MODE, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE, 3, 3, 0, 1>(pl, s);
-            return launch_conv_dw_fast<MODE, 1, 1, 0, 1>(pl, s);
+            return a.pad == 1 ? launch_conv_dw_fast<MODE, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE, 3, 3, 0, 1>(pl, s);
         }
     }
     ConvGeom g = make_geom(a, ModeTraits<MODE>::KCH, k_step<MODE>());

@@ -66,6 +66,8 @@ CASES = [  # N, C, H, Wd, K, R, S, pad
     (2, 7, 12, 9, 5, 5, 3, 2),          # R != S, wide padding
     (1, 4, 6, 6, 3, 3, 3, 3),           # padding beyond the kernel extent
     (2, 64, 30, 30, 40, 3, 3, 1),       # several pixel tiles per image, tile borders inside a row
+    (2, 6, 12, 9, 10, 3, 3, 1),         # odd row length: element-wise scatter into the staging buffers
+    (17, 70, 8, 8, 130, 3, 3, 1),       # more images than one reduction split takes, partial channel tiles
 ]
 
 
@@ -76,7 +78,7 @@ def test_conv_products_match_oracle(case):
     _check(p, run_conv(p))
 
 
-@pytest.mark.parametrize("case", CASES[1:6])
+@pytest.mark.parametrize("case", CASES[1:])
 def test_conv_int8_mode_is_bit_exact(case):
     from gpu_util import run_conv
     p = _problem(*case, c=1.0, i8=True)
