@@ -17,6 +17,8 @@
  *     convolutional layers", Sec. "Dithered backpropagation").
  *   - 8-bit mode: integer codes times int8 activations, exact int32 weight gradient
  *     (Sec. "Quantizing forward pass": everything but the weight update in 8 bit).
+ *   - around the quantiser: the layer's step size Delta = s*std(delta_z) (Algorithm 1),
+ *     delta_z = delta_a (.) f'(z) in front of it and the bias gradient behind it.
  *
  * The paper fixes no random generator, no code width, no storage layout and no sparse
  * format.  Those readings are stated where they are used below; they are spec decisions
@@ -139,6 +141,87 @@ void dbp_oracle_nsd(const float *delta, int64_t n, float step, uint64_t seed,
         codes[j] = (int8_t)k;
     }
     if (st) *st = s;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Step size of a layer (Algorithm 1, first two lines):  sigma = std(delta_z),
+ * Delta = s * sigma.
+ *
+ * Readings (the paper says only "std"): the population standard deviation (divide by n)
+ * of all elements of the tensor,
+ *      sigma = sqrt( (S2 - S1*S1/n) / n ),    S1 = sum x,   S2 = sum x*x,
+ * evaluated in fp64 (x*x of an fp32 value is exact in fp64), a negative radicand (rounding)
+ * counting as 0; Delta = s * sigma rounded once to fp32.  Non-finite inputs make sigma
+ * non-finite: the caller's problem, as for any std.
+ * Because Delta decides integer codes, the ORDER of the two sums is part of the
+ * definition, so that every implementation obtains the same bits:
+ *      a radix-16 summation tree -- the values are summed in groups of 16 consecutive
+ *      elements, left to right inside a group; the group sums (in order) are summed the
+ *      same way; and so on until one value is left.  A short last group is summed as is.
+ * ---------------------------------------------------------------------------------- */
+static double tree16_sum(double *v, int64_t n)
+{
+    if (n == 0) return 0.0;
+    while (n > 1) {
+        int64_t m = (n + 15) / 16;
+        for (int64_t b = 0; b < m; ++b) {
+            int64_t end = (b + 1) * 16 < n ? (b + 1) * 16 : n;
+            double acc = v[b * 16];
+            for (int64_t i = b * 16 + 1; i < end; ++i) acc += v[i];
+            v[b] = acc;                    /* b <= b*16: never overwrites an unread value */
+        }
+        n = m;
+    }
+    return v[0];
+}
+
+float dbp_oracle_step_size(const float *delta, int64_t n, float s, double *sigma_out)
+{
+    double *v = (double *)malloc((size_t)(n > 0 ? n : 1) * sizeof(double));
+    for (int64_t j = 0; j < n; ++j) v[j] = (double)delta[j];
+    const double s1 = tree16_sum(v, n);
+    for (int64_t j = 0; j < n; ++j) v[j] = (double)delta[j] * (double)delta[j];
+    const double s2 = tree16_sum(v, n);
+    free(v);
+    double var = n > 0 ? (s2 - s1 * s1 / (double)n) / (double)n : 0.0;
+    if (var < 0.0) var = 0.0;
+    const double sigma = sqrt(var);
+    if (sigma_out) *sigma_out = sigma;
+    return (float)((double)s * sigma);
+}
+
+/* ------------------------------------------------------------------------------------
+ * The step before the quantiser and its by-product (backward pass as printed before
+ * Eq. (da); bias of Eq. (z)).
+ *
+ *   delta_z = delta_a (.) f'(z).  For the rectifier f(z) = max(0, z) the derivative is 1
+ *   for z > 0 and 0 otherwise (the value at 0 is taken as 0, the usual convention; the
+ *   paper does not say).  `act` may be z or a = f(z): only "act > 0" is used, so -0.0
+ *   and NaN mask the element.  The result is delta_a or +0.0f, exactly.
+ *
+ *   The bias enters Eq. (z) additively, so its gradient is the sum of the (quantised)
+ *   preactivation gradient over everything that shares the bias: delta_b = sum q =
+ *   Delta * sum k.  The integer sums are exact (int64); the float gradient is the ONE
+ *   product Delta * sum evaluated in fp64 and rounded to fp32 (reading: the paper prints
+ *   no formula for delta_b).
+ *     mode 0: codes [rows x cols], bias per column:      sums[c] = sum_r k[r][c]   (FC)
+ *     mode 1: codes [rows x cols], rows = (n, ch) with ch = r % len fastest:
+ *             sums[ch] = sum over rows r with r % len == ch and all columns      (conv)
+ * ---------------------------------------------------------------------------------- */
+void dbp_oracle_relu_backward(const float *delta_a, const float *act, int64_t n, float *delta_z)
+{
+    for (int64_t j = 0; j < n; ++j) delta_z[j] = act[j] > 0.0f ? delta_a[j] : 0.0f;
+}
+
+void dbp_oracle_bias_grad(const int8_t *codes, int64_t rows, int64_t cols, int mode, int64_t len,
+                          float step, int64_t *sums, float *grad)
+{
+    for (int64_t i = 0; i < len; ++i) sums[i] = 0;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c)
+            sums[mode == 0 ? c : r % len] += codes[r * cols + c];
+    if (grad)
+        for (int64_t i = 0; i < len; ++i) grad[i] = (float)((double)step * (double)sums[i]);
 }
 
 /* ------------------------------------------------------------------------------------

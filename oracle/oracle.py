@@ -56,6 +56,7 @@ def lib():
         L.dbp_oracle_linear_dw_i8.restype = C.c_int64
         L.dbp_oracle_conv2d_dw_i8.restype = C.c_int64
         L.dbp_oracle_max_threads.restype = C.c_int
+        L.dbp_oracle_step_size.restype = C.c_float
     return _lib
 
 
@@ -97,6 +98,34 @@ def nsd(delta, step: float, seed: int, idx_base: int = 0):
     lib().dbp_oracle_nsd(_p(d), C.c_int64(d.size), C.c_float(step), C.c_uint64(seed),
                          C.c_uint64(idx_base), _p(codes), C.byref(st))
     return codes, Stats(st.nnz, st.n_saturated, st.n_nonfinite, st.max_abs_code)
+
+
+def step_size(delta, s: float):
+    """(Delta = s*std(delta) as fp32, sigma as fp64): Algorithm 1, population std, radix-16 summation tree."""
+    d = _f32(delta)
+    sigma = C.c_double(0.0)
+    step = lib().dbp_oracle_step_size(_p(d), C.c_int64(d.size), C.c_float(s), C.byref(sigma))
+    return float(step), float(sigma.value)
+
+
+def relu_backward(delta_a, act):
+    """delta_z = delta_a (.) f'(z) for the rectifier: delta_a where act > 0, +0.0 elsewhere (exact)."""
+    d, a = _f32(delta_a), _f32(act)
+    assert d.shape == a.shape
+    out = np.empty(d.shape, dtype=np.float32)
+    lib().dbp_oracle_relu_backward(_p(d), _p(a), C.c_int64(d.size), _p(out))
+    return out
+
+
+def bias_grad(codes, rows: int, cols: int, per_column: bool, length: int, step: float):
+    """(int64 code sums [length], fp32 bias gradient Delta*sum [length]); see dbp_oracle_bias_grad."""
+    k = _i8(codes)
+    assert k.size == rows * cols
+    sums = np.zeros(length, dtype=np.int64)
+    grad = np.zeros(length, dtype=np.float32)
+    lib().dbp_oracle_bias_grad(_p(k), C.c_int64(rows), C.c_int64(cols), C.c_int(0 if per_column else 1),
+                               C.c_int64(length), C.c_float(step), _p(sums), _p(grad))
+    return sums, grad
 
 
 def tile_format(codes, rows: int, cols: int):

@@ -234,3 +234,103 @@ def test_tile_format_decodes_back_to_the_code_plane(rows, cols):
                 dec[r, s * 256 + c] = v
             assert np.all(entries[t, int(tile_nnz[t]):] == 0xFFFF)          # untouched slots
     assert np.array_equal(dec, codes)
+
+
+# ---- the step before the quantiser and its by-product (delta_z = delta_a (.) f'(z); delta_b = sum q) ----
+
+def test_relu_backward_is_the_hadamard_product_with_the_step_function():
+    from oracle import oracle as O
+    # worked by hand: f'(z) = [z > 0]; -0.0, 0.0 and NaN mask the element
+    da = np.array([1.5, -2.0, 3.0, 4.0, 5.0, -6.0], dtype=np.float32)
+    z = np.array([0.1, -0.1, 0.0, -0.0, np.nan, 7.0], dtype=np.float32)
+    assert O.relu_backward(da, z).tolist() == [1.5, 0.0, 0.0, 0.0, 0.0, -6.0]
+    rng = np.random.default_rng(3)
+    da = rng.standard_normal((37, 129)).astype(np.float32)
+    z = rng.standard_normal((37, 129)).astype(np.float32)
+    got = O.relu_backward(da, z)
+    assert np.array_equal(got, da * (z > 0))                       # Hadamard product with the 0/1 derivative
+    assert np.array_equal(got, O.relu_backward(da, np.maximum(z, 0)))   # a = f(z) carries the same sign information
+
+
+def test_bias_gradient_is_the_batch_sum_of_the_quantised_gradient():
+    from oracle import oracle as O
+    # worked by hand, FC: codes [3 x 2], Delta = 0.5: column sums (1-2+4, 0+5-1) = (3, 4) -> (1.5, 2.0)
+    k = np.array([[1, 0], [-2, 5], [4, -1]], dtype=np.int8)
+    s, g = O.bias_grad(k, 3, 2, True, 2, 0.5)
+    assert s.tolist() == [3, 4] and g.tolist() == [1.5, 2.0]
+    # conv: rows are (n, ch) with ch fastest; N = 2, K = 3, 2 pixels: channel sums over n and pixels
+    k = np.array([[1, 2], [3, 4], [5, 6], [-1, -2], [-3, -5], [7, 0]], dtype=np.int8)
+    s, g = O.bias_grad(k, 6, 2, False, 3, 2.0)
+    assert s.tolist() == [0, -1, 18] and g.tolist() == [0.0, -2.0, 36.0]
+    # against numpy on random codes, and against the float sum of q = k*Delta (exact here: small integers, Delta = 2^-3)
+    rng = np.random.default_rng(5)
+    k = rng.integers(-127, 128, size=(64, 300)).astype(np.int8)
+    s, g = O.bias_grad(k, 64, 300, True, 300, 0.125)
+    assert np.array_equal(s, k.astype(np.int64).sum(axis=0))
+    assert np.array_equal(g, (k.astype(np.float64) * 0.125).sum(axis=0).astype(np.float32))
+    k4 = rng.integers(-127, 128, size=(5, 7, 3, 4)).astype(np.int8)               # N, K, P, Q
+    s, _ = O.bias_grad(k4, 35, 12, False, 7, 1.0)
+    assert np.array_equal(s, k4.astype(np.int64).sum(axis=(0, 2, 3)))
+    # the sum over the batch of an unbiased quantiser is unbiased for the true bias gradient (Eq. (unbiased))
+    d = rng.laplace(0, 1e-3, size=(4096, 8)).astype(np.float32)
+    step = 4e-3
+    kk, _ = O.nsd(d, step, 11)
+    _, g = O.bias_grad(kk, 4096, 8, True, 8, step)
+    true = d.astype(np.float64).sum(axis=0)
+    # variance of one element's error <= Delta^2/4 (Eq. (bounded variance)): 5 sigma of the sum
+    assert np.all(np.abs(g - true) < 5 * np.sqrt(4096 * step * step / 4))
+
+
+# ---- step size of a layer: Algorithm 1, sigma = std(delta_z), Delta = s*sigma ----
+
+def test_step_size_is_s_times_the_population_standard_deviation():
+    from oracle import oracle as O
+    # closed forms: +-a in equal numbers -> sigma = a;  0..n-1 -> sqrt((n^2-1)/12);  constant -> 0
+    x = np.array([0.25, -0.25] * 500, dtype=np.float32)
+    step, sigma = O.step_size(x, 4)
+    assert sigma == 0.25 and step == 1.0
+    n = 1000
+    step, sigma = O.step_size(np.arange(n, dtype=np.float32), 1)
+    assert abs(sigma - np.sqrt((n * n - 1) / 12.0)) < 1e-9
+    assert O.step_size(np.full(77, 3.5, dtype=np.float32), 8) == (0.0, 0.0)
+    # worked by hand: (1, 2, 3, 6): mean 3, squared deviations 4+1+0+9 = 14, variance 3.5
+    step, sigma = O.step_size(np.array([1, 2, 3, 6], dtype=np.float32), 2)
+    assert sigma == np.sqrt(3.5) and step == np.float32(2 * np.sqrt(3.5))
+    # against numpy's two-pass fp64 std on the workloads' gradient laws, any size (ragged groups of the tree)
+    rng = np.random.default_rng(7)
+    for size in (1, 15, 16, 17, 255, 4097, 70001):
+        d = rng.laplace(0, 1e-3, size=size).astype(np.float32)
+        step, sigma = O.step_size(d, 8)
+        ref = np.std(d.astype(np.float64))
+        assert abs(sigma - ref) <= 1e-12 * max(ref, 1e-30) + 1e-18
+        assert step == np.float32(8 * sigma)
+    # a shifted distribution (mean >> sigma) still resolves sigma: fp64 sums of fp32 values
+    d = (1.0 + rng.standard_normal(50000) * 1e-3).astype(np.float32)
+    _, sigma = O.step_size(d, 1)
+    assert abs(sigma - np.std(d.astype(np.float64))) < 1e-9
+    # scaling the data by a power of two scales Delta exactly (no dependence on magnitude)
+    d = rng.laplace(0, 1e-3, size=5000).astype(np.float32)
+    assert O.step_size(d * 8, 4)[0] == 8 * O.step_size(d, 4)[0]
+
+
+def test_step_size_summation_order_is_the_radix16_tree():
+    from oracle import oracle as O
+    # Values for which the ORDER of the fp64 additions changes the sum of squares: 2^54 absorbs a following 1.0
+    # (spacing 4 up there) but not a following 16.0.  x = (2^27, then 31 ones): the tree sums group 0 of the
+    # squares to 2^54 (its 15 ones absorbed one by one) and group 1 to 16 exactly, total 2^54 + 16; a plain
+    # left-to-right sum absorbs all 31 ones (2^54); a pairwise tree gives 2^54 + 28 (two ones paired with each
+    # other first everywhere but next to the big value).  S1 = 2^27 + 31 exactly in every order.
+    def sigma_of(s1, s2, n):
+        return float(np.sqrt((np.float64(s2) - np.float64(s1) * np.float64(s1) / np.float64(n)) / np.float64(n)))
+    x = np.array([2.0 ** 27] + [1.0] * 31, dtype=np.float32)
+    _, sigma = O.step_size(x, 1)
+    s1 = 2.0 ** 27 + 31.0
+    tree, sequential = sigma_of(s1, 2.0 ** 54 + 16.0, 32), sigma_of(s1, 2.0 ** 54, 32)
+    assert tree != sequential
+    assert sigma == tree
+    # second level of the tree: 17 groups; group 0 = 2^54 (15 ones absorbed), groups 1..16 = 16 each;
+    # level 2: 2^54 + 15*16 (exact, multiples of 4), then + 16
+    y = np.array([2.0 ** 27] + [1.0] * (15 + 16 * 16), dtype=np.float32)
+    _, sigma = O.step_size(y, 1)
+    assert sigma == sigma_of(2.0 ** 27 + 271.0, 2.0 ** 54 + 256.0, y.size)
+    assert sigma != sigma_of(2.0 ** 27 + 271.0, 2.0 ** 54, y.size)
