@@ -203,6 +203,81 @@ dbp_status dbp_conv2d_products(const int8_t *codes, const void *format, float st
                                float *dX, void *dW, void *workspace, size_t workspace_bytes,
                                dbp_path path, void *stream);
 
+
+/*
+ * ---------------------------------------------------------------------------------------------------------
+ * Algorithm 1 on the device, and the two steps that surround the quantiser in a layer's backward pass.
+ * ---------------------------------------------------------------------------------------------------------
+ * Step size (Algorithm 1, lines 2-3):  sigma = std(delta_z),  Delta = s * sigma.
+ *   Readings: population standard deviation (divide by n) over ALL elements of the tensor, from
+ *   S1 = sum x and S2 = sum x*x accumulated in fp64; because Delta decides integer codes the order of the
+ *   sums is part of the definition: a radix-16 tree (groups of 16 consecutive values summed left to right,
+ *   the group sums likewise, until one value is left).  sigma = sqrt((S2 - S1*S1/n)/n), Delta = fp32(s*sigma).
+ *   With `act` the deviation is that of delta_z = delta_a (.) f'(z) (see below).
+ *   step_out  device, out: {Delta, 1/Delta} (8-byte aligned).  A layer whose sigma is 0 or not finite gets
+ *             {0, 0}: every code is then 0 and both products are exactly 0.
+ *   workspace dbp_step_size_workspace_bytes(n) bytes, 256-byte aligned.
+ * Errors: NULL pointers -> NULL; n <= 0 -> SHAPE; s not positive/finite -> STEP; workspace -> WORKSPACE.
+ */
+size_t     dbp_step_size_workspace_bytes(int64_t n);
+dbp_status dbp_step_size(const float *delta /*device*/, const float *act /*device, nullable*/, int64_t n, float s,
+                         float *step_out /*device [2]*/, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Options of nsd_quantize_ex (a host struct of device pointers; every member may be NULL / 0):
+ *   act        same shape as delta.  delta_z = delta_a (.) f'(z) (the first line of the backward pass) for the
+ *              rectifier: the element is quantised where act > 0 and is +0 elsewhere; act may be z or a = f(z)
+ *              (-0.0 and NaN count as not positive).
+ *   step_dev   {Delta, 1/Delta} in device memory as written by dbp_step_size; replaces the `step` argument.
+ *   bias_sums  out, int64 [bias_len]: exact sums of the codes over everything that shares a bias (the bias
+ *              enters Eq. (z) additively, so delta_b = sum of the quantised gradient = Delta * sum of codes).
+ *              DBP_BIAS_PER_COLUMN: bias_len == cols, sums[c] = sum_r k[r][c]                      (FC, rows = batch)
+ *              DBP_BIAS_PER_ROW_GROUP: rows % bias_len == 0, sums[g] = sum over rows r with r % bias_len == g
+ *              and all columns                                       (conv: rows = (n,k), columns = pixels)
+ *   bias_grad  out, fp32 [bias_len] = fp32( (double)Delta * (double)sums ); needs bias_sums.
+ */
+typedef enum { DBP_BIAS_PER_COLUMN = 0, DBP_BIAS_PER_ROW_GROUP = 1 } dbp_bias_mode;
+typedef struct {
+    const float *act;
+    const float *step_dev;
+    int64_t     *bias_sums;
+    float       *bias_grad;
+    int32_t      bias_mode;
+    int64_t      bias_len;
+} dbp_nsd_extras;
+
+/* nsd_quantize with the options above (extras == NULL: identical to nsd_quantize).
+ * Errors as nsd_quantize; inconsistent bias_len -> SHAPE; unknown bias_mode -> UNSUPPORTED. */
+dbp_status nsd_quantize_ex(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed,
+                           uint64_t idx_base, int8_t *codes, void *format, size_t format_bytes,
+                           dbp_stats *stats, const dbp_nsd_extras *extras /*host*/, void *stream);
+
+/*
+ * The whole backward pass of a layer as Algorithm 1 states it, in one call:
+ *   delta_z = delta_a (.) f'(z)   (act != NULL; rectifier)
+ *   Delta   = s * std(delta_z)    (on the device; also returned in step_out when that is not NULL)
+ *   q       = NSD(delta_z)        Eq. (qdz)
+ *   dX, dW  = Eqs. (qda), (qdw);  db = Delta * sum over the batch (and pixels) of the codes.
+ * dX, dW, db are each nullable (not all three).  Workspace: dbp_*_layer_workspace_bytes.
+ * Errors as dithered_*_backward, with `s` checked in place of the step.
+ */
+size_t     dbp_linear_layer_workspace_bytes(int64_t B, int64_t in, int64_t out, dbp_dtype x_dtype);
+size_t     dbp_conv2d_layer_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
+                                            int64_t S, int64_t stride, int64_t pad, dbp_dtype x_dtype);
+dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act, const float *W, const void *X,
+                                          dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float s,
+                                          uint64_t seed, uint64_t idx_base, int8_t *codes, float *dX, void *dW,
+                                          float *db /*device [out]*/, float *step_out /*device [2]*/,
+                                          void *workspace, size_t workspace_bytes, dbp_stats *stats,
+                                          dbp_path path, void *stream);
+dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act, const float *W, const void *X,
+                                          dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd,
+                                          int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad, float s,
+                                          uint64_t seed, uint64_t idx_base, int8_t *codes, float *dX, void *dW,
+                                          float *db /*device [K]*/, float *step_out /*device [2]*/,
+                                          void *workspace, size_t workspace_bytes, dbp_stats *stats,
+                                          dbp_path path, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,6 +45,13 @@ class Stats:
         return Stats(nnz, sat, nf, mx)
 
 
+class _Extras(C.Structure):
+    _fields_ = [("act", C.c_void_p), ("step_dev", C.c_void_p), ("bias_sums", C.c_void_p), ("bias_grad", C.c_void_p),
+                ("bias_mode", C.c_int32), ("bias_len", C.c_int64)]
+
+
+BIAS_PER_COLUMN, BIAS_PER_ROW_GROUP = 0, 1
+
 _lib = None
 
 
@@ -76,6 +83,20 @@ def lib():
         L.dense_conv2d_backward.argtypes = [vp, vp, vp, ci] + [i64] * 9 + [vp, vp, vp, sz, vp]
         L.dbp_linear_products.argtypes = [vp, vp, f32, vp, vp, ci, i64, i64, i64, vp, vp, vp, sz, ci, vp]
         L.dbp_conv2d_products.argtypes = [vp, vp, f32, vp, vp, ci] + [i64] * 9 + [vp, vp, vp, sz, ci, vp]
+        L.dbp_step_size_workspace_bytes.restype = sz
+        L.dbp_step_size_workspace_bytes.argtypes = [i64]
+        L.dbp_step_size.argtypes = [vp, vp, i64, f32, vp, vp, sz, vp]
+        L.nsd_quantize_ex.argtypes = [vp, i64, i64, f32, u64, u64, vp, vp, sz, vp, C.POINTER(_Extras), vp]
+        L.dbp_linear_layer_workspace_bytes.restype = sz
+        L.dbp_linear_layer_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        L.dbp_conv2d_layer_workspace_bytes.restype = sz
+        L.dbp_conv2d_layer_workspace_bytes.argtypes = [i64] * 9 + [ci]
+        L.dithered_linear_layer_backward.argtypes = [vp, vp, vp, vp, ci, i64, i64, i64, f32, u64, u64, vp, vp, vp, vp, vp,
+                                                     vp, sz, vp, ci, vp]
+        L.dithered_conv2d_layer_backward.argtypes = [vp, vp, vp, vp, ci] + [i64] * 9 + [f32, u64, u64, vp, vp, vp, vp, vp,
+                                                                                        vp, sz, vp, ci, vp]
+        for name in ("dbp_step_size", "nsd_quantize_ex", "dithered_linear_layer_backward", "dithered_conv2d_layer_backward"):
+            getattr(L, name).restype = ci
         for name in ("dbp_format_layout_of", "nsd_quantize", "dithered_linear_backward", "dithered_conv2d_backward",
                      "dense_linear_backward", "dense_conv2d_backward", "dbp_linear_products", "dbp_conv2d_products"):
             getattr(L, name).restype = ci
@@ -160,3 +181,42 @@ def conv2d_products(codes, fmt, step, W, X, x_dtype, N, Cc, H, Wd, K, R, S, stri
                     path=PATH_AUTO, stream=0):
     _check(lib().dbp_conv2d_products(_ptr(codes), _ptr(fmt), step, _ptr(W), _ptr(X), x_dtype, N, Cc, H, Wd, K, R, S,
                                      stride, pad, _ptr(dX), _ptr(dW), _ptr(workspace), _nbytes(workspace), path, stream))
+
+
+def step_size_workspace_bytes(n: int) -> int:
+    return int(lib().dbp_step_size_workspace_bytes(n))
+
+
+def step_size(delta, act, n, s, step_out, workspace, stream=0):
+    """Algorithm 1, lines 2-3, on the device: step_out[0:2] = {s*std(delta_z), its reciprocal}."""
+    _check(lib().dbp_step_size(_ptr(delta), _ptr(act), n, s, _ptr(step_out), _ptr(workspace), _nbytes(workspace), stream))
+
+
+def nsd_quantize_ex(delta, rows, cols, step, seed, idx_base, codes, fmt=None, stats=None, act=None, step_dev=None,
+                    bias_sums=None, bias_grad=None, bias_mode=BIAS_PER_COLUMN, bias_len=0, stream=0):
+    ex = _Extras(_ptr(act), _ptr(step_dev), _ptr(bias_sums), _ptr(bias_grad), bias_mode, bias_len)
+    _check(lib().nsd_quantize_ex(_ptr(delta), rows, cols, step, seed, idx_base, _ptr(codes), _ptr(fmt), _nbytes(fmt),
+                                 _ptr(stats), C.byref(ex), stream))
+
+
+def linear_layer_workspace_bytes(B: int, in_: int, out: int, x_dtype: int = F32) -> int:
+    return int(lib().dbp_linear_layer_workspace_bytes(B, in_, out, x_dtype))
+
+
+def conv2d_layer_workspace_bytes(N, Cc, H, Wd, K, R, S, stride=1, pad=0, x_dtype: int = F32) -> int:
+    return int(lib().dbp_conv2d_layer_workspace_bytes(N, Cc, H, Wd, K, R, S, stride, pad, x_dtype))
+
+
+def dithered_linear_layer_backward(delta_a, act, W, X, x_dtype, B, in_, out, s, seed, idx_base, codes, dX, dW, db, step_out,
+                                   workspace, stats=None, path=PATH_AUTO, stream=0):
+    _check(lib().dithered_linear_layer_backward(_ptr(delta_a), _ptr(act), _ptr(W), _ptr(X), x_dtype, B, in_, out, s, seed,
+                                                idx_base, _ptr(codes), _ptr(dX), _ptr(dW), _ptr(db), _ptr(step_out),
+                                                _ptr(workspace), _nbytes(workspace), _ptr(stats), path, stream))
+
+
+def dithered_conv2d_layer_backward(delta_a, act, W, X, x_dtype, N, Cc, H, Wd, K, R, S, stride, pad, s, seed, idx_base, codes,
+                                   dX, dW, db, step_out, workspace, stats=None, path=PATH_AUTO, stream=0):
+    _check(lib().dithered_conv2d_layer_backward(_ptr(delta_a), _ptr(act), _ptr(W), _ptr(X), x_dtype, N, Cc, H, Wd, K, R, S,
+                                                stride, pad, s, seed, idx_base, _ptr(codes), _ptr(dX), _ptr(dW), _ptr(db),
+                                                _ptr(step_out), _ptr(workspace), _nbytes(workspace), _ptr(stats), path,
+                                                stream))

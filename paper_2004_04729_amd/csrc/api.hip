@@ -56,7 +56,7 @@ Carve carve(int64_t rows, int64_t cols, size_t scratch_bytes)
 // (its statistics records are used either way).
 dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
                    int8_t *codes, char *fmt_base, const dbp_format_layout *L, dbp_stats *stats, hipStream_t s,
-                   bool want_format = true, StatsJob *defer = nullptr)
+                   bool want_format = true, StatsJob *defer = nullptr, const dbp_nsd_extras *ex = nullptr)
 {
     NsdArgs a;
     a.delta = delta; a.codes = codes; a.stats = stats;
@@ -67,6 +67,11 @@ dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, u
     a.partials = fmt_base ? (u32x4 *)(fmt_base + L->scratch_offset) : nullptr;
     a.rows = rows; a.cols = cols; a.tiles_per_row = L->tiles_per_row; a.n_tiles = L->n_tiles;
     a.inv_step = 1.0f / step;
+    a.act = nullptr; a.step_dev = nullptr; a.bias_sums = nullptr; a.bias_grad = nullptr; a.bias_mode = 0; a.bias_len = 0; a.step = step;
+    if (ex) {
+        a.act = ex->act; a.step_dev = ex->step_dev; a.bias_sums = ex->bias_sums; a.bias_grad = ex->bias_grad;
+        a.bias_mode = ex->bias_mode; a.bias_len = ex->bias_len;
+    }
     const DitherKeys k = make_dither_keys(seed);
     a.k0 = k.k0; a.k1 = k.k1; a.idx_base = idx_base;
     return launch_nsd(a, s, defer) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
@@ -94,19 +99,48 @@ dbp_status check_conv_dims(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t 
     return DBP_OK;
 }
 
+dbp_status check_extras(const dbp_nsd_extras *ex, int64_t rows, int64_t cols)
+{
+    if (!ex) return DBP_OK;
+    if (ex->act && !aligned(ex->act, 4)) return DBP_ERR_SHAPE;
+    if (ex->step_dev && !aligned(ex->step_dev, 4)) return DBP_ERR_SHAPE;
+    if (ex->bias_grad && !ex->bias_sums) return DBP_ERR_NULL;
+    if (ex->bias_sums) {
+        if (!aligned(ex->bias_sums, 8)) return DBP_ERR_SHAPE;
+        if (ex->bias_mode == DBP_BIAS_PER_COLUMN) { if (ex->bias_len != cols) return DBP_ERR_SHAPE; }
+        else if (ex->bias_mode == DBP_BIAS_PER_ROW_GROUP) { if (ex->bias_len <= 0 || rows % ex->bias_len) return DBP_ERR_SHAPE; }
+        else return DBP_ERR_UNSUPPORTED;
+    }
+    return DBP_OK;
+}
+
+// Workspace of the whole-layer entry points: the backward workspace, then the step-size scratch, the
+// {Delta, 1/Delta} pair and the bias code sums.
+struct LayerCarve { size_t step_scratch, step_pair, bias_sums, total; };
+LayerCarve layer_carve(size_t backward_total, int64_t n, int64_t bias_len)
+{
+    LayerCarve c;
+    c.step_scratch = align_up(backward_total, 256);
+    c.step_pair = c.step_scratch + step_size_scratch_bytes(n);
+    c.bias_sums = c.step_pair + 256;
+    c.total = c.bias_sums + align_up((size_t)bias_len * sizeof(int64_t), 256);
+    return c;
+}
+
 dbp_status linear_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
                            dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX, void *dW,
-                           void *workspace, size_t workspace_bytes, dbp_path path, void *stream, StatsJob job)
+                           void *workspace, size_t workspace_bytes, dbp_path path, void *stream, StatsJob job,
+                           const float *step_dev = nullptr)
 {
     if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
     dbp_status st = check_linear_dims(B, in, out);
     if (st != DBP_OK) return st;
-    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (!step_dev && !step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     LinearArgs a;
-    a.codes = codes; a.dense = nullptr; a.step = step; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.stats_job = job;
     if (path == DBP_PATH_GATHER) {
         if (!format) return DBP_ERR_NULL;
@@ -125,6 +159,32 @@ dbp_status linear_products(const int8_t *codes, const void *format, float step, 
     a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
+
+dbp_status conv2d_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
+                               dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                               int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW,
+                               void *workspace, size_t workspace_bytes, dbp_path path, void *stream, const float *step_dev = nullptr)
+{
+    (void)format;
+    if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    int64_t P, Q;
+    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
+    if (st != DBP_OK) return st;
+    if (!step_dev && !step_ok(step)) return DBP_ERR_STEP;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (stride != 1 || path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
+    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    ConvArgs a;
+    a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
+    a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
+    a.stats_job = StatsJob{nullptr, 0, nullptr};
+    return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
 
 }  // namespace
 
@@ -221,24 +281,8 @@ dbp_status dbp_conv2d_products(const int8_t *codes, const void *format, float st
                                int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW,
                                void *workspace, size_t workspace_bytes, dbp_path path, void *stream)
 {
-    (void)format;
-    if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
-    int64_t P, Q;
-    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
-    if (st != DBP_OK) return st;
-    if (!step_ok(step)) return DBP_ERR_STEP;
-    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (stride != 1 || path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
-    if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
-    ConvArgs a;
-    a.codes = codes; a.dense = nullptr; a.step = step; a.W = W; a.X = X; a.x_dtype = x_dtype;
-    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
-    a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    a.stats_job = StatsJob{nullptr, 0, nullptr};
-    return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+    return conv2d_products(codes, format, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, workspace,
+                           workspace_bytes, path, stream);
 }
 
 dbp_status dithered_conv2d_backward(const float *delta, const float *W, const void *X, dbp_dtype x_dtype,
@@ -263,8 +307,8 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, false);
     if (st != DBP_OK) return st;
-    return dbp_conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
-                               ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path, stream);
+    return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
+                           ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path, stream);
 }
 
 dbp_status dense_linear_backward(const void *delta, const float *W, const void *X, dbp_dtype x_dtype,
@@ -280,7 +324,7 @@ dbp_status dense_linear_backward(const void *delta, const float *W, const void *
     const size_t need = linear_scratch_bytes(B, in, out);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     LinearArgs a;
-    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr};
     return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
@@ -302,11 +346,131 @@ dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *
     const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     ConvArgs a;
-    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr};
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+
+// ---- Algorithm 1 on the device, and the steps around the quantiser ---------------------------------------
+
+size_t dbp_step_size_workspace_bytes(int64_t n)
+{
+    if (n <= 0 || n > kMaxElems) return 0;
+    return step_size_scratch_bytes(n);
+}
+
+dbp_status dbp_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!delta || !step_out) return DBP_ERR_NULL;
+    if (n <= 0 || n > kMaxElems) return DBP_ERR_SHAPE;
+    if (!(s > 0.0f) || !std::isfinite(s)) return DBP_ERR_STEP;
+    if (!aligned(delta, 4) || (act && !aligned(act, 4)) || !aligned(step_out, 8)) return DBP_ERR_SHAPE;
+    if (!workspace || workspace_bytes < step_size_scratch_bytes(n) || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    return launch_step_size(delta, act, n, s, step_out, workspace, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+dbp_status nsd_quantize_ex(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
+                           int8_t *codes, void *format, size_t format_bytes, dbp_stats *stats,
+                           const dbp_nsd_extras *extras, void *stream)
+{
+    if (!delta || !codes) return DBP_ERR_NULL;
+    dbp_format_layout L;
+    dbp_status st = format_layout(rows, cols, &L);
+    if (st != DBP_OK) return st;
+    if (!(extras && extras->step_dev) && !step_ok(step)) return DBP_ERR_STEP;
+    if (format && (format_bytes < L.total_bytes || !aligned(format, 256))) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    st = check_extras(extras, rows, cols);
+    if (st != DBP_OK) return st;
+    return run_nsd(delta, rows, cols, step, seed, idx_base, codes, (char *)format, &L, stats, (hipStream_t)stream, true,
+                   nullptr, extras);
+}
+
+size_t dbp_linear_layer_workspace_bytes(int64_t B, int64_t in, int64_t out, dbp_dtype x_dtype)
+{
+    const size_t b = dbp_linear_workspace_bytes(B, in, out, x_dtype);
+    return b ? layer_carve(b, B * out, out).total : 0;
+}
+
+size_t dbp_conv2d_layer_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                        int64_t stride, int64_t pad, dbp_dtype x_dtype)
+{
+    const size_t b = dbp_conv2d_workspace_bytes(N, C, H, Wd, K, R, S, stride, pad, x_dtype);
+    if (!b) return 0;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    return layer_carve(b, N * K * P * Q, K).total;
+}
+
+dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act, const float *W, const void *X,
+                                          dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float s,
+                                          uint64_t seed, uint64_t idx_base, int8_t *codes, float *dX, void *dW,
+                                          float *db, float *step_out, void *workspace, size_t workspace_bytes,
+                                          dbp_stats *stats, dbp_path path, void *stream)
+{
+    if (!delta_a || !W || (!dX && !dW && !db) || (dW && !X)) return DBP_ERR_NULL;
+    dbp_status st = check_linear_dims(B, in, out);
+    if (st != DBP_OK) return st;
+    if (!(s > 0.0f) || !std::isfinite(s)) return DBP_ERR_STEP;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const Carve c = carve(B, out, linear_scratch_bytes(B, in, out));
+    const LayerCarve lc = layer_carve(c.total, B * out, out);
+    if (!workspace || workspace_bytes < lc.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta_a, 4) || (act && !aligned(act, 4)) || (step_out && !aligned(step_out, 8))) return DBP_ERR_SHAPE;
+    char *ws = (char *)workspace;
+    hipStream_t hs = (hipStream_t)stream;
+    float *pair = step_out ? step_out : (float *)(ws + lc.step_pair);
+    if (launch_step_size(delta_a, act, B * out, s, pair, ws + lc.step_scratch, hs) != hipSuccess) return DBP_ERR_DEVICE;
+    dbp_nsd_extras ex;
+    ex.act = act; ex.step_dev = pair; ex.bias_sums = db ? (int64_t *)(ws + lc.bias_sums) : nullptr; ex.bias_grad = db;
+    ex.bias_mode = DBP_BIAS_PER_COLUMN; ex.bias_len = out;
+    int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
+    StatsJob job;
+    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex);
+    if (st != DBP_OK) return st;
+    if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+    return linear_products(k, ws, 1.0f, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset,
+                           c.total - c.scratch_offset, path, stream, job, pair);
+}
+
+dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act, const float *W, const void *X,
+                                          dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                                          int64_t R, int64_t S, int64_t stride, int64_t pad, float s, uint64_t seed,
+                                          uint64_t idx_base, int8_t *codes, float *dX, void *dW, float *db,
+                                          float *step_out, void *workspace, size_t workspace_bytes, dbp_stats *stats,
+                                          dbp_path path, void *stream)
+{
+    if (!delta_a || !W || (!dX && !dW && !db) || (dW && !X)) return DBP_ERR_NULL;
+    int64_t P, Q;
+    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
+    if (st != DBP_OK) return st;
+    if (!(s > 0.0f) || !std::isfinite(s)) return DBP_ERR_STEP;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (stride != 1 || path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad));
+    const LayerCarve lc = layer_carve(c.total, N * K * P * Q, K);
+    if (!workspace || workspace_bytes < lc.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta_a, 4) || (act && !aligned(act, 4)) || (step_out && !aligned(step_out, 8))) return DBP_ERR_SHAPE;
+    char *ws = (char *)workspace;
+    hipStream_t hs = (hipStream_t)stream;
+    float *pair = step_out ? step_out : (float *)(ws + lc.step_pair);
+    if (launch_step_size(delta_a, act, N * K * P * Q, s, pair, ws + lc.step_scratch, hs) != hipSuccess) return DBP_ERR_DEVICE;
+    dbp_nsd_extras ex;
+    ex.act = act; ex.step_dev = pair; ex.bias_sums = db ? (int64_t *)(ws + lc.bias_sums) : nullptr; ex.bias_grad = db;
+    ex.bias_mode = DBP_BIAS_PER_ROW_GROUP; ex.bias_len = K;
+    int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
+    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, false, nullptr, &ex);
+    if (st != DBP_OK) return st;
+    if (!dX && !dW) return DBP_OK;
+    return conv2d_products(k, ws, 1.0f, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
+                           ws + c.scratch_offset, c.total - c.scratch_offset, path, stream, pair);
 }
 
 }  // extern "C"

@@ -13,6 +13,13 @@ typedef int32_t  i32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4  __attribute__((ext_vector_type(4)));
 typedef __bf16   bf16x8 __attribute__((ext_vector_type(8)));
 
+// A product's output scale: a host value, or (Algorithm 1 on the device) the Delta an earlier kernel of the
+// same stream left in device memory.
+struct Scale {
+    float host; const float *dev;
+    __device__ __forceinline__ float get() const { return dev ? dev[0] : host; }
+};
+
 constexpr int kWave = 64;
 constexpr int kNsdMaxBlocks = 16384;                                 // measured best on 2^28 elements (8 resident per CU)
 constexpr size_t kNsdScratchBytes = (size_t)kNsdMaxBlocks * 16;      // one 16-byte statistics record per workgroup
@@ -33,6 +40,14 @@ struct NsdArgs {
     float        inv_step;
     uint32_t     k0, k1;
     uint64_t     idx_base;
+    // ---- extensions around the quantiser (nsd_kernel<.., .., true>); all optional
+    const float *act;         // delta_z = delta_a where act > 0, else 0 (rectifier derivative), same shape as delta
+    const float *step_dev;    // device {Delta, 1/Delta} (from launch_step_size) instead of inv_step
+    int64_t     *bias_sums;   // int64 code sums, zeroed by launch_nsd; bias_mode 0: per column, 1: per (row % bias_len)
+    float       *bias_grad;   // Delta * sums, fp32 (nullable)
+    int          bias_mode;
+    int64_t      bias_len;
+    float        step;        // host Delta (bias_grad without step_dev)
     int          run;                                  // consecutive tiles per wavefront run (set by launch_nsd)
     int64_t      wave_stride_rows, wave_stride_segs;   // grid stride in tiles = rows*tiles_per_row + segs (set by launch_nsd)
 };
@@ -43,6 +58,12 @@ struct StatsJob { const u32x4 *partials; int n; dbp_stats *out; };
 // or calls launch_stats_job.
 hipError_t launch_nsd(const NsdArgs &a, hipStream_t s, StatsJob *defer = nullptr);
 hipError_t launch_stats_job(const StatsJob &j, hipStream_t s);
+
+// Step size of Algorithm 1 on the device: step_out = {Delta = s*std(delta_z), 1/Delta}, delta_z = delta masked by act > 0
+// when act is given (both 0 if the standard
+// deviation is 0 or not finite).  scratch: step_size_scratch_bytes(n).
+size_t     step_size_scratch_bytes(int64_t n);
+hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -55,6 +76,7 @@ struct LinearArgs {
     const int8_t *codes;       // dithered path: int8 codes [B,out]
     const void   *dense;       // dense baseline: fp32 (or int8 in 8-bit mode) gradient [B,out]
     float         step;        // Delta (dithered); ignored for dense
+    const float  *step_dev;    // device {Delta, 1/Delta} instead of `step` (nullable)
     const float  *W;           // [out,in]
     const void   *X;           // [B,in] fp32 or int8
     dbp_dtype     x_dtype;
@@ -69,6 +91,7 @@ struct ConvArgs {
     const int8_t *codes;
     const void   *dense;
     float         step;
+    const float  *step_dev;
     const float  *W;           // [K,C,R,S]
     const void   *X;           // [N,C,H,Wd]
     dbp_dtype     x_dtype;

@@ -48,7 +48,7 @@ struct ConvDwArgs {
     int row4x, row4c;          // Wd % 4 == 0 / Q % 4 == 0: a piece never straddles rows -> one wide LDS write
     int row2x, row2c;          // Wd, Q even: at least its halves never do
     int lds_cells;             // 16-byte cells of LDS in use
-    float scale;
+    Scale scale;
 };
 
 template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
                 if (k < a.K && c < a.C) {
 #pragma unroll
                     for (int t = 0; t < RS; ++t) {
-                        if constexpr (MODE == MODE_BF16) out[((int64_t)k * a.C + c) * RS + t] = acc[t][mb][v] * a.scale;
+                        if constexpr (MODE == MODE_BF16) out[((int64_t)k * a.C + c) * RS + t] = acc[t][mb][v] * a.scale.get();
                         else out[((int64_t)k * a.C + c) * RS + t] = acc[t][mb][v];
                     }
                 }
@@ -403,7 +403,7 @@ __global__ __launch_bounds__(256) void conv_dw_reduce_kernel(ConvDwArgs a)
         const int k = kb + j;
         if (k < a.K && c < a.C) {
             AccT *out = (AccT *)a.dW + ((int64_t)k * a.C + c) * RS + t;
-            if constexpr (MODE == MODE_BF16) *out = sum[j] * a.scale; else *out = sum[j];
+            if constexpr (MODE == MODE_BF16) *out = sum[j] * a.scale.get(); else *out = sum[j];
         }
     }
 }

@@ -36,7 +36,7 @@ struct ConvDxArgs {
     int cgroups;              // ceil(C / (32*wc))
     int tiles;                // pixel tiles per image
     int prow, pw, patch_cells;// patch rows (maximum over tiles), patch width Wd+S-1 ... cells per k-group
-    float scale;
+    Scale scale;
 };
 
 // fp32 weights [K][C][R][S] -> bf16 planes in fragment order (plane 0 = lo, 1 = mid, 2 = hi), zero padded.
@@ -221,6 +221,7 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
     // ---- store: lane holds pixel column lcol, channel rows 8*(v/4) + 4*lhalf + v%4 of its block ----
     if (wave_active) {
         float *out = a.dX + (int64_t)n * a.C * a.PI;          // offsets inside one image fit 31 bits (host check)
+        const float sc = a.scale.get();
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int j = jw0 + 32 * nb + lcol;
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int c = c0 + 8 * (v >> 2) + (v & 3);
-                if (c < a.C) out[off] = acc[nb][v] * a.scale;
+                if (c < a.C) out[off] = acc[nb][v] * sc;
                 off += (v & 3) == 3 ? 5 * a.PI : a.PI;
             }
         }

@@ -270,6 +270,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
                 // block (i,j) covers row positions 64*wave + 32*i.. and column positions 32*j.. (column 4*lcol + j);
                 // D[ii][jj] of a block sits in lane (jj, ii%8/4), register 4*(ii/8)+ii%4.
                 const int col = c.tile_n + 4 * lcol;
+                const float sc = p.scale.get();
                 if (col < p.N) {
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
@@ -279,7 +280,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
                             const int row = fc2_row(p.a_kfast, c.tile_m, wave, i, ii);
                             if (row < p.M)
                                 *(float4 *)(p.out + (int64_t)row * p.ldc + col) =
-                                    float4{p.scale * acc[i][0][v], p.scale * acc[i][1][v], p.scale * acc[i][2][v], p.scale * acc[i][3][v]};
+                                    float4{sc * acc[i][0][v], sc * acc[i][1][v], sc * acc[i][2][v], sc * acc[i][3][v]};
                         }
                 }
             }
@@ -315,8 +316,9 @@ __global__ __launch_bounds__(256) void fc2_reduce_kernel(FcPairArgs a, int tiles
     const int i = slot >> 4, v = slot & 15;
     const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
     const int row = fc2_row(p.a_kfast, tile_m, wave, i, ii);
+    const float sc = p.scale.get();
     if (col < p.N && row < p.M)
-        *(float4 *)(p.out + (int64_t)row * p.ldc + col) = float4{p.scale * sum.x, p.scale * sum.y, p.scale * sum.z, p.scale * sum.w};
+        *(float4 *)(p.out + (int64_t)row * p.ldc + col) = float4{sc * sum.x, sc * sum.y, sc * sum.z, sc * sum.w};
 }
 
 }  // namespace dbp

@@ -34,7 +34,7 @@ struct FcProblem {
     float *out; int64_t ldc;          // out[m*ldc + n]
     float *partial;                   // [tile][split][128*128] in thread order (n_split > 1)
     int M, N, K, k_per_split, n_split, tiles_m, n_items;
-    float scale;
+    Scale scale;
     int a_kfast;
 };
 struct FcPairArgs { FcProblem prob[2]; StatsJob stats; };
@@ -197,6 +197,7 @@ __device__ __forceinline__ void fc_item(const FcProblem &p, int item, FcSmem &sm
     // ---- epilogue: block (i,j) covers row positions (2*wr+i)*32.. and column positions (2*wc+j)*32..;
     // D[ii][jj] of a block sits in lane (jj, ii%8/4), register 4*(ii/8)+ii%4.
     const int col = tile_n + 4 * (lane & 31) + 2 * wc;          // columns col, col+1 (j = 0, 1)
+    const float sc = p.scale.get();
     if (col < p.N) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -206,7 +207,7 @@ __device__ __forceinline__ void fc_item(const FcProblem &p, int item, FcSmem &sm
                 const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 const int row = A_KFAST ? tile_m + mbg * 32 + ii : tile_m + 4 * ii + mbg;
                 if (row < p.M)
-                    *(float2 *)(p.out + (int64_t)row * p.ldc + col) = float2{p.scale * acc[i][0][v], p.scale * acc[i][1][v]};
+                    *(float2 *)(p.out + (int64_t)row * p.ldc + col) = float2{sc * acc[i][0][v], sc * acc[i][1][v]};
             }
         }
     }
@@ -286,13 +287,14 @@ __global__ __launch_bounds__(256) void fc_reduce_kernel(FcPairArgs a, int tiles0
         }
     }
     if (col >= p.N) return;
+    const float sc = p.scale.get();
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
         const int slot = quarter * 8 + u, i = slot >> 4, v = slot & 15;
         const int mbg = wr * 2 + i;
         const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
         const int row = p.a_kfast ? tile_m + mbg * 32 + ii : tile_m + 4 * ii + mbg;
-        if (row < p.M) *(float2 *)(p.out + (int64_t)row * p.ldc + col) = float2{p.scale * sum[u].x, p.scale * sum[u].y};
+        if (row < p.M) *(float2 *)(p.out + (int64_t)row * p.ldc + col) = float2{sc * sum[u].x, sc * sum[u].y};
     }
 }
 

@@ -13,7 +13,7 @@ constexpr int kSlab = 1024;     // output columns per workgroup: 256 threads x 4
 // dX[b, i] = step * sum over nonzero (o, k) of row b:  k * W[o, i]
 template <bool VEC>
 __global__ __launch_bounds__(256) void linear_dx_gather_kernel(FormatView f, const float *W, float *dX,
-                                                                int in, int out, float step)
+                                                                int in, int out, Scale step_arg)
 {
     const int b = blockIdx.y;
     const int i0 = blockIdx.x * kSlab + 4 * threadIdx.x;
@@ -56,13 +56,13 @@ __global__ __launch_bounds__(256) void linear_dx_gather_kernel(FormatView f, con
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-        if (i0 + j < in) dX[(int64_t)b * in + i0 + j] = step * acc[j];
+        if (i0 + j < in) dX[(int64_t)b * in + i0 + j] = step_arg.get() * acc[j];
 }
 
 // dW[o, i] = step * sum over batch rows b with code[b,o] != 0:  k * X[b, i]   (int32 sum for int8 X)
 template <class XT, class AccT, bool VEC>
 __global__ __launch_bounds__(256) void linear_dw_gather_kernel(const int8_t *codes, const XT *X, AccT *dW,
-                                                                int B, int in, int out, float step)
+                                                                int B, int in, int out, Scale step_arg)
 {
     __shared__ uint32_t s_list[4096];       // (b << 8) | code, batch order; B <= 4096 per pass
     __shared__ int s_cnt[4];
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void linear_dw_gather_kernel(const int8_t *cod
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         if (i0 + j < in) {
-            if (sizeof(XT) == 4) dW[(int64_t)o * in + i0 + j] = (AccT)(step * (float)acc[j]);
+            if (sizeof(XT) == 4) dW[(int64_t)o * in + i0 + j] = (AccT)(step_arg.get() * (float)acc[j]);
             else dW[(int64_t)o * in + i0 + j] = acc[j];
         }
 }
@@ -136,8 +136,8 @@ hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStr
     const unsigned slabs = (unsigned)((in + kSlab - 1) / kSlab);
     if (a.dX) {
         const bool vec = in % 4 == 0 && ((uintptr_t)a.W % 16) == 0;
-        if (vec) hipLaunchKernelGGL(linear_dx_gather_kernel<true>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, a.step);
-        else     hipLaunchKernelGGL(linear_dx_gather_kernel<false>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, a.step);
+        if (vec) hipLaunchKernelGGL(linear_dx_gather_kernel<true>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, Scale{a.step, a.step_dev});
+        else     hipLaunchKernelGGL(linear_dx_gather_kernel<false>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, Scale{a.step, a.step_dev});
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -145,15 +145,15 @@ hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStr
         if (a.x_dtype == DBP_F32) {
             const bool vec = in % 4 == 0 && ((uintptr_t)a.X % 16) == 0;
             if (vec) hipLaunchKernelGGL((linear_dw_gather_kernel<float, float, true>), dim3(slabs, out), block, 0, s,
-                                        a.codes, (const float *)a.X, (float *)a.dW, B, in, out, a.step);
+                                        a.codes, (const float *)a.X, (float *)a.dW, B, in, out, Scale{a.step, a.step_dev});
             else     hipLaunchKernelGGL((linear_dw_gather_kernel<float, float, false>), dim3(slabs, out), block, 0, s,
-                                        a.codes, (const float *)a.X, (float *)a.dW, B, in, out, a.step);
+                                        a.codes, (const float *)a.X, (float *)a.dW, B, in, out, Scale{a.step, a.step_dev});
         } else {
             const bool vec = in % 4 == 0 && ((uintptr_t)a.X % 4) == 0;
             if (vec) hipLaunchKernelGGL((linear_dw_gather_kernel<int8_t, int32_t, true>), dim3(slabs, out), block, 0, s,
-                                        a.codes, (const int8_t *)a.X, (int32_t *)a.dW, B, in, out, a.step);
+                                        a.codes, (const int8_t *)a.X, (int32_t *)a.dW, B, in, out, Scale{a.step, a.step_dev});
             else     hipLaunchKernelGGL((linear_dw_gather_kernel<int8_t, int32_t, false>), dim3(slabs, out), block, 0, s,
-                                        a.codes, (const int8_t *)a.X, (int32_t *)a.dW, B, in, out, a.step);
+                                        a.codes, (const int8_t *)a.X, (int32_t *)a.dW, B, in, out, Scale{a.step, a.step_dev});
         }
         return hipGetLastError();
     }

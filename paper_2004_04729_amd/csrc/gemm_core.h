@@ -280,7 +280,7 @@ struct GemmShape {
 // The kernel
 // ----------------------------------------------------------------------------------------------
 template <int MODE, class AL, class BL, class OM>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(AL al, BL bl, OM om, GemmShape sh, float scale,
+__global__ __launch_bounds__(256, 2) void gemm_kernel(AL al, BL bl, OM om, GemmShape sh, Scale scale_arg,
                                                        typename ModeTraits<MODE>::Acc *out,
                                                        typename ModeTraits<MODE>::Acc *partial)
 {
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(AL al, BL bl, OM om, GemmS
                 if (row >= sh.M) continue;
                 if (direct) {
                     if (MODE == MODE_I8) out[om(row, col)] = acc[i][j][v];
-                    else out[om(row, col)] = (Acc)(scale * (float)acc[i][j][v]);
+                    else out[om(row, col)] = (Acc)(scale_arg.get() * (float)acc[i][j][v]);
                 } else {
                     partial[((int64_t)blockIdx.z * sh.M + row) * sh.N + col] = acc[i][j][v];
                 }
@@ -412,14 +412,14 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(AL al, BL bl, OM om, GemmS
 
 // Sum the split-K partials in a fixed order, scale, and scatter through the output map.
 template <class Acc, class OM>
-__global__ __launch_bounds__(256) void reduce_kernel(const Acc *partial, Acc *out, OM om, int M, int N, int nsplit, float scale)
+__global__ __launch_bounds__(256) void reduce_kernel(const Acc *partial, Acc *out, OM om, int M, int N, int nsplit, Scale scale_arg)
 {
     const int64_t total = (int64_t)M * N;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
         Acc s = 0;
         for (int z = 0; z < nsplit; ++z) s += partial[(int64_t)z * total + idx];
         const int row = (int)(idx / N), col = (int)(idx - (int64_t)row * N);
-        if constexpr (std::is_same<Acc, float>::value) out[om(row, col)] = scale * s;
+        if constexpr (std::is_same<Acc, float>::value) out[om(row, col)] = scale_arg.get() * s;
         else out[om(row, col)] = s;
     }
 }

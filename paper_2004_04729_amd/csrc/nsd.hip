@@ -62,13 +62,16 @@ __device__ __forceinline__ uint32_t pack_low_bytes(int a, int b, int c, int d)
 
 // One wavefront owns one 256-column tile per loop trip; every index that is the same for the whole
 // wavefront (tile, row, segment, base offsets, the high half of the dither counter) lives in SGPRs.
-template <bool VEC, bool FORMAT>
+// EX adds what surrounds the quantiser in a layer's backward pass: the rectifier's derivative applied on load
+// (delta_z = delta_a (.) f'(z)), a step size that an earlier kernel left in device memory (Algorithm 1), and the
+// bias gradient's integer code sums (the bias enters z additively: delta_b = sum of q over what shares the bias).
+template <bool VEC, bool FORMAT, bool EX>
 __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
 {
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t n_waves = (int64_t)gridDim.x * 4;
-    const float inv = a.inv_step;
+    const float inv = (EX && a.step_dev) ? a.step_dev[1] : a.inv_step;
     const int c_in = 4 * lane;                                        // in-tile column of this lane's first element
 
     __shared__ __attribute__((aligned(16))) uint16_t s_ent[4][DBP_TILE];                          // per-wavefront staging of compacted entries
@@ -85,9 +88,9 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
     int64_t seg = t - row * a.tiles_per_row;
 
     auto tile_base = [&](int64_t r, int64_t sg) { return r * a.cols + sg * DBP_TILE; };
-    auto load_tile = [&](int64_t base, int valid, float (&x)[4]) {
+    auto load_tile = [&](const float *tensor, int64_t base, int valid, float (&x)[4]) {
         x[0] = x[1] = x[2] = x[3] = 0.f;
-        const float *src = a.delta + base;
+        const float *src = tensor + base;
         if (VEC) {
             if (c_in < valid) {
                 const f32x4 v = __builtin_nontemporal_load((const f32x4 *)(src + c_in));
@@ -101,12 +104,15 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
     };
 
     float x[4], x_next[4];
+    float m[4] = {1.f, 1.f, 1.f, 1.f}, m_next[4] = {1.f, 1.f, 1.f, 1.f};     // EX: the activation of each element
+    const bool masked = EX && a.act != nullptr;
     int64_t base = 0;
     int valid = 0;
     if (t < a.n_tiles) {
         base = tile_base(row, seg);
         valid = (int)min((int64_t)DBP_TILE, a.cols - seg * DBP_TILE);
-        load_tile(base, valid, x);
+        load_tile(a.delta, base, valid, x);
+        if (masked) load_tile(a.act, base, valid, m);
     }
 
     while (t < a.n_tiles) {
@@ -130,7 +136,13 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
         int valid_next = 0;
         if (t_next < a.n_tiles) {
             valid_next = (int)min((int64_t)DBP_TILE, a.cols - seg_next * DBP_TILE);
-            load_tile(base_next, valid_next, x_next);
+            load_tile(a.delta, base_next, valid_next, x_next);
+            if (masked) load_tile(a.act, base_next, valid_next, m_next);
+        }
+        if (masked) {
+            // derivative of the rectifier: 1 where the activation is positive (-0.0 and NaN count as not positive)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[j] = m[j] > 0.0f ? x[j] : 0.0f;
         }
 
         // ---- dither: elements share hash words pairwise by the parity of the GLOBAL index
@@ -184,6 +196,23 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
                 if (c_in + j < valid) dst[c_in + j] = (int8_t)k[j];
         }
 
+        // ---- bias gradient: integer sums of the codes (exact, order-free: atomics are deterministic here)
+        if (EX && a.bias_sums) {
+            if (a.bias_mode == 0) {
+                // per column; columns past the row's end hold x = 0 -> code 0 and add nothing
+                int64_t *col = a.bias_sums + seg * DBP_TILE + c_in;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (k[j] != 0) atomicAdd((unsigned long long *)(col + j), (unsigned long long)(long long)k[j]);
+            } else {
+                int sum = (k[0] + k[1]) + (k[2] + k[3]);
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+                if (lane == 0 && sum != 0)
+                    atomicAdd((unsigned long long *)(a.bias_sums + row % a.bias_len), (unsigned long long)(long long)sum);
+            }
+        }
+
         // ---- tile-sparse format
         const uint64_t b0 = __builtin_amdgcn_ballot_w64(k[0] != 0);
         const uint64_t b1 = __builtin_amdgcn_ballot_w64(k[1] != 0);
@@ -228,7 +257,7 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
 
         t = t_next; row = row_next; seg = seg_next; base = base_next; valid = valid_next;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) x[j] = x_next[j];
+        for (int j = 0; j < 4; ++j) { x[j] = x_next[j]; m[j] = m_next[j]; }
     }
 
     if (a.stats) {
@@ -293,7 +322,128 @@ __global__ void zero_stats_kernel(dbp_stats *s)
     if (threadIdx.x == 0) { s->nnz = 0; s->n_saturated = 0; s->n_nonfinite = 0; s->max_abs_code = 0; s->reserved = 0; }
 }
 
+__global__ void zero_i64_kernel(int64_t *p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// delta_b = Delta * (sum of codes): one fp64 product rounded to fp32 per bias element.
+__global__ void bias_grad_kernel(const int64_t *sums, int64_t n, float step, const float *step_dev, float *grad)
+{
+    const double d = step_dev ? (double)step_dev[0] : (double)step;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        grad[i] = (float)(d * (double)sums[i]);
+}
+
+// ---- step size of Algorithm 1: sigma = std(delta_z), Delta = s * sigma --------------------------------------
+// Population standard deviation from S1 = sum x and S2 = sum x*x in fp64 (x*x is exact there).  Delta decides
+// integer codes, so the ORDER of the sums is fixed: a radix-16 tree -- groups of 16 consecutive values are
+// summed left to right, the group sums again in groups of 16, and so on.  The first kernel does three levels
+// (a thread sums its 16 consecutive elements; lane 16g adds the 16 thread sums of its lane group in order; one
+// thread adds the workgroup's 16 lane-group sums in order), the second kernel finishes the tree with one
+// workgroup and writes {Delta, 1/Delta}.
+__global__ __launch_bounds__(256) void std_tree_kernel(const float *delta, const float *act, int64_t n, double *out1, double *out2)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int64_t first = ((int64_t)blockIdx.x * 256 + tid) * 16;     // this thread's 16 consecutive elements
+    const int have = (int)max((int64_t)0, min((int64_t)16, n - first));
+    float v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = 0.f;
+    if (have == 16 && (((uintptr_t)(delta + first)) & 15) == 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 t = *(const f32x4 *)(delta + first + 4 * q);
+            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) if (j < have) v[j] = delta[first + j];
+    }
+    if (act) {                                                         // delta_z = delta_a where the activation is positive
+#pragma unroll
+        for (int j = 0; j < 16; ++j) if (j < have) v[j] = act[first + j] > 0.0f ? v[j] : 0.0f;
+    }
+    // level 0 (elements past the end do not exist; adding their +0.0 squares or values changes nothing)
+    double s1 = (double)v[0], s2 = (double)v[0] * (double)v[0];
+#pragma unroll
+    for (int j = 1; j < 16; ++j) {
+        const double x = (double)v[j];
+        if (j < have) { s1 += x; s2 = __builtin_fma(x, x, s2); }       // x*x is exact: fma == multiply, then add
+    }
+    // level 1: lane 16g collects lanes 16g+1 .. 16g+15 in order (a thread without elements holds no value)
+    const int64_t n0 = (n + 15) / 16;                                  // values at level 0
+    const int64_t i0 = (int64_t)blockIdx.x * 256 + tid;
+    double a1 = s1, a2 = s2;
+#pragma unroll
+    for (int i = 1; i < 16; ++i) {
+        const double o1 = __shfl(s1, (lane & 48) + i), o2 = __shfl(s2, (lane & 48) + i);
+        if ((lane & 15) == 0 && i0 + i < n0) { a1 += o1; a2 += o2; }
+    }
+    // level 2: the workgroup's 16 lane groups in order
+    __shared__ double l1[2][16];
+    if ((lane & 15) == 0) { l1[0][tid >> 4] = a1; l1[1][tid >> 4] = a2; }
+    __syncthreads();
+    if (tid == 0) {
+        const int64_t n1 = (n0 + 15) / 16, i1 = (int64_t)blockIdx.x * 16;
+        double t1 = l1[0][0], t2 = l1[1][0];
+        for (int i = 1; i < 16; ++i)
+            if (i1 + i < n1) { t1 += l1[0][i]; t2 += l1[1][i]; }
+        out1[blockIdx.x] = t1; out2[blockIdx.x] = t2;
+    }
+}
+
+__global__ __launch_bounds__(256) void std_finish_kernel(double *a1, double *a2, double *b1, double *b2, int64_t count,
+                                                         int64_t n, float s, float *step_out)
+{
+    // remaining levels of the tree, ping-pong between the two scratch halves
+    double *src1 = a1, *src2 = a2, *dst1 = b1, *dst2 = b2;
+    while (count > 1) {
+        const int64_t groups = (count + 15) / 16;
+        for (int64_t g = threadIdx.x; g < groups; g += 256) {
+            const int64_t lo = g * 16, hi = min(count, lo + 16);
+            double t1 = src1[lo], t2 = src2[lo];
+            for (int64_t i = lo + 1; i < hi; ++i) { t1 += src1[i]; t2 += src2[i]; }
+            dst1[g] = t1; dst2[g] = t2;
+        }
+        __syncthreads();
+        double *t;
+        t = src1; src1 = dst1; dst1 = t;
+        t = src2; src2 = dst2; dst2 = t;
+        count = groups;
+    }
+    if (threadIdx.x == 0) {
+        const double S1 = n > 0 ? src1[0] : 0.0, S2 = n > 0 ? src2[0] : 0.0;
+        double var = n > 0 ? (S2 - S1 * S1 / (double)n) / (double)n : 0.0;
+        if (var < 0.0) var = 0.0;
+        const double sigma = __builtin_sqrt(var);
+        float step = (float)((double)s * sigma);
+        float inv = __fdiv_rn(1.0f, step);
+        // degenerate layer (constant or non-finite gradient): everything quantises to zero codes, products are zero
+        const bool ok = step > 0.0f && step < __builtin_inff() && inv >= 1.17549435e-38f && inv < __builtin_inff();
+        step_out[0] = ok ? step : 0.0f;
+        step_out[1] = ok ? inv : 0.0f;
+    }
+}
+
 }  // namespace
+
+size_t step_size_scratch_bytes(int64_t n)
+{
+    const int64_t wgs = (n + 4095) / 4096 > 0 ? (n + 4095) / 4096 : 1;
+    const int64_t second = (wgs + 15) / 16;                            // the finishing kernel's other half
+    return align_up((size_t)(2 * wgs + 2 * second) * sizeof(double), 256);
+}
+
+hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st)
+{
+    const int64_t wgs = (n + 4095) / 4096 > 0 ? (n + 4095) / 4096 : 1;
+    const int64_t second = (wgs + 15) / 16;
+    double *a1 = (double *)scratch, *a2 = a1 + wgs, *b1 = a2 + wgs, *b2 = b1 + second;
+    hipLaunchKernelGGL(std_tree_kernel, dim3((unsigned)wgs), dim3(256), 0, st, delta, act, n, a1, a2);
+    hipLaunchKernelGGL(std_finish_kernel, dim3(1), dim3(256), 0, st, a1, a2, b1, b2, wgs, n, s, step_out);
+    return hipGetLastError();
+}
 
 DitherKeys make_dither_keys(uint64_t seed)
 {
@@ -327,15 +477,33 @@ hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s, StatsJob *defer)
     const int64_t max_blocks = use_atomics ? 256 : kNsdMaxBlocks;
     if (blocks > max_blocks) blocks = max_blocks;
     if (blocks < 1) blocks = 1;
-    const bool vec = (a.cols % 4 == 0) && ((uintptr_t)a.delta % 16 == 0) && ((uintptr_t)a.codes % 4 == 0);
+    const bool vec_d = (a.cols % 4 == 0) && ((uintptr_t)a.delta % 16 == 0) && ((uintptr_t)a.codes % 4 == 0);
     const int64_t jump = (blocks * 4 - 1) * run + 1;        // tiles from the last tile of a run to the next run
     a.wave_stride_rows = jump / a.tiles_per_row;
     a.wave_stride_segs = jump % a.tiles_per_row;
     const dim3 grid((unsigned)blocks), block(256);
-    if (vec && a.bitmap)       hipLaunchKernelGGL((nsd_kernel<true, true>), grid, block, 0, s, a);
-    else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false>), grid, block, 0, s, a);
-    else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true>), grid, block, 0, s, a);
-    else                       hipLaunchKernelGGL((nsd_kernel<false, false>), grid, block, 0, s, a);
+    const bool ex = a.act || a.step_dev || a.bias_sums;
+    if (a.bias_sums) {
+        const int64_t zb = (a.bias_len + 255) / 256;
+        hipLaunchKernelGGL(zero_i64_kernel, dim3((unsigned)(zb < 1024 ? zb : 1024)), dim3(256), 0, s, a.bias_sums, a.bias_len);
+    }
+    const bool vec = vec_d && (!a.act || ((uintptr_t)a.act % 16 == 0));
+    if (!ex) {
+        if (vec && a.bitmap)       hipLaunchKernelGGL((nsd_kernel<true, true, false>), grid, block, 0, s, a);
+        else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false, false>), grid, block, 0, s, a);
+        else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true, false>), grid, block, 0, s, a);
+        else                       hipLaunchKernelGGL((nsd_kernel<false, false, false>), grid, block, 0, s, a);
+    } else {
+        if (vec && a.bitmap)       hipLaunchKernelGGL((nsd_kernel<true, true, true>), grid, block, 0, s, a);
+        else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false, true>), grid, block, 0, s, a);
+        else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true, true>), grid, block, 0, s, a);
+        else                       hipLaunchKernelGGL((nsd_kernel<false, false, true>), grid, block, 0, s, a);
+    }
+    if (a.bias_sums && a.bias_grad) {
+        const int64_t zb = (a.bias_len + 255) / 256;
+        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)(zb < 1024 ? zb : 1024)), dim3(256), 0, s,
+                           (const int64_t *)a.bias_sums, a.bias_len, a.step, a.step_dev, a.bias_grad);
+    }
     if (a.partials) {
         const StatsJob j{(const u32x4 *)a.partials, (int)blocks, a.stats};
         if (defer) *defer = j;

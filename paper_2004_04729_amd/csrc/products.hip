@@ -31,7 +31,7 @@ Split choose_split(int64_t tiles, int64_t K, int granule)
 template <int MODE> constexpr int k_step() { return NCHUNK * ModeTraits<MODE>::KCH; }
 
 template <int MODE, class AL, class BL, class OM>
-hipError_t run_gemm(const AL &al, const BL &bl, const OM &om, int M, int N, int K, int granule, float scale,
+hipError_t run_gemm(const AL &al, const BL &bl, const OM &om, int M, int N, int K, int granule, Scale scale,
                     typename ModeTraits<MODE>::Acc *out, void *scratch, size_t scratch_bytes, hipStream_t s)
 {
     using Acc = typename ModeTraits<MODE>::Acc;
@@ -296,7 +296,7 @@ bool fc_fast_ok(bool a_kfast, const int8_t *A, int64_t lda, const float *B, int6
 }
 
 FcProblem fc_problem(bool a_kfast, const int8_t *A, int64_t lda, const float *B, int64_t ldb, int M, int N, int K,
-                     float scale, float *out, const FcPlan &pl, char *&scratch)
+                     Scale scale, float *out, const FcPlan &pl, char *&scratch)
 {
     FcProblem p;
     p.A = A; p.lda = lda; p.B = B; p.ldb = ldb; p.out = out; p.ldc = N;
@@ -382,8 +382,8 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             fc2_plans(B, in, out, dx_fast, dw_fast, pdx, pdw);
             if (!dx_fast) { pdx.n_split = 1; pdx.partial_bytes = 0; }
             if (!dw_fast) { pdw.n_split = 1; pdw.partial_bytes = 0; }
-            pa.prob[0] = fc_problem(true, a.codes, a.out, a.W, a.in, B, in, out, a.step, a.dX, pdx, scratch);
-            pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, a.step, (float *)a.dW, pdw, scratch);
+            pa.prob[0] = fc_problem(true, a.codes, a.out, a.W, a.in, B, in, out, Scale{a.step, a.step_dev}, a.dX, pdx, scratch);
+            pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, Scale{a.step, a.step_dev}, (float *)a.dW, pdw, scratch);
             if (!dx_fast) pa.prob[0].n_items = 0;
             if (!dw_fast) pa.prob[1].n_items = 0;
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
@@ -406,8 +406,8 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             FcPairArgs pa;
             const FcPlan none = {0, 0, 1, FC_KT, 0, 0};
             const FcPlan pdx = dx_fast ? fc_plan(B, in, out) : none, pdw = dw_fast ? fc_plan(out, in, B) : none;
-            pa.prob[0] = fc_problem(true, a.codes, a.out, a.W, a.in, B, in, out, a.step, a.dX, pdx, scratch);
-            pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, a.step, (float *)a.dW, pdw, scratch);
+            pa.prob[0] = fc_problem(true, a.codes, a.out, a.W, a.in, B, in, out, Scale{a.step, a.step_dev}, a.dX, pdx, scratch);
+            pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, Scale{a.step, a.step_dev}, (float *)a.dW, pdw, scratch);
             if (!dx_fast) pa.prob[0].n_items = 0;
             if (!dw_fast) pa.prob[1].n_items = 0;
             pa.stats = pending;                            // summed by the last workgroup of the launch
@@ -433,17 +433,17 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
         if (a.dX && !dx_fast) {
             MatrixLoader<MODE_BF16, true, true>   al{a.codes, a.out, B, out};
             MatrixLoader<MODE_BF16, false, false> bl{a.W, a.in, in, out};
-            e = run_gemm<MODE_BF16>(al, bl, om, B, in, out, k_step<MODE_BF16>(), a.step, a.dX, a.scratch, a.scratch_bytes, s);
+            e = run_gemm<MODE_BF16>(al, bl, om, B, in, out, k_step<MODE_BF16>(), Scale{a.step, a.step_dev}, a.dX, a.scratch, a.scratch_bytes, s);
             if (e != hipSuccess) return e;
         }
         if (a.dW && a.x_dtype == DBP_F32 && !dw_fast) {
             MatrixLoader<MODE_BF16, true, false>  al{a.codes, a.out, out, B};
             MatrixLoader<MODE_BF16, false, false> bl{(const float *)a.X, a.in, in, B};
-            e = run_gemm<MODE_BF16>(al, bl, om, out, in, B, k_step<MODE_BF16>(), a.step, (float *)a.dW, a.scratch, a.scratch_bytes, s);
+            e = run_gemm<MODE_BF16>(al, bl, om, out, in, B, k_step<MODE_BF16>(), Scale{a.step, a.step_dev}, (float *)a.dW, a.scratch, a.scratch_bytes, s);
         } else if (a.dW && a.x_dtype != DBP_F32) {
             MatrixLoader<MODE_I8, true, false>  al{a.codes, a.out, out, B};
             MatrixLoader<MODE_I8, false, false> bl{(const int8_t *)a.X, a.in, in, B};
-            e = run_gemm<MODE_I8>(al, bl, om, out, in, B, k_step<MODE_I8>(), 1.0f, (int32_t *)a.dW, a.scratch, a.scratch_bytes, s);
+            e = run_gemm<MODE_I8>(al, bl, om, out, in, B, k_step<MODE_I8>(), Scale{1.0f, nullptr}, (int32_t *)a.dW, a.scratch, a.scratch_bytes, s);
         }
         return e;
     }
@@ -452,17 +452,17 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
     if (a.dX) {
         MatrixLoader<MODE_F32, false, true>  al{(const float *)a.dense, a.out, B, out};
         MatrixLoader<MODE_F32, false, false> bl{a.W, a.in, in, out};
-        e = run_gemm<MODE_F32>(al, bl, om, B, in, out, k_step<MODE_F32>(), 1.0f, a.dX, a.scratch, a.scratch_bytes, s);
+        e = run_gemm<MODE_F32>(al, bl, om, B, in, out, k_step<MODE_F32>(), Scale{1.0f, nullptr}, a.dX, a.scratch, a.scratch_bytes, s);
         if (e != hipSuccess) return e;
     }
     if (a.dW && a.x_dtype == DBP_F32) {
         MatrixLoader<MODE_F32, false, false> al{(const float *)a.dense, a.out, out, B};
         MatrixLoader<MODE_F32, false, false> bl{(const float *)a.X, a.in, in, B};
-        e = run_gemm<MODE_F32>(al, bl, om, out, in, B, k_step<MODE_F32>(), 1.0f, (float *)a.dW, a.scratch, a.scratch_bytes, s);
+        e = run_gemm<MODE_F32>(al, bl, om, out, in, B, k_step<MODE_F32>(), Scale{1.0f, nullptr}, (float *)a.dW, a.scratch, a.scratch_bytes, s);
     } else if (a.dW) {
         MatrixLoader<MODE_I8, false, false> al{(const int8_t *)a.dense, a.out, out, B};
         MatrixLoader<MODE_I8, false, false> bl{(const int8_t *)a.X, a.in, in, B};
-        e = run_gemm<MODE_I8>(al, bl, om, out, in, B, k_step<MODE_I8>(), 1.0f, (int32_t *)a.dW, a.scratch, a.scratch_bytes, s);
+        e = run_gemm<MODE_I8>(al, bl, om, out, in, B, k_step<MODE_I8>(), Scale{1.0f, nullptr}, (int32_t *)a.dW, a.scratch, a.scratch_bytes, s);
     }
     return e;
 }
@@ -471,7 +471,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
 // Convolution (stride 1).
 // ------------------------------------------------------------------------------------------------
 template <int MODE_G>
-static hipError_t conv_dx(const ConvArgs &a, const void *grad, float scale, hipStream_t s)
+static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipStream_t s)
 {
     // MODE_G: MODE_BF16 (codes) or MODE_F32 (dense).  Weights are fp32 in every mode.
     if constexpr (MODE_G == MODE_BF16) {
@@ -505,7 +505,7 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, float scale, hipS
 }
 
 template <int MODE>
-static hipError_t conv_dw(const ConvArgs &a, const void *grad, float scale, hipStream_t s)
+static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipStream_t s)
 {
     using Acc = typename ModeTraits<MODE>::Acc;
     const size_t rb = relayout_bytes(a.K, a.C, a.R, a.S);
@@ -531,12 +531,12 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s)
 {
     hipError_t e = hipSuccess;
     if (a.codes) {
-        if (a.dX) { e = conv_dx<MODE_BF16>(a, a.codes, a.step, s); if (e != hipSuccess) return e; }
-        if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_BF16>(a, a.codes, a.step, s) : conv_dw<MODE_I8>(a, a.codes, 1.0f, s);
+        if (a.dX) { e = conv_dx<MODE_BF16>(a, a.codes, Scale{a.step, a.step_dev}, s); if (e != hipSuccess) return e; }
+        if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_BF16>(a, a.codes, Scale{a.step, a.step_dev}, s) : conv_dw<MODE_I8>(a, a.codes, Scale{1.0f, nullptr}, s);
         return e;
     }
-    if (a.dX) { e = conv_dx<MODE_F32>(a, a.dense, 1.0f, s); if (e != hipSuccess) return e; }
-    if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_F32>(a, a.dense, 1.0f, s) : conv_dw<MODE_I8>(a, a.dense, 1.0f, s);
+    if (a.dX) { e = conv_dx<MODE_F32>(a, a.dense, Scale{1.0f, nullptr}, s); if (e != hipSuccess) return e; }
+    if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_F32>(a, a.dense, Scale{1.0f, nullptr}, s) : conv_dw<MODE_I8>(a, a.dense, Scale{1.0f, nullptr}, s);
     return e;
 }
 

@@ -118,3 +118,39 @@ def test_conv_argument_errors():
     g = dbp.lib().dense_conv2d_backward
     assert g(FAKE, FAKE, FAKE, 0, 2, 3, 8, 8, 4, 3, 3, 2, 1, FAKE, FAKE, FAKE, big, None) == UNSUPPORTED
     assert g(FAKE, FAKE, None, 0, 2, 3, 8, 8, 4, 3, 3, 1, 1, FAKE, FAKE, FAKE, big, None) == NULL
+
+
+def test_algorithm1_entry_points_reject_bad_arguments():
+    assert dbp.step_size_workspace_bytes(0) == 0 and dbp.step_size_workspace_bytes(1 << 20) >= 2 * 256 * 8
+    ws = dbp.step_size_workspace_bytes(4096)
+    raw = dbp.lib()
+    assert raw.dbp_step_size(None, None, 16, 4.0, FAKE, FAKE, ws, None) == NULL
+    assert raw.dbp_step_size(FAKE, None, 16, 4.0, None, FAKE, ws, None) == NULL
+    assert raw.dbp_step_size(FAKE, None, 0, 4.0, FAKE, FAKE, ws, None) == SHAPE
+    for bad in (0.0, -2.0, float("nan"), float("inf")):
+        assert raw.dbp_step_size(FAKE, None, 16, bad, FAKE, FAKE, ws, None) == STEP
+    assert raw.dbp_step_size(FAKE, None, 16, 4.0, FAKE, None, ws, None) == WORKSPACE
+    assert raw.dbp_step_size(FAKE, None, 16, 4.0, FAKE, FAKE, 8, None) == WORKSPACE
+    # extras of the quantiser
+    q = dbp.nsd_quantize_ex
+    assert _code(q, FAKE, 4, 8, 1.0, 1, 0, FAKE, bias_grad=FAKE) == NULL                          # gradient without sums
+    assert _code(q, FAKE, 4, 8, 1.0, 1, 0, FAKE, bias_sums=FAKE, bias_len=7) == SHAPE             # per column: len == cols
+    assert _code(q, FAKE, 4, 8, 1.0, 1, 0, FAKE, bias_sums=FAKE, bias_mode=dbp.BIAS_PER_ROW_GROUP, bias_len=3) == SHAPE
+    assert _code(q, FAKE, 4, 8, 1.0, 1, 0, FAKE, bias_sums=FAKE, bias_mode=5, bias_len=8) == UNSUPPORTED
+    assert _code(q, FAKE, 4, 8, 0.0, 1, 0, FAKE) == STEP                                          # host step still checked ...
+    assert _code(q, FAKE, 0, 8, 0.0, 1, 0, FAKE, step_dev=FAKE) == SHAPE                          # ... unless a device step is given
+    # whole-layer calls
+    wl = dbp.linear_layer_workspace_bytes(8, 16, 12)
+    assert wl > dbp.linear_workspace_bytes(8, 16, 12)
+    f = dbp.dithered_linear_layer_backward
+    assert _code(f, None, None, FAKE, FAKE, dbp.F32, 8, 16, 12, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == NULL
+    assert _code(f, FAKE, None, FAKE, FAKE, dbp.F32, 8, 16, 12, 4.0, 1, 0, None, None, None, None, None, None) == NULL
+    assert _code(f, FAKE, None, FAKE, FAKE, dbp.F32, 8, 0, 12, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == SHAPE
+    assert _code(f, FAKE, None, FAKE, FAKE, dbp.F32, 8, 16, 12, 0.0, 1, 0, None, FAKE, FAKE, None, None, None) == STEP
+    assert _code(f, FAKE, None, FAKE, FAKE, dbp.F32, 8, 16, 12, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == WORKSPACE
+    wc = dbp.conv2d_layer_workspace_bytes(2, 3, 8, 8, 4, 3, 3, 1, 1)
+    assert wc > dbp.conv2d_workspace_bytes(2, 3, 8, 8, 4, 3, 3, 1, 1)
+    g = dbp.dithered_conv2d_layer_backward
+    assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 2, 1, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == UNSUPPORTED
+    assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 1, 1, -1.0, 1, 0, None, FAKE, FAKE, None, None, None) == STEP
+    assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 1, 1, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == WORKSPACE
