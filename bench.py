@@ -193,6 +193,27 @@ def main():
             torch.matmul(b["d"], b["W"], out=b["dX"])
             torch.matmul(b["d"].t(), b["X"], out=b["dW"])
 
+    # the same chain through the whole-layer entry point (Algorithm 1 on the device: + std, + mask, + bias gradient)
+    lsets = []
+    for bufs in sets:
+        row = []
+        for b in bufs:
+            Bq, iq, oq = b["p"].dims
+            row.append(dict(ws=torch.empty(dbp.linear_layer_workspace_bytes(Bq, iq, oq), dtype=torch.uint8, device=dev),
+                            act=torch.empty((Bq, oq), dtype=torch.float32, device=dev).uniform_(-0.2, 1.0),
+                            db=torch.empty(oq, dtype=torch.float32, device=dev), pair=torch.zeros(2, dtype=torch.float32, device=dev)))
+        lsets.append(row)
+
+    def layer_step(i):
+        for b, l in zip(sets[i % NSETS], lsets[i % NSETS]):
+            p = b["p"]
+            Bq, iq, oq = p.dims
+            dbp.dithered_linear_layer_backward(b["d"], l["act"], b["W"], b["X"], dbp.F32, Bq, iq, oq, args.c, p.seed, 0,
+                                               b["codes"], b["dX"], b["dW"], l["db"], l["pair"], l["ws"], b["stats"],
+                                               dbp.PATH_AUTO, stream)
+
+    t_layer = timed(layer_step, max(10, args.steps // 2))
+    del lsets
     t_dense = timed(dense_step, max(5, args.steps // 4))
     torch.backends.cuda.matmul.allow_tf32 = False
     t_torch = timed(torch_step, max(5, args.steps // 4))
@@ -218,7 +239,22 @@ def main():
            "frac_of_8TBps": nsd_bytes / t_nsd / 1e9 / PEAK_HBM_GBS, "bytes_per_element": nsd_bytes / n_big}
     t_nsd_codes = timed(lambda i: dbp.nsd_quantize(big, rows_b, cols_b, step_big, 1, 0, codes_big, None, None, stream), 10)
     nsd["codes_only_GBps"] = n_big * 5.0 / t_nsd_codes / 1e9
-    del big, codes_big, fmt_big
+    # Algorithm 1 on the device and the steps around the quantiser, same tensor: step size (one read of delta),
+    # then the quantiser with the rectifier mask on load, the device step and the bias code sums
+    pair = torch.zeros(2, dtype=torch.float32, device=dev)
+    ws_std = torch.empty(dbp.step_size_workspace_bytes(n_big), dtype=torch.uint8, device=dev)
+    t_std = timed(lambda i: dbp.step_size(big, None, n_big, 8.0, pair, ws_std, stream), 10)
+    act_big = torch.empty(n_big, dtype=torch.float32, device=dev).uniform_(-1, 1, generator=g)
+    sums_big = torch.zeros(cols_b, dtype=torch.int64, device=dev)
+    grad_big = torch.zeros(cols_b, dtype=torch.float32, device=dev)
+    t_ex = timed(lambda i: dbp.nsd_quantize_ex(big, rows_b, cols_b, step_big, 1, 0, codes_big, None, st_big, act=act_big,
+                                               step_dev=pair, bias_sums=sums_big, bias_grad=grad_big,
+                                               bias_mode=dbp.BIAS_PER_COLUMN, bias_len=cols_b, stream=stream), 10)
+    nsd["step_size_ms"] = t_std * 1e3
+    nsd["step_size_GBps"] = n_big * 4.0 / t_std / 1e9
+    nsd["masked_bias_nsd_ms"] = t_ex * 1e3
+    nsd["masked_bias_nsd_GBps"] = n_big * 9.0 / t_ex / 1e9            # delta + activation read, codes written
+    del big, codes_big, fmt_big, act_big
 
     extra = {}
     if args.all:
@@ -252,6 +288,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "host_wall_ms_per_step": wall * 1e3,
+        "whole_layer_entry_ms_per_step": t_layer * 1e3,
         "vs_dense": {"same_library_fp32_mfma_ms": t_dense * 1e3, "torch_matmul_fp32_ms": t_torch * 1e3,
                      "speedup_vs_same_library": t_dense / t_step, "speedup_vs_torch": t_torch / t_step},
         "kernels_L2_us": {"nsd_1M_elements": t_nsd_small * 1e6, "dX_mfma": t_dx * 1e6, "dW_mfma": t_dw * 1e6,

@@ -232,6 +232,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     Fc2Cursor c;
     fc2_open(a, 0, c);
+    const float scale0 = a.prob[0].scale.get(), scale1 = a.prob[1].scale.get();   // resolved once (host value or device Delta)
 
     __syncthreads();
     for (int g = 0; g < G; ++g) {
@@ -270,7 +271,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
                 // block (i,j) covers row positions 64*wave + 32*i.. and column positions 32*j.. (column 4*lcol + j);
                 // D[ii][jj] of a block sits in lane (jj, ii%8/4), register 4*(ii/8)+ii%4.
                 const int col = c.tile_n + 4 * lcol;
-                const float sc = p.scale.get();
+                const float sc = c.which ? scale1 : scale0;
                 if (col < p.N) {
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
