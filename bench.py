@@ -247,7 +247,7 @@ def main():
     act_big = torch.empty(n_big, dtype=torch.float32, device=dev).uniform_(-1, 1, generator=g)
     sums_big = torch.zeros(cols_b, dtype=torch.int64, device=dev)
     grad_big = torch.zeros(cols_b, dtype=torch.float32, device=dev)
-    t_ex = timed(lambda i: dbp.nsd_quantize_ex(big, rows_b, cols_b, step_big, 1, 0, codes_big, None, st_big, act=act_big,
+    t_ex = timed(lambda i: dbp.nsd_quantize_ex(big, rows_b, cols_b, step_big, 1, 0, codes_big, None, None, act=act_big,
                                                step_dev=pair, bias_sums=sums_big, bias_grad=grad_big,
                                                bias_mode=dbp.BIAS_PER_COLUMN, bias_len=cols_b, stream=stream), 10)
     nsd["step_size_ms"] = t_std * 1e3

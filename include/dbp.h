@@ -208,7 +208,7 @@ dbp_status dbp_conv2d_products(const int8_t *codes, const void *format, float st
  * ---------------------------------------------------------------------------------------------------------
  * Algorithm 1 on the device, and the two steps that surround the quantiser in a layer's backward pass.
  * ---------------------------------------------------------------------------------------------------------
- * Step size (Algorithm 1, lines 2-3):  sigma = std(delta_z),  Delta = s * sigma.
+ * Step size (Algorithm 1, the two assignments before the quantiser):  sigma = std(delta_z),  Delta = s * sigma.
  *   Readings: population standard deviation (divide by n) over ALL elements of the tensor, from
  *   S1 = sum x and S2 = sum x*x accumulated in fp64; because Delta decides integer codes the order of the
  *   sums is part of the definition: a radix-16 tree (groups of 16 consecutive values summed left to right,

@@ -144,7 +144,7 @@ void dbp_oracle_nsd(const float *delta, int64_t n, float step, uint64_t seed,
 }
 
 /* ------------------------------------------------------------------------------------
- * Step size of a layer (Algorithm 1, first two lines):  sigma = std(delta_z),
+ * Step size of a layer (Algorithm 1, the two assignments before the quantiser):  sigma = std(delta_z),
  * Delta = s * sigma.
  *
  * Readings (the paper says only "std"): the population standard deviation (divide by n)

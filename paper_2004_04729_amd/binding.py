@@ -188,7 +188,7 @@ def step_size_workspace_bytes(n: int) -> int:
 
 
 def step_size(delta, act, n, s, step_out, workspace, stream=0):
-    """Algorithm 1, lines 2-3, on the device: step_out[0:2] = {s*std(delta_z), its reciprocal}."""
+    """The step-size computation of Algorithm 1 on the device: step_out[0:2] = {s*std(delta_z), its reciprocal}."""
     _check(lib().dbp_step_size(_ptr(delta), _ptr(act), n, s, _ptr(step_out), _ptr(workspace), _nbytes(workspace), stream))
 
 

@@ -56,7 +56,7 @@ Carve carve(int64_t rows, int64_t cols, size_t scratch_bytes)
 // (its statistics records are used either way).
 dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
                    int8_t *codes, char *fmt_base, const dbp_format_layout *L, dbp_stats *stats, hipStream_t s,
-                   bool want_format = true, StatsJob *defer = nullptr, const dbp_nsd_extras *ex = nullptr)
+                   bool want_format = true, StatsJob *defer = nullptr, const dbp_nsd_extras *ex = nullptr, bool bias_zeroed = false)
 {
     NsdArgs a;
     a.delta = delta; a.codes = codes; a.stats = stats;
@@ -68,6 +68,7 @@ dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, u
     a.rows = rows; a.cols = cols; a.tiles_per_row = L->tiles_per_row; a.n_tiles = L->n_tiles;
     a.inv_step = 1.0f / step;
     a.act = nullptr; a.step_dev = nullptr; a.bias_sums = nullptr; a.bias_grad = nullptr; a.bias_mode = 0; a.bias_len = 0; a.step = step;
+    a.bias_zeroed = bias_zeroed ? 1 : 0;
     if (ex) {
         a.act = ex->act; a.step_dev = ex->step_dev; a.bias_sums = ex->bias_sums; a.bias_grad = ex->bias_grad;
         a.bias_mode = ex->bias_mode; a.bias_len = ex->bias_len;
@@ -181,7 +182,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    a.stats_job = StatsJob{nullptr, 0, nullptr};
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -247,7 +248,7 @@ dbp_status dbp_linear_products(const int8_t *codes, const void *format, float st
                                void *workspace, size_t workspace_bytes, dbp_path path, void *stream)
 {
     return linear_products(codes, format, step, W, X, x_dtype, B, in, out, dX, dW, workspace, workspace_bytes, path,
-                           stream, StatsJob{nullptr, 0, nullptr});
+                           stream, StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr});
 }
 
 dbp_status dithered_linear_backward(const float *delta, const float *W, const void *X, dbp_dtype x_dtype,
@@ -326,7 +327,7 @@ dbp_status dense_linear_backward(const void *delta, const float *W, const void *
     LinearArgs a;
     a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    a.stats_job = StatsJob{nullptr, 0, nullptr};
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -349,7 +350,7 @@ dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *
     a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    a.stats_job = StatsJob{nullptr, 0, nullptr};
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -425,13 +426,14 @@ dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act
     char *ws = (char *)workspace;
     hipStream_t hs = (hipStream_t)stream;
     float *pair = step_out ? step_out : (float *)(ws + lc.step_pair);
-    if (launch_step_size(delta_a, act, B * out, s, pair, ws + lc.step_scratch, hs) != hipSuccess) return DBP_ERR_DEVICE;
+    if (launch_step_size(delta_a, act, B * out, s, pair, ws + lc.step_scratch, hs,
+                         db ? (int64_t *)(ws + lc.bias_sums) : nullptr, db ? out : 0) != hipSuccess) return DBP_ERR_DEVICE;
     dbp_nsd_extras ex;
     ex.act = act; ex.step_dev = pair; ex.bias_sums = db ? (int64_t *)(ws + lc.bias_sums) : nullptr; ex.bias_grad = db;
     ex.bias_mode = DBP_BIAS_PER_COLUMN; ex.bias_len = out;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     StatsJob job;
-    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex);
+    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex, true);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     return linear_products(k, ws, 1.0f, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset,
@@ -461,12 +463,13 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     char *ws = (char *)workspace;
     hipStream_t hs = (hipStream_t)stream;
     float *pair = step_out ? step_out : (float *)(ws + lc.step_pair);
-    if (launch_step_size(delta_a, act, N * K * P * Q, s, pair, ws + lc.step_scratch, hs) != hipSuccess) return DBP_ERR_DEVICE;
+    if (launch_step_size(delta_a, act, N * K * P * Q, s, pair, ws + lc.step_scratch, hs,
+                         db ? (int64_t *)(ws + lc.bias_sums) : nullptr, db ? K : 0) != hipSuccess) return DBP_ERR_DEVICE;
     dbp_nsd_extras ex;
     ex.act = act; ex.step_dev = pair; ex.bias_sums = db ? (int64_t *)(ws + lc.bias_sums) : nullptr; ex.bias_grad = db;
     ex.bias_mode = DBP_BIAS_PER_ROW_GROUP; ex.bias_len = K;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, false, nullptr, &ex);
+    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, false, nullptr, &ex, true);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return DBP_OK;
     return conv2d_products(k, ws, 1.0f, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,

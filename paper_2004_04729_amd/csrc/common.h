@@ -48,11 +48,16 @@ struct NsdArgs {
     int          bias_mode;
     int64_t      bias_len;
     float        step;        // host Delta (bias_grad without step_dev)
+    int          bias_zeroed; // bias_sums were cleared by an earlier kernel of the stream (launch_step_size)
     int          run;                                  // consecutive tiles per wavefront run (set by launch_nsd)
     int64_t      wave_stride_rows, wave_stride_segs;   // grid stride in tiles = rows*tiles_per_row + segs (set by launch_nsd)
 };
 // Pending reduction of the per-workgroup statistics records into one dbp_stats (n == 0: nothing pending).
-struct StatsJob { const u32x4 *partials; int n; dbp_stats *out; };
+struct StatsJob {
+    const u32x4 *partials; int n; dbp_stats *out;                  // statistics records -> dbp_stats (n == 0: none)
+    const int64_t *bias_sums; int64_t bias_len; float *bias_grad;   // code sums -> fp32 bias gradient (bias_len == 0: none)
+    float step; const float *step_dev;
+};
 // Launches the quantiser.  With `defer` non-null and statistics kept in records, the final sum is not
 // launched: *defer describes it, and the caller either folds it into a later kernel of the same stream
 // or calls launch_stats_job.
@@ -63,7 +68,8 @@ hipError_t launch_stats_job(const StatsJob &j, hipStream_t s);
 // when act is given (both 0 if the standard
 // deviation is 0 or not finite).  scratch: step_size_scratch_bytes(n).
 size_t     step_size_scratch_bytes(int64_t n);
-hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st);
+hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st,
+                            int64_t *zero = nullptr, int64_t zero_len = 0);   // also clears zero[0..zero_len)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

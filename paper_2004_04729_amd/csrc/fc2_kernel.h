@@ -98,6 +98,13 @@ __device__ __forceinline__ void fc2_sum_stats(const StatsJob &j, int lane)
     }
 }
 
+// Bias gradient of the layer from the quantiser's code sums: one fp64 product rounded to fp32 per element.
+__device__ __forceinline__ void fc2_bias_grad(const StatsJob &j, int lane)
+{
+    const double d = j.step_dev ? (double)j.step_dev[0] : (double)j.step;
+    for (int64_t i = lane; i < j.bias_len; i += 64) j.bias_grad[i] = (float)(d * (double)j.bias_sums[i]);
+}
+
 // Matrix row of element ii of row block i of multiplier wavefront `wave`: row positions are rows
 // (a_kfast) or, inside each 128-row half, the interleave 4*nq + j -> position 32*j + nq of the staging.
 __device__ __forceinline__ int fc2_row(int a_kfast, int tile_m, int wave, int i, int ii)
@@ -116,8 +123,12 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
     if (wave >= 4) {
         // ================================ stagers ================================
         const int tid = threadIdx.x & 255;
-        // the last workgroup has the fewest items: one of its stager wavefronts finishes the statistics
-        if (a.stats.n > 0 && blockIdx.x == gridDim.x - 1 && wave == 7) fc2_sum_stats(a.stats, lane);
+        // the last workgroup has the fewest items: one of its stager wavefronts finishes the quantiser's
+        // statistics and the bias gradient
+        if (blockIdx.x == gridDim.x - 1 && wave == 7) {
+            if (a.stats.n > 0) fc2_sum_stats(a.stats, lane);
+            if (a.stats.bias_len > 0) fc2_bias_grad(a.stats, lane);
+        }
         const int nq = tid & 31, kq = tid >> 5;
         Fc2Cursor c;
         bool open = fc2_open(a, 0, c);

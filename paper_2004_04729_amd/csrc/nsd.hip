@@ -342,9 +342,12 @@ __global__ void bias_grad_kernel(const int64_t *sums, int64_t n, float step, con
 // (a thread sums its 16 consecutive elements; lane 16g adds the 16 thread sums of its lane group in order; one
 // thread adds the workgroup's 16 lane-group sums in order), the second kernel finishes the tree with one
 // workgroup and writes {Delta, 1/Delta}.
-__global__ __launch_bounds__(256) void std_tree_kernel(const float *delta, const float *act, int64_t n, double *out1, double *out2)
+__global__ __launch_bounds__(256) void std_tree_kernel(const float *delta, const float *act, int64_t n, double *out1, double *out2,
+                                                       int64_t *zero, int64_t zero_len)
 {
     const int tid = threadIdx.x, lane = tid & 63;
+    // by the way: clear the bias code sums that the quantiser (the next kernel of the stream) adds into
+    for (int64_t i = (int64_t)blockIdx.x * 256 + tid; i < zero_len; i += (int64_t)gridDim.x * 256) zero[i] = 0;
     const int64_t first = ((int64_t)blockIdx.x * 256 + tid) * 16;     // this thread's 16 consecutive elements
     const int have = (int)max((int64_t)0, min((int64_t)16, n - first));
     float v[16];
@@ -435,12 +438,13 @@ size_t step_size_scratch_bytes(int64_t n)
     return align_up((size_t)(2 * wgs + 2 * second) * sizeof(double), 256);
 }
 
-hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st)
+hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st,
+                            int64_t *zero, int64_t zero_len)
 {
     const int64_t wgs = (n + 4095) / 4096 > 0 ? (n + 4095) / 4096 : 1;
     const int64_t second = (wgs + 15) / 16;
     double *a1 = (double *)scratch, *a2 = a1 + wgs, *b1 = a2 + wgs, *b2 = b1 + second;
-    hipLaunchKernelGGL(std_tree_kernel, dim3((unsigned)wgs), dim3(256), 0, st, delta, act, n, a1, a2);
+    hipLaunchKernelGGL(std_tree_kernel, dim3((unsigned)wgs), dim3(256), 0, st, delta, act, n, a1, a2, zero, zero_len);
     hipLaunchKernelGGL(std_finish_kernel, dim3(1), dim3(256), 0, st, a1, a2, b1, b2, wgs, n, s, step_out);
     return hipGetLastError();
 }
@@ -455,14 +459,18 @@ DitherKeys make_dither_keys(uint64_t seed)
 
 hipError_t launch_stats_job(const StatsJob &j, hipStream_t s)
 {
-    if (j.n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(finalize_stats_kernel, dim3(1), dim3(1024), 0, s, j.partials, j.n, j.out);
+    if (j.n > 0) hipLaunchKernelGGL(finalize_stats_kernel, dim3(1), dim3(1024), 0, s, j.partials, j.n, j.out);
+    if (j.bias_len > 0) {
+        const int64_t zb = (j.bias_len + 255) / 256;
+        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)(zb < 1024 ? zb : 1024)), dim3(256), 0, s, j.bias_sums, j.bias_len,
+                           j.step, j.step_dev, j.bias_grad);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s, StatsJob *defer)
 {
-    if (defer) *defer = StatsJob{nullptr, 0, nullptr};
+    if (defer) *defer = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     NsdArgs a = a_in;
     if (!a.stats) a.partials = nullptr;
     const bool use_atomics = a.stats && !a.partials;
@@ -483,7 +491,7 @@ hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s, StatsJob *defer)
     a.wave_stride_segs = jump % a.tiles_per_row;
     const dim3 grid((unsigned)blocks), block(256);
     const bool ex = a.act || a.step_dev || a.bias_sums;
-    if (a.bias_sums) {
+    if (a.bias_sums && !a.bias_zeroed) {
         const int64_t zb = (a.bias_len + 255) / 256;
         hipLaunchKernelGGL(zero_i64_kernel, dim3((unsigned)(zb < 1024 ? zb : 1024)), dim3(256), 0, s, a.bias_sums, a.bias_len);
     }
@@ -499,16 +507,14 @@ hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s, StatsJob *defer)
         else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true, true>), grid, block, 0, s, a);
         else                       hipLaunchKernelGGL((nsd_kernel<false, false, true>), grid, block, 0, s, a);
     }
+    StatsJob later{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     if (a.bias_sums && a.bias_grad) {
-        const int64_t zb = (a.bias_len + 255) / 256;
-        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)(zb < 1024 ? zb : 1024)), dim3(256), 0, s,
-                           (const int64_t *)a.bias_sums, a.bias_len, a.step, a.step_dev, a.bias_grad);
+        later.bias_sums = a.bias_sums; later.bias_len = a.bias_len; later.bias_grad = a.bias_grad;
+        later.step = a.step; later.step_dev = a.step_dev;
     }
-    if (a.partials) {
-        const StatsJob j{(const u32x4 *)a.partials, (int)blocks, a.stats};
-        if (defer) *defer = j;
-        else return launch_stats_job(j, s);
-    }
+    if (a.partials) { later.partials = (const u32x4 *)a.partials; later.n = (int)blocks; later.out = a.stats; }
+    if (defer) *defer = later;
+    else return launch_stats_job(later, s);
     return hipGetLastError();
 }
 

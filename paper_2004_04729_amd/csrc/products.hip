@@ -387,8 +387,8 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             if (!dx_fast) pa.prob[0].n_items = 0;
             if (!dw_fast) pa.prob[1].n_items = 0;
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
-            pa.stats = pending;                            // summed by a stager wavefront of the last workgroup
-            pending.n = 0;
+            pa.stats = pending;                            // finished by a stager wavefront of the last workgroup
+            pending.n = 0; pending.bias_len = 0;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
             const int grid = total < 256 ? total : 256;    // persistent: one workgroup per CU
             hipLaunchKernelGGL(fc2_pair_kernel, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
@@ -410,6 +410,13 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, Scale{a.step, a.step_dev}, (float *)a.dW, pdw, scratch);
             if (!dx_fast) pa.prob[0].n_items = 0;
             if (!dw_fast) pa.prob[1].n_items = 0;
+            if (pending.bias_len) {                        // this kernel folds the statistics only
+                StatsJob bias = pending;
+                bias.n = 0;
+                e = launch_stats_job(bias, s);
+                if (e != hipSuccess) return e;
+                pending.bias_len = 0;
+            }
             pa.stats = pending;                            // summed by the last workgroup of the launch
             pending.n = 0;
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
@@ -429,7 +436,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
                 if (e != hipSuccess) return e;
             }
         }
-        if (pending.n) { e = launch_stats_job(pending, s); if (e != hipSuccess) return e; }
+        if (pending.n || pending.bias_len) { e = launch_stats_job(pending, s); if (e != hipSuccess) return e; }
         if (a.dX && !dx_fast) {
             MatrixLoader<MODE_BF16, true, true>   al{a.codes, a.out, B, out};
             MatrixLoader<MODE_BF16, false, false> bl{a.W, a.in, in, out};
@@ -448,7 +455,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
         return e;
     }
     // dense baseline
-    if (pending.n) { e = launch_stats_job(pending, s); if (e != hipSuccess) return e; }
+    if (pending.n || pending.bias_len) { e = launch_stats_job(pending, s); if (e != hipSuccess) return e; }
     if (a.dX) {
         MatrixLoader<MODE_F32, false, true>  al{(const float *)a.dense, a.out, B, out};
         MatrixLoader<MODE_F32, false, false> bl{a.W, a.in, in, out};
