@@ -21,18 +21,26 @@
 namespace dbp {
 
 constexpr int FC2_TM = 256, FC2_TN = 128, FC2_KT = 32;
-constexpr int FC2_LDS_BYTES = 2 * (16 + 24) * 1024;
+constexpr int FC2_MAX_ITEMS = 128;                 // work items of one workgroup (the host checks)
+constexpr int FC2_LDS_BYTES = 2 * (16 + 24) * 1024 + FC2_MAX_ITEMS * 32;
 
 struct Fc2Stage {
     uint2 a[NCHUNK][FC2_TM][2];       // [chunk][row position][half]          16 KiB
     uint2 b[3][NCHUNK][FC2_TN][2];    // [plane][chunk][col position][half]   24 KiB
 };
-static_assert(sizeof(Fc2Stage) * 2 == FC2_LDS_BYTES, "two stages");
+// A decoded work item as the workgroup keeps it in LDS (after the two stages).
+struct Fc2Item { int which, tile, z, tile_m, tile_n, k0, k_end, pad; };
+static_assert(sizeof(Fc2Stage) * 2 + FC2_MAX_ITEMS * sizeof(Fc2Item) == FC2_LDS_BYTES, "two stages and the item table");
 
 // Position of a workgroup in its sequence of (item, K step) pairs; both roles walk the same sequence.
 struct Fc2Cursor {
     int t;                            // position in this workgroup's list of items
     int which, tile, z, tile_m, tile_n, k0, k_end;
+    // the item's problem, copied once per item (indexing the kernel arguments by `which` at every use costs a
+    // scalar load, and its latency, each time)
+    const int8_t *A; const float *B; float *out, *partial;
+    int64_t lda, ldb, ldc;
+    int M, N, K, n_split, a_kfast;
 };
 
 // The i-th work item of this workgroup.  Items are numbered with those of problem 0 first (the longer
@@ -40,42 +48,76 @@ struct Fc2Cursor {
 // workgroups (pass p gives workgroup w item p*G + w, the next pass p*G + G-1-w), which balances the number
 // of K steps; every workgroup then starts at a different place of its own list (rotation by w), so that
 // the tiles of the chip are not all finished, and stored, at the same moment.
-__device__ __forceinline__ bool fc2_open(const FcPairArgs &a, int i, Fc2Cursor &c)
+__device__ __forceinline__ int fc2_items_of_workgroup(const FcPairArgs &a)
 {
-    const int n0 = a.prob[0].n_items, total = n0 + a.prob[1].n_items;
+    const int total = a.prob[0].n_items + a.prob[1].n_items;
     const int G = gridDim.x, w = blockIdx.x;
     const int passes = (total + G - 1) / G;
     const int last = (passes - 1) * G + (((passes - 1) & 1) ? G - 1 - w : w);
-    const int mine = last < total ? passes : passes - 1;             // items of this workgroup
-    if (i >= mine) return false;
+    return last < total ? passes : passes - 1;
+}
+
+__device__ __forceinline__ Fc2Item fc2_decode(const FcPairArgs &a, int i, int mine)
+{
+    const int n0 = a.prob[0].n_items;
+    const int G = gridDim.x, w = blockIdx.x;
     const int ps = (i + w) % mine;
     const int t = ps * G + ((ps & 1) ? G - 1 - w : w);
+    Fc2Item c;
     c.which = t < n0 ? 0 : 1;
     const int item = t < n0 ? t : t - n0;
     const FcProblem &p = a.prob[c.which];
-    c.t = i;
     c.tile = item / p.n_split; c.z = item - c.tile * p.n_split;
+    // Workgroup w runs on XCD w % 8, and each XCD has an L2 of its own.  Where the counts divide evenly the items
+    // are renumbered so that one XCD keeps to one share of the re-read operand: the same reduction slice of
+    // the codes for a split product, the same column tiles of the dense operand otherwise.
+    if ((G & 7) == 0 && (n0 & 7) == 0 && (p.n_items & 7) == 0) {
+        const int x = ((t / G) & 1) ? 7 - (t & 7) : (t & 7), r = item >> 3;
+        const int tiles_n = p.n_items / (p.n_split * p.tiles_m);
+        if (p.n_split > 1 && (p.n_split & 7) == 0) {
+            const int ns8 = p.n_split >> 3;
+            c.tile = r / ns8; c.z = x * ns8 + (r - c.tile * ns8);
+        } else if (p.n_split == 1 && (tiles_n & 7) == 0) {
+            const int tn8 = tiles_n >> 3, tm = r / tn8;
+            c.tile = (x * tn8 + (r - tm * tn8)) * p.tiles_m + tm;
+        }
+    }
     c.tile_m = (c.tile % p.tiles_m) * FC2_TM;
     c.tile_n = (c.tile / p.tiles_m) * FC2_TN;
     c.k0 = c.z * p.k_per_split;
     c.k_end = min(p.K, c.k0 + p.k_per_split);
-    return true;
+    c.pad = 0;
+    return c;
 }
 
-// K steps of all items of this workgroup (the trip count of both roles).
-__device__ __forceinline__ int fc2_total_steps(const FcPairArgs &a)
+// Makes item i of the workgroup's table the cursor's item (false past the end).  The table is decoded once per
+// workgroup, by all threads in parallel: decoding in the K loop costs the roles, which are single wavefronts
+// per SIMD and bound by the number of instructions they issue, about as much as a whole step's loads.
+__device__ __forceinline__ bool fc2_open(const FcPairArgs &a, const Fc2Item *table, int mine, int i, Fc2Cursor &c)
 {
-    int g = 0;
-    Fc2Cursor c;
-    for (int i = 0; fc2_open(a, i, c); ++i) g += (c.k_end - c.k0 + FC2_KT - 1) / FC2_KT;
-    return g;
+    if (i >= mine) return false;
+    const int4 lo = *(const int4 *)&table[i], hi = *((const int4 *)&table[i] + 1);
+    c.t = i;
+    c.which = __builtin_amdgcn_readfirstlane(lo.x); c.tile = __builtin_amdgcn_readfirstlane(lo.y);
+    c.z = __builtin_amdgcn_readfirstlane(lo.z); c.tile_m = __builtin_amdgcn_readfirstlane(lo.w);
+    c.tile_n = __builtin_amdgcn_readfirstlane(hi.x); c.k0 = __builtin_amdgcn_readfirstlane(hi.y);
+    c.k_end = __builtin_amdgcn_readfirstlane(hi.z);
+    const FcProblem &p = a.prob[c.which];
+    c.A = p.A; c.B = p.B; c.out = p.out; c.partial = p.partial;
+    c.lda = p.lda; c.ldb = p.ldb; c.ldc = p.ldc;
+    c.M = p.M; c.N = p.N; c.K = p.K; c.n_split = p.n_split; c.a_kfast = p.a_kfast;
+    return true;
 }
 
 struct Fc2Raw {                       // one K step of one stager thread, as loaded
     f32x4 b[4];
     uint32_t a[8];
     int kfast, k_valid;               // operand layout of the item; reduction indices of the step that exist
+    int a_shift;                      // !kfast: dwords by which the loaded run of rows was moved back to stay inside the matrix
 };
+
+// 16 bytes from an address that is only known to be a multiple of 4 (one global_load_dwordx4)
+typedef uint32_t u32x4_dw __attribute__((ext_vector_type(4), aligned(4)));
 
 // Sum of the quantiser's statistics records by one wavefront (integers: any order gives the same result).
 __device__ __forceinline__ void fc2_sum_stats(const StatsJob &j, int lane)
@@ -117,8 +159,14 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 {
     extern __shared__ uint4 fc2_lds[];
     Fc2Stage *stages = (Fc2Stage *)fc2_lds;
+    Fc2Item *table = (Fc2Item *)(stages + 2);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int G = fc2_total_steps(a);
+    const int mine = fc2_items_of_workgroup(a);
+    for (int i = threadIdx.x; i < mine; i += 512) table[i] = fc2_decode(a, i, mine);
+    __syncthreads();
+    int steps = 0;                                    // K steps of all items (the trip count of both roles)
+    for (int i = 0; i < mine; ++i) steps += (table[i].k_end - table[i].k0 + FC2_KT - 1) / FC2_KT;
+    const int G = __builtin_amdgcn_readfirstlane(steps);
 
     if (wave >= 4) {
         // ================================ stagers ================================
@@ -131,75 +179,136 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
         }
         const int nq = tid & 31, kq = tid >> 5;
         Fc2Cursor c;
-        bool open = fc2_open(a, 0, c);
-
-        // Loads of the cursor's K step; then the cursor moves on (to the next item after an item's last
-        // step).  Straight-line: reduction indices past the end of the item are clamped to its last one here
-        // and zeroed when the step is committed (zero weights and zero codes add exactly 0).
-        auto issue = [&](Fc2Raw &r) {
-            if (!open) return;
-            const FcProblem &p = a.prob[c.which];
-            const int k0 = c.k0, k_last = c.k_end - 1;
-            r.kfast = p.a_kfast;
-            r.k_valid = c.k_end - k0;
-            const float *b_col = p.B + min(c.tile_n + 4 * nq, p.N - 4);
+        // Addresses: a base that is the same for all lanes and moves with the K step (scalar additions), plus a
+        // 32-bit lane offset that is fixed for the item (the matrices are smaller than 4 GiB here).  Rows and
+        // columns past the edge of a matrix are clamped once per item, inside the lane offsets.  A step always
+        // loads a full window of 32 reduction indices: the last window of an item whose length is not a
+        // multiple of 32 ends at the item's end and overlaps the window before it; the indices it repeats are
+        // zeroed when the step is committed (K >= 32, so the window never leaves the row or column).
+        const char *b_step = nullptr, *b_cur = nullptr;
+        const int8_t *a_step = nullptr, *a_cur = nullptr;
+        int64_t b_unit = 0, a_unit = 0;                   // bytes per reduction index
+        uint32_t boff[4] = {0, 0, 0, 0}, aoff[2] = {0, 0};
+        int a_shift = 0, kv_cur = 0;
+        auto open_item = [&](int i) {
+            if (!fc2_open(a, table, mine, i, c)) return false;
+            const uint32_t ldb4 = (uint32_t)c.ldb * 4u, lda = (uint32_t)c.lda;
+            b_unit = (int64_t)c.ldb * 4;
+            b_step = (const char *)c.B + (int64_t)c.k0 * b_unit;
+            const uint32_t b0 = 4u * (uint32_t)kq * ldb4 + 4u * (uint32_t)min(c.tile_n + 4 * nq, c.N - 4);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r.b[i] = *(const f32x4 *)(b_col + (int64_t)min(k0 + 4 * kq + i, k_last) * p.ldb);
-            if (p.a_kfast) {
-                // row tid of the tile, 32 consecutive reduction indices (8 dwords; K is a multiple of 4 here)
-                const int8_t *a_row = p.A + (int64_t)min(c.tile_m + tid, p.M - 1) * p.lda;
+            for (int j = 0; j < 4; ++j) boff[j] = b0 + (uint32_t)j * ldb4;
+            if (c.a_kfast) {
+                // rows tid/2 and 128 + tid/2 of the tile, 16 consecutive reduction indices each (a pair of lanes
+                // takes a 32-byte run of a row)
+                a_unit = 1;
+                a_step = c.A + c.k0;
+                a_shift = 0;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) r.a[i] = *(const uint32_t *)(a_row + min(k0 + 4 * i, p.K - 4));
+                for (int j = 0; j < 2; ++j)
+                    aoff[j] = (uint32_t)min(c.tile_m + 128 * j + (tid >> 1), c.M - 1) * lda + 16u * (uint32_t)(tid & 1);
             } else {
-                // rows 4*nq..4*nq+3 of each 128-row half, reduction rows 4*kq..4*kq+3 (one dword each)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int8_t *a_col = p.A + min(c.tile_m + 128 * h + 4 * nq, p.M - 4);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) r.a[4 * h + i] = *(const uint32_t *)(a_col + (int64_t)min(k0 + 4 * kq + i, k_last) * p.lda);
-                }
+                // reduction indices 2*(tid/16), +1 and 16 consecutive rows of the matrix each (M >= 16, M % 4 == 0);
+                // a run that would pass the last row starts earlier and is moved back when the step is committed
+                a_unit = c.lda;
+                a_step = c.A + (int64_t)c.k0 * c.lda;
+                const int m = c.tile_m + 16 * (tid & 15);
+                a_shift = max(0, m + 16 - c.M) >> 2;
+                aoff[0] = 2u * (uint32_t)(tid >> 4) * lda + (uint32_t)max(0, min(m, c.M - 16));
+                aoff[1] = aoff[0] + lda;
             }
-            c.k0 += FC2_KT;
-            if (c.k0 >= c.k_end) open = fc2_open(a, c.t + 1, c);
+            return true;
+        };
+        bool open = open_item(0);
+
+        // Loads of the cursor's K step; then the cursor moves on (to the next item after an item's last step).
+        // Every call issues the same six 16-byte loads, also once the list is exhausted (the last window again;
+        // it is never committed): with equal load counts on every path the compiler can wait for exactly the
+        // loads of three calls ago instead of for all outstanding ones.
+        auto issue = [&](Fc2Raw &r) {
+            if (open) {
+                kv_cur = c.k_end - c.k0;
+                const int back = max(0, FC2_KT - kv_cur);
+                b_cur = b_step - back * b_unit;
+                a_cur = a_step - back * a_unit;
+            }
+            r.kfast = c.a_kfast;
+            r.k_valid = kv_cur;
+            r.a_shift = a_shift;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r.b[i] = *(const f32x4 *)(b_cur + (size_t)boff[i]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const u32x4 v = *(const u32x4_dw *)(a_cur + (size_t)aoff[i]);
+                r.a[4 * i] = v.x; r.a[4 * i + 1] = v.y; r.a[4 * i + 2] = v.z; r.a[4 * i + 3] = v.w;
+            }
+            if (open) {
+                c.k0 += FC2_KT;
+                b_step += FC2_KT * b_unit; a_step += FC2_KT * a_unit;
+                if (c.k0 >= c.k_end) open = open_item(c.t + 1);
+            }
+        };
+
+        // dwords of a 16-byte run moved back by `sh` dwords (what lies past the last row is zero)
+        auto unshift = [](uint32_t (&w)[4], int sh) {
+            const uint32_t t0 = w[0], t1 = w[1], t2 = w[2], t3 = w[3];
+            w[0] = sh == 0 ? t0 : sh == 1 ? t1 : sh == 2 ? t2 : sh == 3 ? t3 : 0u;
+            w[1] = sh == 0 ? t1 : sh == 1 ? t2 : sh == 2 ? t3 : 0u;
+            w[2] = sh == 0 ? t2 : sh == 1 ? t3 : 0u;
+            w[3] = sh == 0 ? t3 : 0u;
         };
 
         auto commit = [&](const Fc2Raw &r, Fc2Stage &sm) {
-            const int kv = r.k_valid;                                // reduction indices of this step that exist (>= 32: all)
+            // window indices below `dup` repeat the step before (only in an item's last, shorter step)
+            const int dup = FC2_KT - r.k_valid;
             if (r.kfast) {
-                // dwords 2c, 2c+1 = chunk c of row tid
+                // dwords 0..3 of set i = chunks 2q, 2q+1 (q = tid & 1) of row position 128*i + tid/2
 #pragma unroll
-                for (int ch = 0; ch < 4; ++ch) {
-                    uint32_t w0 = r.a[2 * ch], w1 = r.a[2 * ch + 1];
-                    if (kv < FC2_KT) {
-                        const int n0 = kv - 8 * ch, n1 = n0 - 4;       // valid bytes of the two dwords
-                        w0 = n0 >= 4 ? w0 : n0 > 0 ? w0 & ((1u << (8 * n0)) - 1u) : 0u;
-                        w1 = n1 >= 4 ? w1 : n1 > 0 ? w1 & ((1u << (8 * n1)) - 1u) : 0u;
+                for (int i = 0; i < 2; ++i) {
+                    uint32_t w[4] = {r.a[4 * i], r.a[4 * i + 1], r.a[4 * i + 2], r.a[4 * i + 3]};
+                    if (dup > 0) {
+                        // the item's ends are multiples of 4, so whole dwords are in or out
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) w[d] = 16 * (tid & 1) + 4 * d >= dup ? w[d] : 0u;
                     }
-                    sm.a[ch][tid][0] = uint2{bf16x2_from_codes((int8_t)w0, (int8_t)(w0 >> 8)),
-                                             bf16x2_from_codes((int8_t)(w0 >> 16), (int8_t)(w0 >> 24))};
-                    sm.a[ch][tid][1] = uint2{bf16x2_from_codes((int8_t)w1, (int8_t)(w1 >> 8)),
-                                             bf16x2_from_codes((int8_t)(w1 >> 16), (int8_t)(w1 >> 24))};
+                    const int pos = 128 * i + (tid >> 1);
+#pragma unroll
+                    for (int e = 0; e < 2; ++e)
+                        *(u32x4 *)&sm.a[2 * (tid & 1) + e][pos][0] =
+                            u32x4{bf16x2_from_codes((int8_t)w[2 * e], (int8_t)(w[2 * e] >> 8)),
+                                  bf16x2_from_codes((int8_t)(w[2 * e] >> 16), (int8_t)(w[2 * e] >> 24)),
+                                  bf16x2_from_codes((int8_t)w[2 * e + 1], (int8_t)(w[2 * e + 1] >> 8)),
+                                  bf16x2_from_codes((int8_t)(w[2 * e + 1] >> 16), (int8_t)(w[2 * e + 1] >> 24))};
                 }
             } else {
-                // byte j of the 4 dwords = 4 consecutive reduction indices of row 4*nq+j -> position j*32+nq of its half
+                // set i = reduction index 2*k2 + i (k2 = tid/16); byte j of dword d = matrix row 16*(tid&15) + 4*d + j
+                // of the tile -> position 128*half + 32*j + (row%128)/4, dword k2%4 of the cell of chunk k2/4
+                const int k2 = tid >> 4, m16 = tid & 15;
+                uint32_t w0[4] = {r.a[0], r.a[1], r.a[2], r.a[3]}, w1[4] = {r.a[4], r.a[5], r.a[6], r.a[7]};
+                if (r.a_shift) { unshift(w0, r.a_shift); unshift(w1, r.a_shift); }
+                if (dup > 0) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    uint32_t w[4];
+                    for (int d = 0; d < 4; ++d) { w0[d] = 2 * k2 >= dup ? w0[d] : 0u; w1[d] = 2 * k2 + 1 >= dup ? w1[d] : 0u; }
+                }
+                uint32_t *cell = (uint32_t *)&sm.a[k2 >> 2][128 * (m16 >> 3) + 4 * (m16 & 7)][0] + (k2 & 3);
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) w[i] = 4 * kq + i < kv ? r.a[4 * h + i] : 0u;
+                for (int d = 0; d < 4; ++d)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        sm.a[kq >> 1][128 * h + j * 32 + nq][kq & 1] =
-                            uint2{bf16x2_from_codes((int8_t)(w[0] >> (8 * j)), (int8_t)(w[1] >> (8 * j))),
-                                  bf16x2_from_codes((int8_t)(w[2] >> (8 * j)), (int8_t)(w[3] >> (8 * j)))};
-                }
+                        cell[4 * (32 * j + d)] = bf16x2_from_codes((int8_t)(w0[d] >> (8 * j)), (int8_t)(w1[d] >> (8 * j)));
             }
             // fp32 -> three exact bf16 planes; column 4*nq+j -> position j*32+nq
+            f32x4 bv[4] = {r.b[0], r.b[1], r.b[2], r.b[3]};
+            if (dup > 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (4 * kq + i < dup) bv[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint32_t h[4], m[4], l[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) split3(4 * kq + i < kv ? r.b[i][j] : 0.0f, h[i], m[i], l[i]);
+                for (int i = 0; i < 4; ++i) split3(bv[i][j], h[i], m[i], l[i]);
                 const int pos = j * 32 + nq;
                 sm.b[0][kq >> 1][pos][kq & 1] = uint2{upper_halves(l[1], l[0]), upper_halves(l[3], l[2])};
                 sm.b[1][kq >> 1][pos][kq & 1] = uint2{upper_halves(m[1], m[0]), upper_halves(m[3], m[2])};
@@ -209,22 +318,23 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 
         // Step g lives in register set g % 3 and LDS stage g % 2.  Barriers: one after step 0 is staged, then
         // one per step; in the iteration of step g the stagers write step g + 1 and load step g + 4.
+        // The loads are unconditional (see issue); only commits and barriers depend on the trip count.
+        if (G == 0) { __syncthreads(); return; }
         Fc2Raw r0, r1, r2;
         issue(r0); issue(r1); issue(r2);
-        if (G > 0) commit(r0, stages[0]);
+        commit(r0, stages[0]);
         issue(r0);
         __syncthreads();
         for (int g = 0; g < G; g += 3) {
-            if (g + 1 < G) { commit(r1, stages[(g + 1) & 1]); issue(r1); }
+            if (g + 1 < G) commit(r1, stages[(g + 1) & 1]);
+            issue(r1);
             __syncthreads();
-            if (g + 1 < G) {
-                if (g + 2 < G) { commit(r2, stages[(g + 2) & 1]); issue(r2); }
-                __syncthreads();
-            }
-            if (g + 2 < G) {
-                if (g + 3 < G) { commit(r0, stages[(g + 3) & 1]); issue(r0); }
-                __syncthreads();
-            }
+            if (g + 2 < G) commit(r2, stages[(g + 2) & 1]);
+            issue(r2);
+            if (g + 1 < G) __syncthreads();
+            if (g + 3 < G) commit(r0, stages[(g + 3) & 1]);
+            issue(r0);
+            if (g + 2 < G) __syncthreads();
         }
         return;
     }
@@ -242,7 +352,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     Fc2Cursor c;
-    fc2_open(a, 0, c);
+    fc2_open(a, table, mine, 0, c);
     const float scale0 = a.prob[0].scale.get(), scale1 = a.prob[1].scale.get();   // resolved once (host value or device Delta)
 
     __syncthreads();
@@ -269,7 +379,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
         c.k0 += FC2_KT;
         if (c.k0 >= c.k_end) {
             // ---- the item is complete: store (the stagers are already loading the next one) ----
-            const FcProblem &p = a.prob[c.which];
+            const Fc2Cursor p = c;
             if (p.n_split > 1) {
                 // partial tile in thread order; fc2_reduce_kernel sums the splits in a fixed order
                 float4 *mine = (float4 *)(p.partial + ((int64_t)c.tile * p.n_split + c.z) * (FC2_TM * FC2_TN));
@@ -302,7 +412,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-            fc2_open(a, c.t + 1, c);
+            fc2_open(a, table, mine, c.t + 1, c);
         }
         __syncthreads();
     }

@@ -367,8 +367,17 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
                              fc_fast_ok(false, a.codes, a.out, (const float *)a.X, a.in, out, in, (const float *)a.dW);
         // Large products: the kernel with separate staging and multiplying wavefronts (256x128 tiles, one
         // workgroup per CU); small ones (less than half such a tile of rows): the 128x128 kernel.
-        const bool big = (!dx_fast || B > FC2_TM / 2) && (!dw_fast || out > FC2_TM / 2);
-        if ((dx_fast || dw_fast) && big) {
+        const bool big = (!dx_fast || B > FC2_TM / 2) && (!dw_fast || out > FC2_TM / 2) &&
+                         (!dx_fast || out >= 32) && (!dw_fast || (B >= 32 && out >= 16)) &&         // a full window of 32 reduction indices; 16-row runs
+                         B * in < (1ll << 30) && out * in < (1ll << 30) && B * out < (1ll << 30);                // 32-bit lane offsets
+        FcPlan pdx, pdw;
+        bool use_fc2 = (dx_fast || dw_fast) && big;
+        if (use_fc2) {
+            fc2_plans(B, in, out, dx_fast, dw_fast, pdx, pdw);
+            const int64_t items = (dx_fast ? pdx.tiles * pdx.n_split : 0) + (dw_fast ? pdw.tiles * pdw.n_split : 0);
+            if (items > (int64_t)FC2_MAX_ITEMS * 256) use_fc2 = false;     // the per-workgroup item table is fixed
+        }
+        if (use_fc2) {
             static bool raised = false;
             if (!raised) {
                 e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel),
@@ -378,8 +387,6 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             }
             char *scratch = (char *)a.scratch;
             FcPairArgs pa;
-            FcPlan pdx, pdw;
-            fc2_plans(B, in, out, dx_fast, dw_fast, pdx, pdw);
             if (!dx_fast) { pdx.n_split = 1; pdx.partial_bytes = 0; }
             if (!dw_fast) { pdw.n_split = 1; pdw.partial_bytes = 0; }
             pa.prob[0] = fc_problem(true, a.codes, a.out, a.W, a.in, B, in, out, Scale{a.step, a.step_dev}, a.dX, pdx, scratch);
@@ -548,3 +555,4 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s)
 }
 
 }  // namespace dbp
+
