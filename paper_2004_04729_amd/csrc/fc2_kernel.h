@@ -147,12 +147,13 @@ __device__ __forceinline__ void fc2_bias_grad(const StatsJob &j, int lane)
     for (int64_t i = lane; i < j.bias_len; i += 64) j.bias_grad[i] = (float)(d * (double)j.bias_sums[i]);
 }
 
-// Matrix row of element ii of row block i of multiplier wavefront `wave`: row positions are rows
-// (a_kfast) or, inside each 128-row half, the interleave 4*nq + j -> position 32*j + nq of the staging.
+// Matrix row of element ii of row block i of multiplier wavefront `wave`: row positions are rows (a_kfast)
+// or the transposition position 16*(row % 16) + row / 16 of the staging (a stager lane holds 16 consecutive
+// rows; with this order the 64 lanes of one LDS write fall into 64 different banks).
 __device__ __forceinline__ int fc2_row(int a_kfast, int tile_m, int wave, int i, int ii)
 {
     return a_kfast ? tile_m + wave * 64 + i * 32 + ii
-                   : tile_m + 128 * (wave >> 1) + 4 * ii + 2 * (wave & 1) + i;
+                   : tile_m + 16 * (ii & 15) + 4 * wave + 2 * i + (ii >> 4);
 }
 
 __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
@@ -177,7 +178,9 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
             if (a.stats.n > 0) fc2_sum_stats(a.stats, lane);
             if (a.stats.bias_len > 0) fc2_bias_grad(a.stats, lane);
         }
-        const int nq = tid & 31, kq = tid >> 5;
+        // lane pairs share four columns of the dense operand and take neighbouring groups of four reduction
+        // indices: their 8-byte LDS writes are then contiguous over the wavefront
+        const int nq = (tid >> 1) & 31, kq = 2 * (tid >> 6) + (tid & 1);
         Fc2Cursor c;
         // Addresses: a base that is the same for all lanes and moves with the K step (scalar additions), plus a
         // 32-bit lane offset that is fixed for the item (the matrices are smaller than 4 GiB here).  Rows and
@@ -282,7 +285,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
                 }
             } else {
                 // set i = reduction index 2*k2 + i (k2 = tid/16); byte j of dword d = matrix row 16*(tid&15) + 4*d + j
-                // of the tile -> position 128*half + 32*j + (row%128)/4, dword k2%4 of the cell of chunk k2/4
+                // of the tile -> position 16*(4*d + j) + tid%16, dword k2%4 of the cell of chunk k2/4
                 const int k2 = tid >> 4, m16 = tid & 15;
                 uint32_t w0[4] = {r.a[0], r.a[1], r.a[2], r.a[3]}, w1[4] = {r.a[4], r.a[5], r.a[6], r.a[7]};
                 if (r.a_shift) { unshift(w0, r.a_shift); unshift(w1, r.a_shift); }
@@ -290,12 +293,12 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 #pragma unroll
                     for (int d = 0; d < 4; ++d) { w0[d] = 2 * k2 >= dup ? w0[d] : 0u; w1[d] = 2 * k2 + 1 >= dup ? w1[d] : 0u; }
                 }
-                uint32_t *cell = (uint32_t *)&sm.a[k2 >> 2][128 * (m16 >> 3) + 4 * (m16 & 7)][0] + (k2 & 3);
+                uint32_t *cell = (uint32_t *)&sm.a[k2 >> 2][m16][0] + (k2 & 3);
 #pragma unroll
                 for (int d = 0; d < 4; ++d)
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        cell[4 * (32 * j + d)] = bf16x2_from_codes((int8_t)(w0[d] >> (8 * j)), (int8_t)(w1[d] >> (8 * j)));
+                        cell[64 * (4 * d + j)] = bf16x2_from_codes((int8_t)(w0[d] >> (8 * j)), (int8_t)(w1[d] >> (8 * j)));
             }
             // fp32 -> three exact bf16 planes; column 4*nq+j -> position j*32+nq
             f32x4 bv[4] = {r.b[0], r.b[1], r.b[2], r.b[3]};
