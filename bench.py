@@ -341,6 +341,21 @@ def bench_conv_configs(dbp, workloads, torch, np, timed, stream):
             except Exception as e:                                   # context line: never fail the run over it
                 row["torch_conv_backward_fp32_ms"] = None
             del dt
+        if i8 and name == "cfg5_s0.9":
+            # full 8-bit backward on the same layer: int8 weights too, both products exact int32
+            W8 = torch.randint(-127, 128, p.W.shape, dtype=torch.int8, device=dev)
+            dX32 = torch.empty(p.X.shape, dtype=torch.int32, device=dev)
+            t8 = timed(lambda i: dbp.dithered_conv2d_backward_q8(d, W8, X, N, Cc, H, Wd, K, R, S, 1, p.pad, p.step, p.seed, 0,
+                                                                 codes, dX32, dW, ws, st, stream), 5, warm=1)
+            t8x = timed(lambda i: dbp.dithered_conv2d_backward_q8(d, W8, X, N, Cc, H, Wd, K, R, S, 1, p.pad, p.step, p.seed, 0,
+                                                                  codes, dX32, None, ws, st, stream), 5, warm=1)
+            row["full_8bit"] = {"ms": t8 * 1e3, "dense_equiv_tops": flops / t8 / 1e12, "nsd_plus_dX32_ms": t8x * 1e3}
+            Wq = torch.empty(p.W.size, dtype=torch.int8, device=dev)
+            sc = torch.empty(2, dtype=torch.float32, device=dev)
+            wsq = torch.empty(dbp.quantize_int8_workspace_bytes(p.W.size), dtype=torch.uint8, device=dev)
+            tq = timed(lambda i: dbp.quantize_int8(W, p.W.size, Wq, sc, wsq, stream), 5, warm=1)
+            row["full_8bit"]["quantize_W_us"] = tq * 1e6
+            del W8, dX32, Wq, sc, wsq
         res[name] = row
         del d, W, X, codes, dX, dW, ws
     return res

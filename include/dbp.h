@@ -278,6 +278,41 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
                                           void *workspace, size_t workspace_bytes, dbp_stats *stats,
                                           dbp_path path, void *stream);
 
+/*
+ * ---------------------------------------------------------------------------------------------------------
+ * Full 8-bit backward (Sec. "Quantizing forward pass": weights and activations are 8-bit too, so that every
+ * product of the backward pass is an 8-bit computation and only the weight update stays in full precision).
+ * ---------------------------------------------------------------------------------------------------------
+ * dbp_quantize_int8: the forward pass's quantiser.  The paper takes it from the work it cites and does not
+ * print it; reading taken here: symmetric, one scale per tensor,
+ *     amax = max |x_i| over the finite x_i,  scale = amax / 127,  inv = 127 / amax          (fp32 divisions)
+ *     q_i  = clamp(round-half-even(x_i * inv), -127, 127)                              (one fp32 product)
+ *   NaN -> 0, +-Inf -> +-127; amax == 0 or nothing finite: scale = inv = 0 and every finite q_i is 0.
+ *   x device [n]; q device, out [n]; scale_out device, out: {scale, inv} (8-byte aligned);
+ *   workspace dbp_quantize_int8_workspace_bytes(n), 256-byte aligned.
+ *   Errors: NULL -> NULL; n <= 0 or misaligned -> SHAPE; workspace -> WORKSPACE.
+ *
+ * dithered_*_backward_q8: NSD of delta, then both products on int8 matrix cores with exact int32 sums:
+ *     dX32[b,i] = sum_o k[b,o] * W8[o,i]          dW32[o,i] = sum_b k[b,o] * X8[b,i]        (conv: the adjoints of
+ *     the stride-1 cross-correlation, as in dithered_conv2d_backward).
+ *   The real gradients are Delta*scale_W*dX32 and Delta*scale_X*dW32; the caller applies the scales (in the weight
+ *   update, which stays in full precision).  dX32 / dW32 nullable (not both); W8 needed for dX32, X8 for dW32.
+ *   Workspace: dbp_linear_workspace_bytes / dbp_conv2d_workspace_bytes (any path, DBP_I8).
+ *   Errors as dithered_*_backward; a reduction long enough to overflow int32 (length*127*127 >= 2^31) -> OVERFLOW.
+ */
+size_t     dbp_quantize_int8_workspace_bytes(int64_t n);
+dbp_status dbp_quantize_int8(const float *x /*device*/, int64_t n, int8_t *q /*device*/, float *scale_out /*device [2]*/,
+                             void *workspace, size_t workspace_bytes, void *stream);
+dbp_status dithered_linear_backward_q8(const float *delta, const int8_t *W8, const int8_t *X8,
+                                       int64_t B, int64_t in, int64_t out, float step, uint64_t seed, uint64_t idx_base,
+                                       int8_t *codes, int32_t *dX32, int32_t *dW32, void *workspace,
+                                       size_t workspace_bytes, dbp_stats *stats, void *stream);
+dbp_status dithered_conv2d_backward_q8(const float *delta, const int8_t *W8, const int8_t *X8,
+                                       int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                       int64_t stride, int64_t pad, float step, uint64_t seed, uint64_t idx_base,
+                                       int8_t *codes, int32_t *dX32, int32_t *dW32, void *workspace,
+                                       size_t workspace_bytes, dbp_stats *stats, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

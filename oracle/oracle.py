@@ -272,3 +272,49 @@ def conv2d_dw_at(X, Wshape, idx, *, codes=None, dense=None, step=0.0, stride=1, 
                                   *[C.c_int64(v) for v in (N, Cc, H, Wd, K, R, S, stride, pad)],
                                   _p(idx), C.c_int64(idx.size), _p(val))
     return val
+
+
+# ---- full 8-bit backward (Sec. "Quantizing forward pass") ---------------------------------------
+def quantize_int8(x):
+    """Symmetric per-tensor int8 quantiser: returns (q int8, scale float32, inv float32).
+
+    amax over the finite values; scale = amax/127 and inv = 127/amax as fp32 divisions; q = round-half-even(x*inv)
+    with one fp32 product, clamped to [-127, 127]; NaN -> 0, +-Inf -> +-127; amax == 0 -> scale = inv = 0.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    fin = np.isfinite(x)
+    amax = np.float32(np.abs(x[fin]).max()) if fin.any() else np.float32(0.0)
+    if amax > 0:
+        scale = np.float32(amax) / np.float32(127.0)
+        inv = np.float32(127.0) / np.float32(amax)
+    else:
+        scale = inv = np.float32(0.0)
+    with np.errstate(invalid="ignore", over="ignore"):
+        t = np.rint((x * inv).astype(np.float32))
+    q = np.clip(np.where(fin, t, 0.0), -127.0, 127.0)
+    q = np.where(np.isposinf(x), 127.0, np.where(np.isneginf(x), -127.0, q))
+    return q.astype(np.int8), np.float32(scale), np.float32(inv)
+
+
+def _as_int32(v, what):
+    r = np.rint(v)
+    if not np.array_equal(r, v):
+        raise ArithmeticError("%s: the fp64 sum of integer products is not an integer" % what)
+    if r.size and (r.max() > 2**31 - 1 or r.min() < -2**31):
+        raise OverflowError("%s leaves int32" % what)
+    return r.astype(np.int32)
+
+
+def linear_backward_q8(codes, W8, X8, threads=None):
+    """Exact (dX32 [B,in], dW32 [out,in]) = (codes . W8, codes^T . X8).  Every term of Eqs. (qda)/(qdw) is an
+    integer here, so the fp64 sums of linear_backward (step 1) are exact as long as they stay below 2^53."""
+    dX, dW, _ = linear_backward(np.asarray(W8, np.float32), np.asarray(X8, np.float32), codes=codes, step=1.0,
+                                threads=threads)
+    return _as_int32(dX, "dX32"), _as_int32(dW, "dW32")
+
+
+def conv2d_backward_q8(codes, W8, X8, stride=1, pad=0, threads=None):
+    """Exact int32 (dX32, dW32) of the convolution's adjoints with int8 weights and activations."""
+    dX, dW, _ = conv2d_backward(np.asarray(W8, np.float32), np.asarray(X8, np.float32), codes=codes, step=1.0,
+                                stride=stride, pad=pad, threads=threads)
+    return _as_int32(dX, "dX32"), _as_int32(dW, "dW32")

@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     BIAS_PER_COLUMN, BIAS_PER_ROW_GROUP, step_size_workspace_bytes, step_size, nsd_quantize_ex,
     linear_layer_workspace_bytes, conv2d_layer_workspace_bytes,
     dithered_linear_layer_backward, dithered_conv2d_layer_backward,
+    quantize_int8_workspace_bytes, quantize_int8, dithered_linear_backward_q8, dithered_conv2d_backward_q8,
     lib, lib_path,
 )

@@ -95,7 +95,13 @@ def lib():
                                                      vp, sz, vp, ci, vp]
         L.dithered_conv2d_layer_backward.argtypes = [vp, vp, vp, vp, ci] + [i64] * 9 + [f32, u64, u64, vp, vp, vp, vp, vp,
                                                                                         vp, sz, vp, ci, vp]
-        for name in ("dbp_step_size", "nsd_quantize_ex", "dithered_linear_layer_backward", "dithered_conv2d_layer_backward"):
+        L.dbp_quantize_int8_workspace_bytes.restype = sz
+        L.dbp_quantize_int8_workspace_bytes.argtypes = [i64]
+        L.dbp_quantize_int8.argtypes = [vp, i64, vp, vp, vp, sz, vp]
+        L.dithered_linear_backward_q8.argtypes = [vp, vp, vp, i64, i64, i64, f32, u64, u64, vp, vp, vp, vp, sz, vp, vp]
+        L.dithered_conv2d_backward_q8.argtypes = [vp, vp, vp] + [i64] * 9 + [f32, u64, u64, vp, vp, vp, vp, sz, vp, vp]
+        for name in ("dbp_step_size", "nsd_quantize_ex", "dithered_linear_layer_backward", "dithered_conv2d_layer_backward",
+                     "dbp_quantize_int8", "dithered_linear_backward_q8", "dithered_conv2d_backward_q8"):
             getattr(L, name).restype = ci
         for name in ("dbp_format_layout_of", "nsd_quantize", "dithered_linear_backward", "dithered_conv2d_backward",
                      "dense_linear_backward", "dense_conv2d_backward", "dbp_linear_products", "dbp_conv2d_products"):
@@ -220,3 +226,26 @@ def dithered_conv2d_layer_backward(delta_a, act, W, X, x_dtype, N, Cc, H, Wd, K,
                                                 stride, pad, s, seed, idx_base, _ptr(codes), _ptr(dX), _ptr(dW), _ptr(db),
                                                 _ptr(step_out), _ptr(workspace), _nbytes(workspace), _ptr(stats), path,
                                                 stream))
+
+
+def quantize_int8_workspace_bytes(n):
+    return int(lib().dbp_quantize_int8_workspace_bytes(n))
+
+
+def quantize_int8(x, n, q, scale_out, workspace, stream=0):
+    """The forward pass's symmetric int8 quantiser: q[0:n], scale_out[0:2] = {scale, 1/scale}."""
+    _check(lib().dbp_quantize_int8(_ptr(x), n, _ptr(q), _ptr(scale_out), _ptr(workspace), _nbytes(workspace), stream))
+
+
+def dithered_linear_backward_q8(delta, W8, X8, B, in_, out, step, seed, idx_base, codes, dX32, dW32, workspace,
+                                stats=None, stream=0):
+    _check(lib().dithered_linear_backward_q8(_ptr(delta), _ptr(W8), _ptr(X8), B, in_, out, step, seed, idx_base,
+                                             _ptr(codes), _ptr(dX32), _ptr(dW32), _ptr(workspace), _nbytes(workspace),
+                                             _ptr(stats), stream))
+
+
+def dithered_conv2d_backward_q8(delta, W8, X8, N, Cc, H, Wd, K, R, S, stride, pad, step, seed, idx_base, codes, dX32,
+                                dW32, workspace, stats=None, stream=0):
+    _check(lib().dithered_conv2d_backward_q8(_ptr(delta), _ptr(W8), _ptr(X8), N, Cc, H, Wd, K, R, S, stride, pad, step,
+                                             seed, idx_base, _ptr(codes), _ptr(dX32), _ptr(dW32), _ptr(workspace),
+                                             _nbytes(workspace), _ptr(stats), stream))

@@ -141,7 +141,7 @@ dbp_status linear_products(const int8_t *codes, const void *format, float step, 
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     LinearArgs a;
-    a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.stats_job = job;
     if (path == DBP_PATH_GATHER) {
         if (!format) return DBP_ERR_NULL;
@@ -179,7 +179,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     ConvArgs a;
-    a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
@@ -325,7 +325,7 @@ dbp_status dense_linear_backward(const void *delta, const float *W, const void *
     const size_t need = linear_scratch_bytes(B, in, out);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     LinearArgs a;
-    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
@@ -347,7 +347,7 @@ dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *
     const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     ConvArgs a;
-    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.X = X; a.x_dtype = x_dtype;
+    a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
@@ -356,6 +356,74 @@ dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *
 
 
 // ---- Algorithm 1 on the device, and the steps around the quantiser ---------------------------------------
+
+// ---- full 8-bit backward -------------------------------------------------------------------------------
+size_t dbp_quantize_int8_workspace_bytes(int64_t n) { return n > 0 ? quantize_scratch_bytes(n) : 0; }
+
+dbp_status dbp_quantize_int8(const float *x, int64_t n, int8_t *q, float *scale_out, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    if (!x || !q || !scale_out) return DBP_ERR_NULL;
+    if (n <= 0) return DBP_ERR_SHAPE;
+    if (!aligned(x, 4) || !aligned(scale_out, 8)) return DBP_ERR_SHAPE;
+    if (!workspace || workspace_bytes < quantize_scratch_bytes(n) || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    return launch_quantize_int8(x, n, q, scale_out, workspace, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+dbp_status dithered_linear_backward_q8(const float *delta, const int8_t *W8, const int8_t *X8,
+                                       int64_t B, int64_t in, int64_t out, float step, uint64_t seed, uint64_t idx_base,
+                                       int8_t *codes, int32_t *dX32, int32_t *dW32, void *workspace,
+                                       size_t workspace_bytes, dbp_stats *stats, void *stream)
+{
+    if (!delta || (!dX32 && !dW32) || (dX32 && !W8) || (dW32 && !X8)) return DBP_ERR_NULL;
+    dbp_status st = check_linear_dims(B, in, out);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (dX32 && out * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    if (dW32 && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const Carve c = carve(B, out, linear_scratch_bytes(B, in, out));
+    if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    char *ws = (char *)workspace;
+    int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
+    st = run_nsd(delta, B, out, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, false);
+    if (st != DBP_OK) return st;
+    LinearArgs a;
+    a.codes = k; a.dense = nullptr; a.step = 1.0f; a.step_dev = nullptr; a.W = nullptr; a.W8 = W8 ? W8 : X8; a.X = X8;
+    a.x_dtype = DBP_I8; a.B = B; a.in = in; a.out = out; a.dX = (float *)dX32; a.dW = dW32;
+    a.scratch = ws + c.scratch_offset; a.scratch_bytes = workspace_bytes - c.scratch_offset;
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    return launch_linear_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+dbp_status dithered_conv2d_backward_q8(const float *delta, const int8_t *W8, const int8_t *X8,
+                                       int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                       int64_t stride, int64_t pad, float step, uint64_t seed, uint64_t idx_base,
+                                       int8_t *codes, int32_t *dX32, int32_t *dW32, void *workspace,
+                                       size_t workspace_bytes, dbp_stats *stats, void *stream)
+{
+    if (!delta || (!dX32 && !dW32) || (dX32 && !W8) || (dW32 && !X8)) return DBP_ERR_NULL;
+    int64_t P, Q;
+    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (stride != 1) return DBP_ERR_UNSUPPORTED;
+    if (dX32 && K * R * S * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    if (dW32 && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad));
+    if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    char *ws = (char *)workspace;
+    int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, false);
+    if (st != DBP_OK) return st;
+    ConvArgs a;
+    a.codes = k; a.dense = nullptr; a.step = 1.0f; a.step_dev = nullptr; a.W = nullptr; a.W8 = W8 ? W8 : X8; a.X = X8;
+    a.x_dtype = DBP_I8; a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
+    a.dX = (float *)dX32; a.dW = dW32; a.scratch = ws + c.scratch_offset; a.scratch_bytes = workspace_bytes - c.scratch_offset;
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
 
 size_t dbp_step_size_workspace_bytes(int64_t n)
 {

@@ -68,6 +68,9 @@ hipError_t launch_stats_job(const StatsJob &j, hipStream_t s);
 // when act is given (both 0 if the standard
 // deviation is 0 or not finite).  scratch: step_size_scratch_bytes(n).
 size_t     step_size_scratch_bytes(int64_t n);
+// symmetric int8 quantiser of the forward pass (nsd.hip)
+size_t     quantize_scratch_bytes(int64_t n);
+hipError_t launch_quantize_int8(const float *x, int64_t n, int8_t *q, float *scale_out, void *scratch, hipStream_t st);
 hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st,
                             int64_t *zero = nullptr, int64_t zero_len = 0);   // also clears zero[0..zero_len)
 
@@ -84,6 +87,7 @@ struct LinearArgs {
     float         step;        // Delta (dithered); ignored for dense
     const float  *step_dev;    // device {Delta, 1/Delta} instead of `step` (nullable)
     const float  *W;           // [out,in]
+    const int8_t *W8;          // full 8-bit mode: int8 weights [out,in] instead of W; dX is then exact int32 (nullable)
     const void   *X;           // [B,in] fp32 or int8
     dbp_dtype     x_dtype;
     int64_t       B, in, out;
@@ -99,6 +103,7 @@ struct ConvArgs {
     float         step;
     const float  *step_dev;
     const float  *W;           // [K,C,R,S]
+    const int8_t *W8;          // full 8-bit mode: int8 weights instead of W; dX is then exact int32 (nullable)
     const void   *X;           // [N,C,H,Wd]
     dbp_dtype     x_dtype;
     int64_t       N, C, H, Wd, K, R, S, pad;

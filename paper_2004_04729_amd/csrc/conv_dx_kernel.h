@@ -1,6 +1,9 @@
 // Input-gradient product of a stride-1 convolution from int8 codes, the convolutional analogue of Eq. (qda):
 //   dX[n,c,h,w] = Delta * sum_{k,r,s} code[n,k,h+pad-r,w+pad-s] * W[k,c,r,s]
-// on bf16 matrix cores with the bf16x3 weight split (exact codes x three-plane weights, fp32 accumulate).
+// on bf16 matrix cores with the bf16x3 weight split (exact codes x three-plane weights, fp32 accumulate),
+// or, in the full 8-bit mode (int8 weights), on int8 matrix cores with an exact int32 result: the same
+// kernel with 16 reduction channels per cell instead of 8, one weight plane instead of three, and a byte
+// transposition of the codes in place of their conversion.
 //
 // Orientation: D[c][pixel] = sum_kk Wp[c][kk] * code[kk][pixel], kk = (tap, k).  Output pixels are the
 // matrix-core columns, so every store instruction writes runs of 32 consecutive pixels of one channel.
@@ -21,17 +24,17 @@
 
 namespace dbp {
 
-constexpr int CDX_KGC = 4;            // k-groups (of 8 channels) per reduction chunk
+constexpr int CDX_KGC = 4;            // k-groups (of 8 channels, 16 in the int8 mode) per reduction chunk
 constexpr int CDX_ITMAX = 2;          // patch-fill items per thread and chunk, at most
 constexpr int CDX_MAX_LDS = 64 * 1024;   // dynamic LDS a launch may ask for without raising the function attribute
 
 struct ConvDxArgs {
     const int8_t *codes;      // [N][K][P][Q]
-    const uint4  *wp;         // prepared weights, cell ((tap*KG + kg)*3 + plane)*Cp + c
-    float        *dX;         // [N][C][H][Wd]
+    const uint4  *wp;         // prepared weights, cell ((tap*KG + kg)*planes + plane)*Cp + c
+    void         *dX;         // [N][C][H][Wd] fp32, or int32 in the int8 mode
     int N, C, H, Wd, K, R, S, pad, P, Q;
     int PI, PQ;               // H*Wd, P*Q
-    int Cp, KG, n_chunks;     // C rounded to 32; k-groups in total (K rounded to 32, over 8); chunks of 32 channels
+    int Cp, KG, n_chunks;     // C rounded to 32; k-groups in total (K rounded to a chunk); chunks of CDX_KGC k-groups
     int wc, wpx;              // waves along channels x waves along pixels (wc * wpx == 4)
     int cgroups;              // ceil(C / (32*wc))
     int tiles;                // pixel tiles per image
@@ -61,6 +64,29 @@ __global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W
     }
 }
 
+// int8 weights [K][C][R][S] -> cells of 16 reduction channels in fragment order [tap][k-group][c], zero padded.
+__global__ __launch_bounds__(256) void conv_dx_weight_prep_i8_kernel(const int8_t *W, uint4 *wp, int K, int C, int RS, int KG, int Cp)
+{
+    const int64_t total = (int64_t)RS * KG * Cp;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int c = (int)(i % Cp);
+        const int64_t t = i / Cp;
+        const int kg = (int)(t % KG), tap = (int)(t / KG);
+        uint32_t d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int k = kg * 16 + j;
+            const uint32_t w = (k < K && c < C) ? (uint32_t)(uint8_t)W[((int64_t)k * C + c) * RS + tap] : 0u;
+            d[j >> 2] |= w << (8 * (j & 3));
+        }
+        wp[i] = uint4{d[0], d[1], d[2], d[3]};
+    }
+}
+
+template <int MODE> struct CdxTraits;
+template <> struct CdxTraits<MODE_BF16> { static constexpr int G = 8,  PL = 3; using Acc = f32x16; using Out = float; };
+template <> struct CdxTraits<MODE_I8>   { static constexpr int G = 16, PL = 1; using Acc = i32x16; using Out = int32_t; };
+
 __device__ __forceinline__ uint32_t cdx_bf16_pair(uint32_t wa, uint32_t wb, int e)
 {
     // bytes e of words wa, wb as signed codes -> two bf16 (exact), wa's in the low half
@@ -68,9 +94,11 @@ __device__ __forceinline__ uint32_t cdx_bf16_pair(uint32_t wa, uint32_t wb, int 
     return __builtin_amdgcn_perm(__float_as_uint(fb), __float_as_uint(fa), 0x07060302u);
 }
 
-template <int NB>
+template <int NB, int MODE>
 __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 {
+    using TR = CdxTraits<MODE>;
+    constexpr int G = TR::G, PL = TR::PL;                       // reduction channels per cell; weight planes
     extern __shared__ uint4 cdx_lds[];                       // [2][CDX_KGC][patch_cells]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lcol = lane & 31, lhalf = lane >> 5;
@@ -110,7 +138,7 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
         if (it < n_items) {
             const int kgl = it / n_dw, f = it - kgl * n_dw;
             const int pix0 = f_a + 4 * f;
-            item_goff[i] = kgl * 8 * a.PQ + pix0; item_k[i] = kgl * 8;
+            item_goff[i] = kgl * G * a.PQ + pix0; item_k[i] = kgl * G;
             uint32_t cells[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -122,18 +150,18 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
             item_cell[i][1] = cells[2] | (cells[3] << 16);
         }
     }
-    uint32_t raw[CDX_ITMAX][8];
+    uint32_t raw[CDX_ITMAX][G];
     const int8_t *img = a.codes + (int64_t)n * a.K * a.PQ;
     auto fetch_chunk = [&](int chunk) {
 #pragma unroll
         for (int i = 0; i < CDX_ITMAX; ++i) {
 #pragma unroll
-            for (int kq = 0; kq < 8; ++kq) raw[i][kq] = 0u;
+            for (int kq = 0; kq < G; ++kq) raw[i][kq] = 0u;
             if (item_goff[i] >= 0) {
-                const int k0 = chunk * (8 * CDX_KGC) + item_k[i];
-                const int8_t *src = img + (int64_t)chunk * (8 * CDX_KGC) * a.PQ + item_goff[i];
+                const int k0 = chunk * (G * CDX_KGC) + item_k[i];
+                const int8_t *src = img + (int64_t)chunk * (G * CDX_KGC) * a.PQ + item_goff[i];
 #pragma unroll
-                for (int kq = 0; kq < 8; ++kq)
+                for (int kq = 0; kq < G; ++kq)
                     if (k0 + kq < a.K) raw[i][kq] = *(const uint32_t *)(src + (int64_t)kq * a.PQ);
             }
         }
@@ -143,12 +171,31 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 #pragma unroll
         for (int i = 0; i < CDX_ITMAX; ++i) {
             if (item_goff[i] < 0) continue;
+            if constexpr (MODE == MODE_I8) {
+                // byte e of the 16 channel words -> the 16 bytes of pixel e's cell: four 4x4 byte transpositions
+                uint32_t t[4][4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t cell = (item_cell[i][e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                if (cell == 0xFFFFu) continue;
-                dst[cell] = uint4{cdx_bf16_pair(raw[i][0], raw[i][1], e), cdx_bf16_pair(raw[i][2], raw[i][3], e),
-                                  cdx_bf16_pair(raw[i][4], raw[i][5], e), cdx_bf16_pair(raw[i][6], raw[i][7], e)};
+                for (int g = 0; g < 4; ++g) {
+                    const uint32_t r0 = raw[i][4 * g], r1 = raw[i][4 * g + 1], r2 = raw[i][4 * g + 2], r3 = raw[i][4 * g + 3];
+                    const uint32_t x0 = __builtin_amdgcn_perm(r1, r0, 0x05010400u), x1 = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
+                    const uint32_t y0 = __builtin_amdgcn_perm(r1, r0, 0x07030602u), y1 = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
+                    t[g][0] = __builtin_amdgcn_perm(x1, x0, 0x05040100u); t[g][1] = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
+                    t[g][2] = __builtin_amdgcn_perm(y1, y0, 0x05040100u); t[g][3] = __builtin_amdgcn_perm(y1, y0, 0x07060302u);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t cell = (item_cell[i][e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    if (cell == 0xFFFFu) continue;
+                    dst[cell] = uint4{t[0][e], t[1][e], t[2][e], t[3][e]};
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t cell = (item_cell[i][e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    if (cell == 0xFFFFu) continue;
+                    dst[cell] = uint4{cdx_bf16_pair(raw[i][0], raw[i][1], e), cdx_bf16_pair(raw[i][2], raw[i][3], e),
+                                      cdx_bf16_pair(raw[i][4], raw[i][5], e), cdx_bf16_pair(raw[i][6], raw[i][7], e)};
+                }
             }
         }
     };
@@ -163,28 +210,28 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
         lane_cell[nb] = (h - h_first + a.R - 1) * a.pw + (w + a.S - 1) + lhalf * a.patch_cells;
     }
 
-    f32x16 acc[NB];
+    typename TR::Acc acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0;
 
     const bool wave_active = cb * 32 < a.C && jw0 < j_end;   // uniform per wave
     const int RS = a.R * a.S;
-    const uint4 *wlane = a.wp + (int64_t)lhalf * 3 * a.Cp + cb * 32 + lcol;
-    const int64_t kg_stride = (int64_t)3 * a.Cp;             // cells per k-group
-    auto load_a = [&](int chunk, int tap, int kk, u32x4 (&dst)[3]) {
+    const uint4 *wlane = a.wp + (int64_t)lhalf * PL * a.Cp + cb * 32 + lcol;
+    const int64_t kg_stride = (int64_t)PL * a.Cp;            // cells per k-group
+    auto load_a = [&](int chunk, int tap, int kk, u32x4 (&dst)[PL]) {
         const uint4 *p = wlane + ((int64_t)tap * a.KG + chunk * CDX_KGC + 2 * kk) * kg_stride;
 #pragma unroll
-        for (int pl = 0; pl < 3; ++pl) { const uint4 t = p[(int64_t)pl * a.Cp]; dst[pl] = u32x4{t.x, t.y, t.z, t.w}; }
+        for (int pl = 0; pl < PL; ++pl) { const uint4 t = p[(int64_t)pl * a.Cp]; dst[pl] = u32x4{t.x, t.y, t.z, t.w}; }
     };
 
     fetch_chunk(0);
-    u32x4 a0[3], a1[3];                                       // weight fragments of kk = 0 / kk = 1 (ping-pong)
+    u32x4 a0[PL], a1[PL];                                     // weight fragments of kk = 0 / kk = 1 (ping-pong)
     if (wave_active) load_a(0, 0, 0, a0);
     __syncthreads();                                          // zero fill done before the first patch writes
 
-    auto multiply = [&](const uint4 *pb, int off, const u32x4 (&af)[3]) {
+    auto multiply = [&](const uint4 *pb, int off, const u32x4 (&af)[PL]) {
         u32x4 bfrag[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -192,9 +239,9 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
             bfrag[nb] = u32x4{t.x, t.y, t.z, t.w};
         }
 #pragma unroll
-        for (int pl = 0; pl < 3; ++pl)
+        for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) Mma<MODE_BF16>::run(af[pl], bfrag[nb], acc[nb]);
+            for (int nb = 0; nb < NB; ++nb) Mma<MODE>::run(af[pl], bfrag[nb], acc[nb]);
     };
 
     for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
@@ -220,8 +267,8 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 
     // ---- store: lane holds pixel column lcol, channel rows 8*(v/4) + 4*lhalf + v%4 of its block ----
     if (wave_active) {
-        float *out = a.dX + (int64_t)n * a.C * a.PI;          // offsets inside one image fit 31 bits (host check)
-        const float sc = a.scale.get();
+        typename TR::Out *out = (typename TR::Out *)a.dX + (int64_t)n * a.C * a.PI;   // offsets inside one image fit 31 bits (host check)
+        const float sc = MODE == MODE_I8 ? 1.0f : a.scale.get();
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int j = jw0 + 32 * nb + lcol;
@@ -231,7 +278,9 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int c = c0 + 8 * (v >> 2) + (v & 3);
-                if (c < a.C) out[off] = acc[nb][v] * sc;
+                if (c < a.C) {
+                    if constexpr (MODE == MODE_I8) out[off] = acc[nb][v]; else out[off] = acc[nb][v] * sc;
+                }
                 off += (v & 3) == 3 ? 5 * a.PI : a.PI;
             }
         }

@@ -431,6 +431,80 @@ __global__ __launch_bounds__(256) void std_finish_kernel(double *a1, double *a2,
 
 }  // namespace
 
+// ------------------------------------------------------------------------------------------------
+// Symmetric int8 quantiser of weights and activations (Sec. "Quantizing forward pass": the forward pass
+// computes with 8-bit weights and activations; the paper takes the quantiser from the work it cites
+// and does not print it, so the plainest one is used).  One scale per tensor:
+//   amax = max |x_i| over the finite x_i;   scale = amax / 127;   inv = 127 / amax   (fp32 divisions)
+//   q_i  = clamp(round-half-even(x_i * inv), -127, 127)   (one fp32 multiplication)
+// NaN -> 0, +-Inf -> +-127; amax == 0 (or nothing finite): scale = inv = 0 and every finite q_i is 0.
+// ------------------------------------------------------------------------------------------------
+constexpr int kQuantBlocks = 2048;
+
+__global__ __launch_bounds__(256) void absmax_kernel(const float *x, int64_t n, uint32_t *partial)
+{
+    // magnitudes of finite floats order like their bit patterns
+    uint32_t m = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const uint32_t b = __float_as_uint(x[i]) & 0x7fffffffu;
+        if (b < 0x7f800000u) m = b > m ? b : m;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { const uint32_t o = __shfl_xor(m, off); m = o > m ? o : m; }
+    __shared__ uint32_t wm[4];
+    if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) m = wm[w] > m ? wm[w] : m;
+        partial[blockIdx.x] = m;
+    }
+}
+
+__global__ __launch_bounds__(256) void absmax_finish_kernel(const uint32_t *partial, int blocks, float *scale_out)
+{
+    uint32_t m = 0;
+    for (int i = threadIdx.x; i < blocks; i += 256) m = partial[i] > m ? partial[i] : m;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { const uint32_t o = __shfl_xor(m, off); m = o > m ? o : m; }
+    __shared__ uint32_t wm[4];
+    if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) m = wm[w] > m ? wm[w] : m;
+        const float amax = __uint_as_float(m);
+        scale_out[0] = amax > 0.0f ? __fdiv_rn(amax, 127.0f) : 0.0f;
+        scale_out[1] = amax > 0.0f ? __fdiv_rn(127.0f, amax) : 0.0f;
+    }
+}
+
+__device__ __forceinline__ int quantize_one(float x, float inv)
+{
+    const uint32_t b = __float_as_uint(x) & 0x7fffffffu;
+    if (b > 0x7f800000u) return 0;                                         // NaN
+    if (b == 0x7f800000u) return x > 0.0f ? 127 : -127;                    // +-Inf
+    const float t = __builtin_rintf(__fmul_rn(x, inv));                    // ties to even
+    return (int)fminf(fmaxf(t, -127.0f), 127.0f);
+}
+
+__global__ __launch_bounds__(256) void quantize_int8_kernel(const float *x, int64_t n, const float *scale, int8_t *q)
+{
+    const float inv = scale[1];
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        q[i] = (int8_t)quantize_one(x[i], inv);
+}
+
+size_t quantize_scratch_bytes(int64_t) { return align_up((size_t)kQuantBlocks * sizeof(uint32_t), 256); }
+
+hipError_t launch_quantize_int8(const float *x, int64_t n, int8_t *q, float *scale_out, void *scratch, hipStream_t st)
+{
+    int64_t blocks = (n + 1023) / 1024;                                    // four elements per thread at least
+    blocks = blocks < 1 ? 1 : blocks > kQuantBlocks ? kQuantBlocks : blocks;
+    hipLaunchKernelGGL(absmax_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, n, (uint32_t *)scratch);
+    hipLaunchKernelGGL(absmax_finish_kernel, dim3(1), dim3(256), 0, st, (const uint32_t *)scratch, (int)blocks, scale_out);
+    hipLaunchKernelGGL(quantize_int8_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, n, (const float *)scale_out, q);
+    return hipGetLastError();
+}
+
 size_t step_size_scratch_bytes(int64_t n)
 {
     const int64_t wgs = (n + 4095) / 4096 > 0 ? (n + 4095) / 4096 : 1;

@@ -62,14 +62,15 @@ hipError_t run_gemm(const AL &al, const BL &bl, const OM &om, int M, int N, int 
 }
 
 // Weights re-laid for the dX product of a convolution: Wt[(r*S+s)*Kp + k][c] = W[k][c][r][s], zero for k >= K.
-__global__ __launch_bounds__(256) void conv_weight_relayout_kernel(const float *W, float *Wt, ConvGeom g)
+template <class T>
+__global__ __launch_bounds__(256) void conv_weight_relayout_kernel(const T *W, T *Wt, ConvGeom g)
 {
     const int64_t total = (int64_t)g.R * g.S * g.Kp * g.C;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
         const int c = (int)(i % g.C);
         const int64_t kk = i / g.C;
         const int k = (int)(kk % g.Kp), rs = (int)(kk / g.Kp);
-        Wt[i] = k < g.K ? W[((int64_t)k * g.C + c) * g.R * g.S + rs] : 0.0f;
+        Wt[i] = k < g.K ? W[((int64_t)k * g.C + c) * g.R * g.S + rs] : (T)0;
     }
 }
 
@@ -97,7 +98,7 @@ size_t relayout_bytes(int64_t K, int64_t C, int64_t R, int64_t S)
 // Geometry of the fast dX kernel for one problem, or ok == false when the generic kernel has to serve.
 struct ConvDxPlan { bool ok; int nb; ConvDxArgs args; size_t lds_bytes; int grid; };
 
-ConvDxPlan conv_dx_plan(const ConvArgs &a)
+ConvDxPlan conv_dx_plan(const ConvArgs &a, bool i8 = false)
 {
     ConvDxPlan pl;
     pl.ok = false;
@@ -109,7 +110,8 @@ ConvDxPlan conv_dx_plan(const ConvArgs &a)
     if (k.PQ % 4 || ((uintptr_t)a.codes % 4)) return pl;         // the patch fill reads aligned dwords of a code plane
     if ((int64_t)(k.C + 32) * k.PI >= ((int64_t)1 << 31)) return pl;   // 32-bit offsets inside one image
     k.Cp = (k.C + 31) / 32 * 32;
-    k.KG = (k.K + 31) / 32 * 4;
+    const int chunk_k = CDX_KGC * (i8 ? 16 : 8);                 // reduction channels per chunk
+    k.KG = (k.K + chunk_k - 1) / chunk_k * CDX_KGC;
     k.n_chunks = k.KG / CDX_KGC;
     const int ncb = k.Cp / 32;
     k.wc = ncb >= 3 ? 4 : ncb;
@@ -360,6 +362,22 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
     hipError_t e = hipSuccess;
     RowMajorOut om{a.in};
     StatsJob pending = a.stats_job;
+    if (a.codes && a.W8) {
+        // full 8-bit mode: both products on int8 matrix cores, exact int32 results
+        if (pending.n || pending.bias_len) { e = launch_stats_job(pending, s); if (e != hipSuccess) return e; }
+        if (a.dX) {
+            MatrixLoader<MODE_I8, true, true>   al{a.codes, a.out, B, out};
+            MatrixLoader<MODE_I8, false, false> bl{a.W8, a.in, in, out};
+            e = run_gemm<MODE_I8>(al, bl, om, B, in, out, k_step<MODE_I8>(), Scale{1.0f, nullptr}, (int32_t *)a.dX, a.scratch, a.scratch_bytes, s);
+            if (e != hipSuccess) return e;
+        }
+        if (a.dW) {
+            MatrixLoader<MODE_I8, true, false>  al{a.codes, a.out, out, B};
+            MatrixLoader<MODE_I8, false, false> bl{(const int8_t *)a.X, a.in, in, B};
+            e = run_gemm<MODE_I8>(al, bl, om, out, in, B, k_step<MODE_I8>(), Scale{1.0f, nullptr}, (int32_t *)a.dW, a.scratch, a.scratch_bytes, s);
+        }
+        return e;
+    }
     if (a.codes) {
         // fast path: one launch for every product whose layout allows it
         const bool dx_fast = a.dX && fc_fast_ok(true, a.codes, a.out, a.W, a.in, B, in, a.dX);
@@ -487,34 +505,43 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
 template <int MODE_G>
 static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipStream_t s)
 {
-    // MODE_G: MODE_BF16 (codes) or MODE_F32 (dense).  Weights are fp32 in every mode.
-    if constexpr (MODE_G == MODE_BF16) {
-        ConvDxPlan pl = conv_dx_plan(a);
+    // MODE_G: MODE_BF16 (codes, fp32 weights), MODE_I8 (codes, int8 weights) or MODE_F32 (dense).
+    if constexpr (MODE_G != MODE_F32) {
+        constexpr bool I8 = MODE_G == MODE_I8;
+        ConvDxPlan pl = conv_dx_plan(a, I8);
         if (pl.ok) {
             ConvDxArgs &k = pl.args;
             k.codes = (const int8_t *)grad; k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale;
             const int64_t cells = (int64_t)k.R * k.S * k.KG * k.Cp;
             const int pb = (int)((cells + 255) / 256 < 4096 ? (cells + 255) / 256 : 4096);
-            hipLaunchKernelGGL(conv_dx_weight_prep_kernel, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch,
-                               k.K, k.C, k.R * k.S, k.KG, k.Cp);
-            if (pl.nb == 7) hipLaunchKernelGGL(conv_dx_kernel<7>, dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
-            else            hipLaunchKernelGGL(conv_dx_kernel<4>, dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
+            if constexpr (I8) {
+                hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch,
+                                   k.K, k.C, k.R * k.S, k.KG, k.Cp);
+            } else {
+                hipLaunchKernelGGL(conv_dx_weight_prep_kernel, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch,
+                                   k.K, k.C, k.R * k.S, k.KG, k.Cp);
+            }
+            if (pl.nb == 7) hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
+            else            hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
             return hipGetLastError();
         }
     }
     ConvGeom g = make_geom(a, ModeTraits<MODE_G>::KCH, k_step<MODE_G>());
-    float *Wt = (float *)a.scratch;
+    using WT = typename std::conditional<MODE_G == MODE_I8, int8_t, float>::type;      // int8 weights in the full 8-bit mode
+    using Acc = typename ModeTraits<MODE_G>::Acc;
+    WT *Wt = (WT *)a.scratch;
+    const WT *Wsrc = MODE_G == MODE_I8 ? (const WT *)a.W8 : (const WT *)a.W;
     const size_t rb = relayout_bytes(a.K, a.C, a.R, a.S);
     const int64_t total = (int64_t)g.R * g.S * g.Kp * g.C;
     int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
-    hipLaunchKernelGGL(conv_weight_relayout_kernel, dim3(blocks), dim3(256), 0, s, a.W, Wt, g);
+    hipLaunchKernelGGL(conv_weight_relayout_kernel<WT>, dim3(blocks), dim3(256), 0, s, Wsrc, Wt, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int M = g.N * g.H * g.Wd, Kred = g.R * g.S * g.Kp;
     ConvDxGradLoader<MODE_G> al{(const typename GradElem<MODE_G>::T *)grad, g};
     MatrixLoader<MODE_G, false, false> bl{Wt, g.C, g.C, Kred};
     ConvDxOut om{g.C, g.H * g.Wd};
-    return run_gemm<MODE_G>(al, bl, om, M, g.C, Kred, k_step<MODE_G>(), scale, a.dX,
+    return run_gemm<MODE_G>(al, bl, om, M, g.C, Kred, k_step<MODE_G>(), scale, (Acc *)a.dX,
                             (char *)a.scratch + rb, a.scratch_bytes - rb, s);
 }
 
@@ -544,6 +571,12 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s)
 {
     hipError_t e = hipSuccess;
+    if (a.codes && a.W8) {
+        // full 8-bit mode: int8 weights and activations, exact int32 results
+        if (a.dX) { e = conv_dx<MODE_I8>(a, a.codes, Scale{1.0f, nullptr}, s); if (e != hipSuccess) return e; }
+        if (a.dW) e = conv_dw<MODE_I8>(a, a.codes, Scale{1.0f, nullptr}, s);
+        return e;
+    }
     if (a.codes) {
         if (a.dX) { e = conv_dx<MODE_BF16>(a, a.codes, Scale{a.step, a.step_dev}, s); if (e != hipSuccess) return e; }
         if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_BF16>(a, a.codes, Scale{a.step, a.step_dev}, s) : conv_dw<MODE_I8>(a, a.codes, Scale{1.0f, nullptr}, s);

@@ -154,3 +154,30 @@ def test_algorithm1_entry_points_reject_bad_arguments():
     assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 2, 1, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == UNSUPPORTED
     assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 1, 1, -1.0, 1, 0, None, FAKE, FAKE, None, None, None) == STEP
     assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 1, 1, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == WORKSPACE
+
+
+def test_full_8bit_entry_points_reject_bad_arguments():
+    raw = dbp.lib()
+    wq = dbp.quantize_int8_workspace_bytes(1000)
+    assert wq >= 256 and dbp.quantize_int8_workspace_bytes(0) == 0
+    assert raw.dbp_quantize_int8(None, 16, FAKE, FAKE, FAKE, wq, None) == NULL
+    assert raw.dbp_quantize_int8(FAKE, 16, None, FAKE, FAKE, wq, None) == NULL
+    assert raw.dbp_quantize_int8(FAKE, 16, FAKE, None, FAKE, wq, None) == NULL
+    assert raw.dbp_quantize_int8(FAKE, 0, FAKE, FAKE, FAKE, wq, None) == SHAPE
+    assert raw.dbp_quantize_int8(FAKE, 16, FAKE, FAKE, None, wq, None) == WORKSPACE
+    assert raw.dbp_quantize_int8(FAKE, 16, FAKE, FAKE, FAKE, 8, None) == WORKSPACE
+    f = dbp.dithered_linear_backward_q8
+    assert _code(f, None, FAKE, FAKE, 8, 16, 12, 1.0, 1, 0, None, FAKE, FAKE, None) == NULL
+    assert _code(f, FAKE, None, FAKE, 8, 16, 12, 1.0, 1, 0, None, FAKE, None, None) == NULL           # dX32 needs W8
+    assert _code(f, FAKE, FAKE, None, 8, 16, 12, 1.0, 1, 0, None, None, FAKE, None) == NULL           # dW32 needs X8
+    assert _code(f, FAKE, FAKE, FAKE, 8, 16, 12, 1.0, 1, 0, None, None, None, None) == NULL
+    assert _code(f, FAKE, FAKE, FAKE, 8, 0, 12, 1.0, 1, 0, None, FAKE, FAKE, None) == SHAPE
+    assert _code(f, FAKE, FAKE, FAKE, 8, 16, 12, 0.0, 1, 0, None, FAKE, FAKE, None) == STEP
+    assert _code(f, FAKE, FAKE, FAKE, 8, 16, 140000, 1.0, 1, 0, None, FAKE, None, None) == OVERFLOW  # 140000*127*127 >= 2^31
+    assert _code(f, FAKE, FAKE, FAKE, 140000, 16, 12, 1.0, 1, 0, None, None, FAKE, None) == OVERFLOW
+    assert _code(f, FAKE, FAKE, FAKE, 8, 16, 12, 1.0, 1, 0, None, FAKE, FAKE, None) == WORKSPACE
+    g = dbp.dithered_conv2d_backward_q8
+    assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 2, 1, 1.0, 1, 0, None, FAKE, FAKE, None) == UNSUPPORTED
+    assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 1, 1, -1.0, 1, 0, None, FAKE, FAKE, None) == STEP
+    assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 20000, 3, 3, 1, 1, 1.0, 1, 0, None, FAKE, None, None) == OVERFLOW
+    assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 1, 1, 1.0, 1, 0, None, FAKE, FAKE, None) == WORKSPACE
