@@ -434,9 +434,15 @@ __global__ __launch_bounds__(256) void fc2_reduce_kernel(FcPairArgs a, int tiles
     const float4 *all = (const float4 *)(p.partial + (int64_t)tile * p.n_split * (FC2_TM * FC2_TN)) + slot * 256 + tid;
     const int col = tile_n + 4 * (lane & 31);
     float4 sum = float4{0.f, 0.f, 0.f, 0.f};
-    for (int q = 0; q < p.n_split; ++q) {
-        const float4 t = all[(int64_t)q * (FC2_TM * FC2_TN / 4)];
-        sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
+    // eight loads in flight at a time (the loop is bound by their latency); the additions stay in split order
+    const int n_split = p.n_split;
+    for (int q = 0; q < n_split; q += 8) {
+        float4 t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = all[(int64_t)min(q + j, n_split - 1) * (FC2_TM * FC2_TN / 4)];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (q + j < n_split) { sum.x += t[j].x; sum.y += t[j].y; sum.z += t[j].z; sum.w += t[j].w; }
     }
     const int i = slot >> 4, v = slot & 15;
     const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
