@@ -307,6 +307,7 @@ def bench_conv_configs(dbp, workloads, torch, np, timed, stream):
     res = {}
     problems = [("cfg3", workloads.config3()), ("cfg4a", workloads.config4a()), ("cfg4b", workloads.config4b())]
     problems += [("cfg5_s%g" % s, workloads.config5(s)) for s in (0.5, 0.9, 0.99)]
+    problems += [("resnet_3x3_stride2", workloads.resnet_downsample())]
     for name, p in problems:
         N, Cc, H, Wd = p.X.shape
         K, _, R, S = p.W.shape
@@ -316,25 +317,25 @@ def bench_conv_configs(dbp, workloads, torch, np, timed, stream):
         codes = torch.empty(p.delta.shape, dtype=torch.int8, device=dev)
         dX = torch.empty(p.X.shape, dtype=torch.float32, device=dev)
         dW = torch.empty(p.W.shape, dtype=torch.int32 if i8 else torch.float32, device=dev)
-        ws = torch.empty(dbp.conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, 1, p.pad, xd), dtype=torch.uint8, device=dev)
+        ws = torch.empty(dbp.conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, p.stride, p.pad, xd), dtype=torch.uint8, device=dev)
         st = torch.zeros(32, dtype=torch.uint8, device=dev)
-        t = timed(lambda i: dbp.dithered_conv2d_backward(d, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, p.step, p.seed, 0,
+        t = timed(lambda i: dbp.dithered_conv2d_backward(d, W, X, xd, N, Cc, H, Wd, K, R, S, p.stride, p.pad, p.step, p.seed, 0,
                                                          codes, dX, dW, ws, st, dbp.PATH_AUTO, stream), 5, warm=1)
         P, Q = p.delta.shape[2:]
         flops = 2 * 2.0 * N * K * P * Q * Cc * R * S
         row = {"ms": t * 1e3, "dense_equiv_tflops": flops / t / 1e12, "sparsity": 1 - dbp.Stats.from_tensor(st).nnz / p.delta.size}
-        t_x = timed(lambda i: dbp.conv2d_products(codes, None, p.step, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, dX, None, ws,
+        t_x = timed(lambda i: dbp.conv2d_products(codes, None, p.step, W, X, xd, N, Cc, H, Wd, K, R, S, p.stride, p.pad, dX, None, ws,
                                                   dbp.PATH_MFMA, stream), 5, warm=1)
-        t_w = timed(lambda i: dbp.conv2d_products(codes, None, p.step, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, None, dW, ws,
+        t_w = timed(lambda i: dbp.conv2d_products(codes, None, p.step, W, X, xd, N, Cc, H, Wd, K, R, S, p.stride, p.pad, None, dW, ws,
                                                   dbp.PATH_MFMA, stream), 5, warm=1)
         row["dX_us"], row["dW_us"], row["nsd_us"] = t_x * 1e6, t_w * 1e6, max(t - t_x - t_w, 0.0) * 1e6
         if not i8:
-            t_d = timed(lambda i: dbp.dense_conv2d_backward(d, W, X, xd, N, Cc, H, Wd, K, R, S, 1, p.pad, dX, dW, ws, stream), 3, warm=1)
+            t_d = timed(lambda i: dbp.dense_conv2d_backward(d, W, X, xd, N, Cc, H, Wd, K, R, S, p.stride, p.pad, dX, dW, ws, stream), 3, warm=1)
             row["same_library_dense_ms"] = t_d * 1e3
             # context only: the vendor library's fp32 convolution backward on the same shapes (dense gradient)
             dt = torch.from_numpy(p.delta).to(dev)
             torch.backends.cudnn.allow_tf32 = False
-            f = lambda i: torch.ops.aten.convolution_backward(dt, X, W, None, [1, 1], [p.pad, p.pad], [1, 1], False, [0, 0], 1,
+            f = lambda i: torch.ops.aten.convolution_backward(dt, X, W, None, [p.stride, p.stride], [p.pad, p.pad], [1, 1], False, [0, 0], 1,
                                                               [True, True, False])
             try:
                 row["torch_conv_backward_fp32_ms"] = timed(f, 3, warm=2) * 1e3

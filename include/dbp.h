@@ -58,7 +58,7 @@ typedef enum {
     DBP_ERR_STEP = 3,          /* Delta is <= 0, NaN, Inf, or 1/Delta is not finite            */
     DBP_ERR_DTYPE = 4,         /* unknown dbp_dtype                                            */
     DBP_ERR_WORKSPACE = 5,     /* workspace NULL/too small/misaligned                          */
-    DBP_ERR_UNSUPPORTED = 6,   /* valid request this build does not implement (e.g. stride>1)  */
+    DBP_ERR_UNSUPPORTED = 6,   /* valid request this build does not implement (e.g. conv gather)*/
     DBP_ERR_OVERFLOW = 7,      /* int32 weight gradient could overflow: reduction*127*127>=2^31 */
     DBP_ERR_DEVICE = 8         /* a HIP call failed (launch error, wrong device, ...)          */
 } dbp_status;
@@ -160,7 +160,7 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
  *   dX[n,c,h,w] = Delta * sum_{k,r,s} code[n,k,p,q] W[k,c,r,s],  h = p*stride+r-pad, w = q*stride+s-pad
  *   dW[k,c,r,s] = Delta * sum_{n,p,q} code[n,k,p,q] X[n,c,p*stride+r-pad,q*stride+s-pad]
  * computed as implicit-im2col GEMMs (no im2col buffer is materialised).  x_dtype as above.
- * Errors as above; stride != 1 -> DBP_ERR_UNSUPPORTED in this build.
+ * Errors as above.  Stride 1 runs on the specialised kernels, other strides on the generic implicit-im2col kernel.
  */
 dbp_status dithered_conv2d_backward(const float *delta, const float *W, const void *X,
                                     dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H,
@@ -294,7 +294,7 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
  *
  * dithered_*_backward_q8: NSD of delta, then both products on int8 matrix cores with exact int32 sums:
  *     dX32[b,i] = sum_o k[b,o] * W8[o,i]          dW32[o,i] = sum_b k[b,o] * X8[b,i]        (conv: the adjoints of
- *     the stride-1 cross-correlation, as in dithered_conv2d_backward).
+ *     the cross-correlation, as in dithered_conv2d_backward).
  *   The real gradients are Delta*scale_W*dX32 and Delta*scale_X*dW32; the caller applies the scales (in the weight
  *   update, which stays in full precision).  dX32 / dW32 nullable (not both); W8 needed for dX32, X8 for dW32.
  *   Workspace: dbp_linear_workspace_bytes / dbp_conv2d_workspace_bytes (any path, DBP_I8).

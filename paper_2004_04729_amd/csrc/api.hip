@@ -89,7 +89,7 @@ dbp_status check_conv_dims(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t 
                            int64_t stride, int64_t pad, int64_t *P, int64_t *Q)
 {
     if (N <= 0 || C <= 0 || H <= 0 || Wd <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return DBP_ERR_SHAPE;
-    if (N > 65535 || C > 65535 || K > 65535 || H > 65535 || Wd > 65535 || R > 255 || S > 255 || pad > 255) return DBP_ERR_SHAPE;
+    if (N > 65535 || C > 65535 || K > 65535 || H > 65535 || Wd > 65535 || R > 255 || S > 255 || pad > 255 || stride > 255) return DBP_ERR_SHAPE;
     if (H + 2 * pad < R || Wd + 2 * pad < S) return DBP_ERR_SHAPE;
     *P = (H + 2 * pad - R) / stride + 1;
     *Q = (Wd + 2 * pad - S) / stride + 1;
@@ -174,13 +174,13 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     if (!step_dev && !step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (stride != 1 || path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
+    const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     ConvArgs a;
     a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
-    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
+    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
@@ -226,8 +226,7 @@ size_t dbp_conv2d_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, i
     int64_t P, Q;
     if (check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q) != DBP_OK) return 0;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return 0;
-    if (stride != 1) return 0;
-    return carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad)).total;
+    return carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride)).total;
 }
 
 dbp_status nsd_quantize(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
@@ -299,9 +298,9 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
     if (!step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (stride != 1 || path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad));
+    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
@@ -341,14 +340,13 @@ dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *
     dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
     if (st != DBP_OK) return st;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (stride != 1) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dX) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 128 * 128 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad);
+    const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     ConvArgs a;
     a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
-    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
+    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
@@ -407,10 +405,9 @@ dbp_status dithered_conv2d_backward_q8(const float *delta, const int8_t *W8, con
     dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
     if (st != DBP_OK) return st;
     if (!step_ok(step)) return DBP_ERR_STEP;
-    if (stride != 1) return DBP_ERR_UNSUPPORTED;
     if (dX32 && K * R * S * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     if (dW32 && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad));
+    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
@@ -419,7 +416,7 @@ dbp_status dithered_conv2d_backward_q8(const float *delta, const int8_t *W8, con
     if (st != DBP_OK) return st;
     ConvArgs a;
     a.codes = k; a.dense = nullptr; a.step = 1.0f; a.step_dev = nullptr; a.W = nullptr; a.W8 = W8 ? W8 : X8; a.X = X8;
-    a.x_dtype = DBP_I8; a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad;
+    a.x_dtype = DBP_I8; a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = (float *)dX32; a.dW = dW32; a.scratch = ws + c.scratch_offset; a.scratch_bytes = workspace_bytes - c.scratch_offset;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
@@ -522,9 +519,9 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     if (!(s > 0.0f) || !std::isfinite(s)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (stride != 1 || path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad));
+    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     const LayerCarve lc = layer_carve(c.total, N * K * P * Q, K);
     if (!workspace || workspace_bytes < lc.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     if (!aligned(delta_a, 4) || (act && !aligned(act, 4)) || (step_out && !aligned(step_out, 8))) return DBP_ERR_SHAPE;

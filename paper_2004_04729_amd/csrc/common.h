@@ -106,7 +106,7 @@ struct ConvArgs {
     const int8_t *W8;          // full 8-bit mode: int8 weights instead of W; dX is then exact int32 (nullable)
     const void   *X;           // [N,C,H,Wd]
     dbp_dtype     x_dtype;
-    int64_t       N, C, H, Wd, K, R, S, pad;
+    int64_t       N, C, H, Wd, K, R, S, pad, stride;
     float        *dX;
     void         *dW;
     void         *scratch;
@@ -114,7 +114,7 @@ struct ConvArgs {
     StatsJob      stats_job;
 };
 size_t     linear_scratch_bytes(int64_t B, int64_t in, int64_t out);
-size_t     conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad);
+size_t     conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride = 1);
 hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s);
 

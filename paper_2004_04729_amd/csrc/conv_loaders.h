@@ -1,10 +1,11 @@
 // Implicit-im2col loaders: the convolutional analogues of Eqs. (qda)/(qdw) as GEMMs whose operands
-// are never materialised.  Stride 1, zero padding, NCHW / KCRS storage.
+// are never materialised.  Any stride, zero padding, NCHW / KCRS storage.
 //
 //   dX:  rows m = (n,h,w) output pixels, cols c, reduction kk = (r,s,k) with k fastest (k padded to Kp)
-//          A(m,kk) = code[n,k,h+pad-r,w+pad-s]      B(c,kk) = Wt[kk][c]  (weights re-laid by prep kernel)
+//          A(m,kk) = code[n,k,(h+pad-r)/st,(w+pad-s)/st] where both divisions are exact, else 0
+//                                                   B(c,kk) = Wt[kk][c]  (weights re-laid by prep kernel)
 //   dW:  rows k output channels, cols j = (c,r,s), reduction kk = (n,pq) with pq fastest (pq padded to PQp)
-//          A(k,kk) = code[n,k,pq]                   B(j,kk) = X[n,c,p+r-pad,q+s-pad]
+//          A(k,kk) = code[n,k,pq]                   B(j,kk) = X[n,c,p*st+r-pad,q*st+s-pad]
 #pragma once
 #include "gemm_core.h"
 
@@ -12,6 +13,7 @@ namespace dbp {
 
 struct ConvGeom {
     int N, C, H, Wd, K, R, S, pad, P, Q;
+    int st;      // stride
     int Kp;      // K rounded up to the chunk length (dX reduction padding)
     int PQp;     // P*Q rounded up to the K step (dW reduction padding)
 };
@@ -55,9 +57,16 @@ template <int MODE> struct ConvDxGradLoader {
     {
         const int rs = kk0 / g.Kp, k0 = kk0 - rs * g.Kp;
         const int r = rs / g.S, s = rs - r * g.S;
-        const int p = rw.h + g.pad - r, q = rw.w + g.pad - s;
+        int p = rw.h + g.pad - r, q = rw.w + g.pad - s;
         const int nv = g.K - k0;
-        if (!rw.ok || rs >= g.R * g.S || nv <= 0 || p < 0 || p >= g.P || q < 0 || q >= g.Q) return raw_zero<Raw>();
+        if (!rw.ok || rs >= g.R * g.S || nv <= 0 || p < 0 || q < 0) return raw_zero<Raw>();
+        if (g.st != 1) {
+            // an input pixel receives from output pixel p only if p*st + r - pad == h exactly
+            const int pd = p / g.st, qd = q / g.st;
+            if (pd * g.st != p || qd * g.st != q) return raw_zero<Raw>();
+            p = pd; q = qd;
+        }
+        if (p >= g.P || q >= g.Q) return raw_zero<Raw>();
         const int64_t pq = (int64_t)g.P * g.Q;
         return RunLoad<KCH, Raw, T>::strided(base + rw.img + (int64_t)k0 * pq + (int64_t)p * g.Q + q, pq, nv);
     }
@@ -93,7 +102,7 @@ template <class T> __device__ __forceinline__ void conv_act_walk(const T *X, con
     const T *img = X + ((int64_t)n * g.C + c) * g.H * g.Wd;
     const bool n_ok = n < g.N;
     for (int j = 0; j < kch; ++j) {
-        const int h = p + r - g.pad, w = q + s - g.pad;
+        const int h = p * g.st + r - g.pad, w = q * g.st + s - g.pad;
         T v = 0;
         if (n_ok && p < g.P && h >= 0 && h < g.H && w >= 0 && w < g.Wd) v = img[(int64_t)h * g.Wd + w];
         vals[j] = v;

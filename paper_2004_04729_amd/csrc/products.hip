@@ -78,9 +78,9 @@ ConvGeom make_geom(const ConvArgs &a, int kch, int kstep)
 {
     ConvGeom g;
     g.N = (int)a.N; g.C = (int)a.C; g.H = (int)a.H; g.Wd = (int)a.Wd; g.K = (int)a.K; g.R = (int)a.R; g.S = (int)a.S;
-    g.pad = (int)a.pad;
-    g.P = g.H + 2 * g.pad - g.R + 1;
-    g.Q = g.Wd + 2 * g.pad - g.S + 1;
+    g.pad = (int)a.pad; g.st = (int)a.stride;
+    g.P = (g.H + 2 * g.pad - g.R) / g.st + 1;
+    g.Q = (g.Wd + 2 * g.pad - g.S) / g.st + 1;
     g.Kp = (g.K + kch - 1) / kch * kch;
     g.PQp = (g.P * g.Q + kstep - 1) / kstep * kstep;
     return g;
@@ -103,6 +103,7 @@ ConvDxPlan conv_dx_plan(const ConvArgs &a, bool i8 = false)
     ConvDxPlan pl;
     pl.ok = false;
     ConvDxArgs &k = pl.args;
+    if (a.stride != 1) return pl;                                // the fast kernels are stride-1 kernels
     k.N = (int)a.N; k.C = (int)a.C; k.H = (int)a.H; k.Wd = (int)a.Wd; k.K = (int)a.K; k.R = (int)a.R; k.S = (int)a.S;
     k.pad = (int)a.pad;
     k.P = k.H + 2 * k.pad - k.R + 1; k.Q = k.Wd + 2 * k.pad - k.S + 1;
@@ -334,9 +335,9 @@ size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
     return (generic > fast ? generic : fast) + 256;
 }
 
-size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad)
+size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride)
 {
-    const int64_t P = H + 2 * pad - R + 1, Q = Wd + 2 * pad - S + 1;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
     auto part = [](int64_t M, int64_t Nn, int64_t Kr, int64_t gran) {
         int64_t tiles = ((M + TM - 1) / TM) * ((Nn + TN - 1) / TN);
         Split sp = choose_split(tiles, Kr, (int)gran);
@@ -500,7 +501,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------------
-// Convolution (stride 1).
+// Convolution (fast kernels: stride 1; any stride through the generic kernel).
 // ------------------------------------------------------------------------------------------------
 template <int MODE_G>
 static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipStream_t s)
@@ -552,6 +553,7 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
     const size_t rb = relayout_bytes(a.K, a.C, a.R, a.S);
     if constexpr (MODE != MODE_F32) {
         ConvDwPlan pl = conv_dw_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad, MODE == MODE_I8);
+        if (a.stride != 1) pl.ok = false;                            // the fast kernel is a stride-1 kernel
         const size_t xal = MODE == MODE_I8 ? 4 : 16;                 // aligned 4-element loads of both operands
         if (pl.ok && rb + pl.partial_bytes <= a.scratch_bytes && (uintptr_t)a.X % xal == 0 && (uintptr_t)grad % 4 == 0) {
             ConvDwArgs &k = pl.args;

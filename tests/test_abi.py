@@ -53,7 +53,7 @@ def test_workspace_sizes():
     assert dbp.linear_workspace_bytes(64, 784, 300) > 64 * 300
     assert dbp.linear_workspace_bytes(0, 784, 300) == 0 and dbp.linear_workspace_bytes(64, 784, 300, 7) == 0
     assert dbp.conv2d_workspace_bytes(128, 64, 32, 32, 64, 3, 3, 1, 1) > 128 * 64 * 32 * 32
-    assert dbp.conv2d_workspace_bytes(128, 64, 32, 32, 64, 3, 3, 2, 1) == 0       # stride 2 not in this build
+    assert dbp.conv2d_workspace_bytes(128, 64, 32, 32, 64, 3, 3, 2, 1) > 128 * 64 * 16 * 16      # stride 2: P = Q = 16
     assert dbp.conv2d_workspace_bytes(1, 1, 2, 2, 1, 5, 5, 1, 0) == 0             # kernel larger than input
 
 
@@ -112,11 +112,12 @@ def test_conv_argument_errors():
     assert call(delta=None) == NULL and call(dX=None, dW=None) == NULL
     assert call(N=0) == SHAPE and call(R=9, pad=0, H=4) == SHAPE and call(pad=-1) == SHAPE
     assert call(step=float("nan")) == STEP and call(xd=3) == DTYPE
-    assert call(stride=2) == UNSUPPORTED and call(path=2) == UNSUPPORTED
+    assert call(stride=0) == SHAPE and call(path=2) == UNSUPPORTED
     assert call(wsb=1000) == WORKSPACE
     assert call(xd=1, N=64, H=64, Wd=64) == OVERFLOW
     g = dbp.lib().dense_conv2d_backward
-    assert g(FAKE, FAKE, FAKE, 0, 2, 3, 8, 8, 4, 3, 3, 2, 1, FAKE, FAKE, FAKE, big, None) == UNSUPPORTED
+    assert g(FAKE, FAKE, FAKE, 0, 2, 3, 8, 8, 4, 3, 3, 0, 1, FAKE, FAKE, FAKE, big, None) == SHAPE          # stride 0
+    assert g(FAKE, FAKE, FAKE, 0, 2, 3, 8, 8, 4, 3, 3, 2, 1, FAKE, FAKE, FAKE, 64, None) == WORKSPACE      # stride 2 is served
     assert g(FAKE, FAKE, None, 0, 2, 3, 8, 8, 4, 3, 3, 1, 1, FAKE, FAKE, FAKE, big, None) == NULL
 
 
@@ -151,7 +152,7 @@ def test_algorithm1_entry_points_reject_bad_arguments():
     wc = dbp.conv2d_layer_workspace_bytes(2, 3, 8, 8, 4, 3, 3, 1, 1)
     assert wc > dbp.conv2d_workspace_bytes(2, 3, 8, 8, 4, 3, 3, 1, 1)
     g = dbp.dithered_conv2d_layer_backward
-    assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 2, 1, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == UNSUPPORTED
+    assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 0, 1, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == SHAPE
     assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 1, 1, -1.0, 1, 0, None, FAKE, FAKE, None, None, None) == STEP
     assert _code(g, FAKE, None, FAKE, FAKE, dbp.F32, 2, 3, 8, 8, 4, 3, 3, 1, 1, 4.0, 1, 0, None, FAKE, FAKE, None, None, None) == WORKSPACE
 
@@ -177,7 +178,7 @@ def test_full_8bit_entry_points_reject_bad_arguments():
     assert _code(f, FAKE, FAKE, FAKE, 140000, 16, 12, 1.0, 1, 0, None, None, FAKE, None) == OVERFLOW
     assert _code(f, FAKE, FAKE, FAKE, 8, 16, 12, 1.0, 1, 0, None, FAKE, FAKE, None) == WORKSPACE
     g = dbp.dithered_conv2d_backward_q8
-    assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 2, 1, 1.0, 1, 0, None, FAKE, FAKE, None) == UNSUPPORTED
+    assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 0, 1, 1.0, 1, 0, None, FAKE, FAKE, None) == SHAPE
     assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 1, 1, -1.0, 1, 0, None, FAKE, FAKE, None) == STEP
     assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 20000, 3, 3, 1, 1, 1.0, 1, 0, None, FAKE, None, None) == OVERFLOW
     assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 1, 1, 1.0, 1, 0, None, FAKE, FAKE, None) == WORKSPACE

@@ -8,14 +8,14 @@ from workloads import ConvProblem
 pytestmark = pytest.mark.gpu
 
 
-def _problem(N, C, H, Wd, K, R, S, pad, c=4.0, seed=0, i8=False):
+def _problem(N, C, H, Wd, K, R, S, pad, c=4.0, seed=0, i8=False, stride=1):
     rng = np.random.default_rng(seed + N * 131 + C * 17 + H * 5 + K)
-    P, Q = H + 2 * pad - R + 1, Wd + 2 * pad - S + 1
+    P, Q = (H + 2 * pad - R) // stride + 1, (Wd + 2 * pad - S) // stride + 1
     X = workloads.int8_relu_uniform(rng, (N, C, H, Wd)) if i8 else workloads.relu_normal(rng, (N, C, H, Wd))
     W = (rng.standard_normal((K, C, R, S)) * np.sqrt(2.0 / (C * R * S))).astype(np.float32)
     d = rng.laplace(0, 5e-4, size=(N, K, P, Q)).astype(np.float32)
-    return ConvProblem("t_n%d_c%d_%dx%d_k%d_%dx%d_p%d" % (N, C, H, Wd, K, R, S, pad), d, W, X,
-                       float(np.float32(c * 7.071e-4)), 1, pad)
+    return ConvProblem("t_n%d_c%d_%dx%d_k%d_%dx%d_p%d_s%d" % (N, C, H, Wd, K, R, S, pad, stride), d, W, X,
+                       float(np.float32(c * 7.071e-4)), stride, pad)
 
 
 def _check(p, res, sample=None):
@@ -83,6 +83,25 @@ def test_conv_int8_mode_is_bit_exact(case):
     from gpu_util import run_conv
     p = _problem(*case, c=1.0, i8=True)
     _check(p, run_conv(p))
+
+
+STRIDED = [  # N, C, H, Wd, K, R, S, pad, stride  (the strided layers of a ResNet: 3x3/2, 1x1/2 shortcuts, 7x7/2 stem)
+    (2, 5, 9, 7, 6, 3, 3, 1, 2),
+    (3, 16, 14, 14, 24, 3, 3, 1, 2),
+    (2, 33, 14, 14, 20, 1, 1, 0, 2),
+    (2, 3, 23, 20, 8, 7, 7, 3, 2),
+    (2, 8, 11, 13, 9, 3, 3, 0, 3),       # stride 3, sizes that leave a remainder
+    (4, 64, 28, 28, 128, 3, 3, 1, 2),
+]
+
+
+@pytest.mark.parametrize("case", STRIDED)
+def test_conv_strided_matches_oracle(case):
+    from gpu_util import run_conv
+    p = _problem(*case[:8], stride=case[8])
+    _check(p, run_conv(p))
+    p8 = _problem(*case[:8], c=1.0, i8=True, stride=case[8])
+    _check(p8, run_conv(p8))
 
 
 def test_conv_dense_codes_and_structured_zeros():

@@ -127,14 +127,14 @@ def config2(c: float = 8.0, batch: int = 256, widths=MLP_WIDTHS) -> list:
     return layers
 
 
-def _conv(name, seed, N, C, K, H, R, pad, delta_fn, x_fn, w_std, step_fn):
+def _conv(name, seed, N, C, K, H, R, pad, delta_fn, x_fn, w_std, step_fn, stride=1):
     rng = np.random.default_rng(seed)
-    P = H + 2 * pad - R + 1
+    P = (H + 2 * pad - R) // stride + 1
     X = x_fn(rng, (N, C, H, H))
     W = (w_std * rng.standard_normal((K, C, R, R))).astype(np.float32)
     d = delta_fn(rng, (N, K, P, P))
     step = step_fn(d)
-    return ConvProblem(name, d, W, X, step, 1, pad, predicted_sparsity=expected_sparsity(d, step))
+    return ConvProblem(name, d, W, X, step, stride, pad, predicted_sparsity=expected_sparsity(d, step))
 
 
 def config3(c: float = 4.0, N: int = 128) -> ConvProblem:
@@ -142,6 +142,12 @@ def config3(c: float = 4.0, N: int = 128) -> ConvProblem:
     return _conv("cfg3_conv3x3_n%d_64x64_32x32_c%g" % (N, c), 1003, N, 64, 64, 32, 3, 1,
                  lambda r, s: laplace(r, 5e-4, s), relu_normal, np.sqrt(2.0 / 576.0),
                  lambda d: step_from_std(d, c))
+
+
+def resnet_downsample(target: float = 0.92, N: int = 64) -> ConvProblem:
+    """The strided 3x3 convolution that opens a ResNet-18 stage: 128 -> 256 channels, 28x28 -> 14x14, stride 2."""
+    return _conv("resnet_conv3x3s2_n%d_128x256_28x28_s%g" % (N, target), 1006, N, 128, 256, 28, 3, 1,
+                 laplace_mixture, relu_normal, np.sqrt(2.0 / 1152.0), lambda d: step_for_sparsity(d, target), stride=2)
 
 
 def config4a(target: float = 0.92, N: int = 64) -> ConvProblem:
