@@ -71,7 +71,7 @@ __device__ __forceinline__ u32x4 cdw_funnel(const uint4 &lo, const uint4 &hi)
                       __builtin_amdgcn_alignbyte(d[q + 3], d[q + 2], b), __builtin_amdgcn_alignbyte(d[q + 4], d[q + 3], b)};
 }
 
-template <int MODE, int R, int S, int PAD, int MB>
+template <int MODE, int R, int S, int PAD, int MB, bool ROW4>
 __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
 {
     using TR = CdwTraits<MODE>;
@@ -134,7 +134,146 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
         }
     };
 
-    // Convert the raw loads and scatter them to their pitched positions in LDS.
+    // ---- ROW4: image rows and code rows are whole numbers of aligned 4-element pieces (Wd % 4 == 0, Q % 4 == 0).
+    // A piece then never straddles rows and its place inside a unit is the same for every unit: its LDS address
+    // and its lane offset in global memory are computed once; a unit only moves the bases (the same for all
+    // lanes) and the limits at the image's top and bottom.  The stagers are single wavefronts per SIMD and are
+    // bound by the number of instructions they issue: per piece this path issues an addition, a comparison
+    // and a select on either side of the load, where the general path below recomputes positions (two
+    // integer divisions per unit), multiplies addresses per piece and branches around every write.
+    const int xrel = 4 * xq, crel = 4 * cq;
+    bool x_own = false, c_own = false;
+    uint32_t x_lds0 = 0, c_lds0 = 0, x_g0 = 0;
+    int c_g0 = 0;
+    if constexpr (ROW4) {
+        const int xrow = xrel / a.Wd, xw = xrel - xrow * a.Wd;
+        x_own = stager && xq < a.nqx && xrow < a.RU;
+        x_lds0 = (uint32_t)((xch * a.pitchX + xrow * a.PW + xw) * ESZ);
+        x_g0 = (uint32_t)(xch * PI + xrel) * (uint32_t)sizeof(XT);
+        const int crow = crel / a.Q, cqq = crel - crow * a.Q;
+        const int cps = (crow - 1) * a.PW + cqq + CDW_M8;          // pitched coordinate inside the patch
+        c_own = stager && cq < a.nqc && crow < a.NR && cps >= 0 && cps < a.lenC;
+        c_lds0 = (uint32_t)(x_bytes + (size_t)(cch * a.pitchC + (c_own ? cps : 0)) * ESZ);
+        c_g0 = cch * PQ + crel;
+    }
+    const uint32_t x_gstep = (uint32_t)(XCH * PI) * (uint32_t)sizeof(XT), x_lstep = (uint32_t)(XCH * a.pitchX * ESZ);
+    const int c_gstep = CCH * PQ;
+    const uint32_t c_lstep = (uint32_t)(CCH * a.pitchC * ESZ);
+
+    // A tile that has all its 64*MB output channels and 64 input channels needs no test per piece: validity is then
+    // one mask per lane and unit (all ones or zero) that is and-ed into the lane offset before the load (an
+    // invalid piece reads offset 0) and into the value before the LDS write; no comparison, no select through
+    // scalar registers, no branch per piece.
+    const bool whole_tile = k0 + TK <= a.K && c0 + TC <= a.C;            // uniform
+
+    auto issue_fast = [&](int unit) {
+        const int n = unit / a.chunks, h_a = (unit - n * a.chunks) * a.RU;
+        const char *xb = (const char *)((const XT *)a.X + ((int64_t)n * a.C + c0) * PI + h_a * a.Wd);      // uniform
+        const bool x_ld = x_own && xrel < PI - h_a * a.Wd;               // below the image's last row: nothing to load
+        const int c_shift = (h_a - 1 - (R - 1) + a.pad) * a.Q;           // first code element of the patch rows (may be < 0)
+        const char *cb = (const char *)(a.codes + ((int64_t)n * a.K + k0) * PQ);                         // uniform
+        const bool c_ld = c_own && crel + c_shift >= 0 && crel + c_shift < PQ;
+        if (whole_tile) {
+            const uint32_t cm = c_ld ? 0xFFFFFFFFu : 0u, xm = x_ld ? 0xFFFFFFFFu : 0u;
+            uint32_t co = (uint32_t)(c_g0 + c_shift) & cm, xo = x_g0 & xm;
+            const uint32_t cs = (uint32_t)c_gstep & cm, xs = x_gstep & xm;
+#pragma unroll
+            for (int j = 0; j < CI; ++j) {
+                if (j >= ci_n) break;
+                cr[j] = *(const uint32_t *)(cb + co);
+                co += cs;
+            }
+#pragma unroll
+            for (int j = 0; j < XI; ++j) {
+                if (j >= xi_n) break;
+                xr[j] = *(const XRaw *)(xb + xo);
+                xo += xs;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < CI; ++j) {
+                if (j >= ci_n) break;
+                const bool ok = c_ld && k0 + cch + CCH * j < a.K;
+                cr[j] = *(const uint32_t *)(cb + (ok ? (uint32_t)(c_g0 + c_shift + j * c_gstep) : 0u));
+            }
+#pragma unroll
+            for (int j = 0; j < XI; ++j) {
+                if (j >= xi_n) break;
+                const bool ok = x_ld && c0 + xch + XCH * j < a.C;
+                xr[j] = *(const XRaw *)(xb + (ok ? x_g0 + (uint32_t)j * x_gstep : 0u));
+            }
+        }
+    };
+
+    // One piece into LDS; `m` is the piece's validity mask (all ones or zero).
+    auto put_x = [&](uint32_t addr, const XRaw &raw, uint32_t m) {
+        char *d = (char *)cdw_lds + addr;
+        if constexpr (MODE == MODE_BF16) {
+            const uint32_t rw[4] = {raw.x & m, raw.y & m, raw.z & m, raw.w & m};
+            uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) split3(__uint_as_float(rw[e]), hi[e], mid[e], lo[e]);
+            *(uint2 *)d                 = uint2{(lo[0] >> 16) | lo[1], (lo[2] >> 16) | lo[3]};
+            *(uint2 *)(d + x_plane)     = uint2{(mid[0] >> 16) | mid[1], (mid[2] >> 16) | mid[3]};
+            *(uint2 *)(d + 2 * x_plane) = uint2{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]};
+        } else {
+            *(uint32_t *)d = raw & m;
+        }
+    };
+    auto put_c = [&](uint32_t addr, uint32_t t) {
+        char *d = (char *)cdw_lds + addr;
+        if constexpr (MODE == MODE_BF16)
+            *(uint2 *)d = uint2{bf16_pair_from_i8((int8_t)t, (int8_t)(t >> 8)), bf16_pair_from_i8((int8_t)(t >> 16), (int8_t)(t >> 24))};
+        else
+            *(uint32_t *)d = t;
+    };
+
+    auto stage_fast = [&](int unit, uint32_t buf_off) {
+        const int n = unit / a.chunks, h_a = (unit - n * a.chunks) * a.RU;
+        if (x_own) {
+            const bool x_ld = xrel < PI - h_a * a.Wd;
+            const uint32_t xm = x_ld ? 0xFFFFFFFFu : 0u;
+            uint32_t addr = buf_off + x_lds0;                              // 32-bit LDS byte address of the piece
+            if (whole_tile) {
+#pragma unroll
+                for (int j = 0; j < XI; ++j) {
+                    if (j >= xi_n) break;
+                    put_x(addr, xr[j], xm);
+                    addr += x_lstep;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < XI; ++j) {
+                    if (j >= xi_n) break;
+                    put_x(addr, xr[j], c0 + xch + XCH * j < a.C ? xm : 0u);
+                    addr += x_lstep;
+                }
+            }
+        }
+        if (c_own) {
+            const int c_shift = (h_a - 1 - (R - 1) + a.pad) * a.Q;
+            const bool c_ld = crel + c_shift >= 0 && crel + c_shift < PQ;
+            const uint32_t cm = c_ld ? 0xFFFFFFFFu : 0u;
+            uint32_t addr = buf_off + c_lds0;
+            if (whole_tile) {
+#pragma unroll
+                for (int j = 0; j < CI; ++j) {
+                    if (j >= ci_n) break;
+                    put_c(addr, cr[j] & cm);
+                    addr += c_lstep;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < CI; ++j) {
+                    if (j >= ci_n) break;
+                    put_c(addr, k0 + cch + CCH * j < a.K ? cr[j] & cm : 0u);
+                    addr += c_lstep;
+                }
+            }
+        }
+    };
+
+    // Convert the raw loads and scatter them to their pitched positions in LDS (rows of any length).
     auto stage = [&](int unit, char *lds_x, char *lds_c) {
         const int n = unit / a.chunks, h_a = (unit - n * a.chunks) * a.RU;
         if (xq < a.nqx) {
@@ -282,12 +421,21 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
             constexpr int r = decltype(rr)::value;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
+                // Every dword of the cells counts as used: a tap needs only five of a window's eight, and the
+                // compiler would then read the window as single dwords, which for lanes one LDS row apart is a
+                // four-way bank conflict; whole 16-byte cells are conflict-free.
+                uint4 w[NCELL];
+#pragma unroll
+                for (int c = 0; c < NCELL; ++c) {
+                    w[c] = f.w[r][mb][c];
+                    if constexpr (MODE == MODE_I8) asm volatile("" : "+v"(w[c].x), "+v"(w[c].y), "+v"(w[c].z), "+v"(w[c].w));
+                }
                 u32x4 af[S];
                 static_for<0, S>([&](auto ss) {
                     constexpr int sx = decltype(ss)::value;
                     constexpr int cb = (CDW_M8 + PAD - sx) * ESZ, ci = cb / 16 - LO_CELL, sb = cb & 15;
-                    if constexpr (sb == 0) af[sx] = u32x4{f.w[r][mb][ci].x, f.w[r][mb][ci].y, f.w[r][mb][ci].z, f.w[r][mb][ci].w};
-                    else af[sx] = cdw_funnel<sb>(f.w[r][mb][ci], f.w[r][mb][ci + 1]);
+                    if constexpr (sb == 0) af[sx] = u32x4{w[ci].x, w[ci].y, w[ci].z, w[ci].w};
+                    else af[sx] = cdw_funnel<sb>(w[ci], w[ci + 1]);
                 });
 #pragma unroll
                 for (int pl = 0; pl < PL; ++pl)
@@ -303,16 +451,18 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
     char *const lds0 = (char *)cdw_lds;
     const int n_units = unit_b - unit_a;
     if (stager) {
-        if (n_units > 0) issue_loads(unit_a);
+        // (the calls are written out: wrapping them in further lambdas keeps the raw-load arrays out of registers)
+        if (n_units > 0) { if constexpr (ROW4) issue_fast(unit_a); else issue_loads(unit_a); }
         __syncthreads();
-        if (n_units > 0) stage(unit_a, lds0, lds0 + x_bytes);
-        if (n_units > 1) issue_loads(unit_a + 1);
+        if (n_units > 0) { if constexpr (ROW4) stage_fast(unit_a, 0u); else stage(unit_a, lds0, lds0 + x_bytes); }
+        if (n_units > 1) { if constexpr (ROW4) issue_fast(unit_a + 1); else issue_loads(unit_a + 1); }
         __syncthreads();
         for (int i = 0; i < n_units; ++i) {
             if (i + 1 < n_units) {
-                char *nb = lds0 + ((i + 1) & 1) * buf_bytes;
-                stage(unit_a + i + 1, nb, nb + x_bytes);
-                if (i + 2 < n_units) issue_loads(unit_a + i + 2);
+                const uint32_t nb_off = (uint32_t)(((i + 1) & 1) * buf_bytes);
+                if constexpr (ROW4) stage_fast(unit_a + i + 1, nb_off);
+                else stage(unit_a + i + 1, lds0 + nb_off, lds0 + nb_off + x_bytes);
+                if (i + 2 < n_units) { if constexpr (ROW4) issue_fast(unit_a + i + 2); else issue_loads(unit_a + i + 2); }
             }
             __syncthreads();
         }
@@ -334,10 +484,16 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
         StepFrags fa, fb;
         load_frags(cur, 0, fa);
         for (int step = 0; step < n_steps; step += 2) {
+            // the scheduling barriers keep the LDS reads of the next step in front of this step's matrix-core
+            // instructions (left alone, the compiler sinks them behind and their latency is exposed)
             if (step + 1 < n_steps) load_frags(cur, step + 1, fb);
+            __builtin_amdgcn_sched_barrier(0);
             multiply(fa);
+            __builtin_amdgcn_sched_barrier(0);
             if (step + 2 < n_steps) load_frags(cur, step + 2, fa);
+            __builtin_amdgcn_sched_barrier(0);
             if (step + 1 < n_steps) multiply(fb);
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
     }

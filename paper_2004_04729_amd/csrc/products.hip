@@ -224,21 +224,29 @@ ConvDwPlan conv_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, 
     return pl;
 }
 
-template <int MODE, int R, int S, int PAD, int MB>
-hipError_t launch_conv_dw_fast(const ConvDwPlan &pl, hipStream_t s)
+template <int MODE, int R, int S, int PAD, int MB, bool ROW4>
+hipError_t launch_conv_dw_fast_as(const ConvDwPlan &pl, hipStream_t s)
 {
     // more than 64 KiB of dynamic LDS has to be allowed per kernel, once
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dw_kernel<MODE, R, S, PAD, MB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dw_kernel<MODE, R, S, PAD, MB, ROW4>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, CDW_MAX_LDS);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((conv_dw_kernel<MODE, R, S, PAD, MB>), dim3(pl.grid), dim3(512), pl.lds_bytes, s, pl.args);
+    hipLaunchKernelGGL((conv_dw_kernel<MODE, R, S, PAD, MB, ROW4>), dim3(pl.grid), dim3(512), pl.lds_bytes, s, pl.args);
     if (pl.args.n_split > 1)
         hipLaunchKernelGGL((conv_dw_reduce_kernel<MODE, R, S, MB>), dim3(pl.reduce_grid), dim3(256), 0, s, pl.args);
     return hipGetLastError();
+}
+
+template <int MODE, int R, int S, int PAD, int MB>
+hipError_t launch_conv_dw_fast(const ConvDwPlan &pl, hipStream_t s)
+{
+    // rows that are whole numbers of aligned 4-element pieces have a staging path of their own
+    return pl.args.row4x && pl.args.row4c ? launch_conv_dw_fast_as<MODE, R, S, PAD, MB, true>(pl, s)
+                                          : launch_conv_dw_fast_as<MODE, R, S, PAD, MB, false>(pl, s);
 }
 
 // ---- fast fully connected path (fc_kernel.h) -------------------------------------------------------
