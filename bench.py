@@ -213,6 +213,24 @@ def main():
                                                dbp.PATH_AUTO, stream)
 
     t_layer = timed(layer_step, max(10, args.steps // 2))
+
+    # the same chain in the full 8-bit mode: int8 weights and activations, exact int32 dX and dW
+    q8 = []
+    for b in sets[0]:
+        Bq, iq, oq = b["p"].dims
+        q8.append(dict(W8=torch.randint(-127, 128, (oq, iq), dtype=torch.int8, device=dev),
+                       X8=torch.randint(0, 128, (Bq, iq), dtype=torch.int8, device=dev),
+                       dX=torch.empty((Bq, iq), dtype=torch.int32, device=dev), dW=torch.empty((oq, iq), dtype=torch.int32, device=dev)))
+
+    def q8_step(i):
+        for b, q in zip(sets[0], q8):
+            p = b["p"]
+            Bq, iq, oq = p.dims
+            dbp.dithered_linear_backward_q8(b["d"], q["W8"], q["X8"], Bq, iq, oq, p.step, p.seed, 0, b["codes"], q["dX"], q["dW"],
+                                            b["ws"], b["stats"], stream)
+
+    t_q8 = timed(q8_step, max(10, args.steps // 2))
+    del q8
     del lsets
     t_dense = timed(dense_step, max(5, args.steps // 4))
     torch.backends.cuda.matmul.allow_tf32 = False
@@ -289,6 +307,7 @@ def main():
         "cpu_baseline": cpu,
         "host_wall_ms_per_step": wall * 1e3,
         "whole_layer_entry_ms_per_step": t_layer * 1e3,
+        "full_8bit_ms_per_step": t_q8 * 1e3,
         "vs_dense": {"same_library_fp32_mfma_ms": t_dense * 1e3, "torch_matmul_fp32_ms": t_torch * 1e3,
                      "speedup_vs_same_library": t_dense / t_step, "speedup_vs_torch": t_torch / t_step},
         "kernels_L2_us": {"nsd_1M_elements": t_nsd_small * 1e6, "dX_mfma": t_dx * 1e6, "dW_mfma": t_dw * 1e6,

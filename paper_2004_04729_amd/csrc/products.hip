@@ -3,6 +3,7 @@
 #include "conv_loaders.h"
 #include "fc_kernel.h"
 #include "fc2_kernel.h"
+#include "fc2_i8_kernel.h"
 #include "conv_dx_kernel.h"
 #include "conv_dw_kernel.h"
 
@@ -275,23 +276,23 @@ FcPlan fc_plan(int64_t M, int64_t N, int64_t K, int tm = FC_TM, int tn = FC_TN)
 
 // Plans of the two products for the kernel with staging and multiplying wavefronts: reductions are split
 // into items of about half a workgroup's share of all K steps (one workgroup per CU), at least 8 steps.
-void fc2_plans(int64_t B, int64_t in, int64_t out, bool want_dx, bool want_dw, FcPlan &dx, FcPlan &dw)
+void fc2_plans(int64_t B, int64_t in, int64_t out, bool want_dx, bool want_dw, FcPlan &dx, FcPlan &dw, int kt = FC2_KT)
 {
-    auto base = [](int64_t M, int64_t N, int64_t K, FcPlan &pl) {
+    auto base = [kt](int64_t M, int64_t N, int64_t K, FcPlan &pl) {
         pl.tiles_m = (int)((M + FC2_TM - 1) / FC2_TM);
         pl.tiles_n = (int)((N + FC2_TN - 1) / FC2_TN);
         pl.tiles = (int64_t)pl.tiles_m * pl.tiles_n;
-        return (K + FC2_KT - 1) / FC2_KT;
+        return (K + kt - 1) / kt;
     };
     const int64_t sx = base(B, in, out, dx), sw = base(out, in, B, dw);
     const int64_t all = (want_dx ? dx.tiles * sx : 0) + (want_dw ? dw.tiles * sw : 0);
     int64_t len = all / 512;
     if (len < 8) len = 8;
-    auto split = [len](int64_t steps, FcPlan &pl) {
+    auto split = [len, kt](int64_t steps, FcPlan &pl) {
         int64_t n = (steps + len / 2) / len;
         if (n < 1) n = 1;
         const int64_t per = (steps + n - 1) / n;
-        pl.k_per_split = (int)(per * FC2_KT);
+        pl.k_per_split = (int)(per * kt);
         pl.n_split = (int)((steps + per - 1) / per);
         pl.partial_bytes = pl.n_split > 1 ? (size_t)pl.tiles * pl.n_split * FC2_TM * FC2_TN * sizeof(float) : 0;
     };
@@ -336,9 +337,11 @@ size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
     size_t fast = align_up(dx.partial_bytes, 256) + align_up(dw.partial_bytes, 256);
     for (int m = 1; m < 4; ++m) {                               // every combination of products a call can ask for
         FcPlan dx2, dw2;
-        fc2_plans(B, in, out, (m & 1) != 0, (m & 2) != 0, dx2, dw2);
-        const size_t fast2 = ((m & 1) ? align_up(dx2.partial_bytes, 256) : 0) + ((m & 2) ? align_up(dw2.partial_bytes, 256) : 0);
-        if (fast2 > fast) fast = fast2;
+        for (int kt = FC2_KT; kt <= FC2I_KT; kt *= 2) {              // the bf16 kernel's K step and the int8 kernel's
+            fc2_plans(B, in, out, (m & 1) != 0, (m & 2) != 0, dx2, dw2, kt);
+            const size_t fast2 = ((m & 1) ? align_up(dx2.partial_bytes, 256) : 0) + ((m & 2) ? align_up(dw2.partial_bytes, 256) : 0);
+            if (fast2 > fast) fast = fast2;
+        }
     }
     return (generic > fast ? generic : fast) + 256;
 }
@@ -373,14 +376,61 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
     StatsJob pending = a.stats_job;
     if (a.codes && a.W8) {
         // full 8-bit mode: both products on int8 matrix cores, exact int32 results
+        auto i8_ok = [&](bool a_kfast, const void *Bop, const void *outp, int64_t M) {
+            if (in < 8 || in % 8 || ((uintptr_t)Bop % 8) || ((uintptr_t)outp % 16)) return false;     // 8-byte loads, 16-byte stores
+            if (out % 4 || ((uintptr_t)a.codes % 4)) return false;
+            if (!a_kfast && (M < 16 || M % 4)) return false;
+            return true;
+        };
+        bool dx_fast = a.dX && i8_ok(true, a.W8, a.dX, B) && out >= FC2I_KT && B > FC2_TM / 2;
+        bool dw_fast = a.dW && i8_ok(false, a.X, a.dW, out) && B >= FC2I_KT && out > FC2_TM / 2;
+        if ((int64_t)B * in >= (1ll << 30) || (int64_t)out * in >= (1ll << 30) || (int64_t)B * out >= (1ll << 30)) dx_fast = dw_fast = false;
+        FcPlan pdx, pdw;
+        if (dx_fast || dw_fast) {
+            fc2_plans(B, in, out, dx_fast, dw_fast, pdx, pdw, FC2I_KT);
+            const int64_t items = (dx_fast ? pdx.tiles * pdx.n_split : 0) + (dw_fast ? pdw.tiles * pdw.n_split : 0);
+            if (items > (int64_t)FC2_MAX_ITEMS * 256) dx_fast = dw_fast = false;
+        }
+        if (dx_fast || dw_fast) {
+            static bool raised = false;
+            if (!raised) {
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_i8_pair_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, FC2I_LDS_BYTES);
+                if (e != hipSuccess) return e;
+                raised = true;
+            }
+            char *scratch = (char *)a.scratch;
+            FcPairArgs pa;
+            if (!dx_fast) { pdx.n_split = 1; pdx.partial_bytes = 0; }
+            if (!dw_fast) { pdw.n_split = 1; pdw.partial_bytes = 0; }
+            pa.prob[0] = fc_problem(true, a.codes, a.out, (const float *)a.W8, a.in, B, in, out, Scale{1.0f, nullptr}, a.dX, pdx, scratch);
+            pa.prob[1] = fc_problem(false, a.codes, a.out, (const float *)a.X, a.in, out, in, B, Scale{1.0f, nullptr}, (float *)a.dW, pdw, scratch);
+            if (!dx_fast) pa.prob[0].n_items = 0;
+            if (!dw_fast) pa.prob[1].n_items = 0;
+            if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
+            pa.stats = pending;
+            pending.n = 0; pending.bias_len = 0;
+            const int total = pa.prob[0].n_items + pa.prob[1].n_items;
+            const int grid = total < 256 ? total : 256;
+            hipLaunchKernelGGL(fc2_i8_pair_kernel, dim3(grid), dim3(512), FC2I_LDS_BYTES, s, pa);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            const bool r0 = dx_fast && pdx.n_split > 1, r1 = dw_fast && pdw.n_split > 1;
+            if (r0 || r1) {
+                const int tiles0 = r0 ? (int)pdx.tiles : 0, tiles1 = r1 ? (int)pdw.tiles : 0;
+                hipLaunchKernelGGL(fc2_i8_reduce_kernel, dim3(32 * (tiles0 + tiles1)), dim3(256), 0, s, pa, tiles0);
+                e = hipGetLastError();
+                if (e != hipSuccess) return e;
+            }
+        }
         if (pending.n || pending.bias_len) { e = launch_stats_job(pending, s); if (e != hipSuccess) return e; }
-        if (a.dX) {
+        if (a.dX && !dx_fast) {
             MatrixLoader<MODE_I8, true, true>   al{a.codes, a.out, B, out};
             MatrixLoader<MODE_I8, false, false> bl{a.W8, a.in, in, out};
             e = run_gemm<MODE_I8>(al, bl, om, B, in, out, k_step<MODE_I8>(), Scale{1.0f, nullptr}, (int32_t *)a.dX, a.scratch, a.scratch_bytes, s);
             if (e != hipSuccess) return e;
         }
-        if (a.dW) {
+        if (a.dW && !dw_fast) {
             MatrixLoader<MODE_I8, true, false>  al{a.codes, a.out, out, B};
             MatrixLoader<MODE_I8, false, false> bl{(const int8_t *)a.X, a.in, in, B};
             e = run_gemm<MODE_I8>(al, bl, om, out, in, B, k_step<MODE_I8>(), Scale{1.0f, nullptr}, (int32_t *)a.dW, a.scratch, a.scratch_bytes, s);
