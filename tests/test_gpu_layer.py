@@ -215,15 +215,16 @@ def test_linear_layer_backward_8bit_and_degenerate():
 
 
 @pytest.mark.parametrize("case", [(2, 5, 9, 7, 6, 3, 3, 1), (3, 16, 14, 14, 24, 3, 3, 1), (2, 33, 14, 14, 20, 1, 1, 0),
-                                  (2, 64, 30, 30, 40, 3, 3, 1)])
+                                  (2, 64, 30, 30, 40, 3, 3, 1), (2, 8, 15, 14, 12, 3, 3, 1, 2), (2, 6, 23, 20, 8, 7, 7, 3, 2)])
 @pytest.mark.parametrize("i8", [False, True])
 def test_conv_layer_backward_is_algorithm_1(case, i8):
     import torch
     import paper_2004_04729_amd as dbp
     from gpu_util import check_products, stream
     from oracle import oracle as O
-    N, C, H, Wd, K, R, S, pad = case
-    P, Q = H + 2 * pad - R + 1, Wd + 2 * pad - S + 1
+    N, C, H, Wd, K, R, S, pad = case[:8]
+    stride = case[8] if len(case) > 8 else 1
+    P, Q = (H + 2 * pad - R) // stride + 1, (Wd + 2 * pad - S) // stride + 1
     rng = np.random.default_rng(sum(case))
     X = workloads.int8_relu_uniform(rng, (N, C, H, Wd)) if i8 else np.maximum(rng.standard_normal((N, C, H, Wd)), 0).astype(np.float32)
     W = (rng.standard_normal((K, C, R, S)) * np.sqrt(2.0 / (C * R * S))).astype(np.float32)
@@ -237,8 +238,8 @@ def test_conv_layer_backward_is_algorithm_1(case, i8):
     db = torch.full((K,), float("nan"), dtype=torch.float32, device="cuda:0")
     pair = torch.zeros(2, dtype=torch.float32, device="cuda:0")
     st = torch.zeros(32, dtype=torch.uint8, device="cuda:0")
-    ws = torch.empty(dbp.conv2d_layer_workspace_bytes(N, C, H, Wd, K, R, S, 1, pad, xd), dtype=torch.uint8, device="cuda:0")
-    dbp.dithered_conv2d_layer_backward(_dev(da), _dev(a), _dev(W), _dev(X), xd, N, C, H, Wd, K, R, S, 1, pad, 4.0, 1, 0,
+    ws = torch.empty(dbp.conv2d_layer_workspace_bytes(N, C, H, Wd, K, R, S, stride, pad, xd), dtype=torch.uint8, device="cuda:0")
+    dbp.dithered_conv2d_layer_backward(_dev(da), _dev(a), _dev(W), _dev(X), xd, N, C, H, Wd, K, R, S, stride, pad, 4.0, 1, 0,
                                        codes, dX, dW, db, pair, ws, st, dbp.PATH_AUTO, stream())
     torch.cuda.synchronize()
     dz = O.relu_backward(da, a)
@@ -249,10 +250,10 @@ def test_conv_layer_backward_is_algorithm_1(case, i8):
     assert dbp.Stats.from_tensor(st).nnz == sref.nnz
     assert np.array_equal(db.cpu().numpy(), O.bias_grad(k_ref, N * K, P * Q, False, K, step)[1])
     Xf = X.astype(np.float32)
-    rX, rW, _ = O.conv2d_backward(W, Xf, codes=k_ref, step=step, stride=1, pad=pad)
-    aX, aW, _ = O.conv2d_backward(np.abs(W), np.abs(Xf), codes=np.abs(k_ref), step=step, stride=1, pad=pad)
+    rX, rW, _ = O.conv2d_backward(W, Xf, codes=k_ref, step=step, stride=stride, pad=pad)
+    aX, aW, _ = O.conv2d_backward(np.abs(W), np.abs(Xf), codes=np.abs(k_ref), step=step, stride=stride, pad=pad)
     check_products(dX.cpu().numpy(), rX, aX, "conv layer dX")
     if i8:
-        assert np.array_equal(dW.cpu().numpy(), O.conv2d_dw_i8(k_ref, X, R, S, stride=1, pad=pad))
+        assert np.array_equal(dW.cpu().numpy(), O.conv2d_dw_i8(k_ref, X, R, S, stride=stride, pad=pad))
     else:
         check_products(dW.cpu().numpy(), rW, aW, "conv layer dW")

@@ -99,7 +99,9 @@ def test_fc_q8_single_products_and_dense_codes():
     _fc(40, 64, 2000, seed=5, c=0.02)                    # nearly every code nonzero, many saturated
 
 
-CONV_CASES = [  # N, C, H, Wd, K, R, S, pad
+CONV_CASES = [  # N, C, H, Wd, K, R, S, pad (, stride)
+    (2, 8, 15, 14, 12, 3, 3, 1, 2),
+    (2, 16, 14, 14, 24, 1, 1, 0, 2),
     (1, 1, 1, 1, 1, 1, 1, 0),
     (2, 5, 9, 7, 6, 3, 3, 1),
     (3, 16, 14, 14, 24, 3, 3, 1),
@@ -110,9 +112,9 @@ CONV_CASES = [  # N, C, H, Wd, K, R, S, pad
 ]
 
 
-def _conv_inputs(N, C, H, Wd, K, R, S, pad, seed, c=2.0):
+def _conv_inputs(N, C, H, Wd, K, R, S, pad, seed, c=2.0, stride=1):
     rng = np.random.default_rng(seed)
-    P, Q = H + 2 * pad - R + 1, Wd + 2 * pad - S + 1
+    P, Q = (H + 2 * pad - R) // stride + 1, (Wd + 2 * pad - S) // stride + 1
     delta = rng.laplace(size=(N, K, P, Q)).astype(np.float32) * np.float32(1e-3)
     step = float(np.float32(c * delta.std())) if delta.size > 1 else 1e-3
     W8 = rng.integers(-127, 128, size=(K, C, R, S)).astype(np.int8)
@@ -120,14 +122,14 @@ def _conv_inputs(N, C, H, Wd, K, R, S, pad, seed, c=2.0):
     return delta, step, W8, X8, P, Q
 
 
-def _conv_gpu(delta, step, W8, X8, pad, seed):
+def _conv_gpu(delta, step, W8, X8, pad, seed, stride=1):
     N, C, H, Wd = X8.shape
     K, _, R, S = W8.shape
     codes = torch.empty(delta.shape, dtype=torch.int8, device=DEV)
     dX = torch.full(X8.shape, 12345, dtype=torch.int32, device=DEV)
     dW = torch.full(W8.shape, 12345, dtype=torch.int32, device=DEV)
-    ws = torch.empty(dbp.conv2d_workspace_bytes(N, C, H, Wd, K, R, S, 1, pad, dbp.I8), dtype=torch.uint8, device=DEV)
-    dbp.dithered_conv2d_backward_q8(_dev(delta), _dev(W8), _dev(X8), N, C, H, Wd, K, R, S, 1, pad, step, seed, 0, codes,
+    ws = torch.empty(dbp.conv2d_workspace_bytes(N, C, H, Wd, K, R, S, stride, pad, dbp.I8), dtype=torch.uint8, device=DEV)
+    dbp.dithered_conv2d_backward_q8(_dev(delta), _dev(W8), _dev(X8), N, C, H, Wd, K, R, S, stride, pad, step, seed, 0, codes,
                                     dX, dW, ws, None, _stream())
     torch.cuda.synchronize()
     return codes.cpu().numpy(), dX.cpu().numpy(), dW.cpu().numpy()
@@ -135,13 +137,14 @@ def _conv_gpu(delta, step, W8, X8, pad, seed):
 
 @pytest.mark.parametrize("case", CONV_CASES)
 def test_conv_q8_is_bit_exact(case):
-    N, C, H, Wd, K, R, S, pad = case
-    delta, step, W8, X8, P, Q = _conv_inputs(*case, seed=N + K)
-    codes, dX, dW = _conv_gpu(delta, step, W8, X8, pad, seed=11)
+    N, C, H, Wd, K, R, S, pad = case[:8]
+    stride = case[8] if len(case) > 8 else 1
+    delta, step, W8, X8, P, Q = _conv_inputs(*case[:8], seed=N + K, stride=stride)
+    codes, dX, dW = _conv_gpu(delta, step, W8, X8, pad, seed=11, stride=stride)
     k_ref, _ = O.nsd(delta, step, 11)
     k_ref = k_ref.reshape(delta.shape)
     assert np.array_equal(codes, k_ref)
-    dX_ref, dW_ref = O.conv2d_backward_q8(k_ref, W8, X8, stride=1, pad=pad)
+    dX_ref, dW_ref = O.conv2d_backward_q8(k_ref, W8, X8, stride=stride, pad=pad)
     assert np.array_equal(dX, dX_ref) and np.array_equal(dW, dW_ref)
 
 
