@@ -286,7 +286,9 @@ void fc2_plans(int64_t B, int64_t in, int64_t out, bool want_dx, bool want_dw, F
     };
     const int64_t sx = base(B, in, out, dx), sw = base(out, in, B, dw);
     const int64_t all = (want_dx ? dx.tiles * sx : 0) + (want_dw ? dw.tiles * sw : 0);
-    int64_t len = all / 512;
+    // two items per workgroup when both products share the launch (a dX item and dW tiles interleave well), one when a
+    // product runs alone (half the split-K partials: measured 37 instead of 47 us for dX of the 4096x4096 layer)
+    int64_t len = all / (want_dx && want_dw ? 512 : 256);
     if (len < 8) len = 8;
     auto split = [len, kt](int64_t steps, FcPlan &pl) {
         int64_t n = (steps + len / 2) / len;
