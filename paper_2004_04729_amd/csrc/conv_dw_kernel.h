@@ -93,7 +93,10 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
     const int lcol = lane & 31, lhalf = lane >> 5;
     const int wr = (wave & 3) >> 1, wcl = wave & 1;                  // multiplier's place in the 2x2 arrangement
     const int tiles = a.tiles_k * a.tiles_c;
-    const int tile = blockIdx.x % tiles, split = blockIdx.x / tiles;
+    // Workgroup w runs on XCD w % 8, and each XCD has an L2 of its own: renumber so that the tiles of one split (which
+    // read the same images at about the same time, each operand tile shared by a row or column of tiles) sit on one XCD.
+    const int wg = (gridDim.x & 7) == 0 ? (int)((blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
+    const int tile = wg % tiles, split = wg / tiles;
     const int k0 = (tile % a.tiles_k) * TK, c0 = (tile / a.tiles_k) * TC;
     const int unit_a = split * a.units_per_split, unit_b = min(unit_a + a.units_per_split, a.units);
     const int PI = a.H * a.Wd, PQ = a.P * a.Q;

@@ -6,6 +6,7 @@
 #include "fc2_i8_kernel.h"
 #include "conv_dx_kernel.h"
 #include "conv_dw_kernel.h"
+#include "conv_dw_i8_kernel.h"
 
 namespace dbp {
 
@@ -225,6 +226,72 @@ ConvDwPlan conv_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, 
     return pl;
 }
 
+// Geometry of the int8 3x3 dW kernel with transposed cells (conv_dw_i8_kernel.h); ok == false when it does not apply.
+struct ConvDwI8Plan { bool ok; ConvDwI8Args args; size_t lds_bytes, partial_bytes; int grid, reduce_grid; };
+
+ConvDwI8Plan conv_dw_i8_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad)
+{
+    ConvDwI8Plan pl;
+    pl.ok = false; pl.partial_bytes = 0; pl.lds_bytes = 0;
+    ConvDwI8Args &k = pl.args;
+    if (!(R == 3 && S == 3 && pad == 1)) return pl;
+    if (Wd % 4 || Wd < 16 || Wd > 224 || H < 1) return pl;           // 16-byte loads at dword-aligned addresses inside a row
+    if (H * Wd >= ((int64_t)1 << 24) || K * C * 9 >= ((int64_t)1 << 31)) return pl;   // 64 channels of a tile: 32-bit offsets
+    const int pw = (int)((Wd + 1 + 15) / 16 * 16), cpr = pw / 16, dc = (int)((Wd + 15) / 16);
+    double best = -1.0;
+    for (int ru = 1; ru <= H; ++ru) {
+        const int xpairs = ru * dc, cpairs = (ru + 2) * dc;
+        if (cpairs > 64) break;                                      // 256 stager threads cover >= 4 channels a pass, 16 passes at most
+        const int n_steps = (ru * cpr + 1) / 2;
+        const int xcells = (2 * n_steps) | 1;                        // odd: a fragment read spreads over the banks
+        int ccells = (ru + 2) * cpr + 2;                             // the patch and a zero cell at either end
+        if (ccells < 2 * n_steps + 2 * cpr + 2) ccells = 2 * n_steps + 2 * cpr + 2;   // the last step's reach
+        ccells |= 1;
+        const size_t lds = 2 * (size_t)64 * (xcells + ccells) * 16 + 256 * 16;   // two buffers and a spare cell per stager thread
+        if (lds > (size_t)CDW_MAX_LDS) break;
+        const int chunks = (int)((H + ru - 1) / ru);
+        const double cost = (double)chunks * (n_steps + 1.5);       // matrix-core steps plus a fixed cost per unit
+        if (best < 0.0 || cost < best) {
+            best = cost; pl.ok = true; pl.lds_bytes = lds;
+            k.RU = ru; k.chunks = chunks; k.n_steps = n_steps; k.xcells = xcells; k.ccells = ccells;
+            k.xpairs = xpairs; k.cpairs = cpairs; k.lds_cells = (int)(lds / 16) - 256;
+        }
+    }
+    if (!pl.ok) return pl;
+    k.N = (int)N; k.C = (int)C; k.H = (int)H; k.Wd = (int)Wd; k.K = (int)K; k.PW = pw; k.CPR = cpr; k.DC = dc;
+    k.tiles_k = (int)((K + 63) / 64); k.tiles_c = (int)((C + 63) / 64);
+    const int64_t tiles = (int64_t)k.tiles_k * k.tiles_c, units = N * k.chunks;
+    if (units >= ((int64_t)1 << 31) || tiles > 65535) { pl.ok = false; return pl; }
+    k.units = (int)units;
+    int64_t want = tiles >= 256 ? 1 : 256 / tiles;                   // one workgroup per CU
+    if (want > units) want = units;
+    k.units_per_split = (int)((units + want - 1) / want);
+    k.n_split = (int)((units + k.units_per_split - 1) / k.units_per_split);
+    pl.partial_bytes = k.n_split > 1 ? (size_t)tiles * k.n_split * 144 * 256 * 4 : 0;
+    pl.grid = (int)(tiles * k.n_split);
+    pl.reduce_grid = (int)(tiles * 36 * 16);                         // (tile, group of 4 accumulator elements, 16 of the 256 slots)
+    return pl;
+}
+
+hipError_t launch_conv_dw_i8(const ConvDwI8Plan &pl, hipStream_t s)
+{
+    static bool raised = false;                                      // more than 64 KiB of dynamic LDS: allowed per kernel, once
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dw_i8_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, CDW_MAX_LDS);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL(conv_dw_i8_kernel, dim3(pl.grid), dim3(512), pl.lds_bytes, s, pl.args);
+    if (pl.args.n_split > 1) {
+        ConvDwArgs r{};                                              // the reduction reads the partial layout of both dW kernels
+        r.partial = pl.args.partial; r.dW = pl.args.dW; r.n_split = pl.args.n_split; r.tiles_k = pl.args.tiles_k;
+        r.K = pl.args.K; r.C = pl.args.C; r.scale = Scale{1.0f, nullptr};
+        hipLaunchKernelGGL((conv_dw_reduce_kernel<MODE_I8, 3, 3, 1>), dim3(pl.reduce_grid), dim3(256), 0, s, r);
+    }
+    return hipGetLastError();
+}
+
 template <int MODE, int R, int S, int PAD, int MB, bool ROW4>
 hipError_t launch_conv_dw_fast_as(const ConvDwPlan &pl, hipStream_t s)
 {
@@ -364,6 +431,8 @@ size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K
         const ConvDwPlan pl = conv_dw_plan(N, C, H, Wd, K, R, S, pad, i8 != 0);
         if (pl.ok && pl.partial_bytes > big) big = pl.partial_bytes;
     }
+    const ConvDwI8Plan p8 = conv_dw_i8_plan(N, C, H, Wd, K, R, S, pad);
+    if (p8.ok && p8.partial_bytes > big) big = p8.partial_bytes;
     return relayout_bytes(K, C, R, S) + align_up(big, 256) + 256;
 }
 
@@ -611,6 +680,14 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
 {
     using Acc = typename ModeTraits<MODE>::Acc;
     const size_t rb = relayout_bytes(a.K, a.C, a.R, a.S);
+    if constexpr (MODE == MODE_I8) {
+        ConvDwI8Plan p8 = conv_dw_i8_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad);
+        if (p8.ok && a.stride == 1 && rb + p8.partial_bytes <= a.scratch_bytes && (uintptr_t)a.X % 4 == 0 && (uintptr_t)grad % 4 == 0) {
+            ConvDwI8Args &k = p8.args;
+            k.codes = (const int8_t *)grad; k.X = (const int8_t *)a.X; k.dW = (int32_t *)a.dW; k.partial = (int32_t *)((char *)a.scratch + rb);
+            return launch_conv_dw_i8(p8, s);
+        }
+    }
     if constexpr (MODE != MODE_F32) {
         ConvDwPlan pl = conv_dw_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad, MODE == MODE_I8);
         if (a.stride != 1) pl.ok = false;                            // the fast kernel is a stride-1 kernel

@@ -85,6 +85,26 @@ def test_conv_int8_mode_is_bit_exact(case):
     _check(p, run_conv(p))
 
 
+I8_ROWS = [  # 3x3, padding 1, rows of a multiple of 4 pixels: the int8 dW kernel that loads whole 16-pixel cells
+    (2, 64, 16, 16, 64, 3, 3, 1),       # one full cell per row, a whole image per unit
+    (2, 70, 32, 32, 130, 3, 3, 1),      # two full cells; partial channel tiles on both sides
+    (3, 24, 17, 44, 40, 3, 3, 1),       # a partly filled last cell; image rows not a multiple of the unit
+    (1, 8, 5, 100, 16, 3, 3, 1),        # wide rows, few rows per unit
+    (2, 16, 9, 224, 8, 3, 3, 1),        # widest rows served: single-row units
+    (1, 8, 1, 16, 8, 3, 3, 1),          # an image of one row
+    (9, 64, 28, 28, 64, 3, 3, 1),       # a single tile: the reduction split over many units
+    (2, 32, 56, 56, 32, 3, 3, 1),       # the row geometry of the 8-bit VGG layer
+    (1, 16, 20, 228, 16, 3, 3, 1),      # rows too wide for it: the other kernels serve
+]
+
+
+@pytest.mark.parametrize("case", I8_ROWS)
+def test_conv_int8_whole_cell_rows_bit_exact(case):
+    from gpu_util import run_conv
+    p = _problem(*case, c=1.0, i8=True)
+    _check(p, run_conv(p))
+
+
 STRIDED = [  # N, C, H, Wd, K, R, S, pad, stride  (the strided layers of a ResNet: 3x3/2, 1x1/2 shortcuts, 7x7/2 stem)
     (2, 5, 9, 7, 6, 3, 3, 1, 2),
     (3, 16, 14, 14, 24, 3, 3, 1, 2),
