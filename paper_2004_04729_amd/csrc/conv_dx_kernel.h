@@ -19,6 +19,12 @@
 //   * The patch is double buffered over 32-channel reduction chunks: one barrier per chunk; the next
 //     chunk's codes are in flight as global loads during the current chunk's matrix-core phase.
 //   * The whole reduction stays inside the workgroup: no split-K, no second launch.
+//
+// Stride st > 1: dX[n,c,h,w] only receives the taps r with (h + pad - r) divisible by st (likewise s), so the output
+// pixels fall into st*st classes by (h mod st, w mod st), and each class is a stride-1 problem of its own on the same
+// code image: output i = (h - ph)/st, taps r = r0 + st*t with r0 = (ph + pad) mod st, code row i + (ph + pad - r0)/st - t.
+// The kernel therefore takes a row and a column padding, a tap count per direction and an output mapping
+// (virtual pixel (i, j) -> real pixel (st*i + ph, st*j + pw)); conv_dx_multi_kernel runs all classes in one launch.
 #pragma once
 #include "gemm_core.h"
 
@@ -32,8 +38,10 @@ struct ConvDxArgs {
     const int8_t *codes;      // [N][K][P][Q]
     const uint4  *wp;         // prepared weights, cell ((tap*KG + kg)*planes + plane)*Cp + c
     void         *dX;         // [N][C][H][Wd] fp32, or int32 in the int8 mode
-    int N, C, H, Wd, K, R, S, pad, P, Q;
+    int N, C, H, Wd, K, R, S, pad, P, Q;   // H, Wd, R, S, pad: of the (virtual) stride-1 problem; pad = row padding
+    int pad_w;                // column padding
     int PI, PQ;               // H*Wd, P*Q
+    int oW, oPI, ost, oh0, ow0;   // output: row length and pixels per channel of the real dX, pixel (i, j) -> (ost*i + oh0, ost*j + ow0)
     int Cp, KG, n_chunks;     // C rounded to 32; k-groups in total (K rounded to a chunk); chunks of CDX_KGC k-groups
     int wc, wpx;              // waves along channels x waves along pixels (wc * wpx == 4)
     int cgroups;              // ceil(C / (32*wc))
@@ -43,18 +51,39 @@ struct ConvDxArgs {
 };
 
 // fp32 weights [K][C][R][S] -> bf16 planes in fragment order (plane 0 = lo, 1 = mid, 2 = hi), zero padded.
-__global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W, uint4 *wp, int K, int C, int RS, int KG, int Cp)
+// Prepared tap t holds real tap real[t] (the identity for stride 1; the classes' taps one after the other otherwise).
+struct CdxTapMap { uint8_t real[64]; };
+
+// The map is copied to LDS with compile-time indices (a run-time index into a kernel argument would send the whole
+// argument through private memory); MAPPED = false: the identity, no map.
+template <bool MAPPED>
+__device__ __forceinline__ void cdx_stage_map(uint8_t (&lm)[64], const CdxTapMap &map)
 {
+    if constexpr (MAPPED) {
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int t = 0; t < 64; ++t) lm[t] = map.real[t];
+        }
+        __syncthreads();
+    }
+}
+
+template <bool MAPPED>
+__global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W, uint4 *wp, int K, int C, int RS, int KG, int Cp, int RS_real, CdxTapMap map)
+{
+    __shared__ uint8_t lm[64];
+    cdx_stage_map<MAPPED>(lm, map);
     const int64_t total = (int64_t)RS * KG * Cp;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
         const int c = (int)(i % Cp);
         const int64_t t = i / Cp;
         const int kg = (int)(t % KG), tap = (int)(t / KG);
+        const int rtap = MAPPED ? (int)lm[tap] : tap;
         uint32_t h[8], m[8], l[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int k = kg * 8 + j;
-            const float w = (k < K && c < C) ? W[((int64_t)k * C + c) * RS + tap] : 0.0f;
+            const float w = (k < K && c < C) ? W[((int64_t)k * C + c) * RS_real + rtap] : 0.0f;
             split3(w, h[j], m[j], l[j]);
         }
         uint4 *dst = wp + ((int64_t)tap * KG + kg) * 3 * Cp + c;
@@ -65,18 +94,22 @@ __global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W
 }
 
 // int8 weights [K][C][R][S] -> cells of 16 reduction channels in fragment order [tap][k-group][c], zero padded.
-__global__ __launch_bounds__(256) void conv_dx_weight_prep_i8_kernel(const int8_t *W, uint4 *wp, int K, int C, int RS, int KG, int Cp)
+template <bool MAPPED>
+__global__ __launch_bounds__(256) void conv_dx_weight_prep_i8_kernel(const int8_t *W, uint4 *wp, int K, int C, int RS, int KG, int Cp, int RS_real, CdxTapMap map)
 {
+    __shared__ uint8_t lm[64];
+    cdx_stage_map<MAPPED>(lm, map);
     const int64_t total = (int64_t)RS * KG * Cp;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
         const int c = (int)(i % Cp);
         const int64_t t = i / Cp;
         const int kg = (int)(t % KG), tap = (int)(t / KG);
+        const int rtap = MAPPED ? (int)lm[tap] : tap;
         uint32_t d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int k = kg * 16 + j;
-            const uint32_t w = (k < K && c < C) ? (uint32_t)(uint8_t)W[((int64_t)k * C + c) * RS + tap] : 0u;
+            const uint32_t w = (k < K && c < C) ? (uint32_t)(uint8_t)W[((int64_t)k * C + c) * RS_real + rtap] : 0u;
             d[j >> 2] |= w << (8 * (j & 3));
         }
         wp[i] = uint4{d[0], d[1], d[2], d[3]};
@@ -94,17 +127,19 @@ __device__ __forceinline__ uint32_t cdx_bf16_pair(uint32_t wa, uint32_t wb, int 
     return __builtin_amdgcn_perm(__float_as_uint(fb), __float_as_uint(fa), 0x07060302u);
 }
 
-template <int NB, int MODE>
-__global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
+extern __shared__ uint4 cdx_lds[];                           // [2][CDX_KGC][patch_cells]
+
+// STRIDED = false: the column padding is the row padding and a pixel's flat index is its place in dX (compile-time
+// facts of the stride-1 launch).
+template <int NB, int MODE, bool STRIDED>
+__device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
 {
     using TR = CdxTraits<MODE>;
     constexpr int G = TR::G, PL = TR::PL;                       // reduction channels per cell; weight planes
-    extern __shared__ uint4 cdx_lds[];                       // [2][CDX_KGC][patch_cells]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lcol = lane & 31, lhalf = lane >> 5;
 
     // ---- which tile ------------------------------------------------------------------------------
-    int b = blockIdx.x;
     const int cg = b % a.cgroups; b /= a.cgroups;
     const int tile = b % a.tiles, n = b / a.tiles;
     const int wave_c = wave % a.wc, wave_p = wave / a.wc;
@@ -116,7 +151,7 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 
     // patch geometry: code rows p_lo..p_hi, columns q_lo..q_lo+pw-1
     const int h_first = j0 / a.Wd, h_last = (j_end - 1) / a.Wd;
-    const int p_lo = h_first + a.pad - (a.R - 1), q_lo = a.pad - (a.S - 1);
+    const int p_lo = h_first + a.pad - (a.R - 1), q_lo = (STRIDED ? a.pad_w : a.pad) - (a.S - 1);
     const int p_a = max(p_lo, 0), p_b = min(h_last + a.pad, a.P - 1);   // rows that exist in the code image
     const int buf_cells = CDX_KGC * a.patch_cells;
 
@@ -267,24 +302,46 @@ __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 
     // ---- store: lane holds pixel column lcol, channel rows 8*(v/4) + 4*lhalf + v%4 of its block ----
     if (wave_active) {
-        typename TR::Out *out = (typename TR::Out *)a.dX + (int64_t)n * a.C * a.PI;   // offsets inside one image fit 31 bits (host check)
+        typename TR::Out *out = (typename TR::Out *)a.dX + (int64_t)n * a.C * (STRIDED ? a.oPI : a.PI);  // offsets inside one image fit 31 bits (host check)
         const float sc = MODE == MODE_I8 ? 1.0f : a.scale.get();
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int j = jw0 + 32 * nb + lcol;
             if (j >= j_end) continue;
             const int c0 = cb * 32 + 4 * lhalf;
-            int off = c0 * a.PI + j;
+            int px = j;                                           // where the pixel sits in the real dX plane
+            if constexpr (STRIDED) { const int h = j / a.Wd, w = j - h * a.Wd; px = (a.ost * h + a.oh0) * a.oW + a.ost * w + a.ow0; }
+            const int opi = STRIDED ? a.oPI : a.PI;
+            int off = c0 * opi + px;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int c = c0 + 8 * (v >> 2) + (v & 3);
                 if (c < a.C) {
                     if constexpr (MODE == MODE_I8) out[off] = acc[nb][v]; else out[off] = acc[nb][v] * sc;
                 }
-                off += (v & 3) == 3 ? 5 * a.PI : a.PI;
+                off += (v & 3) == 3 ? 5 * opi : opi;
             }
         }
     }
+}
+
+template <int NB, int MODE>
+__global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
+{
+    conv_dx_body<NB, MODE, false>(a, (int)blockIdx.x);
+}
+
+// The classes of a strided problem in one launch: workgroups [first[i], first[i + 1]) run class i.
+constexpr int CDX_MAX_CLASSES = 9;
+struct ConvDxMulti { ConvDxArgs cls[CDX_MAX_CLASSES]; int first[CDX_MAX_CLASSES + 1]; int n; };
+
+template <int NB, int MODE>
+__global__ __launch_bounds__(256, 2) void conv_dx_multi_kernel(ConvDxMulti m)
+{
+    int ci = 0;
+    for (int i = 1; i < m.n; ++i) if ((int)blockIdx.x >= m.first[i]) ci = i;
+    const ConvDxArgs a = m.cls[ci];
+    conv_dx_body<NB, MODE, true>(a, (int)blockIdx.x - m.first[ci]);
 }
 
 }  // namespace dbp

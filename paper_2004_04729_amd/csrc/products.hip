@@ -97,21 +97,18 @@ size_t relayout_bytes(int64_t K, int64_t C, int64_t R, int64_t S)
     return align_up(generic > fast ? generic : fast, 256);
 }
 
-// Geometry of the fast dX kernel for one problem, or ok == false when the generic kernel has to serve.
+// Geometry of the fast dX kernel for one stride-1 problem (a whole layer, or one class of a strided layer), or
+// ok == false when the generic kernel has to serve.  `k` arrives with the problem (N, C, H, Wd, K, R, S, pad, pad_w, P, Q
+// and the output mapping) filled in; force_nb != 0 asks for that pixel-block count only.
 struct ConvDxPlan { bool ok; int nb; ConvDxArgs args; size_t lds_bytes; int grid; };
 
-ConvDxPlan conv_dx_plan(const ConvArgs &a, bool i8 = false)
+static void conv_dx_plan_core(ConvDxPlan &pl, bool i8, int force_nb)
 {
-    ConvDxPlan pl;
-    pl.ok = false;
     ConvDxArgs &k = pl.args;
-    if (a.stride != 1) return pl;                                // the fast kernels are stride-1 kernels
-    k.N = (int)a.N; k.C = (int)a.C; k.H = (int)a.H; k.Wd = (int)a.Wd; k.K = (int)a.K; k.R = (int)a.R; k.S = (int)a.S;
-    k.pad = (int)a.pad;
-    k.P = k.H + 2 * k.pad - k.R + 1; k.Q = k.Wd + 2 * k.pad - k.S + 1;
+    pl.ok = false;
     k.PI = k.H * k.Wd; k.PQ = k.P * k.Q;
-    if (k.PQ % 4 || ((uintptr_t)a.codes % 4)) return pl;         // the patch fill reads aligned dwords of a code plane
-    if ((int64_t)(k.C + 32) * k.PI >= ((int64_t)1 << 31)) return pl;   // 32-bit offsets inside one image
+    if (k.PQ % 4) return;                                        // the patch fill reads aligned dwords of a code plane
+    if ((int64_t)(k.C + 32) * k.oPI >= ((int64_t)1 << 31)) return;   // 32-bit offsets inside one image
     k.Cp = (k.C + 31) / 32 * 32;
     const int chunk_k = CDX_KGC * (i8 ? 16 : 8);                 // reduction channels per chunk
     k.KG = (k.K + chunk_k - 1) / chunk_k * CDX_KGC;
@@ -125,6 +122,7 @@ ConvDxPlan conv_dx_plan(const ConvArgs &a, bool i8 = false)
     const int cand[2] = {7, 4};
     for (int ci = 0; ci < 2; ++ci) {
         const int nb = cand[ci], tile_px = k.wpx * 32 * nb;
+        if (force_nb && nb != force_nb) continue;
         const int tiles = (k.PI + tile_px - 1) / tile_px;
         int prow = 0, n_dw = 0;
         for (int t = 0; t < tiles; ++t) {
@@ -140,7 +138,8 @@ ConvDxPlan conv_dx_plan(const ConvArgs &a, bool i8 = false)
         }
         const int64_t cells = (int64_t)prow * k.pw;
         const size_t lds = (size_t)2 * CDX_KGC * cells * 16;
-        if (lds > (size_t)CDX_MAX_LDS || (int64_t)n_dw * CDX_KGC > 256 * CDX_ITMAX) continue;
+        // cell indices travel as 16-bit numbers, 0xFFFF meaning "no cell"
+        if (lds > (size_t)CDX_MAX_LDS || (int64_t)n_dw * CDX_KGC > 256 * CDX_ITMAX || CDX_KGC * cells >= 0xFFFF) continue;
         // time ~ rounds of workgroups over the chip (two resident per CU) x work per workgroup
         const int64_t grid = (int64_t)k.N * tiles * k.cgroups;
         const double cost = (double)nb * (double)((grid + 511) / 512);
@@ -149,11 +148,78 @@ ConvDxPlan conv_dx_plan(const ConvArgs &a, bool i8 = false)
             k.tiles = tiles; k.prow = prow; k.patch_cells = (int)cells;
         }
     }
-    if (!pl.ok) return pl;
+    if (!pl.ok) return;
     const int64_t grid = (int64_t)k.N * k.tiles * k.cgroups;
-    if (grid > 0x7FFFFFFF) { pl.ok = false; return pl; }
+    if (grid > 0x7FFFFFFF) { pl.ok = false; return; }
     pl.grid = (int)grid;
+}
+
+ConvDxPlan conv_dx_plan(const ConvArgs &a, bool i8 = false)
+{
+    ConvDxPlan pl;
+    pl.ok = false;
+    ConvDxArgs &k = pl.args;
+    if (a.stride != 1) return pl;                                // strided layers: conv_dx_strided_plan
+    if ((uintptr_t)a.codes % 4) return pl;                       // aligned dwords of a code plane
+    k.N = (int)a.N; k.C = (int)a.C; k.H = (int)a.H; k.Wd = (int)a.Wd; k.K = (int)a.K; k.R = (int)a.R; k.S = (int)a.S;
+    k.pad = (int)a.pad; k.pad_w = (int)a.pad;
+    k.P = k.H + 2 * k.pad - k.R + 1; k.Q = k.Wd + 2 * k.pad - k.S + 1;
+    k.oW = k.Wd; k.oPI = k.H * k.Wd; k.ost = 1; k.oh0 = 0; k.ow0 = 0;
+    conv_dx_plan_core(pl, i8, 0);
     return pl;
+}
+
+// A strided layer as st*st stride-1 problems, one per class of output pixels (h mod st, w mod st): class (ph, pw) has
+// the taps r = r0 + st*t, r0 = (ph + pad) mod st, and reads code row i + (ph + pad - r0)/st - t for its output row i.
+// Classes without taps (a 1x1 kernel with stride 2 has three) are all zero: `zero_fill` asks for dX to be cleared first.
+struct ConvDxStridedPlan { bool ok, zero_fill; int nb; ConvDxMulti multi; CdxTapMap map; int taps, tap_base[CDX_MAX_CLASSES]; size_t lds_bytes; int grid; };
+
+ConvDxStridedPlan conv_dx_strided_plan(const ConvArgs &a, bool i8)
+{
+    ConvDxStridedPlan sp;
+    sp.ok = false; sp.zero_fill = false; sp.taps = 0; sp.lds_bytes = 0; sp.grid = 0;
+    const int st = (int)a.stride, R = (int)a.R, S = (int)a.S, pad = (int)a.pad, H = (int)a.H, Wd = (int)a.Wd;
+    if (st < 2 || st * st > CDX_MAX_CLASSES || R * S > 64 || (uintptr_t)a.codes % 4) return sp;
+    const int P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
+    for (int attempt = 0; attempt < 2 && !sp.ok; ++attempt) {
+        const int nb = attempt == 0 ? 7 : 4;                     // one pixel-block count for all classes (one launch)
+        bool all = true;
+        sp.multi.n = 0; sp.taps = 0; sp.zero_fill = false; sp.lds_bytes = 0;
+        int64_t grid = 0;
+        for (int ph = 0; ph < st && all; ++ph) {
+            for (int pw = 0; pw < st && all; ++pw) {
+                const int Hv = ph < H ? (H - ph + st - 1) / st : 0, Wv = pw < Wd ? (Wd - pw + st - 1) / st : 0;
+                if (Hv == 0 || Wv == 0) continue;                // no such pixels
+                const int r0 = (ph + pad) % st, s0 = (pw + pad) % st;
+                const int Rv = r0 < R ? (R - r0 + st - 1) / st : 0, Sv = s0 < S ? (S - s0 + st - 1) / st : 0;
+                if (Rv == 0 || Sv == 0) { sp.zero_fill = true; continue; }
+                ConvDxPlan pl;
+                ConvDxArgs &k = pl.args;
+                k.N = (int)a.N; k.C = (int)a.C; k.H = Hv; k.Wd = Wv; k.K = (int)a.K; k.R = Rv; k.S = Sv;
+                k.pad = (ph + pad - r0) / st; k.pad_w = (pw + pad - s0) / st;
+                k.P = P; k.Q = Q;
+                k.oW = Wd; k.oPI = H * Wd; k.ost = st; k.oh0 = ph; k.ow0 = pw;
+                conv_dx_plan_core(pl, i8, nb);
+                if (!pl.ok) { all = false; break; }
+                // this class's prepared taps follow the earlier classes'
+                for (int t = 0; t < Rv; ++t)
+                    for (int u = 0; u < Sv; ++u) sp.map.real[sp.taps + t * Sv + u] = (uint8_t)((r0 + st * t) * S + (s0 + st * u));
+                k.codes = nullptr; k.wp = nullptr; k.dX = nullptr; k.scale = Scale{1.0f, nullptr};   // set at the launch
+                sp.multi.cls[sp.multi.n] = k;
+                sp.multi.first[sp.multi.n] = (int)grid;
+                sp.tap_base[sp.multi.n] = sp.taps;
+                sp.taps += Rv * Sv;
+                grid += pl.grid;
+                if (pl.lds_bytes > sp.lds_bytes) sp.lds_bytes = pl.lds_bytes;
+                ++sp.multi.n;
+            }
+        }
+        if (!all || grid > 0x7FFFFFFF) continue;
+        sp.multi.first[sp.multi.n] = (int)grid;
+        sp.ok = true; sp.nb = nb; sp.grid = (int)grid;
+    }
+    for (int t = sp.taps; t < 64; ++t) sp.map.real[t] = 0;
+    return sp;
 }
 
 
@@ -629,8 +695,14 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
     return e;
 }
 
+// Clears n 4-byte words (the output pixels of a strided layer that no tap reaches).
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
+}
+
 // ------------------------------------------------------------------------------------------------
-// Convolution (fast kernels: stride 1; any stride through the generic kernel).
+// Convolution (fast dX kernel: any stride; fast dW kernels: stride 1; the generic kernel serves the rest).
 // ------------------------------------------------------------------------------------------------
 template <int MODE_G>
 static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipStream_t s)
@@ -638,19 +710,46 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
     // MODE_G: MODE_BF16 (codes, fp32 weights), MODE_I8 (codes, int8 weights) or MODE_F32 (dense).
     if constexpr (MODE_G != MODE_F32) {
         constexpr bool I8 = MODE_G == MODE_I8;
+        constexpr int PL = I8 ? 1 : 3;
+        auto prepare = [&](int taps, int KG, int Cp, const CdxTapMap *map) {
+            const int64_t cells = (int64_t)taps * KG * Cp;
+            const int pb = (int)((cells + 255) / 256 < 4096 ? (cells + 255) / 256 : 4096);
+            const int rs = (int)(a.R * a.S);
+            if constexpr (I8) {
+                if (map) hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel<true>, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map);
+                else     hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel<false>, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{});
+            } else {
+                if (map) hipLaunchKernelGGL(conv_dx_weight_prep_kernel<true>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map);
+                else     hipLaunchKernelGGL(conv_dx_weight_prep_kernel<false>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{});
+            }
+        };
+        if (a.stride != 1) {
+            ConvDxStridedPlan sp = conv_dx_strided_plan(a, I8);
+            if (sp.ok) {
+                if (sp.zero_fill) {
+                    const int64_t n = a.N * a.C * a.H * a.Wd;                 // fp32 and int32 zeros are the same bytes
+                    const int fb = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+                    hipLaunchKernelGGL(zero_words_kernel, dim3(fb), dim3(256), 0, s, (uint32_t *)a.dX, n);
+                }
+                if (sp.multi.n > 0) {
+                    const int KG = sp.multi.cls[0].KG, Cp = sp.multi.cls[0].Cp;
+                    prepare(sp.taps, KG, Cp, &sp.map);
+                    for (int i = 0; i < sp.multi.n; ++i) {
+                        ConvDxArgs &k = sp.multi.cls[i];
+                        k.codes = (const int8_t *)grad; k.dX = a.dX; k.scale = scale;
+                        k.wp = (const uint4 *)a.scratch + (int64_t)sp.tap_base[i] * KG * PL * Cp;
+                    }
+                    if (sp.nb == 7) hipLaunchKernelGGL((conv_dx_multi_kernel<7, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
+                    else            hipLaunchKernelGGL((conv_dx_multi_kernel<4, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
+                }
+                return hipGetLastError();
+            }
+        }
         ConvDxPlan pl = conv_dx_plan(a, I8);
         if (pl.ok) {
             ConvDxArgs &k = pl.args;
             k.codes = (const int8_t *)grad; k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale;
-            const int64_t cells = (int64_t)k.R * k.S * k.KG * k.Cp;
-            const int pb = (int)((cells + 255) / 256 < 4096 ? (cells + 255) / 256 : 4096);
-            if constexpr (I8) {
-                hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch,
-                                   k.K, k.C, k.R * k.S, k.KG, k.Cp);
-            } else {
-                hipLaunchKernelGGL(conv_dx_weight_prep_kernel, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch,
-                                   k.K, k.C, k.R * k.S, k.KG, k.Cp);
-            }
+            prepare(k.R * k.S, k.KG, k.Cp, nullptr);
             if (pl.nb == 7) hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
             else            hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
             return hipGetLastError();

@@ -112,6 +112,14 @@ STRIDED = [  # N, C, H, Wd, K, R, S, pad, stride  (the strided layers of a ResNe
     (2, 3, 23, 20, 8, 7, 7, 3, 2),
     (2, 8, 11, 13, 9, 3, 3, 0, 3),       # stride 3, sizes that leave a remainder
     (4, 64, 28, 28, 128, 3, 3, 1, 2),
+    # strided dX as st*st stride-1 problems in one launch (taken when P*Q is a multiple of 4):
+    (2, 33, 16, 16, 20, 1, 1, 0, 2),     # 1x1 / 2: three classes without taps (cleared), one with the single tap
+    (2, 16, 12, 20, 24, 3, 3, 1, 2),
+    (2, 8, 15, 17, 8, 3, 3, 1, 2),       # odd image sizes: the classes have different extents
+    (2, 8, 16, 16, 8, 2, 2, 0, 2),       # even kernel: every class has exactly one tap
+    (1, 130, 8, 8, 70, 3, 3, 1, 2),      # partial channel blocks
+    (3, 12, 20, 24, 10, 5, 5, 2, 2),     # 5x5 / 2: classes of 3x3, 3x2, 2x3, 2x2 taps
+    (1, 8, 17, 17, 8, 3, 3, 1, 4),       # stride 4: more classes than one launch takes, generic kernel
 ]
 
 

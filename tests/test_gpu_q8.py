@@ -102,6 +102,10 @@ def test_fc_q8_single_products_and_dense_codes():
 CONV_CASES = [  # N, C, H, Wd, K, R, S, pad (, stride)
     (2, 8, 15, 14, 12, 3, 3, 1, 2),
     (2, 16, 14, 14, 24, 1, 1, 0, 2),
+    (3, 40, 28, 28, 72, 3, 3, 1, 2),    # strided dX as four stride-1 classes in one launch (P*Q a multiple of 4)
+    (2, 16, 16, 16, 24, 1, 1, 0, 2),    # 1x1 / 2: three classes without taps (cleared), one with the single tap
+    (2, 8, 15, 17, 8, 3, 3, 1, 2),      # odd image sizes: the classes have different extents
+    (2, 6, 11, 13, 9, 3, 3, 0, 3),      # stride 3: nine classes of one tap each
     (1, 1, 1, 1, 1, 1, 1, 0),
     (2, 5, 9, 7, 6, 3, 3, 1),
     (3, 16, 14, 14, 24, 3, 3, 1),
