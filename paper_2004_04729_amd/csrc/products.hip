@@ -7,6 +7,7 @@
 #include "conv_dx_kernel.h"
 #include "conv_dw_kernel.h"
 #include "conv_dw_i8_kernel.h"
+#include "conv_lower.h"
 
 namespace dbp {
 
@@ -481,6 +482,58 @@ size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
     return (generic > fast ? generic : fast) + 256;
 }
 
+// dW lowered to the fully connected kernels (conv_lower.h): taken for shapes the convolution dW kernels decline when the
+// column matrix is small enough to sit in the workspace.  esz = bytes per activation (4, or 1 in the 8-bit modes).
+struct ConvLowerPlan { bool ok; int64_t NPQ, CRS; size_t codes_bytes, col_bytes, fc_bytes, bytes; Im2colArgs im; size_t lds_bytes; };
+
+ConvLowerPlan conv_dw_lower_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride, int esz)
+{
+    ConvLowerPlan lp;
+    lp.ok = false; lp.bytes = 0;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    lp.NPQ = N * P * Q; lp.CRS = C * R * S;
+    // the product kernels want: reduction rows of the codes a multiple of 4 bytes, columns a multiple of 4 (fp32) or 8
+    // (int8) elements; below that, or when the products are tiny, the generic kernel serves
+    if (lp.NPQ % 4 || lp.NPQ < 64 || lp.CRS % (esz == 4 ? 4 : 8) || K < 16) return lp;
+    if (lp.NPQ * lp.CRS >= ((int64_t)1 << 30) || K * lp.NPQ >= ((int64_t)1 << 30) || K * lp.CRS >= ((int64_t)1 << 30)) return lp;
+    if ((double)lp.NPQ * lp.CRS * K < 2e8) return lp;              // launch-bound sizes: three more launches do not pay (measured)
+    lp.col_bytes = align_up((size_t)(lp.NPQ * lp.CRS) * esz, 256);
+    if (lp.col_bytes > ((size_t)256 << 20)) return lp;              // keep the workspace modest
+    lp.codes_bytes = align_up((size_t)(K * lp.NPQ), 256);
+    lp.fc_bytes = linear_scratch_bytes(K, lp.CRS, lp.NPQ);
+    lp.bytes = lp.codes_bytes + lp.col_bytes + lp.fc_bytes;
+    Im2colArgs &m = lp.im;
+    m.N = (int)N; m.C = (int)C; m.H = (int)H; m.Wd = (int)Wd; m.R = (int)R; m.S = (int)S; m.pad = (int)pad; m.st = (int)stride;
+    m.P = (int)P; m.Q = (int)Q;
+    // channels per workgroup: enough for 256 consecutive entries per output pixel; output rows per workgroup: what fits
+    const int64_t RS = R * S;
+    int64_t ct = (256 + RS - 1) / RS;
+    if (ct < 32) ct = 32;
+    if (ct > C) ct = C;
+    if (ct * RS >= (1 << 16) || R > 63 || S > 63) return lp;          // the entry table packs r and s into 6 bits each
+    const size_t budget = 40 * 1024;
+    int64_t pb = 0;
+    for (int64_t t = 1; t <= P; ++t) {
+        const int64_t hb = (t - 1) * stride + R < H ? (t - 1) * stride + R : H;
+        if ((size_t)(ct * (hb * Wd + 1)) * esz > budget) break;
+        pb = t;
+    }
+    if (pb == 0) return lp;
+    const int64_t ctiles = (C + ct - 1) / ct;
+    while (pb > 1 && N * ((P + pb - 1) / pb) * ctiles < 1024) --pb;   // enough workgroups to fill the chip
+    const int64_t hb = (pb - 1) * stride + R < H ? (pb - 1) * stride + R : H;
+    int64_t pitch = hb * Wd;
+    if (pitch % 2 == 0) ++pitch;                                      // odd: the channels of a pixel's entries spread over the banks
+    if (ct * pitch >= (1 << 20)) return lp;
+    m.CT = (int)ct; m.ctiles = (int)((C + ct - 1) / ct);
+    m.PB = (int)pb; m.bands = (int)((P + pb - 1) / pb);
+    m.pitch = (int)pitch;
+    lp.lds_bytes = (size_t)((ct * RS * 4 + 15) & ~15) + (size_t)(ct * pitch) * esz;
+    if (N * m.bands * m.ctiles > 0x7FFFFFFF) return lp;
+    lp.ok = true;
+    return lp;
+}
+
 size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride)
 {
     const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
@@ -499,6 +552,8 @@ size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K
     }
     const ConvDwI8Plan p8 = conv_dw_i8_plan(N, C, H, Wd, K, R, S, pad);
     if (p8.ok && p8.partial_bytes > big) big = p8.partial_bytes;
+    const ConvLowerPlan lp = conv_dw_lower_plan(N, C, H, Wd, K, R, S, pad, stride, 4);   // dW lowered to the FC kernels (fp32 X)
+    if (lp.ok && lp.bytes > big) big = lp.bytes;
     return relayout_bytes(K, C, R, S) + align_up(big, 256) + 256;
 }
 
@@ -795,6 +850,39 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
             ConvDwArgs &k = pl.args;
             k.codes = (const int8_t *)grad; k.X = a.X; k.dW = a.dW; k.partial = (char *)a.scratch + rb; k.scale = scale;
             return a.pad == 1 ? launch_conv_dw_fast<MODE, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE, 3, 3, 0, 1>(pl, s);
+        }
+    }
+    if constexpr (MODE != MODE_F32) {
+        // neither convolution kernel took it: expand the activations into the column matrix, re-lay the codes, and let the
+        // fully connected kernels do dW[k][(c,r,s)] = sum_(n,p,q) code[k][(n,p,q)] col[(n,p,q)][(c,r,s)]
+        // (int8 activations stay on the generic kernel: the column matrix would be written a byte at a time; measured slower)
+        constexpr int ESZ = MODE == MODE_I8 ? 1 : 4;
+        const ConvLowerPlan lp = conv_dw_lower_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad, a.stride, ESZ);
+        if (MODE == MODE_BF16 && lp.ok && rb + lp.bytes <= a.scratch_bytes && (uintptr_t)grad % 4 == 0 && (uintptr_t)a.X % 4 == 0 && (uintptr_t)a.dW % 16 == 0) {
+            int8_t *ck = (int8_t *)a.scratch + rb;
+            char *col = (char *)ck + lp.codes_bytes;
+            const int PQ = lp.im.P * lp.im.Q;
+            const int64_t groups = (int64_t)a.K * lp.NPQ / (PQ % 4 == 0 ? 4 : 1);
+            const int cb = (int)((groups + 255) / 256 < 8192 ? (groups + 255) / 256 : 8192);
+            if (PQ % 4 == 0) hipLaunchKernelGGL(conv_codes_kmajor_kernel<4>, dim3(cb), dim3(256), 0, s, (const int8_t *)grad, ck, (int)a.N, (int)a.K, PQ);
+            else             hipLaunchKernelGGL(conv_codes_kmajor_kernel<1>, dim3(cb), dim3(256), 0, s, (const int8_t *)grad, ck, (int)a.N, (int)a.K, PQ);
+            Im2colArgs im = lp.im;
+            im.X = a.X; im.col = col;
+            const int grid = (int)(a.N * im.bands * im.ctiles);
+            if constexpr (MODE == MODE_I8) hipLaunchKernelGGL(conv_im2col_kernel<int8_t>, dim3(grid), dim3(256), lp.lds_bytes, s, im);
+            else                           hipLaunchKernelGGL(conv_im2col_kernel<float>, dim3(grid), dim3(256), lp.lds_bytes, s, im);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            LinearArgs la{};
+            la.codes = ck; la.dense = nullptr; la.step = scale.host; la.step_dev = scale.dev;
+            la.W = MODE == MODE_I8 ? nullptr : (const float *)col;
+            la.W8 = MODE == MODE_I8 ? (const int8_t *)col : nullptr;
+            la.X = nullptr; la.x_dtype = MODE == MODE_I8 ? DBP_I8 : DBP_F32;
+            la.B = a.K; la.in = lp.CRS; la.out = lp.NPQ;
+            la.dX = (float *)a.dW; la.dW = nullptr;
+            la.scratch = col + lp.col_bytes; la.scratch_bytes = lp.fc_bytes;
+            la.stats_job = StatsJob{};
+            return launch_linear_mfma(la, s);
         }
     }
     ConvGeom g = make_geom(a, ModeTraits<MODE>::KCH, k_step<MODE>());

@@ -105,6 +105,22 @@ def test_conv_int8_whole_cell_rows_bit_exact(case):
     _check(p, run_conv(p))
 
 
+LOWERED = [  # N, C, H, Wd, K, R, S, pad, stride: large enough that dW runs as column matrix x fully connected kernels
+    (32, 128, 14, 14, 256, 1, 1, 0, 1),     # 1x1: the column matrix is the transposed activations
+    (16, 64, 28, 28, 128, 3, 3, 1, 2),      # 3x3 / 2
+    (8, 32, 20, 20, 96, 5, 5, 2, 1),        # 5x5, several bands of rows per image
+    (16, 64, 15, 15, 128, 3, 3, 1, 1),      # rows of 15 pixels: codes re-laid a byte at a time
+    (64, 132, 24, 20, 264, 1, 1, 0, 2),     # 1x1 / 2, channel counts that are not tile multiples
+]
+
+
+@pytest.mark.parametrize("case", LOWERED)
+def test_conv_dw_lowered_to_fc_kernels(case):
+    from gpu_util import run_conv
+    p = _problem(*case[:8], stride=case[8])
+    _check(p, run_conv(p))
+
+
 STRIDED = [  # N, C, H, Wd, K, R, S, pad, stride  (the strided layers of a ResNet: 3x3/2, 1x1/2 shortcuts, 7x7/2 stem)
     (2, 5, 9, 7, 6, 3, 3, 1, 2),
     (3, 16, 14, 14, 24, 3, 3, 1, 2),
