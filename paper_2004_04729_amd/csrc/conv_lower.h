@@ -41,8 +41,9 @@ struct Im2colArgs {
 // [channel][row][w] with loads that run along the rows; then the threads walk the band's output, (pixel, entry) with
 // the entry (c,r,s) fastest, so that stores run along the rows of the column matrix.  Indices advance by additions
 // (thread i handles elements i, i + 256, ...: both coordinates move by constants with a carry); the only divisions
-// are in the table that maps an entry to its LDS offset and taps, built once per workgroup.
-template <class T>
+// are in the table that maps an entry to its LDS offset and taps, built once per workgroup.  VEC = 4: a thread writes four
+// consecutive entries with one store (every tile's entry count and every row of the column matrix a multiple of 4).
+template <class T, int VEC>
 __global__ __launch_bounds__(256) void conv_im2col_kernel(Im2colArgs a)
 {
     extern __shared__ unsigned char im2col_lds[];
@@ -73,23 +74,27 @@ __global__ __launch_bounds__(256) void conv_im2col_kernel(Im2colArgs a)
         }
     }
     __syncthreads();
-    // ---- store: element i = (pixel, e), pixel = (p - p0) * Q + q ----
+    // ---- store: element i = (pixel, group of VEC entries), pixel = (p - p0) * Q + q ----
     const int64_t CRS = (int64_t)a.C * RS;
     T *col = (T *)a.col + ((int64_t)n * a.P + p0) * a.Q * CRS + (int64_t)c0 * RS;
-    const int n_px = np * a.Q;
-    const int dpx = 256 / run, de = 256 - dpx * run;            // per step of 256 elements
+    const int n_px = np * a.Q, groups = run / VEC;
+    const int dpx = 256 / groups, dg = 256 - dpx * groups;      // per step of 256 elements
     const int dp = dpx / a.Q, dq = dpx - dp * a.Q;
-    int px = threadIdx.x / run, e = threadIdx.x - px * run;
+    int px = threadIdx.x / groups, g = threadIdx.x - px * groups;
     int pl = px / a.Q, q = px - pl * a.Q;                       // row of the band, column
+    struct alignas(sizeof(T) * VEC) Pack { T v[VEC]; };
     while (px < n_px) {
-        const uint32_t t = tab[e];
-        const int r = (t >> 20) & 63, s = t >> 26;
-        const int h = (p0 + pl) * a.st + r - a.pad, w = q * a.st + s - a.pad;
-        T v = (T)0;
-        if (h >= h_lo && h <= h_hi && w >= 0 && w < a.Wd) v = rows[(t & 0xFFFFFu) + (h - h_lo) * a.Wd + w];
-        col[(int64_t)px * CRS + e] = v;
-        px += dpx; e += de; pl += dp; q += dq;
-        if (e >= run) { e -= run; ++px; ++q; }
+        Pack out;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+            const uint32_t t = tab[g * VEC + i];
+            const int r = (t >> 20) & 63, s = t >> 26;
+            const int h = (p0 + pl) * a.st + r - a.pad, w = q * a.st + s - a.pad;
+            out.v[i] = (h >= h_lo && h <= h_hi && w >= 0 && w < a.Wd) ? rows[(t & 0xFFFFFu) + (h - h_lo) * a.Wd + w] : (T)0;
+        }
+        *(Pack *)(col + (int64_t)px * CRS + g * VEC) = out;
+        px += dpx; g += dg; pl += dp; q += dq;
+        if (g >= groups) { g -= groups; ++px; ++q; }
         if (q >= a.Q) { q -= a.Q; ++pl; }
         if (q >= a.Q) { q -= a.Q; ++pl; }
     }

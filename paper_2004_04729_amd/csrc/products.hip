@@ -484,7 +484,7 @@ size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
 
 // dW lowered to the fully connected kernels (conv_lower.h): taken for shapes the convolution dW kernels decline when the
 // column matrix is small enough to sit in the workspace.  esz = bytes per activation (4, or 1 in the 8-bit modes).
-struct ConvLowerPlan { bool ok; int64_t NPQ, CRS; size_t codes_bytes, col_bytes, fc_bytes, bytes; Im2colArgs im; size_t lds_bytes; };
+struct ConvLowerPlan { bool ok, vec4; int64_t NPQ, CRS; size_t codes_bytes, col_bytes, fc_bytes, bytes; Im2colArgs im; size_t lds_bytes; };
 
 ConvLowerPlan conv_dw_lower_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride, int esz)
 {
@@ -509,7 +509,9 @@ ConvLowerPlan conv_dw_lower_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, in
     const int64_t RS = R * S;
     int64_t ct = (256 + RS - 1) / RS;
     if (ct < 32) ct = 32;
+    ct = (ct + 3) / 4 * 4;
     if (ct > C) ct = C;
+    lp.vec4 = RS % 4 == 0 || (C % 4 == 0 && ct % 4 == 0);             // every tile's entries and every matrix row: multiples of 4
     if (ct * RS >= (1 << 16) || R > 63 || S > 63) return lp;          // the entry table packs r and s into 6 bits each
     const size_t budget = 40 * 1024;
     int64_t pb = 0;
@@ -552,8 +554,10 @@ size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K
     }
     const ConvDwI8Plan p8 = conv_dw_i8_plan(N, C, H, Wd, K, R, S, pad);
     if (p8.ok && p8.partial_bytes > big) big = p8.partial_bytes;
-    const ConvLowerPlan lp = conv_dw_lower_plan(N, C, H, Wd, K, R, S, pad, stride, 4);   // dW lowered to the FC kernels (fp32 X)
-    if (lp.ok && lp.bytes > big) big = lp.bytes;
+    for (int esz = 1; esz <= 4; esz += 3) {                          // dW lowered to the FC kernels, either X type
+        const ConvLowerPlan lp = conv_dw_lower_plan(N, C, H, Wd, K, R, S, pad, stride, esz);
+        if (lp.ok && lp.bytes > big) big = lp.bytes;
+    }
     return relayout_bytes(K, C, R, S) + align_up(big, 256) + 256;
 }
 
@@ -855,10 +859,10 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
     if constexpr (MODE != MODE_F32) {
         // neither convolution kernel took it: expand the activations into the column matrix, re-lay the codes, and let the
         // fully connected kernels do dW[k][(c,r,s)] = sum_(n,p,q) code[k][(n,p,q)] col[(n,p,q)][(c,r,s)]
-        // (int8 activations stay on the generic kernel: the column matrix would be written a byte at a time; measured slower)
         constexpr int ESZ = MODE == MODE_I8 ? 1 : 4;
         const ConvLowerPlan lp = conv_dw_lower_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad, a.stride, ESZ);
-        if (MODE == MODE_BF16 && lp.ok && rb + lp.bytes <= a.scratch_bytes && (uintptr_t)grad % 4 == 0 && (uintptr_t)a.X % 4 == 0 && (uintptr_t)a.dW % 16 == 0) {
+        if (lp.ok && (MODE == MODE_BF16 || lp.vec4) &&      // int8 entries written one byte at a time: measured slower than generic
+            rb + lp.bytes <= a.scratch_bytes && (uintptr_t)grad % 4 == 0 && (uintptr_t)a.X % 4 == 0 && (uintptr_t)a.dW % 16 == 0) {
             int8_t *ck = (int8_t *)a.scratch + rb;
             char *col = (char *)ck + lp.codes_bytes;
             const int PQ = lp.im.P * lp.im.Q;
@@ -869,8 +873,9 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
             Im2colArgs im = lp.im;
             im.X = a.X; im.col = col;
             const int grid = (int)(a.N * im.bands * im.ctiles);
-            if constexpr (MODE == MODE_I8) hipLaunchKernelGGL(conv_im2col_kernel<int8_t>, dim3(grid), dim3(256), lp.lds_bytes, s, im);
-            else                           hipLaunchKernelGGL(conv_im2col_kernel<float>, dim3(grid), dim3(256), lp.lds_bytes, s, im);
+            using XT = typename std::conditional<MODE == MODE_I8, int8_t, float>::type;
+            if (lp.vec4) hipLaunchKernelGGL((conv_im2col_kernel<XT, 4>), dim3(grid), dim3(256), lp.lds_bytes, s, im);
+            else         hipLaunchKernelGGL((conv_im2col_kernel<XT, 1>), dim3(grid), dim3(256), lp.lds_bytes, s, im);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
             LinearArgs la{};

@@ -119,6 +119,8 @@ def test_conv_dw_lowered_to_fc_kernels(case):
     from gpu_util import run_conv
     p = _problem(*case[:8], stride=case[8])
     _check(p, run_conv(p))
+    p8 = _problem(*case[:8], c=1.0, i8=True, stride=case[8])      # int8 X: the same lowering on the int8 kernels, exact int32
+    _check(p8, run_conv(p8))
 
 
 STRIDED = [  # N, C, H, Wd, K, R, S, pad, stride  (the strided layers of a ResNet: 3x3/2, 1x1/2 shortcuts, 7x7/2 stem)
