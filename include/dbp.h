@@ -161,8 +161,8 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
  *   dW[k,c,r,s] = Delta * sum_{n,p,q} code[n,k,p,q] X[n,c,p*stride+r-pad,q*stride+s-pad]
  * computed as implicit-im2col GEMMs (no im2col buffer is materialised).  x_dtype as above.
  * Errors as above.  Stride 1 runs on the specialised kernels; with another stride dX runs on them as stride*stride
- * stride-1 problems (one per class of output pixels modulo the stride) when stride <= 3 and P*Q is a multiple of 4,
- * and everything else on the generic implicit-im2col kernel.
+ * stride-1 problems (one per class of output pixels modulo the stride) when stride <= 3, dW as a column-matrix
+ * product on the fully connected kernels when the layer is large enough, the rest on the generic implicit-im2col kernel.
  */
 dbp_status dithered_conv2d_backward(const float *delta, const float *W, const void *X,
                                     dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H,

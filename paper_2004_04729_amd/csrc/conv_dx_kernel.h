@@ -35,12 +35,12 @@ constexpr int CDX_ITMAX = 2;          // patch-fill items per thread and chunk, 
 constexpr int CDX_MAX_LDS = 64 * 1024;   // dynamic LDS a launch may ask for without raising the function attribute
 
 struct ConvDxArgs {
-    const int8_t *codes;      // [N][K][P][Q]
+    const int8_t *codes;      // [N][K][P][Q], planes PQ bytes apart and 4-byte aligned
     const uint4  *wp;         // prepared weights, cell ((tap*KG + kg)*planes + plane)*Cp + c
     void         *dX;         // [N][C][H][Wd] fp32, or int32 in the int8 mode
     int N, C, H, Wd, K, R, S, pad, P, Q;   // H, Wd, R, S, pad: of the (virtual) stride-1 problem; pad = row padding
     int pad_w;                // column padding
-    int PI, PQ;               // H*Wd, P*Q
+    int PI, PQ;               // H*Wd; bytes from one code plane to the next (P*Q, or P*Q rounded up to 4 in a padded copy)
     int oW, oPI, ost, oh0, ow0;   // output: row length and pixels per channel of the real dX, pixel (i, j) -> (ost*i + oh0, ost*j + ow0)
     int Cp, KG, n_chunks;     // C rounded to 32; k-groups in total (K rounded to a chunk); chunks of CDX_KGC k-groups
     int wc, wpx;              // waves along channels x waves along pixels (wc * wpx == 4)
@@ -113,6 +113,23 @@ __global__ __launch_bounds__(256) void conv_dx_weight_prep_i8_kernel(const int8_
             d[j >> 2] |= w << (8 * (j & 3));
         }
         wp[i] = uint4{d[0], d[1], d[2], d[3]};
+    }
+}
+
+// Code planes of P*Q bytes -> planes of `plane` bytes (a multiple of 4, zero filled): the patch fill reads aligned dwords.
+__global__ __launch_bounds__(256) void conv_dx_pad_codes_kernel(const int8_t *src, uint32_t *dst, int64_t planes, int pq, int plane)
+{
+    const int dpp = plane >> 2;                                  // dwords per padded plane
+    const int64_t total = planes * dpp;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t pl = i / dpp;
+        const int j0 = 4 * (int)(i - pl * dpp);
+        const int8_t *s = src + pl * pq + j0;
+        uint32_t v = 0u;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (j0 + e < pq) v |= (uint32_t)(uint8_t)s[e] << (8 * e);
+        dst[i] = v;
     }
 }
 

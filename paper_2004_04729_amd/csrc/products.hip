@@ -107,8 +107,7 @@ static void conv_dx_plan_core(ConvDxPlan &pl, bool i8, int force_nb)
 {
     ConvDxArgs &k = pl.args;
     pl.ok = false;
-    k.PI = k.H * k.Wd; k.PQ = k.P * k.Q;
-    if (k.PQ % 4) return;                                        // the patch fill reads aligned dwords of a code plane
+    k.PI = k.H * k.Wd; k.PQ = (k.P * k.Q + 3) / 4 * 4;           // the patch fill reads aligned dwords of a code plane: see conv_dx_codes
     if ((int64_t)(k.C + 32) * k.oPI >= ((int64_t)1 << 31)) return;   // 32-bit offsets inside one image
     k.Cp = (k.C + 31) / 32 * 32;
     const int chunk_k = CDX_KGC * (i8 ? 16 : 8);                 // reduction channels per chunk
@@ -161,7 +160,6 @@ ConvDxPlan conv_dx_plan(const ConvArgs &a, bool i8 = false)
     pl.ok = false;
     ConvDxArgs &k = pl.args;
     if (a.stride != 1) return pl;                                // strided layers: conv_dx_strided_plan
-    if ((uintptr_t)a.codes % 4) return pl;                       // aligned dwords of a code plane
     k.N = (int)a.N; k.C = (int)a.C; k.H = (int)a.H; k.Wd = (int)a.Wd; k.K = (int)a.K; k.R = (int)a.R; k.S = (int)a.S;
     k.pad = (int)a.pad; k.pad_w = (int)a.pad;
     k.P = k.H + 2 * k.pad - k.R + 1; k.Q = k.Wd + 2 * k.pad - k.S + 1;
@@ -180,7 +178,7 @@ ConvDxStridedPlan conv_dx_strided_plan(const ConvArgs &a, bool i8)
     ConvDxStridedPlan sp;
     sp.ok = false; sp.zero_fill = false; sp.taps = 0; sp.lds_bytes = 0; sp.grid = 0;
     const int st = (int)a.stride, R = (int)a.R, S = (int)a.S, pad = (int)a.pad, H = (int)a.H, Wd = (int)a.Wd;
-    if (st < 2 || st * st > CDX_MAX_CLASSES || R * S > 64 || (uintptr_t)a.codes % 4) return sp;
+    if (st < 2 || st * st > CDX_MAX_CLASSES || R * S > 64) return sp;
     const int P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
     for (int attempt = 0; attempt < 2 && !sp.ok; ++attempt) {
         const int nb = attempt == 0 ? 7 : 4;                     // one pixel-block count for all classes (one launch)
@@ -554,6 +552,8 @@ size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K
     }
     const ConvDwI8Plan p8 = conv_dw_i8_plan(N, C, H, Wd, K, R, S, pad);
     if (p8.ok && p8.partial_bytes > big) big = p8.partial_bytes;
+    const size_t padded = (size_t)(N * K * ((P * Q + 3) / 4 * 4));    // dX: the codes in planes that start on 4-byte boundaries
+    if (padded > big) big = padded;
     for (int esz = 1; esz <= 4; esz += 3) {                          // dW lowered to the FC kernels, either X type
         const ConvLowerPlan lp = conv_dw_lower_plan(N, C, H, Wd, K, R, S, pad, stride, esz);
         if (lp.ok && lp.bytes > big) big = lp.bytes;
@@ -782,7 +782,22 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
                 else     hipLaunchKernelGGL(conv_dx_weight_prep_kernel<false>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{});
             }
         };
-        if (a.stride != 1) {
+        // The codes as the kernel wants them: planes that start on 4-byte boundaries.  Planes of a size that is not a
+        // multiple of 4 (7x7 outputs ...) or a misaligned tensor are copied into padded planes behind the prepared weights.
+        const size_t rbw = relayout_bytes(a.K, a.C, a.R, a.S);
+        const int64_t PQ = ((a.H + 2 * a.pad - a.R) / a.stride + 1) * ((a.Wd + 2 * a.pad - a.S) / a.stride + 1);
+        const int64_t plane = (PQ + 3) / 4 * 4;
+        const bool pad_codes = PQ % 4 != 0 || (uintptr_t)grad % 4 != 0;
+        const bool codes_ok = !pad_codes || (rbw + (size_t)(a.N * a.K * plane) <= a.scratch_bytes && plane < (1 << 24));
+        auto kernel_codes = [&]() -> const int8_t * {
+            if (!pad_codes) return (const int8_t *)grad;
+            uint32_t *dst = (uint32_t *)((char *)a.scratch + rbw);
+            const int64_t dwords = a.N * a.K * (plane / 4);
+            const int pbk = (int)((dwords + 255) / 256 < 4096 ? (dwords + 255) / 256 : 4096);
+            hipLaunchKernelGGL(conv_dx_pad_codes_kernel, dim3(pbk), dim3(256), 0, s, (const int8_t *)grad, dst, a.N * a.K, (int)PQ, (int)plane);
+            return (const int8_t *)dst;
+        };
+        if (a.stride != 1 && codes_ok) {
             ConvDxStridedPlan sp = conv_dx_strided_plan(a, I8);
             if (sp.ok) {
                 if (sp.zero_fill) {
@@ -793,9 +808,10 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
                 if (sp.multi.n > 0) {
                     const int KG = sp.multi.cls[0].KG, Cp = sp.multi.cls[0].Cp;
                     prepare(sp.taps, KG, Cp, &sp.map);
+                    const int8_t *kc = kernel_codes();
                     for (int i = 0; i < sp.multi.n; ++i) {
                         ConvDxArgs &k = sp.multi.cls[i];
-                        k.codes = (const int8_t *)grad; k.dX = a.dX; k.scale = scale;
+                        k.codes = kc; k.dX = a.dX; k.scale = scale;
                         k.wp = (const uint4 *)a.scratch + (int64_t)sp.tap_base[i] * KG * PL * Cp;
                     }
                     if (sp.nb == 7) hipLaunchKernelGGL((conv_dx_multi_kernel<7, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
@@ -805,9 +821,9 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
             }
         }
         ConvDxPlan pl = conv_dx_plan(a, I8);
-        if (pl.ok) {
+        if (pl.ok && codes_ok) {
             ConvDxArgs &k = pl.args;
-            k.codes = (const int8_t *)grad; k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale;
+            k.codes = kernel_codes(); k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale;
             prepare(k.R * k.S, k.KG, k.Cp, nullptr);
             if (pl.nb == 7) hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
             else            hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
