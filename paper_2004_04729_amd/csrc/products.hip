@@ -119,8 +119,8 @@ static void conv_dx_plan_core(ConvDxPlan &pl, bool i8, int force_nb)
     k.cgroups = (ncb + k.wc - 1) / k.wc;
     k.pw = k.Wd + k.S - 1;
     double best = -1.0;
-    const int cand[2] = {7, 4};
-    for (int ci = 0; ci < 2; ++ci) {
+    const int cand[3] = {7, 4, 2};
+    for (int ci = 0; ci < 3; ++ci) {
         const int nb = cand[ci], tile_px = k.wpx * 32 * nb;
         if (force_nb && nb != force_nb) continue;
         const int tiles = (k.PI + tile_px - 1) / tile_px;
@@ -180,8 +180,13 @@ ConvDxStridedPlan conv_dx_strided_plan(const ConvArgs &a, bool i8)
     const int st = (int)a.stride, R = (int)a.R, S = (int)a.S, pad = (int)a.pad, H = (int)a.H, Wd = (int)a.Wd;
     if (st < 2 || st * st > CDX_MAX_CLASSES || R * S > 64) return sp;
     const int P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
-    for (int attempt = 0; attempt < 2 && !sp.ok; ++attempt) {
-        const int nb = attempt == 0 ? 7 : 4;                     // one pixel-block count for all classes (one launch)
+    // one pixel-block count for all classes (one launch): the one with the least rounds x work per workgroup
+    ConvDxStridedPlan best;
+    double best_cost = -1.0;
+    const int cand[3] = {7, 4, 2};
+    for (int attempt = 0; attempt < 3; ++attempt) {
+        const int nb = cand[attempt];
+        sp.ok = false;
         bool all = true;
         sp.multi.n = 0; sp.taps = 0; sp.zero_fill = false; sp.lds_bytes = 0;
         int64_t grid = 0;
@@ -216,7 +221,11 @@ ConvDxStridedPlan conv_dx_strided_plan(const ConvArgs &a, bool i8)
         if (!all || grid > 0x7FFFFFFF) continue;
         sp.multi.first[sp.multi.n] = (int)grid;
         sp.ok = true; sp.nb = nb; sp.grid = (int)grid;
+        const double cost = (double)nb * (double)((grid + 511) / 512);
+        if (best_cost < 0.0 || cost < best_cost) { best_cost = cost; best = sp; }
     }
+    if (best_cost < 0.0) { sp.ok = false; return sp; }
+    sp = best;
     for (int t = sp.taps; t < 64; ++t) sp.map.real[t] = 0;
     return sp;
 }
@@ -814,8 +823,9 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
                         k.codes = kc; k.dX = a.dX; k.scale = scale;
                         k.wp = (const uint4 *)a.scratch + (int64_t)sp.tap_base[i] * KG * PL * Cp;
                     }
-                    if (sp.nb == 7) hipLaunchKernelGGL((conv_dx_multi_kernel<7, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
-                    else            hipLaunchKernelGGL((conv_dx_multi_kernel<4, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
+                    if (sp.nb == 7)      hipLaunchKernelGGL((conv_dx_multi_kernel<7, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
+                    else if (sp.nb == 4) hipLaunchKernelGGL((conv_dx_multi_kernel<4, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
+                    else                 hipLaunchKernelGGL((conv_dx_multi_kernel<2, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
                 }
                 return hipGetLastError();
             }
@@ -825,8 +835,9 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
             ConvDxArgs &k = pl.args;
             k.codes = kernel_codes(); k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale;
             prepare(k.R * k.S, k.KG, k.Cp, nullptr);
-            if (pl.nb == 7) hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
-            else            hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
+            if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
+            else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
+            else                 hipLaunchKernelGGL((conv_dx_kernel<2, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
             return hipGetLastError();
         }
     }
