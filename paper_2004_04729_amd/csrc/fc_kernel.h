@@ -263,39 +263,45 @@ __global__ __launch_bounds__(256, 3) void fc_pair_kernel(FcPairArgs a)
     }
 }
 
-// Second launch of a split-K run: workgroup (tile, quarter) sums the partials of 8 of the tile's 32
-// accumulator slots over the splits, in split order, and writes the output with the item's own mapping.
+// Second launch of a split-K run: workgroup (tile, slot) sums the partials of one of the tile's 32 accumulator slots
+// over the splits and writes the output with the item's own mapping.  Four running sums (splits q = 0, 1, 2, 3 mod 4,
+// each in split order, added as (s0 + s1) + (s2 + s3)): a fixed order, and four loads in flight per thread; with few
+// tiles and hundreds of splits (a convolution's dW lowered to this kernel) one sum per thread was latency bound.
 __global__ __launch_bounds__(256) void fc_reduce_kernel(FcPairArgs a, int tiles0)
 {
-    const int which = (int)(blockIdx.x >> 2) < tiles0 ? 0 : 1;
+    const int which = (int)(blockIdx.x >> 5) < tiles0 ? 0 : 1;
     const FcProblem &p = a.prob[which];
-    const int tile = (int)(blockIdx.x >> 2) - (which ? tiles0 : 0), quarter = blockIdx.x & 3;
+    const int tile = (int)(blockIdx.x >> 5) - (which ? tiles0 : 0), slot = blockIdx.x & 31;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1;
     const int tile_m = (tile % p.tiles_m) * FC_TM;
     const int tile_n = (tile / p.tiles_m) * FC_TN;
-    const float2 *all = (const float2 *)(p.partial + (int64_t)tile * p.n_split * (FC_TM * FC_TN));
-    const int col = tile_n + 4 * (lane & 31) + 2 * wc;
-    float2 sum[8];
+    const float2 *src = (const float2 *)(p.partial + (int64_t)tile * p.n_split * (FC_TM * FC_TN)) + slot * 256 + tid;
+    const int64_t per_split = FC_TM * FC_TN / 2;
+    float2 s4[4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) sum[u] = float2{0.f, 0.f};
-    for (int q = 0; q < p.n_split; ++q) {
+    for (int u = 0; u < 4; ++u) s4[u] = float2{0.f, 0.f};
+    int q = 0;
+    for (; q + 4 <= p.n_split; q += 4) {
+        float2 t[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float2 t = all[(int64_t)q * (FC_TM * FC_TN / 2) + (quarter * 8 + u) * 256 + tid];
-            sum[u].x += t.x; sum[u].y += t.y;
-        }
+        for (int u = 0; u < 4; ++u) t[u] = src[(int64_t)(q + u) * per_split];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { s4[u].x += t[u].x; s4[u].y += t[u].y; }
     }
+    for (int u = 0; q < p.n_split; ++q, ++u) {
+        const float2 t = src[(int64_t)q * per_split];
+        s4[u].x += t.x; s4[u].y += t.y;
+    }
+    const float2 sum = float2{(s4[0].x + s4[1].x) + (s4[2].x + s4[3].x), (s4[0].y + s4[1].y) + (s4[2].y + s4[3].y)};
+    const int col = tile_n + 4 * (lane & 31) + 2 * wc;
     if (col >= p.N) return;
     const float sc = p.scale.get();
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int slot = quarter * 8 + u, i = slot >> 4, v = slot & 15;
-        const int mbg = wr * 2 + i;
-        const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int row = p.a_kfast ? tile_m + mbg * 32 + ii : tile_m + 4 * ii + mbg;
-        if (row < p.M) *(float2 *)(p.out + (int64_t)row * p.ldc + col) = float2{sc * sum[u].x, sc * sum[u].y};
-    }
+    const int i = slot >> 4, v = slot & 15;
+    const int mbg = wr * 2 + i;
+    const int ii = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+    const int row = p.a_kfast ? tile_m + mbg * 32 + ii : tile_m + 4 * ii + mbg;
+    if (row < p.M) *(float2 *)(p.out + (int64_t)row * p.ldc + col) = float2{sc * sum.x, sc * sum.y};
 }
 
 }  // namespace dbp

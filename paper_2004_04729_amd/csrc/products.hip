@@ -720,7 +720,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             if (r0 || r1) {
                 FcPairArgs ra = pa;
                 int tiles0 = r0 ? (int)pdx.tiles : 0, tiles1 = r1 ? (int)pdw.tiles : 0;
-                hipLaunchKernelGGL(fc_reduce_kernel, dim3(4 * (tiles0 + tiles1)), dim3(256), 0, s, ra, tiles0);
+                hipLaunchKernelGGL(fc_reduce_kernel, dim3(32 * (tiles0 + tiles1)), dim3(256), 0, s, ra, tiles0);
                 e = hipGetLastError();
                 if (e != hipSuccess) return e;
             }
