@@ -416,8 +416,21 @@ __global__ __launch_bounds__(256) void reduce_kernel(const Acc *partial, Acc *ou
 {
     const int64_t total = (int64_t)M * N;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
-        Acc s = 0;
-        for (int z = 0; z < nsplit; ++z) s += partial[(int64_t)z * total + idx];
+        // eight running sums (splits z = 0..7 mod 8, each in split order, combined pairwise in a fixed order): eight loads
+        // in flight per thread; small outputs with hundreds of splits were latency bound with one
+        Acc t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = 0;
+        int z = 0;
+        for (; z + 8 <= nsplit; z += 8) {
+            Acc v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(z + u) * total + idx];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] += v[u];
+        }
+        for (int u = 0; z < nsplit; ++z, ++u) t[u] += partial[(int64_t)z * total + idx];
+        const Acc s = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
         const int row = (int)(idx / N), col = (int)(idx - (int64_t)row * N);
         if constexpr (std::is_same<Acc, float>::value) out[om(row, col)] = scale_arg.get() * s;
         else out[om(row, col)] = s;
