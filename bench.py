@@ -163,7 +163,7 @@ def main():
     t_dw_g = timed(lambda i: k_dw(i, dbp.PATH_GATHER), max(5, iters // 4))
     mnk = 2.0 * B * in_ * out
     # Dominant kernel: fc2_pair_kernel, both products of the 4096x4096 layer in one launch (its split-K
-    # reduction launch is included in the time).  Algorithmic work per launch (DESIGN.md "Rooflines"):
+    # reduction launch is included in the time).  Algorithmic work per launch:
     # flops = 2 products x 3 exact bf16 planes x 2*B*in*out; HBM bytes = W + X + codes read, dX + dW written.
     alg_flops = 2 * 3 * mnk
     alg_bytes = 4.0 * (out * in_ + B * in_) + B * out + 4.0 * (B * in_ + out * in_)
