@@ -376,6 +376,18 @@ def bench_conv_configs(dbp, workloads, torch, np, timed, stream):
             tq = timed(lambda i: dbp.quantize_int8(W, p.W.size, Wq, sc, wsq, stream), 5, warm=1)
             row["full_8bit"]["quantize_W_us"] = tq * 1e6
             del W8, dX32, Wq, sc, wsq
+        if name == "cfg4a":
+            # the gather kernels (walk the nonzero entries of the tile-sparse format) on the same layer, at the step above
+            # and at steps that leave 1 % and 0.1 % nonzeros: whole call (NSD with the format + both products)
+            row["gather"] = {}
+            for target in (None, 0.99, 0.999):
+                step = p.step if target is None else workloads.step_for_sparsity(p.delta, target)
+                f = lambda i, path: dbp.dithered_conv2d_backward(d, W, X, xd, N, Cc, H, Wd, K, R, S, p.stride, p.pad, step, p.seed, 0,
+                                                                 codes, dX, dW, ws, st, path, stream)
+                tg = timed(lambda i: f(i, dbp.PATH_GATHER), 3, warm=1)
+                sp_ = 1 - dbp.Stats.from_tensor(st).nnz / p.delta.size
+                tm = timed(lambda i: f(i, dbp.PATH_MFMA), 3, warm=1)
+                row["gather"]["sparsity_%.4f" % sp_] = {"gather_ms": tg * 1e3, "matrix_core_ms": tm * 1e3}
         res[name] = row
         del d, W, X, codes, dX, dW, ws
     return res

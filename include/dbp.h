@@ -30,8 +30,8 @@
  *     DBP_ERR_DEVICE can be produced on a machine without a GPU.  Nothing aborts or throws.
  *   - `workspace` is device scratch of at least the size the matching *_workspace_bytes
  *     function returns, 256-byte aligned.  Its contents need not be initialised and are
- *     undefined afterwards, except that dithered_linear_backward with path == DBP_PATH_GATHER
- *     leaves the tile-sparse format (see below) at the start of the workspace.  The other
+ *     undefined afterwards, except that the dithered_* calls with path == DBP_PATH_GATHER
+ *     leave the tile-sparse format (see below) at the start of the workspace.  The other
  *     paths do not read that format and do not spend bandwidth writing it; nsd_quantize
  *     produces it on request.
  *   - The dither of element j of delta is a pure function of (seed, idx_base + j), where j is
@@ -58,7 +58,7 @@ typedef enum {
     DBP_ERR_STEP = 3,          /* Delta is <= 0, NaN, Inf, or 1/Delta is not finite            */
     DBP_ERR_DTYPE = 4,         /* unknown dbp_dtype                                            */
     DBP_ERR_WORKSPACE = 5,     /* workspace NULL/too small/misaligned                          */
-    DBP_ERR_UNSUPPORTED = 6,   /* valid request this build does not implement (e.g. conv gather)*/
+    DBP_ERR_UNSUPPORTED = 6,   /* valid request this build does not implement (e.g. dilation)   */
     DBP_ERR_OVERFLOW = 7,      /* int32 weight gradient could overflow: reduction*127*127>=2^31 */
     DBP_ERR_DEVICE = 8         /* a HIP call failed (launch error, wrong device, ...)          */
 } dbp_status;
@@ -160,8 +160,9 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
  * dilation = 1), the convolutional analogue of Eqs. (qdz), (qda), (qdw):
  *   dX[n,c,h,w] = Delta * sum_{k,r,s} code[n,k,p,q] W[k,c,r,s],  h = p*stride+r-pad, w = q*stride+s-pad
  *   dW[k,c,r,s] = Delta * sum_{n,p,q} code[n,k,p,q] X[n,c,p*stride+r-pad,q*stride+s-pad]
- * computed as implicit-im2col GEMMs (no im2col buffer is materialised).  x_dtype as above.
- * Errors as above.  Stride 1 runs on the specialised kernels; with another stride dX runs on them as stride*stride
+ * x_dtype as above.  Errors as above; path == DBP_PATH_GATHER (kernels that walk the nonzero entries, rows of the
+ * format = the planes (n,k) of P*Q codes) needs R*S <= 64, P, Q < 4096 and, for dX, H*Wd <= 9536 (DBP_ERR_UNSUPPORTED
+ * otherwise).  On the matrix-core paths stride 1 runs on the specialised kernels; with another stride dX runs on them as stride*stride
  * stride-1 problems (one per class of output pixels modulo the stride) when stride <= 3, dW as a column-matrix
  * product on the fully connected kernels when the layer is large enough, the rest on the generic implicit-im2col kernel.
  */

@@ -166,7 +166,6 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
                                int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW,
                                void *workspace, size_t workspace_bytes, dbp_path path, void *stream, const float *step_dev = nullptr)
 {
-    (void)format;
     if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
     int64_t P, Q;
     dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
@@ -174,8 +173,23 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     if (!step_dev && !step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER && !conv_gather_supported(H, Wd, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    if (path == DBP_PATH_GATHER) {
+        if (!format) return DBP_ERR_NULL;
+        if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
+        dbp_format_layout L;
+        format_layout(N * K, P * Q, &L);
+        const char *fb = (const char *)format;
+        FormatView f{(const uint64_t *)(fb + L.bitmap_offset), (const uint16_t *)(fb + L.tile_nnz_offset),
+                     (const uint16_t *)(fb + L.entries_offset), L.tiles_per_row};
+        ConvArgs g;
+        g.codes = codes; g.dense = nullptr; g.step = step; g.step_dev = step_dev; g.W = W; g.W8 = nullptr; g.X = X; g.x_dtype = x_dtype;
+        g.N = N; g.C = C; g.H = H; g.Wd = Wd; g.K = K; g.R = R; g.S = S; g.pad = pad; g.stride = stride;
+        g.dX = dX; g.dW = dW; g.scratch = nullptr; g.scratch_bytes = 0;
+        g.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+        return launch_conv_gather(g, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+    }
     const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride);
     if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     ConvArgs a;
@@ -298,14 +312,14 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
     if (!step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER && !conv_gather_supported(H, Wd, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, false);
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, path == DBP_PATH_GATHER);
     if (st != DBP_OK) return st;
     return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
                            ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path, stream);
@@ -519,7 +533,7 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     if (!(s > 0.0f) || !std::isfinite(s)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER && !conv_gather_supported(H, Wd, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     const LayerCarve lc = layer_carve(c.total, N * K * P * Q, K);
@@ -534,7 +548,7 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     ex.act = act; ex.step_dev = pair; ex.bias_sums = db ? (int64_t *)(ws + lc.bias_sums) : nullptr; ex.bias_grad = db;
     ex.bias_mode = DBP_BIAS_PER_ROW_GROUP; ex.bias_len = K;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, false, nullptr, &ex, true);
+    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, nullptr, &ex, true);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return DBP_OK;
     return conv2d_products(k, ws, 1.0f, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,

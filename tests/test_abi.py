@@ -112,7 +112,9 @@ def test_conv_argument_errors():
     assert call(delta=None) == NULL and call(dX=None, dW=None) == NULL
     assert call(N=0) == SHAPE and call(R=9, pad=0, H=4) == SHAPE and call(pad=-1) == SHAPE
     assert call(step=float("nan")) == STEP and call(xd=3) == DTYPE
-    assert call(stride=0) == SHAPE and call(path=2) == UNSUPPORTED
+    assert call(stride=0) == SHAPE and call(path=3) == UNSUPPORTED
+    # the gather kernels keep four input planes in LDS and give every tap a lane
+    assert call(path=2, H=200, Wd=200) == UNSUPPORTED and call(path=2, R=9, S=9, pad=4, H=16, Wd=16) == UNSUPPORTED
     assert call(wsb=1000) == WORKSPACE
     assert call(xd=1, N=64, H=64, Wd=64) == OVERFLOW
     g = dbp.lib().dense_conv2d_backward

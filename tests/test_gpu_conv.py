@@ -85,6 +85,37 @@ def test_conv_int8_mode_is_bit_exact(case):
     _check(p, run_conv(p))
 
 
+GATHER = [  # N, C, H, Wd, K, R, S, pad, stride: the kernels that walk the nonzero entries of the tile-sparse format
+    (2, 5, 9, 7, 6, 3, 3, 1, 1),
+    (3, 16, 14, 14, 24, 3, 3, 1, 1),
+    (2, 33, 14, 14, 20, 1, 1, 0, 1),        # 1x1: 64 channels per wavefront
+    (2, 3, 11, 8, 4, 5, 3, 2, 1),           # 15 taps: 4 channels per wavefront, wide padding
+    (2, 8, 23, 20, 8, 7, 7, 3, 2),          # 49 taps: one channel per wavefront; stride 2
+    (4, 64, 28, 28, 40, 3, 3, 1, 2),
+    (2, 40, 20, 24, 70, 3, 3, 1, 1),        # planes of more than one 256-pixel tile
+    (1, 30, 40, 40, 8, 3, 3, 1, 1),         # input planes too large for seven per wavefront: fewer channels per workgroup
+]
+
+
+@pytest.mark.parametrize("case", GATHER)
+def test_conv_gather_path_matches_oracle(case):
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_conv
+    p = _problem(*case[:8], stride=case[8])
+    _check(p, run_conv(p, path=dbp.PATH_GATHER))
+    p8 = _problem(*case[:8], c=1.0, i8=True, stride=case[8])      # int8 X: exact int32 dW
+    _check(p8, run_conv(p8, path=dbp.PATH_GATHER))
+
+
+def test_conv_gather_very_sparse_and_empty_planes():
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_conv
+    p = _problem(3, 20, 16, 16, 12, 3, 3, 1, c=40.0)               # step 40 sigma: almost every plane is empty
+    _check(p, run_conv(p, path=dbp.PATH_GATHER))
+    mf = run_conv(p, path=dbp.PATH_MFMA)
+    assert np.array_equal(mf["codes"], run_conv(p, path=dbp.PATH_GATHER)["codes"])
+
+
 I8_ROWS = [  # 3x3, padding 1, rows of a multiple of 4 pixels: the int8 dW kernel that loads whole 16-pixel cells
     (2, 64, 16, 16, 64, 3, 3, 1),       # one full cell per row, a whole image per unit
     (2, 70, 32, 32, 130, 3, 3, 1),      # two full cells; partial channel tiles on both sides

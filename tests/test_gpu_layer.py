@@ -217,7 +217,8 @@ def test_linear_layer_backward_8bit_and_degenerate():
 @pytest.mark.parametrize("case", [(2, 5, 9, 7, 6, 3, 3, 1), (3, 16, 14, 14, 24, 3, 3, 1), (2, 33, 14, 14, 20, 1, 1, 0),
                                   (2, 64, 30, 30, 40, 3, 3, 1), (2, 8, 15, 14, 12, 3, 3, 1, 2), (2, 6, 23, 20, 8, 7, 7, 3, 2)])
 @pytest.mark.parametrize("i8", [False, True])
-def test_conv_layer_backward_is_algorithm_1(case, i8):
+@pytest.mark.parametrize("path", ["auto", "gather"])
+def test_conv_layer_backward_is_algorithm_1(case, i8, path):
     import torch
     import paper_2004_04729_amd as dbp
     from gpu_util import check_products, stream
@@ -240,7 +241,7 @@ def test_conv_layer_backward_is_algorithm_1(case, i8):
     st = torch.zeros(32, dtype=torch.uint8, device="cuda:0")
     ws = torch.empty(dbp.conv2d_layer_workspace_bytes(N, C, H, Wd, K, R, S, stride, pad, xd), dtype=torch.uint8, device="cuda:0")
     dbp.dithered_conv2d_layer_backward(_dev(da), _dev(a), _dev(W), _dev(X), xd, N, C, H, Wd, K, R, S, stride, pad, 4.0, 1, 0,
-                                       codes, dX, dW, db, pair, ws, st, dbp.PATH_AUTO, stream())
+                                       codes, dX, dW, db, pair, ws, st, dbp.PATH_AUTO if path == "auto" else dbp.PATH_GATHER, stream())
     torch.cuda.synchronize()
     dz = O.relu_backward(da, a)
     step, _ = O.step_size(dz, 4.0)
