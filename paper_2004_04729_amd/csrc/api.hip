@@ -173,7 +173,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     if (!step_dev && !step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER && !conv_gather_supported(H, Wd, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     if (path == DBP_PATH_GATHER) {
         if (!format) return DBP_ERR_NULL;
@@ -312,7 +312,7 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
     if (!step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER && !conv_gather_supported(H, Wd, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
@@ -533,7 +533,7 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     if (!(s > 0.0f) || !std::isfinite(s)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER && !conv_gather_supported(H, Wd, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
+    if (path == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     const LayerCarve lc = layer_carve(c.total, N * K * P * Q, K);

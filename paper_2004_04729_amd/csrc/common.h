@@ -123,7 +123,7 @@ struct FormatView { const uint64_t *bitmap; const uint16_t *tile_nnz; const uint
 hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s);
 // Convolution gather kernels: any stride; kernels of at most 64 taps, output planes below 4096 x 4096, and for dX an input
 // plane of at most about 37 KiB (four of them accumulate in LDS).
-bool       conv_gather_supported(int64_t H, int64_t Wd, int64_t R, int64_t S, int64_t P, int64_t Q, bool want_dx);
+bool       conv_gather_supported(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t P, int64_t Q, bool want_dx);
 hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_t s);
 
 }  // namespace dbp

@@ -130,16 +130,55 @@ __global__ __launch_bounds__(256) void linear_dw_gather_kernel(const int8_t *cod
 // ---- convolution -------------------------------------------------------------------------------
 // The format's rows are the code planes (n, k) of P*Q pixels.  Both kernels give every lane ONE (channel, tap) pair
 // and walk the nonzero codes of the planes they need in a fixed order (deterministic sums): 64 / (R*S) channels per
-// wavefront, four wavefronts per workgroup.  A tile's entries are decoded once per workgroup (pixel -> (p, q)) into LDS.
+// wavefront, four wavefronts per workgroup.  The walk goes over the tiles of the workgroup's planes in chunks of up to 256
+// tiles: their entry counts are scanned, and the entries of as many tiles as fit are copied into LDS as (p, q, code,
+// plane) records -- at high sparsity most tiles are empty and one chunk (three barriers) covers hundreds of planes.
 struct ConvGatherGeom { int N, C, H, Wd, K, R, S, pad, st, P, Q, cpw; };   // cpw: channels per wavefront
 
-__device__ __forceinline__ void conv_gather_decode(const FormatView &f, int64_t t, int seg, int cnt, int Q, uint32_t *s_ent)
+constexpr int kChunkCap = 1024;                           // entry records per chunk (a tile has at most 256)
+
+struct GatherChunk {
+    uint32_t ent[kChunkCap];                              // p | q << 12 | code << 24
+    uint16_t plane[kChunkCap];                            // index of the plane in the walk
+    int wave_sum[4];
+    int n_tiles, n_ent;
+};
+
+// Tiles i0 .. of the walk (tile i = segment i % tpr of plane i / tpr; plane j is format row row0 + j * row_stride):
+// as many as fit, at most 256.  Returns after a barrier; ch.n_tiles >= 1 whenever i0 < n_walk.
+__device__ __forceinline__ void conv_gather_chunk(const FormatView &f, int64_t row0, int64_t row_stride, int tpr, int i0, int n_walk,
+                                                  int Q, GatherChunk &ch)
 {
-    __syncthreads();                                     // the tile before has been consumed
-    if ((int)threadIdx.x < cnt) {
-        const uint32_t en = f.entries[t * DBP_TILE + threadIdx.x];
-        const int pix = seg * DBP_TILE + (int)(en >> 8), p = pix / Q, q = pix - p * Q;
-        s_ent[threadIdx.x] = (uint32_t)p | ((uint32_t)q << 12) | ((en & 0xFFu) << 24);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = i0 + tid;
+    const bool valid = i < n_walk;
+    const int j = valid ? i / tpr : 0, seg = valid ? i - j * tpr : 0;
+    const int64_t t = (row0 + (int64_t)j * row_stride) * tpr + seg;
+    const int cnt = valid ? (int)f.tile_nnz[t] : 0;
+    int incl = cnt;                                        // inclusive scan over the workgroup
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+    }
+    __syncthreads();                                       // the chunk before has been consumed
+    if (lane == 63) ch.wave_sum[wave] = incl;
+    if (tid == 0) { ch.n_tiles = 0; ch.n_ent = 0; }
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) incl += ch.wave_sum[w];
+    const bool fits = valid && incl <= kChunkCap;          // a prefix of the threads (counts are non-negative)
+    const uint64_t m = __builtin_amdgcn_ballot_w64(fits);
+    if (lane == 0 && m) { atomicAdd(&ch.n_tiles, __builtin_popcountll(m)); }
+    if (fits) atomicMax(&ch.n_ent, incl);
+    if (fits) {
+        const uint16_t *src = f.entries + t * DBP_TILE;
+        const int at = incl - cnt;
+        for (int e = 0; e < cnt; ++e) {
+            const uint32_t en = src[e];
+            const int pix = seg * DBP_TILE + (int)(en >> 8), p = pix / Q, q = pix - p * Q;
+            ch.ent[at + e] = (uint32_t)p | ((uint32_t)q << 12) | ((en & 0xFFu) << 24);
+            ch.plane[at + e] = (uint16_t)j;
+        }
     }
     __syncthreads();
 }
@@ -150,26 +189,36 @@ __device__ __forceinline__ void conv_gather_decode(const FormatView &f, int64_t 
 template <class XT, class AccT, class OutT>
 __global__ __launch_bounds__(256) void conv_dw_gather_kernel(FormatView f, const XT *X, OutT *dW, ConvGatherGeom g, Scale step_arg)
 {
-    __shared__ uint32_t s_ent[DBP_TILE];
+    __shared__ GatherChunk ch;
     const int k = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int RS = g.R * g.S, cl = lane / RS, tap = lane - cl * RS;
     const int c = ((int)blockIdx.x * 4 + wave) * g.cpw + cl;
     const bool own = cl < g.cpw && c < g.C;
     const int r = tap / g.S, s = tap - r * g.S, tpr = (int)f.tiles_per_row, HW = g.H * g.Wd;
+    const int n_walk = g.N * tpr, img = g.C * HW;          // elements of X per image (the host keeps N*C*H*Wd below 2^31)
+    const XT *xc = X + (own ? c : 0) * HW;
     AccT acc = 0;
-    for (int n = 0; n < g.N; ++n) {
-        const XT *xc = X + ((int64_t)n * g.C + (own ? c : 0)) * HW;
-        for (int seg = 0; seg < tpr; ++seg) {
-            const int64_t t = ((int64_t)n * g.K + k) * tpr + seg;
-            const int cnt = f.tile_nnz[t];                // the same for the whole workgroup
-            if (cnt == 0) continue;
-            conv_gather_decode(f, t, seg, cnt, g.Q, s_ent);
-#pragma unroll 4
-            for (int e = 0; e < cnt; ++e) {
-                const uint32_t v = s_ent[e];
+    for (int i0 = 0; i0 < n_walk;) {
+        conv_gather_chunk(f, k, g.K, tpr, i0, n_walk, g.Q, ch);     // plane j of the walk = image j: row j*K + k
+        const int n_ent = ch.n_ent;
+        i0 += ch.n_tiles;
+        // eight unconditional loads at a time (pixels outside the image read element 0 and add nothing): the loop is
+        // bound by their latency
+        for (int e0 = 0; e0 < n_ent; e0 += 8) {
+            XT x[8];
+            AccT kq[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = min(e0 + u, n_ent - 1);
+                const uint32_t v = ch.ent[e];
+                const int n = ch.plane[e];
                 const int h = (int)(v & 0xFFFu) * g.st + r - g.pad, w = (int)((v >> 12) & 0xFFFu) * g.st + s - g.pad;
-                if (own && h >= 0 && h < g.H && w >= 0 && w < g.Wd) acc += (AccT)(int8_t)(v >> 24) * (AccT)xc[h * g.Wd + w];
+                const bool in = own && e0 + u < n_ent && h >= 0 && h < g.H && w >= 0 && w < g.Wd;
+                x[u] = xc[in ? n * img + h * g.Wd + w : 0];
+                kq[u] = in ? (AccT)(int8_t)(v >> 24) : (AccT)0;
             }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += kq[u] * (AccT)x[u];
         }
     }
     if (own) {
@@ -183,27 +232,39 @@ __global__ __launch_bounds__(256) void conv_dw_gather_kernel(FormatView f, const
 // hit different pixels (one per tap) and different channels different planes, so the read-add-write needs no atomics.
 __global__ __launch_bounds__(256) void conv_dx_gather_kernel(FormatView f, const float *W, float *dX, ConvGatherGeom g, Scale step_arg)
 {
-    extern __shared__ float cg_planes[];                 // [4 * cpw channels][H*Wd], then the decoded entries
+    extern __shared__ float cg_planes[];                 // [4 * cpw channels][H*Wd], then the chunk
     const int n = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int RS = g.R * g.S, cl = lane / RS, tap = lane - cl * RS;
     const int c_first = (int)blockIdx.x * 4 * g.cpw, c = c_first + wave * g.cpw + cl;
     const bool own = cl < g.cpw && c < g.C;
     const int r = tap / g.S, s = tap - r * g.S, tpr = (int)f.tiles_per_row, HW = g.H * g.Wd;
-    const int n_planes = 4 * g.cpw;
-    uint32_t *s_ent = (uint32_t *)(cg_planes + (size_t)n_planes * HW);
-    for (int i = threadIdx.x; i < n_planes * HW; i += 256) cg_planes[i] = 0.f;
+    const int n_planes = 4 * g.cpw, n_walk = g.K * tpr;
+    GatherChunk &ch = *(GatherChunk *)(cg_planes + (size_t)n_planes * HW);
+    for (int i = threadIdx.x; i < n_planes * HW; i += 256) cg_planes[i] = 0.f;   // (ordered by the first chunk's barriers)
     float *mine = cg_planes + (size_t)(wave * g.cpw + (own ? cl : 0)) * HW;
-    for (int k = 0; k < g.K; ++k) {
-        const float wv = own ? W[(((int64_t)k * g.C + c) * g.R + r) * g.S + s] : 0.f;
-        for (int seg = 0; seg < tpr; ++seg) {
-            const int64_t t = ((int64_t)n * g.K + k) * tpr + seg;
-            const int cnt = f.tile_nnz[t];
-            if (cnt == 0) continue;
-            conv_gather_decode(f, t, seg, cnt, g.Q, s_ent);   // (its first barrier also orders the clearing above)
-            for (int e = 0; e < cnt; ++e) {
-                const uint32_t v = s_ent[e];
-                const int h = (int)(v & 0xFFFu) * g.st + r - g.pad, w = (int)((v >> 12) & 0xFFFu) * g.st + s - g.pad;
-                if (own && h >= 0 && h < g.H && w >= 0 && w < g.Wd) mine[h * g.Wd + w] += (float)(int8_t)(v >> 24) * wv;
+    const float *wl = W + ((int64_t)(own ? c : 0) * g.R + r) * g.S + s;          // + k * C*R*S
+    const int CRS = g.C * RS;
+    for (int i0 = 0; i0 < n_walk;) {
+        conv_gather_chunk(f, (int64_t)n * g.K, 1, tpr, i0, n_walk, g.Q, ch);     // plane j of the walk = channel k = j
+        const int n_ent = ch.n_ent;
+        i0 += ch.n_tiles;
+        // Four entries at a time: their weights are loaded together (at high sparsity every entry is another plane k, and
+        // one dependent load per entry was the bound).  The read-add-write of the entries stays in order: the taps of two
+        // nearby entries reach the same pixels through different lanes.
+        for (int e0 = 0; e0 < n_ent; e0 += 4) {
+            uint32_t v[4];
+            float wv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = min(e0 + u, n_ent - 1);
+                v[u] = ch.ent[e];
+                wv[u] = own ? wl[(int64_t)ch.plane[e] * CRS] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int h = (int)(v[u] & 0xFFFu) * g.st + r - g.pad, w = (int)((v[u] >> 12) & 0xFFFu) * g.st + s - g.pad;
+                if (own && e0 + u < n_ent && h >= 0 && h < g.H && w >= 0 && w < g.Wd)
+                    mine[h * g.Wd + w] += (float)(int8_t)(v[u] >> 24) * wv[u];
             }
         }
     }
@@ -217,10 +278,14 @@ __global__ __launch_bounds__(256) void conv_dx_gather_kernel(FormatView f, const
 
 }  // namespace
 
-bool conv_gather_supported(int64_t H, int64_t Wd, int64_t R, int64_t S, int64_t P, int64_t Q, bool want_dx)
+// LDS of the dX kernel beside its planes: the chunk of entry records.
+constexpr size_t kConvGatherFixedLds = sizeof(GatherChunk) + 16;
+
+bool conv_gather_supported(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t P, int64_t Q, bool want_dx)
 {
-    if (R * S > 64 || P >= 4096 || Q >= 4096) return false;
-    if (want_dx && (size_t)(4 * H * Wd * 4 + DBP_TILE * 4) > (size_t)150 * 1024) return false;   // a plane per wavefront at least
+    if (R * S > 64 || P >= 4096 || Q >= 4096) return false;                      // a lane per tap; 12-bit coordinates
+    if (N >= 65536 || K >= 65536 || N * C * H * Wd >= ((int64_t)1 << 31)) return false;   // 16-bit plane numbers, 32-bit offsets into X
+    if (want_dx && (size_t)(4 * H * Wd * 4) + kConvGatherFixedLds > (size_t)150 * 1024) return false;   // a plane per wavefront at least
     return true;
 }
 
@@ -233,11 +298,11 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
     const int RS = g.R * g.S, cpw_max = 64 / RS;
     const Scale step{a.step, a.step_dev};
     if (a.dX) {
-        const size_t HW4 = (size_t)g.H * g.Wd * 4, budget = (size_t)150 * 1024 - DBP_TILE * 4;
+        const size_t HW4 = (size_t)g.H * g.Wd * 4, budget = (size_t)150 * 1024 - kConvGatherFixedLds;
         int cpw = cpw_max;
         while (cpw > 1 && (size_t)4 * cpw * HW4 > budget) --cpw;
         g.cpw = cpw;
-        const size_t lds = (size_t)4 * cpw * HW4 + DBP_TILE * 4;
+        const size_t lds = (((size_t)4 * cpw * HW4 + 15) & ~(size_t)15) + kConvGatherFixedLds;
         static size_t raised = 0;
         if (lds > 64 * 1024 && lds > raised) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dx_gather_kernel),
