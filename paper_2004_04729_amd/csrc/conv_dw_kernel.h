@@ -486,18 +486,22 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
         const int n_steps = a.TPc / KSTEP;
         StepFrags fa, fb;
         load_frags(cur, 0, fa);
-        for (int step = 0; step < n_steps; step += 2) {
-            // the scheduling barriers keep the LDS reads of the next step in front of this step's matrix-core
-            // instructions (left alone, the compiler sinks them behind and their latency is exposed)
-            if (step + 1 < n_steps) load_frags(cur, step + 1, fb);
+        // The scheduling barriers keep the LDS reads of the next step in front of this step's matrix-core
+        // instructions (left alone, the compiler sinks them behind and their latency is exposed).  The loads of the
+        // loop body are unconditional (the last one repeats the last step): with a load on only some paths the
+        // compiler waits for ALL LDS loads in flight where it has to wait for one step's.
+        int step = 0;
+        for (; step + 2 <= n_steps; step += 2) {
+            load_frags(cur, step + 1, fb);
             __builtin_amdgcn_sched_barrier(0);
             multiply(fa);
             __builtin_amdgcn_sched_barrier(0);
-            if (step + 2 < n_steps) load_frags(cur, step + 2, fa);
+            load_frags(cur, min(step + 2, n_steps - 1), fa);
             __builtin_amdgcn_sched_barrier(0);
-            if (step + 1 < n_steps) multiply(fb);
+            multiply(fb);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (step < n_steps) multiply(fa);
         __syncthreads();
     }
 
