@@ -431,8 +431,12 @@ void fc2_plans(int64_t B, int64_t in, int64_t out, bool want_dx, bool want_dw, F
     // product runs alone (half the split-K partials: measured 37 instead of 47 us for dX of the 4096x4096 layer)
     int64_t len = all / (want_dx && want_dw ? 512 : 256);
     if (len < 8) len = 8;
-    auto split = [len, kt](int64_t steps, FcPlan &pl) {
+    const bool alone = want_dx != want_dw;
+    auto split = [len, kt, alone](int64_t steps, FcPlan &pl) {
         int64_t n = (steps + len / 2) / len;
+        // a product that runs alone: at most one item per workgroup (256 of them), so that no workgroup takes a second
+        // item while the others idle (8 tiles x 33 splits = 264 items ran as two rounds)
+        if (alone && pl.tiles <= 256 && n * pl.tiles > 256) n = 256 / pl.tiles;
         if (n < 1) n = 1;
         const int64_t per = (steps + n - 1) / n;
         pl.k_per_split = (int)(per * kt);
