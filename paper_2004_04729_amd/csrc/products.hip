@@ -559,16 +559,22 @@ size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K
     const int64_t PQp16 = (P * Q + 15) / 16 * 16;
     size_t dw = part(K, C * R * S, N * PQp16, 16);
     size_t big = dx > dw ? dx : dw;
-    for (int i8 = 0; i8 < 2; ++i8) {                                 // fast dW kernel, either X type
+    bool fast[2] = {false, false};                                   // a convolution dW kernel serves fp32 / int8 activations
+    for (int i8 = 0; i8 < 2; ++i8) {
         const ConvDwPlan pl = conv_dw_plan(N, C, H, Wd, K, R, S, pad, i8 != 0);
+        if (pl.ok && stride == 1) fast[i8] = true;
         if (pl.ok && pl.partial_bytes > big) big = pl.partial_bytes;
     }
     const ConvDwI8Plan p8 = conv_dw_i8_plan(N, C, H, Wd, K, R, S, pad);
+    if (p8.ok && stride == 1) fast[1] = true;
     if (p8.ok && p8.partial_bytes > big) big = p8.partial_bytes;
     const size_t padded = (size_t)(N * K * ((P * Q + 3) / 4 * 4));    // dX: the codes in planes that start on 4-byte boundaries
     if (padded > big) big = padded;
-    for (int esz = 1; esz <= 4; esz += 3) {                          // dW lowered to the FC kernels, either X type
-        const ConvLowerPlan lp = conv_dw_lower_plan(N, C, H, Wd, K, R, S, pad, stride, esz);
+    // dW lowered to the FC kernels: room for the column matrix only where no convolution dW kernel serves the shape (a
+    // call whose pointers those kernels cannot take then runs on the generic kernel, which needs less)
+    for (int i8 = 0; i8 < 2; ++i8) {
+        if (fast[i8]) continue;
+        const ConvLowerPlan lp = conv_dw_lower_plan(N, C, H, Wd, K, R, S, pad, stride, i8 ? 1 : 4);
         if (lp.ok && lp.bytes > big) big = lp.bytes;
     }
     return relayout_bytes(K, C, R, S) + align_up(big, 256) + 256;
