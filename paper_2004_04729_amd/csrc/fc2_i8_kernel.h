@@ -52,10 +52,6 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
     if (wave >= 4) {
         // ================================ stagers ================================
         const int tid = threadIdx.x & 255;
-        if (blockIdx.x == gridDim.x - 1 && wave == 7) {
-            if (a.stats.n > 0) fc2_sum_stats(a.stats, lane);
-            if (a.stats.bias_len > 0) fc2_bias_grad(a.stats, lane);
-        }
         // dense operand B[k][n] (int8): reduction rows 4*k4 .. +3, columns 8*n8 .. +7 (one 8-byte load per row)
         const int k4 = tid >> 4, n8 = tid & 15;
         Fc2Cursor c;
@@ -188,7 +184,7 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
             }
         };
 
-        if (G == 0) { __syncthreads(); return; }
+        if (G == 0) { __syncthreads(); if (wave == 7) fc2_side_jobs(a.stats, lane); return; }
         Fc2IRaw r0, r1, r2;
         issue(r0); issue(r1); issue(r2);
         commit(r0, stages[0]);
@@ -205,6 +201,7 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
             issue(r0);
             if (g + 2 < G) __syncthreads();
         }
+        if (wave == 7) fc2_side_jobs(a.stats, lane);     // the statistics and the bias gradient, once the staging is over
         return;
     }
 

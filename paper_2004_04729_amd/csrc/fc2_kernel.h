@@ -119,13 +119,18 @@ struct Fc2Raw {                       // one K step of one stager thread, as loa
 // 16 bytes from an address that is only known to be a multiple of 4 (one global_load_dwordx4)
 typedef uint32_t u32x4_dw __attribute__((ext_vector_type(4), aligned(4)));
 
-// Sum of the quantiser's statistics records by one wavefront (integers: any order gives the same result).
+// Sum of the quantiser's statistics records by one wavefront (integers: any order gives the same result); four
+// loads in flight per lane.
 __device__ __forceinline__ void fc2_sum_stats(const StatsJob &j, int lane)
 {
     uint64_t nnz = 0, sat = 0, nf = 0, mx = 0;
-    for (int i = lane; i < j.n; i += 64) {
-        const u32x4 q = j.partials[i];
-        nnz += q.x; sat += q.y; nf += q.z; mx = mx > q.w ? mx : q.w;
+    for (int i = lane; i < j.n; i += 256) {
+        u32x4 q[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) q[u] = j.partials[min(i + 64 * u, j.n - 1)];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + 64 * u < j.n) { nnz += q[u].x; sat += q[u].y; nf += q[u].z; mx = mx > q[u].w ? mx : q[u].w; }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -140,11 +145,22 @@ __device__ __forceinline__ void fc2_sum_stats(const StatsJob &j, int lane)
     }
 }
 
-// Bias gradient of the layer from the quantiser's code sums: one fp64 product rounded to fp32 per element.
+// Bias gradient of the layer from the quantiser's code sums: one fp64 product rounded to fp32 per element.  Every
+// workgroup's wavefront takes every gridDim.x-th run of 64 elements.
 __device__ __forceinline__ void fc2_bias_grad(const StatsJob &j, int lane)
 {
     const double d = j.step_dev ? (double)j.step_dev[0] : (double)j.step;
-    for (int64_t i = lane; i < j.bias_len; i += 64) j.bias_grad[i] = (float)(d * (double)j.bias_sums[i]);
+    for (int64_t i = (int64_t)blockIdx.x * 64 + lane; i < j.bias_len; i += (int64_t)gridDim.x * 64)
+        j.bias_grad[i] = (float)(d * (double)j.bias_sums[i]);
+}
+
+// What a stager wavefront does once its staging is over, while the multipliers finish the last steps and store: the last
+// workgroup (it has the fewest items) sums the quantiser's statistics, every workgroup takes its share of the bias gradient.
+// (Done in front of the staging loop by one wavefront, the two cost the kernel 20 us: that workgroup started late.)
+__device__ __forceinline__ void fc2_side_jobs(const StatsJob &j, int lane)
+{
+    if (j.n > 0 && blockIdx.x == gridDim.x - 1) fc2_sum_stats(j, lane);
+    if (j.bias_len > 0) fc2_bias_grad(j, lane);
 }
 
 // Matrix row of element ii of row block i of multiplier wavefront `wave`: row positions are rows (a_kfast)
@@ -172,12 +188,6 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
     if (wave >= 4) {
         // ================================ stagers ================================
         const int tid = threadIdx.x & 255;
-        // the last workgroup has the fewest items: one of its stager wavefronts finishes the quantiser's
-        // statistics and the bias gradient
-        if (blockIdx.x == gridDim.x - 1 && wave == 7) {
-            if (a.stats.n > 0) fc2_sum_stats(a.stats, lane);
-            if (a.stats.bias_len > 0) fc2_bias_grad(a.stats, lane);
-        }
         // lane pairs share four columns of the dense operand and take neighbouring groups of four reduction
         // indices: their 8-byte LDS writes are then contiguous over the wavefront
         const int nq = (tid >> 1) & 31, kq = 2 * (tid >> 6) + (tid & 1);
@@ -322,7 +332,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
         // Step g lives in register set g % 3 and LDS stage g % 2.  Barriers: one after step 0 is staged, then
         // one per step; in the iteration of step g the stagers write step g + 1 and load step g + 4.
         // The loads are unconditional (see issue); only commits and barriers depend on the trip count.
-        if (G == 0) { __syncthreads(); return; }
+        if (G == 0) { __syncthreads(); if (wave == 7) fc2_side_jobs(a.stats, lane); return; }
         Fc2Raw r0, r1, r2;
         issue(r0); issue(r1); issue(r2);
         commit(r0, stages[0]);
@@ -339,6 +349,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
             issue(r0);
             if (g + 2 < G) __syncthreads();
         }
+        if (wave == 7) fc2_side_jobs(a.stats, lane);
         return;
     }
 
