@@ -172,6 +172,10 @@ __device__ __forceinline__ int fc2_row(int a_kfast, int tile_m, int wave, int i,
                    : tile_m + 16 * (ii & 15) + 4 * wave + 2 * i + (ii >> 4);
 }
 
+// NT: the batched form with both operands reduction-contiguous (the weight gradient of a 1x1 convolution straight from
+// NCHW tensors: rows = output channels, columns = input channels, reduction = the pixels of every image).  Only the
+// stagers' addresses and the order in which they read the dense operand's registers differ.
+template <bool NT>
 __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 {
     extern __shared__ uint4 fc2_lds[];
@@ -203,8 +207,30 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
         int64_t b_unit = 0, a_unit = 0;                   // bytes per reduction index
         uint32_t boff[4] = {0, 0, 0, 0}, aoff[2] = {0, 0};
         int a_shift = 0, kv_cur = 0;
+        // NT: position inside the item's run of images (window s of image `nt_img`) and the image's operands
+        int nt_s = 0, nt_pq = 0, nt_spi = 1;
+        int64_t nt_a_img = 0, nt_b_img4 = 0;
+        const int8_t *nt_a = nullptr;
+        const char *nt_b = nullptr;
         auto open_item = [&](int i) {
             if (!fc2_open(a, table, mine, i, c)) return false;
+            if constexpr (NT) {
+                const FcProblem &p = a.prob[c.which];
+                nt_pq = p.nt_pq; nt_spi = p.nt_spi; nt_a_img = p.nt_a_img; nt_b_img4 = p.nt_b_img * 4;
+                const int img = c.k0 / (nt_spi * FC2_KT);                 // items start and end at image borders
+                nt_s = 0;
+                nt_a = c.A + (int64_t)img * nt_a_img;
+                nt_b = (const char *)c.B + (int64_t)img * nt_b_img4;
+                // dense operand: columns 4*nq .. +3 of the tile (one per load), reduction indices 4*kq .. +3 of the window
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    boff[j] = (uint32_t)min(c.tile_n + 4 * nq + j, c.N - 1) * (uint32_t)c.ldb * 4u + 16u * (uint32_t)kq;
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    aoff[j] = (uint32_t)min(c.tile_m + 128 * j + (tid >> 1), c.M - 1) * (uint32_t)c.lda + 16u * (uint32_t)(tid & 1);
+                a_shift = 0;
+                return true;
+            }
             const uint32_t ldb4 = (uint32_t)c.ldb * 4u, lda = (uint32_t)c.lda;
             b_unit = (int64_t)c.ldb * 4;
             b_step = (const char *)c.B + (int64_t)c.k0 * b_unit;
@@ -239,13 +265,23 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
         // it is never committed): with equal load counts on every path the compiler can wait for exactly the
         // loads of three calls ago instead of for all outstanding ones.
         auto issue = [&](Fc2Raw &r) {
+            if constexpr (NT) {
+                if (open) {
+                    // window s of the image: 32 reduction indices that end inside the image (the last window overlaps the
+                    // one before it; what it repeats is zeroed when the step is committed)
+                    const int win = min(FC2_KT * nt_s, nt_pq - FC2_KT);
+                    kv_cur = min(FC2_KT, nt_pq - FC2_KT * nt_s);
+                    b_cur = nt_b + (int64_t)win * 4;
+                    a_cur = nt_a + win;
+                }
+            } else
             if (open) {
                 kv_cur = c.k_end - c.k0;
                 const int back = max(0, FC2_KT - kv_cur);
                 b_cur = b_step - back * b_unit;
                 a_cur = a_step - back * a_unit;
             }
-            r.kfast = c.a_kfast;
+            r.kfast = NT ? 1 : c.a_kfast;
             r.k_valid = kv_cur;
             r.a_shift = a_shift;
 #pragma unroll
@@ -257,7 +293,11 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
             }
             if (open) {
                 c.k0 += FC2_KT;
-                b_step += FC2_KT * b_unit; a_step += FC2_KT * a_unit;
+                if constexpr (NT) {
+                    if (++nt_s == nt_spi) { nt_s = 0; nt_a += nt_a_img; nt_b += nt_b_img4; }
+                } else {
+                    b_step += FC2_KT * b_unit; a_step += FC2_KT * a_unit;
+                }
                 if (c.k0 >= c.k_end) open = open_item(c.t + 1);
             }
         };
@@ -311,17 +351,21 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
                         cell[64 * (4 * d + j)] = bf16x2_from_codes((int8_t)(w0[d] >> (8 * j)), (int8_t)(w1[d] >> (8 * j)));
             }
             // fp32 -> three exact bf16 planes; column 4*nq+j -> position j*32+nq
+            // (NT: register i holds column 4*nq+i, its component j reduction index 4*kq+j -- the transposed arrangement)
             f32x4 bv[4] = {r.b[0], r.b[1], r.b[2], r.b[3]};
             if (dup > 0) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if (4 * kq + i < dup) bv[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (4 * kq + i < dup) {
+                        if constexpr (NT) { bv[0][i] = 0.f; bv[1][i] = 0.f; bv[2][i] = 0.f; bv[3][i] = 0.f; }
+                        else bv[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint32_t h[4], m[4], l[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) split3(bv[i][j], h[i], m[i], l[i]);
+                for (int i = 0; i < 4; ++i) split3(NT ? bv[j][i] : bv[i][j], h[i], m[i], l[i]);
                 const int pos = j * 32 + nq;
                 sm.b[0][kq >> 1][pos][kq & 1] = uint2{upper_halves(l[1], l[0]), upper_halves(l[3], l[2])};
                 sm.b[1][kq >> 1][pos][kq & 1] = uint2{upper_halves(m[1], m[0]), upper_halves(m[3], m[2])};

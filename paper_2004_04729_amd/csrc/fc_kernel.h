@@ -36,6 +36,11 @@ struct FcProblem {
     int M, N, K, k_per_split, n_split, tiles_m, n_items;
     Scale scale;
     int a_kfast;
+    // Batched form of the kernel of fc2_kernel.h (both operands reduction-contiguous, one pair per image, accumulated):
+    // A_img[m*lda + k], B_img[n*ldb + k], k < nt_pq; image i at A + i*nt_a_img, B + i*nt_b_img (elements); the
+    // reduction axis K counts nt_spi windows of 32 per image.  nt_pq == 0: the plain form above.
+    int nt_pq, nt_spi;
+    int64_t nt_a_img, nt_b_img;
 };
 struct FcPairArgs { FcProblem prob[2]; StatsJob stats; };
 

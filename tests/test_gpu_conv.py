@@ -154,6 +154,23 @@ def test_conv_dw_lowered_to_fc_kernels(case):
     _check(p8, run_conv(p8))
 
 
+ONE_BY_ONE = [  # N, C, H, Wd, K: 1x1, stride 1, no padding, more than 128 output channels: dW straight from the NCHW tensors
+    (4, 36, 14, 14, 130),       # 196 pixels: six windows of 32 and one that overlaps; partial row and column tiles
+    (3, 64, 8, 8, 200),         # 64 pixels: whole windows only
+    (5, 16, 6, 6, 140),         # 36 pixels: the second window repeats 28 indices of the first
+    (70, 128, 14, 14, 256),     # the reduction split over groups of images
+    (2, 260, 10, 10, 300),      # several column tiles, two row tiles
+]
+
+
+@pytest.mark.parametrize("case", ONE_BY_ONE)
+def test_conv_1x1_dw_batched_fc_kernel(case):
+    from gpu_util import run_conv
+    N, C, H, Wd, K = case
+    p = _problem(N, C, H, Wd, K, 1, 1, 0)
+    _check(p, run_conv(p))
+
+
 STRIDED = [  # N, C, H, Wd, K, R, S, pad, stride  (the strided layers of a ResNet: 3x3/2, 1x1/2 shortcuts, 7x7/2 stem)
     (2, 5, 9, 7, 6, 3, 3, 1, 2),
     (3, 16, 14, 14, 24, 3, 3, 1, 2),
