@@ -36,6 +36,9 @@ __device__ __forceinline__ void fc2i_transpose(uint32_t r0, uint32_t r1, uint32_
     out[2] = __builtin_amdgcn_perm(y1, y0, 0x05040100u); out[3] = __builtin_amdgcn_perm(y1, y0, 0x07060302u);
 }
 
+// NT: the batched form with both operands reduction-contiguous, as in fc2_kernel.h (weight gradient of a 1x1
+// convolution with int8 activations straight from the NCHW tensors); here the dense operand's cells are plain copies too.
+template <bool NT>
 __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
 {
     extern __shared__ uint4 fc2_lds[];
@@ -64,8 +67,30 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
         int64_t b_unit = 0, a_unit = 0;                   // bytes per reduction index
         uint32_t boff[4] = {0, 0, 0, 0}, aoff[4] = {0, 0, 0, 0};
         int a_shift = 0, kv_cur = 0;
+        // NT: position inside the item's run of images (window s of image `nt_a`/`nt_b`) and the image strides
+        int nt_s = 0, nt_pq = 0, nt_spi = 1;
+        int64_t nt_a_img = 0, nt_b_img = 0;
+        const int8_t *nt_a = nullptr;
+        const char *nt_b = nullptr;
         auto open_item = [&](int i) {
             if (!fc2_open(a, table, mine, i, c)) return false;
+            if constexpr (NT) {
+                const FcProblem &p = a.prob[c.which];
+                nt_pq = p.nt_pq; nt_spi = p.nt_spi; nt_a_img = p.nt_a_img; nt_b_img = p.nt_b_img;
+                const int img = c.k0 / (nt_spi * FC2I_KT);                // items start and end at image borders
+                nt_s = 0;
+                nt_a = c.A + (int64_t)img * nt_a_img;
+                nt_b = (const char *)c.B + (int64_t)img * nt_b_img;
+                // dense operand: columns tid/4 and 64 + tid/4 of the tile, reduction indices 16*(tid%4) .. +15 of the window
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    boff[j] = (uint32_t)min(c.tile_n + 64 * j + (tid >> 2), c.N - 1) * (uint32_t)c.ldb + 16u * (uint32_t)(tid & 3);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    aoff[j] = (uint32_t)min(c.tile_m + 64 * j + (tid >> 2), c.M - 1) * (uint32_t)c.lda + 16u * (uint32_t)(tid & 3);
+                a_shift = 0;
+                return true;
+            }
             const uint32_t ldb = (uint32_t)c.ldb, lda = (uint32_t)c.lda;
             b_unit = c.ldb;
             b_step = (const char *)c.B + (int64_t)c.k0 * b_unit;
@@ -98,17 +123,35 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
         // Every call issues the same eight loads (also once the list is exhausted: the last window again, never
         // committed), so the compiler can wait for exactly the loads of three calls ago.
         auto issue = [&](Fc2IRaw &r) {
+            if constexpr (NT) {
+                if (open) {
+                    // window s of the image: 64 reduction indices that end inside the image (the last window overlaps
+                    // the one before it; what it repeats is zeroed when the step is committed)
+                    const int win = min(FC2I_KT * nt_s, nt_pq - FC2I_KT);
+                    kv_cur = min(FC2I_KT, nt_pq - FC2I_KT * nt_s);
+                    b_cur = nt_b + win;
+                    a_cur = nt_a + win;
+                }
+            } else
             if (open) {
                 kv_cur = c.k_end - c.k0;
                 const int back = max(0, FC2I_KT - kv_cur);
                 b_cur = b_step - back * b_unit;
                 a_cur = a_step - back * a_unit;
             }
-            r.kfast = c.a_kfast;
+            r.kfast = NT ? 1 : c.a_kfast;
             r.k_valid = kv_cur;
             r.a_shift = a_shift;
+            if constexpr (NT) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) r.b[i] = *(const uint2 *)(b_cur + (size_t)boff[i]);
+                for (int i = 0; i < 2; ++i) {
+                    const u32x4 v = *(const u32x4_dw *)(b_cur + (size_t)boff[i]);
+                    r.b[2 * i] = uint2{v.x, v.y}; r.b[2 * i + 1] = uint2{v.z, v.w};
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) r.b[i] = *(const uint2 *)(b_cur + (size_t)boff[i]);
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const u32x4 v = *(const u32x4_dw *)(a_cur + (size_t)aoff[i]);
@@ -116,7 +159,11 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
             }
             if (open) {
                 c.k0 += FC2I_KT;
-                b_step += FC2I_KT * b_unit; a_step += FC2I_KT * a_unit;
+                if constexpr (NT) {
+                    if (++nt_s == nt_spi) { nt_s = 0; nt_a += nt_a_img; nt_b += nt_b_img; }
+                } else {
+                    b_step += FC2I_KT * b_unit; a_step += FC2I_KT * a_unit;
+                }
                 if (c.k0 >= c.k_end) open = open_item(c.t + 1);
             }
         };
@@ -164,6 +211,20 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) cell[64 * (4 * d + j)] = t[j];
                 }
+            }
+            if constexpr (NT) {
+                // set i = the cell of chunk tid%4 of column n = tid/4 + 64*i -> position 32*(n%4) + n/4
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    uint32_t w[4] = {r.b[2 * i].x, r.b[2 * i].y, r.b[2 * i + 1].x, r.b[2 * i + 1].y};
+                    if (dup > 0) {
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) w[d] = 16 * (tid & 3) + 4 * d >= dup ? w[d] : 0u;
+                    }
+                    const int n = 64 * i + (tid >> 2);
+                    sm.b[tid & 3][32 * (n & 3) + (n >> 2)] = uint4{w[0], w[1], w[2], w[3]};
+                }
+                return;
             }
             // dense operand: column 8*n8 + e -> position 32*(e%4) + 2*n8 + e/4 (a multiplier lane then holds four
             // adjacent columns), dword k4%4 of the cell of chunk k4/4

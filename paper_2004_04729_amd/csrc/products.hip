@@ -494,20 +494,23 @@ size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
     return (generic > fast ? generic : fast) + 256;
 }
 
-// dW of a 1x1, stride-1, unpadded convolution with fp32 activations: dW[k][c] = sum_n sum_p code[n][k][p] X[n][c][p] is the
-// batched, reduction-contiguous form of the FC kernel (fc2_kernel.h, NT) straight on the NCHW tensors: no copy pass.
-struct Conv1x1Plan { bool ok; int n_split, imgs_per_split, spi, tiles_m, tiles_n; size_t partial_bytes; };
+// dW of a 1x1, stride-1, unpadded convolution: dW[k][c] = sum_n sum_p code[n][k][p] X[n][c][p] is the batched,
+// reduction-contiguous form of the FC kernels (fc2_kernel.h / fc2_i8_kernel.h, NT) straight on the NCHW tensors: no copy
+// pass.  kt = reduction indices per K step of the kernel (32 with fp32 activations, 64 with int8 activations).
+struct Conv1x1Plan { bool ok; int n_split, imgs_per_split, spi, tiles_m, tiles_n, kt; size_t partial_bytes; };
 
-Conv1x1Plan conv1x1_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride)
+Conv1x1Plan conv1x1_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride,
+                            int kt = FC2_KT)
 {
     Conv1x1Plan pl;
     pl.ok = false; pl.partial_bytes = 0;
     const int64_t PQ = H * Wd;
     if (!(R == 1 && S == 1 && pad == 0 && stride == 1)) return pl;
-    if (K <= FC2_TM / 2 || C < 4 || C % 4 || PQ % 4 || PQ < FC2_KT) return pl;      // large row tiles; 16-byte loads and stores
+    pl.kt = kt;
+    if (K <= FC2_TM / 2 || C < 4 || C % 4 || PQ % 4 || PQ < kt) return pl;          // large row tiles; 16-byte loads and stores
     if (C * PQ >= ((int64_t)1 << 29) || K * PQ >= ((int64_t)1 << 31) || K * C >= ((int64_t)1 << 30)) return pl;   // 32-bit lane offsets
-    pl.spi = (int)((PQ + FC2_KT - 1) / FC2_KT);
-    if (N * pl.spi >= ((int64_t)1 << 26)) return pl;                              // the reduction axis counts windows of 32
+    pl.spi = (int)((PQ + kt - 1) / kt);
+    if (N * pl.spi >= ((int64_t)1 << 25)) return pl;                              // the reduction axis counts windows of kt
     pl.tiles_m = (int)((K + FC2_TM - 1) / FC2_TM); pl.tiles_n = (int)((C + FC2_TN - 1) / FC2_TN);
     const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
     int64_t n = tiles >= 256 ? 1 : 256 / tiles;                                   // at most one item per workgroup
@@ -521,12 +524,15 @@ Conv1x1Plan conv1x1_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t
     return pl;
 }
 
+template <bool I8>
 hipError_t launch_conv1x1_dw(const ConvArgs &a, const Conv1x1Plan &pl, const int8_t *codes, Scale scale, char *scratch, hipStream_t s)
 {
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, FC2_LDS_BYTES);
+        hipError_t e = I8 ? hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_i8_pair_kernel<true>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, FC2I_LDS_BYTES)
+                          : hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel<true>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, FC2_LDS_BYTES);
         if (e != hipSuccess) return e;
         raised = true;
     }
@@ -535,8 +541,8 @@ hipError_t launch_conv1x1_dw(const ConvArgs &a, const Conv1x1Plan &pl, const int
     FcProblem &p = pa.prob[0];
     p.A = codes; p.lda = PQ; p.B = (const float *)a.X; p.ldb = PQ; p.out = (float *)a.dW; p.ldc = a.C;
     p.partial = (float *)scratch;
-    p.M = (int)a.K; p.N = (int)a.C; p.K = (int)(a.N * pl.spi * FC2_KT);
-    p.k_per_split = pl.imgs_per_split * pl.spi * FC2_KT; p.n_split = pl.n_split; p.tiles_m = pl.tiles_m;
+    p.M = (int)a.K; p.N = (int)a.C; p.K = (int)(a.N * pl.spi * pl.kt);
+    p.k_per_split = pl.imgs_per_split * pl.spi * pl.kt; p.n_split = pl.n_split; p.tiles_m = pl.tiles_m;
     p.n_items = pl.tiles_m * pl.tiles_n * pl.n_split;
     p.scale = scale; p.a_kfast = 1;
     p.nt_pq = (int)PQ; p.nt_spi = pl.spi; p.nt_a_img = a.K * PQ; p.nt_b_img = a.C * PQ;
@@ -544,11 +550,14 @@ hipError_t launch_conv1x1_dw(const ConvArgs &a, const Conv1x1Plan &pl, const int
     pa.prob[1].n_items = 0;
     pa.stats = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     const int grid = p.n_items < 256 ? p.n_items : 256;
-    hipLaunchKernelGGL(fc2_pair_kernel<true>, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
+    if constexpr (I8) hipLaunchKernelGGL(fc2_i8_pair_kernel<true>, dim3(grid), dim3(512), FC2I_LDS_BYTES, s, pa);
+    else              hipLaunchKernelGGL(fc2_pair_kernel<true>, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (pl.n_split > 1) {
-        hipLaunchKernelGGL(fc2_reduce_kernel, dim3(32 * pl.tiles_m * pl.tiles_n), dim3(256), 0, s, pa, pl.tiles_m * pl.tiles_n);
+        const int tiles = pl.tiles_m * pl.tiles_n;
+        if constexpr (I8) hipLaunchKernelGGL(fc2_i8_reduce_kernel, dim3(32 * tiles), dim3(256), 0, s, pa, tiles);
+        else              hipLaunchKernelGGL(fc2_reduce_kernel, dim3(32 * tiles), dim3(256), 0, s, pa, tiles);
         e = hipGetLastError();
     }
     return e;
@@ -629,8 +638,10 @@ size_t conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K
     const ConvDwI8Plan p8 = conv_dw_i8_plan(N, C, H, Wd, K, R, S, pad);
     if (p8.ok && stride == 1) fast[1] = true;
     if (p8.ok && p8.partial_bytes > big) big = p8.partial_bytes;
-    const Conv1x1Plan p1 = conv1x1_dw_plan(N, C, H, Wd, K, R, S, pad, stride);
-    if (p1.ok && p1.partial_bytes > big) big = p1.partial_bytes;
+    for (int i8 = 0; i8 < 2; ++i8) {
+        const Conv1x1Plan p1 = conv1x1_dw_plan(N, C, H, Wd, K, R, S, pad, stride, i8 ? FC2I_KT : FC2_KT);
+        if (p1.ok && p1.partial_bytes > big) big = p1.partial_bytes;
+    }
     const size_t padded = (size_t)(N * K * ((P * Q + 3) / 4 * 4));    // dX: the codes in planes that start on 4-byte boundaries
     if (padded > big) big = padded;
     // dW lowered to the FC kernels: room for the column matrix only where no convolution dW kernel serves the shape (a
@@ -672,7 +683,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
         if (dx_fast || dw_fast) {
             static bool raised = false;
             if (!raised) {
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_i8_pair_kernel),
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_i8_pair_kernel<false>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, FC2I_LDS_BYTES);
                 if (e != hipSuccess) return e;
                 raised = true;
@@ -690,7 +701,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             pending.n = 0; pending.bias_len = 0;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
             const int grid = total < 256 ? total : 256;
-            hipLaunchKernelGGL(fc2_i8_pair_kernel, dim3(grid), dim3(512), FC2I_LDS_BYTES, s, pa);
+            hipLaunchKernelGGL(fc2_i8_pair_kernel<false>, dim3(grid), dim3(512), FC2I_LDS_BYTES, s, pa);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
             const bool r0 = dx_fast && pdx.n_split > 1, r1 = dw_fast && pdw.n_split > 1;
@@ -956,10 +967,12 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
             return a.pad == 1 ? launch_conv_dw_fast<MODE, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE, 3, 3, 0, 1>(pl, s);
         }
     }
-    if constexpr (MODE == MODE_BF16) {
-        const Conv1x1Plan p1 = conv1x1_dw_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad, a.stride);
-        if (p1.ok && rb + p1.partial_bytes <= a.scratch_bytes && (uintptr_t)grad % 4 == 0 && (uintptr_t)a.X % 16 == 0 && (uintptr_t)a.dW % 16 == 0)
-            return launch_conv1x1_dw(a, p1, (const int8_t *)grad, scale, (char *)a.scratch + rb, s);
+    if constexpr (MODE != MODE_F32) {
+        constexpr bool I8 = MODE == MODE_I8;
+        const Conv1x1Plan p1 = conv1x1_dw_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad, a.stride, I8 ? FC2I_KT : FC2_KT);
+        if (p1.ok && rb + p1.partial_bytes <= a.scratch_bytes && (uintptr_t)grad % 4 == 0 && (uintptr_t)a.X % (I8 ? 4 : 16) == 0 &&
+            (uintptr_t)a.dW % 16 == 0)
+            return launch_conv1x1_dw<I8>(a, p1, (const int8_t *)grad, scale, (char *)a.scratch + rb, s);
     }
     if constexpr (MODE != MODE_F32) {
         // neither convolution kernel took it: expand the activations into the column matrix, re-lay the codes, and let the

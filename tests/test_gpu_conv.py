@@ -171,6 +171,24 @@ def test_conv_1x1_dw_batched_fc_kernel(case):
     _check(p, run_conv(p))
 
 
+ONE_BY_ONE_I8 = [  # the same with int8 activations: windows of 64 pixels
+    (4, 36, 14, 14, 130),       # 196 pixels: three windows and one that overlaps; partial row and column tiles
+    (3, 64, 8, 8, 200),         # 64 pixels: one whole window per image
+    (5, 16, 10, 10, 140),       # 100 pixels: the second window repeats 28 indices of the first
+    (70, 128, 14, 14, 256),     # the reduction split over groups of images
+    (2, 260, 10, 10, 300),      # several column tiles, two row tiles
+    (3, 16, 6, 6, 140),         # 36 pixels, less than a window: the other kernels serve
+]
+
+
+@pytest.mark.parametrize("case", ONE_BY_ONE_I8)
+def test_conv_1x1_dw_batched_fc_kernel_int8_bit_exact(case):
+    from gpu_util import run_conv
+    N, C, H, Wd, K = case
+    p = _problem(N, C, H, Wd, K, 1, 1, 0, c=1.0, i8=True)
+    _check(p, run_conv(p))
+
+
 STRIDED = [  # N, C, H, Wd, K, R, S, pad, stride  (the strided layers of a ResNet: 3x3/2, 1x1/2 shortcuts, 7x7/2 stem)
     (2, 5, 9, 7, 6, 3, 3, 1, 2),
     (3, 16, 14, 14, 24, 3, 3, 1, 2),

@@ -107,7 +107,8 @@ CONV_CASES = [  # N, C, H, Wd, K, R, S, pad (, stride)
     (2, 8, 15, 17, 8, 3, 3, 1, 2),      # odd image sizes: the classes have different extents
     (2, 6, 11, 13, 9, 3, 3, 0, 3),      # stride 3: nine classes of one tap each
     (16, 64, 28, 28, 128, 3, 3, 1, 2),  # large enough that dW runs as column matrix x int8 fully connected kernel
-    (32, 128, 14, 14, 256, 1, 1, 0),    # the same for a 1x1 kernel
+    (32, 128, 14, 14, 256, 1, 1, 0),    # 1x1, more than 128 output channels: dW by the int8 fully connected kernel on the NCHW tensors
+    (4, 36, 14, 14, 130, 1, 1, 0),      # the same with partial tiles
     (1, 1, 1, 1, 1, 1, 1, 0),
     (2, 5, 9, 7, 6, 3, 3, 1),
     (3, 16, 14, 14, 24, 3, 3, 1),
