@@ -365,7 +365,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
             for (int j = 0; j < 4; ++j) {
                 uint32_t h[4], m[4], l[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) split3(NT ? bv[j][i] : bv[i][j], h[i], m[i], l[i]);
+                for (int i = 0; i < 4; ++i) split3_upper(NT ? bv[j][i] : bv[i][j], h[i], m[i], l[i]);
                 const int pos = j * 32 + nq;
                 sm.b[0][kq >> 1][pos][kq & 1] = uint2{upper_halves(l[1], l[0]), upper_halves(l[3], l[2])};
                 sm.b[1][kq >> 1][pos][kq & 1] = uint2{upper_halves(m[1], m[0]), upper_halves(m[3], m[2])};

@@ -144,7 +144,7 @@ __device__ __forceinline__ void fc_item(const FcProblem &p, int item, FcSmem &sm
         for (int j = 0; j < 4; ++j) {
             uint32_t h[4], m[4], l[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) split3(b_raw[r][j], h[r], m[r], l[r]);
+            for (int r = 0; r < 4; ++r) split3_upper(b_raw[r][j], h[r], m[r], l[r]);
             const int pos = j * 32 + nq;
             sm.b[0][kq >> 1][pos][kq & 1] = uint2{upper_halves(l[1], l[0]), upper_halves(l[3], l[2])};
             sm.b[1][kq >> 1][pos][kq & 1] = uint2{upper_halves(m[1], m[0]), upper_halves(m[3], m[2])};

@@ -71,6 +71,16 @@ __device__ __forceinline__ void split3(float x, uint32_t &hi, uint32_t &mid, uin
     lo = __float_as_uint(r2) & 0xFFFF0000u;
 }
 
+// The same split for callers that pack the pieces with a byte permute of the upper halves: `lo` keeps its lower 16 bits
+// (the permute drops them), which saves the last mask.
+__device__ __forceinline__ void split3_upper(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+{
+    hi = __float_as_uint(x) & 0xFFFF0000u;
+    float r1 = x - __uint_as_float(hi);
+    mid = __float_as_uint(r1) & 0xFFFF0000u;
+    lo = __float_as_uint(r1 - __uint_as_float(mid));
+}
+
 __device__ __forceinline__ void convert(const RawF32x8 &r, u32x4 (&out)[3])
 {
     uint32_t h[8], m[8], l[8];
