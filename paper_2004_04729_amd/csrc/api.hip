@@ -164,7 +164,8 @@ dbp_status linear_products(const int8_t *codes, const void *format, float step, 
 dbp_status conv2d_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
                                dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
                                int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW,
-                               void *workspace, size_t workspace_bytes, dbp_path path, void *stream, const float *step_dev = nullptr)
+                               void *workspace, size_t workspace_bytes, dbp_path path, void *stream, const float *step_dev = nullptr,
+                               StatsJob job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr})
 {
     if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
     int64_t P, Q;
@@ -187,7 +188,8 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
         g.codes = codes; g.dense = nullptr; g.step = step; g.step_dev = step_dev; g.W = W; g.W8 = nullptr; g.X = X; g.x_dtype = x_dtype;
         g.N = N; g.C = C; g.H = H; g.Wd = Wd; g.K = K; g.R = R; g.S = S; g.pad = pad; g.stride = stride;
         g.dX = dX; g.dW = dW; g.scratch = nullptr; g.scratch_bytes = 0;
-        g.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+        g.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; g.pending = nullptr;
+        if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
         return launch_conv_gather(g, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     }
     const size_t need = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride);
@@ -196,7 +198,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    a.stats_job = job; a.pending = nullptr;
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -319,10 +321,11 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, path == DBP_PATH_GATHER);
+    StatsJob job;
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, path == DBP_PATH_GATHER, &job);
     if (st != DBP_OK) return st;
     return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
-                           ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path, stream);
+                           ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path, stream, nullptr, job);
 }
 
 dbp_status dense_linear_backward(const void *delta, const float *W, const void *X, dbp_dtype x_dtype,
@@ -362,7 +365,7 @@ dbp_status dense_conv2d_backward(const void *delta, const float *W, const void *
     a.codes = nullptr; a.dense = delta; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; a.pending = nullptr;
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -426,13 +429,14 @@ dbp_status dithered_conv2d_backward_q8(const float *delta, const int8_t *W8, con
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, false);
+    StatsJob job;
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, false, &job);
     if (st != DBP_OK) return st;
     ConvArgs a;
     a.codes = k; a.dense = nullptr; a.step = 1.0f; a.step_dev = nullptr; a.W = nullptr; a.W8 = W8 ? W8 : X8; a.X = X8;
     a.x_dtype = DBP_I8; a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = (float *)dX32; a.dW = dW32; a.scratch = ws + c.scratch_offset; a.scratch_bytes = workspace_bytes - c.scratch_offset;
-    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    a.stats_job = job; a.pending = nullptr;
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -548,11 +552,12 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     ex.act = act; ex.step_dev = pair; ex.bias_sums = db ? (int64_t *)(ws + lc.bias_sums) : nullptr; ex.bias_grad = db;
     ex.bias_mode = DBP_BIAS_PER_ROW_GROUP; ex.bias_len = K;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, nullptr, &ex, true);
+    StatsJob job;
+    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex, true);
     if (st != DBP_OK) return st;
-    if (!dX && !dW) return DBP_OK;
+    if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     return conv2d_products(k, ws, 1.0f, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
-                           ws + c.scratch_offset, c.total - c.scratch_offset, path, stream, pair);
+                           ws + c.scratch_offset, c.total - c.scratch_offset, path, stream, pair, job);
 }
 
 }  // extern "C"

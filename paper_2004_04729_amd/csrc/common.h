@@ -111,7 +111,8 @@ struct ConvArgs {
     void         *dW;
     void         *scratch;
     size_t        scratch_bytes;
-    StatsJob      stats_job;
+    StatsJob      stats_job;   // statistics sum / bias gradient still to be done on this stream (none: n == 0 and bias_len == 0)
+    StatsJob     *pending;     // set by launch_conv_mfma: what of stats_job no kernel has taken along yet
 };
 size_t     linear_scratch_bytes(int64_t B, int64_t in, int64_t out);
 size_t     conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride = 1);

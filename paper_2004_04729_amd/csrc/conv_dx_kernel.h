@@ -68,13 +68,62 @@ __device__ __forceinline__ void cdx_stage_map(uint8_t (&lm)[64], const CdxTapMap
     }
 }
 
+// The quantiser's pending statistics sum and bias gradient, taken along by the weight preparation (the first kernel after
+// the quantiser on the stream): the launch has one workgroup more, and that one does nothing else.  All of its loads are
+// in flight at once (the sum is of integers: any order gives the same result).  `workers` = workgroups that prepare weights.
+__device__ __forceinline__ bool cdx_side_jobs(const StatsJob &job, int &workers)
+{
+    workers = (int)gridDim.x;
+    if (job.n <= 0 && job.bias_len <= 0) return false;
+    workers = (int)gridDim.x - 1;
+    if ((int)blockIdx.x != workers) return false;
+    if (job.n > 0) {
+        __shared__ uint64_t s_sum[3][4];
+        __shared__ uint32_t s_max[4];
+        uint64_t nnz = 0, sat = 0, nf = 0; uint32_t mx = 0;
+        for (int base = 0; base < job.n; base += 256 * 8) {
+            u32x4 q[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int i = base + (int)threadIdx.x + 256 * r;
+                q[r] = i < job.n ? job.partials[i] : u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int r = 0; r < 8; ++r) { nnz += q[r].x; sat += q[r].y; nf += q[r].z; mx = max(mx, q[r].w); }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            nnz += __shfl_xor((unsigned long long)nnz, off); sat += __shfl_xor((unsigned long long)sat, off);
+            nf += __shfl_xor((unsigned long long)nf, off); mx = max(mx, (uint32_t)__shfl_xor((int)mx, off));
+        }
+        const int w = threadIdx.x >> 6;
+        if ((threadIdx.x & 63) == 0) { s_sum[0][w] = nnz; s_sum[1][w] = sat; s_sum[2][w] = nf; s_max[w] = mx; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            job.out->nnz = s_sum[0][0] + s_sum[0][1] + s_sum[0][2] + s_sum[0][3];
+            job.out->n_saturated = s_sum[1][0] + s_sum[1][1] + s_sum[1][2] + s_sum[1][3];
+            job.out->n_nonfinite = s_sum[2][0] + s_sum[2][1] + s_sum[2][2] + s_sum[2][3];
+            job.out->max_abs_code = (int32_t)max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3]));
+            job.out->reserved = 0;
+        }
+    }
+    if (job.bias_len > 0) {
+        const double d = job.step_dev ? (double)job.step_dev[0] : (double)job.step;
+        for (int64_t i = threadIdx.x; i < job.bias_len; i += 256) job.bias_grad[i] = (float)(d * (double)job.bias_sums[i]);
+    }
+    return true;
+}
+
 template <bool MAPPED>
-__global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W, uint4 *wp, int K, int C, int RS, int KG, int Cp, int RS_real, CdxTapMap map)
+__global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W, uint4 *wp, int K, int C, int RS, int KG, int Cp, int RS_real, CdxTapMap map,
+                                                                  StatsJob job)
 {
     __shared__ uint8_t lm[64];
+    int workers;
+    if (cdx_side_jobs(job, workers)) return;
     cdx_stage_map<MAPPED>(lm, map);
     const int64_t total = (int64_t)RS * KG * Cp;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)workers * 256) {
         const int c = (int)(i % Cp);
         const int64_t t = i / Cp;
         const int kg = (int)(t % KG), tap = (int)(t / KG);
@@ -95,12 +144,15 @@ __global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W
 
 // int8 weights [K][C][R][S] -> cells of 16 reduction channels in fragment order [tap][k-group][c], zero padded.
 template <bool MAPPED>
-__global__ __launch_bounds__(256) void conv_dx_weight_prep_i8_kernel(const int8_t *W, uint4 *wp, int K, int C, int RS, int KG, int Cp, int RS_real, CdxTapMap map)
+__global__ __launch_bounds__(256) void conv_dx_weight_prep_i8_kernel(const int8_t *W, uint4 *wp, int K, int C, int RS, int KG, int Cp, int RS_real, CdxTapMap map,
+                                                                     StatsJob job)
 {
     __shared__ uint8_t lm[64];
+    int workers;
+    if (cdx_side_jobs(job, workers)) return;
     cdx_stage_map<MAPPED>(lm, map);
     const int64_t total = (int64_t)RS * KG * Cp;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)workers * 256) {
         const int c = (int)(i % Cp);
         const int64_t t = i / Cp;
         const int kg = (int)(t % KG), tap = (int)(t / KG);

@@ -865,14 +865,17 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
         constexpr int PL = I8 ? 1 : 3;
         auto prepare = [&](int taps, int KG, int Cp, const CdxTapMap *map) {
             const int64_t cells = (int64_t)taps * KG * Cp;
-            const int pb = (int)((cells + 255) / 256 < 4096 ? (cells + 255) / 256 : 4096);
+            int pb = (int)((cells + 255) / 256 < 4096 ? (cells + 255) / 256 : 4096);
             const int rs = (int)(a.R * a.S);
+            // the quantiser's pending statistics sum / bias gradient ride along in one more workgroup
+            StatsJob job{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+            if (a.pending && (a.pending->n > 0 || a.pending->bias_len > 0)) { job = *a.pending; a.pending->n = 0; a.pending->bias_len = 0; ++pb; }
             if constexpr (I8) {
-                if (map) hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel<true>, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map);
-                else     hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel<false>, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{});
+                if (map) hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel<true>, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map, job);
+                else     hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel<false>, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{}, job);
             } else {
-                if (map) hipLaunchKernelGGL(conv_dx_weight_prep_kernel<true>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map);
-                else     hipLaunchKernelGGL(conv_dx_weight_prep_kernel<false>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{});
+                if (map) hipLaunchKernelGGL(conv_dx_weight_prep_kernel<true>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map, job);
+                else     hipLaunchKernelGGL(conv_dx_weight_prep_kernel<false>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{}, job);
             }
         };
         // The codes as the kernel wants them: planes that start on 4-byte boundaries.  Planes of a size that is not a
@@ -1017,7 +1020,7 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
                           (char *)a.scratch + rb, a.scratch_bytes - rb, s);
 }
 
-hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s)
+static hipError_t conv_products(const ConvArgs &a, hipStream_t s)
 {
     hipError_t e = hipSuccess;
     if (a.codes && a.W8) {
@@ -1033,6 +1036,18 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s)
     }
     if (a.dX) { e = conv_dx<MODE_F32>(a, a.dense, Scale{1.0f, nullptr}, s); if (e != hipSuccess) return e; }
     if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_F32>(a, a.dense, Scale{1.0f, nullptr}, s) : conv_dw<MODE_I8>(a, a.dense, Scale{1.0f, nullptr}, s);
+    return e;
+}
+
+// The quantiser's pending statistics sum and bias gradient go with the first kernel that can take them along (the weight
+// preparation of the dX kernels); what nobody took is launched on its own afterwards.
+hipError_t launch_conv_mfma(const ConvArgs &a_in, hipStream_t s)
+{
+    ConvArgs a = a_in;
+    StatsJob pending = a_in.stats_job;
+    a.pending = &pending;
+    hipError_t e = conv_products(a, s);
+    if (e == hipSuccess && (pending.n > 0 || pending.bias_len > 0)) e = launch_stats_job(pending, s);
     return e;
 }
 
