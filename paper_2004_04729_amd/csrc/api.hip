@@ -56,7 +56,8 @@ Carve carve(int64_t rows, int64_t cols, size_t scratch_bytes)
 // (its statistics records are used either way).
 dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
                    int8_t *codes, char *fmt_base, const dbp_format_layout *L, dbp_stats *stats, hipStream_t s,
-                   bool want_format = true, StatsJob *defer = nullptr, const dbp_nsd_extras *ex = nullptr, bool bias_zeroed = false)
+                   bool want_format = true, StatsJob *defer = nullptr, const dbp_nsd_extras *ex = nullptr, bool bias_zeroed = false,
+                   const StepTree *tree = nullptr)
 {
     NsdArgs a;
     a.delta = delta; a.codes = codes; a.stats = stats;
@@ -69,6 +70,7 @@ dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, u
     a.inv_step = 1.0f / step;
     a.act = nullptr; a.step_dev = nullptr; a.bias_sums = nullptr; a.bias_grad = nullptr; a.bias_mode = 0; a.bias_len = 0; a.step = step;
     a.bias_zeroed = bias_zeroed ? 1 : 0;
+    a.tree = tree ? *tree : StepTree{nullptr, nullptr, 0, 0, 0.0f, nullptr};
     if (ex) {
         a.act = ex->act; a.step_dev = ex->step_dev; a.bias_sums = ex->bias_sums; a.bias_grad = ex->bias_grad;
         a.bias_mode = ex->bias_mode; a.bias_len = ex->bias_len;
@@ -509,14 +511,15 @@ dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act
     char *ws = (char *)workspace;
     hipStream_t hs = (hipStream_t)stream;
     float *pair = step_out ? step_out : (float *)(ws + lc.step_pair);
+    StepTree tree;
     if (launch_step_size(delta_a, act, B * out, s, pair, ws + lc.step_scratch, hs,
-                         db ? (int64_t *)(ws + lc.bias_sums) : nullptr, db ? out : 0) != hipSuccess) return DBP_ERR_DEVICE;
+                         db ? (int64_t *)(ws + lc.bias_sums) : nullptr, db ? out : 0, &tree) != hipSuccess) return DBP_ERR_DEVICE;
     dbp_nsd_extras ex;
     ex.act = act; ex.step_dev = pair; ex.bias_sums = db ? (int64_t *)(ws + lc.bias_sums) : nullptr; ex.bias_grad = db;
     ex.bias_mode = DBP_BIAS_PER_COLUMN; ex.bias_len = out;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     StatsJob job;
-    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex, true);
+    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex, true, &tree);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     return linear_products(k, ws, 1.0f, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset,
@@ -546,14 +549,15 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     char *ws = (char *)workspace;
     hipStream_t hs = (hipStream_t)stream;
     float *pair = step_out ? step_out : (float *)(ws + lc.step_pair);
+    StepTree tree;
     if (launch_step_size(delta_a, act, N * K * P * Q, s, pair, ws + lc.step_scratch, hs,
-                         db ? (int64_t *)(ws + lc.bias_sums) : nullptr, db ? K : 0) != hipSuccess) return DBP_ERR_DEVICE;
+                         db ? (int64_t *)(ws + lc.bias_sums) : nullptr, db ? K : 0, &tree) != hipSuccess) return DBP_ERR_DEVICE;
     dbp_nsd_extras ex;
     ex.act = act; ex.step_dev = pair; ex.bias_sums = db ? (int64_t *)(ws + lc.bias_sums) : nullptr; ex.bias_grad = db;
     ex.bias_mode = DBP_BIAS_PER_ROW_GROUP; ex.bias_len = K;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     StatsJob job;
-    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex, true);
+    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex, true, &tree);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     return conv2d_products(k, ws, 1.0f, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,

@@ -28,6 +28,10 @@ constexpr size_t kNsdScratchBytes = (size_t)kNsdMaxBlocks * 16;      // one 16-b
 struct DitherKeys { uint32_t k0, k1; };
 DitherKeys make_dither_keys(uint64_t seed);
 
+// A step-size tree that launch_step_size left unfinished (at most 256 partial sums): the quantiser's workgroups add the
+// last levels themselves, in the tree's order, and its first workgroup writes {Delta, 1/Delta}.  count == 0: none.
+struct StepTree { const double *s1, *s2; int count; int64_t n; float s; float *step_out; };
+
 struct NsdArgs {
     const float *delta;
     int8_t      *codes;
@@ -49,6 +53,7 @@ struct NsdArgs {
     int64_t      bias_len;
     float        step;        // host Delta (bias_grad without step_dev)
     int          bias_zeroed; // bias_sums were cleared by an earlier kernel of the stream (launch_step_size)
+    StepTree     tree;        // unfinished step size (then step_dev is what the kernel writes, not what it reads)
     int          run;                                  // consecutive tiles per wavefront run (set by launch_nsd)
     int64_t      wave_stride_rows, wave_stride_segs;   // grid stride in tiles = rows*tiles_per_row + segs (set by launch_nsd)
 };
@@ -72,7 +77,8 @@ size_t     step_size_scratch_bytes(int64_t n);
 size_t     quantize_scratch_bytes(int64_t n);
 hipError_t launch_quantize_int8(const float *x, int64_t n, int8_t *q, float *scale_out, void *scratch, hipStream_t st);
 hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st,
-                            int64_t *zero = nullptr, int64_t zero_len = 0);   // also clears zero[0..zero_len)
+                            int64_t *zero = nullptr, int64_t zero_len = 0,    // also clears zero[0..zero_len)
+                            StepTree *defer = nullptr);   // non-null: small trees are left to the quantiser (defer->count > 0)
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

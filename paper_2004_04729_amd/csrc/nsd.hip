@@ -60,6 +60,21 @@ __device__ __forceinline__ uint32_t pack_low_bytes(int a, int b, int c, int d)
     return ab | cd;
 }
 
+// {Delta, 1/Delta} of Algorithm 1 from the sums of the values and of their squares: Delta = s * sqrt(S2/n - (S1/n)^2) in
+// fp64, rounded to fp32 once.  A degenerate tensor (constant or non-finite gradient) gives {0, 0}: everything quantises
+// to zero codes and the products are zero.
+__device__ __forceinline__ void step_pair_from_sums(double S1, double S2, int64_t n, float s, float &step_out, float &inv_out)
+{
+    double var = n > 0 ? (S2 - S1 * S1 / (double)n) / (double)n : 0.0;
+    if (var < 0.0) var = 0.0;
+    const double sigma = __builtin_sqrt(var);
+    const float step = (float)((double)s * sigma);
+    const float inv = __fdiv_rn(1.0f, step);
+    const bool ok = step > 0.0f && step < __builtin_inff() && inv >= 1.17549435e-38f && inv < __builtin_inff();
+    step_out = ok ? step : 0.0f;
+    inv_out = ok ? inv : 0.0f;
+}
+
 // One wavefront owns one 256-column tile per loop trip; every index that is the same for the whole
 // wavefront (tile, row, segment, base offsets, the high half of the dither counter) lives in SGPRs.
 // EX adds what surrounds the quantiser in a layer's backward pass: the rectifier's derivative applied on load
@@ -71,7 +86,39 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t n_waves = (int64_t)gridDim.x * 4;
-    const float inv = (EX && a.step_dev) ? a.step_dev[1] : a.inv_step;
+    float inv = a.inv_step;
+    if constexpr (EX) {
+        if (a.tree.count > 0) {
+            // the step size's tree is unfinished: every workgroup adds its last two levels (groups of 16 partial sums in
+            // order, then the group sums in order: the same additions as std_finish_kernel), the first one publishes it
+            __shared__ double s_tree[2][16];
+            __shared__ float s_pair[2];
+            const int count = a.tree.count, groups = (count + 15) >> 4;
+            if ((int)threadIdx.x < groups) {
+                const int lo = (int)threadIdx.x * 16;
+                double v1[16], v2[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) { const int i = min(lo + j, count - 1); v1[j] = a.tree.s1[i]; v2[j] = a.tree.s2[i]; }
+                double t1 = v1[0], t2 = v2[0];
+#pragma unroll
+                for (int j = 1; j < 16; ++j) if (lo + j < count) { t1 += v1[j]; t2 += v2[j]; }
+                s_tree[0][threadIdx.x] = t1; s_tree[1][threadIdx.x] = t2;
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                double S1 = s_tree[0][0], S2 = s_tree[1][0];
+                for (int i = 1; i < groups; ++i) { S1 += s_tree[0][i]; S2 += s_tree[1][i]; }
+                float step, inv_step;
+                step_pair_from_sums(S1, S2, a.tree.n, a.tree.s, step, inv_step);
+                s_pair[0] = step; s_pair[1] = inv_step;
+                if (blockIdx.x == 0) { a.tree.step_out[0] = step; a.tree.step_out[1] = inv_step; }
+            }
+            __syncthreads();
+            inv = s_pair[1];
+        } else if (a.step_dev) {
+            inv = a.step_dev[1];
+        }
+    }
     const int c_in = 4 * lane;                                        // in-tile column of this lane's first element
 
     __shared__ __attribute__((aligned(16))) uint16_t s_ent[4][DBP_TILE];                          // per-wavefront staging of compacted entries
@@ -416,16 +463,10 @@ __global__ __launch_bounds__(256) void std_finish_kernel(double *a1, double *a2,
         count = groups;
     }
     if (threadIdx.x == 0) {
-        const double S1 = n > 0 ? src1[0] : 0.0, S2 = n > 0 ? src2[0] : 0.0;
-        double var = n > 0 ? (S2 - S1 * S1 / (double)n) / (double)n : 0.0;
-        if (var < 0.0) var = 0.0;
-        const double sigma = __builtin_sqrt(var);
-        float step = (float)((double)s * sigma);
-        float inv = __fdiv_rn(1.0f, step);
-        // degenerate layer (constant or non-finite gradient): everything quantises to zero codes, products are zero
-        const bool ok = step > 0.0f && step < __builtin_inff() && inv >= 1.17549435e-38f && inv < __builtin_inff();
-        step_out[0] = ok ? step : 0.0f;
-        step_out[1] = ok ? inv : 0.0f;
+        float step, inv;
+        step_pair_from_sums(n > 0 ? src1[0] : 0.0, n > 0 ? src2[0] : 0.0, n, s, step, inv);
+        step_out[0] = step;
+        step_out[1] = inv;
     }
 }
 
@@ -513,12 +554,18 @@ size_t step_size_scratch_bytes(int64_t n)
 }
 
 hipError_t launch_step_size(const float *delta, const float *act, int64_t n, float s, float *step_out, void *scratch, hipStream_t st,
-                            int64_t *zero, int64_t zero_len)
+                            int64_t *zero, int64_t zero_len, StepTree *defer)
 {
     const int64_t wgs = (n + 4095) / 4096 > 0 ? (n + 4095) / 4096 : 1;
     const int64_t second = (wgs + 15) / 16;
     double *a1 = (double *)scratch, *a2 = a1 + wgs, *b1 = a2 + wgs, *b2 = b1 + second;
     hipLaunchKernelGGL(std_tree_kernel, dim3((unsigned)wgs), dim3(256), 0, st, delta, act, n, a1, a2, zero, zero_len);
+    if (defer) *defer = StepTree{nullptr, nullptr, 0, 0, 0.0f, nullptr};
+    if (defer && wgs <= 256) {
+        // two levels are left: the quantiser's workgroups add them on their way in (a launch less)
+        *defer = StepTree{a1, a2, (int)wgs, n, s, step_out};
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(std_finish_kernel, dim3(1), dim3(256), 0, st, a1, a2, b1, b2, wgs, n, s, step_out);
     return hipGetLastError();
 }

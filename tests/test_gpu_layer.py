@@ -163,7 +163,10 @@ def _linear_layer(p, s, act, want_db=True, path=None, x_i8=None):
                 pair=pair.cpu().numpy(), stats=dbp.Stats.from_tensor(st))
 
 
-@pytest.mark.parametrize("B,in_,out", [(5, 3, 2), (64, 784, 300), (300, 520, 1030), (256, 1024, 1000)])
+# the step size's sum tree: 1, 5, 76, 63 partial sums; 17 (a second level of two groups), 256 (the most the quantiser
+# finishes itself) and 269 (finished by the kernel of its own)
+@pytest.mark.parametrize("B,in_,out", [(5, 3, 2), (64, 784, 300), (300, 520, 1030), (256, 1024, 1000),
+                                       (65, 8, 1024), (1024, 16, 1024), (1100, 64, 1000)])
 @pytest.mark.parametrize("path", ["mfma", "gather"])
 def test_linear_layer_backward_is_algorithm_1(B, in_, out, path):
     import paper_2004_04729_amd as dbp
