@@ -95,11 +95,11 @@ def main():
         dst = torch.empty_like(src)
         torch.mul(src, 2.0, out=dst)
         torch.cuda.synchronize()
-        for i in range(6):
+        for i in range(50):
             dbp.linear_products(b["codes"], fmt, p2.step, b["W"], b["X"], dbp.F32, B, in_, out, b["dX"], b["dW"], b["ws"],
                                 dbp.PATH_MFMA, stream)
         torch.cuda.synchronize()
-        print(json.dumps({"probe": "torch.mul on 2^28 floats (1 GiB read, 1 GiB written) + 6 launches of fc2_pair_kernel "
+        print(json.dumps({"probe": "torch.mul on 2^28 floats (1 GiB read, 1 GiB written) + 50 launches of fc2_pair_kernel "
                                    "and fc2_reduce_kernel on the 256x4096x4096 layer"}))
         return
 

@@ -48,8 +48,17 @@ struct Fc2Cursor {
 // workgroups (pass p gives workgroup w item p*G + w, the next pass p*G + G-1-w), which balances the number
 // of K steps; every workgroup then starts at a different place of its own list (rotation by w), so that
 // the tiles of the chip are not all finished, and stored, at the same moment.
+// With a.gx > 0 the workgroups are two groups instead, one per problem: a split product then needs fewer, longer items
+// (fewer partial tiles to write and to sum) for the same balance.
 __device__ __forceinline__ int fc2_items_of_workgroup(const FcPairArgs &a)
 {
+    if (a.gx > 0) {
+        const int w = blockIdx.x;
+        const bool first = w < a.gx;
+        const int n = first ? a.prob[0].n_items : a.prob[1].n_items;
+        const int wi = first ? w : w - a.gx, gp = first ? a.gx : (int)gridDim.x - a.gx;
+        return n > wi ? (n - wi + gp - 1) / gp : 0;
+    }
     const int total = a.prob[0].n_items + a.prob[1].n_items;
     const int G = gridDim.x, w = blockIdx.x;
     const int passes = (total + G - 1) / G;
@@ -62,16 +71,24 @@ __device__ __forceinline__ Fc2Item fc2_decode(const FcPairArgs &a, int i, int mi
     const int n0 = a.prob[0].n_items;
     const int G = gridDim.x, w = blockIdx.x;
     const int ps = (i + w) % mine;
-    const int t = ps * G + ((ps & 1) ? G - 1 - w : w);
     Fc2Item c;
-    c.which = t < n0 ? 0 : 1;
-    const int item = t < n0 ? t : t - n0;
+    int t, item;
+    if (a.gx > 0) {
+        const bool first = w < a.gx;
+        c.which = first ? 0 : 1;
+        item = ps * (first ? a.gx : G - a.gx) + (first ? w : w - a.gx);
+        t = -1;
+    } else {
+        t = ps * G + ((ps & 1) ? G - 1 - w : w);
+        c.which = t < n0 ? 0 : 1;
+        item = t < n0 ? t : t - n0;
+    }
     const FcProblem &p = a.prob[c.which];
     c.tile = item / p.n_split; c.z = item - c.tile * p.n_split;
     // Workgroup w runs on XCD w % 8, and each XCD has an L2 of its own.  Where the counts divide evenly the items
     // are renumbered so that one XCD keeps to one share of the re-read operand: the same reduction slice of
     // the codes for a split product, the same column tiles of the dense operand otherwise.
-    if ((G & 7) == 0 && (n0 & 7) == 0 && (p.n_items & 7) == 0) {
+    if (t >= 0 && (G & 7) == 0 && (n0 & 7) == 0 && (p.n_items & 7) == 0) {
         const int x = ((t / G) & 1) ? 7 - (t & 7) : (t & 7), r = item >> 3;
         const int tiles_n = p.n_items / (p.n_split * p.tiles_m);
         if (p.n_split > 1 && (p.n_split & 7) == 0) {

@@ -42,7 +42,9 @@ struct FcProblem {
     int nt_pq, nt_spi;
     int64_t nt_a_img, nt_b_img;
 };
-struct FcPairArgs { FcProblem prob[2]; StatsJob stats; };
+// gx > 0 (kernels of fc2_kernel.h / fc2_i8_kernel.h): the first gx workgroups of the launch take the items of problem 0, the
+// others those of problem 1, each group dealing its items round robin; gx == 0: one list for both, dealt in a serpentine.
+struct FcPairArgs { FcProblem prob[2]; StatsJob stats; int gx = 0; };
 
 __device__ __forceinline__ uint32_t bf16x2_from_codes(int a, int b)
 {

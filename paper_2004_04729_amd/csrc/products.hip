@@ -446,6 +446,48 @@ void fc2_plans(int64_t B, int64_t in, int64_t out, bool want_dx, bool want_dw, F
     split(sx, dx); split(sw, dw);
 }
 
+// The two products on two groups of workgroups (FcPairArgs::gx) where that needs fewer split-K partials than the common
+// list for the same longest workgroup: group sizes in proportion to the products' K steps (multiples of 8: every XCD
+// gets its share of both), a split product cut into about one item per workgroup of its group.  Returns gx, or 0 to keep
+// the common list; dx and dw are replaced by the group plan when it is taken.
+int fc2_group_plan(int64_t B, int64_t in, int64_t out, FcPlan &dx, FcPlan &dw, int kt = FC2_KT)
+{
+    const int G = 256;
+    const int64_t sx = (out + kt - 1) / kt, sw = (B + kt - 1) / kt;
+    const int64_t all_x = dx.tiles * sx, all_w = dw.tiles * sw;
+    if (dx.tiles * dx.n_split + dw.tiles * dw.n_split < G) return 0;
+    int gx = (int)((G * all_x + (all_x + all_w) / 2) / (all_x + all_w) + 4) / 8 * 8;
+    gx = gx < 8 ? 8 : gx > G - 8 ? G - 8 : gx;
+    auto cut = [kt](int64_t steps, FcPlan pl, int g) {
+        int64_t n = pl.tiles >= g ? 1 : g / pl.tiles;
+        const int64_t most = steps / 8 > 0 ? steps / 8 : 1;            // at least eight K steps per item
+        if (n > most) n = most;
+        const int64_t per = (steps + n - 1) / n;
+        pl.k_per_split = (int)(per * kt);
+        pl.n_split = (int)((steps + per - 1) / per);
+        pl.partial_bytes = pl.n_split > 1 ? (size_t)pl.tiles * pl.n_split * FC2_TM * FC2_TN * sizeof(float) : 0;
+        return pl;
+    };
+    const FcPlan gdx = cut(sx, dx, gx), gdw = cut(sw, dw, G - gx);
+    auto rounds = [](const FcPlan &pl, int g) { return (pl.tiles * pl.n_split + g - 1) / g * (int64_t)(pl.k_per_split); };
+    const int64_t longest_groups = rounds(gdx, gx) > rounds(gdw, G - gx) ? rounds(gdx, gx) : rounds(gdw, G - gx);
+    // the common list: workgroup w takes items p*G + (w or G-1-w) of the concatenated lists
+    const int64_t n0 = dx.tiles * dx.n_split, total = n0 + dw.tiles * dw.n_split;
+    int64_t longest_common = 0;
+    for (int w = 0; w < G; ++w) {
+        int64_t len = 0;
+        for (int64_t ps = 0; ps * G < total; ++ps) {
+            const int64_t t = ps * G + ((ps & 1) ? G - 1 - w : w);
+            if (t < total) len += t < n0 ? dx.k_per_split : dw.k_per_split;
+        }
+        if (len > longest_common) longest_common = len;
+    }
+    if (longest_groups > longest_common || gdx.partial_bytes + gdw.partial_bytes >= dx.partial_bytes + dw.partial_bytes) return 0;
+    if ((gdx.tiles * gdx.n_split + gx - 1) / gx > FC2_MAX_ITEMS || (gdw.tiles * gdw.n_split + G - gx - 1) / (G - gx) > FC2_MAX_ITEMS) return 0;
+    dx = gdx; dw = gdw;
+    return gx;
+}
+
 bool fc_fast_ok(bool a_kfast, const int8_t *A, int64_t lda, const float *B, int64_t ldb, int64_t M, int64_t N, const float *out)
 {
     if (N < 4 || N % 4 || ldb % 4 || ((uintptr_t)B % 16) || ((uintptr_t)out % 8)) return false;
@@ -680,6 +722,8 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             const int64_t items = (dx_fast ? pdx.tiles * pdx.n_split : 0) + (dw_fast ? pdw.tiles * pdw.n_split : 0);
             if (items > (int64_t)FC2_MAX_ITEMS * 256) dx_fast = dw_fast = false;
         }
+        int gx = 0;
+        if (dx_fast && dw_fast) gx = fc2_group_plan(B, in, out, pdx, pdw, FC2I_KT);
         if (dx_fast || dw_fast) {
             static bool raised = false;
             if (!raised) {
@@ -699,6 +743,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
             pa.stats = pending;
             pending.n = 0; pending.bias_len = 0;
+            pa.gx = gx;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
             const int grid = total < 256 ? total : 256;
             hipLaunchKernelGGL(fc2_i8_pair_kernel<false>, dim3(grid), dim3(512), FC2I_LDS_BYTES, s, pa);
@@ -743,6 +788,8 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             const int64_t items = (dx_fast ? pdx.tiles * pdx.n_split : 0) + (dw_fast ? pdw.tiles * pdw.n_split : 0);
             if (items > (int64_t)FC2_MAX_ITEMS * 256) use_fc2 = false;     // the per-workgroup item table is fixed
         }
+        int gx = 0;
+        if (use_fc2 && dx_fast && dw_fast) gx = fc2_group_plan(B, in, out, pdx, pdw);
         if (use_fc2) {
             static bool raised = false;
             if (!raised) {
@@ -762,8 +809,9 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
             pa.stats = pending;                            // finished by a stager wavefront of the last workgroup
             pending.n = 0; pending.bias_len = 0;
+            pa.gx = gx;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
-            const int grid = total < 256 ? total : 256;    // persistent: one workgroup per CU
+            const int grid = total < 256 ? total : 256;    // persistent: one workgroup per CU (256 whenever gx > 0)
             hipLaunchKernelGGL(fc2_pair_kernel<false>, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
             e = hipGetLastError();
             if (e != hipSuccess) return e;

@@ -158,6 +158,14 @@ def test_fc_many_items_per_workgroup_sampled():
     check_products(res["dW"].ravel()[iw], r, a, "dW (sampled)")
 
 
+def test_fc_two_groups_of_unequal_size():
+    # 300 x 4096 x 4000: the products run on two groups of workgroups (160 for dX, two splits per tile; 96 for dW), with
+    # ragged row tiles, a ragged last K step on both sides and idle workgroups in the first group
+    from gpu_util import run_linear
+    p = _problem(300, 4096, 4000, seed=41, c=8.0)
+    _check_fp32(p, run_linear(p))
+
+
 def test_config1_and_config2_full_size():
     import paper_2004_04729_amd as dbp
     from gpu_util import run_linear

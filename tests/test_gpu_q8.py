@@ -86,7 +86,8 @@ def test_fc_q8_is_bit_exact(B, in_, out):
 # shapes the role-specialised int8 kernel takes (batch and out above 128, in a multiple of 8), through its edges:
 # ragged tiles, reductions that end inside a window of 64, a batch that is not a multiple of 4
 @pytest.mark.parametrize("B,in_,out", [(258, 264, 200), (130, 4104, 140), (1000, 136, 260), (512, 512, 392),
-                                       (256, 1024, 4096), (256, 4096, 1000)])
+                                       (256, 1024, 4096), (256, 4096, 1000),
+                                       (256, 4096, 4096)])     # the two products on two groups of workgroups
 def test_fc_q8_large_layer_kernel(B, in_, out):
     _fc(B, in_, out, seed=B + in_ + out, c=8.0)
     _fc(B, in_, out, seed=B + in_ + out, c=8.0, want_dw=False)
