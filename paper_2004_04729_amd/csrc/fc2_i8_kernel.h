@@ -316,8 +316,8 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
                             const int ii = 8 * (v >> 2) + 4 * lhalf + (v & 3);
                             const int row = fc2_row(p.a_kfast, c.tile_m, wave, i, ii);
                             if (row < p.M)
-                                *(i32v4 *)((int32_t *)p.out + (int64_t)row * p.ldc + col) =
-                                    i32v4{acc[i][0][v], acc[i][1][v], acc[i][2][v], acc[i][3][v]};
+                                __builtin_nontemporal_store(i32v4{acc[i][0][v], acc[i][1][v], acc[i][2][v], acc[i][3][v]},
+                                                            (i32v4 *)((int32_t *)p.out + (int64_t)row * p.ldc + col));
                         }
                 }
             }
