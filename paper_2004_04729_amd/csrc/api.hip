@@ -142,6 +142,7 @@ dbp_status linear_products(const int8_t *codes, const void *format, float step, 
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    if (path == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
     LinearArgs a;
     a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.stats_job = job;
@@ -153,7 +154,9 @@ dbp_status linear_products(const int8_t *codes, const void *format, float step, 
         const char *fb = (const char *)format;
         FormatView f{(const uint64_t *)(fb + L.bitmap_offset), (const uint16_t *)(fb + L.tile_nnz_offset),
                      (const uint16_t *)(fb + L.entries_offset), L.tiles_per_row};
-        a.scratch = nullptr; a.scratch_bytes = 0;
+        // split partials of the dX kernel live in the workspace; without one the kernel runs unsplit
+        const bool ws_ok = workspace && aligned(workspace, 256);
+        a.scratch = ws_ok ? workspace : nullptr; a.scratch_bytes = ws_ok ? workspace_bytes : 0;
         if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
         return launch_linear_gather(a, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     }
@@ -280,6 +283,7 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    if (path == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
     const Carve c = carve(B, out, linear_scratch_bytes(B, in, out));
     if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
@@ -504,6 +508,7 @@ dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
     if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    if (path == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
     const Carve c = carve(B, out, linear_scratch_bytes(B, in, out));
     const LayerCarve lc = layer_carve(c.total, B * out, out);
     if (!workspace || workspace_bytes < lc.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;

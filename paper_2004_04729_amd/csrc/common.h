@@ -127,7 +127,10 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s);
 
 // ---- gather path (gather.hip) ------------------------------------------------------------------
 struct FormatView { const uint64_t *bitmap; const uint16_t *tile_nnz; const uint16_t *entries; int64_t tiles_per_row; };
-hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s);
+// flag != nullptr: device-side dispatch, the kernels run only when *flag == flag_want (fc_rows_kernel shapes only).
+hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s, const int *flag = nullptr, int flag_want = 0);
+size_t     linear_gather_scratch_bytes(int64_t B, int64_t in, int64_t out);    // split partials of the gather dX kernel
+bool       linear_gather_supported(int64_t B, int64_t in, int64_t out);
 // Convolution gather kernels: any stride; kernels of at most 64 taps, output planes below 4096 x 4096, and for dX an input
 // plane of at most about 37 KiB (four of them accumulate in LDS).
 bool       conv_gather_supported(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t P, int64_t Q, bool want_dx);

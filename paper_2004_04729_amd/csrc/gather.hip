@@ -1,7 +1,12 @@
-// Gather path of the fully connected products: walk only the nonzero codes (Sec. "Computational
-// complexity": O(p_nz * m*k*n) multiply-adds instead of O(m*k*n)).  Plain fp32 FMA on the vector ALUs,
-// one output row slab per workgroup, operands streamed through L2.  Pays off only at very high
-// sparsity; the matrix-core path is faster below the measured threshold.
+// Gather path of the backward products: walk only the nonzero codes (Sec. "Computational complexity":
+// O(p_nz * m*k*n) multiply-adds instead of O(m*k*n)).  Plain fp32 FMA on the vector ALUs.
+//
+// Fully connected layers: fc_rows_kernel.  A workgroup owns 256 output rows x 128 output columns, stages the dense
+// operand (W for dX, X for dW) through LDS in tiles of 64 reduction indices, and every wavefront walks the nonzero
+// codes of its 16 rows against the staged tile: one LDS read feeds one multiply-add per lane, so the staged tile is
+// shared by all 256 rows and the dense operand leaves HBM / L2 once per workgroup.  The one-row-per-workgroup kernels
+// further down serve the shapes it declines (odd strides and alignments, int8 activations).
+// Convolutions: conv_d{x,w}_gather_kernel walk the compacted entries of the tile-sparse format.
 #include "common.h"
 
 namespace dbp {
@@ -125,6 +130,238 @@ __global__ __launch_bounds__(256) void linear_dw_gather_kernel(const int8_t *cod
             if (sizeof(XT) == 4) dW[(int64_t)o * in + i0 + j] = (AccT)(step_arg.get() * (float)acc[j]);
             else dW[(int64_t)o * in + i0 + j] = acc[j];
         }
+}
+
+// ---- LDS-staged row-list kernel of the fully connected products ------------------------------------
+//   out[r][i] = scale * sum over c with A(r,c) != 0 of  A(r,c) * D[c][i]
+//   dX (TR = false): r = b, c = o, A(r,c) = codes[r*ldc + c], D = W [out][in]
+//   dW (TR = true):  r = o, c = b, A(r,c) = codes[c*ldc + r], D = X [B][in]
+// A workgroup of 16 wavefronts owns 256 output rows x 64*CPL output columns and walks the reduction in chunks of 64
+// indices; the chunk's tile of D goes through LDS once and serves all 256 rows.  A wavefront's lanes are the chunk's
+// reduction indices when it looks at codes (the nonzero mask of a row is one ballot, a code reaches the scalar unit
+// through a lane read) and CPL output columns each when it multiplies (one LDS read of 4*CPL bytes feeds CPL
+// multiply-adds).  The accumulators of a wavefront's 16 rows are registers with compile-time indices; the walk over a
+// row's nonzeros is a scalar loop.  Sums run in a fixed order (chunks in order, nonzeros by lane): deterministic.
+// Codes: dX stages the chunk's 256 x 64 code bytes in LDS beside the tile (coalesced 4-byte loads; a row's codes are
+// then one byte read per lane); dW loads, per lane (= batch row), the 16 code bytes of the wavefront's 16 output rows.
+// dX (DEEP): W comes from HBM and is fetched two tiles ahead (two sets of staging registers); 128-column slabs keep the
+// number of reduction parts, hence of partial sums, low.  dW: X is small and sits in L2; one tile ahead, 256-column slabs.
+// Every step issues the same loads in the same order on every path (addresses are clamped and values masked rather
+// than loads predicated; steps past the end repeat the last one): the compiler's wait counts can then leave exactly the
+// younger loads outstanding -- a load that only some paths issue makes it wait for all of them.
+constexpr int FR_THREADS = 1024, FR_WAVES = 16, FR_CH = 64;
+constexpr int FR_RW_DX = 8, FR_RW_DW = 16;                        // rows per wavefront: 128-row blocks for dX (fewer reduction parts), 256 for dW
+constexpr int FR_CPL_DX = 4, FR_CPL_DW = 4;                       // output columns per lane: 256-column slabs
+constexpr size_t fr_lds_bytes(int cpl, int rw, bool tr) { return (size_t)2 * FR_CH * 64 * cpl * sizeof(float) + (tr ? 0 : 2 * FR_WAVES * rw * FR_CH); }
+
+struct FcRowsArgs {
+    const int8_t *codes; int64_t ldc;
+    const float *D; int64_t ldd;
+    float *out, *partial;                     // partial [sparts][rows][cols] when sparts > 1
+    int rows, red, cols;
+    int slabs, row_blocks, n_chunks;
+    int rparts, rb_per_part;                  // parts over the row blocks
+    int sparts, ch_per_part;                  // parts over the reduction (partial sums when sparts > 1)
+    Scale scale;
+    const int *flag; int flag_want;           // device-side dispatch: run only when *flag == flag_want (flag may be null)
+};
+
+template <bool TR, int FR_RW, int FR_CPL, bool DEEP, int ALIGN>
+__global__ __launch_bounds__(FR_THREADS) void fc_rows_kernel(FcRowsArgs a)
+{
+    static_assert(TR ? FR_RW == 16 : (FR_RW == 8 || FR_RW == 16), "dW: 16 code bytes per lane; dX: code tiles of 8 or 16 KiB");
+    constexpr int FR_ROWS = FR_WAVES * FR_RW, FR_CODE_TILE = FR_ROWS * FR_CH;
+    constexpr int FR_SLAB = 64 * FR_CPL;
+    constexpr int FR_TILE = FR_CH * FR_SLAB;                      // floats per staged tile
+    constexpr int FR_STAGE = FR_TILE / 4 / FR_THREADS;            // 16-byte pieces per thread and tile
+    constexpr int FR_SROWS = FR_THREADS * 4 / FR_SLAB;            // tile rows one pass of the workgroup's 16-byte loads covers
+    extern __shared__ __attribute__((aligned(16))) float fr_lds[];
+    if (a.flag && a.flag[0] != a.flag_want) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slab = (int)blockIdx.x % a.slabs, part = (int)blockIdx.x / a.slabs;
+    const int rp = part / a.sparts, sp = part - rp * a.sparts;
+    const int col0 = slab * FR_SLAB;
+    const int rb_lo = rp * a.rb_per_part, rb_hi = min(a.row_blocks, rb_lo + a.rb_per_part);
+    const int ch_lo = sp * a.ch_per_part, ch_hi = min(a.n_chunks, ch_lo + a.ch_per_part);
+    const int n_ch = ch_hi - ch_lo, n_steps = (rb_hi - rb_lo) * n_ch;
+    if (n_steps <= 0) return;
+    int8_t *code_lds = (int8_t *)(fr_lds + 2 * FR_TILE);          // dX: two code tiles [256 rows][64 reduction indices]
+
+    constexpr int NCD = FR_RW / 4;                                // dX: code dwords a thread stages per step
+    struct Stage { f32x4 d[FR_STAGE]; int c[TR ? 1 : NCD]; };     // what a thread moves per step: tile pieces (+ dX code dwords)
+    // ---- staging: consecutive threads move consecutive 16-byte pieces of a tile row (and of a code row)
+    const int sr = tid / (FR_SLAB / 4), sc = (tid % (FR_SLAB / 4)) * 4;
+    const int scol = min(col0 + sc, a.cols - 4);                 // columns past the end repeat the last ones (never stored)
+    const int cr = tid / (16 / NCD), cc = (tid % (16 / NCD)) * 4 * NCD;   // dX codes: row of the block, first of this thread's reduction indices
+    auto stage_load = [&](Stage &st, int rb, int ch) {
+        if constexpr (!TR) {
+            const int8_t *src = a.codes + (int64_t)min(rb * FR_ROWS + cr, a.rows - 1) * a.ldc;
+#pragma unroll
+            for (int q = 0; q < NCD; ++q) st.c[q] = *(const int *)(src + min(ch * FR_CH + cc + 4 * q, a.red - 4));
+        }
+#pragma unroll
+        for (int i = 0; i < FR_STAGE; ++i) {
+            const int r = min(ch * FR_CH + sr + FR_SROWS * i, a.red - 1);   // rows past the end repeat the last one (never read: their codes are 0)
+            st.d[i] = *(const f32x4 *)(a.D + (int64_t)r * a.ldd + scol);
+        }
+    };
+    auto stage_store = [&](Stage &st, int buf, int rb, int ch) {
+        float *t = fr_lds + buf * FR_TILE;
+#pragma unroll
+        for (int i = 0; i < FR_STAGE; ++i) *(f32x4 *)(t + (sr + FR_SROWS * i) * FR_SLAB + sc) = st.d[i];
+        if constexpr (!TR) {
+            // codes outside the matrix become 0 here (bit masks: a select on a wave-uniform condition would be turned into
+            // a branch around the load)
+            const int row_mask = -(int)(rb * FR_ROWS + cr < a.rows);
+            int *dstc = (int *)(code_lds + buf * FR_CODE_TILE + cr * FR_CH + cc);
+#pragma unroll
+            for (int q = 0; q < NCD; ++q) dstc[q] = st.c[q] & row_mask & -(int)(ch * FR_CH + cc + 4 * q < a.red);
+        }
+    };
+
+    // ---- dW: the 16 code bytes of batch row c that belong to the wavefront's output rows, in registers
+    auto fetch_codes = [&](int (&raw)[4], int rb, int ch) {
+        const int row0 = rb * FR_ROWS + wave * FR_RW;
+        const int8_t *src = a.codes + (int64_t)min(ch * FR_CH + lane, a.red - 1) * a.ldc;
+        if constexpr (ALIGN == 16) {
+            const i32x4 v = *(const i32x4 *)(src + min(row0, a.rows - 16));
+            raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
+        } else if constexpr (ALIGN == 4) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) raw[q] = *(const int *)(src + min(row0 + 4 * q, a.rows - 4));
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                raw[q] = (int)(uint8_t)src[min(row0 + 4 * q, a.rows - 1)] | (int)(uint8_t)src[min(row0 + 4 * q + 1, a.rows - 1)] << 8 |
+                         (int)(uint8_t)src[min(row0 + 4 * q + 2, a.rows - 1)] << 16 | (int)(uint8_t)src[min(row0 + 4 * q + 3, a.rows - 1)] << 24;
+        }
+    };
+    auto mask_codes = [&](int (&raw)[4], int rb, int ch) {
+        const int row0 = rb * FR_ROWS + wave * FR_RW;
+        const int lane_mask = -(int)(ch * FR_CH + lane < a.red);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            // bytes of the rows that exist (ALIGN 16: rows % 16 == 0, a wavefront's rows exist all or not at all)
+            const int left = a.rows - (row0 + 4 * q);
+            const int row_mask = left >= 4 ? -1 : left <= 0 ? 0 : (1 << (8 * left)) - 1;
+            raw[q] &= lane_mask & row_mask;
+        }
+    };
+
+    float acc[FR_RW][FR_CPL];
+#pragma unroll
+    for (int r = 0; r < FR_RW; ++r)
+#pragma unroll
+        for (int j = 0; j < FR_CPL; ++j) acc[r][j] = 0.f;
+    int raw[4] = {0, 0, 0, 0}, raw_next[4] = {0, 0, 0, 0};
+    // (row block, chunk) of the steps s, s + 1 and s + 2; steps past the end repeat the last one
+    struct Pos { int rb, ch; };
+    auto next_pos = [&](Pos p) {
+        Pos q = p;
+        if (++q.ch == ch_hi) { q.ch = ch_lo; ++q.rb; }
+        return q.rb < rb_hi ? q : p;
+    };
+    Pos p0{rb_lo, ch_lo}, p1 = next_pos(p0), p2 = next_pos(p1);
+    const bool partial = a.sparts > 1;
+    const float sc_out = partial ? 1.0f : a.scale.get();
+    float *dst = partial ? a.partial + (int64_t)sp * a.rows * a.cols : a.out;
+    Stage stA, stB;                                    // tiles of the odd / even steps on their way to LDS (stA: DEEP only)
+    if constexpr (TR) fetch_codes(raw_next, p0.rb, p0.ch);
+    stage_load(stB, p0.rb, p0.ch);
+    if constexpr (DEEP) stage_load(stA, p1.rb, p1.ch);
+    stage_store(stB, 0, p0.rb, p0.ch);
+    __syncthreads();
+
+    // One step: multiply against the tile in buffer s & 1 while tile s + 1 (registers `nxt`) and, DEEP, tile s + 2 (fetched
+    // into `cur`, whose tile is already in LDS) are on their way.
+    auto step = [&](int s, Stage &cur, Stage &nxt) {
+        const int rb = p0.rb, ch = p0.ch;
+        if constexpr (TR) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) raw[q] = raw_next[q];
+            mask_codes(raw, rb, ch);
+            fetch_codes(raw_next, p1.rb, p1.ch);
+        }
+        if constexpr (DEEP) stage_load(cur, p2.rb, p2.ch);
+        else                stage_load(nxt, p1.rb, p1.ch);
+        const float *tile = fr_lds + (s & 1) * FR_TILE + FR_CPL * lane;
+        const int8_t *ctile = code_lds + (s & 1) * FR_CODE_TILE + wave * FR_RW * FR_CH + lane;
+#pragma unroll
+        for (int r = 0; r < FR_RW; ++r) {
+            int code;
+            if constexpr (TR) code = (int)(int8_t)(raw[r >> 2] >> (8 * (r & 3)));
+            else              code = ctile[r * FR_CH];
+            const float kf = (float)code;
+            uint64_t m = __builtin_amdgcn_ballot_w64(code != 0);
+            float av[FR_CPL];
+#pragma unroll
+            for (int j = 0; j < FR_CPL; ++j) av[j] = acc[r][j];
+            while (m) {
+                const int l = __builtin_ctzll(m);
+                m &= ~(1ull << l);
+                const float k = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(kf), l));
+                if constexpr (FR_CPL == 4) {
+                    const f32x4 x = *(const f32x4 *)(tile + l * FR_SLAB);
+                    av[0] = __builtin_fmaf(k, x.x, av[0]); av[1] = __builtin_fmaf(k, x.y, av[1]);
+                    av[2] = __builtin_fmaf(k, x.z, av[2]); av[3] = __builtin_fmaf(k, x.w, av[3]);
+                } else {
+                    const float2 x = *(const float2 *)(tile + l * FR_SLAB);
+                    av[0] = __builtin_fmaf(k, x.x, av[0]); av[1] = __builtin_fmaf(k, x.y, av[1]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < FR_CPL; ++j) acc[r][j] = av[j];
+        }
+        if (ch == ch_hi - 1) {
+            // the row block is complete for this part: store (scaled when these are final values) and start over
+            const int row0 = rb * FR_ROWS + wave * FR_RW, col = col0 + FR_CPL * lane;
+#pragma unroll
+            for (int r = 0; r < FR_RW; ++r) {
+                if (row0 + r < a.rows && col < a.cols) {
+                    float *o = dst + (int64_t)(row0 + r) * a.cols + col;
+                    if constexpr (FR_CPL == 4) *(f32x4 *)o = f32x4{sc_out * acc[r][0], sc_out * acc[r][1], sc_out * acc[r][2], sc_out * acc[r][3]};
+                    else                       *(float2 *)o = float2{sc_out * acc[r][0], sc_out * acc[r][1]};
+                }
+#pragma unroll
+                for (int j = 0; j < FR_CPL; ++j) acc[r][j] = 0.f;
+            }
+            // Stores and loads share one counter and complete out of order: with stores possibly in flight the compiler
+            // would wait for everything at every later wait of the loop.  Drain here, once per row block, instead.
+            __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+        }
+        stage_store(nxt, (s + 1) & 1, p1.rb, p1.ch);   // after the last step: into the buffer nobody reads any more
+        __syncthreads();
+        p0 = p1; p1 = p2; p2 = next_pos(p2);
+    };
+    if constexpr (DEEP) {
+        // both copies of the step run in every trip (the odd last step is peeled): a copy that only some trips run would
+        // again leave the wait counts of the next trip unknown
+        int s = 0;
+        for (; s + 1 < n_steps; s += 2) {
+            step(s, stB, stA);
+            step(s + 1, stA, stB);
+        }
+        if (s < n_steps) step(s, stB, stA);
+    } else {
+        for (int s = 0; s < n_steps; ++s) step(s, stB, stB);      // one set of staging registers, one tile ahead
+    }
+}
+
+// out = scale * (partial[0] + partial[1] + ...), in split order (deterministic)
+__global__ __launch_bounds__(256) void fc_rows_reduce_kernel(const float *partial, float *out, int64_t n4, int n_split, Scale scale,
+                                                             const int *flag, int flag_want)
+{
+    if (flag && flag[0] != flag_want) return;
+    const float sc = scale.get();
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+        f32x4 v = ((const f32x4 *)partial)[i];
+        for (int z = 1; z < n_split; ++z) {
+            const f32x4 w = ((const f32x4 *)partial)[i + (int64_t)z * n4];
+            v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+        }
+        ((f32x4 *)out)[i] = f32x4{sc * v.x, sc * v.y, sc * v.z, sc * v.w};
+    }
 }
 
 // ---- convolution -------------------------------------------------------------------------------
@@ -327,31 +564,144 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
     return hipSuccess;
 }
 
-hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s)
+// ---- host side of the fully connected gather path ---------------------------------------------------------
+namespace {
+
+constexpr int kGatherWorkgroups = 256;                  // one 1024-thread workgroup per CU
+
+// Shapes fc_rows_kernel takes: 16-byte rows of the dense operand, 16-byte stores; dX also reads the codes as dwords.
+bool fc_rows_dx_ok(const LinearArgs &a)
+{
+    return a.in % 4 == 0 && (uintptr_t)a.W % 16 == 0 && (uintptr_t)a.dX % 16 == 0 && a.out % 4 == 0 && (uintptr_t)a.codes % 4 == 0 &&
+           a.B < (1ll << 31) - 256 && a.out < (1ll << 31) - 256 && a.in < (1ll << 31) - 256;
+}
+bool fc_rows_dw_ok(const LinearArgs &a)
+{
+    return a.x_dtype == DBP_F32 && a.in % 4 == 0 && (uintptr_t)a.X % 16 == 0 && (uintptr_t)a.dW % 16 == 0 &&
+           a.B < (1ll << 31) - 256 && a.out < (1ll << 31) - 256 && a.in < (1ll << 31) - 256;
+}
+
+// Parts of one product over the chip: first over the row blocks, then (dX only: `blocks` > 0 counts the blocks of 256
+// reduction indices) over the reduction, every reduction part writing a partial [rows][cols] that the reduction kernel
+// sums.  `room`: bytes available for partials.
+struct FcRowsPlan { int slabs, row_blocks, rparts, rb_per_part, sparts, ch_per_part; size_t partial_bytes; };
+FcRowsPlan fc_rows_plan(int64_t rows, int64_t cols, int64_t n_chunks, bool may_split, size_t room)
+{
+    FcRowsPlan pl;
+    const int block_rows = FR_WAVES * (may_split ? FR_RW_DX : FR_RW_DW), slab = 64 * (may_split ? FR_CPL_DX : FR_CPL_DW);
+    pl.slabs = (int)((cols + slab - 1) / slab);
+    pl.row_blocks = (int)((rows + block_rows - 1) / block_rows);
+    int64_t want = kGatherWorkgroups / pl.slabs;
+    if (want < 1) want = 1;
+    int64_t rparts = want < pl.row_blocks ? want : pl.row_blocks;
+    pl.rb_per_part = (int)((pl.row_blocks + rparts - 1) / rparts);
+    pl.rparts = (pl.row_blocks + pl.rb_per_part - 1) / pl.rb_per_part;
+    int64_t sparts = 1;
+    if (may_split) {
+        const int64_t blocks = n_chunks;
+        sparts = want / pl.rparts;
+        if (sparts > blocks) sparts = blocks;
+        if (sparts < 1) sparts = 1;
+        while (sparts > 1 && (size_t)sparts * rows * cols * sizeof(float) > room) --sparts;
+        const int64_t bps = (blocks + sparts - 1) / sparts;
+        sparts = (blocks + bps - 1) / bps;
+        pl.ch_per_part = (int)bps;
+    } else {
+        pl.ch_per_part = (int)n_chunks;
+    }
+    pl.sparts = (int)sparts;
+    pl.partial_bytes = sparts > 1 ? (size_t)sparts * rows * cols * sizeof(float) : 0;
+    return pl;
+}
+
+}  // namespace
+
+size_t linear_gather_scratch_bytes(int64_t B, int64_t in, int64_t out)
+{
+    return fc_rows_plan(B, in, (out + FR_CH - 1) / FR_CH, true, (size_t)-1).partial_bytes;
+}
+
+bool linear_gather_supported(int64_t B, int64_t in, int64_t out)
+{
+    (void)in;
+    return B <= 65535 && out <= 65535;                    // the one-row-per-workgroup kernels index workgroups by row
+}
+
+hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s, const int *flag, int flag_want)
 {
     const int B = (int)a.B, in = (int)a.in, out = (int)a.out;
+    static bool raised = false;
+    if (!raised) {
+        const void *fns[4] = {reinterpret_cast<const void *>(&fc_rows_kernel<false, FR_RW_DX, FR_CPL_DX, true, 4>),
+                              reinterpret_cast<const void *>(&fc_rows_kernel<true, FR_RW_DW, FR_CPL_DW, false, 16>),
+                              reinterpret_cast<const void *>(&fc_rows_kernel<true, FR_RW_DW, FR_CPL_DW, false, 4>),
+                              reinterpret_cast<const void *>(&fc_rows_kernel<true, FR_RW_DW, FR_CPL_DW, false, 1>)};
+        for (int i = 0; i < 4; ++i) {
+            hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)fr_lds_bytes(i ? FR_CPL_DW : FR_CPL_DX, i ? FR_RW_DW : FR_RW_DX, i != 0));
+            if (e != hipSuccess) return e;
+        }
+        raised = true;
+    }
+    const Scale scale{a.step, a.step_dev};
     const dim3 block(256);
     const unsigned slabs = (unsigned)((in + kSlab - 1) / kSlab);
-    if (a.dX) {
+    if (a.dX && fc_rows_dx_ok(a)) {
+        const int n_chunks = (int)((a.out + FR_CH - 1) / FR_CH);
+        const FcRowsPlan pl = fc_rows_plan(a.B, a.in, n_chunks, true, a.scratch ? a.scratch_bytes : 0);
+        FcRowsArgs k;
+        k.codes = a.codes; k.ldc = a.out; k.D = a.W; k.ldd = a.in; k.out = a.dX; k.partial = (float *)a.scratch;
+        k.rows = B; k.red = out; k.cols = in;
+        k.slabs = pl.slabs; k.row_blocks = pl.row_blocks; k.n_chunks = n_chunks;
+        k.rparts = pl.rparts; k.rb_per_part = pl.rb_per_part; k.sparts = pl.sparts; k.ch_per_part = pl.ch_per_part;
+        k.scale = scale; k.flag = flag; k.flag_want = flag_want;
+        hipLaunchKernelGGL((fc_rows_kernel<false, FR_RW_DX, FR_CPL_DX, true, 4>), dim3((unsigned)(k.slabs * k.rparts * k.sparts)), dim3(FR_THREADS), fr_lds_bytes(FR_CPL_DX, FR_RW_DX, false), s, k);
+        if (pl.sparts > 1) {
+            const int64_t n4 = (int64_t)B * in / 4;
+            const int rb = (int)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048);
+            hipLaunchKernelGGL(fc_rows_reduce_kernel, dim3(rb), dim3(256), 0, s, (const float *)a.scratch, a.dX, n4, pl.sparts, scale, flag, flag_want);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    } else if (a.dX) {
+        if (flag) return hipErrorInvalidValue;            // the fallback kernels take no dispatch flag
+        if (B > 65535) return hipErrorInvalidValue;
         const bool vec = in % 4 == 0 && ((uintptr_t)a.W % 16) == 0;
-        if (vec) hipLaunchKernelGGL(linear_dx_gather_kernel<true>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, Scale{a.step, a.step_dev});
-        else     hipLaunchKernelGGL(linear_dx_gather_kernel<false>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, Scale{a.step, a.step_dev});
+        if (vec) hipLaunchKernelGGL(linear_dx_gather_kernel<true>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, scale);
+        else     hipLaunchKernelGGL(linear_dx_gather_kernel<false>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, scale);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    if (a.dW && fc_rows_dw_ok(a)) {
+        const int n_chunks = (B + FR_CH - 1) / FR_CH;
+        const FcRowsPlan pl = fc_rows_plan(a.out, a.in, n_chunks, false, 0);
+        FcRowsArgs k;
+        k.codes = a.codes; k.ldc = a.out; k.D = (const float *)a.X; k.ldd = a.in; k.out = (float *)a.dW; k.partial = nullptr;
+        k.rows = out; k.red = B; k.cols = in;
+        k.slabs = pl.slabs; k.row_blocks = pl.row_blocks; k.n_chunks = n_chunks;
+        const int code_align = (a.out % 16 == 0 && (uintptr_t)a.codes % 16 == 0) ? 16 : (a.out % 4 == 0 && (uintptr_t)a.codes % 4 == 0) ? 4 : 1;
+        k.rparts = pl.rparts; k.rb_per_part = pl.rb_per_part; k.sparts = 1; k.ch_per_part = n_chunks;
+        k.scale = scale; k.flag = flag; k.flag_want = flag_want;
+        const dim3 grid((unsigned)(k.slabs * k.rparts));
+        if (code_align == 16)     hipLaunchKernelGGL((fc_rows_kernel<true, FR_RW_DW, FR_CPL_DW, false, 16>), grid, dim3(FR_THREADS), fr_lds_bytes(FR_CPL_DW, FR_RW_DW, true), s, k);
+        else if (code_align == 4) hipLaunchKernelGGL((fc_rows_kernel<true, FR_RW_DW, FR_CPL_DW, false, 4>), grid, dim3(FR_THREADS), fr_lds_bytes(FR_CPL_DW, FR_RW_DW, true), s, k);
+        else                      hipLaunchKernelGGL((fc_rows_kernel<true, FR_RW_DW, FR_CPL_DW, false, 1>), grid, dim3(FR_THREADS), fr_lds_bytes(FR_CPL_DW, FR_RW_DW, true), s, k);
+        return hipGetLastError();
+    }
     if (a.dW) {
+        if (flag) return hipErrorInvalidValue;
+        if (out > 65535) return hipErrorInvalidValue;
         if (a.x_dtype == DBP_F32) {
             const bool vec = in % 4 == 0 && ((uintptr_t)a.X % 16) == 0;
             if (vec) hipLaunchKernelGGL((linear_dw_gather_kernel<float, float, true>), dim3(slabs, out), block, 0, s,
-                                        a.codes, (const float *)a.X, (float *)a.dW, B, in, out, Scale{a.step, a.step_dev});
+                                        a.codes, (const float *)a.X, (float *)a.dW, B, in, out, scale);
             else     hipLaunchKernelGGL((linear_dw_gather_kernel<float, float, false>), dim3(slabs, out), block, 0, s,
-                                        a.codes, (const float *)a.X, (float *)a.dW, B, in, out, Scale{a.step, a.step_dev});
+                                        a.codes, (const float *)a.X, (float *)a.dW, B, in, out, scale);
         } else {
             const bool vec = in % 4 == 0 && ((uintptr_t)a.X % 4) == 0;
             if (vec) hipLaunchKernelGGL((linear_dw_gather_kernel<int8_t, int32_t, true>), dim3(slabs, out), block, 0, s,
-                                        a.codes, (const int8_t *)a.X, (int32_t *)a.dW, B, in, out, Scale{a.step, a.step_dev});
+                                        a.codes, (const int8_t *)a.X, (int32_t *)a.dW, B, in, out, scale);
             else     hipLaunchKernelGGL((linear_dw_gather_kernel<int8_t, int32_t, false>), dim3(slabs, out), block, 0, s,
-                                        a.codes, (const int8_t *)a.X, (int32_t *)a.dW, B, in, out, Scale{a.step, a.step_dev});
+                                        a.codes, (const int8_t *)a.X, (int32_t *)a.dW, B, in, out, scale);
         }
         return hipGetLastError();
     }

@@ -224,10 +224,11 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
         if (__builtin_amdgcn_ballot_w64(odd)) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const bool nan = x[j] != x[j];
-                const bool inf = fabsf(x[j]) == __builtin_inff();
+                // a NaN t (NaN input, or +-Inf input times the 1/Delta = 0 of a degenerate layer) gives code 0
+                const bool nan = kf[j] != kf[j];
+                const bool bad = (x[j] != x[j]) | (fabsf(x[j]) == __builtin_inff());
                 if (nan) { k[j] = 0; kc[j] = 0.f; }
-                ws.nonfinite += __builtin_popcountll(__builtin_amdgcn_ballot_w64(nan | inf));
+                ws.nonfinite += __builtin_popcountll(__builtin_amdgcn_ballot_w64(bad));
                 ws.sat += __builtin_popcountll(__builtin_amdgcn_ballot_w64(!nan && fabsf(kf[j]) > 127.0f));
             }
         }

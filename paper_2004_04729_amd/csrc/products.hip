@@ -533,7 +533,9 @@ size_t linear_scratch_bytes(int64_t B, int64_t in, int64_t out)
             if (fast2 > fast) fast = fast2;
         }
     }
-    return (generic > fast ? generic : fast) + 256;
+    const size_t gather = align_up(linear_gather_scratch_bytes(B, in, out), 256);      // split partials of the gather dX kernel
+    const size_t mfma = generic > fast ? generic : fast;
+    return (mfma > gather ? mfma : gather) + 256;
 }
 
 // dW of a 1x1, stride-1, unpadded convolution: dW[k][c] = sum_n sum_p code[n][k][p] X[n][c][p] is the batched,
@@ -780,7 +782,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
         // workgroup per CU); small ones (less than half such a tile of rows): the 128x128 kernel.
         const bool big = (!dx_fast || B > FC2_TM / 2) && (!dw_fast || out > FC2_TM / 2) &&
                          (!dx_fast || out >= 32) && (!dw_fast || (B >= 32 && out >= 16)) &&         // a full window of 32 reduction indices; 16-row runs
-                         B * in < (1ll << 30) && out * in < (1ll << 30) && B * out < (1ll << 30);                // 32-bit lane offsets
+                         (int64_t)B * in < (1ll << 30) && (int64_t)out * in < (1ll << 30) && (int64_t)B * out < (1ll << 30);                // 32-bit lane offsets
         FcPlan pdx, pdw;
         bool use_fc2 = (dx_fast || dw_fast) && big;
         if (use_fc2) {

@@ -92,6 +92,8 @@ def test_linear_argument_errors():
     assert call(path=9) == UNSUPPORTED
     assert call(ws=None) == WORKSPACE and call(wsb=100) == WORKSPACE and call(ws=FAKE + 4) == WORKSPACE
     assert call(xd=1, B=140000) == OVERFLOW
+    # the gather kernels that serve odd shapes number their workgroups by row: rejected on the host, not at the launch
+    assert call(path=2, B=70000) == UNSUPPORTED and call(path=2, o=70000) == UNSUPPORTED
     g = dbp.lib().dense_linear_backward
     assert g(None, FAKE, FAKE, 0, 8, 8, 8, FAKE, FAKE, FAKE, big, None) == NULL
     assert g(FAKE, FAKE, FAKE, 1, 8, 8, 8, FAKE, FAKE, FAKE, big, None) == UNSUPPORTED

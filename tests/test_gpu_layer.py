@@ -215,6 +215,14 @@ def test_linear_layer_backward_8bit_and_degenerate():
     assert res["pair"].tolist() == [0.0, 0.0]
     assert not res["codes"].any() and not res["dX"].any() and not res["dW"].any() and not res["db"].any()
     assert res["stats"].nnz == 0
+    # a gradient with +-Inf or NaN in it has no finite deviation: the same degenerate layer, every code 0 (t = Inf * 0 + u
+    # is NaN, and a NaN t quantises to 0 as in the oracle's quantiser), the non-finite inputs counted
+    bad = da.copy()
+    bad[3, 7], bad[50, 100], bad[95, 259] = np.inf, -np.inf, np.nan
+    res = _linear_layer(LinearProblem("layer_inf", bad, W, np.abs(p.X), 1.0), 4.0, None)
+    assert res["pair"].tolist() == [0.0, 0.0]
+    assert not res["codes"].any() and not res["dX"].any() and not res["dW"].any() and not res["db"].any()
+    assert (res["stats"].nnz, res["stats"].n_saturated, res["stats"].n_nonfinite, res["stats"].max_abs_code) == (0, 0, 3, 0)
 
 
 @pytest.mark.parametrize("case", [(2, 5, 9, 7, 6, 3, 3, 1), (3, 16, 14, 14, 24, 3, 3, 1), (2, 33, 14, 14, 20, 1, 1, 0),

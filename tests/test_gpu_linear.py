@@ -137,25 +137,11 @@ def test_fc_large_layer_kernel_edges(B, in_, out):
     _check_fp32(p, run_linear(p, want_dx=False))
 
 
-def test_fc_many_items_per_workgroup_sampled():
-    # 256 x 8192 x 8192: 2048 dW tiles and 64 split dX tiles, about ten work items per workgroup; the oracle
-    # computes 3000 sampled outputs of each product one by one
-    from gpu_util import run_linear, check_products
-    from oracle import oracle as O
-    B, in_, out = 256, 8192, 8192
-    p = _problem(B, in_, out, seed=99, c=8.0)
-    res = run_linear(p)
-    k_ref, _ = O.nsd(p.delta, p.step, p.seed)
-    assert np.array_equal(res["codes"], k_ref)
-    rng = np.random.default_rng(5)
-    ix = rng.integers(0, B * in_, size=3000)
-    r = O.linear_dx_at(p.W, ix, B=B, codes=k_ref, step=p.step)
-    a = O.linear_dx_at(np.abs(p.W), ix, B=B, codes=np.abs(k_ref), step=p.step)
-    check_products(res["dX"].ravel()[ix], r, a, "dX (sampled)")
-    iw = rng.integers(0, out * in_, size=3000)
-    r = O.linear_dw_at(p.X, iw, out=out, codes=k_ref, step=p.step)
-    a = O.linear_dw_at(np.abs(p.X), iw, out=out, codes=np.abs(k_ref), step=p.step)
-    check_products(res["dW"].ravel()[iw], r, a, "dW (sampled)")
+def test_fc_many_items_per_workgroup():
+    # 256 x 8192 x 8192: 2048 dW tiles and 64 split dX tiles, about ten work items per workgroup; every element
+    from gpu_util import run_linear
+    p = _problem(256, 8192, 8192, seed=99, c=8.0)
+    _check_fp32(p, run_linear(p))
 
 
 def test_fc_two_groups_of_unequal_size():
