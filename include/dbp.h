@@ -31,9 +31,9 @@
  *   - `workspace` is device scratch of at least the size the matching *_workspace_bytes
  *     function returns, 256-byte aligned.  Its contents need not be initialised and are
  *     undefined afterwards, except that the dithered_* calls with path == DBP_PATH_GATHER
- *     leave the tile-sparse format (see below) at the start of the workspace.  The other
- *     paths do not read that format and do not spend bandwidth writing it; nsd_quantize
- *     produces it on request.
+ *     leave the tile-sparse format (see below) at the start of the workspace.  The matrix-core
+ *     kernels and the fully connected gather kernels read the code plane, not that format, and no
+ *     bandwidth is spent writing it for them; nsd_quantize produces it on request.
  *   - The dither of element j of delta is a pure function of (seed, idx_base + j), where j is
  *     the row-major flat index; a shard of a larger tensor passes its offset as idx_base and
  *     obtains bit-identical codes.
@@ -65,14 +65,20 @@ typedef enum {
 
 typedef enum { DBP_F32 = 0, DBP_I8 = 1 } dbp_dtype;
 
-/* Which kernels compute the two products.  AUTO picks among the matrix-core kernels by problem size and,
- * in this build, never takes GATHER: measured on MI355X the gather kernels only win above about 96 % zeros,
- * so they run when asked for. */
+/* Which kernels compute the two products.
+ *   MFMA    the codes as exact bf16 (or int8) operands of matrix-core tiles: dense work, the same at any sparsity (only the
+ *           generic kernel that serves odd shapes skips all-zero code fragments).
+ *   GATHER  kernels that walk the nonzero codes: work in proportion to the nonzeros (Sec. "Computational complexity",
+ *           O(p_nz m k n)) plus the fixed cost of streaming the dense operand and writing the outputs.
+ *   AUTO    matrix cores, unless the shape is one where the gather kernels can win by a wide margin at high sparsity; then
+ *           BOTH families are launched behind a gate and the device decides: the kernel that sums the quantiser's statistics
+ *           compares the nonzero count with a threshold (a linear cost model with constants measured on MI355X) and writes a
+ *           flag; the kernels of the family the flag does not name return at once.  No host round trip, no allocation.
+ *           Results are those of whichever family ran (both meet the same tolerance; each is deterministic). */
 typedef enum {
     DBP_PATH_AUTO = 0,
-    DBP_PATH_MFMA = 1,         /* codes as exact bf16 (or int8) operands of matrix-core tiles,
-                                  all-zero code fragments skipped                              */
-    DBP_PATH_GATHER = 2        /* walk the nonzero entries of the tile-sparse format           */
+    DBP_PATH_MFMA = 1,
+    DBP_PATH_GATHER = 2
 } dbp_path;
 
 /* Per-call statistics, device resident (the paper's reported quantities: sparsity and the

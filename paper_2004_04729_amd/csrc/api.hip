@@ -130,10 +130,72 @@ LayerCarve layer_carve(size_t backward_total, int64_t n, int64_t bias_len)
     return c;
 }
 
+// ---- density dispatch of DBP_PATH_AUTO ----------------------------------------------------------------------
+// The matrix-core kernels do the dense work whatever the codes are; the gather kernels do work in proportion to the
+// nonzero codes plus a fixed cost (streaming the dense operand, writing the outputs).  Only the device knows the nonzero
+// count when the products are launched, so where the gather family can win at all, BOTH families are launched behind a
+// gate: the kernel that sums the quantiser's statistics also writes a flag (1 when fewer than `gather_below` codes are
+// nonzero) and each family's kernels return at once unless the flag names them.  No host round trip, no allocation; the
+// losing family costs its empty launches, which is why shapes where the gather kernels' fixed cost alone is close to the
+// matrix-core time are not dispatched at all.  The estimates below are linear models with constants measured on MI355X
+// (microseconds; flop per microsecond; bytes per microsecond).
+struct AutoPlan { bool dual; uint64_t gather_below; };
+
+AutoPlan linear_auto_plan(const LinearArgs &call, bool launchable)
+{
+    AutoPlan ap{false, 0};
+    if (!launchable) return ap;
+    LinearArgs probe = call;
+    if (!linear_gather_gated_ok(probe)) return ap;
+    int ungated = 0;
+    probe.plan_only = &ungated;
+    (void)launch_linear_mfma(probe, nullptr);                    // plan only: launches nothing
+    if (ungated) return ap;
+    const double B = (double)call.B, in = (double)call.in, out = (double)call.out;
+    const int products = (call.dX ? 1 : 0) + (call.dW ? 1 : 0);
+    const double mfma_us = products * 2.0 * B * in * out * 3.0 / 0.85e9;             // three bf16 planes at 0.85 PFLOP/s
+    const double partial = (double)linear_gather_scratch_bytes(call.B, call.in, call.out);
+    double fixed_us = 10.0;
+    if (call.dX) fixed_us += (out * in * 4.0 + 2.0 * partial + B * in * 4.0) / 3.6e6;   // W streamed once, partial sums written and read
+    if (call.dW) fixed_us += (out * in * 4.0 + B * in * 4.0) / 3.6e6;                   // dW written once
+    if (fixed_us > 0.7 * mfma_us) return ap;
+    const double per_nnz_us = products * 2.0 * in / 24e6;                            // 24 TFLOP/s of multiply-adds on nonzeros
+    const double thr = (mfma_us - fixed_us) / per_nnz_us;
+    ap.dual = true;
+    ap.gather_below = thr >= B * out ? (uint64_t)(B * out) + 1 : (uint64_t)thr;
+    return ap;
+}
+
+AutoPlan conv_auto_plan(const ConvArgs &call, int64_t P, int64_t Q)
+{
+    AutoPlan ap{false, 0};
+    if (!conv_gather_supported(call.N, call.C, call.H, call.Wd, call.K, call.R, call.S, P, Q, call.dX != nullptr)) return ap;
+    ConvArgs probe = call;
+    int ungated = 0;
+    StatsJob none{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    probe.plan_only = &ungated; probe.stats_job = none;
+    (void)launch_conv_mfma(probe, nullptr);                      // plan only: launches nothing
+    if (ungated) return ap;
+    const double crs = (double)(call.C * call.R * call.S), n_codes = (double)(call.N * call.K * P * Q);
+    const double flops = 2.0 * n_codes * crs;                                        // one dense product
+    double mfma_us = 0.0;
+    if (call.dX) mfma_us += flops * 3.0 / 0.9e9;
+    if (call.dW) mfma_us += call.x_dtype == DBP_I8 ? flops / 1.4e9 : flops * 3.0 / 0.6e9;
+    const double x_elems = (double)(call.N * call.C * call.H * call.Wd);
+    const double fixed_us = 15.0 + (call.dX ? x_elems * 4.0 : 0.0) / 2.0e6 + (call.dW ? x_elems * (call.x_dtype == DBP_I8 ? 1.0 : 4.0) : 0.0) / 2.0e6;
+    if (fixed_us > 0.5 * mfma_us) return ap;
+    const int products = (call.dX ? 1 : 0) + (call.dW ? 1 : 0);
+    const double per_nnz_us = products * 2.0 * crs / 1.4e6;                          // 1.4 TFLOP/s on nonzeros (LDS read-modify-write bound)
+    const double thr = (mfma_us - fixed_us) / per_nnz_us;
+    ap.dual = true;
+    ap.gather_below = thr >= n_codes ? (uint64_t)n_codes + 1 : (uint64_t)thr;
+    return ap;
+}
+
 dbp_status linear_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
                            dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX, void *dW,
                            void *workspace, size_t workspace_bytes, dbp_path path, void *stream, StatsJob job,
-                           const float *step_dev = nullptr)
+                           const float *step_dev = nullptr, Gate gate = Gate{})
 {
     if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
     dbp_status st = check_linear_dims(B, in, out);
@@ -145,7 +207,7 @@ dbp_status linear_products(const int8_t *codes, const void *format, float step, 
     if (path == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
     LinearArgs a;
     a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
-    a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.stats_job = job;
+    a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.stats_job = job; a.gate = gate;
     if (path == DBP_PATH_GATHER) {
         if (!format) return DBP_ERR_NULL;
         if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
@@ -170,7 +232,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
                                dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
                                int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW,
                                void *workspace, size_t workspace_bytes, dbp_path path, void *stream, const float *step_dev = nullptr,
-                               StatsJob job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr})
+                               StatsJob job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}, Gate gate = Gate{})
 {
     if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
     int64_t P, Q;
@@ -193,7 +255,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
         g.codes = codes; g.dense = nullptr; g.step = step; g.step_dev = step_dev; g.W = W; g.W8 = nullptr; g.X = X; g.x_dtype = x_dtype;
         g.N = N; g.C = C; g.H = H; g.Wd = Wd; g.K = K; g.R = R; g.S = S; g.pad = pad; g.stride = stride;
         g.dX = dX; g.dW = dW; g.scratch = nullptr; g.scratch_bytes = 0;
-        g.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; g.pending = nullptr;
+        g.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; g.pending = nullptr; g.gate = gate;
         if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
         return launch_conv_gather(g, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     }
@@ -203,10 +265,69 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    a.stats_job = job; a.pending = nullptr;
+    a.stats_job = job; a.pending = nullptr; a.gate = gate;
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
+// The products of a dithered_* call after its quantiser: one family, or (DBP_PATH_AUTO on a shape where the gather
+// kernels can win) both behind the density gate.  `ws` is the call's workspace (format region first), `job` the
+// quantiser's pending statistics sum.
+dbp_status linear_products_dispatch(const AutoPlan &ap, const int8_t *k, char *ws, const Carve &c, size_t scratch_bytes, float step,
+                                    const float *W, const void *X, dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX,
+                                    void *dW, dbp_path path, void *stream, StatsJob job, const float *step_dev)
+{
+    if (!ap.dual)
+        return linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset, scratch_bytes, path, stream, job, step_dev);
+    int *flag = (int *)(ws + c.fmt.scratch_offset + kNsdFlagOffset);
+    job.flag = flag; job.gather_below = ap.gather_below;
+    if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
+    const StatsJob none{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    dbp_status st = linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset, scratch_bytes, DBP_PATH_MFMA,
+                                    stream, none, step_dev, Gate{flag, 0});
+    if (st != DBP_OK) return st;
+    return linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset, scratch_bytes, DBP_PATH_GATHER,
+                           stream, none, step_dev, Gate{flag, 1});
+}
+
+dbp_status conv2d_products_dispatch(const AutoPlan &ap, const int8_t *k, char *ws, const Carve &c, size_t scratch_bytes, float step,
+                                    const float *W, const void *X, dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd,
+                                    int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW, dbp_path path,
+                                    void *stream, StatsJob job, const float *step_dev)
+{
+    if (!ap.dual)
+        return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset, scratch_bytes,
+                               path, stream, step_dev, job);
+    int *flag = (int *)(ws + c.fmt.scratch_offset + kNsdFlagOffset);
+    job.flag = flag; job.gather_below = ap.gather_below;
+    if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
+    const StatsJob none{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    dbp_status st = conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset,
+                                    scratch_bytes, DBP_PATH_MFMA, stream, step_dev, none, Gate{flag, 0});
+    if (st != DBP_OK) return st;
+    return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset,
+                           scratch_bytes, DBP_PATH_GATHER, stream, step_dev, none, Gate{flag, 1});
+}
+
+LinearArgs linear_call(const float *W, const void *X, dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX, void *dW,
+                       const int8_t *codes, char *scratch, size_t scratch_bytes)
+{
+    LinearArgs a;
+    a.codes = codes; a.dense = nullptr; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
+    a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.scratch = scratch; a.scratch_bytes = scratch_bytes;
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    return a;
+}
+
+ConvArgs conv_call(const float *W, const void *X, dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
+                   int64_t S, int64_t stride, int64_t pad, float *dX, void *dW, const int8_t *codes, char *scratch, size_t scratch_bytes)
+{
+    ConvArgs a;
+    a.codes = codes; a.dense = nullptr; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
+    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
+    a.dX = dX; a.dW = dW; a.scratch = scratch; a.scratch_bytes = scratch_bytes;
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; a.pending = nullptr;
+    return a;
+}
 
 }  // namespace
 
@@ -289,13 +410,18 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    // only the gather kernels read the tile-sparse arrays; the statistics are summed by the products' launch
+    // only the gather kernels that serve odd shapes read the tile-sparse arrays; the statistics are summed by the
+    // products' launch, or, with both families behind the density gate, by the kernel that writes the gate's flag
+    const AutoPlan ap = path == DBP_PATH_AUTO
+        ? linear_auto_plan(linear_call(W, X, x_dtype, B, in, out, dX, dW, k, ws + c.scratch_offset, workspace_bytes - c.scratch_offset), true)
+        : AutoPlan{false, 0};
+    dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
     StatsJob job;
-    st = run_nsd(delta, B, out, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream,
+    st = run_nsd(delta, B, out, step, seed, idx_base, k, ws, &c.fmt, st_dev, (hipStream_t)stream,
                  path == DBP_PATH_GATHER, &job);
     if (st != DBP_OK) return st;
-    return linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset,
-                           workspace_bytes - c.scratch_offset, path, stream, job);
+    return linear_products_dispatch(ap, k, ws, c, workspace_bytes - c.scratch_offset, step, W, X, x_dtype, B, in, out, dX, dW, path,
+                                    stream, job, nullptr);
 }
 
 dbp_status dbp_conv2d_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,
@@ -327,11 +453,17 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
+    const AutoPlan ap = path == DBP_PATH_AUTO
+        ? conv_auto_plan(conv_call(W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, k, ws + c.scratch_offset,
+                                   workspace_bytes - c.scratch_offset), P, Q)
+        : AutoPlan{false, 0};
+    dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
     StatsJob job;
-    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, path == DBP_PATH_GATHER, &job);
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, st_dev, (hipStream_t)stream,
+                 path == DBP_PATH_GATHER || ap.dual, &job);
     if (st != DBP_OK) return st;
-    return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
-                           ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path, stream, nullptr, job);
+    return conv2d_products_dispatch(ap, k, ws, c, workspace_bytes - c.scratch_offset, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride,
+                                    pad, dX, dW, path, stream, job, nullptr);
 }
 
 dbp_status dense_linear_backward(const void *delta, const float *W, const void *X, dbp_dtype x_dtype,
@@ -524,11 +656,14 @@ dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act
     ex.bias_mode = DBP_BIAS_PER_COLUMN; ex.bias_len = out;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     StatsJob job;
-    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex, true, &tree);
+    const AutoPlan ap = path == DBP_PATH_AUTO && (dX || dW)
+        ? linear_auto_plan(linear_call(W, X, x_dtype, B, in, out, dX, dW, k, ws + c.scratch_offset, c.total - c.scratch_offset), true)
+        : AutoPlan{false, 0};
+    dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
+    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, st_dev, hs, path == DBP_PATH_GATHER, &job, &ex, true, &tree);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
-    return linear_products(k, ws, 1.0f, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset,
-                           c.total - c.scratch_offset, path, stream, job, pair);
+    return linear_products_dispatch(ap, k, ws, c, c.total - c.scratch_offset, 1.0f, W, X, x_dtype, B, in, out, dX, dW, path, stream, job, pair);
 }
 
 dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act, const float *W, const void *X,
@@ -562,11 +697,17 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     ex.bias_mode = DBP_BIAS_PER_ROW_GROUP; ex.bias_len = K;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     StatsJob job;
-    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, stats, hs, path == DBP_PATH_GATHER, &job, &ex, true, &tree);
+    const AutoPlan ap = path == DBP_PATH_AUTO && (dX || dW)
+        ? conv_auto_plan(conv_call(W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, k, ws + c.scratch_offset,
+                                   c.total - c.scratch_offset), P, Q)
+        : AutoPlan{false, 0};
+    dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
+    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, st_dev, hs, path == DBP_PATH_GATHER || ap.dual, &job, &ex,
+                 true, &tree);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
-    return conv2d_products(k, ws, 1.0f, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
-                           ws + c.scratch_offset, c.total - c.scratch_offset, path, stream, pair, job);
+    return conv2d_products_dispatch(ap, k, ws, c, c.total - c.scratch_offset, 1.0f, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW,
+                                    path, stream, job, pair);
 }
 
 }  // extern "C"

@@ -20,9 +20,17 @@ struct Scale {
     __device__ __forceinline__ float get() const { return dev ? dev[0] : host; }
 };
 
+// Device-side dispatch between the kernel families (matrix cores / gather): a gated kernel runs only when the flag an
+// earlier kernel of the stream wrote equals `want`; flag == nullptr: always.
+struct Gate {
+    const int *flag = nullptr; int want = 0;
+    __device__ __forceinline__ bool closed() const { return flag && flag[0] != want; }
+};
+
 constexpr int kWave = 64;
 constexpr int kNsdMaxBlocks = 16384;                                 // measured best on 2^28 elements (8 resident per CU)
-constexpr size_t kNsdScratchBytes = (size_t)kNsdMaxBlocks * 16;      // one 16-byte statistics record per workgroup
+constexpr size_t kNsdFlagOffset = (size_t)kNsdMaxBlocks * 16;        // the density flag follows the statistics records
+constexpr size_t kNsdScratchBytes = kNsdFlagOffset + 256;            // one 16-byte statistics record per workgroup, then the flag
 
 // Dither keys derived from the 64-bit seed on the host (constants: golden ratio, frac sqrt2, frac sqrt3).
 struct DitherKeys { uint32_t k0, k1; };
@@ -62,6 +70,8 @@ struct StatsJob {
     const u32x4 *partials; int n; dbp_stats *out;                  // statistics records -> dbp_stats (n == 0: none)
     const int64_t *bias_sums; int64_t bias_len; float *bias_grad;   // code sums -> fp32 bias gradient (bias_len == 0: none)
     float step; const float *step_dev;
+    // density dispatch: flag[0] = 1 (gather kernels) when fewer than gather_below codes are nonzero, else 0 (matrix cores)
+    int *flag = nullptr; uint64_t gather_below = 0;
 };
 // Launches the quantiser.  With `defer` non-null and statistics kept in records, the final sum is not
 // launched: *defer describes it, and the caller either folds it into a later kernel of the same stream
@@ -102,6 +112,8 @@ struct LinearArgs {
     void         *scratch;     // split-K partials
     size_t        scratch_bytes;
     StatsJob      stats_job;   // statistics sum still to be done on this stream (n == 0: none)
+    Gate          gate;        // device-side dispatch (fast kernels only)
+    int          *plan_only = nullptr;   // non-null: launch nothing, set *plan_only = 1 if some product would run on an ungated kernel
 };
 struct ConvArgs {
     const int8_t *codes;
@@ -119,6 +131,8 @@ struct ConvArgs {
     size_t        scratch_bytes;
     StatsJob      stats_job;   // statistics sum / bias gradient still to be done on this stream (none: n == 0 and bias_len == 0)
     StatsJob     *pending;     // set by launch_conv_mfma: what of stats_job no kernel has taken along yet
+    Gate          gate;        // device-side dispatch (the large kernels; the small preparation kernels run regardless)
+    int          *plan_only = nullptr;   // non-null: launch nothing, set *plan_only = 1 if a large kernel would run ungated
 };
 size_t     linear_scratch_bytes(int64_t B, int64_t in, int64_t out);
 size_t     conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride = 1);
@@ -128,12 +142,14 @@ hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s);
 // ---- gather path (gather.hip) ------------------------------------------------------------------
 struct FormatView { const uint64_t *bitmap; const uint16_t *tile_nnz; const uint16_t *entries; int64_t tiles_per_row; };
 // flag != nullptr: device-side dispatch, the kernels run only when *flag == flag_want (fc_rows_kernel shapes only).
-hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s, const int *flag = nullptr, int flag_want = 0);
+hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s);   // a.gate: fc_rows_kernel shapes only
+bool       linear_gather_gated_ok(const LinearArgs &a);     // every requested product runs on the gated fc_rows_kernel
 size_t     linear_gather_scratch_bytes(int64_t B, int64_t in, int64_t out);    // split partials of the gather dX kernel
 bool       linear_gather_supported(int64_t B, int64_t in, int64_t out);
 // Convolution gather kernels: any stride; kernels of at most 64 taps, output planes below 4096 x 4096, and for dX an input
 // plane of at most about 37 KiB (four of them accumulate in LDS).
 bool       conv_gather_supported(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t P, int64_t Q, bool want_dx);
-hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_t s);
+hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_t s);     // honours a.gate
+
 
 }  // namespace dbp

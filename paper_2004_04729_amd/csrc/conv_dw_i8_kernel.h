@@ -39,12 +39,14 @@ struct ConvDwI8Args {
     int n_steps;               // RU*CPR/2 matrix-core steps of 32 pixels per unit
     int xpairs, cpairs;        // (row, cell) pairs a unit loads per channel: RU*DC, (RU+2)*DC
     int lds_cells;
+    Gate gate;
 };
 
 __global__ __launch_bounds__(512, 1) void conv_dw_i8_kernel(ConvDwI8Args a)
 {
     constexpr int TK = 64, TC = 64, RS = 9;
     extern __shared__ uint4 cdw_lds[];
+    if (a.gate.closed()) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool stager = wave >= 4;
     const int tid = threadIdx.x & 255;

@@ -49,6 +49,7 @@ struct ConvDwArgs {
     int row2x, row2c;          // Wd, Q even: at least its halves never do
     int lds_cells;             // 16-byte cells of LDS in use
     Scale scale;
+    Gate gate;
 };
 
 template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
@@ -74,6 +75,7 @@ __device__ __forceinline__ u32x4 cdw_funnel(const uint4 &lo, const uint4 &hi)
 template <int MODE, int R, int S, int PAD, int MB, bool ROW4>
 __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
 {
+    if (a.gate.closed()) return;
     using TR = CdwTraits<MODE>;
     using XT = typename TR::XT;
     using XRaw = typename TR::XRaw;
@@ -543,6 +545,7 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
 template <int MODE, int R, int S, int MB>
 __global__ __launch_bounds__(256) void conv_dw_reduce_kernel(ConvDwArgs a)
 {
+    if (a.gate.closed()) return;
     using AccT = typename CdwTraits<MODE>::AccT;
     typedef AccT Acc4 __attribute__((ext_vector_type(4)));
     constexpr int RS = R * S, NG = RS * MB * 4;

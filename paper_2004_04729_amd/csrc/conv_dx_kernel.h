@@ -48,6 +48,7 @@ struct ConvDxArgs {
     int tiles;                // pixel tiles per image
     int prow, pw, patch_cells;// patch rows (maximum over tiles), patch width Wd+S-1 ... cells per k-group
     Scale scale;
+    Gate gate;
 };
 
 // fp32 weights [K][C][R][S] -> bf16 planes in fragment order (plane 0 = lo, 1 = mid, 2 = hi), zero padded.
@@ -397,6 +398,7 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
 template <int NB, int MODE>
 __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 {
+    if (a.gate.closed()) return;
     conv_dx_body<NB, MODE, false>(a, (int)blockIdx.x);
 }
 
@@ -407,6 +409,7 @@ struct ConvDxMulti { ConvDxArgs cls[CDX_MAX_CLASSES]; int first[CDX_MAX_CLASSES 
 template <int NB, int MODE>
 __global__ __launch_bounds__(256, 2) void conv_dx_multi_kernel(ConvDxMulti m)
 {
+    if (m.cls[0].gate.closed()) return;
     int ci = 0;
     for (int i = 1; i < m.n; ++i) if ((int)blockIdx.x >= m.first[i]) ci = i;
     const ConvDxArgs a = m.cls[ci];

@@ -42,6 +42,7 @@ template <bool NT>
 __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
 {
     extern __shared__ uint4 fc2_lds[];
+    if (a.gate.closed()) return;
     Fc2IStage *stages = (Fc2IStage *)fc2_lds;
     Fc2Item *table = (Fc2Item *)(stages + 2);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -336,6 +337,7 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
 // Split-K sums of the int8 kernel (integers: exact in any order; the order is fixed all the same).
 __global__ __launch_bounds__(256) void fc2_i8_reduce_kernel(FcPairArgs a, int tiles0)
 {
+    if (a.gate.closed()) return;
     typedef int32_t i32v4 __attribute__((ext_vector_type(4)));
     const int which = (int)(blockIdx.x >> 5) < tiles0 ? 0 : 1;
     const FcProblem &p = a.prob[which];

@@ -196,6 +196,7 @@ template <bool NT>
 __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 {
     extern __shared__ uint4 fc2_lds[];
+    if (a.gate.closed()) return;
     Fc2Stage *stages = (Fc2Stage *)fc2_lds;
     Fc2Item *table = (Fc2Item *)(stages + 2);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -499,6 +500,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 // columns per thread) over the splits, in split order, and writes the output with the item's own mapping.
 __global__ __launch_bounds__(256) void fc2_reduce_kernel(FcPairArgs a, int tiles0)
 {
+    if (a.gate.closed()) return;
     const int which = (int)(blockIdx.x >> 5) < tiles0 ? 0 : 1;
     const FcProblem &p = a.prob[which];
     const int tile = (int)(blockIdx.x >> 5) - (which ? tiles0 : 0), slot = blockIdx.x & 31;

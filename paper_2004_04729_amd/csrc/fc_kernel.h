@@ -44,7 +44,7 @@ struct FcProblem {
 };
 // gx > 0 (kernels of fc2_kernel.h / fc2_i8_kernel.h): the first gx workgroups of the launch take the items of problem 0, the
 // others those of problem 1, each group dealing its items round robin; gx == 0: one list for both, dealt in a serpentine.
-struct FcPairArgs { FcProblem prob[2]; StatsJob stats; int gx = 0; };
+struct FcPairArgs { FcProblem prob[2]; StatsJob stats; int gx = 0; Gate gate; };
 
 __device__ __forceinline__ uint32_t bf16x2_from_codes(int a, int b)
 {
@@ -254,6 +254,7 @@ __device__ __forceinline__ void fc_sum_stats(const StatsJob &j, uint64_t *lds)
 // long as both have items left, so that neighbouring workgroups work on different products.
 __global__ __launch_bounds__(256, 3) void fc_pair_kernel(FcPairArgs a)
 {
+    if (a.gate.closed()) return;
     __shared__ FcSmem sm;
     // the last workgroup has the fewest items: it also finishes the quantiser's statistics
     if (a.stats.n > 0 && blockIdx.x == gridDim.x - 1) fc_sum_stats(a.stats, (uint64_t *)&sm);
@@ -276,6 +277,7 @@ __global__ __launch_bounds__(256, 3) void fc_pair_kernel(FcPairArgs a)
 // tiles and hundreds of splits (a convolution's dW lowered to this kernel) one sum per thread was latency bound.
 __global__ __launch_bounds__(256) void fc_reduce_kernel(FcPairArgs a, int tiles0)
 {
+    if (a.gate.closed()) return;
     const int which = (int)(blockIdx.x >> 5) < tiles0 ? 0 : 1;
     const FcProblem &p = a.prob[which];
     const int tile = (int)(blockIdx.x >> 5) - (which ? tiles0 : 0), slot = blockIdx.x & 31;

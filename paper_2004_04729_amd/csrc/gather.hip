@@ -163,7 +163,7 @@ struct FcRowsArgs {
     int rparts, rb_per_part;                  // parts over the row blocks
     int sparts, ch_per_part;                  // parts over the reduction (partial sums when sparts > 1)
     Scale scale;
-    const int *flag; int flag_want;           // device-side dispatch: run only when *flag == flag_want (flag may be null)
+    Gate gate;
 };
 
 template <bool TR, int FR_RW, int FR_CPL, bool DEEP, int ALIGN>
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(FR_THREADS) void fc_rows_kernel(FcRowsArgs a)
     constexpr int FR_STAGE = FR_TILE / 4 / FR_THREADS;            // 16-byte pieces per thread and tile
     constexpr int FR_SROWS = FR_THREADS * 4 / FR_SLAB;            // tile rows one pass of the workgroup's 16-byte loads covers
     extern __shared__ __attribute__((aligned(16))) float fr_lds[];
-    if (a.flag && a.flag[0] != a.flag_want) return;
+    if (a.gate.closed()) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int slab = (int)blockIdx.x % a.slabs, part = (int)blockIdx.x / a.slabs;
@@ -349,10 +349,9 @@ __global__ __launch_bounds__(FR_THREADS) void fc_rows_kernel(FcRowsArgs a)
 }
 
 // out = scale * (partial[0] + partial[1] + ...), in split order (deterministic)
-__global__ __launch_bounds__(256) void fc_rows_reduce_kernel(const float *partial, float *out, int64_t n4, int n_split, Scale scale,
-                                                             const int *flag, int flag_want)
+__global__ __launch_bounds__(256) void fc_rows_reduce_kernel(const float *partial, float *out, int64_t n4, int n_split, Scale scale, Gate gate)
 {
-    if (flag && flag[0] != flag_want) return;
+    if (gate.closed()) return;
     const float sc = scale.get();
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
         f32x4 v = ((const f32x4 *)partial)[i];
@@ -370,7 +369,7 @@ __global__ __launch_bounds__(256) void fc_rows_reduce_kernel(const float *partia
 // wavefront, four wavefronts per workgroup.  The walk goes over the tiles of the workgroup's planes in chunks of up to 256
 // tiles: their entry counts are scanned, and the entries of as many tiles as fit are copied into LDS as (p, q, code,
 // plane) records -- at high sparsity most tiles are empty and one chunk (three barriers) covers hundreds of planes.
-struct ConvGatherGeom { int N, C, H, Wd, K, R, S, pad, st, P, Q, cpw; };   // cpw: channels per wavefront
+struct ConvGatherGeom { int N, C, H, Wd, K, R, S, pad, st, P, Q, cpw; Gate gate; };   // cpw: channels per wavefront
 
 constexpr int kChunkCap = 1024;                           // entry records per chunk (a tile has at most 256)
 
@@ -427,6 +426,7 @@ template <class XT, class AccT, class OutT>
 __global__ __launch_bounds__(256) void conv_dw_gather_kernel(FormatView f, const XT *X, OutT *dW, ConvGatherGeom g, Scale step_arg)
 {
     __shared__ GatherChunk ch;
+    if (g.gate.closed()) return;
     const int k = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int RS = g.R * g.S, cl = lane / RS, tap = lane - cl * RS;
     const int c = ((int)blockIdx.x * 4 + wave) * g.cpw + cl;
@@ -470,6 +470,7 @@ __global__ __launch_bounds__(256) void conv_dw_gather_kernel(FormatView f, const
 __global__ __launch_bounds__(256) void conv_dx_gather_kernel(FormatView f, const float *W, float *dX, ConvGatherGeom g, Scale step_arg)
 {
     extern __shared__ float cg_planes[];                 // [4 * cpw channels][H*Wd], then the chunk
+    if (g.gate.closed()) return;
     const int n = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int RS = g.R * g.S, cl = lane / RS, tap = lane - cl * RS;
     const int c_first = (int)blockIdx.x * 4 * g.cpw, c = c_first + wave * g.cpw + cl;
@@ -530,7 +531,7 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
 {
     ConvGatherGeom g;
     g.N = (int)a.N; g.C = (int)a.C; g.H = (int)a.H; g.Wd = (int)a.Wd; g.K = (int)a.K; g.R = (int)a.R; g.S = (int)a.S;
-    g.pad = (int)a.pad; g.st = (int)a.stride;
+    g.pad = (int)a.pad; g.st = (int)a.stride; g.gate = a.gate;
     g.P = (int)((a.H + 2 * a.pad - a.R) / a.stride + 1); g.Q = (int)((a.Wd + 2 * a.pad - a.S) / a.stride + 1);
     const int RS = g.R * g.S, cpw_max = 64 / RS;
     const Scale step{a.step, a.step_dev};
@@ -627,7 +628,12 @@ bool linear_gather_supported(int64_t B, int64_t in, int64_t out)
     return B <= 65535 && out <= 65535;                    // the one-row-per-workgroup kernels index workgroups by row
 }
 
-hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s, const int *flag, int flag_want)
+bool linear_gather_gated_ok(const LinearArgs &a)
+{
+    return (!a.dX || fc_rows_dx_ok(a)) && (!a.dW || fc_rows_dw_ok(a));
+}
+
+hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s)
 {
     const int B = (int)a.B, in = (int)a.in, out = (int)a.out;
     static bool raised = false;
@@ -653,17 +659,17 @@ hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStr
         k.rows = B; k.red = out; k.cols = in;
         k.slabs = pl.slabs; k.row_blocks = pl.row_blocks; k.n_chunks = n_chunks;
         k.rparts = pl.rparts; k.rb_per_part = pl.rb_per_part; k.sparts = pl.sparts; k.ch_per_part = pl.ch_per_part;
-        k.scale = scale; k.flag = flag; k.flag_want = flag_want;
+        k.scale = scale; k.gate = a.gate;
         hipLaunchKernelGGL((fc_rows_kernel<false, FR_RW_DX, FR_CPL_DX, true, 4>), dim3((unsigned)(k.slabs * k.rparts * k.sparts)), dim3(FR_THREADS), fr_lds_bytes(FR_CPL_DX, FR_RW_DX, false), s, k);
         if (pl.sparts > 1) {
             const int64_t n4 = (int64_t)B * in / 4;
             const int rb = (int)((n4 + 255) / 256 < 2048 ? (n4 + 255) / 256 : 2048);
-            hipLaunchKernelGGL(fc_rows_reduce_kernel, dim3(rb), dim3(256), 0, s, (const float *)a.scratch, a.dX, n4, pl.sparts, scale, flag, flag_want);
+            hipLaunchKernelGGL(fc_rows_reduce_kernel, dim3(rb), dim3(256), 0, s, (const float *)a.scratch, a.dX, n4, pl.sparts, scale, a.gate);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     } else if (a.dX) {
-        if (flag) return hipErrorInvalidValue;            // the fallback kernels take no dispatch flag
+        if (a.gate.flag) return hipErrorInvalidValue;     // the fallback kernels take no gate
         if (B > 65535) return hipErrorInvalidValue;
         const bool vec = in % 4 == 0 && ((uintptr_t)a.W % 16) == 0;
         if (vec) hipLaunchKernelGGL(linear_dx_gather_kernel<true>, dim3(slabs, B), block, 0, s, f, a.W, a.dX, in, out, scale);
@@ -680,7 +686,7 @@ hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStr
         k.slabs = pl.slabs; k.row_blocks = pl.row_blocks; k.n_chunks = n_chunks;
         const int code_align = (a.out % 16 == 0 && (uintptr_t)a.codes % 16 == 0) ? 16 : (a.out % 4 == 0 && (uintptr_t)a.codes % 4 == 0) ? 4 : 1;
         k.rparts = pl.rparts; k.rb_per_part = pl.rb_per_part; k.sparts = 1; k.ch_per_part = n_chunks;
-        k.scale = scale; k.flag = flag; k.flag_want = flag_want;
+        k.scale = scale; k.gate = a.gate;
         const dim3 grid((unsigned)(k.slabs * k.rparts));
         if (code_align == 16)     hipLaunchKernelGGL((fc_rows_kernel<true, FR_RW_DW, FR_CPL_DW, false, 16>), grid, dim3(FR_THREADS), fr_lds_bytes(FR_CPL_DW, FR_RW_DW, true), s, k);
         else if (code_align == 4) hipLaunchKernelGGL((fc_rows_kernel<true, FR_RW_DW, FR_CPL_DW, false, 4>), grid, dim3(FR_THREADS), fr_lds_bytes(FR_CPL_DW, FR_RW_DW, true), s, k);
@@ -688,7 +694,7 @@ hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStr
         return hipGetLastError();
     }
     if (a.dW) {
-        if (flag) return hipErrorInvalidValue;
+        if (a.gate.flag) return hipErrorInvalidValue;
         if (out > 65535) return hipErrorInvalidValue;
         if (a.x_dtype == DBP_F32) {
             const bool vec = in % 4 == 0 && ((uintptr_t)a.X % 16) == 0;

@@ -360,7 +360,7 @@ hipError_t launch_conv_dw_i8(const ConvDwI8Plan &pl, hipStream_t s)
     if (pl.args.n_split > 1) {
         ConvDwArgs r{};                                              // the reduction reads the partial layout of both dW kernels
         r.partial = pl.args.partial; r.dW = pl.args.dW; r.n_split = pl.args.n_split; r.tiles_k = pl.args.tiles_k;
-        r.K = pl.args.K; r.C = pl.args.C; r.scale = Scale{1.0f, nullptr};
+        r.K = pl.args.K; r.C = pl.args.C; r.scale = Scale{1.0f, nullptr}; r.gate = pl.args.gate;
         hipLaunchKernelGGL((conv_dw_reduce_kernel<MODE_I8, 3, 3, 1>), dim3(pl.reduce_grid), dim3(256), 0, s, r);
     }
     return hipGetLastError();
@@ -593,6 +593,7 @@ hipError_t launch_conv1x1_dw(const ConvArgs &a, const Conv1x1Plan &pl, const int
     pa.prob[1] = p;
     pa.prob[1].n_items = 0;
     pa.stats = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    pa.gate = a.gate;
     const int grid = p.n_items < 256 ? p.n_items : 256;
     if constexpr (I8) hipLaunchKernelGGL(fc2_i8_pair_kernel<true>, dim3(grid), dim3(512), FC2I_LDS_BYTES, s, pa);
     else              hipLaunchKernelGGL(fc2_pair_kernel<true>, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
@@ -707,6 +708,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
     hipError_t e = hipSuccess;
     RowMajorOut om{a.in};
     StatsJob pending = a.stats_job;
+    if (a.plan_only && (!a.codes || a.W8)) { *a.plan_only = 1; return hipSuccess; }
     if (a.codes && a.W8) {
         // full 8-bit mode: both products on int8 matrix cores, exact int32 results
         auto i8_ok = [&](bool a_kfast, const void *Bop, const void *outp, int64_t M) {
@@ -745,7 +747,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
             pa.stats = pending;
             pending.n = 0; pending.bias_len = 0;
-            pa.gx = gx;
+            pa.gx = gx; pa.gate = a.gate;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
             const int grid = total < 256 ? total : 256;
             hipLaunchKernelGGL(fc2_i8_pair_kernel<false>, dim3(grid), dim3(512), FC2I_LDS_BYTES, s, pa);
@@ -792,6 +794,12 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
         }
         int gx = 0;
         if (use_fc2 && dx_fast && dw_fast) gx = fc2_group_plan(B, in, out, pdx, pdw);
+        if (a.plan_only) {
+            // gated: both requested products on one of the pair kernels (the generic kernel takes no gate)
+            const bool int8_dw = a.dW && a.x_dtype != DBP_F32;
+            if ((a.dX && !dx_fast) || (a.dW && !dw_fast) || int8_dw) *a.plan_only = 1;
+            return hipSuccess;
+        }
         if (use_fc2) {
             static bool raised = false;
             if (!raised) {
@@ -811,7 +819,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
             pa.stats = pending;                            // finished by a stager wavefront of the last workgroup
             pending.n = 0; pending.bias_len = 0;
-            pa.gx = gx;
+            pa.gx = gx; pa.gate = a.gate;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
             const int grid = total < 256 ? total : 256;    // persistent: one workgroup per CU (256 whenever gx > 0)
             hipLaunchKernelGGL(fc2_pair_kernel<false>, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
@@ -842,6 +850,7 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             }
             pa.stats = pending;                            // summed by the last workgroup of the launch
             pending.n = 0;
+            pa.gate = a.gate;
             if ((size_t)(scratch - (char *)a.scratch) > a.scratch_bytes) return hipErrorInvalidValue;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
             // odd grid: a persistent workgroup then alternates between the two products
@@ -945,6 +954,7 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
         };
         if (a.stride != 1 && codes_ok) {
             ConvDxStridedPlan sp = conv_dx_strided_plan(a, I8);
+            if (sp.ok && a.plan_only) return hipSuccess;
             if (sp.ok) {
                 if (sp.zero_fill) {
                     const int64_t n = a.N * a.C * a.H * a.Wd;                 // fp32 and int32 zeros are the same bytes
@@ -957,7 +967,7 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
                     const int8_t *kc = kernel_codes();
                     for (int i = 0; i < sp.multi.n; ++i) {
                         ConvDxArgs &k = sp.multi.cls[i];
-                        k.codes = kc; k.dX = a.dX; k.scale = scale;
+                        k.codes = kc; k.dX = a.dX; k.scale = scale; k.gate = a.gate;
                         k.wp = (const uint4 *)a.scratch + (int64_t)sp.tap_base[i] * KG * PL * Cp;
                     }
                     if (sp.nb == 7)      hipLaunchKernelGGL((conv_dx_multi_kernel<7, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
@@ -968,9 +978,10 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
             }
         }
         ConvDxPlan pl = conv_dx_plan(a, I8);
+        if (pl.ok && codes_ok && a.plan_only) return hipSuccess;
         if (pl.ok && codes_ok) {
             ConvDxArgs &k = pl.args;
-            k.codes = kernel_codes(); k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale;
+            k.codes = kernel_codes(); k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale; k.gate = a.gate;
             prepare(k.R * k.S, k.KG, k.Cp, nullptr);
             if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
             else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
@@ -978,6 +989,7 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
             return hipGetLastError();
         }
     }
+    if (a.plan_only) { *a.plan_only = 1; return hipSuccess; }         // the generic kernel takes no gate
     ConvGeom g = make_geom(a, ModeTraits<MODE_G>::KCH, k_step<MODE_G>());
     using WT = typename std::conditional<MODE_G == MODE_I8, int8_t, float>::type;      // int8 weights in the full 8-bit mode
     using Acc = typename ModeTraits<MODE_G>::Acc;
@@ -1005,8 +1017,10 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
     if constexpr (MODE == MODE_I8) {
         ConvDwI8Plan p8 = conv_dw_i8_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad);
         if (p8.ok && a.stride == 1 && rb + p8.partial_bytes <= a.scratch_bytes && (uintptr_t)a.X % 4 == 0 && (uintptr_t)grad % 4 == 0) {
+            if (a.plan_only) return hipSuccess;
             ConvDwI8Args &k = p8.args;
             k.codes = (const int8_t *)grad; k.X = (const int8_t *)a.X; k.dW = (int32_t *)a.dW; k.partial = (int32_t *)((char *)a.scratch + rb);
+            k.gate = a.gate;
             return launch_conv_dw_i8(p8, s);
         }
     }
@@ -1015,8 +1029,9 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
         if (a.stride != 1) pl.ok = false;                            // the fast kernel is a stride-1 kernel
         const size_t xal = MODE == MODE_I8 ? 4 : 16;                 // aligned 4-element loads of both operands
         if (pl.ok && rb + pl.partial_bytes <= a.scratch_bytes && (uintptr_t)a.X % xal == 0 && (uintptr_t)grad % 4 == 0) {
+            if (a.plan_only) return hipSuccess;
             ConvDwArgs &k = pl.args;
-            k.codes = (const int8_t *)grad; k.X = a.X; k.dW = a.dW; k.partial = (char *)a.scratch + rb; k.scale = scale;
+            k.codes = (const int8_t *)grad; k.X = a.X; k.dW = a.dW; k.partial = (char *)a.scratch + rb; k.scale = scale; k.gate = a.gate;
             return a.pad == 1 ? launch_conv_dw_fast<MODE, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE, 3, 3, 0, 1>(pl, s);
         }
     }
@@ -1025,8 +1040,9 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
         const Conv1x1Plan p1 = conv1x1_dw_plan(a.N, a.C, a.H, a.Wd, a.K, a.R, a.S, a.pad, a.stride, I8 ? FC2I_KT : FC2_KT);
         if (p1.ok && rb + p1.partial_bytes <= a.scratch_bytes && (uintptr_t)grad % 4 == 0 && (uintptr_t)a.X % (I8 ? 4 : 16) == 0 &&
             (uintptr_t)a.dW % 16 == 0)
-            return launch_conv1x1_dw<I8>(a, p1, (const int8_t *)grad, scale, (char *)a.scratch + rb, s);
+            return a.plan_only ? hipSuccess : launch_conv1x1_dw<I8>(a, p1, (const int8_t *)grad, scale, (char *)a.scratch + rb, s);
     }
+    if (a.plan_only) { *a.plan_only = 1; return hipSuccess; }         // the lowered and the generic forms are not gated
     if constexpr (MODE != MODE_F32) {
         // neither convolution kernel took it: expand the activations into the column matrix, re-lay the codes, and let the
         // fully connected kernels do dW[k][(c,r,s)] = sum_(n,p,q) code[k][(n,p,q)] col[(n,p,q)][(c,r,s)]

@@ -271,3 +271,25 @@ def test_config5_int8_full_size_in_full(target):
     assert abs(1 - res["stats"].nnz / p.delta.size - target) < 5e-3
     assert res["stats"].n_saturated == 0
     _check(p, res)
+
+
+@pytest.mark.parametrize("target,expect", [(0.92, 0), (0.999, 1)])
+def test_conv_auto_dispatches_by_density_on_the_device(target, expect):
+    # the ResNet-stage layer is large enough for both kernel families behind the density gate: matrix cores at 92 %
+    # zeros, the gather kernels at 99.9 % -- decided on the device from the quantiser's nonzero count
+    import torch
+    import paper_2004_04729_amd as dbp
+    from gpu_util import dev, stream, conv_dims
+    p = workloads.config4a(target)
+    N, Cc, H, Wd, K, R, S = conv_dims(p)
+    codes = torch.empty(p.delta.shape, dtype=torch.int8, device="cuda:0")
+    dX = torch.full(p.X.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    dW = torch.full(p.W.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    ws = torch.zeros(dbp.conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, 1, p.pad), dtype=torch.uint8, device="cuda:0")
+    st = torch.zeros(32, dtype=torch.uint8, device="cuda:0")
+    dbp.dithered_conv2d_backward(dev(p.delta), dev(p.W), dev(p.X), dbp.F32, N, Cc, H, Wd, K, R, S, 1, p.pad, p.step, p.seed, 0,
+                                 codes, dX, dW, ws, st, dbp.PATH_AUTO, stream())
+    torch.cuda.synchronize()
+    off = dbp.format_layout(N * K, p.delta.shape[2] * p.delta.shape[3])["scratch_offset"] + 16384 * 16
+    assert int(ws[off:off + 4].cpu().numpy().view(np.int32)[0]) == expect
+    _check(p, {"codes": codes.cpu().numpy(), "dX": dX.cpu().numpy(), "dW": dW.cpu().numpy(), "stats": dbp.Stats.from_tensor(st)})

@@ -176,3 +176,47 @@ def test_fc_fused_call_reports_statistics(B, in_, out):
     _, st = O.nsd(p.delta, p.step, p.seed)
     assert st.n_saturated > 0 and st.n_nonfinite > 0 and st.max_abs_code == 127
     _check_fp32(p, res)
+
+
+def _auto_flag(ws, rows, cols):
+    """The density gate's flag of a dithered_* call with DBP_PATH_AUTO (1: the gather kernels ran), read back from the workspace."""
+    import paper_2004_04729_amd as dbp
+    off = dbp.format_layout(rows, cols)["scratch_offset"] + 16384 * 16
+    return int(ws[off:off + 4].cpu().numpy().view(np.int32)[0])
+
+
+@pytest.mark.parametrize("c,expect", [(8.0, 0), (64.0, 1)])
+def test_fc_auto_dispatches_by_density_on_the_device(c, expect):
+    # 2048 x 2048 x 2048: large enough that both kernel families are launched behind the density gate; at 91 % zeros the
+    # matrix-core kernels run, at 98.9 % the gather kernels -- decided on the device from the quantiser's nonzero count
+    import torch
+    import paper_2004_04729_amd as dbp
+    from gpu_util import dev, stream
+    B, in_, out = 2048, 2048, 2048
+    p = _problem(B, in_, out, seed=5, c=c)
+    codes = torch.empty((B, out), dtype=torch.int8, device="cuda:0")
+    dX = torch.full((B, in_), float("nan"), dtype=torch.float32, device="cuda:0")
+    dW = torch.full((out, in_), float("nan"), dtype=torch.float32, device="cuda:0")
+    ws = torch.zeros(dbp.linear_workspace_bytes(B, in_, out), dtype=torch.uint8, device="cuda:0")
+    ws[dbp.format_layout(B, out)["scratch_offset"] + 16384 * 16] = 77          # stale flag: the call must overwrite it
+    for stats in (torch.zeros(32, dtype=torch.uint8, device="cuda:0"), None):
+        dbp.dithered_linear_backward(dev(p.delta), dev(p.W), dev(p.X), dbp.F32, B, in_, out, p.step, p.seed, 0, codes, dX, dW, ws,
+                                     stats, dbp.PATH_AUTO, stream())
+        torch.cuda.synchronize()
+        assert _auto_flag(ws, B, out) == expect
+        res = {"codes": codes.cpu().numpy(), "dX": dX.cpu().numpy(), "dW": dW.cpu().numpy(),
+               "stats": None if stats is None else dbp.Stats.from_tensor(stats)}
+        _check_fp32(p, res)
+        dX.fill_(float("nan")); dW.fill_(float("nan"))
+
+
+@pytest.mark.parametrize("B,in_,out", [(256, 516, 260), (300, 1028, 1000), (128, 256, 4100), (520, 260, 64), (1030, 132, 520)])
+def test_fc_gather_row_list_kernel_edges(B, in_, out):
+    # the LDS-staged gather kernels at their edges: column slabs and row blocks that end inside a tile, reductions that
+    # end inside a chunk of 64, code rows that are only 4-byte aligned, several row blocks with a split reduction
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_linear
+    p = _problem(B, in_, out, seed=B + out, c=6.0)
+    _check_fp32(p, run_linear(p, path=dbp.PATH_GATHER))
+    _check_fp32(p, run_linear(p, path=dbp.PATH_GATHER, want_dw=False))
+    _check_fp32(p, run_linear(p, path=dbp.PATH_GATHER, want_dx=False))
