@@ -146,6 +146,21 @@ dbp_status nsd_quantize(const float *delta, int64_t rows, int64_t cols, float st
                         void *format, size_t format_bytes, dbp_stats *stats, void *stream);
 
 /*
+ * nsd_quantize for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Codes and statistics as nsd_quantize (no tile-sparse format); the
+ * quantiser's scratch (its per-workgroup statistics records, 256 KiB) lives in a device array inside the library, one per
+ * GPU, held until the process ends.  The call allocates and frees nothing and launches the same kernels as nsd_quantize.
+ *   rows*cols <= DBP_STATIC_MAX_ELEMENTS, else DBP_ERR_SHAPE; stats is required; other errors as nsd_quantize;
+ *   DBP_ERR_DEVICE if the array's address cannot be obtained.
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two threads) race on it and
+ * may report wrong statistics (the codes are not affected); serialise them, or use nsd_quantize with buffers of your own.
+ */
+#define DBP_STATIC_MAX_ELEMENTS ((int64_t)1 << 32)
+dbp_status nsd_quantize_static(const float *delta, int64_t rows, int64_t cols, float step,
+                               uint64_t seed, uint64_t idx_base, int8_t *codes,
+                               dbp_stats *stats, void *stream);
+
+/*
  * Dithered backward pass of a fully connected layer, Eqs. (qdz), (qda), (qdw):
  * NSD of delta, then dX = q.W and dW = q^T.X  (storage form of W^T.q and q.a^T).
  *   X, dW   fp32 when x_dtype == DBP_F32; int8 X and int32 dW when x_dtype == DBP_I8

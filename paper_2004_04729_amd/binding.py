@@ -77,6 +77,7 @@ def lib():
         L.dbp_conv2d_workspace_bytes.restype = sz
         L.dbp_conv2d_workspace_bytes.argtypes = [i64] * 9 + [ci]
         L.nsd_quantize.argtypes = [vp, i64, i64, f32, u64, u64, vp, vp, sz, vp, vp]
+        L.nsd_quantize_static.argtypes = [vp, i64, i64, f32, u64, u64, vp, vp, vp]
         L.dithered_linear_backward.argtypes = [vp, vp, vp, ci, i64, i64, i64, f32, u64, u64, vp, vp, vp, vp, sz, vp, ci, vp]
         L.dithered_conv2d_backward.argtypes = [vp, vp, vp, ci] + [i64] * 9 + [f32, u64, u64, vp, vp, vp, vp, sz, vp, ci, vp]
         L.dense_linear_backward.argtypes = [vp, vp, vp, ci, i64, i64, i64, vp, vp, vp, sz, vp]
@@ -152,6 +153,10 @@ def conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, stride=1, pad=0, x_dtype: int 
 def nsd_quantize(delta, rows, cols, step, seed, idx_base, codes, fmt=None, stats=None, stream=0):
     _check(lib().nsd_quantize(_ptr(delta), rows, cols, step, seed, idx_base, _ptr(codes), _ptr(fmt), _nbytes(fmt),
                               _ptr(stats), stream))
+
+
+def nsd_quantize_static(delta, rows, cols, step, seed, idx_base, codes, stats, stream=0):
+    _check(lib().nsd_quantize_static(_ptr(delta), rows, cols, step, seed, idx_base, _ptr(codes), _ptr(stats), stream))
 
 
 def dithered_linear_backward(delta, W, X, x_dtype, B, in_, out, step, seed, idx_base, codes, dX, dW, workspace,

@@ -3,9 +3,15 @@
 // reachable on a machine without a GPU.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include "common.h"
 
 using namespace dbp;
+
+// Scratch of nsd_quantize_static (the per-workgroup statistics records of the quantiser): device memory that lives in the
+// library's code object, one copy per GPU, until the process ends.  In host code `scratch` is only a handle of the symbol:
+// its device address comes from hipGetSymbolAddress, once per device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[dbp::kNsdScratchBytes];
 
 namespace {
 
@@ -576,6 +582,50 @@ dbp_status dithered_conv2d_backward_q8(const float *delta, const int8_t *W8, con
     a.dX = (float *)dX32; a.dW = dW32; a.scratch = ws + c.scratch_offset; a.scratch_bytes = workspace_bytes - c.scratch_offset;
     a.stats_job = job; a.pending = nullptr;
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------------------------------
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+hipError_t static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+dbp_status nsd_quantize_static(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
+                               int8_t *codes, dbp_stats *stats, void *stream)
+{
+    if (!delta || !codes || !stats) return DBP_ERR_NULL;
+    dbp_format_layout L;
+    dbp_status st = format_layout(rows, cols, &L);
+    if (st != DBP_OK) return st;
+    if (rows * cols > DBP_STATIC_MAX_ELEMENTS) return DBP_ERR_SHAPE;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    void *base = nullptr;
+    if (static_scratch(&base) != hipSuccess) return DBP_ERR_DEVICE;
+    // the records need no clearing: every workgroup of the quantiser overwrites its own, and the final sum reads exactly
+    // those; run_nsd places them at L.scratch_offset of a format buffer, so hand it the address that puts them at `base`
+    char *fmt_base = (char *)((uintptr_t)base - (uintptr_t)L.scratch_offset);        // never dereferenced below L.scratch_offset
+    return run_nsd(delta, rows, cols, step, seed, idx_base, codes, fmt_base, &L, stats, (hipStream_t)stream, /*want_format=*/false);
 }
 
 size_t dbp_step_size_workspace_bytes(int64_t n)
