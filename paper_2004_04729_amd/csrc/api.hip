@@ -159,13 +159,21 @@ AutoPlan linear_auto_plan(const LinearArgs &call, bool launchable)
     if (ungated) return ap;
     const double B = (double)call.B, in = (double)call.in, out = (double)call.out;
     const int products = (call.dX ? 1 : 0) + (call.dW ? 1 : 0);
-    const double mfma_us = products * 2.0 * B * in * out * 3.0 / 0.85e9;             // three bf16 planes at 0.85 PFLOP/s
-    const double partial = (double)linear_gather_scratch_bytes(call.B, call.in, call.out);
-    double fixed_us = 10.0;
-    if (call.dX) fixed_us += (out * in * 4.0 + 2.0 * partial + B * in * 4.0) / 3.6e6;   // W streamed once, partial sums written and read
-    if (call.dW) fixed_us += (out * in * 4.0 + B * in * 4.0) / 3.6e6;                   // dW written once
-    if (fixed_us > 0.7 * mfma_us) return ap;
-    const double per_nnz_us = products * 2.0 * in / 24e6;                            // 24 TFLOP/s of multiply-adds on nonzeros
+    const double mfma_us = products * 2.0 * B * in * out * 3.0 / 0.95e9;             // three bf16 planes at 0.95 PFLOP/s
+    // gather kernels: a step (one 64-index chunk of one row block: tile through LDS, barrier) costs about 2.2 us however
+    // few nonzeros it holds; the nonzeros themselves run at about 32 TFLOP/s per product when all CUs have a workgroup
+    GatherShape gs[2];
+    linear_gather_shape(call.B, call.in, call.out, gs);
+    double fixed_us = 0.0, per_nnz_us = 0.0;
+    for (int i = 0; i < 2; ++i) {
+        if (!(i == 0 ? call.dX != nullptr : call.dW != nullptr)) continue;
+        const double waves = (double)((gs[i].workgroups + 255) / 256);
+        fixed_us += waves * gs[i].steps * 2.2 + (gs[i].partial_bytes ? 6.0 + 2.0 * gs[i].partial_bytes / 5.0e6 : 0.0);
+        if (i == 1) fixed_us += out * in * 4.0 / 5.0e6;                                // dW is written once
+        const double util = gs[i].workgroups >= 256 ? 1.0 : gs[i].workgroups / 256.0;
+        per_nnz_us += 2.0 * in / (32e6 * util);
+    }
+    if (fixed_us > 0.9 * mfma_us) return ap;
     const double thr = (mfma_us - fixed_us) / per_nnz_us;
     ap.dual = true;
     ap.gather_below = thr >= B * out ? (uint64_t)(B * out) + 1 : (uint64_t)thr;
@@ -176,6 +184,11 @@ AutoPlan conv_auto_plan(const ConvArgs &call, int64_t P, int64_t Q)
 {
     AutoPlan ap{false, 0};
     if (!conv_gather_supported(call.N, call.C, call.H, call.Wd, call.K, call.R, call.S, P, Q, call.dX != nullptr)) return ap;
+    // The convolution gather kernels give every workgroup a few channels and let it walk ALL entries of its image (dX) or of
+    // its output channel (dW): with large planes few channels fit a workgroup (their dX planes accumulate in LDS) and the
+    // walk is repeated by many workgroups -- measured on 56x56 planes: 1.0 ms at 99.9 % zeros against 0.41 ms on matrix
+    // cores.  The gate is only worth its empty launches on small planes (14x14: 0.065 against 0.155 ms at 99.9 %).
+    if (call.H * call.Wd > 1024 || P * Q > 1024) return ap;
     ConvArgs probe = call;
     int ungated = 0;
     StatsJob none{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};

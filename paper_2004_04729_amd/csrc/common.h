@@ -144,6 +144,9 @@ struct FormatView { const uint64_t *bitmap; const uint16_t *tile_nnz; const uint
 // flag != nullptr: device-side dispatch, the kernels run only when *flag == flag_want (fc_rows_kernel shapes only).
 hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStream_t s);   // a.gate: fc_rows_kernel shapes only
 bool       linear_gather_gated_ok(const LinearArgs &a);     // every requested product runs on the gated fc_rows_kernel
+// Launch shape of fc_rows_kernel for dX ([0]) and dW ([1]): what the density dispatch's cost model needs.
+struct GatherShape { int64_t workgroups, steps; size_t partial_bytes; };
+void       linear_gather_shape(int64_t B, int64_t in, int64_t out, GatherShape (&gs)[2]);
 size_t     linear_gather_scratch_bytes(int64_t B, int64_t in, int64_t out);    // split partials of the gather dX kernel
 bool       linear_gather_supported(int64_t B, int64_t in, int64_t out);
 // Convolution gather kernels: any stride; kernels of at most 64 taps, output planes below 4096 x 4096, and for dX an input

@@ -622,6 +622,14 @@ size_t linear_gather_scratch_bytes(int64_t B, int64_t in, int64_t out)
     return fc_rows_plan(B, in, (out + FR_CH - 1) / FR_CH, true, (size_t)-1).partial_bytes;
 }
 
+void linear_gather_shape(int64_t B, int64_t in, int64_t out, GatherShape (&gs)[2])
+{
+    const int64_t cx = (out + FR_CH - 1) / FR_CH, cw = (B + FR_CH - 1) / FR_CH;
+    const FcRowsPlan px = fc_rows_plan(B, in, cx, true, (size_t)-1), pw = fc_rows_plan(out, in, cw, false, 0);
+    gs[0] = GatherShape{(int64_t)px.slabs * px.rparts * px.sparts, (int64_t)px.rb_per_part * px.ch_per_part, px.partial_bytes};
+    gs[1] = GatherShape{(int64_t)pw.slabs * pw.rparts, (int64_t)pw.rb_per_part * cw, 0};
+}
+
 bool linear_gather_supported(int64_t B, int64_t in, int64_t out)
 {
     (void)in;

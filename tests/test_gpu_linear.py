@@ -185,29 +185,50 @@ def _auto_flag(ws, rows, cols):
     return int(ws[off:off + 4].cpu().numpy().view(np.int32)[0])
 
 
-@pytest.mark.parametrize("c,expect", [(8.0, 0), (64.0, 1)])
+@pytest.mark.parametrize("c,expect", [(8.0, 0), (128.0, 1)])
 def test_fc_auto_dispatches_by_density_on_the_device(c, expect):
-    # 2048 x 2048 x 2048: large enough that both kernel families are launched behind the density gate; at 91 % zeros the
-    # matrix-core kernels run, at 98.9 % the gather kernels -- decided on the device from the quantiser's nonzero count
+    # 256 x 4096 x 16384: a layer wide enough that the gather kernels' fixed cost (streaming W, writing dW) is below the
+    # matrix-core time, so both kernel families are launched behind the density gate; at 91 % zeros the matrix-core
+    # kernels run, at 99.4 % the gather kernels -- decided on the device from the quantiser's nonzero count
     import torch
     import paper_2004_04729_amd as dbp
     from gpu_util import dev, stream
-    B, in_, out = 2048, 2048, 2048
+    B, in_, out = 256, 4096, 16384
     p = _problem(B, in_, out, seed=5, c=c)
     codes = torch.empty((B, out), dtype=torch.int8, device="cuda:0")
     dX = torch.full((B, in_), float("nan"), dtype=torch.float32, device="cuda:0")
     dW = torch.full((out, in_), float("nan"), dtype=torch.float32, device="cuda:0")
     ws = torch.zeros(dbp.linear_workspace_bytes(B, in_, out), dtype=torch.uint8, device="cuda:0")
     ws[dbp.format_layout(B, out)["scratch_offset"] + 16384 * 16] = 77          # stale flag: the call must overwrite it
+    d, W, X = dev(p.delta), dev(p.W), dev(p.X)
     for stats in (torch.zeros(32, dtype=torch.uint8, device="cuda:0"), None):
-        dbp.dithered_linear_backward(dev(p.delta), dev(p.W), dev(p.X), dbp.F32, B, in_, out, p.step, p.seed, 0, codes, dX, dW, ws,
-                                     stats, dbp.PATH_AUTO, stream())
+        dbp.dithered_linear_backward(d, W, X, dbp.F32, B, in_, out, p.step, p.seed, 0, codes, dX, dW, ws, stats, dbp.PATH_AUTO, stream())
         torch.cuda.synchronize()
         assert _auto_flag(ws, B, out) == expect
         res = {"codes": codes.cpu().numpy(), "dX": dX.cpu().numpy(), "dW": dW.cpu().numpy(),
                "stats": None if stats is None else dbp.Stats.from_tensor(stats)}
         _check_fp32(p, res)
         dX.fill_(float("nan")); dW.fill_(float("nan"))
+
+
+def test_fc_auto_leaves_the_gate_out_where_gather_cannot_win():
+    # 2048^3: the gather kernels' fixed cost alone exceeds the matrix-core time (measured: 0.13 ms at 99.5 % zeros against
+    # 0.093 ms), so AUTO launches the matrix-core family only and the flag word is not written
+    import torch
+    import paper_2004_04729_amd as dbp
+    from gpu_util import dev, stream
+    B = in_ = out = 2048
+    p = _problem(B, in_, out, seed=5, c=128.0)
+    codes = torch.empty((B, out), dtype=torch.int8, device="cuda:0")
+    dX = torch.empty((B, in_), dtype=torch.float32, device="cuda:0")
+    dW = torch.empty((out, in_), dtype=torch.float32, device="cuda:0")
+    ws = torch.zeros(dbp.linear_workspace_bytes(B, in_, out), dtype=torch.uint8, device="cuda:0")
+    ws[dbp.format_layout(B, out)["scratch_offset"] + 16384 * 16] = 77
+    dbp.dithered_linear_backward(dev(p.delta), dev(p.W), dev(p.X), dbp.F32, B, in_, out, p.step, p.seed, 0, codes, dX, dW, ws, None,
+                                 dbp.PATH_AUTO, stream())
+    torch.cuda.synchronize()
+    assert _auto_flag(ws, B, out) == 77
+    _check_fp32(p, {"codes": codes.cpu().numpy(), "dX": dX.cpu().numpy(), "dW": dW.cpu().numpy()})
 
 
 @pytest.mark.parametrize("B,in_,out", [(256, 516, 260), (300, 1028, 1000), (128, 256, 4100), (520, 260, 64), (1030, 132, 520)])
