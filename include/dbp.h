@@ -338,6 +338,17 @@ dbp_status dithered_conv2d_backward_q8(const float *delta, const int8_t *W8, con
                                        int8_t *codes, int32_t *dX32, int32_t *dW32, void *workspace,
                                        size_t workspace_bytes, dbp_stats *stats, void *stream);
 
+/*
+ * Host-side self-check of the launch plans (no GPU call): walks, for one layer shape, the planning arithmetic that decides
+ * the kernels' work items, split-K partial sums and workspace offsets -- every work item handed out exactly once, every
+ * tile / split / class index in range, every buffer inside the size the *_workspace_bytes functions report -- with the
+ * same functions the launchers and kernels use.  Returns 0 when consistent (or when the shape takes a kernel without a
+ * plan), a positive number naming the first violated invariant, -1 for invalid dimensions.  For tests and diagnostics.
+ */
+int dbp_plan_check_linear(int64_t B, int64_t in, int64_t out);
+int dbp_plan_check_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                          int64_t stride, int64_t pad);
+
 #ifdef __cplusplus
 }
 #endif

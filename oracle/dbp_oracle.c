@@ -556,6 +556,39 @@ void dbp_oracle_conv2d_dw_at(const int8_t *codes, const float *dense, double ste
     }
 }
 
+/* ------------------------------------------------------------------------------------
+ * Forward-pass quantiser of the 8-bit mode (Sec. "Quantizing forward pass": weights and
+ * activations are 8-bit in the forward pass; the paper takes the quantiser from the work
+ * it cites and prints no formula).  Reading taken: symmetric, one scale per tensor,
+ *      amax  = max |x_i| over the finite x_i
+ *      scale = amax / 127,  inv = 127 / amax              (fp32 divisions)
+ *      q_i   = clamp(round-half-even(x_i * inv), -127, 127)   (ONE fp32 product)
+ * NaN -> 0, +-Inf -> +-127; amax == 0 (or nothing finite): scale = inv = 0, every finite
+ * q_i = 0.  Parity unpinned against the cited work; pinned by hand-computed values.
+ * ---------------------------------------------------------------------------------- */
+void dbp_oracle_quantize_int8(const float *x, int64_t n, int8_t *q, float *scale_out, float *inv_out)
+{
+    float amax = 0.0f;
+    for (int64_t i = 0; i < n; ++i)
+        if (isfinite(x[i]) && fabsf(x[i]) > amax) amax = fabsf(x[i]);
+    const float scale = amax > 0.0f ? amax / 127.0f : 0.0f;
+    const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        float v;
+        if (isnan(x[i])) v = 0.0f;
+        else if (isinf(x[i])) v = x[i] > 0.0f ? 127.0f : -127.0f;
+        else {
+            volatile float prod = x[i] * inv;          /* one fp32 product, rounded to fp32 before the rounding to integer */
+            v = nearbyintf(prod);                      /* default rounding mode: ties to even */
+            if (v > 127.0f) v = 127.0f;
+            if (v < -127.0f) v = -127.0f;
+        }
+        q[i] = (int8_t)v;
+    }
+    *scale_out = scale;
+    *inv_out = inv;
+}
+
 int dbp_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -276,24 +276,12 @@ def conv2d_dw_at(X, Wshape, idx, *, codes=None, dense=None, step=0.0, stride=1, 
 
 # ---- full 8-bit backward (Sec. "Quantizing forward pass") ---------------------------------------
 def quantize_int8(x):
-    """Symmetric per-tensor int8 quantiser: returns (q int8, scale float32, inv float32).
-
-    amax over the finite values; scale = amax/127 and inv = 127/amax as fp32 divisions; q = round-half-even(x*inv)
-    with one fp32 product, clamped to [-127, 127]; NaN -> 0, +-Inf -> +-127; amax == 0 -> scale = inv = 0.
-    """
+    """Symmetric per-tensor int8 quantiser (dbp_oracle_quantize_int8): returns (q int8, scale float32, inv float32)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    fin = np.isfinite(x)
-    amax = np.float32(np.abs(x[fin]).max()) if fin.any() else np.float32(0.0)
-    if amax > 0:
-        scale = np.float32(amax) / np.float32(127.0)
-        inv = np.float32(127.0) / np.float32(amax)
-    else:
-        scale = inv = np.float32(0.0)
-    with np.errstate(invalid="ignore", over="ignore"):
-        t = np.rint((x * inv).astype(np.float32))
-    q = np.clip(np.where(fin, t, 0.0), -127.0, 127.0)
-    q = np.where(np.isposinf(x), 127.0, np.where(np.isneginf(x), -127.0, q))
-    return q.astype(np.int8), np.float32(scale), np.float32(inv)
+    q = np.empty(x.shape, dtype=np.int8)
+    scale, inv = C.c_float(0.0), C.c_float(0.0)
+    lib().dbp_oracle_quantize_int8(_p(x), C.c_int64(x.size), _p(q), C.byref(scale), C.byref(inv))
+    return q, np.float32(scale.value), np.float32(inv.value)
 
 
 def _as_int32(v, what):

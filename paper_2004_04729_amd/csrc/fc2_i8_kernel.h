@@ -46,8 +46,8 @@ __global__ __launch_bounds__(512, 1) void fc2_i8_pair_kernel(FcPairArgs a)
     Fc2IStage *stages = (Fc2IStage *)fc2_lds;
     Fc2Item *table = (Fc2Item *)(stages + 2);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int mine = fc2_items_of_workgroup(a);
-    for (int i = threadIdx.x; i < mine; i += 512) table[i] = fc2_decode(a, i, mine);
+    const int mine = fc2_items_of_workgroup(a, (int)gridDim.x, (int)blockIdx.x);
+    for (int i = threadIdx.x; i < mine; i += 512) table[i] = fc2_decode(a, i, mine, (int)gridDim.x, (int)blockIdx.x);
     __syncthreads();
     int steps = 0;                                    // K steps of all items (the trip count of both roles)
     for (int i = 0; i < mine; ++i) steps += (table[i].k_end - table[i].k0 + FC2I_KT - 1) / FC2I_KT;

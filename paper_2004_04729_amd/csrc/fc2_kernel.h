@@ -50,26 +50,24 @@ struct Fc2Cursor {
 // the tiles of the chip are not all finished, and stored, at the same moment.
 // With a.gx > 0 the workgroups are two groups instead, one per problem: a split product then needs fewer, longer items
 // (fewer partial tiles to write and to sum) for the same balance.
-__device__ __forceinline__ int fc2_items_of_workgroup(const FcPairArgs &a)
+// (G workgroups in the launch, w = this one: parameters, so that a host-side check can walk the same arithmetic.)
+__host__ __device__ __forceinline__ int fc2_items_of_workgroup(const FcPairArgs &a, int G, int w)
 {
     if (a.gx > 0) {
-        const int w = blockIdx.x;
         const bool first = w < a.gx;
         const int n = first ? a.prob[0].n_items : a.prob[1].n_items;
-        const int wi = first ? w : w - a.gx, gp = first ? a.gx : (int)gridDim.x - a.gx;
+        const int wi = first ? w : w - a.gx, gp = first ? a.gx : G - a.gx;
         return n > wi ? (n - wi + gp - 1) / gp : 0;
     }
     const int total = a.prob[0].n_items + a.prob[1].n_items;
-    const int G = gridDim.x, w = blockIdx.x;
     const int passes = (total + G - 1) / G;
     const int last = (passes - 1) * G + (((passes - 1) & 1) ? G - 1 - w : w);
     return last < total ? passes : passes - 1;
 }
 
-__device__ __forceinline__ Fc2Item fc2_decode(const FcPairArgs &a, int i, int mine)
+__host__ __device__ __forceinline__ Fc2Item fc2_decode(const FcPairArgs &a, int i, int mine, int G, int w)
 {
     const int n0 = a.prob[0].n_items;
-    const int G = gridDim.x, w = blockIdx.x;
     const int ps = (i + w) % mine;
     Fc2Item c;
     int t, item;
@@ -102,7 +100,7 @@ __device__ __forceinline__ Fc2Item fc2_decode(const FcPairArgs &a, int i, int mi
     c.tile_m = (c.tile % p.tiles_m) * FC2_TM;
     c.tile_n = (c.tile / p.tiles_m) * FC2_TN;
     c.k0 = c.z * p.k_per_split;
-    c.k_end = min(p.K, c.k0 + p.k_per_split);
+    c.k_end = p.K < c.k0 + p.k_per_split ? p.K : c.k0 + p.k_per_split;
     c.pad = 0;
     return c;
 }
@@ -200,8 +198,8 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
     Fc2Stage *stages = (Fc2Stage *)fc2_lds;
     Fc2Item *table = (Fc2Item *)(stages + 2);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int mine = fc2_items_of_workgroup(a);
-    for (int i = threadIdx.x; i < mine; i += 512) table[i] = fc2_decode(a, i, mine);
+    const int mine = fc2_items_of_workgroup(a, (int)gridDim.x, (int)blockIdx.x);
+    for (int i = threadIdx.x; i < mine; i += 512) table[i] = fc2_decode(a, i, mine, (int)gridDim.x, (int)blockIdx.x);
     __syncthreads();
     int steps = 0;                                    // K steps of all items (the trip count of both roles)
     for (int i = 0; i < mine; ++i) steps += (table[i].k_end - table[i].k0 + FC2_KT - 1) / FC2_KT;

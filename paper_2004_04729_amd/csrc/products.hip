@@ -1,5 +1,6 @@
 // Host-side launchers of the matrix-core products: fully connected and implicit-im2col convolution,
 // dithered (bf16x3 / int8) and dense (fp32) variants, with deterministic split-K.
+#include <vector>
 #include "conv_loaders.h"
 #include "fc_kernel.h"
 #include "fc2_kernel.h"
@@ -1117,5 +1118,148 @@ hipError_t launch_conv_mfma(const ConvArgs &a_in, hipStream_t s)
     return e;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Host-side self-check of the launch plans (no GPU): the planning arithmetic above decides every kernel's indexing, so
+// a mistake in it is where an out-of-bounds access would come from.  The checks walk the same functions the launchers
+// and the kernels use.  0 = consistent (or the shape takes no planned kernel), otherwise the number of the first
+// violated invariant.
+// ------------------------------------------------------------------------------------------------
+static int check_fc2_pair(int64_t B, int64_t in, int64_t out, bool want_dx, bool want_dw, int kt)
+{
+    FcPlan pdx, pdw;
+    fc2_plans(B, in, out, want_dx, want_dw, pdx, pdw, kt);
+    const int64_t items = (want_dx ? pdx.tiles * pdx.n_split : 0) + (want_dw ? pdw.tiles * pdw.n_split : 0);
+    if (items > (int64_t)FC2_MAX_ITEMS * 256 || items <= 0) return 0;         // the launcher takes another kernel
+    int gx = 0;
+    if (want_dx && want_dw) gx = fc2_group_plan(B, in, out, pdx, pdw, kt);
+    if (!want_dx) { pdx.n_split = 1; pdx.partial_bytes = 0; }
+    if (!want_dw) { pdw.n_split = 1; pdw.partial_bytes = 0; }
+    char *scratch = nullptr;
+    FcPairArgs pa;
+    pa.prob[0] = fc_problem(true, nullptr, out, nullptr, in, (int)B, (int)in, (int)out, Scale{1.0f, nullptr}, nullptr, pdx, scratch);
+    pa.prob[1] = fc_problem(false, nullptr, out, nullptr, in, (int)out, (int)in, (int)B, Scale{1.0f, nullptr}, nullptr, pdw, scratch);
+    if (!want_dx) pa.prob[0].n_items = 0;
+    if (!want_dw) pa.prob[1].n_items = 0;
+    pa.gx = gx;
+    if ((size_t)(scratch - (char *)nullptr) > linear_scratch_bytes(B, in, out)) return 1;      // partial sums beyond the workspace
+    const int total = pa.prob[0].n_items + pa.prob[1].n_items;
+    const int G = total < 256 ? total : 256;
+    if (gx > 0 && gx >= G) return 2;                                            // the second group would have no workgroup
+    std::vector<unsigned char> seen[2];
+    seen[0].assign((size_t)pa.prob[0].n_items, 0); seen[1].assign((size_t)pa.prob[1].n_items, 0);
+    for (int w = 0; w < G; ++w) {
+        const int mine = fc2_items_of_workgroup(pa, G, w);
+        if (mine < 0 || mine > FC2_MAX_ITEMS) return 3;
+        for (int i = 0; i < mine; ++i) {
+            const Fc2Item it = fc2_decode(pa, i, mine, G, w);
+            if (it.which < 0 || it.which > 1) return 4;
+            const FcProblem &p = pa.prob[it.which];
+            if (p.n_items <= 0) return 5;
+            const int tiles = p.n_items / p.n_split;
+            if (it.tile < 0 || it.tile >= tiles || it.z < 0 || it.z >= p.n_split) return 6;
+            if (it.tile_m < 0 || it.tile_m >= p.M || it.tile_n < 0 || it.tile_n >= p.N) return 7;
+            if (it.k0 < 0 || it.k0 >= it.k_end || it.k_end > p.K) return 8;
+            unsigned char &flag = seen[it.which][(size_t)it.tile * p.n_split + it.z];
+            if (flag) return 9;                                                     // an item handed out twice
+            flag = 1;
+        }
+    }
+    for (int q = 0; q < 2; ++q)
+        for (unsigned char f : seen[q]) if (!f) return 10;                          // an item nobody takes
+    return 0;
+}
+
+static int check_conv_plans(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad)
+{
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    const size_t total = conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride), rb = relayout_bytes(K, C, R, S);
+    if (rb > total) return 20;
+    ConvArgs a{};
+    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
+    for (int i8 = 0; i8 < 2; ++i8) {
+        // dX: the stride-1 kernel or the classes of a strided layer
+        auto check_dx = [&](const ConvDxArgs &k, int nb, size_t lds, int64_t grid) {
+            const int tile_px = k.wpx * 32 * nb;
+            if (lds > (size_t)CDX_MAX_LDS || lds < (size_t)2 * CDX_KGC * k.patch_cells * 16) return 21;
+            if ((int64_t)k.tiles * tile_px < k.PI || (int64_t)(k.tiles - 1) * tile_px >= k.PI) return 22;      // tiles cover the pixels, none is empty
+            if (grid != (int64_t)k.N * k.tiles * k.cgroups || grid <= 0) return 23;
+            if (k.wc * k.wpx != 4 || (int64_t)k.cgroups * k.wc * 32 < k.Cp || k.Cp < k.C) return 24;
+            if (k.KG % CDX_KGC || (int64_t)k.KG * (i8 ? 16 : 8) < k.K || k.n_chunks * CDX_KGC != k.KG) return 25;
+            if ((int64_t)k.prow * k.pw != k.patch_cells || CDX_KGC * (int64_t)k.patch_cells >= 0xFFFF) return 26;
+            return 0;
+        };
+        if (stride == 1) {
+            const ConvDxPlan pl = conv_dx_plan(a, i8 != 0);
+            if (pl.ok) { const int e = check_dx(pl.args, pl.nb, pl.lds_bytes, pl.grid); if (e) return e; }
+        } else {
+            const ConvDxStridedPlan sp = conv_dx_strided_plan(a, i8 != 0);
+            if (sp.ok) {
+                if (sp.multi.n < 0 || sp.multi.n > CDX_MAX_CLASSES || sp.taps > 64) return 27;
+                for (int i = 0; i < sp.multi.n; ++i) {
+                    const int e = check_dx(sp.multi.cls[i], sp.nb, sp.lds_bytes, (int64_t)sp.multi.first[i + 1] - sp.multi.first[i]);
+                    if (e) return e;
+                    if (sp.tap_base[i] + sp.multi.cls[i].R * sp.multi.cls[i].S > sp.taps) return 28;
+                }
+                if (sp.multi.first[sp.multi.n] != sp.grid) return 29;
+                for (int t = 0; t < sp.taps; ++t) if (sp.map.real[t] >= R * S) return 30;
+            }
+        }
+        const size_t padded = (size_t)(N * K * ((P * Q + 3) / 4 * 4));
+        if (rb + padded > total) return 31;                                       // the padded copy of the codes
+        // dW
+        const ConvDwPlan pw = conv_dw_plan(N, C, H, Wd, K, R, S, pad, i8 != 0);
+        if (pw.ok && stride == 1) {
+            const ConvDwArgs &k = pw.args;
+            if (pw.lds_bytes > (size_t)CDW_MAX_LDS || rb + pw.partial_bytes > total) return 32;
+            if ((int64_t)k.n_split * k.units_per_split < k.units || (int64_t)(k.n_split - 1) * k.units_per_split >= k.units) return 33;
+            if ((int64_t)k.chunks * k.RU < k.H || (int64_t)(k.chunks - 1) * k.RU >= k.H || k.units != N * k.chunks) return 34;
+            if ((int64_t)k.tiles_k * 64 * pw.mb < K || (int64_t)k.tiles_c * 64 < C || pw.grid != k.tiles_k * k.tiles_c * k.n_split) return 35;
+        }
+        if (i8) {
+            const ConvDwI8Plan p8 = conv_dw_i8_plan(N, C, H, Wd, K, R, S, pad);
+            if (p8.ok && stride == 1) {
+                const ConvDwI8Args &k = p8.args;
+                if (p8.lds_bytes > (size_t)CDW_MAX_LDS || rb + p8.partial_bytes > total) return 36;
+                if ((int64_t)k.n_split * k.units_per_split < k.units || (int64_t)(k.n_split - 1) * k.units_per_split >= k.units) return 37;
+                if ((int64_t)k.chunks * k.RU < k.H || k.units != N * k.chunks || k.PW < k.Wd + 1 || k.PW % 16) return 38;
+            }
+        }
+        const Conv1x1Plan p1 = conv1x1_dw_plan(N, C, H, Wd, K, R, S, pad, stride, i8 ? FC2I_KT : FC2_KT);
+        if (p1.ok) {
+            if (rb + p1.partial_bytes > total) return 39;
+            if ((int64_t)p1.n_split * p1.imgs_per_split < N || (int64_t)(p1.n_split - 1) * p1.imgs_per_split >= N) return 40;
+            if ((int64_t)p1.spi * p1.kt < H * Wd) return 41;
+        }
+        const ConvLowerPlan lp = conv_dw_lower_plan(N, C, H, Wd, K, R, S, pad, stride, i8 ? 1 : 4);
+        const bool fast_dw = stride == 1 && (pw.ok || (i8 && conv_dw_i8_plan(N, C, H, Wd, K, R, S, pad).ok));
+        if (lp.ok && !fast_dw) {
+            if (rb + lp.bytes > total) return 42;
+            if (lp.lds_bytes > (size_t)64 * 1024) return 43;
+            if ((int64_t)lp.im.bands * lp.im.PB < lp.im.P || (int64_t)lp.im.ctiles * lp.im.CT < C) return 44;
+            // the product on the lowered operands is a fully connected dX: its own plan must be consistent too
+            const int e = check_fc2_pair(K, lp.CRS, lp.NPQ, true, false, i8 ? FC2I_KT : FC2_KT);
+            if (e) return 50 + e;
+        }
+    }
+    return 0;
+}
+
 }  // namespace dbp
 
+extern "C" int dbp_plan_check_linear(int64_t B, int64_t in, int64_t out)
+{
+    if (B <= 0 || in <= 0 || out <= 0 || B > (1 << 24) || in > (1 << 24) || out > (1 << 24)) return -1;
+    for (int kt = dbp::FC2_KT; kt <= dbp::FC2I_KT; kt *= 2)
+        for (int m = 1; m < 4; ++m) {
+            const int e = dbp::check_fc2_pair(B, in, out, (m & 1) != 0, (m & 2) != 0, kt);
+            if (e) return e;
+        }
+    return 0;
+}
+
+extern "C" int dbp_plan_check_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || Wd <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0 || H + 2 * pad < R || Wd + 2 * pad < S) return -1;
+    if (N > 65535 || C > 65535 || K > 65535 || H > 65535 || Wd > 65535 || R > 255 || S > 255 || pad > 255 || stride > 255) return -1;
+    return dbp::check_conv_plans(N, C, H, Wd, K, R, S, stride, pad);
+}

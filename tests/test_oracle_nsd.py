@@ -334,3 +334,14 @@ def test_step_size_summation_order_is_the_radix16_tree():
     _, sigma = O.step_size(y, 1)
     assert sigma == sigma_of(2.0 ** 27 + 271.0, 2.0 ** 54 + 256.0, y.size)
     assert sigma != sigma_of(2.0 ** 27 + 271.0, 2.0 ** 54, y.size)
+
+
+def test_tile_format_matches_the_hand_written_tile(golden):
+    # pins the bit order of the bitmap and the entry encoding with a tile written out by hand (tests/golden)
+    g = golden("tile_format_example.txt")
+    rows, cols = int(g["rows"][0][0]), int(g["cols"][0][0])
+    codes = np.array([int(v) for v in g["codes"][0]], dtype=np.int8)
+    bitmap, tile_nnz, entries = O.tile_format(codes, rows, cols)
+    assert [int(w) for w in bitmap[0]] == [int(v, 16) for v in g["bitmap"][0]]
+    assert int(tile_nnz[0]) == int(g["tile_nnz"][0][0])
+    assert [int(e) for e in entries[0, :int(tile_nnz[0])]] == [int(v, 16) for v in g["entries"][0]]

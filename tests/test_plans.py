@@ -1,0 +1,59 @@
+"""Host-side walk of the launch plans (no GPU): for a grid of layer shapes, the planning code of the fast kernels must hand
+out every work item exactly once, keep every tile / split / class index in range and every partial-sum buffer inside
+the workspace size the library reports.  This is the arithmetic a GPU fault would come from."""
+import ctypes as C
+import itertools
+
+import pytest
+
+import paper_2004_04729_amd as dbp
+
+
+def _lib():
+    L = dbp.lib()
+    L.dbp_plan_check_linear.argtypes = [C.c_int64] * 3
+    L.dbp_plan_check_conv2d.argtypes = [C.c_int64] * 9
+    return L
+
+
+FC_DIMS = [1, 2, 3, 4, 31, 32, 33, 64, 100, 127, 128, 129, 255, 256, 257, 300, 511, 512, 513, 784, 1000, 1024, 1030, 2048, 4096, 4100, 8192]
+
+
+def test_fc_plans_cover_every_item_once_and_stay_in_bounds():
+    L = _lib()
+    bad = []
+    for B, in_, out in itertools.product(FC_DIMS, FC_DIMS, FC_DIMS):
+        e = L.dbp_plan_check_linear(B, in_, out)
+        if e:
+            bad.append((B, in_, out, e))
+    assert not bad, bad[:10]
+    # the configurations and a few very large layers
+    for B, in_, out in [(64, 784, 300), (256, 1024, 4096), (256, 4096, 4096), (256, 4096, 1000), (256, 8192, 8192), (300, 4096, 4000),
+                        (2048, 2048, 2048), (256, 4096, 16384), (65536, 65536, 8), (8, 65536, 65536), (4096, 16384, 16384)]:
+        assert L.dbp_plan_check_linear(B, in_, out) == 0, (B, in_, out)
+    assert L.dbp_plan_check_linear(0, 4, 4) == -1
+
+
+CONV = [  # N, C, H, Wd, K, R, S, stride, pad
+    (128, 64, 32, 32, 64, 3, 3, 1, 1), (64, 256, 14, 14, 256, 3, 3, 1, 1), (64, 1024, 14, 14, 256, 1, 1, 1, 0), (32, 256, 56, 56, 256, 3, 3, 1, 1),
+    (64, 128, 28, 28, 256, 3, 3, 2, 1), (64, 256, 14, 14, 512, 3, 3, 2, 1), (64, 3, 224, 224, 64, 7, 7, 2, 3), (32, 64, 15, 15, 64, 3, 3, 1, 1),
+    (16, 512, 7, 7, 512, 3, 3, 1, 1), (8, 96, 27, 27, 256, 5, 5, 1, 2), (1, 1, 1, 1, 1, 1, 1, 1, 0), (2, 5, 9, 7, 6, 3, 3, 1, 1),
+    (64, 132, 24, 20, 264, 1, 1, 2, 0), (1, 8, 17, 17, 8, 3, 3, 4, 1), (2, 16, 9, 224, 8, 3, 3, 1, 1), (1, 16, 20, 228, 16, 3, 3, 1, 1),
+]
+
+
+def test_conv_plans_stay_in_bounds():
+    L = _lib()
+    for case in CONV:
+        assert L.dbp_plan_check_conv2d(*case) == 0, case
+    bad = []
+    for N, C_, H, K, (R, st, pad) in itertools.product([1, 3, 32, 70], [1, 3, 16, 33, 64, 130, 256], [1, 5, 7, 8, 14, 15, 28, 31, 56],
+                                                        [1, 8, 20, 64, 130, 260], [(1, 1, 0), (3, 1, 1), (3, 1, 0), (3, 2, 1), (5, 1, 2), (7, 2, 3), (2, 2, 0), (3, 3, 0)]):
+        for Wd in {H, H + 3, 4 * ((H + 3) // 4)}:
+            if H + 2 * pad < R or Wd + 2 * pad < R:
+                continue
+            e = L.dbp_plan_check_conv2d(N, C_, H, Wd, K, R, R, st, pad)
+            if e:
+                bad.append((N, C_, H, Wd, K, R, st, pad, e))
+    assert not bad, bad[:10]
+    assert L.dbp_plan_check_conv2d(1, 1, 2, 2, 1, 5, 5, 1, 0) == -1
