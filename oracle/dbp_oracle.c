@@ -144,6 +144,78 @@ void dbp_oracle_nsd(const float *delta, int64_t n, float step, uint64_t seed,
 }
 
 /* ------------------------------------------------------------------------------------
+ * Top-k sparsifier (the comparison method of Sec. "Comparison to meProp", recalled in
+ * Sec. "Related work": keep the k elements of largest magnitude of each gradient vector,
+ * drop the rest) emitting the same int8 codes as the dithered quantiser, so that both
+ * sparsifiers can feed the same product kernels.
+ *
+ * Readings (the paper describes the selection in one clause and no code format for it):
+ *   - the tensor is cut into n_vec consecutive vectors of `len` elements (one example's
+ *     gradient for a fully connected layer); the selection is per vector;
+ *   - an element is kept iff fewer than k elements of its vector have a STRICTLY larger
+ *     magnitude, i.e. iff |x| >= the k-th largest magnitude of the vector.  Without ties
+ *     at the threshold that is exactly the k largest; with ties all of the tied elements
+ *     are kept (a unique result that does not depend on any traversal order);
+ *     k <= 0 keeps nothing, k >= len keeps everything.  The magnitude of a NaN counts as 0;
+ *   - kept elements are quantised with the paper's uniform quantiser of Eq. (nsd) WITHOUT
+ *     the dither (nu = 0, so u = 1/2): code = floor(fma(x, 1/Delta, 0.5f)) in fp32,
+ *     saturating to [-127, 127], NaN -> 0: deterministic rounding to the nearest level
+ *     (this is the "deterministic quantisation function" the paper contrasts with NSD);
+ *     dropped elements get code 0.  The statistics are those of the quantiser applied to
+ *     the tensor with the dropped elements replaced by +0.
+ * ---------------------------------------------------------------------------------- */
+static float magnitude_of(float x) { return isnan(x) ? 0.0f : fabsf(x); }
+
+static int descending_float(const void *a, const void *b)
+{
+    float x = *(const float *)a, y = *(const float *)b;
+    return (x < y) - (x > y);
+}
+
+/* thr[v] = k-th largest magnitude of vector v (k clipped to len); +Inf's successor does not
+ * exist in fp32, so "keep nothing" (k <= 0) is reported as NaN, which no magnitude reaches. */
+void dbp_oracle_topk_threshold(const float *delta, int64_t n_vec, int64_t len, int64_t k, float *thr)
+{
+    float *mag = (float *)malloc((size_t)(len > 0 ? len : 1) * sizeof(float));
+    for (int64_t v = 0; v < n_vec; ++v) {
+        if (k <= 0) { thr[v] = NAN; continue; }
+        for (int64_t j = 0; j < len; ++j) mag[j] = magnitude_of(delta[v * len + j]);
+        qsort(mag, (size_t)len, sizeof(float), descending_float);
+        thr[v] = mag[(k < len ? k : len) - 1];
+    }
+    free(mag);
+}
+
+void dbp_oracle_topk_quantize(const float *delta, int64_t n_vec, int64_t len, int64_t k, float step,
+                              int8_t *codes, dbp_oracle_stats *st)
+{
+    const float inv = 1.0f / step;
+    float *thr = (float *)malloc((size_t)(n_vec > 0 ? n_vec : 1) * sizeof(float));
+    dbp_oracle_topk_threshold(delta, n_vec, len, k, thr);
+    dbp_oracle_stats s;
+    memset(&s, 0, sizeof s);
+    for (int64_t v = 0; v < n_vec; ++v)
+        for (int64_t j = 0; j < len; ++j) {
+            const float raw = delta[v * len + j];
+            const float x = magnitude_of(raw) >= thr[v] ? raw : 0.0f;      /* NaN threshold: never true */
+            const float t = fmaf(x, inv, 0.5f);
+            const float kf = floorf(t);
+            int c;
+            if (!isfinite(x)) s.n_nonfinite++;
+            if (isnan(t)) c = 0;
+            else if (kf > 127.0f) { c = 127; s.n_saturated++; }
+            else if (kf < -127.0f) { c = -127; s.n_saturated++; }
+            else c = (int)kf;
+            if (c != 0) s.nnz++;
+            const int a = c < 0 ? -c : c;
+            if (a > s.max_abs_code) s.max_abs_code = a;
+            codes[v * len + j] = (int8_t)c;
+        }
+    free(thr);
+    if (st) *st = s;
+}
+
+/* ------------------------------------------------------------------------------------
  * Step size of a layer (Algorithm 1, the two assignments before the quantiser):  sigma = std(delta_z),
  * Delta = s * sigma.
  *

@@ -100,6 +100,27 @@ def nsd(delta, step: float, seed: int, idx_base: int = 0):
     return codes, Stats(st.nnz, st.n_saturated, st.n_nonfinite, st.max_abs_code)
 
 
+def topk_threshold(delta, k: int):
+    """k-th largest magnitude of every row of the 2-D `delta` (NaN when k <= 0): top-k sparsifier of Sec. "Comparison to meProp"."""
+    d = _f32(delta)
+    assert d.ndim == 2
+    thr = np.empty(d.shape[0], dtype=np.float32)
+    lib().dbp_oracle_topk_threshold(_p(d), C.c_int64(d.shape[0]), C.c_int64(d.shape[1]), C.c_int64(k), _p(thr))
+    return thr
+
+
+def topk_quantize(delta, k: int, step: float):
+    """Codes and Stats of the top-k sparsifier: per row of the 2-D `delta` the elements whose magnitude reaches the k-th
+    largest are rounded to the nearest level of step `step` (Eq. (nsd) without dither), the others are 0."""
+    d = _f32(delta)
+    assert d.ndim == 2
+    codes = np.empty(d.shape, dtype=np.int8)
+    st = _Stats()
+    lib().dbp_oracle_topk_quantize(_p(d), C.c_int64(d.shape[0]), C.c_int64(d.shape[1]), C.c_int64(k), C.c_float(step),
+                                   _p(codes), C.byref(st))
+    return codes, Stats(st.nnz, st.n_saturated, st.n_nonfinite, st.max_abs_code)
+
+
 def step_size(delta, s: float):
     """(Delta = s*std(delta) as fp32, sigma as fp64): Algorithm 1, population std, radix-16 summation tree."""
     d = _f32(delta)

@@ -38,6 +38,8 @@ void dbp_oracle_conv2d_dx_at(const int8_t *, const float *, double, const float 
 void dbp_oracle_conv2d_dw_at(const int8_t *, const float *, double, const float *, const int8_t *, int64_t, int64_t, int64_t,
                              int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, const int64_t *, int64_t, double *);
 void dbp_oracle_quantize_int8(const float *, int64_t, int8_t *, float *, float *);
+void dbp_oracle_topk_threshold(const float *, int64_t, int64_t, int64_t, float *);
+void dbp_oracle_topk_quantize(const float *, int64_t, int64_t, int64_t, float, int8_t *, stats_t *);
 
 static uint64_t lcg = 88172645463325252ull;
 static double rnd(void) { lcg ^= lcg << 13; lcg ^= lcg >> 7; lcg ^= lcg << 17; return (double)(lcg >> 11) / 9007199254740992.0 - 0.5; }
@@ -77,6 +79,12 @@ int main(void)
     int8_t *q8 = malloc((size_t)n);
     float sc, inv;
     dbp_oracle_quantize_int8(d, n, q8, &sc, &inv);
+    float *thr = malloc((size_t)rows * sizeof(float));
+    dbp_oracle_topk_threshold(d, rows, cols, 7, thr);
+    dbp_oracle_topk_threshold(d, rows, cols, cols + 5, thr);
+    dbp_oracle_topk_threshold(d, rows, cols, 0, thr);
+    dbp_oracle_topk_quantize(d, rows, cols, 7, 4e-3f, codes, &st);
+    dbp_oracle_topk_quantize(d, 1, n, n, 4e-3f, codes, NULL);
 
     /* fully connected products: B x out codes (the first B*out of `codes`), W [out x in], X [B x in] */
     const int64_t B = 5, in = 13, out = 7;
@@ -122,7 +130,7 @@ int main(void)
         dbp_oracle_conv2d_dw_at(ck, NULL, 1.0, NULL, cx8, N, C, H, Wd, K, R, S, stv, pad, iw, 3, val);
         free(cx); free(cw); free(cd); free(ck); free(y); free(cdx); free(cdw); free(cx8); free(cdw32);
     }
-    free(d); free(codes); free(act); free(dz); free(bitmap); free(tnz); free(ent); free(sums); free(grad); free(q8);
+    free(d); free(codes); free(act); free(dz); free(bitmap); free(tnz); free(ent); free(sums); free(grad); free(q8); free(thr);
     free(W); free(X); free(dX); free(dW); free(X8); free(dW32);
     puts("oracle sanitizer run: ok");
     return 0;
