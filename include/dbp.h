@@ -161,6 +161,29 @@ dbp_status nsd_quantize_static(const float *delta, int64_t rows, int64_t cols, f
                                dbp_stats *stats, void *stream);
 
 /*
+ * Top-k sparsifier: the comparison method of Sec. "Comparison to meProp" (of every gradient vector the k elements of
+ * largest magnitude survive, the rest become zero), emitting the same int8 codes, tile-sparse format and statistics as
+ * nsd_quantize, so that the two sparsifiers can be compared on identical product kernels (dbp_*_products).
+ *   delta     [rows*cols] fp32, in; rows/cols shape the tile-sparse format as in nsd_quantize.
+ *   vec_rows  a vector = vec_rows consecutive rows (vec_rows*cols consecutive elements); rows % vec_rows == 0.
+ *             Fully connected layer: 1 (one example's gradient).  Convolution, codes [N*K x P*Q]: K for one vector per
+ *             example, 1 for one per feature-map plane.
+ *   k         elements kept per vector: those whose magnitude reaches the k-th largest of the vector (ties at that
+ *             magnitude all survive); k <= 0 keeps nothing, k >= the vector's length everything.  NaN has magnitude 0.
+ *   step      Delta > 0 of the code grid (e.g. max|delta|/127): survivors become floor(fma(x, 1/Delta, 0.5f)) clamped to
+ *             [-127,127] -- Eq. (nsd) without the dither, i.e. deterministic rounding to the nearest level.
+ *   workspace dbp_topk_workspace_bytes(rows, vec_rows) bytes, 256-byte aligned (the per-vector thresholds).
+ *   format, stats as nsd_quantize (the statistics are those of the tensor with the dropped elements set to 0).
+ * Two kernels: a per-vector selection (binary search over the magnitude bits; vectors up to 65536 elements are held in
+ * registers, longer ones are re-read 31 times and are slow), then the quantiser's kernel.
+ * Errors: as nsd_quantize; vec_rows <= 0, rows % vec_rows != 0, vec_rows*cols >= 2^31 -> SHAPE; workspace -> WORKSPACE.
+ */
+size_t     dbp_topk_workspace_bytes(int64_t rows, int64_t vec_rows);
+dbp_status topk_quantize(const float *delta, int64_t rows, int64_t cols, int64_t vec_rows, int64_t k, float step,
+                         int8_t *codes, void *format, size_t format_bytes, void *workspace, size_t workspace_bytes,
+                         dbp_stats *stats, void *stream);
+
+/*
  * Dithered backward pass of a fully connected layer, Eqs. (qdz), (qda), (qdw):
  * NSD of delta, then dX = q.W and dW = q^T.X  (storage form of W^T.q and q.a^T).
  *   X, dW   fp32 when x_dtype == DBP_F32; int8 X and int32 dW when x_dtype == DBP_I8

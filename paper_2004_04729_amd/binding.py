@@ -78,6 +78,10 @@ def lib():
         L.dbp_conv2d_workspace_bytes.argtypes = [i64] * 9 + [ci]
         L.nsd_quantize.argtypes = [vp, i64, i64, f32, u64, u64, vp, vp, sz, vp, vp]
         L.nsd_quantize_static.argtypes = [vp, i64, i64, f32, u64, u64, vp, vp, vp]
+        L.dbp_topk_workspace_bytes.restype = sz
+        L.dbp_topk_workspace_bytes.argtypes = [i64, i64]
+        L.topk_quantize.argtypes = [vp, i64, i64, i64, i64, f32, vp, vp, sz, vp, sz, vp, vp]
+        L.topk_quantize.restype = ci
         L.dithered_linear_backward.argtypes = [vp, vp, vp, ci, i64, i64, i64, f32, u64, u64, vp, vp, vp, vp, sz, vp, ci, vp]
         L.dithered_conv2d_backward.argtypes = [vp, vp, vp, ci] + [i64] * 9 + [f32, u64, u64, vp, vp, vp, vp, sz, vp, ci, vp]
         L.dense_linear_backward.argtypes = [vp, vp, vp, ci, i64, i64, i64, vp, vp, vp, sz, vp]
@@ -157,6 +161,15 @@ def nsd_quantize(delta, rows, cols, step, seed, idx_base, codes, fmt=None, stats
 
 def nsd_quantize_static(delta, rows, cols, step, seed, idx_base, codes, stats, stream=0):
     _check(lib().nsd_quantize_static(_ptr(delta), rows, cols, step, seed, idx_base, _ptr(codes), _ptr(stats), stream))
+
+
+def topk_workspace_bytes(rows: int, vec_rows: int = 1) -> int:
+    return int(lib().dbp_topk_workspace_bytes(rows, vec_rows))
+
+
+def topk_quantize(delta, rows, cols, vec_rows, k, step, codes, workspace, fmt=None, stats=None, stream=0):
+    _check(lib().topk_quantize(_ptr(delta), rows, cols, vec_rows, k, step, _ptr(codes), _ptr(fmt), _nbytes(fmt),
+                               _ptr(workspace), _nbytes(workspace), _ptr(stats), stream))
 
 
 def dithered_linear_backward(delta, W, X, x_dtype, B, in_, out, step, seed, idx_base, codes, dX, dW, workspace,

@@ -63,9 +63,10 @@ Carve carve(int64_t rows, int64_t cols, size_t scratch_bytes)
 dbp_status run_nsd(const float *delta, int64_t rows, int64_t cols, float step, uint64_t seed, uint64_t idx_base,
                    int8_t *codes, char *fmt_base, const dbp_format_layout *L, dbp_stats *stats, hipStream_t s,
                    bool want_format = true, StatsJob *defer = nullptr, const dbp_nsd_extras *ex = nullptr, bool bias_zeroed = false,
-                   const StepTree *tree = nullptr)
+                   const StepTree *tree = nullptr, const uint32_t *topk_thr = nullptr, int64_t topk_vec_rows = 1)
 {
     NsdArgs a;
+    a.topk_thr = topk_thr; a.topk_vec_rows = topk_vec_rows;
     a.delta = delta; a.codes = codes; a.stats = stats;
     const bool fmt = fmt_base && want_format;
     a.bitmap = fmt ? (uint64_t *)(fmt_base + L->bitmap_offset) : nullptr;
@@ -401,6 +402,32 @@ dbp_status nsd_quantize(const float *delta, int64_t rows, int64_t cols, float st
     if (format && (format_bytes < L.total_bytes || !aligned(format, 256))) return DBP_ERR_WORKSPACE;
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     return run_nsd(delta, rows, cols, step, seed, idx_base, codes, (char *)format, &L, stats, (hipStream_t)stream);
+}
+
+size_t dbp_topk_workspace_bytes(int64_t rows, int64_t vec_rows)
+{
+    if (rows <= 0 || vec_rows <= 0 || rows % vec_rows != 0) return 0;
+    return align_up((size_t)(rows / vec_rows) * sizeof(uint32_t), 256);
+}
+
+dbp_status topk_quantize(const float *delta, int64_t rows, int64_t cols, int64_t vec_rows, int64_t k, float step, int8_t *codes,
+                         void *format, size_t format_bytes, void *workspace, size_t workspace_bytes, dbp_stats *stats, void *stream)
+{
+    if (!delta || !codes) return DBP_ERR_NULL;
+    dbp_format_layout L;
+    dbp_status st = format_layout(rows, cols, &L);
+    if (st != DBP_OK) return st;
+    if (vec_rows <= 0 || rows % vec_rows != 0) return DBP_ERR_SHAPE;
+    if (cols > (((int64_t)1 << 31) - 1) / vec_rows) return DBP_ERR_SHAPE;          // per-vector counts are 32-bit
+    if (rows / vec_rows >= ((int64_t)1 << 31)) return DBP_ERR_SHAPE;                // one workgroup (or wavefront) per vector
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (format && (format_bytes < L.total_bytes || !aligned(format, 256))) return DBP_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < dbp_topk_workspace_bytes(rows, vec_rows) || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    uint32_t *thr = (uint32_t *)workspace;
+    if (launch_topk_threshold(delta, rows / vec_rows, vec_rows * cols, k, thr, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
+    return run_nsd(delta, rows, cols, step, 0, 0, codes, (char *)format, &L, stats, (hipStream_t)stream, true, nullptr, nullptr, false,
+                   nullptr, thr, vec_rows);
 }
 
 dbp_status dbp_linear_products(const int8_t *codes, const void *format, float step, const float *W, const void *X,

@@ -63,6 +63,9 @@ struct NsdArgs {
     int          bias_zeroed; // bias_sums were cleared by an earlier kernel of the stream (launch_step_size)
     StepTree     tree;        // unfinished step size (then step_dev is what the kernel writes, not what it reads)
     int          run;                                  // consecutive tiles per wavefront run (set by launch_nsd)
+    // ---- top-k sparsifier (nsd_kernel<.., .., false, true>): no dither, elements below their vector's threshold are dropped
+    const uint32_t *topk_thr = nullptr;                // per vector: smallest magnitude bit pattern that survives
+    int64_t      topk_vec_rows = 1;                    // a vector = this many consecutive rows
     int64_t      wave_stride_rows, wave_stride_segs;   // grid stride in tiles = rows*tiles_per_row + segs (set by launch_nsd)
 };
 // Pending reduction of the per-workgroup statistics records into one dbp_stats (n == 0: nothing pending).
@@ -78,6 +81,9 @@ struct StatsJob {
 // or calls launch_stats_job.
 hipError_t launch_nsd(const NsdArgs &a, hipStream_t s, StatsJob *defer = nullptr);
 hipError_t launch_stats_job(const StatsJob &j, hipStream_t s);
+// Top-k sparsifier, first half: thr[v] = bit pattern of the k-th largest magnitude of vector v (n_vec vectors of len
+// consecutive elements, len < 2^31); the quantiser (launch_nsd with NsdArgs::topk_thr) keeps what reaches it.
+hipError_t launch_topk_threshold(const float *delta, int64_t n_vec, int64_t len, int64_t k, uint32_t *thr, hipStream_t s);
 
 // Step size of Algorithm 1 on the device: step_out = {Delta = s*std(delta_z), 1/Delta}, delta_z = delta masked by act > 0
 // when act is given (both 0 if the standard

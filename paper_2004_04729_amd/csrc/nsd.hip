@@ -80,9 +80,20 @@ __device__ __forceinline__ void step_pair_from_sums(double S1, double S2, int64_
 // EX adds what surrounds the quantiser in a layer's backward pass: the rectifier's derivative applied on load
 // (delta_z = delta_a (.) f'(z)), a step size that an earlier kernel left in device memory (Algorithm 1), and the
 // bias gradient's integer code sums (the bias enters z additively: delta_b = sum of q over what shares the bias).
-template <bool VEC, bool FORMAT, bool EX>
+// Magnitude of an element as an integer that orders like it: the bit pattern of |x|, 0 for a NaN.
+__device__ __forceinline__ uint32_t magnitude_key(float x)
+{
+    const uint32_t b = __float_as_uint(x) & 0x7fffffffu;
+    return b > 0x7f800000u ? 0u : b;
+}
+
+// TOPK replaces the dither by the constant 1/2 (Eq. (nsd) with nu = 0: rounding to the nearest level) and drops the elements
+// whose magnitude is below their vector's threshold: the top-k sparsifier of Sec. "Comparison to meProp" in the same code
+// and tile format.
+template <bool VEC, bool FORMAT, bool EX, bool TOPK = false>
 __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
 {
+    static_assert(!(EX && TOPK), "the top-k sparsifier takes none of the layer extensions");
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t n_waves = (int64_t)gridDim.x * 4;
@@ -197,7 +208,14 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
         float u[4];
         const uint64_t c_tile = g_tile >> 1;
         const bool paired = VEC && !(g_tile & 1) && (uint32_t)c_tile < 0xFFFFFF00u;    // wave-uniform
-        if (paired) {
+        if constexpr (TOPK) {
+            const uint32_t thr = a.topk_thr[a.topk_vec_rows == 1 ? row : row / a.topk_vec_rows];   // wave-uniform
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[j] = magnitude_key(x[j]) >= thr ? x[j] : 0.0f;
+                u[j] = 0.5f;
+            }
+        } else if (paired) {
             const uint32_t k1c = a.k1 + (uint32_t)(c_tile >> 32) * kC;                 // scalar
             const uint32_t c0 = (uint32_t)c_tile + 2u * (uint32_t)lane;
             const uint32_t hA = hash_word(c0, a.k0, k1c);
@@ -572,6 +590,75 @@ hipError_t launch_step_size(const float *delta, const float *act, int64_t n, flo
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Top-k sparsifier, selection: the k-th largest magnitude of every vector, found by a binary search over the 31 bits of
+// the magnitude keys, most significant first: the threshold is the largest T with at least k keys >= T.  WAVES
+// wavefronts share a vector (one: four vectors per workgroup, no barrier; sixteen: one vector per workgroup, one barrier
+// per bit); each lane keeps E keys in registers, or (MEM) re-reads the vector at every bit.
+template <int WAVES, int E, bool MEM>
+__global__ __launch_bounds__(WAVES == 1 ? 256 : 64 * WAVES) void topk_threshold_kernel(const float *delta, int64_t n_vec, int64_t len,
+                                                                                      int64_t k, uint32_t *thr)
+{
+    constexpr int GROUP = 64 * WAVES;                                  // threads per vector
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t v = WAVES == 1 ? (int64_t)blockIdx.x * 4 + wave : (int64_t)blockIdx.x;
+    if (v >= n_vec) return;                                            // whole wavefronts (WAVES == 1) or never (grid = n_vec)
+    const int t = WAVES == 1 ? lane : (int)threadIdx.x;
+    const float *src = delta + v * len;
+    __shared__ uint32_t s_cnt[2][16];
+    uint32_t key[E];
+    if constexpr (!MEM) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int64_t idx = (int64_t)e * GROUP + t;
+            key[e] = idx < len ? magnitude_key(src[idx]) : 0u;        // a candidate is never 0: padding is never counted
+        }
+    }
+    uint32_t prefix = 0;
+    for (int b = 30; b >= 0; --b) {
+        const uint32_t cand = prefix | (1u << b);
+        uint32_t c = 0;
+        if constexpr (!MEM) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) c += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(key[e] >= cand));
+        } else {
+            for (int64_t base = 0; base < len; base += GROUP) {        // the same trips for every lane
+                const int64_t idx = base + t;
+                const uint32_t kk = idx < len ? magnitude_key(src[idx]) : 0u;
+                c += (uint32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(kk >= cand));
+            }
+        }
+        if constexpr (WAVES > 1) {
+            // buffer b & 1 is written again two bits later, after the barrier of the bit in between: every read is over by then
+            if (lane == 0) s_cnt[b & 1][wave] = c;
+            __syncthreads();
+            c = 0;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) c += s_cnt[b & 1][w];
+        }
+        if ((int64_t)c >= k) prefix = cand;
+    }
+    // k <= 0: a threshold above the key of +-Inf, nothing survives; fewer than k keys >= 1: prefix stays 0, everything does
+    if (t == 0) thr[v] = k <= 0 ? 0x7f800001u : prefix;
+}
+
+hipError_t launch_topk_threshold(const float *delta, int64_t n_vec, int64_t len, int64_t k, uint32_t *thr, hipStream_t s)
+{
+    if (len <= 4096) {
+        const dim3 grid((unsigned)((n_vec + 3) / 4)), block(256);
+        if (len <= 256)       hipLaunchKernelGGL((topk_threshold_kernel<1, 4, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
+        else if (len <= 1024) hipLaunchKernelGGL((topk_threshold_kernel<1, 16, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
+        else                  hipLaunchKernelGGL((topk_threshold_kernel<1, 64, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
+    } else {
+        const dim3 grid((unsigned)n_vec), block(1024);
+        if (len <= 16384)      hipLaunchKernelGGL((topk_threshold_kernel<16, 16, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
+        else if (len <= 65536) hipLaunchKernelGGL((topk_threshold_kernel<16, 64, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
+        else                   hipLaunchKernelGGL((topk_threshold_kernel<16, 1, true>), grid, block, 0, s, delta, n_vec, len, k, thr);
+    }
+    return hipGetLastError();
+}
+
 DitherKeys make_dither_keys(uint64_t seed)
 {
     DitherKeys k;
@@ -619,7 +706,12 @@ hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s, StatsJob *defer)
         hipLaunchKernelGGL(zero_i64_kernel, dim3((unsigned)(zb < 1024 ? zb : 1024)), dim3(256), 0, s, a.bias_sums, a.bias_len);
     }
     const bool vec = vec_d && (!a.act || ((uintptr_t)a.act % 16 == 0));
-    if (!ex) {
+    if (a.topk_thr) {
+        if (vec && a.bitmap)       hipLaunchKernelGGL((nsd_kernel<true, true, false, true>), grid, block, 0, s, a);
+        else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false, false, true>), grid, block, 0, s, a);
+        else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true, false, true>), grid, block, 0, s, a);
+        else                       hipLaunchKernelGGL((nsd_kernel<false, false, false, true>), grid, block, 0, s, a);
+    } else if (!ex) {
         if (vec && a.bitmap)       hipLaunchKernelGGL((nsd_kernel<true, true, false>), grid, block, 0, s, a);
         else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false, false>), grid, block, 0, s, a);
         else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true, false>), grid, block, 0, s, a);
