@@ -499,6 +499,88 @@ void dbp_oracle_conv2d_backward(const int8_t *codes, const float *dense, double 
     if (macs) *macs = n_mac;
 }
 
+/* ------------------------------------------------------------------------------------
+ * Grouped convolution (the layer type of the two-tower AlexNet and of later CNNs of the kind
+ * Sec. "Experiments" trains; the paper gives no formula, this is the standard definition):
+ * input and output channels are cut into `groups` equal consecutive blocks, Cg = C/groups and
+ * Kg = K/groups, and output channel k sees only the input channels of its own block
+ * g(k) = k / Kg.  W is [K, Cg, R, S].
+ *   forward   Y[n,k,p,q]   = sum_{c'<Cg, r, s} W[k,c',r,s] X[n, g(k)*Cg + c', p*st+r-pad, q*st+s-pad]
+ *   Eq. (qda) dX[n,c,h,w]  = Delta * sum over k with g(k) == c / Cg, and (r,s) with h = p*st+r-pad, w = q*st+s-pad
+ *                            of code[n,k,p,q] W[k, c % Cg, r, s]
+ *   Eq. (qdw) dW[k,c',r,s] = Delta * sum_{n,p,q} code[n,k,p,q] X[n, g(k)*Cg + c', p*st+r-pad, q*st+s-pad]
+ * groups == 1 is dbp_oracle_conv2d_forward / _backward.
+ * ---------------------------------------------------------------------------------- */
+void dbp_oracle_conv2d_forward_grouped(const float *X, const float *W, int64_t N, int64_t C, int64_t H, int64_t Wd,
+                                       int64_t K, int64_t R, int64_t S, int64_t st, int64_t pad, int64_t groups, double *Y)
+{
+    const int64_t P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
+    const int64_t Cg = C / groups, Kg = K / groups;
+    for (int64_t n = 0; n < N; ++n)
+      for (int64_t k = 0; k < K; ++k)
+        for (int64_t p = 0; p < P; ++p)
+          for (int64_t q = 0; q < Q; ++q) {
+              double acc = 0.0;
+              for (int64_t cl = 0; cl < Cg; ++cl)
+                for (int64_t r = 0; r < R; ++r)
+                  for (int64_t s = 0; s < S; ++s) {
+                      const int64_t h = p * st + r - pad, w = q * st + s - pad, c = (k / Kg) * Cg + cl;
+                      if (h < 0 || h >= H || w < 0 || w >= Wd) continue;
+                      acc += (double)W[((k * Cg + cl) * R + r) * S + s] * (double)X[((n * C + c) * H + h) * Wd + w];
+                  }
+              Y[((n * K + k) * P + p) * Q + q] = acc;
+          }
+}
+
+void dbp_oracle_conv2d_backward_grouped(const int8_t *codes, const float *dense, double step, const float *W, const float *X,
+                                        int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                        int64_t st, int64_t pad, int64_t groups, double *dX, double *dW, int threads)
+{
+    const int64_t P = (H + 2 * pad - R) / st + 1, Q = (Wd + 2 * pad - S) / st + 1;
+    const int64_t Cg = C / groups, Kg = K / groups;
+    if (threads < 1) threads = 1;
+    if (dX) {
+        #pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+        for (int64_t n = 0; n < N; ++n) {
+            double *img = dX + n * C * H * Wd;
+            for (int64_t i = 0; i < C * H * Wd; ++i) img[i] = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+              for (int64_t p = 0; p < P; ++p)
+                for (int64_t q = 0; q < Q; ++q) {
+                    const double g = qval(codes, dense, step, ((n * K + k) * P + p) * Q + q);
+                    if (g == 0.0) continue;
+                    for (int64_t cl = 0; cl < Cg; ++cl)
+                      for (int64_t r = 0; r < R; ++r)
+                        for (int64_t s = 0; s < S; ++s) {
+                            const int64_t h = p * st + r - pad, w = q * st + s - pad, c = (k / Kg) * Cg + cl;
+                            if (h < 0 || h >= H || w < 0 || w >= Wd) continue;
+                            img[(c * H + h) * Wd + w] += g * (double)W[((k * Cg + cl) * R + r) * S + s];
+                        }
+                }
+        }
+    }
+    if (dW) {
+        #pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+        for (int64_t k = 0; k < K; ++k) {
+            double *flt = dW + k * Cg * R * S;
+            for (int64_t i = 0; i < Cg * R * S; ++i) flt[i] = 0.0;
+            for (int64_t n = 0; n < N; ++n)
+              for (int64_t p = 0; p < P; ++p)
+                for (int64_t q = 0; q < Q; ++q) {
+                    const double g = qval(codes, dense, step, ((n * K + k) * P + p) * Q + q);
+                    if (g == 0.0) continue;
+                    for (int64_t cl = 0; cl < Cg; ++cl)
+                      for (int64_t r = 0; r < R; ++r)
+                        for (int64_t s = 0; s < S; ++s) {
+                            const int64_t h = p * st + r - pad, w = q * st + s - pad, c = (k / Kg) * Cg + cl;
+                            if (h < 0 || h >= H || w < 0 || w >= Wd) continue;
+                            flt[(cl * R + r) * S + s] += g * (double)X[((n * C + c) * H + h) * Wd + w];
+                        }
+                }
+        }
+    }
+}
+
 /* 8-bit mode conv weight gradient, exact; same contract as dbp_oracle_linear_dw_i8. */
 int64_t dbp_oracle_conv2d_dw_i8(const int8_t *codes, const int8_t *X8,
                                 int64_t N, int64_t C, int64_t H, int64_t Wd,

@@ -229,6 +229,36 @@ def conv2d_backward(W, X, *, codes=None, dense=None, step=0.0, stride=1, pad=0,
     return dX, dW, macs.value
 
 
+def conv2d_forward_grouped(X, W, groups, stride=1, pad=0):
+    """fp64 Y [N,K,P,Q] of a grouped cross-correlation; X [N,C,H,Wd], W [K,C/groups,R,S]."""
+    X, W = _f32(X), _f32(W)
+    N, Cc, H, Wd = X.shape
+    K, Cg, R, S = W.shape
+    assert Cc == Cg * groups and K % groups == 0
+    P, Q = (H + 2 * pad - R) // stride + 1, (Wd + 2 * pad - S) // stride + 1
+    Y = np.empty((N, K, P, Q), dtype=np.float64)
+    lib().dbp_oracle_conv2d_forward_grouped(_p(X), _p(W), *[C.c_int64(v) for v in (N, Cc, H, Wd, K, R, S, stride, pad, groups)], _p(Y))
+    return Y
+
+
+def conv2d_backward_grouped(W, X, groups, *, codes=None, dense=None, step=0.0, stride=1, pad=0, want_dx=True, want_dw=True,
+                            threads=None):
+    """fp64 (dX [N,C,H,Wd], dW [K,C/groups,R,S]) of the grouped convolution's Eqs. (qda), (qdw)."""
+    X, W = _f32(X), _f32(W)
+    N, Cc, H, Wd = X.shape
+    K, Cg, R, S = W.shape
+    assert Cc == Cg * groups and K % groups == 0
+    P, Q = (H + 2 * pad - R) // stride + 1, (Wd + 2 * pad - S) // stride + 1
+    k, d, s = _q_args(codes, dense, step)
+    assert (k if k is not None else d).shape == (N, K, P, Q)
+    dX = np.empty(X.shape, dtype=np.float64) if want_dx else None
+    dW = np.empty(W.shape, dtype=np.float64) if want_dw else None
+    lib().dbp_oracle_conv2d_backward_grouped(_p(k), _p(d), s, _p(W), _p(X),
+                                             *[C.c_int64(v) for v in (N, Cc, H, Wd, K, R, S, stride, pad, groups)],
+                                             _p(dX), _p(dW), C.c_int(threads or max_threads()))
+    return dX, dW
+
+
 def conv2d_dw_i8(codes, X8, R, S, stride=1, pad=0, threads=None):
     k, x = _i8(codes), _i8(X8)
     N, Cc, H, Wd = x.shape

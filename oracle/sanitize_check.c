@@ -38,6 +38,10 @@ void dbp_oracle_conv2d_dx_at(const int8_t *, const float *, double, const float 
 void dbp_oracle_conv2d_dw_at(const int8_t *, const float *, double, const float *, const int8_t *, int64_t, int64_t, int64_t,
                              int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, const int64_t *, int64_t, double *);
 void dbp_oracle_quantize_int8(const float *, int64_t, int8_t *, float *, float *);
+void dbp_oracle_conv2d_forward_grouped(const float *, const float *, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t,
+                                       int64_t, int64_t, double *);
+void dbp_oracle_conv2d_backward_grouped(const int8_t *, const float *, double, const float *, const float *, int64_t, int64_t, int64_t,
+                                        int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t, double *, double *, int);
 void dbp_oracle_topk_threshold(const float *, int64_t, int64_t, int64_t, float *);
 void dbp_oracle_topk_quantize(const float *, int64_t, int64_t, int64_t, float, int8_t *, stats_t *);
 
@@ -106,7 +110,7 @@ int main(void)
     dbp_oracle_linear_dw_at(codes, NULL, 1.0, NULL, X8, B, in, out, idw, 4, val);
 
     /* convolutions: odd sizes, stride 2 and 3, padding wider than the kernel reach */
-    const int64_t geo[4][9] = {/* N, C, H, Wd, K, R, S, stride, pad */ {2, 3, 7, 5, 4, 3, 3, 1, 1}, {1, 2, 9, 8, 3, 5, 3, 2, 2},
+    const int64_t geo[4][9] = {/* N, C, H, Wd, K, R, S, stride, pad */ {2, 4, 7, 5, 6, 3, 3, 1, 1}, {1, 2, 9, 8, 3, 5, 3, 2, 2},
                                {2, 1, 6, 6, 2, 3, 3, 3, 3}, {1, 4, 4, 4, 4, 1, 1, 1, 0}};
     for (int g = 0; g < 4; ++g) {
         const int64_t N = geo[g][0], C = geo[g][1], H = geo[g][2], Wd = geo[g][3], K = geo[g][4], R = geo[g][5], S = geo[g][6],
@@ -128,6 +132,14 @@ int main(void)
         dbp_oracle_conv2d_dx_at(ck, NULL, 4e-3, cw, N, C, H, Wd, K, R, S, stv, pad, ix, 3, val);
         dbp_oracle_conv2d_dw_at(ck, NULL, 4e-3, cx, NULL, N, C, H, Wd, K, R, S, stv, pad, iw, 3, val);
         dbp_oracle_conv2d_dw_at(ck, NULL, 1.0, NULL, cx8, N, C, H, Wd, K, R, S, stv, pad, iw, 3, val);
+        for (int64_t grp = 2; grp <= 4; grp += 2)
+            if (C % grp == 0 && K % grp == 0) {
+                float *gw = falloc(K * (C / grp) * R * S, 1.0);
+                double *gdw = malloc((size_t)(K * (C / grp) * R * S) * sizeof(double));
+                dbp_oracle_conv2d_forward_grouped(cx, gw, N, C, H, Wd, K, R, S, stv, pad, grp, y);
+                dbp_oracle_conv2d_backward_grouped(ck, NULL, 4e-3, gw, cx, N, C, H, Wd, K, R, S, stv, pad, grp, cdx, gdw, 2);
+                free(gw); free(gdw);
+            }
         free(cx); free(cw); free(cd); free(ck); free(y); free(cdx); free(cdw); free(cx8); free(cdw32);
     }
     free(d); free(codes); free(act); free(dz); free(bitmap); free(tnz); free(ent); free(sums); free(grad); free(q8); free(thr);
