@@ -200,8 +200,8 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
                                     dbp_stats *stats, dbp_path path, void *stream);
 
 /*
- * Dithered backward pass of a 2-D convolution (cross-correlation, zero padding, groups = 1,
- * dilation = 1), the convolutional analogue of Eqs. (qdz), (qda), (qdw):
+ * Dithered backward pass of a 2-D convolution (cross-correlation, zero padding, dilation = 1; grouped layers:
+ * dithered_conv2d_backward_grouped), the convolutional analogue of Eqs. (qdz), (qda), (qdw):
  *   dX[n,c,h,w] = Delta * sum_{k,r,s} code[n,k,p,q] W[k,c,r,s],  h = p*stride+r-pad, w = q*stride+s-pad
  *   dW[k,c,r,s] = Delta * sum_{n,p,q} code[n,k,p,q] X[n,c,p*stride+r-pad,q*stride+s-pad]
  * x_dtype as above.  Errors as above; path == DBP_PATH_GATHER (kernels that walk the nonzero entries, rows of the
@@ -218,6 +218,35 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
                                     int8_t *codes, float *dX, void *dW,
                                     void *workspace, size_t workspace_bytes,
                                     dbp_stats *stats, dbp_path path, void *stream);
+
+/*
+ * Grouped convolution (the layer type of the two-tower AlexNet and of later CNNs of the kind Sec. "Experiments" trains): input
+ * and output channels are cut into `groups` equal consecutive blocks and output channel k sees only the input channels of
+ * block k / (K/groups).  Eqs. (qdz), (qda), (qdw) as in dithered_conv2d_backward, with
+ *   W, dW [K, C/groups, R, S];  X, dX [N, C, H, Wd];  delta, codes [N, K, P, Q]   (groups == 1: dithered_conv2d_backward).
+ * One quantiser pass over the whole delta, then the groups run one after the other on the stream as independent layers
+ * (N, C/groups, H, Wd, K/groups) on channel blocks of the same tensors, on the kernels of the ungrouped layer; a group
+ * with few channels fills little of a 64- or 128-wide matrix-core tile (depthwise layers run, slowly).
+ * DBP_PATH_AUTO takes the matrix-core kernels (no density dispatch).  workspace: dbp_conv2d_grouped_workspace_bytes.
+ * Errors as dithered_conv2d_backward; groups < 1 or not dividing C and K -> DBP_ERR_SHAPE.
+ */
+size_t     dbp_conv2d_grouped_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                              int64_t stride, int64_t pad, int64_t groups, dbp_dtype x_dtype);
+dbp_status dithered_conv2d_backward_grouped(const float *delta, const float *W, const void *X, dbp_dtype x_dtype,
+                                            int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                            int64_t stride, int64_t pad, int64_t groups,
+                                            float step, uint64_t seed, uint64_t idx_base,
+                                            int8_t *codes, float *dX, void *dW,
+                                            void *workspace, size_t workspace_bytes,
+                                            dbp_stats *stats, dbp_path path, void *stream);
+/* The products alone, as dbp_conv2d_products: `format` (rows = N*K, cols = P*Q) is read by DBP_PATH_GATHER only; the other
+ * paths need a workspace of conv scratch for one group (dbp_conv2d_grouped_workspace_bytes is enough). */
+dbp_status dbp_conv2d_products_grouped(const int8_t *codes, const void *format, float step,
+                                       const float *W, const void *X, dbp_dtype x_dtype,
+                                       int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
+                                       int64_t R, int64_t S, int64_t stride, int64_t pad, int64_t groups,
+                                       float *dX, void *dW, void *workspace, size_t workspace_bytes,
+                                       dbp_path path, void *stream);
 
 /*
  * Same-library dense baselines: the undithered backward pass, Eqs. (da), (dw), on fp32 matrix

@@ -84,6 +84,12 @@ def lib():
         L.topk_quantize.restype = ci
         L.dithered_linear_backward.argtypes = [vp, vp, vp, ci, i64, i64, i64, f32, u64, u64, vp, vp, vp, vp, sz, vp, ci, vp]
         L.dithered_conv2d_backward.argtypes = [vp, vp, vp, ci] + [i64] * 9 + [f32, u64, u64, vp, vp, vp, vp, sz, vp, ci, vp]
+        L.dbp_conv2d_grouped_workspace_bytes.restype = sz
+        L.dbp_conv2d_grouped_workspace_bytes.argtypes = [i64] * 10 + [ci]
+        L.dithered_conv2d_backward_grouped.argtypes = [vp, vp, vp, ci] + [i64] * 10 + [f32, u64, u64, vp, vp, vp, vp, sz, vp, ci, vp]
+        L.dithered_conv2d_backward_grouped.restype = ci
+        L.dbp_conv2d_products_grouped.argtypes = [vp, vp, f32, vp, vp, ci] + [i64] * 10 + [vp, vp, vp, sz, ci, vp]
+        L.dbp_conv2d_products_grouped.restype = ci
         L.dense_linear_backward.argtypes = [vp, vp, vp, ci, i64, i64, i64, vp, vp, vp, sz, vp]
         L.dense_conv2d_backward.argtypes = [vp, vp, vp, ci] + [i64] * 9 + [vp, vp, vp, sz, vp]
         L.dbp_linear_products.argtypes = [vp, vp, f32, vp, vp, ci, i64, i64, i64, vp, vp, vp, sz, ci, vp]
@@ -184,6 +190,24 @@ def dithered_conv2d_backward(delta, W, X, x_dtype, N, Cc, H, Wd, K, R, S, stride
     _check(lib().dithered_conv2d_backward(_ptr(delta), _ptr(W), _ptr(X), x_dtype, N, Cc, H, Wd, K, R, S, stride, pad,
                                           step, seed, idx_base, _ptr(codes), _ptr(dX), _ptr(dW), _ptr(workspace),
                                           _nbytes(workspace), _ptr(stats), path, stream))
+
+
+def conv2d_grouped_workspace_bytes(N, Cc, H, Wd, K, R, S, stride, pad, groups, x_dtype: int = F32) -> int:
+    return int(lib().dbp_conv2d_grouped_workspace_bytes(N, Cc, H, Wd, K, R, S, stride, pad, groups, x_dtype))
+
+
+def dithered_conv2d_backward_grouped(delta, W, X, x_dtype, N, Cc, H, Wd, K, R, S, stride, pad, groups, step, seed, idx_base,
+                                     codes, dX, dW, workspace, stats=None, path=PATH_AUTO, stream=0):
+    _check(lib().dithered_conv2d_backward_grouped(_ptr(delta), _ptr(W), _ptr(X), x_dtype, N, Cc, H, Wd, K, R, S, stride, pad,
+                                                  groups, step, seed, idx_base, _ptr(codes), _ptr(dX), _ptr(dW),
+                                                  _ptr(workspace), _nbytes(workspace), _ptr(stats), path, stream))
+
+
+def conv2d_products_grouped(codes, fmt, step, W, X, x_dtype, N, Cc, H, Wd, K, R, S, stride, pad, groups, dX, dW, workspace,
+                            path=PATH_AUTO, stream=0):
+    _check(lib().dbp_conv2d_products_grouped(_ptr(codes), _ptr(fmt), step, _ptr(W), _ptr(X), x_dtype, N, Cc, H, Wd, K, R, S,
+                                             stride, pad, groups, _ptr(dX), _ptr(dW), _ptr(workspace), _nbytes(workspace),
+                                             path, stream))
 
 
 def dense_linear_backward(delta, W, X, x_dtype, B, in_, out, dX, dW, workspace, stream=0):

@@ -512,6 +512,133 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
                                     pad, dX, dW, path, stream, job, nullptr);
 }
 
+// ---- grouped convolution: the groups are independent layers on channel blocks of the same tensors, launched one after
+// the other on the stream with the kernels of the ungrouped layer (which take the tensors' channel counts as strides)
+namespace {
+
+dbp_status check_groups(int64_t C, int64_t K, int64_t groups)
+{
+    if (groups < 1 || C % groups != 0 || K % groups != 0) return DBP_ERR_SHAPE;
+    return DBP_OK;
+}
+
+dbp_status conv2d_products_grouped(const int8_t *codes, const void *format, float step, const float *W, const void *X, dbp_dtype x_dtype,
+                                   int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
+                                   int64_t groups, float *dX, void *dW, void *scratch, size_t scratch_bytes, dbp_path path, hipStream_t s,
+                                   StatsJob job)
+{
+    int64_t P, Q;
+    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q);
+    if (st != DBP_OK) return st;
+    if ((st = check_groups(C, K, groups)) != DBP_OK) return st;
+    const int64_t Cg = C / groups, Kg = K / groups, HW = H * Wd;
+    const size_t xsz = x_dtype == DBP_I8 ? 1 : 4;
+    if (launch_stats_job(job, s) != hipSuccess) return DBP_ERR_DEVICE;
+    const bool gather = path == DBP_PATH_GATHER;
+    FormatView f{nullptr, nullptr, nullptr, 0};
+    if (gather) {
+        dbp_format_layout L;
+        format_layout(N * K, P * Q, &L);
+        const char *fb = (const char *)format;
+        f = FormatView{(const uint64_t *)(fb + L.bitmap_offset), (const uint16_t *)(fb + L.tile_nnz_offset),
+                       (const uint16_t *)(fb + L.entries_offset), L.tiles_per_row};
+    }
+    ConvArgs a;
+    a.dense = nullptr; a.step = step; a.step_dev = nullptr; a.W8 = nullptr; a.x_dtype = x_dtype;
+    a.N = N; a.C = Cg; a.H = H; a.Wd = Wd; a.K = Kg; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
+    a.Ct = C; a.Kt = K;
+    a.scratch = gather ? nullptr : scratch; a.scratch_bytes = gather ? 0 : scratch_bytes;
+    a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; a.pending = nullptr; a.gate = Gate{};
+    if (!gather && dX && stride != 1 && groups > 1) {
+        // output pixels that no tap reaches (a 1x1 kernel with stride 2 ...): the ungrouped launch clears its contiguous dX
+        // itself, a group's block of channels is not contiguous, so the whole tensor is cleared once, here
+        if (launch_zero_words(dX, N * C * HW, s) != hipSuccess) return DBP_ERR_DEVICE;
+        a.dx_zeroed = true;
+    }
+    for (int64_t j = 0; j < groups; ++j) {
+        a.codes = codes + j * Kg * P * Q;
+        a.k_first = j * Kg;
+        a.W = W + j * Kg * Cg * R * S;
+        a.X = X ? (const char *)X + (size_t)(j * Cg * HW) * xsz : nullptr;
+        a.dX = dX ? dX + j * Cg * HW : nullptr;
+        a.dW = dW ? (char *)dW + (size_t)(j * Kg * Cg * R * S) * 4 : nullptr;           // fp32 and int32 alike
+        const hipError_t e = gather ? launch_conv_gather(a, f, s) : launch_conv_mfma(a, s);
+        if (e != hipSuccess) return DBP_ERR_DEVICE;
+    }
+    return DBP_OK;
+}
+
+dbp_status check_grouped_call(const void *W, const void *X, const float *dX, const void *dW, dbp_dtype x_dtype, int64_t N, int64_t C,
+                              int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad, int64_t groups,
+                              dbp_path path, int64_t *P, int64_t *Q)
+{
+    if (!W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
+    dbp_status st = check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, P, Q);
+    if (st != DBP_OK) return st;
+    if ((st = check_groups(C, K, groups)) != DBP_OK) return st;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
+    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    // the gather kernels' limits, on the whole tensors (32-bit offsets into X, 16-bit plane numbers)
+    if (path == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, *P, *Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
+    if (x_dtype == DBP_I8 && dW && N * *P * *Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
+    return DBP_OK;
+}
+
+}  // namespace
+
+size_t dbp_conv2d_grouped_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                          int64_t stride, int64_t pad, int64_t groups, dbp_dtype x_dtype)
+{
+    int64_t P, Q;
+    if (check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q) != DBP_OK || check_groups(C, K, groups) != DBP_OK) return 0;
+    if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return 0;
+    return carve(N * K, P * Q, conv_scratch_bytes(N, C / groups, H, Wd, K / groups, R, S, pad, stride)).total;
+}
+
+dbp_status dbp_conv2d_products_grouped(const int8_t *codes, const void *format, float step, const float *W, const void *X,
+                                       dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                       int64_t stride, int64_t pad, int64_t groups, float *dX, void *dW, void *workspace,
+                                       size_t workspace_bytes, dbp_path path, void *stream)
+{
+    if (!codes) return DBP_ERR_NULL;
+    int64_t P, Q;
+    dbp_status st = check_grouped_call(W, X, dX, dW, x_dtype, N, C, H, Wd, K, R, S, stride, pad, groups, path, &P, &Q);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    if (path == DBP_PATH_GATHER) {
+        if (!format) return DBP_ERR_NULL;
+        if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
+    } else {
+        const size_t need = conv_scratch_bytes(N, C / groups, H, Wd, K / groups, R, S, pad, stride);
+        if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    }
+    return conv2d_products_grouped(codes, format, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, groups, dX, dW, workspace,
+                                   workspace_bytes, path, (hipStream_t)stream, StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr});
+}
+
+dbp_status dithered_conv2d_backward_grouped(const float *delta, const float *W, const void *X, dbp_dtype x_dtype, int64_t N, int64_t C,
+                                            int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
+                                            int64_t groups, float step, uint64_t seed, uint64_t idx_base, int8_t *codes, float *dX,
+                                            void *dW, void *workspace, size_t workspace_bytes, dbp_stats *stats, dbp_path path,
+                                            void *stream)
+{
+    if (!delta) return DBP_ERR_NULL;
+    int64_t P, Q;
+    dbp_status st = check_grouped_call(W, X, dX, dW, x_dtype, N, C, H, Wd, K, R, S, stride, pad, groups, path, &P, &Q);
+    if (st != DBP_OK) return st;
+    if (!step_ok(step)) return DBP_ERR_STEP;
+    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C / groups, H, Wd, K / groups, R, S, pad, stride));
+    if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
+    if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
+    char *ws = (char *)workspace;
+    int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
+    StatsJob job;
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, path == DBP_PATH_GATHER, &job);
+    if (st != DBP_OK) return st;
+    return conv2d_products_grouped(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, groups, dX, dW, ws + c.scratch_offset,
+                                   workspace_bytes - c.scratch_offset, path, (hipStream_t)stream, job);
+}
+
 dbp_status dense_linear_backward(const void *delta, const float *W, const void *X, dbp_dtype x_dtype,
                                  int64_t B, int64_t in, int64_t out, float *dX, void *dW,
                                  void *workspace, size_t workspace_bytes, void *stream)

@@ -131,6 +131,13 @@ struct ConvArgs {
     const void   *X;           // [N,C,H,Wd]
     dbp_dtype     x_dtype;
     int64_t       N, C, H, Wd, K, R, S, pad, stride;
+    // One group of a grouped convolution: X/dX and the codes are channel blocks of tensors with Ct resp. Kt channels
+    // (image n of X starts n*Ct*H*Wd elements in; 0 = C resp. K: an ordinary layer); W and dW are the group's own block.
+    int64_t       Ct = 0, Kt = 0;
+    int64_t       k_first = 0;         // first code plane of the group inside an image's Kt planes (what the gather kernels' format rows need)
+    bool          dx_zeroed = false;   // dX is already cleared (the strided dX kernels then skip their own clearing pass)
+    int64_t ct() const { return Ct ? Ct : C; }
+    int64_t kt() const { return Kt ? Kt : K; }
     float        *dX;
     void         *dW;
     void         *scratch;
@@ -144,6 +151,7 @@ size_t     linear_scratch_bytes(int64_t B, int64_t in, int64_t out);
 size_t     conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t pad, int64_t stride = 1);
 hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s);
+hipError_t launch_zero_words(void *p, int64_t n_words, hipStream_t s);      // clears n 4-byte words
 
 // ---- gather path (gather.hip) ------------------------------------------------------------------
 struct FormatView { const uint64_t *bitmap; const uint16_t *tile_nnz; const uint16_t *entries; int64_t tiles_per_row; };

@@ -32,6 +32,7 @@ struct ConvDwI8Args {
     int32_t      *dW;          // [K][C][3][3]
     int32_t      *partial;     // [tile][split][tap][v/4][thread][v%4] (n_split > 1), as conv_dw_reduce_kernel reads it
     int N, C, H, Wd, K;
+    int Ct, Kt;                // channels of the tensors that hold X and the codes (C, K unless this is one group's block)
     int PW, CPR, DC;           // row pitch (pixels), cells per pitched row, cells of a row that hold pixels
     int RU, chunks;            // image rows per unit; units per image
     int units, units_per_split, n_split, tiles_k, tiles_c;
@@ -99,10 +100,10 @@ __global__ __launch_bounds__(512, 1) void conv_dw_i8_kernel(ConvDwI8Args a)
 
         auto issue = [&](int unit) {
             const int n = unit / a.chunks, h_a = (unit - n * a.chunks) * a.RU;
-            const int8_t *xb = a.X + ((int64_t)n * a.C + c0) * PI + (int64_t)h_a * a.Wd;             // uniform
+            const int8_t *xb = a.X + ((int64_t)n * a.Ct + c0) * PI + (int64_t)h_a * a.Wd;             // uniform
             // the patch starts a row above the unit's rows: offsets from there are never negative (the address itself may
             // lie in front of the tensor for the first unit, whose row above is not read)
-            const int8_t *cb = a.codes + ((int64_t)n * a.K + k0) * PI + ((int64_t)h_a - 1) * a.Wd;   // uniform
+            const int8_t *cb = a.codes + ((int64_t)n * a.Kt + k0) * PI + ((int64_t)h_a - 1) * a.Wd;   // uniform
             // rows outside the image read the first 16 bytes of the unit's first row in the tile's first channel and are
             // cleared when staged
             const bool x_ld = x_own && h_a + xrow < a.H;

@@ -37,6 +37,7 @@ struct ConvDwArgs {
     void         *dW;          // [K][C][R][S] fp32 or int32
     void         *partial;     // [tile][split][element][256] (n_split > 1)
     int N, C, H, Wd, K, P, Q, pad;
+    int Ct, Kt;                // channels of the tensors that hold X and the codes (C, K unless this is one group's block)
     int PW;                    // row pitch in pitched coordinates
     int RU, TPc, chunks;       // image rows per unit; RU*PW; units per image
     int units, units_per_split, n_split;
@@ -118,11 +119,11 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
         const int n = unit / a.chunks, h_a = (unit - n * a.chunks) * a.RU;
         const int fe0 = ((h_a * a.Wd) & ~3) + 4 * xq;
         const bool x_ld = xq < a.nqx && fe0 < PI;
-        const char *xb0 = (const char *)((const XT *)a.X + ((int64_t)n * a.C + c0) * PI);         // uniform
+        const char *xb0 = (const char *)((const XT *)a.X + ((int64_t)n * a.Ct + c0) * PI);         // uniform
         const int p_lo = h_a - 1 - (R - 1) + a.pad;
         const int fc0 = ((p_lo * a.Q) & ~3) + 4 * cq;
         const bool c_ld = cq < a.nqc && fc0 >= 0 && fc0 < PQ;
-        const char *cb0 = (const char *)(a.codes + ((int64_t)n * a.K + k0) * PQ);                  // uniform
+        const char *cb0 = (const char *)(a.codes + ((int64_t)n * a.Kt + k0) * PQ);                  // uniform
 #pragma unroll
         for (int j = 0; j < CI; ++j) {
             if (j >= ci_n) break;
@@ -173,10 +174,10 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
 
     auto issue_fast = [&](int unit) {
         const int n = unit / a.chunks, h_a = (unit - n * a.chunks) * a.RU;
-        const char *xb = (const char *)((const XT *)a.X + ((int64_t)n * a.C + c0) * PI + h_a * a.Wd);      // uniform
+        const char *xb = (const char *)((const XT *)a.X + ((int64_t)n * a.Ct + c0) * PI + h_a * a.Wd);      // uniform
         const bool x_ld = x_own && xrel < PI - h_a * a.Wd;               // below the image's last row: nothing to load
         const int c_shift = (h_a - 1 - (R - 1) + a.pad) * a.Q;           // first code element of the patch rows (may be < 0)
-        const char *cb = (const char *)(a.codes + ((int64_t)n * a.K + k0) * PQ);                         // uniform
+        const char *cb = (const char *)(a.codes + ((int64_t)n * a.Kt + k0) * PQ);                         // uniform
         const bool c_ld = c_own && crel + c_shift >= 0 && crel + c_shift < PQ;
         if (whole_tile) {
             const uint32_t cm = c_ld ? 0xFFFFFFFFu : 0u, xm = x_ld ? 0xFFFFFFFFu : 0u;

@@ -41,6 +41,7 @@ struct ConvDxArgs {
     int N, C, H, Wd, K, R, S, pad, P, Q;   // H, Wd, R, S, pad: of the (virtual) stride-1 problem; pad = row padding
     int pad_w;                // column padding
     int PI, PQ;               // H*Wd; bytes from one code plane to the next (P*Q, or P*Q rounded up to 4 in a padded copy)
+    int64_t code_img, dx_img; // bytes from one image's codes to the next (planes of the tensor x PQ); elements from one image of dX to the next
     int oW, oPI, ost, oh0, ow0;   // output: row length and pixels per channel of the real dX, pixel (i, j) -> (ost*i + oh0, ost*j + ow0)
     int Cp, KG, n_chunks;     // C rounded to 32; k-groups in total (K rounded to a chunk); chunks of CDX_KGC k-groups
     int wc, wpx;              // waves along channels x waves along pixels (wc * wpx == 4)
@@ -170,14 +171,15 @@ __global__ __launch_bounds__(256) void conv_dx_weight_prep_i8_kernel(const int8_
 }
 
 // Code planes of P*Q bytes -> planes of `plane` bytes (a multiple of 4, zero filled): the patch fill reads aligned dwords.
-__global__ __launch_bounds__(256) void conv_dx_pad_codes_kernel(const int8_t *src, uint32_t *dst, int64_t planes, int pq, int plane)
+// Plane pl = (n, k) of the copy is plane n*Kt + k of the source tensor (Kt = K unless the K planes are one group's block).
+__global__ __launch_bounds__(256) void conv_dx_pad_codes_kernel(const int8_t *src, uint32_t *dst, int64_t planes, int pq, int plane, int K, int Kt)
 {
     const int dpp = plane >> 2;                                  // dwords per padded plane
     const int64_t total = planes * dpp;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
         const int64_t pl = i / dpp;
         const int j0 = 4 * (int)(i - pl * dpp);
-        const int8_t *s = src + pl * pq + j0;
+        const int8_t *s = src + (pl / K * Kt + pl % K) * pq + j0;
         uint32_t v = 0u;
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -256,7 +258,7 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
         }
     }
     uint32_t raw[CDX_ITMAX][G];
-    const int8_t *img = a.codes + (int64_t)n * a.K * a.PQ;
+    const int8_t *img = a.codes + (int64_t)n * a.code_img;
     auto fetch_chunk = [&](int chunk) {
 #pragma unroll
         for (int i = 0; i < CDX_ITMAX; ++i) {
@@ -372,7 +374,7 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
 
     // ---- store: lane holds pixel column lcol, channel rows 8*(v/4) + 4*lhalf + v%4 of its block ----
     if (wave_active) {
-        typename TR::Out *out = (typename TR::Out *)a.dX + (int64_t)n * a.C * (STRIDED ? a.oPI : a.PI);  // offsets inside one image fit 31 bits (host check)
+        typename TR::Out *out = (typename TR::Out *)a.dX + (int64_t)n * a.dx_img;  // offsets inside one image fit 31 bits (host check)
         const float sc = MODE == MODE_I8 ? 1.0f : a.scale.get();
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {

@@ -16,6 +16,7 @@ struct ConvGeom {
     int st;      // stride
     int Kp;      // K rounded up to the chunk length (dX reduction padding)
     int PQp;     // P*Q rounded up to the K step (dW reduction padding)
+    int Ct, Kt;  // channels of the tensors that hold X/dX and the gradient (C, K unless this is one group's block)
 };
 
 template <int MODE> struct GradElem;      // element type of the gradient operand per mode
@@ -51,7 +52,7 @@ template <int MODE> struct ConvDxGradLoader {
         const int hw = g.H * g.Wd;
         const int n = m / hw, rem = m - n * hw;
         const int h = rem / g.Wd;
-        return Row{(int64_t)n * g.K * g.P * g.Q, h, rem - h * g.Wd, m < g.N * hw};
+        return Row{(int64_t)n * g.Kt * g.P * g.Q, h, rem - h * g.Wd, m < g.N * hw};
     }
     __device__ Raw fetch(const Row &rw, int kk0) const
     {
@@ -87,7 +88,7 @@ template <int MODE> struct ConvDwGradLoader {
         const int n = kk0 / g.PQp, pq0 = kk0 - n * g.PQp;
         const int pq = g.P * g.Q, nv = pq - pq0;
         if (!rw.ok || n >= g.N || nv <= 0) return raw_zero<Raw>();
-        return RunLoad<KCH, Raw, T>::run(base + ((int64_t)n * g.K + rw.k) * pq + pq0, nv);
+        return RunLoad<KCH, Raw, T>::run(base + ((int64_t)n * g.Kt + rw.k) * pq + pq0, nv);
     }
 };
 
@@ -99,7 +100,7 @@ template <class T> __device__ __forceinline__ void conv_act_walk(const T *X, con
 {
     const int n = kk0 / g.PQp, pq0 = kk0 - n * g.PQp;
     int p = pq0 / g.Q, q = pq0 - p * g.Q;
-    const T *img = X + ((int64_t)n * g.C + c) * g.H * g.Wd;
+    const T *img = X + ((int64_t)n * g.Ct + c) * g.H * g.Wd;
     const bool n_ok = n < g.N;
     for (int j = 0; j < kch; ++j) {
         const int h = p * g.st + r - g.pad, w = q * g.st + s - g.pad;
@@ -178,11 +179,11 @@ template <> struct ConvDwActLoader<MODE_I8> {
 
 // dX output: row m = (n,hw), col c  ->  dX[n][c][hw]
 struct ConvDxOut {
-    int C, HW;
+    int Ct, HW;                 // channels of the tensor that holds dX
     __device__ int64_t operator()(int row, int col) const
     {
         const int n = row / HW, hw = row - n * HW;
-        return ((int64_t)n * C + col) * HW + hw;
+        return ((int64_t)n * Ct + col) * HW + hw;
     }
 };
 

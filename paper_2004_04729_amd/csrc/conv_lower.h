@@ -14,7 +14,7 @@ namespace dbp {
 
 // codes [N][K][PQ] -> [K][N*PQ].  One thread per group of 4 bytes when PQ is a multiple of 4 (VEC = 4), else per byte.
 template <int VEC>
-__global__ __launch_bounds__(256) void conv_codes_kmajor_kernel(const int8_t *src, int8_t *dst, int N, int K, int PQ)
+__global__ __launch_bounds__(256) void conv_codes_kmajor_kernel(const int8_t *src, int8_t *dst, int N, int K, int PQ, int Kt)
 {
     const int64_t row = (int64_t)N * PQ, total = (int64_t)K * row / VEC;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void conv_codes_kmajor_kernel(const int8_t *sr
         const int k = (int)(e / row);
         const int64_t np = e - (int64_t)k * row;
         const int n = (int)(np / PQ), pq = (int)(np - (int64_t)n * PQ);
-        const int8_t *s = src + ((int64_t)n * K + k) * PQ + pq;
+        const int8_t *s = src + ((int64_t)n * Kt + k) * PQ + pq;          // Kt: planes per image of the source tensor
         if constexpr (VEC == 4) *(uint32_t *)(dst + e) = *(const uint32_t *)s;
         else dst[e] = *s;
     }
@@ -32,6 +32,7 @@ struct Im2colArgs {
     const void *X;             // [N][C][H][Wd]
     void       *col;           // [N*P*Q][C*R*S]
     int N, C, H, Wd, R, S, pad, st, P, Q;
+    int Ct;                    // channels of the tensor that holds X (C unless this is one group's block)
     int CT, ctiles;            // channels per workgroup; ceil(C / CT)
     int PB, bands;             // output rows per workgroup; ceil(P / PB)
     int pitch;                 // LDS elements per channel (the band's input rows, plus one when that makes it odd)
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256) void conv_im2col_kernel(Im2colArgs a)
     }
     // ---- load: element i = (c, j), j along the band's rows (contiguous in memory) ----
     if (per_c > 0) {
-        const T *X = (const T *)a.X + (((int64_t)n * a.C + c0) * a.H + h_lo) * a.Wd;
+        const T *X = (const T *)a.X + (((int64_t)n * a.Ct + c0) * a.H + h_lo) * a.Wd;
         const int HW = a.H * a.Wd, dc = 256 / per_c, dj = 256 - dc * per_c;
         int c = threadIdx.x / per_c, j = threadIdx.x - c * per_c;
         while (c < nc) {

@@ -369,7 +369,9 @@ __global__ __launch_bounds__(256) void fc_rows_reduce_kernel(const float *partia
 // wavefront, four wavefronts per workgroup.  The walk goes over the tiles of the workgroup's planes in chunks of up to 256
 // tiles: their entry counts are scanned, and the entries of as many tiles as fit are copied into LDS as (p, q, code,
 // plane) records -- at high sparsity most tiles are empty and one chunk (three barriers) covers hundreds of planes.
-struct ConvGatherGeom { int N, C, H, Wd, K, R, S, pad, st, P, Q, cpw; Gate gate; };   // cpw: channels per wavefront
+// cpw: channels per wavefront.  Ct, Kt: channels of the tensors that hold X/dX and the codes, k_first: the first code plane
+// of this problem inside an image's Kt planes (C, K, 0 unless the problem is one group of a grouped convolution).
+struct ConvGatherGeom { int N, C, H, Wd, K, R, S, pad, st, P, Q, cpw; int Ct, Kt, k_first; Gate gate; };
 
 constexpr int kChunkCap = 1024;                           // entry records per chunk (a tile has at most 256)
 
@@ -432,11 +434,11 @@ __global__ __launch_bounds__(256) void conv_dw_gather_kernel(FormatView f, const
     const int c = ((int)blockIdx.x * 4 + wave) * g.cpw + cl;
     const bool own = cl < g.cpw && c < g.C;
     const int r = tap / g.S, s = tap - r * g.S, tpr = (int)f.tiles_per_row, HW = g.H * g.Wd;
-    const int n_walk = g.N * tpr, img = g.C * HW;          // elements of X per image (the host keeps N*C*H*Wd below 2^31)
+    const int n_walk = g.N * tpr, img = g.Ct * HW;         // elements of X per image (the host keeps N*Ct*H*Wd below 2^31)
     const XT *xc = X + (own ? c : 0) * HW;
     AccT acc = 0;
     for (int i0 = 0; i0 < n_walk;) {
-        conv_gather_chunk(f, k, g.K, tpr, i0, n_walk, g.Q, ch);     // plane j of the walk = image j: row j*K + k
+        conv_gather_chunk(f, g.k_first + k, g.Kt, tpr, i0, n_walk, g.Q, ch);     // plane j of the walk = image j: row j*Kt + k_first + k
         const int n_ent = ch.n_ent;
         i0 += ch.n_tiles;
         // eight unconditional loads at a time (pixels outside the image read element 0 and add nothing): the loop is
@@ -483,7 +485,7 @@ __global__ __launch_bounds__(256) void conv_dx_gather_kernel(FormatView f, const
     const float *wl = W + ((int64_t)(own ? c : 0) * g.R + r) * g.S + s;          // + k * C*R*S
     const int CRS = g.C * RS;
     for (int i0 = 0; i0 < n_walk;) {
-        conv_gather_chunk(f, (int64_t)n * g.K, 1, tpr, i0, n_walk, g.Q, ch);     // plane j of the walk = channel k = j
+        conv_gather_chunk(f, (int64_t)n * g.Kt + g.k_first, 1, tpr, i0, n_walk, g.Q, ch);     // plane j of the walk = channel k = j
         const int n_ent = ch.n_ent;
         i0 += ch.n_tiles;
         // Four entries at a time: their weights are loaded together (at high sparsity every entry is another plane k, and
@@ -510,7 +512,7 @@ __global__ __launch_bounds__(256) void conv_dx_gather_kernel(FormatView f, const
     const float step = step_arg.get();
     const int nc = min(n_planes, g.C - c_first);
     // plane j of the tile is channel c_first + j (wavefront j / cpw, channel j % cpw of its group)
-    float *out = dX + ((int64_t)n * g.C + c_first) * HW;
+    float *out = dX + ((int64_t)n * g.Ct + c_first) * HW;
     for (int i = threadIdx.x; i < nc * HW; i += 256) out[i] = step * cg_planes[i];
 }
 
@@ -532,6 +534,7 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
     ConvGatherGeom g;
     g.N = (int)a.N; g.C = (int)a.C; g.H = (int)a.H; g.Wd = (int)a.Wd; g.K = (int)a.K; g.R = (int)a.R; g.S = (int)a.S;
     g.pad = (int)a.pad; g.st = (int)a.stride; g.gate = a.gate;
+    g.Ct = (int)a.ct(); g.Kt = (int)a.kt(); g.k_first = (int)a.k_first;
     g.P = (int)((a.H + 2 * a.pad - a.R) / a.stride + 1); g.Q = (int)((a.Wd + 2 * a.pad - a.S) / a.stride + 1);
     const int RS = g.R * g.S, cpw_max = 64 / RS;
     const Scale step{a.step, a.step_dev};

@@ -87,6 +87,7 @@ ConvGeom make_geom(const ConvArgs &a, int kch, int kstep)
     g.Q = (g.Wd + 2 * g.pad - g.S) / g.st + 1;
     g.Kp = (g.K + kch - 1) / kch * kch;
     g.PQp = (g.P * g.Q + kstep - 1) / kstep * kstep;
+    g.Ct = (int)a.ct(); g.Kt = (int)a.kt();
     return g;
 }
 
@@ -248,6 +249,7 @@ ConvDwPlan conv_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, 
     if ((H * Wd) % 4 || (P * Q) % 4) return pl;                     // rows are fetched as aligned 4-element pieces
     if (C * H * Wd >= ((int64_t)1 << 29) || K * P * Q >= ((int64_t)1 << 29) || K * C * R * S >= ((int64_t)1 << 31)) return pl;
     k.N = (int)N; k.C = (int)C; k.H = (int)H; k.Wd = (int)Wd; k.K = (int)K; k.P = (int)P; k.Q = (int)Q; k.pad = (int)pad;
+    k.Ct = k.C; k.Kt = k.K;                                          // one group of a grouped layer: set at the launch
     const int FRAG = i8 ? 16 : 8, KSTEP = 2 * FRAG, ESZ = i8 ? 1 : 2, PL = i8 ? 1 : 3, CQL = 128, XQL = 64;
     int64_t pw = Wd + pad;
     const int64_t over = S - 1 - pad > 0 ? S - 1 - pad : 0;
@@ -334,6 +336,7 @@ ConvDwI8Plan conv_dw_i8_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_
     }
     if (!pl.ok) return pl;
     k.N = (int)N; k.C = (int)C; k.H = (int)H; k.Wd = (int)Wd; k.K = (int)K; k.PW = pw; k.CPR = cpr; k.DC = dc;
+    k.Ct = k.C; k.Kt = k.K;
     k.tiles_k = (int)((K + 63) / 64); k.tiles_c = (int)((C + 63) / 64);
     const int64_t tiles = (int64_t)k.tiles_k * k.tiles_c, units = N * k.chunks;
     if (units >= ((int64_t)1 << 31) || tiles > 65535) { pl.ok = false; return pl; }
@@ -590,7 +593,7 @@ hipError_t launch_conv1x1_dw(const ConvArgs &a, const Conv1x1Plan &pl, const int
     p.k_per_split = pl.imgs_per_split * pl.spi * pl.kt; p.n_split = pl.n_split; p.tiles_m = pl.tiles_m;
     p.n_items = pl.tiles_m * pl.tiles_n * pl.n_split;
     p.scale = scale; p.a_kfast = 1;
-    p.nt_pq = (int)PQ; p.nt_spi = pl.spi; p.nt_a_img = a.K * PQ; p.nt_b_img = a.C * PQ;
+    p.nt_pq = (int)PQ; p.nt_spi = pl.spi; p.nt_a_img = a.kt() * PQ; p.nt_b_img = a.ct() * PQ;
     pa.prob[1] = p;
     pa.prob[1].n_items = 0;
     pa.stats = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
@@ -913,6 +916,13 @@ __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *p, int64_t n)
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
+hipError_t launch_zero_words(void *p, int64_t n_words, hipStream_t s)
+{
+    const int fb = (int)((n_words + 255) / 256 < 8192 ? (n_words + 255) / 256 : 8192);
+    hipLaunchKernelGGL(zero_words_kernel, dim3(fb < 1 ? 1 : fb), dim3(256), 0, s, (uint32_t *)p, n_words);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------
 // Convolution (fast dX kernel: any stride; fast dW kernels: stride 1; the generic kernel serves the rest).
 // ------------------------------------------------------------------------------------------------
@@ -950,14 +960,16 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
             uint32_t *dst = (uint32_t *)((char *)a.scratch + rbw);
             const int64_t dwords = a.N * a.K * (plane / 4);
             const int pbk = (int)((dwords + 255) / 256 < 4096 ? (dwords + 255) / 256 : 4096);
-            hipLaunchKernelGGL(conv_dx_pad_codes_kernel, dim3(pbk), dim3(256), 0, s, (const int8_t *)grad, dst, a.N * a.K, (int)PQ, (int)plane);
+            hipLaunchKernelGGL(conv_dx_pad_codes_kernel, dim3(pbk), dim3(256), 0, s, (const int8_t *)grad, dst, a.N * a.K, (int)PQ, (int)plane,
+                               (int)a.K, (int)a.kt());
             return (const int8_t *)dst;
         };
         if (a.stride != 1 && codes_ok) {
             ConvDxStridedPlan sp = conv_dx_strided_plan(a, I8);
             if (sp.ok && a.plan_only) return hipSuccess;
             if (sp.ok) {
-                if (sp.zero_fill) {
+                if (sp.zero_fill && !a.dx_zeroed) {
+                    // (one group of a grouped layer never comes here: its dX is not contiguous and the caller has cleared it)
                     const int64_t n = a.N * a.C * a.H * a.Wd;                 // fp32 and int32 zeros are the same bytes
                     const int fb = (int)((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
                     hipLaunchKernelGGL(zero_words_kernel, dim3(fb), dim3(256), 0, s, (uint32_t *)a.dX, n);
@@ -969,6 +981,7 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
                     for (int i = 0; i < sp.multi.n; ++i) {
                         ConvDxArgs &k = sp.multi.cls[i];
                         k.codes = kc; k.dX = a.dX; k.scale = scale; k.gate = a.gate;
+                        k.code_img = (pad_codes ? a.K : a.kt()) * k.PQ; k.dx_img = a.ct() * k.oPI;
                         k.wp = (const uint4 *)a.scratch + (int64_t)sp.tap_base[i] * KG * PL * Cp;
                     }
                     if (sp.nb == 7)      hipLaunchKernelGGL((conv_dx_multi_kernel<7, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
@@ -983,6 +996,7 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
         if (pl.ok && codes_ok) {
             ConvDxArgs &k = pl.args;
             k.codes = kernel_codes(); k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale; k.gate = a.gate;
+            k.code_img = (pad_codes ? a.K : a.kt()) * k.PQ; k.dx_img = a.ct() * k.PI;
             prepare(k.R * k.S, k.KG, k.Cp, nullptr);
             if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
             else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
@@ -1005,7 +1019,7 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
     const int M = g.N * g.H * g.Wd, Kred = g.R * g.S * g.Kp;
     ConvDxGradLoader<MODE_G> al{(const typename GradElem<MODE_G>::T *)grad, g};
     MatrixLoader<MODE_G, false, false> bl{Wt, g.C, g.C, Kred};
-    ConvDxOut om{g.C, g.H * g.Wd};
+    ConvDxOut om{g.Ct, g.H * g.Wd};
     return run_gemm<MODE_G>(al, bl, om, M, g.C, Kred, k_step<MODE_G>(), scale, (Acc *)a.dX,
                             (char *)a.scratch + rb, a.scratch_bytes - rb, s);
 }
@@ -1021,7 +1035,7 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
             if (a.plan_only) return hipSuccess;
             ConvDwI8Args &k = p8.args;
             k.codes = (const int8_t *)grad; k.X = (const int8_t *)a.X; k.dW = (int32_t *)a.dW; k.partial = (int32_t *)((char *)a.scratch + rb);
-            k.gate = a.gate;
+            k.gate = a.gate; k.Ct = (int)a.ct(); k.Kt = (int)a.kt();
             return launch_conv_dw_i8(p8, s);
         }
     }
@@ -1033,6 +1047,7 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
             if (a.plan_only) return hipSuccess;
             ConvDwArgs &k = pl.args;
             k.codes = (const int8_t *)grad; k.X = a.X; k.dW = a.dW; k.partial = (char *)a.scratch + rb; k.scale = scale; k.gate = a.gate;
+            k.Ct = (int)a.ct(); k.Kt = (int)a.kt();
             return a.pad == 1 ? launch_conv_dw_fast<MODE, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE, 3, 3, 0, 1>(pl, s);
         }
     }
@@ -1056,10 +1071,10 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
             const int PQ = lp.im.P * lp.im.Q;
             const int64_t groups = (int64_t)a.K * lp.NPQ / (PQ % 4 == 0 ? 4 : 1);
             const int cb = (int)((groups + 255) / 256 < 8192 ? (groups + 255) / 256 : 8192);
-            if (PQ % 4 == 0) hipLaunchKernelGGL(conv_codes_kmajor_kernel<4>, dim3(cb), dim3(256), 0, s, (const int8_t *)grad, ck, (int)a.N, (int)a.K, PQ);
-            else             hipLaunchKernelGGL(conv_codes_kmajor_kernel<1>, dim3(cb), dim3(256), 0, s, (const int8_t *)grad, ck, (int)a.N, (int)a.K, PQ);
+            if (PQ % 4 == 0) hipLaunchKernelGGL(conv_codes_kmajor_kernel<4>, dim3(cb), dim3(256), 0, s, (const int8_t *)grad, ck, (int)a.N, (int)a.K, PQ, (int)a.kt());
+            else             hipLaunchKernelGGL(conv_codes_kmajor_kernel<1>, dim3(cb), dim3(256), 0, s, (const int8_t *)grad, ck, (int)a.N, (int)a.K, PQ, (int)a.kt());
             Im2colArgs im = lp.im;
-            im.X = a.X; im.col = col;
+            im.X = a.X; im.col = col; im.Ct = (int)a.ct();
             const int grid = (int)(a.N * im.bands * im.ctiles);
             using XT = typename std::conditional<MODE == MODE_I8, int8_t, float>::type;
             if (lp.vec4) hipLaunchKernelGGL((conv_im2col_kernel<XT, 4>), dim3(grid), dim3(256), lp.lds_bytes, s, im);
