@@ -65,6 +65,16 @@ def main():
         for i in range(warm):
             fn(i)
         torch.cuda.synchronize()
+        # after an idle phase (host-side set-up, the CPU baseline) the GPU takes a while to return to its working clocks: keep
+        # warming until about 30 ms of calls have run, so that every row is a steady-state figure like the headline's
+        t0 = time.perf_counter()
+        i = warm
+        while time.perf_counter() - t0 < 0.03:
+            fn(i)
+            i += 1
+            if i % 8 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
         ev[0].record()
         for i in range(iters):
