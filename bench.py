@@ -555,6 +555,60 @@ def bench_rows(dbp, workloads, torch, np, med, timed, stream, conv_buffers, conv
                              "ms_matrix_cores": med(lambda i: linear_call(bl, step=step, path=dbp.PATH_MFMA), 10) * 1e3,
                              "ms_gather": med(lambda i: linear_call(bl, step=step, path=dbp.PATH_GATHER), 10) * 1e3}
     res["fc_256x4096x16384_density_gate"] = gated
+    del bl
+
+    # ---- top-k sparsifier against the dithered quantiser on identical kernels (Sec. "Comparison to meProp"): the 256 x 4096 x 4096
+    # layer, k chosen so that both leave the same share of nonzeros (Delta = 8 std: 8.8 %)
+    p2 = workloads.config2(8.0)[1]
+    Bq, iq, oq = p2.dims
+    dq, Wq, Xq = (torch.from_numpy(a).to(dev) for a in (p2.delta, p2.W, p2.X))
+    cq = torch.empty((Bq, oq), dtype=torch.int8, device=dev)
+    fq = torch.empty(dbp.format_layout(Bq, oq)["total_bytes"], dtype=torch.uint8, device=dev)
+    sq = torch.zeros(32, dtype=torch.uint8, device=dev)
+    tq = torch.empty(dbp.topk_workspace_bytes(Bq, 1), dtype=torch.uint8, device=dev)
+    dXq = torch.empty((Bq, iq), dtype=torch.float32, device=dev)
+    dWq = torch.empty((oq, iq), dtype=torch.float32, device=dev)
+    wsq = torch.empty(dbp.linear_workspace_bytes(Bq, iq, oq), dtype=torch.uint8, device=dev)
+    ab = {}
+    t_nsd = med(lambda i: dbp.nsd_quantize(dq, Bq, oq, p2.step, p2.seed, 0, cq, fq, sq, stream), 30)
+    nnz = dbp.Stats.from_tensor(sq).nnz
+    k_top = max(1, round(nnz / Bq))
+    step_top = float(np.abs(p2.delta).max() / 127)
+    for name, quant in (("dithered", lambda i: dbp.nsd_quantize(dq, Bq, oq, p2.step, p2.seed, 0, cq, fq, sq, stream)),
+                        ("top_k", lambda i: dbp.topk_quantize(dq, Bq, oq, 1, k_top, step_top, cq, tq, fq, sq, stream))):
+        tq_ms = med(quant, 30) * 1e3
+        st_now = dbp.Stats.from_tensor(sq)
+        step_now = p2.step if name == "dithered" else step_top
+        ab[name] = {"quantiser_us": tq_ms * 1e3, "sparsity": 1 - st_now.nnz / p2.delta.size, "max_abs_code": st_now.max_abs_code,
+                    "products_matrix_cores_us": med(lambda i: dbp.linear_products(cq, fq, step_now, Wq, Xq, dbp.F32, Bq, iq, oq, dXq, dWq, wsq,
+                                                                                  dbp.PATH_MFMA, stream), 30) * 1e6,
+                    "products_gather_us": med(lambda i: dbp.linear_products(cq, fq, step_now, Wq, Xq, dbp.F32, Bq, iq, oq, dXq, dWq, wsq,
+                                                                            dbp.PATH_GATHER, stream), 30) * 1e6}
+    ab["k_per_example"] = k_top
+    ab["note"] = ("same kernels after the quantiser; top-k keeps k per example (Delta = max|delta|/127: survivors below Delta/2 round to 0), "
+                  "the dithered quantiser the same share in expectation")
+    res["fc_256x4096x4096_topk_vs_dithered"] = ab
+    del dq, Wq, Xq, cq, fq, dXq, dWq, wsq
+
+    # ---- grouped convolution: N=64, 256 -> 256, 28 x 28, 3 x 3 (a ResNeXt-like block), Delta = 8 std, against the group count
+    rng = np.random.default_rng(6)
+    Ng, Cg_, Hg, Kg_ = 64, 256, 28, 256
+    dg = rng.laplace(0, 5e-4, size=(Ng, Kg_, Hg, Hg)).astype(np.float32)
+    step_g = workloads.step_from_std(dg, 8.0)
+    Xg = torch.from_numpy(np.maximum(rng.standard_normal((Ng, Cg_, Hg, Hg)), 0).astype(np.float32)).to(dev)
+    dgd = torch.from_numpy(dg).to(dev)
+    cg = torch.empty(dg.shape, dtype=torch.int8, device=dev)
+    dXg = torch.empty_like(Xg)
+    grouped = {}
+    for groups in (1, 2, 4, 32):
+        Wg = torch.from_numpy((rng.standard_normal((Kg_, Cg_ // groups, 3, 3)) * 0.05).astype(np.float32)).to(dev)
+        dWg = torch.empty_like(Wg)
+        wsg = torch.empty(dbp.conv2d_grouped_workspace_bytes(Ng, Cg_, Hg, Hg, Kg_, 3, 3, 1, 1, groups), dtype=torch.uint8, device=dev)
+        t = med(lambda i: dbp.dithered_conv2d_backward_grouped(dgd, Wg, Xg, dbp.F32, Ng, Cg_, Hg, Hg, Kg_, 3, 3, 1, 1, groups, step_g, 1, 0, cg, dXg,
+                                                               dWg, wsg, None, dbp.PATH_MFMA, stream), 20)
+        flops = 2 * 2.0 * dg.size * (Cg_ // groups) * 9
+        grouped["groups=%d" % groups] = {"ms": t * 1e3, "dense_equiv_tflops": flops / t / 1e12}
+    res["grouped_conv_n64_256to256_28x28_3x3"] = grouped
     return res
 
 

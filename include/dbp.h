@@ -224,9 +224,11 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
  * and output channels are cut into `groups` equal consecutive blocks and output channel k sees only the input channels of
  * block k / (K/groups).  Eqs. (qdz), (qda), (qdw) as in dithered_conv2d_backward, with
  *   W, dW [K, C/groups, R, S];  X, dX [N, C, H, Wd];  delta, codes [N, K, P, Q]   (groups == 1: dithered_conv2d_backward).
- * One quantiser pass over the whole delta, then the groups run one after the other on the stream as independent layers
- * (N, C/groups, H, Wd, K/groups) on channel blocks of the same tensors, on the kernels of the ungrouped layer; a group
- * with few channels fills little of a 64- or 128-wide matrix-core tile (depthwise layers run, slowly).
+ * One quantiser pass over the whole delta.  With at least 64 input channels per group the groups then run one after the
+ * other on the stream as independent layers (N, C/groups, H, Wd, K/groups) on channel blocks of the same tensors, on the
+ * kernels of the ungrouped layer.  Smaller groups (down to depthwise layers) would fill little of a 64- or 128-channel
+ * matrix-core tile each and cost their own launches: they run as ONE ungrouped layer with block-diagonal weights (the
+ * products outside a channel's group are exact zeros) at the ungrouped layer's cost, whatever the group count.
  * DBP_PATH_AUTO takes the matrix-core kernels (no density dispatch).  workspace: dbp_conv2d_grouped_workspace_bytes.
  * Errors as dithered_conv2d_backward; groups < 1 or not dividing C and K -> DBP_ERR_SHAPE.
  */

@@ -522,6 +522,22 @@ dbp_status check_groups(int64_t C, int64_t K, int64_t groups)
     return DBP_OK;
 }
 
+// Groups of fewer than 64 input channels fill less than one 64-channel dW tile and half of a workgroup's 128 dX channels
+// each, and every group costs its own launches: such layers run as ONE ungrouped layer with block-diagonal weights
+// (measured on N=64, 256->256, 28x28, 3x3: 32 groups 1.74 ms group by group, 0.33 ms this way; 4 groups 0.24 ms group by
+// group).  Scratch: the expanded weights and the ungrouped dW (K*C*R*S 4-byte elements each) before the layer's own.
+bool grouped_as_block_diagonal(int64_t C, int64_t groups) { return groups > 1 && C / groups < 64; }
+size_t block_diagonal_bytes(int64_t C, int64_t K, int64_t R, int64_t S) { return align_up((size_t)(K * C * R * S) * 4, 256); }
+
+size_t grouped_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
+                             int64_t groups)
+{
+    const size_t per_group = conv_scratch_bytes(N, C / groups, H, Wd, K / groups, R, S, pad, stride);
+    if (!grouped_as_block_diagonal(C, groups)) return per_group;
+    const size_t whole = 2 * block_diagonal_bytes(C, K, R, S) + conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride);
+    return whole > per_group ? whole : per_group;                  // the gather path and callers' sizing use one figure
+}
+
 dbp_status conv2d_products_grouped(const int8_t *codes, const void *format, float step, const float *W, const void *X, dbp_dtype x_dtype,
                                    int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
                                    int64_t groups, float *dX, void *dW, void *scratch, size_t scratch_bytes, dbp_path path, hipStream_t s,
@@ -549,6 +565,18 @@ dbp_status conv2d_products_grouped(const int8_t *codes, const void *format, floa
     a.Ct = C; a.Kt = K;
     a.scratch = gather ? nullptr : scratch; a.scratch_bytes = gather ? 0 : scratch_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; a.pending = nullptr; a.gate = Gate{};
+    if (!gather && grouped_as_block_diagonal(C, groups)) {
+        const size_t bd = block_diagonal_bytes(C, K, R, S);
+        float *w_full = (float *)scratch;
+        void *dw_full = (char *)scratch + bd;
+        if (launch_group_weights_expand(W, w_full, K, C, groups, R * S, s) != hipSuccess) return DBP_ERR_DEVICE;
+        a.C = C; a.K = K; a.Ct = 0; a.Kt = 0;
+        a.codes = codes; a.W = w_full; a.X = X; a.dX = dX; a.dW = dW ? dw_full : nullptr;
+        a.scratch = (char *)scratch + 2 * bd; a.scratch_bytes = scratch_bytes - 2 * bd;
+        if (launch_conv_mfma(a, s) != hipSuccess) return DBP_ERR_DEVICE;
+        if (dW && launch_group_dw_extract(dw_full, dW, K, C, groups, R * S, s) != hipSuccess) return DBP_ERR_DEVICE;
+        return DBP_OK;
+    }
     if (!gather && dX && stride != 1 && groups > 1) {
         // output pixels that no tap reaches (a 1x1 kernel with stride 2 ...): the ungrouped launch clears its contiguous dX
         // itself, a group's block of channels is not contiguous, so the whole tensor is cleared once, here
@@ -592,7 +620,7 @@ size_t dbp_conv2d_grouped_workspace_bytes(int64_t N, int64_t C, int64_t H, int64
     int64_t P, Q;
     if (check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q) != DBP_OK || check_groups(C, K, groups) != DBP_OK) return 0;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return 0;
-    return carve(N * K, P * Q, conv_scratch_bytes(N, C / groups, H, Wd, K / groups, R, S, pad, stride)).total;
+    return carve(N * K, P * Q, grouped_scratch_bytes(N, C, H, Wd, K, R, S, stride, pad, groups)).total;
 }
 
 dbp_status dbp_conv2d_products_grouped(const int8_t *codes, const void *format, float step, const float *W, const void *X,
@@ -609,7 +637,7 @@ dbp_status dbp_conv2d_products_grouped(const int8_t *codes, const void *format, 
         if (!format) return DBP_ERR_NULL;
         if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
     } else {
-        const size_t need = conv_scratch_bytes(N, C / groups, H, Wd, K / groups, R, S, pad, stride);
+        const size_t need = grouped_scratch_bytes(N, C, H, Wd, K, R, S, stride, pad, groups);
         if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     }
     return conv2d_products_grouped(codes, format, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, groups, dX, dW, workspace,
@@ -627,7 +655,7 @@ dbp_status dithered_conv2d_backward_grouped(const float *delta, const float *W, 
     dbp_status st = check_grouped_call(W, X, dX, dW, x_dtype, N, C, H, Wd, K, R, S, stride, pad, groups, path, &P, &Q);
     if (st != DBP_OK) return st;
     if (!step_ok(step)) return DBP_ERR_STEP;
-    const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C / groups, H, Wd, K / groups, R, S, pad, stride));
+    const Carve c = carve(N * K, P * Q, grouped_scratch_bytes(N, C, H, Wd, K, R, S, stride, pad, groups));
     if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;

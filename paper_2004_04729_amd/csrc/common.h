@@ -152,6 +152,9 @@ size_t     conv_scratch_bytes(int64_t N, int64_t C, int64_t H, int64_t Wd, int64
 hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t s);
 hipError_t launch_zero_words(void *p, int64_t n_words, hipStream_t s);      // clears n 4-byte words
+// grouped convolution as one ungrouped layer: block-diagonal weights in, diagonal blocks of dW out (products.hip)
+hipError_t launch_group_weights_expand(const float *W, float *full, int64_t K, int64_t C, int64_t groups, int64_t RS, hipStream_t s);
+hipError_t launch_group_dw_extract(const void *full, void *dW, int64_t K, int64_t C, int64_t groups, int64_t RS, hipStream_t s);
 
 // ---- gather path (gather.hip) ------------------------------------------------------------------
 struct FormatView { const uint64_t *bitmap; const uint16_t *tile_nnz; const uint16_t *entries; int64_t tiles_per_row; };

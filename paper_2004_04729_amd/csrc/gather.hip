@@ -1,10 +1,11 @@
 // Gather path of the backward products: walk only the nonzero codes (Sec. "Computational complexity":
 // O(p_nz * m*k*n) multiply-adds instead of O(m*k*n)).  Plain fp32 FMA on the vector ALUs.
 //
-// Fully connected layers: fc_rows_kernel.  A workgroup owns 256 output rows x 128 output columns, stages the dense
-// operand (W for dX, X for dW) through LDS in tiles of 64 reduction indices, and every wavefront walks the nonzero
-// codes of its 16 rows against the staged tile: one LDS read feeds one multiply-add per lane, so the staged tile is
-// shared by all 256 rows and the dense operand leaves HBM / L2 once per workgroup.  The one-row-per-workgroup kernels
+// Fully connected layers: fc_rows_kernel.  A workgroup of 16 wavefronts owns 128 (dX) or 256 (dW) output rows x 256 output
+// columns, stages the dense operand (W for dX, X for dW) through LDS in tiles of 64 reduction indices x 256 columns, and
+// every wavefront walks the nonzero codes of its 8 or 16 rows against the staged tile: one LDS read of a lane's four
+// columns feeds four multiply-adds, so the staged tile is shared by all rows of the block and the dense operand leaves
+// HBM / L2 once per workgroup.  The one-row-per-workgroup kernels
 // further down serve the shapes it declines (odd strides and alignments, int8 activations).
 // Convolutions: conv_d{x,w}_gather_kernel walk the compacted entries of the tile-sparse format.
 #include "common.h"

@@ -645,14 +645,17 @@ __global__ __launch_bounds__(WAVES == 1 ? 256 : 64 * WAVES) void topk_threshold_
 
 hipError_t launch_topk_threshold(const float *delta, int64_t n_vec, int64_t len, int64_t k, uint32_t *thr, hipStream_t s)
 {
-    if (len <= 4096) {
+    // one wavefront per vector only when there are enough vectors to fill the chip with them (1024 SIMDs); few long-ish
+    // vectors get sixteen wavefronts each
+    if (len <= 256 || (len <= 4096 && n_vec >= 2048)) {
         const dim3 grid((unsigned)((n_vec + 3) / 4)), block(256);
         if (len <= 256)       hipLaunchKernelGGL((topk_threshold_kernel<1, 4, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
         else if (len <= 1024) hipLaunchKernelGGL((topk_threshold_kernel<1, 16, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
         else                  hipLaunchKernelGGL((topk_threshold_kernel<1, 64, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
     } else {
         const dim3 grid((unsigned)n_vec), block(1024);
-        if (len <= 16384)      hipLaunchKernelGGL((topk_threshold_kernel<16, 16, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
+        if (len <= 4096)       hipLaunchKernelGGL((topk_threshold_kernel<16, 4, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
+        else if (len <= 16384) hipLaunchKernelGGL((topk_threshold_kernel<16, 16, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
         else if (len <= 65536) hipLaunchKernelGGL((topk_threshold_kernel<16, 64, false>), grid, block, 0, s, delta, n_vec, len, k, thr);
         else                   hipLaunchKernelGGL((topk_threshold_kernel<16, 1, true>), grid, block, 0, s, delta, n_vec, len, k, thr);
     }

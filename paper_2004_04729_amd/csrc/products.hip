@@ -916,6 +916,50 @@ __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *p, int64_t n)
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
+// Grouped convolution with few channels per group, run as ONE ungrouped layer: the weights [K][Cg][RS] are expanded into
+// the block-diagonal [K][C][RS] (zero outside a channel's own group: those products add exact zeros), and the diagonal
+// blocks of the ungrouped dW are copied back.  4-byte elements either way (fp32 weights; fp32 or int32 dW).
+__global__ __launch_bounds__(256) void group_weights_expand_kernel(const uint32_t *W, uint32_t *full, int K, int C, int Cg, int Kg, int RS)
+{
+    const int64_t total = (int64_t)K * C * RS;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int rs = (int)(i % RS);
+        const int64_t kc = i / RS;
+        const int c = (int)(kc % C), k = (int)(kc / C);
+        const bool own = c / Cg == k / Kg;
+        full[i] = own ? W[((int64_t)k * Cg + c % Cg) * RS + rs] : 0u;
+    }
+}
+
+__global__ __launch_bounds__(256) void group_dw_extract_kernel(const uint32_t *full, uint32_t *dW, int K, int C, int Cg, int Kg, int RS)
+{
+    const int64_t total = (int64_t)K * Cg * RS;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int rs = (int)(i % RS);
+        const int64_t kc = i / RS;
+        const int cl = (int)(kc % Cg), k = (int)(kc / Cg);
+        dW[i] = full[((int64_t)k * C + (k / Kg) * Cg + cl) * RS + rs];
+    }
+}
+
+hipError_t launch_group_weights_expand(const float *W, float *full, int64_t K, int64_t C, int64_t groups, int64_t RS, hipStream_t s)
+{
+    const int64_t total = K * C * RS;
+    const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(group_weights_expand_kernel, dim3(blocks), dim3(256), 0, s, (const uint32_t *)W, (uint32_t *)full, (int)K, (int)C,
+                       (int)(C / groups), (int)(K / groups), (int)RS);
+    return hipGetLastError();
+}
+
+hipError_t launch_group_dw_extract(const void *full, void *dW, int64_t K, int64_t C, int64_t groups, int64_t RS, hipStream_t s)
+{
+    const int64_t total = K * (C / groups) * RS;
+    const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(group_dw_extract_kernel, dim3(blocks), dim3(256), 0, s, (const uint32_t *)full, (uint32_t *)dW, (int)K, (int)C,
+                       (int)(C / groups), (int)(K / groups), (int)RS);
+    return hipGetLastError();
+}
+
 hipError_t launch_zero_words(void *p, int64_t n_words, hipStream_t s)
 {
     const int fb = (int)((n_words + 255) / 256 < 8192 ? (n_words + 255) / 256 : 8192);

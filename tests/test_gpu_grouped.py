@@ -58,6 +58,14 @@ CASES = [  # N, C, H, Wd, K, R, S, stride, pad, groups
     (2, 12, 10, 10, 12, 3, 3, 1, 1, 12),        # depthwise
     (1, 8, 6, 6, 16, 5, 5, 3, 2, 8),            # depthwise with a channel multiplier, stride 3
     (2, 70, 8, 8, 130, 3, 3, 1, 1, 1),          # one group: the ungrouped layer through this entry point
+    # 64 and more channels per group: the groups run one after the other on channel blocks of the tensors (fewer: one
+    # ungrouped layer with block-diagonal weights)
+    (3, 128, 14, 14, 192, 3, 3, 1, 1, 2),       # fast dX kernel and 3x3 dW kernel per group
+    (2, 192, 12, 12, 384, 1, 1, 1, 0, 3),       # 1x1: dW on the fully connected form, images strided by the whole tensor
+    (2, 128, 13, 13, 128, 3, 3, 2, 1, 2),       # strided: dX per pixel class, dW lowered or generic
+    (2, 128, 12, 12, 256, 1, 1, 2, 0, 2),       # 1x1 with stride 2: pixel classes without taps, dX cleared once
+    (4, 128, 7, 7, 256, 3, 3, 1, 1, 2),         # 7x7 planes: codes copied into padded planes, planes strided by the whole tensor
+    (2, 130, 9, 11, 70, 5, 3, 1, 2, 2),         # odd sizes: generic kernels
 ]
 
 
@@ -66,12 +74,12 @@ def test_grouped_conv_matrix_core_path_matches_oracle(case):
     _run(*case, path=dbp.PATH_MFMA)
 
 
-@pytest.mark.parametrize("case", [CASES[0], CASES[1], CASES[4], CASES[7]])
+@pytest.mark.parametrize("case", [CASES[0], CASES[1], CASES[4], CASES[7], CASES[10], CASES[12]])
 def test_grouped_conv_gather_path_matches_oracle(case):
     _run(*case, path=dbp.PATH_GATHER, c=8.0)
 
 
-@pytest.mark.parametrize("case", [CASES[1], CASES[2], CASES[3], CASES[4], CASES[7]])
+@pytest.mark.parametrize("case", [CASES[1], CASES[2], CASES[3], CASES[4], CASES[7], CASES[10], CASES[11], CASES[12], CASES[14]])
 def test_grouped_conv_int8_activations(case):
     _run(*case, path=dbp.PATH_MFMA, i8=True)
 

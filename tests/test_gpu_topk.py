@@ -52,7 +52,8 @@ def check(delta, rows, cols, vec_rows, k, step, with_format=True):
 # (rows, cols, vec_rows, k): vector lengths on both sides of every variant's limit (256, 1024, 4096, 16384, 65536)
 CASES = [(1, 1, 1, 1), (5, 3, 1, 2), (9, 256, 1, 10), (7, 257, 1, 25), (300, 500, 1, 30), (13, 1024, 1, 100), (6, 1025, 1, 1),
          (5, 4096, 1, 400), (3, 4097, 1, 37), (16, 16384, 1, 1000), (2, 16385, 1, 500), (3, 65536, 1, 2000), (2, 70001, 1, 3000),
-         (12, 196, 4, 50), (64, 49, 16, 7), (6, 3136, 3, 900), (8, 12544, 8, 5000)]
+         (12, 196, 4, 50), (64, 49, 16, 7), (6, 3136, 3, 900), (8, 12544, 8, 5000),
+         (2100, 300, 1, 20), (2048, 1025, 1, 40), (2052, 2049, 1, 300)]        # many vectors: one wavefront each (16 / 64 keys per lane)
 
 
 @pytest.mark.parametrize("rows,cols,vec_rows,k", CASES)
