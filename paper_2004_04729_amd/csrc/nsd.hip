@@ -90,10 +90,15 @@ __device__ __forceinline__ uint32_t magnitude_key(float x)
 // TOPK replaces the dither by the constant 1/2 (Eq. (nsd) with nu = 0: rounding to the nearest level) and drops the elements
 // whose magnitude is below their vector's threshold: the top-k sparsifier of Sec. "Comparison to meProp" in the same code
 // and tile format.
-template <bool VEC, bool FORMAT, bool EX, bool TOPK = false>
+// COLWALK (per-column bias sums without the format) changes the order of the tiles only: a run of a.run tiles is the same
+// 256-column segment of a.run consecutive rows, so that a lane meets the same four columns on every trip and keeps their
+// code sums in registers: four atomics per lane and run instead of one per nonzero code.  Tile number t then counts
+// (row block, segment, row in block), and the last block's rows past the tensor are empty tiles.
+template <bool VEC, bool FORMAT, bool EX, bool TOPK = false, bool COLWALK = false>
 __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
 {
     static_assert(!(EX && TOPK), "the top-k sparsifier takes none of the layer extensions");
+    static_assert(!COLWALK || (EX && !FORMAT), "the column walk serves the bias sums of a pass that writes no format");
     const int lane = threadIdx.x & 63;
     const int wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t n_waves = (int64_t)gridDim.x * 4;
@@ -144,6 +149,14 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
     int in_run = 0;
     int64_t row = t / a.tiles_per_row;
     int64_t seg = t - row * a.tiles_per_row;
+    int bias_acc[4] = {0, 0, 0, 0};                                   // COLWALK: code sums of this lane's four columns in the run
+    // COLWALK: unit u = t / run is (row block u / tiles_per_row, segment u % tiles_per_row); the run walks the block's rows
+    auto colwalk_place = [&](int64_t tt, int64_t &r, int64_t &sg) {
+        const int64_t u = tt / a.run, rb = u / a.tiles_per_row;
+        sg = u - rb * a.tiles_per_row;
+        r = rb * a.run + (tt - u * a.run);
+    };
+    if constexpr (COLWALK) colwalk_place(t, row, seg);
 
     auto tile_base = [&](int64_t r, int64_t sg) { return r * a.cols + sg * DBP_TILE; };
     auto load_tile = [&](const float *tensor, int64_t base, int valid, float (&x)[4]) {
@@ -169,6 +182,7 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
     if (t < a.n_tiles) {
         base = tile_base(row, seg);
         valid = (int)min((int64_t)DBP_TILE, a.cols - seg * DBP_TILE);
+        if (COLWALK && row >= a.rows) valid = 0;                       // a row past the tensor: an empty tile
         load_tile(a.delta, base, valid, x);
         if (masked) load_tile(a.act, base, valid, m);
     }
@@ -180,13 +194,22 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
         int64_t t_next, row_next, seg_next, base_next;
         if (!jump) {                                                   // next tile of the run: it starts right
             t_next = t + 1; seg_next = seg + 1; row_next = row;        // after this one, also across a row end
-            if (seg_next == a.tiles_per_row) { seg_next = 0; ++row_next; }
-            base_next = base + valid;
+            if constexpr (COLWALK) {                                   // (column walk: the same segment of the next row)
+                seg_next = seg; row_next = row + 1;
+                base_next = base + a.cols;
+            } else {
+                if (seg_next == a.tiles_per_row) { seg_next = 0; ++row_next; }
+                base_next = base + valid;
+            }
             ++in_run;
         } else {                                                       // first tile of this wavefront's next run
             t_next = t + (n_waves - 1) * a.run + 1;
-            row_next = row + a.wave_stride_rows; seg_next = seg + a.wave_stride_segs;
-            if (seg_next >= a.tiles_per_row) { seg_next -= a.tiles_per_row; ++row_next; }
+            if constexpr (COLWALK) {
+                colwalk_place(t_next, row_next, seg_next);
+            } else {
+                row_next = row + a.wave_stride_rows; seg_next = seg + a.wave_stride_segs;
+                if (seg_next >= a.tiles_per_row) { seg_next -= a.tiles_per_row; ++row_next; }
+            }
             base_next = tile_base(row_next, seg_next);
             in_run = 0;
         }
@@ -194,6 +217,7 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
         int valid_next = 0;
         if (t_next < a.n_tiles) {
             valid_next = (int)min((int64_t)DBP_TILE, a.cols - seg_next * DBP_TILE);
+            if (COLWALK && row_next >= a.rows) valid_next = 0;
             load_tile(a.delta, base_next, valid_next, x_next);
             if (masked) load_tile(a.act, base_next, valid_next, m_next);
         }
@@ -267,9 +291,22 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
             if (a.bias_mode == 0) {
                 // per column; columns past the row's end hold x = 0 -> code 0 and add nothing
                 int64_t *col = a.bias_sums + seg * DBP_TILE + c_in;
+                if constexpr (COLWALK) {
+                    // at most 16384 rows of |code| <= 127 per run: the 32-bit sums cannot overflow
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (k[j] != 0) atomicAdd((unsigned long long *)(col + j), (unsigned long long)(long long)k[j]);
+                    for (int j = 0; j < 4; ++j) bias_acc[j] += k[j];
+                    if (last_of_run) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            if (bias_acc[j] != 0) atomicAdd((unsigned long long *)(col + j), (unsigned long long)(long long)bias_acc[j]);
+                            bias_acc[j] = 0;
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (k[j] != 0) atomicAdd((unsigned long long *)(col + j), (unsigned long long)(long long)k[j]);
+                }
             } else {
                 int sum = (k[0] + k[1]) + (k[2] + k[3]);
 #pragma unroll
@@ -693,6 +730,19 @@ hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s, StatsJob *defer)
     // occupancy of 256 CUs) busy, at most kMaxRun; beyond kNsdMaxBlocks workgroups the runs are grid-strided.
     int64_t run = a.n_tiles / 8192;
     run = run < 1 ? 1 : run > kMaxRun ? kMaxRun : run;
+    // Per-column bias sums without the format: runs go down the rows of one 256-column segment (sums in registers, see
+    // nsd_kernel), as many rows as leave 16384 runs for the chip, at most 64; a.n_tiles then counts the row blocks' tiles,
+    // the empty ones past the last row included.
+    bool colwalk = false;
+    if (a.bias_sums && a.bias_mode == 0 && !a.bitmap) {
+        int64_t rb = a.n_tiles / 16384;
+        rb = rb > 64 ? 64 : rb;
+        if (rb >= 2) {
+            colwalk = true;
+            run = rb;
+            a.n_tiles = a.tiles_per_row * ((a.rows + rb - 1) / rb) * rb;
+        }
+    }
     a.run = (int)run;
     int64_t blocks = (a.n_tiles + 4 * run - 1) / (4 * run);
     const int64_t max_blocks = use_atomics ? 256 : kNsdMaxBlocks;
@@ -719,6 +769,9 @@ hipError_t launch_nsd(const NsdArgs &a_in, hipStream_t s, StatsJob *defer)
         else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false, false>), grid, block, 0, s, a);
         else if (a.bitmap)         hipLaunchKernelGGL((nsd_kernel<false, true, false>), grid, block, 0, s, a);
         else                       hipLaunchKernelGGL((nsd_kernel<false, false, false>), grid, block, 0, s, a);
+    } else if (colwalk) {
+        if (vec)                   hipLaunchKernelGGL((nsd_kernel<true, false, true, false, true>), grid, block, 0, s, a);
+        else                       hipLaunchKernelGGL((nsd_kernel<false, false, true, false, true>), grid, block, 0, s, a);
     } else {
         if (vec && a.bitmap)       hipLaunchKernelGGL((nsd_kernel<true, true, true>), grid, block, 0, s, a);
         else if (vec)              hipLaunchKernelGGL((nsd_kernel<true, false, true>), grid, block, 0, s, a);

@@ -108,6 +108,25 @@ def test_fused_mask_and_bias_per_column(rows, cols, with_format):
     assert np.array_equal(grad, g_ref)
 
 
+@pytest.mark.parametrize("rows,cols", [(5000, 1700), (33001, 520), (66000, 1030), (530003, 257)])
+def test_bias_per_column_on_tall_matrices_walks_the_columns(rows, cols):
+    # from 32768 tiles on, a pass without the format keeps the column sums in registers over runs of 2 .. 64 rows of one
+    # 256-column segment (here 2, 6, 20 and 64 rows; the last three with rows past the tensor in the last run)
+    import paper_2004_04729_amd as dbp
+    from oracle import oracle as O
+    rng = np.random.default_rng(rows + cols)
+    d = rng.laplace(0, 1e-3, size=(rows, cols)).astype(np.float32)
+    z = rng.standard_normal((rows, cols)).astype(np.float32)
+    step = float(np.float32(6e-3))
+    codes, sums, grad, st = _run_nsd_ex(d, z, rows, cols, step, 9, dbp.BIAS_PER_COLUMN, cols, with_format=False)
+    k_ref, st_ref = O.nsd(O.relu_backward(d, z), step, 9)
+    assert np.array_equal(codes, k_ref)
+    assert (st.nnz, st.n_saturated, st.n_nonfinite, st.max_abs_code) == (st_ref.nnz, st_ref.n_saturated, st_ref.n_nonfinite, st_ref.max_abs_code)
+    s_ref, g_ref = O.bias_grad(k_ref, rows, cols, True, cols, step)
+    assert np.array_equal(sums, s_ref)
+    assert np.array_equal(grad, g_ref)
+
+
 @pytest.mark.parametrize("N,K,PQ", [(1, 1, 1), (3, 5, 49), (4, 24, 196), (2, 7, 1024), (6, 3, 300)])
 def test_fused_mask_and_bias_per_channel(N, K, PQ):
     import paper_2004_04729_amd as dbp
