@@ -453,6 +453,25 @@ def bench_rows(dbp, workloads, torch, np, med, timed, stream, conv_buffers, conv
             row["ms_" + pname] = t * 1e3
         row["sparsity_per_layer"] = [round(1 - dbp.Stats.from_tensor(bq["st"]).nnz / bq["d"].numel(), 4) for bq in sets[0]]
         row["dense_equiv_tflops_auto"] = dense_flops / (row["ms_auto"] * 1e-3) / 1e12
+        # the gather kernels alone on the 4096x4096 layer: the method's own work, 2*nnz*in per product, against the fp32 vector peak
+        g2 = [s_[1] for s_ in sets]
+        Bg, ig, og = g2[0]["p"].dims
+        for bq in g2:
+            dbp.nsd_quantize(bq["d"], Bg, og, bq["p"].step, bq["p"].seed, 0, bq["codes"], None, bq["st"], stream)
+        alg_g = 2.0 * dbp.Stats.from_tensor(g2[0]["st"]).nnz * ig
+        # (the format argument is only read by the gather kernels that serve odd shapes: a buffer of the right size stands in)
+        fmt_g = torch.empty(dbp.format_layout(Bg, og)["total_bytes"], dtype=torch.uint8, device=dev)
+        gk = {}
+        for nm, wdx, wdw in (("dX", True, False), ("dW", False, True)):
+            def gf(i, wdx=wdx, wdw=wdw):
+                bq = g2[i % NSETS]
+                dbp.linear_products(bq["codes"], fmt_g, bq["p"].step, bq["W"], bq["X"], dbp.F32, Bg, ig, og, bq["dX"] if wdx else None,
+                                    bq["dW"] if wdw else None, bq["ws"], dbp.PATH_GATHER, stream)
+            tg = med(gf, 20)
+            gk[nm + "_us"] = tg * 1e6
+            gk[nm + "_algorithmic_tflops"] = alg_g / tg / 1e12
+            gk[nm + "_frac_of_fp32_vector_peak"] = alg_g / tg / 1e12 / PEAK_F32_VECTOR_TFLOPS
+        row["gather_kernels_4096x4096_layer"] = gk
         if c == 8.0:
             def dense_step(i):
                 for bq in sets[i % NSETS]:
