@@ -53,6 +53,7 @@ CASES = [  # N, C, H, Wd, K, R, S, pad
     (2, 64, 30, 30, 40, 3, 3, 1),       # several pixel tiles per image, tile borders inside a row
     (2, 6, 12, 9, 10, 3, 3, 1),         # odd row length: element-wise scatter into the staging buffers
     (17, 70, 8, 8, 130, 3, 3, 1),       # more images than one reduction split takes, partial channel tiles
+    (32, 256, 48, 48, 16, 3, 3, 1),     # dX as two problems of one launch: eight 7-block tiles per image, then three 6-block tiles
 ]
 
 
