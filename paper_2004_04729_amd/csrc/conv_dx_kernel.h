@@ -26,6 +26,7 @@
 // The kernel therefore takes a row and a column padding, a tap count per direction and an output mapping
 // (virtual pixel (i, j) -> real pixel (st*i + ph, st*j + pw)); conv_dx_multi_kernel runs all classes in one launch.
 #pragma once
+#include <type_traits>
 #include "gemm_core.h"
 
 namespace dbp {
@@ -203,7 +204,9 @@ extern __shared__ uint4 cdx_lds[];                           // [2][CDX_KGC][pat
 
 // STRIDED = false: the column padding is the row padding and a pixel's flat index is its place in dX (compile-time
 // facts of the stride-1 launch).
-template <int NB, int MODE, bool STRIDED>
+// RING3: the weight fragments go through three register sets instead of two (tap counts that are a multiple of 3 only; see the
+// loop itself).
+template <int NB, int MODE, bool STRIDED, bool RING3>
 __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
 {
     using TR = CdxTraits<MODE>;
@@ -333,41 +336,100 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
         for (int pl = 0; pl < PL; ++pl) { const uint4 t = p[(int64_t)pl * a.Cp]; dst[pl] = u32x4{t.x, t.y, t.z, t.w}; }
     };
 
-    fetch_chunk(0);
-    u32x4 a0[PL], a1[PL];                                     // weight fragments of kk = 0 / kk = 1 (ping-pong)
-    if (wave_active) load_a(0, 0, 0, a0);
-    __syncthreads();                                          // zero fill done before the first patch writes
-
-    auto multiply = [&](const uint4 *pb, int off, const u32x4 (&af)[PL]) {
-        u32x4 bfrag[NB];
+    // SPLIT: the code fragments of a step are read and multiplied in two groups of pixel blocks (four, then the rest): the
+    // second group's LDS reads run behind the first group's matrix instructions, and the fragments take 16 registers
+    // instead of 28 -- what the third weight set of the loop below needs.
+    auto multiply_blocks = [&](const uint4 *pb, int off, const u32x4 (&af)[PL], auto first, auto count) {
+        constexpr int B0 = decltype(first)::value, BN = decltype(count)::value;
+        u32x4 bfrag[BN];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const uint4 t = pb[lane_cell[nb] + off];
+        for (int nb = 0; nb < BN; ++nb) {
+            const uint4 t = pb[lane_cell[B0 + nb] + off];
             bfrag[nb] = u32x4{t.x, t.y, t.z, t.w};
         }
 #pragma unroll
         for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) Mma<MODE>::run(af[pl], bfrag[nb], acc[nb]);
+            for (int nb = 0; nb < BN; ++nb) Mma<MODE>::run(af[pl], bfrag[nb], acc[B0 + nb]);
+    };
+    auto multiply = [&](const uint4 *pb, int off, const u32x4 (&af)[PL]) {
+        multiply_blocks(pb, off, af, std::integral_constant<int, 0>{}, std::integral_constant<int, NB>{});
+    };
+    auto multiply_split = [&](const uint4 *pb, int off, const u32x4 (&af)[PL]) {
+        constexpr int NB0 = NB > 4 ? 4 : NB;
+        multiply_blocks(pb, off, af, std::integral_constant<int, 0>{}, std::integral_constant<int, NB0>{});
+        if constexpr (NB > NB0) multiply_blocks(pb, off, af, std::integral_constant<int, NB0>{}, std::integral_constant<int, NB - NB0>{});
     };
 
-    for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
-        const int buf = chunk & 1;
-        store_chunk(buf);
-        __syncthreads();
-        if (chunk + 1 < a.n_chunks) fetch_chunk(chunk + 1);   // in flight during the matrix-core phase
-        if (wave_active) {
-            const uint4 *pb = cdx_lds + buf * buf_cells;
-            int r = 0, s = 0;
-            for (int tap = 0; tap < RS; ++tap) {
-                const int tapoff = r * a.pw + s;
-                // the next weight fragment is loaded while the current one is multiplied
-                load_a(chunk, tap, 1, a1);
-                multiply(pb, -tapoff, a0);
-                if (tap + 1 < RS) load_a(chunk, tap + 1, 0, a0);
-                else if (chunk + 1 < a.n_chunks) load_a(chunk + 1, 0, 0, a0);
-                multiply(pb, 2 * a.patch_cells - tapoff, a1);
-                if (++s == a.S) { s = 0; ++r; }
+    fetch_chunk(0);
+    if constexpr (RING3) {
+        // Tap counts that are a multiple of 3 (3x3 kernels above all): the weight fragments go through a ring of THREE register
+        // sets, loaded two multiply steps ahead (a fragment comes from L2, several hundred cycles away; one step ahead, as in
+        // the loop below, the matrix cores waited for it at every step: they were busy 54 % of the kernel on the 56x56
+        // layer).  A step is (tap, half of the chunk's k-groups); six steps = three taps bring the ring back to where it was, so
+        // the sets keep compile-time names.  The loads are the same on every path: a cursor walks the steps in order and stays
+        // on the last one when it gets there (a load on only some paths makes the compiler wait for ALL loads in flight).
+        // The row of a step is a uniform pointer, the lane's place in it a 32-bit index: one address register per plane.
+        const uint32_t wl = (uint32_t)(lhalf * PL * a.Cp + cb * 32 + lcol);
+        int l_chunk = 0, l_tap = 0, l_kk = 0;                     // uniform: the step the next load fetches
+        auto next_load = [&](u32x4 (&dst)[PL]) {
+            const uint4 *row = a.wp + ((int64_t)l_tap * a.KG + l_chunk * CDX_KGC + 2 * l_kk) * kg_stride;
+#pragma unroll
+            for (int pl = 0; pl < PL; ++pl) { const uint4 t = row[wl + (uint32_t)(pl * a.Cp)]; dst[pl] = u32x4{t.x, t.y, t.z, t.w}; }
+            if (l_kk == 0) l_kk = 1;
+            else { l_kk = 0; if (++l_tap == RS) { l_tap = 0; ++l_chunk; } }
+            if (l_chunk == a.n_chunks) { l_chunk = a.n_chunks - 1; l_tap = RS - 1; l_kk = 1; }
+        };
+        u32x4 f0[PL], f1[PL], f2[PL];
+        if (wave_active) { next_load(f0); next_load(f1); }
+        __syncthreads();                                      // zero fill done before the first patch writes
+        for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+            const int buf = chunk & 1;
+            store_chunk(buf);
+            __syncthreads();
+            fetch_chunk(min(chunk + 1, a.n_chunks - 1));      // in flight during the matrix-core phase (the last chunk once more, unused)
+            if (wave_active) {
+                const uint4 *pb = cdx_lds + buf * buf_cells;
+                const int hi = 2 * a.patch_cells;             // the second half of the chunk's k-groups
+                int r = 0, s = 0;
+                for (int tap = 0; tap < RS; tap += 3) {
+                    const int o0 = r * a.pw + s;
+                    if (++s == a.S) { s = 0; ++r; }
+                    const int o1 = r * a.pw + s;
+                    if (++s == a.S) { s = 0; ++r; }
+                    const int o2 = r * a.pw + s;
+                    if (++s == a.S) { s = 0; ++r; }
+                    next_load(f2); multiply_split(pb, -o0, f0);
+                    next_load(f0); multiply_split(pb, hi - o0, f1);
+                    next_load(f1); multiply_split(pb, -o1, f2);
+                    next_load(f2); multiply_split(pb, hi - o1, f0);
+                    next_load(f0); multiply_split(pb, -o2, f1);
+                    next_load(f1); multiply_split(pb, hi - o2, f2);
+                }
+            }
+        }
+    } else {
+        u32x4 a0[PL], a1[PL];                                 // weight fragments of kk = 0 / kk = 1 (ping-pong)
+        if (wave_active) load_a(0, 0, 0, a0);
+        __syncthreads();                                      // zero fill done before the first patch writes
+        for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+            const int buf = chunk & 1;
+            store_chunk(buf);
+            __syncthreads();
+            if (chunk + 1 < a.n_chunks) fetch_chunk(chunk + 1);   // in flight during the matrix-core phase
+            if (wave_active) {
+                const uint4 *pb = cdx_lds + buf * buf_cells;
+                int r = 0, s = 0;
+                for (int tap = 0; tap < RS; ++tap) {
+                    const int tapoff = r * a.pw + s;
+                    // the next weight fragment is loaded while the current one is multiplied
+                    load_a(chunk, tap, 1, a1);
+                    multiply(pb, -tapoff, a0);
+                    if (tap + 1 < RS) load_a(chunk, tap + 1, 0, a0);
+                    else if (chunk + 1 < a.n_chunks) load_a(chunk + 1, 0, 0, a0);
+                    multiply(pb, 2 * a.patch_cells - tapoff, a1);
+                    if (++s == a.S) { s = 0; ++r; }
+                }
             }
         }
     }
@@ -397,11 +459,11 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
     }
 }
 
-template <int NB, int MODE>
+template <int NB, int MODE, bool RING3>
 __global__ __launch_bounds__(256, 2) void conv_dx_kernel(ConvDxArgs a)
 {
     if (a.gate.closed()) return;
-    conv_dx_body<NB, MODE, false>(a, (int)blockIdx.x);
+    conv_dx_body<NB, MODE, false, RING3>(a, (int)blockIdx.x);
 }
 
 // The classes of a strided problem in one launch: workgroups [first[i], first[i + 1]) run class i.
@@ -415,7 +477,7 @@ __global__ __launch_bounds__(256, 2) void conv_dx_multi_kernel(ConvDxMulti m)
     int ci = 0;
     for (int i = 1; i < m.n; ++i) if ((int)blockIdx.x >= m.first[i]) ci = i;
     const ConvDxArgs a = m.cls[ci];
-    conv_dx_body<NB, MODE, true>(a, (int)blockIdx.x - m.first[ci]);
+    conv_dx_body<NB, MODE, true, false>(a, (int)blockIdx.x - m.first[ci]);
 }
 
 }  // namespace dbp

@@ -1042,9 +1042,18 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
             k.codes = kernel_codes(); k.wp = (const uint4 *)a.scratch; k.dX = a.dX; k.scale = scale; k.gate = a.gate;
             k.code_img = (pad_codes ? a.K : a.kt()) * k.PQ; k.dx_img = a.ct() * k.PI;
             prepare(k.R * k.S, k.KG, k.Cp, nullptr);
-            if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
-            else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
-            else                 hipLaunchKernelGGL((conv_dx_kernel<2, MODE_G>), dim3(pl.grid), dim3(256), pl.lds_bytes, s, k);
+            // tap counts that are a multiple of 3 (3x3 above all) take the form with three weight fragment sets in flight
+            const bool ring3 = (k.R * k.S) % 3 == 0;
+            const dim3 grid(pl.grid), block(256);
+            if (ring3) {
+                if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G, true>), grid, block, pl.lds_bytes, s, k);
+                else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G, true>), grid, block, pl.lds_bytes, s, k);
+                else                 hipLaunchKernelGGL((conv_dx_kernel<2, MODE_G, true>), grid, block, pl.lds_bytes, s, k);
+            } else {
+                if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G, false>), grid, block, pl.lds_bytes, s, k);
+                else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G, false>), grid, block, pl.lds_bytes, s, k);
+                else                 hipLaunchKernelGGL((conv_dx_kernel<2, MODE_G, false>), grid, block, pl.lds_bytes, s, k);
+            }
             return hipGetLastError();
         }
     }
