@@ -328,12 +328,20 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
 
     const bool wave_active = cb * 32 < a.C && jw0 < j_end;   // uniform per wave
     const int RS = a.R * a.S;
-    const uint4 *wlane = a.wp + (int64_t)lhalf * PL * a.Cp + cb * 32 + lcol;
     const int64_t kg_stride = (int64_t)PL * a.Cp;            // cells per k-group
-    auto load_a = [&](int chunk, int tap, int kk, u32x4 (&dst)[PL]) {
-        const uint4 *p = wlane + ((int64_t)tap * a.KG + chunk * CDX_KGC + 2 * kk) * kg_stride;
+    // Weight fragments: a step is (tap, half of the chunk's k-groups); its row of the prepared weights is a uniform pointer
+    // and the lane's place in the row a 32-bit index (one address register per plane).  A cursor walks the steps in the
+    // order in which they are multiplied and stays on the last one when it gets there: the loads are the same on every
+    // path (a load on only some paths makes the compiler wait for ALL loads in flight at every step).
+    const uint32_t wl = (uint32_t)(lhalf * PL * a.Cp + cb * 32 + lcol);
+    int l_chunk = 0, l_tap = 0, l_kk = 0;                     // uniform: the step the next load fetches
+    auto next_load = [&](u32x4 (&dst)[PL]) {
+        const uint4 *row = a.wp + ((int64_t)l_tap * a.KG + l_chunk * CDX_KGC + 2 * l_kk) * kg_stride;
 #pragma unroll
-        for (int pl = 0; pl < PL; ++pl) { const uint4 t = p[(int64_t)pl * a.Cp]; dst[pl] = u32x4{t.x, t.y, t.z, t.w}; }
+        for (int pl = 0; pl < PL; ++pl) { const uint4 t = row[wl + (uint32_t)(pl * a.Cp)]; dst[pl] = u32x4{t.x, t.y, t.z, t.w}; }
+        if (l_kk == 0) l_kk = 1;
+        else { l_kk = 0; if (++l_tap == RS) { l_tap = 0; ++l_chunk; } }
+        if (l_chunk == a.n_chunks) { l_chunk = a.n_chunks - 1; l_tap = RS - 1; l_kk = 1; }
     };
 
     // SPLIT: the code fragments of a step are read and multiplied in two groups of pixel blocks (four, then the rest): the
@@ -367,19 +375,7 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
         // sets, loaded two multiply steps ahead (a fragment comes from L2, several hundred cycles away; one step ahead, as in
         // the loop below, the matrix cores waited for it at every step: they were busy 54 % of the kernel on the 56x56
         // layer).  A step is (tap, half of the chunk's k-groups); six steps = three taps bring the ring back to where it was, so
-        // the sets keep compile-time names.  The loads are the same on every path: a cursor walks the steps in order and stays
-        // on the last one when it gets there (a load on only some paths makes the compiler wait for ALL loads in flight).
-        // The row of a step is a uniform pointer, the lane's place in it a 32-bit index: one address register per plane.
-        const uint32_t wl = (uint32_t)(lhalf * PL * a.Cp + cb * 32 + lcol);
-        int l_chunk = 0, l_tap = 0, l_kk = 0;                     // uniform: the step the next load fetches
-        auto next_load = [&](u32x4 (&dst)[PL]) {
-            const uint4 *row = a.wp + ((int64_t)l_tap * a.KG + l_chunk * CDX_KGC + 2 * l_kk) * kg_stride;
-#pragma unroll
-            for (int pl = 0; pl < PL; ++pl) { const uint4 t = row[wl + (uint32_t)(pl * a.Cp)]; dst[pl] = u32x4{t.x, t.y, t.z, t.w}; }
-            if (l_kk == 0) l_kk = 1;
-            else { l_kk = 0; if (++l_tap == RS) { l_tap = 0; ++l_chunk; } }
-            if (l_chunk == a.n_chunks) { l_chunk = a.n_chunks - 1; l_tap = RS - 1; l_kk = 1; }
-        };
+        // the sets keep compile-time names.
         u32x4 f0[PL], f1[PL], f2[PL];
         if (wave_active) { next_load(f0); next_load(f1); }
         __syncthreads();                                      // zero fill done before the first patch writes
@@ -409,24 +405,23 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
             }
         }
     } else {
-        u32x4 a0[PL], a1[PL];                                 // weight fragments of kk = 0 / kk = 1 (ping-pong)
-        if (wave_active) load_a(0, 0, 0, a0);
+        u32x4 a0[PL], a1[PL];                                 // weight fragments of kk = 0 / kk = 1 (ping-pong), one step ahead
+        if (wave_active) next_load(a0);
         __syncthreads();                                      // zero fill done before the first patch writes
         for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
             const int buf = chunk & 1;
             store_chunk(buf);
             __syncthreads();
-            if (chunk + 1 < a.n_chunks) fetch_chunk(chunk + 1);   // in flight during the matrix-core phase
+            fetch_chunk(min(chunk + 1, a.n_chunks - 1));      // in flight during the matrix-core phase (the last chunk once more, unused)
             if (wave_active) {
                 const uint4 *pb = cdx_lds + buf * buf_cells;
                 int r = 0, s = 0;
                 for (int tap = 0; tap < RS; ++tap) {
                     const int tapoff = r * a.pw + s;
                     // the next weight fragment is loaded while the current one is multiplied
-                    load_a(chunk, tap, 1, a1);
+                    next_load(a1);
                     multiply(pb, -tapoff, a0);
-                    if (tap + 1 < RS) load_a(chunk, tap + 1, 0, a0);
-                    else if (chunk + 1 < a.n_chunks) load_a(chunk + 1, 0, 0, a0);
+                    next_load(a0);
                     multiply(pb, 2 * a.patch_cells - tapoff, a1);
                     if (++s == a.S) { s = 0; ++r; }
                 }
