@@ -44,7 +44,7 @@ def main():
     ap.add_argument("--sparsity", type=float, default=0.90, help="target fraction of zero codes of the headline step")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--headline-only", action="store_true", help="skip the rows of the other configurations")
-    ap.add_argument("--probe", choices=["conv_dx", "nsd", "fc2"], default=None,
+    ap.add_argument("--probe", choices=["conv_dx", "conv_dw", "nsd", "fc2"], default=None,
                     help="counter probe: one 1 GiB device copy of known size, then only the named kernel "
                          "(for `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` runs)")
     args = ap.parse_args()
@@ -142,6 +142,13 @@ def main():
                 dbp.conv2d_products(b["codes"], None, p5.step, b["W"], b["X"], xd5, N, Cc, H, Wd, K, R, S, p5.stride, p5.pad, b["dX"], None,
                                     b["ws"], dbp.PATH_MFMA, stream)
             what = "20 launches of conv_dx_weight_prep_kernel + conv_dx_kernel on config 5 (90 % zeros)"
+        elif args.probe == "conv_dw":
+            b = sets5[0]
+            dbp.nsd_quantize(b["d"], N * K, P * Q, p5.step, p5.seed, 0, b["codes"], None, None, stream)
+            for _ in range(20):
+                dbp.conv2d_products(b["codes"], None, p5.step, b["W"], b["X"], xd5, N, Cc, H, Wd, K, R, S, p5.stride, p5.pad, None, b["dW"],
+                                    b["ws"], dbp.PATH_MFMA, stream)
+            what = "20 launches of conv_dw_i8_kernel + conv_dw_reduce_kernel on config 5 (90 % zeros)"
         elif args.probe == "nsd":
             fmt = torch.empty(dbp.format_layout(1 << 16, 1 << 12)["total_bytes"], dtype=torch.uint8, device=dev)
             codes = torch.empty(1 << 28, dtype=torch.int8, device=dev)
