@@ -16,6 +16,8 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-I" + INCLUDE,
          # packed-fp32 VALU forms are disabled on purpose (hipcc's host pass warns it does not know the feature)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument"]
+# extra compiler flags for measurement builds (e.g. -DDBP_NSD_DITHER23, see nsd.hip); never set for the product
+FLAGS += os.environ.get("DBP_HIPCC_EXTRA", "").split()
 
 
 def _compile(src: str) -> str:

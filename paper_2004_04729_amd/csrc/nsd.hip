@@ -241,11 +241,20 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
             }
         } else if (paired) {
             const uint32_t k1c = a.k1 + (uint32_t)(c_tile >> 32) * kC;                 // scalar
+#ifdef DBP_NSD_DITHER23
+            // MEASUREMENT BUILD ONLY (never the product: these codes are not the oracle's): one hash word per ELEMENT and a
+            // 23-bit dither u = (2m+1) * 2^-24, to price the choice of one word per element pair and 16 bits.
+            const uint32_t c0 = (uint32_t)g_tile + 4u * (uint32_t)lane;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                u[j] = __uint_as_float(0x3F800000u | (hash_word(c0 + (uint32_t)j, a.k0, k1c) >> 9)) - 0x1.fffffep-1f;
+#else
             const uint32_t c0 = (uint32_t)c_tile + 2u * (uint32_t)lane;
             const uint32_t hA = hash_word(c0, a.k0, k1c);
             const uint32_t hB = hash_word(c0 + 1u, a.k0, k1c);
             u[0] = dither_from_m16(hA & 0xFFFFu); u[1] = dither_from_m16(hA >> 16);
             u[2] = dither_from_m16(hB & 0xFFFFu); u[3] = dither_from_m16(hB >> 16);
+#endif
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) u[j] = dither_u(g_tile + (uint64_t)(c_in + j), a.k0, a.k1);
