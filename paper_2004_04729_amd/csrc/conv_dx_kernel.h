@@ -379,28 +379,92 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
         u32x4 f0[PL], f1[PL], f2[PL];
         if (wave_active) { next_load(f0); next_load(f1); }
         __syncthreads();                                      // zero fill done before the first patch writes
-        for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
-            const int buf = chunk & 1;
-            store_chunk(buf);
-            __syncthreads();
-            fetch_chunk(min(chunk + 1, a.n_chunks - 1));      // in flight during the matrix-core phase (the last chunk once more, unused)
-            if (wave_active) {
-                const uint4 *pb = cdx_lds + buf * buf_cells;
-                const int hi = 2 * a.patch_cells;             // the second half of the chunk's k-groups
-                int r = 0, s = 0;
-                for (int tap = 0; tap < RS; tap += 3) {
-                    const int o0 = r * a.pw + s;
-                    if (++s == a.S) { s = 0; ++r; }
-                    const int o1 = r * a.pw + s;
-                    if (++s == a.S) { s = 0; ++r; }
-                    const int o2 = r * a.pw + s;
-                    if (++s == a.S) { s = 0; ++r; }
-                    next_load(f2); multiply_split(pb, -o0, f0);
-                    next_load(f0); multiply_split(pb, hi - o0, f1);
-                    next_load(f1); multiply_split(pb, -o1, f2);
-                    next_load(f2); multiply_split(pb, hi - o1, f0);
-                    next_load(f0); multiply_split(pb, -o2, f1);
-                    next_load(f1); multiply_split(pb, hi - o2, f2);
+        if constexpr (NB > 4) {
+            // Seven pixel blocks: the code fragments of a step are read in two groups (blocks 0-3, blocks 4-6), and the reads
+            // are software-pipelined against the matrix instructions: while a step's first group is multiplied its second
+            // group is on its way from LDS, and while the second group is multiplied the NEXT step's first group is.  (One
+            // wavefront per SIMD and workgroup: nothing else hides its LDS latency.  In-kernel cycle stamps: a step took 1420
+            // cycles for 672 cycles of matrix instructions, alone on its SIMD or not.)  The registers of a group are reused as
+            // soon as the instructions that read them have been issued.  At a chunk's last step the next first group is not
+            // known yet (it is in the other buffer, behind a barrier): that step re-reads its own, so that every step issues the
+            // same loads, and the chunk's first group is read after the barrier.
+            constexpr int NB0 = 4, NB1 = NB - NB0;
+            u32x4 bA[NB0], bB[NB1];
+            const uint4 *pb = cdx_lds;
+            auto read0 = [&](int off) {
+#pragma unroll
+                for (int nb = 0; nb < NB0; ++nb) { const uint4 t = pb[lane_cell[nb] + off]; bA[nb] = u32x4{t.x, t.y, t.z, t.w}; }
+            };
+            auto read1 = [&](int off) {
+#pragma unroll
+                for (int nb = 0; nb < NB1; ++nb) { const uint4 t = pb[lane_cell[NB0 + nb] + off]; bB[nb] = u32x4{t.x, t.y, t.z, t.w}; }
+            };
+            auto mma0 = [&](const u32x4 (&af)[PL]) {
+#pragma unroll
+                for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+                    for (int nb = 0; nb < NB0; ++nb) Mma<MODE>::run(af[pl], bA[nb], acc[nb]);
+            };
+            auto mma1 = [&](const u32x4 (&af)[PL]) {
+#pragma unroll
+                for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+                    for (int nb = 0; nb < NB1; ++nb) Mma<MODE>::run(af[pl], bB[nb], acc[NB0 + nb]);
+            };
+            const int hi = 2 * a.patch_cells;                 // the second half of the chunk's k-groups
+            for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+                const int buf = chunk & 1;
+                store_chunk(buf);
+                __syncthreads();
+                fetch_chunk(min(chunk + 1, a.n_chunks - 1));  // in flight during the matrix-core phase (the last chunk once more, unused)
+                if (wave_active) {
+                    pb = cdx_lds + buf * buf_cells;
+                    int m_r = 0, m_s = 0, m_kk = 0;           // the step whose patch offset next_off() returns next
+                    auto next_off = [&]() {
+                        const int o = (m_kk ? hi : 0) - (m_r * a.pw + m_s);
+                        if (m_kk == 0) m_kk = 1;
+                        else { m_kk = 0; if (++m_s == a.S) { m_s = 0; ++m_r; } }
+                        return o;
+                    };
+                    int off = next_off();
+                    read0(off);
+                    for (int tap = 0; tap < RS; tap += 3) {
+                        const bool last3 = tap + 3 >= RS;
+                        int nxt;
+                        nxt = next_off(); next_load(f2); read1(off); mma0(f0); read0(nxt); mma1(f0); off = nxt;
+                        nxt = next_off(); next_load(f0); read1(off); mma0(f1); read0(nxt); mma1(f1); off = nxt;
+                        nxt = next_off(); next_load(f1); read1(off); mma0(f2); read0(nxt); mma1(f2); off = nxt;
+                        nxt = next_off(); next_load(f2); read1(off); mma0(f0); read0(nxt); mma1(f0); off = nxt;
+                        nxt = next_off(); next_load(f0); read1(off); mma0(f1); read0(nxt); mma1(f1); off = nxt;
+                        nxt = last3 ? off : next_off();
+                        next_load(f1); read1(off); mma0(f2); read0(nxt); mma1(f2); off = nxt;
+                    }
+                }
+            }
+        } else {
+            for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+                const int buf = chunk & 1;
+                store_chunk(buf);
+                __syncthreads();
+                fetch_chunk(min(chunk + 1, a.n_chunks - 1));      // in flight during the matrix-core phase (the last chunk once more, unused)
+                if (wave_active) {
+                    const uint4 *pb = cdx_lds + buf * buf_cells;
+                    const int hi = 2 * a.patch_cells;             // the second half of the chunk's k-groups
+                    int r = 0, s = 0;
+                    for (int tap = 0; tap < RS; tap += 3) {
+                        const int o0 = r * a.pw + s;
+                        if (++s == a.S) { s = 0; ++r; }
+                        const int o1 = r * a.pw + s;
+                        if (++s == a.S) { s = 0; ++r; }
+                        const int o2 = r * a.pw + s;
+                        if (++s == a.S) { s = 0; ++r; }
+                        next_load(f2); multiply_split(pb, -o0, f0);
+                        next_load(f0); multiply_split(pb, hi - o0, f1);
+                        next_load(f1); multiply_split(pb, -o1, f2);
+                        next_load(f2); multiply_split(pb, hi - o1, f0);
+                        next_load(f0); multiply_split(pb, -o2, f1);
+                        next_load(f1); multiply_split(pb, hi - o2, f2);
+                    }
                 }
             }
         }
