@@ -344,150 +344,104 @@ __device__ __forceinline__ void conv_dx_body(const ConvDxArgs &a, int b)
         if (l_chunk == a.n_chunks) { l_chunk = a.n_chunks - 1; l_tap = RS - 1; l_kk = 1; }
     };
 
-    // SPLIT: the code fragments of a step are read and multiplied in two groups of pixel blocks (four, then the rest): the
-    // second group's LDS reads run behind the first group's matrix instructions, and the fragments take 16 registers
-    // instead of 28 -- what the third weight set of the loop below needs.
-    auto multiply_blocks = [&](const uint4 *pb, int off, const u32x4 (&af)[PL], auto first, auto count) {
-        constexpr int B0 = decltype(first)::value, BN = decltype(count)::value;
-        u32x4 bfrag[BN];
+    // ---- the multiply phase ------------------------------------------------------------------------------------------
+    // A STEP is (tap, half of the chunk's k-groups): one weight fragment set (PL planes) against the code fragments of the
+    // wavefront's NB pixel blocks, PL*NB matrix instructions.  One wavefront per SIMD and workgroup: nothing but the
+    // wavefront's own instruction order hides the latency of its operands (in-kernel cycle stamps on the 56x56 layer: a step
+    // took 1420 cycles for 672 cycles of matrix instructions, whether the wavefront had its SIMD to itself or not).  Hence:
+    //   * weight fragments (from L2, several hundred cycles away) are requested one or two steps ahead (RING3: three register
+    //     sets instead of two; tap counts that are a multiple of 3, where six steps bring the ring back to its start and the sets
+    //     keep compile-time names);
+    //   * code fragments (from LDS) are software-pipelined against the matrix instructions.  Seven pixel blocks: two groups
+    //     (blocks 0-3, 4-6); while a step's first group is multiplied its second group is on its way, and while the second
+    //     is multiplied the NEXT step's first group is; a group's registers are reused as soon as the instructions that read
+    //     them have been issued.  Up to four blocks: one group in two register sets that alternate between the steps;
+    //   * every step issues the same loads.  At a chunk's last step the next fragments are not there yet (other buffer,
+    //     behind a barrier): that step reads its own again, and the chunk's first fragments are read after the barrier.
+    constexpr int NB0 = NB > 4 ? 4 : NB, NB1 = NB > 4 ? NB - 4 : NB;   // seven blocks: the two groups; else: the two sets
+    u32x4 bA[NB0], bB[NB1];
+    const uint4 *pb = cdx_lds;
+    const int hi = 2 * a.patch_cells;                         // the second half of the chunk's k-groups
+    int m_r = 0, m_s = 0, m_kk = 0;                           // the step whose patch offset next_off() returns next
+    auto next_off = [&]() {
+        const int o = (m_kk ? hi : 0) - (m_r * a.pw + m_s);
+        if (m_kk == 0) m_kk = 1;
+        else { m_kk = 0; if (++m_s == a.S) { m_s = 0; ++m_r; } }
+        return o;
+    };
+    auto read_a = [&](int off) {                              // blocks 0 .. NB0-1 -> bA
 #pragma unroll
-        for (int nb = 0; nb < BN; ++nb) {
-            const uint4 t = pb[lane_cell[B0 + nb] + off];
-            bfrag[nb] = u32x4{t.x, t.y, t.z, t.w};
-        }
+        for (int nb = 0; nb < NB0; ++nb) { const uint4 t = pb[lane_cell[nb] + off]; bA[nb] = u32x4{t.x, t.y, t.z, t.w}; }
+    };
+    auto read_b = [&](int off) {                              // seven blocks: blocks 4-6; else blocks 0 .. NB-1 -> bB
+        constexpr int first = NB > 4 ? NB0 : 0;
+#pragma unroll
+        for (int nb = 0; nb < NB1; ++nb) { const uint4 t = pb[lane_cell[first + nb] + off]; bB[nb] = u32x4{t.x, t.y, t.z, t.w}; }
+    };
+    auto mma_a = [&](const u32x4 (&af)[PL]) {
 #pragma unroll
         for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
-            for (int nb = 0; nb < BN; ++nb) Mma<MODE>::run(af[pl], bfrag[nb], acc[B0 + nb]);
+            for (int nb = 0; nb < NB0; ++nb) Mma<MODE>::run(af[pl], bA[nb], acc[nb]);
     };
-    auto multiply = [&](const uint4 *pb, int off, const u32x4 (&af)[PL]) {
-        multiply_blocks(pb, off, af, std::integral_constant<int, 0>{}, std::integral_constant<int, NB>{});
+    auto mma_b = [&](const u32x4 (&af)[PL]) {
+        constexpr int first = NB > 4 ? NB0 : 0;
+#pragma unroll
+        for (int pl = 0; pl < PL; ++pl)
+#pragma unroll
+            for (int nb = 0; nb < NB1; ++nb) Mma<MODE>::run(af[pl], bB[nb], acc[first + nb]);
     };
-    auto multiply_split = [&](const uint4 *pb, int off, const u32x4 (&af)[PL]) {
-        constexpr int NB0 = NB > 4 ? 4 : NB;
-        multiply_blocks(pb, off, af, std::integral_constant<int, 0>{}, std::integral_constant<int, NB0>{});
-        if constexpr (NB > NB0) multiply_blocks(pb, off, af, std::integral_constant<int, NB0>{}, std::integral_constant<int, NB - NB0>{});
+    int off = 0;
+    // one step with weight set `cur`, the load of the step one or two ahead into `nxt_w`; `again`: the chunk's last step.
+    // Seven blocks: both groups belong to this step.  Else: EVEN steps multiply bA and read the next step into bB, odd ones
+    // the other way round.
+    auto step = [&](u32x4 (&nxt_w)[PL], const u32x4 (&cur)[PL], bool again, auto even) {
+        const int nxt = again ? off : next_off();
+        next_load(nxt_w);
+        if constexpr (NB > 4) { read_b(off); mma_a(cur); read_a(nxt); mma_b(cur); }
+        else if constexpr (decltype(even)::value) { read_b(nxt); mma_a(cur); }
+        else { read_a(nxt); mma_b(cur); }
+        off = nxt;
+    };
+    constexpr std::true_type EVEN{};
+    constexpr std::false_type ODD{};
+    auto begin_chunk = [&](int chunk) {                       // all wavefronts: stage the chunk, fetch the next one's codes
+        const int buf = chunk & 1;
+        store_chunk(buf);
+        __syncthreads();
+        fetch_chunk(min(chunk + 1, a.n_chunks - 1));          // in flight during the matrix-core phase (the last chunk once more, unused)
+        pb = cdx_lds + buf * buf_cells;
+        m_r = m_s = m_kk = 0;
     };
 
     fetch_chunk(0);
     if constexpr (RING3) {
-        // Tap counts that are a multiple of 3 (3x3 kernels above all): the weight fragments go through a ring of THREE register
-        // sets, loaded two multiply steps ahead (a fragment comes from L2, several hundred cycles away; one step ahead, as in
-        // the loop below, the matrix cores waited for it at every step: they were busy 54 % of the kernel on the 56x56
-        // layer).  A step is (tap, half of the chunk's k-groups); six steps = three taps bring the ring back to where it was, so
-        // the sets keep compile-time names.
         u32x4 f0[PL], f1[PL], f2[PL];
         if (wave_active) { next_load(f0); next_load(f1); }
         __syncthreads();                                      // zero fill done before the first patch writes
-        if constexpr (NB > 4) {
-            // Seven pixel blocks: the code fragments of a step are read in two groups (blocks 0-3, blocks 4-6), and the reads
-            // are software-pipelined against the matrix instructions: while a step's first group is multiplied its second
-            // group is on its way from LDS, and while the second group is multiplied the NEXT step's first group is.  (One
-            // wavefront per SIMD and workgroup: nothing else hides its LDS latency.  In-kernel cycle stamps: a step took 1420
-            // cycles for 672 cycles of matrix instructions, alone on its SIMD or not.)  The registers of a group are reused as
-            // soon as the instructions that read them have been issued.  At a chunk's last step the next first group is not
-            // known yet (it is in the other buffer, behind a barrier): that step re-reads its own, so that every step issues the
-            // same loads, and the chunk's first group is read after the barrier.
-            constexpr int NB0 = 4, NB1 = NB - NB0;
-            u32x4 bA[NB0], bB[NB1];
-            const uint4 *pb = cdx_lds;
-            auto read0 = [&](int off) {
-#pragma unroll
-                for (int nb = 0; nb < NB0; ++nb) { const uint4 t = pb[lane_cell[nb] + off]; bA[nb] = u32x4{t.x, t.y, t.z, t.w}; }
-            };
-            auto read1 = [&](int off) {
-#pragma unroll
-                for (int nb = 0; nb < NB1; ++nb) { const uint4 t = pb[lane_cell[NB0 + nb] + off]; bB[nb] = u32x4{t.x, t.y, t.z, t.w}; }
-            };
-            auto mma0 = [&](const u32x4 (&af)[PL]) {
-#pragma unroll
-                for (int pl = 0; pl < PL; ++pl)
-#pragma unroll
-                    for (int nb = 0; nb < NB0; ++nb) Mma<MODE>::run(af[pl], bA[nb], acc[nb]);
-            };
-            auto mma1 = [&](const u32x4 (&af)[PL]) {
-#pragma unroll
-                for (int pl = 0; pl < PL; ++pl)
-#pragma unroll
-                    for (int nb = 0; nb < NB1; ++nb) Mma<MODE>::run(af[pl], bB[nb], acc[NB0 + nb]);
-            };
-            const int hi = 2 * a.patch_cells;                 // the second half of the chunk's k-groups
-            for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
-                const int buf = chunk & 1;
-                store_chunk(buf);
-                __syncthreads();
-                fetch_chunk(min(chunk + 1, a.n_chunks - 1));  // in flight during the matrix-core phase (the last chunk once more, unused)
-                if (wave_active) {
-                    pb = cdx_lds + buf * buf_cells;
-                    int m_r = 0, m_s = 0, m_kk = 0;           // the step whose patch offset next_off() returns next
-                    auto next_off = [&]() {
-                        const int o = (m_kk ? hi : 0) - (m_r * a.pw + m_s);
-                        if (m_kk == 0) m_kk = 1;
-                        else { m_kk = 0; if (++m_s == a.S) { m_s = 0; ++m_r; } }
-                        return o;
-                    };
-                    int off = next_off();
-                    read0(off);
-                    for (int tap = 0; tap < RS; tap += 3) {
-                        const bool last3 = tap + 3 >= RS;
-                        int nxt;
-                        nxt = next_off(); next_load(f2); read1(off); mma0(f0); read0(nxt); mma1(f0); off = nxt;
-                        nxt = next_off(); next_load(f0); read1(off); mma0(f1); read0(nxt); mma1(f1); off = nxt;
-                        nxt = next_off(); next_load(f1); read1(off); mma0(f2); read0(nxt); mma1(f2); off = nxt;
-                        nxt = next_off(); next_load(f2); read1(off); mma0(f0); read0(nxt); mma1(f0); off = nxt;
-                        nxt = next_off(); next_load(f0); read1(off); mma0(f1); read0(nxt); mma1(f1); off = nxt;
-                        nxt = last3 ? off : next_off();
-                        next_load(f1); read1(off); mma0(f2); read0(nxt); mma1(f2); off = nxt;
-                    }
-                }
-            }
-        } else {
-            for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
-                const int buf = chunk & 1;
-                store_chunk(buf);
-                __syncthreads();
-                fetch_chunk(min(chunk + 1, a.n_chunks - 1));      // in flight during the matrix-core phase (the last chunk once more, unused)
-                if (wave_active) {
-                    const uint4 *pb = cdx_lds + buf * buf_cells;
-                    const int hi = 2 * a.patch_cells;             // the second half of the chunk's k-groups
-                    int r = 0, s = 0;
-                    for (int tap = 0; tap < RS; tap += 3) {
-                        const int o0 = r * a.pw + s;
-                        if (++s == a.S) { s = 0; ++r; }
-                        const int o1 = r * a.pw + s;
-                        if (++s == a.S) { s = 0; ++r; }
-                        const int o2 = r * a.pw + s;
-                        if (++s == a.S) { s = 0; ++r; }
-                        next_load(f2); multiply_split(pb, -o0, f0);
-                        next_load(f0); multiply_split(pb, hi - o0, f1);
-                        next_load(f1); multiply_split(pb, -o1, f2);
-                        next_load(f2); multiply_split(pb, hi - o1, f0);
-                        next_load(f0); multiply_split(pb, -o2, f1);
-                        next_load(f1); multiply_split(pb, hi - o2, f2);
-                    }
+        for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+            begin_chunk(chunk);
+            if (wave_active) {
+                off = next_off();
+                read_a(off);
+                for (int tap = 0; tap < RS; tap += 3) {
+                    step(f2, f0, false, EVEN); step(f0, f1, false, ODD); step(f1, f2, false, EVEN);
+                    step(f2, f0, false, ODD);  step(f0, f1, false, EVEN); step(f1, f2, tap + 3 >= RS, ODD);
                 }
             }
         }
     } else {
-        u32x4 a0[PL], a1[PL];                                 // weight fragments of kk = 0 / kk = 1 (ping-pong), one step ahead
+        u32x4 a0[PL], a1[PL];                                 // weight fragments of the two halves of a chunk's k-groups, one step ahead
         if (wave_active) next_load(a0);
         __syncthreads();                                      // zero fill done before the first patch writes
         for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
-            const int buf = chunk & 1;
-            store_chunk(buf);
-            __syncthreads();
-            fetch_chunk(min(chunk + 1, a.n_chunks - 1));      // in flight during the matrix-core phase (the last chunk once more, unused)
+            begin_chunk(chunk);
             if (wave_active) {
-                const uint4 *pb = cdx_lds + buf * buf_cells;
-                int r = 0, s = 0;
+                off = next_off();
+                read_a(off);
                 for (int tap = 0; tap < RS; ++tap) {
-                    const int tapoff = r * a.pw + s;
-                    // the next weight fragment is loaded while the current one is multiplied
-                    next_load(a1);
-                    multiply(pb, -tapoff, a0);
-                    next_load(a0);
-                    multiply(pb, 2 * a.patch_cells - tapoff, a1);
-                    if (++s == a.S) { s = 0; ++r; }
+                    step(a1, a0, false, EVEN);
+                    step(a0, a1, tap + 1 >= RS, ODD);
                 }
             }
         }
