@@ -53,7 +53,11 @@ CASES = [  # N, C, H, Wd, K, R, S, pad
     (2, 64, 30, 30, 40, 3, 3, 1),       # several pixel tiles per image, tile borders inside a row
     (2, 6, 12, 9, 10, 3, 3, 1),         # odd row length: element-wise scatter into the staging buffers
     (17, 70, 8, 8, 130, 3, 3, 1),       # more images than one reduction split takes, partial channel tiles
-    (32, 256, 48, 48, 16, 3, 3, 1),     # dX as two problems of one launch: eight 7-block tiles per image, then three 6-block tiles
+    (2, 16, 12, 12, 24, 1, 3, 0),       # three taps in a row: the three-set weight ring with one turn per chunk
+    (2, 40, 12, 12, 24, 3, 1, 1),       # three taps in a column, output wider than the input (padding on a 1-wide kernel)
+    (2, 16, 12, 12, 40, 2, 3, 1),       # six taps
+    (2, 16, 13, 12, 24, 3, 2, 1),       # six taps the other way round, odd height
+    (32, 256, 48, 48, 16, 3, 3, 1),     # 704 workgroups: two rounds over the chip, the second one partly filled
 ]
 
 
