@@ -186,3 +186,13 @@ def test_full_8bit_entry_points_reject_bad_arguments():
     assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 1, 1, -1.0, 1, 0, None, FAKE, FAKE, None) == STEP
     assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 20000, 3, 3, 1, 1, 1.0, 1, 0, None, FAKE, None, None) == OVERFLOW
     assert _code(g, FAKE, FAKE, FAKE, 2, 3, 8, 8, 4, 3, 3, 1, 1, 1.0, 1, 0, None, FAKE, FAKE, None) == WORKSPACE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the hot path has no collectives: the bench says so instead of pretending to scale
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
