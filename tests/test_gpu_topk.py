@@ -126,3 +126,30 @@ def test_products_on_top_k_codes_fc_layer():
         absW = step * np.abs(ref.astype(np.float64)).T @ np.abs(X.astype(np.float64))
         check_products(dX.cpu().numpy(), dX_ref, absX, "top-k dX path %d" % path)
         check_products(dW.cpu().numpy(), dW_ref, absW, "top-k dW path %d" % path)
+
+
+@pytest.mark.parametrize("vec_rows", [1, 12])
+def test_products_on_top_k_codes_conv_layer(vec_rows):
+    # top-k per feature-map plane (vec_rows = 1) or per example (vec_rows = K) of a small convolution's gradient; the
+    # codes and the format then feed both kernel families (the gather kernels read the format's entries)
+    rng = np.random.default_rng(21 + vec_rows)
+    N, C, H, K = 6, 10, 14, 12
+    d = rng.laplace(0, 1e-3, size=(N, K, H, H)).astype(np.float32)
+    W = (rng.standard_normal((K, C, 3, 3)) * 0.1).astype(np.float32)
+    X = np.maximum(rng.standard_normal((N, C, H, H)), 0).astype(np.float32)
+    step = float(np.float32(np.abs(d).max() / 127))
+    k = 12 if vec_rows == 1 else 150
+    got, ref = check(d.reshape(N * K, H * H), N * K, H * H, vec_rows, k, step)
+    ref4 = ref.reshape(N, K, H, H)
+    dX_ref, dW_ref, _ = O.conv2d_backward(W, X, codes=ref4, step=step, stride=1, pad=1)
+    aX, aW, _ = O.conv2d_backward(np.abs(W), np.abs(X), codes=np.abs(ref4), step=step, stride=1, pad=1)
+    Wd, Xd = torch.from_numpy(W).to(DEV), torch.from_numpy(X).to(DEV)
+    for path in (dbp.PATH_MFMA, dbp.PATH_GATHER):
+        dX = torch.full(X.shape, float("nan"), device=DEV)
+        dW = torch.full(W.shape, float("nan"), device=DEV)
+        ws = torch.empty(dbp.conv2d_workspace_bytes(N, C, H, H, K, 3, 3, 1, 1), dtype=torch.uint8, device=DEV)
+        dbp.conv2d_products(got["codes_dev"], got["fmt_dev"], step, Wd, Xd, dbp.F32, N, C, H, H, K, 3, 3, 1, 1, dX, dW, ws, path,
+                            torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        check_products(dX.cpu().numpy(), dX_ref, aX, "top-k conv dX path %d" % path)
+        check_products(dW.cpu().numpy(), dW_ref, aW, "top-k conv dW path %d" % path)
