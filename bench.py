@@ -243,6 +243,22 @@ def main():
     kernels5 = {"nsd_us": t_nsd5["median"] * 1e6, "dX_us": t_dx["median"] * 1e6, "dW_int8_us": t_dw["median"] * 1e6,
                 "nsd_GBps": (5.0 * n_codes) / t_nsd5["median"] / 1e9}
 
+    # the same step with the opt-in two-plane operand split (W in two bf16 planes, 16 significant bits): reported beside the headline
+    t_step2 = med(lambda i: conv_call(sets5[i % 2], dims5, xd5, p5, p5.step, path=dbp.PATH_AUTO | dbp.PATH_TWO_PLANES), max(20, args.steps // 2))
+
+    def k_dx2(i):
+        b = sets5[i % 2]
+        dbp.conv2d_products(b["codes"], None, p5.step, b["W"], b["X"], xd5, N, Cc, H, Wd, K, R, S, p5.stride, p5.pad, b["dX"], None, b["ws"],
+                            dbp.PATH_MFMA | dbp.PATH_TWO_PLANES, stream)
+
+    t_dx2 = timed(k_dx2, it)
+    two_planes = {
+        "ms_per_step": t_step2 * 1e3, "dense_equiv_tflops": dense_flops5 / t_step2 / 1e12, "dX_us": t_dx2["median"] * 1e6,
+        "executed_mfma_frac_of_2.5PFLOPs_bf16": 2 * 2.0 * n_codes * Cc * R * S / t_dx2["mean"] / 1e12 / PEAK_BF16_TFLOPS,
+        "note": "opt-in flag DBP_PATH_TWO_PLANES: fp32 W in two bf16 planes rounded to nearest (error <= 2^-16 * sum|q||w| per output, inside the "
+                "1e-4 tolerance); NOT the headline, which multiplies the exact three-plane split",
+    }
+
     out_line = {
         "metric": "dithered backward dense-equiv TFLOP/s (NSD + dX + dW, one call on config 5: VGG conv3-shaped layer, 8-bit mode)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -255,6 +271,7 @@ def main():
         "cpu_baseline": None,
         "ms_per_step_mean": t_mean * 1e3, "ms_per_step_min": min(per_step) * 1e3, "host_wall_ms_per_step": wall * 1e3,
         "kernels_cfg5_us": kernels5,
+        "two_plane_operands": two_planes,
     }
 
     if not args.headline_only:
@@ -389,6 +406,7 @@ def bench_rows(dbp, workloads, torch, np, med, timed, stream, conv_buffers, conv
         t_w = med(lambda i: dbp.conv2d_products(bb["codes"], None, p.step, bb["W"], bb["X"], xd, Nn, Cq, Hq, Wq, Kq, Rq, Sq, p.stride, p.pad,
                                                 None, bb["dW"], bb["ws"], dbp.PATH_MFMA, stream), 20)
         row["dX_us"], row["dW_us"], row["nsd_us"] = t_x * 1e6, t_w * 1e6, max(t - t_x - t_w, 0.0) * 1e6
+        row["ms_two_planes"] = med(lambda i: conv_call(bb, dims, xd, p, p.step, path=dbp.PATH_AUTO | dbp.PATH_TWO_PLANES), 20) * 1e3
         t_d = med(lambda i: dbp.dense_conv2d_backward(bb["d"], bb["W"], bb["X"], xd, Nn, Cq, Hq, Wq, Kq, Rq, Sq, p.stride, p.pad, bb["dX"], bb["dW"],
                                                       bb["ws"], stream), 5, warm=1)
         row["same_library_dense_ms"] = t_d * 1e3
@@ -458,6 +476,10 @@ def bench_rows(dbp, workloads, torch, np, med, timed, stream, conv_buffers, conv
                     linear_call(bq, path=path)
             t = med(step, 60 if pname == "auto" else 20, warm=5)
             row["ms_" + pname] = t * 1e3
+        def step2(i):
+            for bq in sets[i % NSETS]:
+                linear_call(bq, path=dbp.PATH_AUTO | dbp.PATH_TWO_PLANES)
+        row["ms_auto_two_planes"] = med(step2, 60, warm=5) * 1e3
         row["sparsity_per_layer"] = [round(1 - dbp.Stats.from_tensor(bq["st"]).nnz / bq["d"].numel(), 4) for bq in sets[0]]
         row["dense_equiv_tflops_auto"] = dense_flops / (row["ms_auto"] * 1e-3) / 1e12
         # the gather kernels alone on the 4096x4096 layer: the method's own work, 2*nnz*in per product, against the fp32 vector peak

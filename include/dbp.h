@@ -78,7 +78,15 @@ typedef enum { DBP_F32 = 0, DBP_I8 = 1 } dbp_dtype;
 typedef enum {
     DBP_PATH_AUTO = 0,
     DBP_PATH_MFMA = 1,
-    DBP_PATH_GATHER = 2
+    DBP_PATH_GATHER = 2,
+    /* A flag, OR-ed onto one of the three above.  The matrix-core kernels multiply the integer codes with the fp32 operand (W for dX,
+     * X for dW) cut into bf16 planes.  By default three planes that add up to the operand exactly, so the only rounding is the fp32
+     * accumulation.  With this flag the kernels that support it (the rest ignore it) cut the operand into TWO planes, rounded to
+     * nearest: the operand then carries 16 significant bits, |w - hi - lo| <= 2^-16 |w|, and an output differs from the three-plane
+     * one by at most 2^-16 * sum_r |q_r| |w_r| over its own reduction (1.5e-5, against the 1e-4 this library's results are held to;
+     * the dither of Eq. (nsd) itself moves every term by up to Delta) for two thirds of the matrix-core work.  The int8 products
+     * (x_dtype == DBP_I8 dW, the *_q8 calls) and the gather kernels have no planes and are unchanged. */
+    DBP_PATH_TWO_PLANES = 0x100
 } dbp_path;
 
 /* Per-call statistics, device resident (the paper's reported quantities: sparsity and the

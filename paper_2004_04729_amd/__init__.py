@@ -5,7 +5,7 @@ The Python layer only marshals arguments; every step runs in the HIP library.  T
 fallback: importing :mod:`paper_2004_04729_amd.binding` fails loudly when the library is missing.
 """
 from .binding import (  # noqa: F401
-    DbpError, Stats, PATH_AUTO, PATH_MFMA, PATH_GATHER, F32, I8,
+    DbpError, Stats, PATH_AUTO, PATH_MFMA, PATH_GATHER, PATH_TWO_PLANES, F32, I8,
     abi_version, status_string, format_layout, linear_workspace_bytes, conv2d_workspace_bytes,
     nsd_quantize, nsd_quantize_static, topk_workspace_bytes, topk_quantize, dithered_linear_backward, dithered_conv2d_backward,
     conv2d_grouped_workspace_bytes, dithered_conv2d_backward_grouped, conv2d_products_grouped,

@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libdbp_hip.so")
 
 F32, I8 = 0, 1
 PATH_AUTO, PATH_MFMA, PATH_GATHER = 0, 1, 2
+PATH_TWO_PLANES = 0x100      # a flag, OR-ed onto a path: two bf16 planes of the fp32 operand instead of three
 
 
 class DbpError(RuntimeError):

@@ -15,6 +15,17 @@ static __device__ __align__(256) unsigned char scratch[dbp::kNsdScratchBytes];
 
 namespace {
 
+// `path` = a kernel family, optionally with DBP_PATH_TWO_PLANES.
+inline dbp_path path_family(dbp_path p) { return (dbp_path)((int)p & ~(int)DBP_PATH_TWO_PLANES); }
+inline bool     path_two_planes(dbp_path p) { return ((int)p & (int)DBP_PATH_TWO_PLANES) != 0; }
+inline bool     path_ok(dbp_path p)
+{
+    const dbp_path f = path_family(p);
+    return f == DBP_PATH_AUTO || f == DBP_PATH_MFMA || f == DBP_PATH_GATHER;
+}
+inline dbp_path path_with_flags(dbp_path family, dbp_path from) { return (dbp_path)((int)family | ((int)from & (int)DBP_PATH_TWO_PLANES)); }
+
+
 constexpr int64_t kMaxElems = (int64_t)1 << 40;
 constexpr int64_t kMaxDim = (int64_t)1 << 30;          // GEMM indices are 32-bit
 
@@ -160,7 +171,7 @@ AutoPlan linear_auto_plan(const LinearArgs &call, bool launchable)
     if (ungated) return ap;
     const double B = (double)call.B, in = (double)call.in, out = (double)call.out;
     const int products = (call.dX ? 1 : 0) + (call.dW ? 1 : 0);
-    const double mfma_us = products * 2.0 * B * in * out * 3.0 / 0.95e9;             // three bf16 planes at 0.95 PFLOP/s
+    const double mfma_us = products * 2.0 * B * in * out * (call.two_planes ? 2.0 : 3.0) / 0.95e9;   // the bf16 planes at 0.95 PFLOP/s
     // gather kernels: a step (one 64-index chunk of one row block: tile through LDS, barrier) costs about 2.2 us however
     // few nonzeros it holds; the nonzeros themselves run at about 32 TFLOP/s per product when all CUs have a workgroup
     GatherShape gs[2];
@@ -199,8 +210,9 @@ AutoPlan conv_auto_plan(const ConvArgs &call, int64_t P, int64_t Q)
     const double crs = (double)(call.C * call.R * call.S), n_codes = (double)(call.N * call.K * P * Q);
     const double flops = 2.0 * n_codes * crs;                                        // one dense product
     double mfma_us = 0.0;
-    if (call.dX) mfma_us += flops * 3.0 / 0.9e9;
-    if (call.dW) mfma_us += call.x_dtype == DBP_I8 ? flops / 1.4e9 : flops * 3.0 / 0.6e9;
+    const double planes = call.two_planes ? 2.0 : 3.0;
+    if (call.dX) mfma_us += flops * planes / 0.9e9;
+    if (call.dW) mfma_us += call.x_dtype == DBP_I8 ? flops / 1.4e9 : flops * planes / 0.6e9;
     const double x_elems = (double)(call.N * call.C * call.H * call.Wd);
     const double fixed_us = 15.0 + (call.dX ? x_elems * 4.0 : 0.0) / 2.0e6 + (call.dW ? x_elems * (call.x_dtype == DBP_I8 ? 1.0 : 4.0) : 0.0) / 2.0e6;
     if (fixed_us > 0.5 * mfma_us) return ap;
@@ -222,13 +234,14 @@ dbp_status linear_products(const int8_t *codes, const void *format, float step, 
     if (st != DBP_OK) return st;
     if (!step_dev && !step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (!path_ok(path)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    if (path == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
+    if (path_family(path) == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
     LinearArgs a;
     a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.stats_job = job; a.gate = gate;
-    if (path == DBP_PATH_GATHER) {
+    a.two_planes = path_two_planes(path);
+    if (path_family(path) == DBP_PATH_GATHER) {
         if (!format) return DBP_ERR_NULL;
         if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
         dbp_format_layout L;
@@ -260,10 +273,10 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     if (st != DBP_OK) return st;
     if (!step_dev && !step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
+    if (!path_ok(path)) return DBP_ERR_UNSUPPORTED;
+    if (path_family(path) == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    if (path == DBP_PATH_GATHER) {
+    if (path_family(path) == DBP_PATH_GATHER) {
         if (!format) return DBP_ERR_NULL;
         if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
         dbp_format_layout L;
@@ -286,6 +299,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
     a.stats_job = job; a.pending = nullptr; a.gate = gate;
+    a.two_planes = path_two_planes(path);
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
 
@@ -302,7 +316,7 @@ dbp_status linear_products_dispatch(const AutoPlan &ap, const int8_t *k, char *w
     job.flag = flag; job.gather_below = ap.gather_below;
     if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
     const StatsJob none{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
-    dbp_status st = linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset, scratch_bytes, DBP_PATH_MFMA,
+    dbp_status st = linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset, scratch_bytes, path_with_flags(DBP_PATH_MFMA, path),
                                     stream, none, step_dev, Gate{flag, 0});
     if (st != DBP_OK) return st;
     return linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset, scratch_bytes, DBP_PATH_GATHER,
@@ -322,16 +336,17 @@ dbp_status conv2d_products_dispatch(const AutoPlan &ap, const int8_t *k, char *w
     if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
     const StatsJob none{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
     dbp_status st = conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset,
-                                    scratch_bytes, DBP_PATH_MFMA, stream, step_dev, none, Gate{flag, 0});
+                                    scratch_bytes, path_with_flags(DBP_PATH_MFMA, path), stream, step_dev, none, Gate{flag, 0});
     if (st != DBP_OK) return st;
     return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset,
                            scratch_bytes, DBP_PATH_GATHER, stream, step_dev, none, Gate{flag, 1});
 }
 
 LinearArgs linear_call(const float *W, const void *X, dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX, void *dW,
-                       const int8_t *codes, char *scratch, size_t scratch_bytes)
+                       const int8_t *codes, char *scratch, size_t scratch_bytes, bool two_planes)
 {
     LinearArgs a;
+    a.two_planes = two_planes;
     a.codes = codes; a.dense = nullptr; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.B = B; a.in = in; a.out = out; a.dX = dX; a.dW = dW; a.scratch = scratch; a.scratch_bytes = scratch_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
@@ -339,9 +354,11 @@ LinearArgs linear_call(const float *W, const void *X, dbp_dtype x_dtype, int64_t
 }
 
 ConvArgs conv_call(const float *W, const void *X, dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R,
-                   int64_t S, int64_t stride, int64_t pad, float *dX, void *dW, const int8_t *codes, char *scratch, size_t scratch_bytes)
+                   int64_t S, int64_t stride, int64_t pad, float *dX, void *dW, const int8_t *codes, char *scratch, size_t scratch_bytes,
+                   bool two_planes)
 {
     ConvArgs a;
+    a.two_planes = two_planes;
     a.codes = codes; a.dense = nullptr; a.step = 1.0f; a.step_dev = nullptr; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = dX; a.dW = dW; a.scratch = scratch; a.scratch_bytes = scratch_bytes;
@@ -448,9 +465,9 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
     if (st != DBP_OK) return st;
     if (!step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (!path_ok(path)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    if (path == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
+    if (path_family(path) == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
     const Carve c = carve(B, out, linear_scratch_bytes(B, in, out));
     if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
@@ -458,13 +475,13 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     // only the gather kernels that serve odd shapes read the tile-sparse arrays; the statistics are summed by the
     // products' launch, or, with both families behind the density gate, by the kernel that writes the gate's flag
-    const AutoPlan ap = path == DBP_PATH_AUTO
-        ? linear_auto_plan(linear_call(W, X, x_dtype, B, in, out, dX, dW, k, ws + c.scratch_offset, workspace_bytes - c.scratch_offset), true)
+    const AutoPlan ap = path_family(path) == DBP_PATH_AUTO
+        ? linear_auto_plan(linear_call(W, X, x_dtype, B, in, out, dX, dW, k, ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path_two_planes(path)), true)
         : AutoPlan{false, 0};
     dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
     StatsJob job;
     st = run_nsd(delta, B, out, step, seed, idx_base, k, ws, &c.fmt, st_dev, (hipStream_t)stream,
-                 path == DBP_PATH_GATHER, &job);
+                 path_family(path) == DBP_PATH_GATHER, &job);
     if (st != DBP_OK) return st;
     return linear_products_dispatch(ap, k, ws, c, workspace_bytes - c.scratch_offset, step, W, X, x_dtype, B, in, out, dX, dW, path,
                                     stream, job, nullptr);
@@ -491,22 +508,22 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
     if (st != DBP_OK) return st;
     if (!step_ok(step)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
+    if (!path_ok(path)) return DBP_ERR_UNSUPPORTED;
+    if (path_family(path) == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     if (!workspace || workspace_bytes < c.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
     if (!aligned(delta, 4)) return DBP_ERR_SHAPE;
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
-    const AutoPlan ap = path == DBP_PATH_AUTO
+    const AutoPlan ap = path_family(path) == DBP_PATH_AUTO
         ? conv_auto_plan(conv_call(W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, k, ws + c.scratch_offset,
-                                   workspace_bytes - c.scratch_offset), P, Q)
+                                   workspace_bytes - c.scratch_offset, path_two_planes(path)), P, Q)
         : AutoPlan{false, 0};
     dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
     StatsJob job;
     st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, st_dev, (hipStream_t)stream,
-                 path == DBP_PATH_GATHER || ap.dual, &job);
+                 path_family(path) == DBP_PATH_GATHER || ap.dual, &job);
     if (st != DBP_OK) return st;
     return conv2d_products_dispatch(ap, k, ws, c, workspace_bytes - c.scratch_offset, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride,
                                     pad, dX, dW, path, stream, job, nullptr);
@@ -550,7 +567,7 @@ dbp_status conv2d_products_grouped(const int8_t *codes, const void *format, floa
     const int64_t Cg = C / groups, Kg = K / groups, HW = H * Wd;
     const size_t xsz = x_dtype == DBP_I8 ? 1 : 4;
     if (launch_stats_job(job, s) != hipSuccess) return DBP_ERR_DEVICE;
-    const bool gather = path == DBP_PATH_GATHER;
+    const bool gather = path_family(path) == DBP_PATH_GATHER;
     FormatView f{nullptr, nullptr, nullptr, 0};
     if (gather) {
         dbp_format_layout L;
@@ -565,6 +582,7 @@ dbp_status conv2d_products_grouped(const int8_t *codes, const void *format, floa
     a.Ct = C; a.Kt = K;
     a.scratch = gather ? nullptr : scratch; a.scratch_bytes = gather ? 0 : scratch_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; a.pending = nullptr; a.gate = Gate{};
+    a.two_planes = path_two_planes(path);
     if (!gather && grouped_as_block_diagonal(C, groups)) {
         const size_t bd = block_diagonal_bytes(C, K, R, S);
         float *w_full = (float *)scratch;
@@ -605,9 +623,9 @@ dbp_status check_grouped_call(const void *W, const void *X, const float *dX, con
     if (st != DBP_OK) return st;
     if ((st = check_groups(C, K, groups)) != DBP_OK) return st;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (!path_ok(path)) return DBP_ERR_UNSUPPORTED;
     // the gather kernels' limits, on the whole tensors (32-bit offsets into X, 16-bit plane numbers)
-    if (path == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, *P, *Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
+    if (path_family(path) == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, *P, *Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * *P * *Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     return DBP_OK;
 }
@@ -633,7 +651,7 @@ dbp_status dbp_conv2d_products_grouped(const int8_t *codes, const void *format, 
     dbp_status st = check_grouped_call(W, X, dX, dW, x_dtype, N, C, H, Wd, K, R, S, stride, pad, groups, path, &P, &Q);
     if (st != DBP_OK) return st;
     if (!step_ok(step)) return DBP_ERR_STEP;
-    if (path == DBP_PATH_GATHER) {
+    if (path_family(path) == DBP_PATH_GATHER) {
         if (!format) return DBP_ERR_NULL;
         if (!aligned(format, 256)) return DBP_ERR_WORKSPACE;
     } else {
@@ -661,7 +679,7 @@ dbp_status dithered_conv2d_backward_grouped(const float *delta, const float *W, 
     char *ws = (char *)workspace;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     StatsJob job;
-    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, path == DBP_PATH_GATHER, &job);
+    st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, stats, (hipStream_t)stream, path_family(path) == DBP_PATH_GATHER, &job);
     if (st != DBP_OK) return st;
     return conv2d_products_grouped(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, groups, dX, dW, ws + c.scratch_offset,
                                    workspace_bytes - c.scratch_offset, path, (hipStream_t)stream, job);
@@ -883,9 +901,9 @@ dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act
     if (st != DBP_OK) return st;
     if (!(s > 0.0f) || !std::isfinite(s)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
+    if (!path_ok(path)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && B * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
-    if (path == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
+    if (path_family(path) == DBP_PATH_GATHER && !linear_gather_supported(B, in, out)) return DBP_ERR_UNSUPPORTED;
     const Carve c = carve(B, out, linear_scratch_bytes(B, in, out));
     const LayerCarve lc = layer_carve(c.total, B * out, out);
     if (!workspace || workspace_bytes < lc.total || !aligned(workspace, 256)) return DBP_ERR_WORKSPACE;
@@ -901,11 +919,11 @@ dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act
     ex.bias_mode = DBP_BIAS_PER_COLUMN; ex.bias_len = out;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     StatsJob job;
-    const AutoPlan ap = path == DBP_PATH_AUTO && (dX || dW)
-        ? linear_auto_plan(linear_call(W, X, x_dtype, B, in, out, dX, dW, k, ws + c.scratch_offset, c.total - c.scratch_offset), true)
+    const AutoPlan ap = path_family(path) == DBP_PATH_AUTO && (dX || dW)
+        ? linear_auto_plan(linear_call(W, X, x_dtype, B, in, out, dX, dW, k, ws + c.scratch_offset, c.total - c.scratch_offset, path_two_planes(path)), true)
         : AutoPlan{false, 0};
     dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
-    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, st_dev, hs, path == DBP_PATH_GATHER, &job, &ex, true, &tree);
+    st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, st_dev, hs, path_family(path) == DBP_PATH_GATHER, &job, &ex, true, &tree);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     return linear_products_dispatch(ap, k, ws, c, c.total - c.scratch_offset, 1.0f, W, X, x_dtype, B, in, out, dX, dW, path, stream, job, pair);
@@ -924,8 +942,8 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     if (st != DBP_OK) return st;
     if (!(s > 0.0f) || !std::isfinite(s)) return DBP_ERR_STEP;
     if (x_dtype != DBP_F32 && x_dtype != DBP_I8) return DBP_ERR_DTYPE;
-    if (path != DBP_PATH_AUTO && path != DBP_PATH_MFMA && path != DBP_PATH_GATHER) return DBP_ERR_UNSUPPORTED;
-    if (path == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
+    if (!path_ok(path)) return DBP_ERR_UNSUPPORTED;
+    if (path_family(path) == DBP_PATH_GATHER && !conv_gather_supported(N, C, H, Wd, K, R, S, P, Q, dX != nullptr)) return DBP_ERR_UNSUPPORTED;
     if (x_dtype == DBP_I8 && dW && N * P * Q * 127 * 127 >= ((int64_t)1 << 31)) return DBP_ERR_OVERFLOW;
     const Carve c = carve(N * K, P * Q, conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride));
     const LayerCarve lc = layer_carve(c.total, N * K * P * Q, K);
@@ -942,12 +960,12 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
     ex.bias_mode = DBP_BIAS_PER_ROW_GROUP; ex.bias_len = K;
     int8_t *k = codes ? codes : (int8_t *)(ws + c.codes_offset);
     StatsJob job;
-    const AutoPlan ap = path == DBP_PATH_AUTO && (dX || dW)
+    const AutoPlan ap = path_family(path) == DBP_PATH_AUTO && (dX || dW)
         ? conv_auto_plan(conv_call(W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, k, ws + c.scratch_offset,
-                                   c.total - c.scratch_offset), P, Q)
+                                   c.total - c.scratch_offset, path_two_planes(path)), P, Q)
         : AutoPlan{false, 0};
     dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
-    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, st_dev, hs, path == DBP_PATH_GATHER || ap.dual, &job, &ex,
+    st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, st_dev, hs, path_family(path) == DBP_PATH_GATHER || ap.dual, &job, &ex,
                  true, &tree);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;

@@ -120,6 +120,7 @@ struct LinearArgs {
     StatsJob      stats_job;   // statistics sum still to be done on this stream (n == 0: none)
     Gate          gate;        // device-side dispatch (fast kernels only)
     int          *plan_only = nullptr;   // non-null: launch nothing, set *plan_only = 1 if some product would run on an ungated kernel
+    bool          two_planes = false;    // fp32 operands of the matrix-core kernels in two bf16 planes instead of three (DBP_PATH_TWO_PLANES)
 };
 struct ConvArgs {
     const int8_t *codes;
@@ -136,6 +137,7 @@ struct ConvArgs {
     int64_t       Ct = 0, Kt = 0;
     int64_t       k_first = 0;         // first code plane of the group inside an image's Kt planes (what the gather kernels' format rows need)
     bool          dx_zeroed = false;   // dX is already cleared (the strided dX kernels then skip their own clearing pass)
+    bool          two_planes = false;  // fp32 operands of the matrix-core kernels in two bf16 planes instead of three (DBP_PATH_TWO_PLANES)
     int64_t ct() const { return Ct ? Ct : C; }
     int64_t kt() const { return Kt ? Kt : K; }
     float        *dX;

@@ -60,7 +60,21 @@ template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&
 
 template <int MODE> struct CdwTraits;
 template <> struct CdwTraits<MODE_BF16> { using XT = float;  using XRaw = uint4;    using Acc = f32x16; using AccT = float;   static constexpr int PLANES = 3, ESZ = 2, FRAG = 8; };
+template <> struct CdwTraits<MODE_BF16X2> { using XT = float; using XRaw = uint4;   using Acc = f32x16; using AccT = float;   static constexpr int PLANES = 2, ESZ = 2, FRAG = 8; };
 template <> struct CdwTraits<MODE_I8>   { using XT = int8_t; using XRaw = uint32_t; using Acc = i32x16; using AccT = int32_t; static constexpr int PLANES = 1, ESZ = 1, FRAG = 16; };
+
+// The bf16 planes of two fp32 values, least significant plane first, packed (`a` in the low half of each word): three exact
+// planes, or two rounded to nearest.
+template <int PL> __device__ __forceinline__ void cdw_planes(float a, float b, uint32_t (&p)[PL])
+{
+    if constexpr (PL == 3) {
+        uint32_t ha, ma, la, hb, mb, lb;
+        split3(a, ha, ma, la); split3(b, hb, mb, lb);
+        p[0] = (la >> 16) | lb; p[1] = (ma >> 16) | mb; p[2] = (ha >> 16) | hb;
+    } else {
+        split2_pk(a, b, p[1], p[0]);
+    }
+}
 
 // The 16 bytes that start SB bytes into the 32 bytes {lo, hi}.
 template <int SB>
@@ -214,21 +228,20 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
     // One piece into LDS; `m` is the piece's validity mask (all ones or zero).
     auto put_x = [&](uint32_t addr, const XRaw &raw, uint32_t m) {
         char *d = (char *)cdw_lds + addr;
-        if constexpr (MODE == MODE_BF16) {
+        if constexpr (MODE != MODE_I8) {
             const uint32_t rw[4] = {raw.x & m, raw.y & m, raw.z & m, raw.w & m};
-            uint32_t hi[4], mid[4], lo[4];
+            uint32_t p01[PL], p23[PL];
+            cdw_planes<PL>(__uint_as_float(rw[0]), __uint_as_float(rw[1]), p01);
+            cdw_planes<PL>(__uint_as_float(rw[2]), __uint_as_float(rw[3]), p23);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) split3(__uint_as_float(rw[e]), hi[e], mid[e], lo[e]);
-            *(uint2 *)d                 = uint2{(lo[0] >> 16) | lo[1], (lo[2] >> 16) | lo[3]};
-            *(uint2 *)(d + x_plane)     = uint2{(mid[0] >> 16) | mid[1], (mid[2] >> 16) | mid[3]};
-            *(uint2 *)(d + 2 * x_plane) = uint2{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]};
+            for (int pl = 0; pl < PL; ++pl) *(uint2 *)(d + pl * x_plane) = uint2{p01[pl], p23[pl]};
         } else {
             *(uint32_t *)d = raw & m;
         }
     };
     auto put_c = [&](uint32_t addr, uint32_t t) {
         char *d = (char *)cdw_lds + addr;
-        if constexpr (MODE == MODE_BF16)
+        if constexpr (MODE != MODE_I8)
             *(uint2 *)d = uint2{bf16_pair_from_i8((int8_t)t, (int8_t)(t >> 8)), bf16_pair_from_i8((int8_t)(t >> 16), (int8_t)(t >> 24))};
         else
             *(uint32_t *)d = t;
@@ -298,35 +311,32 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
                 const int cl = xch + XCH * j;
                 const bool ok = x_ld && c0 + cl < a.C;
                 char *row = lds_x + (size_t)cl * a.pitchX * ESZ;
-                if constexpr (MODE == MODE_BF16) {
+                if constexpr (MODE != MODE_I8) {
                     const uint32_t rw[4] = {xr[j].x, xr[j].y, xr[j].z, xr[j].w};
-                    uint32_t hi[4], mid[4], lo[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) split3(ok ? __uint_as_float(rw[e]) : 0.0f, hi[e], mid[e], lo[e]);
+                    uint32_t pp[2][PL];                                  // elements (0, 1) and (2, 3)
+                    cdw_planes<PL>(ok ? __uint_as_float(rw[0]) : 0.0f, ok ? __uint_as_float(rw[1]) : 0.0f, pp[0]);
+                    cdw_planes<PL>(ok ? __uint_as_float(rw[2]) : 0.0f, ok ? __uint_as_float(rw[3]) : 0.0f, pp[1]);
                     if (a.row4x) {
                         if (pos[0] >= 0) {
                             char *d = row + pos[0] * ESZ;
-                            *(uint2 *)d                 = uint2{(lo[0] >> 16) | lo[1], (lo[2] >> 16) | lo[3]};
-                            *(uint2 *)(d + x_plane)     = uint2{(mid[0] >> 16) | mid[1], (mid[2] >> 16) | mid[3]};
-                            *(uint2 *)(d + 2 * x_plane) = uint2{(hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]};
+#pragma unroll
+                            for (int pl = 0; pl < PL; ++pl) *(uint2 *)(d + pl * x_plane) = uint2{pp[0][pl], pp[1][pl]};
                         }
                     } else if (a.row2x) {
 #pragma unroll
                         for (int e = 0; e < 4; e += 2)
                             if (pos[e] >= 0) {
                                 char *d = row + pos[e] * ESZ;
-                                *(uint32_t *)d                 = (lo[e] >> 16) | lo[e + 1];
-                                *(uint32_t *)(d + x_plane)     = (mid[e] >> 16) | mid[e + 1];
-                                *(uint32_t *)(d + 2 * x_plane) = (hi[e] >> 16) | hi[e + 1];
+#pragma unroll
+                                for (int pl = 0; pl < PL; ++pl) *(uint32_t *)(d + pl * x_plane) = pp[e >> 1][pl];
                             }
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
                             if (pos[e] >= 0) {
                                 char *d = row + pos[e] * ESZ;
-                                *(uint16_t *)d                 = (uint16_t)(lo[e] >> 16);
-                                *(uint16_t *)(d + x_plane)     = (uint16_t)(mid[e] >> 16);
-                                *(uint16_t *)(d + 2 * x_plane) = (uint16_t)(hi[e] >> 16);
+#pragma unroll
+                                for (int pl = 0; pl < PL; ++pl) *(uint16_t *)(d + pl * x_plane) = (uint16_t)(pp[e >> 1][pl] >> (16 * (e & 1)));
                             }
                     }
                 } else {
@@ -363,7 +373,7 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
                 const int kl = cch + CCH * j;
                 const uint32_t t = (c_ld && k0 + kl < a.K) ? cr[j] : 0u;
                 char *row = lds_c + (size_t)kl * a.pitchC * ESZ;
-                if constexpr (MODE == MODE_BF16) {
+                if constexpr (MODE != MODE_I8) {
                     const uint32_t b01 = bf16_pair_from_i8((int8_t)t, (int8_t)(t >> 8));
                     const uint32_t b23 = bf16_pair_from_i8((int8_t)(t >> 16), (int8_t)(t >> 24));
                     if (a.row4c) {
@@ -531,7 +541,7 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
                 if (k < a.K && c < a.C) {
 #pragma unroll
                     for (int t = 0; t < RS; ++t) {
-                        if constexpr (MODE == MODE_BF16) out[((int64_t)k * a.C + c) * RS + t] = acc[t][mb][v] * a.scale.get();
+                        if constexpr (MODE != MODE_I8) out[((int64_t)k * a.C + c) * RS + t] = acc[t][mb][v] * a.scale.get();
                         else out[((int64_t)k * a.C + c) * RS + t] = acc[t][mb][v];
                     }
                 }
@@ -570,7 +580,7 @@ __global__ __launch_bounds__(256) void conv_dw_reduce_kernel(ConvDwArgs a)
         const int k = kb + j;
         if (k < a.K && c < a.C) {
             AccT *out = (AccT *)a.dW + ((int64_t)k * a.C + c) * RS + t;
-            if constexpr (MODE == MODE_BF16) *out = sum[j] * a.scale.get(); else *out = sum[j];
+            if constexpr (MODE != MODE_I8) *out = sum[j] * a.scale.get(); else *out = sum[j];
         }
     }
 }

@@ -53,7 +53,8 @@ struct ConvDxArgs {
     Gate gate;
 };
 
-// fp32 weights [K][C][R][S] -> bf16 planes in fragment order (plane 0 = lo, 1 = mid, 2 = hi), zero padded.
+// fp32 weights [K][C][R][S] -> bf16 planes in fragment order (three planes: 0 = lo, 1 = mid, 2 = hi, their sum the weight exactly;
+// two planes: 0 = lo, 1 = hi, rounded to nearest, 16 significant bits), zero padded.
 // Prepared tap t holds real tap real[t] (the identity for stride 1; the classes' taps one after the other otherwise).
 struct CdxTapMap { uint8_t real[64]; };
 
@@ -117,7 +118,7 @@ __device__ __forceinline__ bool cdx_side_jobs(const StatsJob &job, int &workers)
     return true;
 }
 
-template <bool MAPPED>
+template <bool MAPPED, int PL>
 __global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W, uint4 *wp, int K, int C, int RS, int KG, int Cp, int RS_real, CdxTapMap map,
                                                                   StatsJob job)
 {
@@ -131,17 +132,27 @@ __global__ __launch_bounds__(256) void conv_dx_weight_prep_kernel(const float *W
         const int64_t t = i / Cp;
         const int kg = (int)(t % KG), tap = (int)(t / KG);
         const int rtap = MAPPED ? (int)lm[tap] : tap;
-        uint32_t h[8], m[8], l[8];
+        float w[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int k = kg * 8 + j;
-            const float w = (k < K && c < C) ? W[((int64_t)k * C + c) * RS_real + rtap] : 0.0f;
-            split3(w, h[j], m[j], l[j]);
+            w[j] = (k < K && c < C) ? W[((int64_t)k * C + c) * RS_real + rtap] : 0.0f;
         }
-        uint4 *dst = wp + ((int64_t)tap * KG + kg) * 3 * Cp + c;
-        dst[0]      = uint4{(l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]};
-        dst[Cp]     = uint4{(m[0] >> 16) | m[1], (m[2] >> 16) | m[3], (m[4] >> 16) | m[5], (m[6] >> 16) | m[7]};
-        dst[2 * Cp] = uint4{(h[0] >> 16) | h[1], (h[2] >> 16) | h[3], (h[4] >> 16) | h[5], (h[6] >> 16) | h[7]};
+        uint4 *dst = wp + ((int64_t)tap * KG + kg) * PL * Cp + c;
+        if constexpr (PL == 3) {
+            uint32_t h[8], m[8], l[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) split3(w[j], h[j], m[j], l[j]);
+            dst[0]      = uint4{(l[0] >> 16) | l[1], (l[2] >> 16) | l[3], (l[4] >> 16) | l[5], (l[6] >> 16) | l[7]};
+            dst[Cp]     = uint4{(m[0] >> 16) | m[1], (m[2] >> 16) | m[3], (m[4] >> 16) | m[5], (m[6] >> 16) | m[7]};
+            dst[2 * Cp] = uint4{(h[0] >> 16) | h[1], (h[2] >> 16) | h[3], (h[4] >> 16) | h[5], (h[6] >> 16) | h[7]};
+        } else {
+            uint32_t h[4], l[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) split2_pk(w[2 * j], w[2 * j + 1], h[j], l[j]);
+            dst[0]  = uint4{l[0], l[1], l[2], l[3]};
+            dst[Cp] = uint4{h[0], h[1], h[2], h[3]};
+        }
     }
 }
 
@@ -191,6 +202,7 @@ __global__ __launch_bounds__(256) void conv_dx_pad_codes_kernel(const int8_t *sr
 
 template <int MODE> struct CdxTraits;
 template <> struct CdxTraits<MODE_BF16> { static constexpr int G = 8,  PL = 3; using Acc = f32x16; using Out = float; };
+template <> struct CdxTraits<MODE_BF16X2> { static constexpr int G = 8, PL = 2; using Acc = f32x16; using Out = float; };
 template <> struct CdxTraits<MODE_I8>   { static constexpr int G = 16, PL = 1; using Acc = i32x16; using Out = int32_t; };
 
 __device__ __forceinline__ uint32_t cdx_bf16_pair(uint32_t wa, uint32_t wb, int e)

@@ -190,7 +190,8 @@ __device__ __forceinline__ int fc2_row(int a_kfast, int tile_m, int wave, int i,
 // NT: the batched form with both operands reduction-contiguous (the weight gradient of a 1x1 convolution straight from
 // NCHW tensors: rows = output channels, columns = input channels, reduction = the pixels of every image).  Only the
 // stagers' addresses and the order in which they read the dense operand's registers differ.
-template <bool NT>
+// PL: bf16 planes of the fp32 operand, 3 (exact) or 2 (rounded to nearest, 16 significant bits).
+template <bool NT, int PL = 3>
 __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 {
     extern __shared__ uint4 fc2_lds[];
@@ -366,7 +367,7 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
                     for (int j = 0; j < 4; ++j)
                         cell[64 * (4 * d + j)] = bf16x2_from_codes((int8_t)(w0[d] >> (8 * j)), (int8_t)(w1[d] >> (8 * j)));
             }
-            // fp32 -> three exact bf16 planes; column 4*nq+j -> position j*32+nq
+            // fp32 -> three exact bf16 planes (or two rounded ones); column 4*nq+j -> position j*32+nq
             // (NT: register i holds column 4*nq+i, its component j reduction index 4*kq+j -- the transposed arrangement)
             f32x4 bv[4] = {r.b[0], r.b[1], r.b[2], r.b[3]};
             if (dup > 0) {
@@ -379,13 +380,22 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uint32_t h[4], m[4], l[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) split3_upper(NT ? bv[j][i] : bv[i][j], h[i], m[i], l[i]);
                 const int pos = j * 32 + nq;
-                sm.b[0][kq >> 1][pos][kq & 1] = uint2{upper_halves(l[1], l[0]), upper_halves(l[3], l[2])};
-                sm.b[1][kq >> 1][pos][kq & 1] = uint2{upper_halves(m[1], m[0]), upper_halves(m[3], m[2])};
-                sm.b[2][kq >> 1][pos][kq & 1] = uint2{upper_halves(h[1], h[0]), upper_halves(h[3], h[2])};
+                if constexpr (PL == 3) {
+                    uint32_t h[4], m[4], l[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) split3_upper(NT ? bv[j][i] : bv[i][j], h[i], m[i], l[i]);
+                    sm.b[0][kq >> 1][pos][kq & 1] = uint2{upper_halves(l[1], l[0]), upper_halves(l[3], l[2])};
+                    sm.b[1][kq >> 1][pos][kq & 1] = uint2{upper_halves(m[1], m[0]), upper_halves(m[3], m[2])};
+                    sm.b[2][kq >> 1][pos][kq & 1] = uint2{upper_halves(h[1], h[0]), upper_halves(h[3], h[2])};
+                } else {
+                    uint32_t h[2], l[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        split2_pk(NT ? bv[j][2 * i] : bv[2 * i][j], NT ? bv[j][2 * i + 1] : bv[2 * i + 1][j], h[i], l[i]);
+                    sm.b[0][kq >> 1][pos][kq & 1] = uint2{l[0], l[1]};
+                    sm.b[1][kq >> 1][pos][kq & 1] = uint2{h[0], h[1]};
+                }
             }
         };
 
@@ -435,16 +445,16 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int ch = 2 * kk + lhalf;
-            u32x4 af[2], bf[3][4];
+            u32x4 af[2], bf[PL][4];
 #pragma unroll
             for (int i = 0; i < 2; ++i) af[i] = *(const u32x4 *)&sm.a[ch][wave * 64 + i * 32 + lcol][0];
 #pragma unroll
-            for (int pl = 0; pl < 3; ++pl)
+            for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) bf[pl][j] = *(const u32x4 *)&sm.b[pl][ch][j * 32 + lcol][0];
             // planes outermost: consecutive instructions accumulate into different blocks
 #pragma unroll
-            for (int pl = 0; pl < 3; ++pl)
+            for (int pl = 0; pl < PL; ++pl)
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll

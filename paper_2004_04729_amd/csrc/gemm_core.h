@@ -27,7 +27,7 @@
 
 namespace dbp {
 
-enum { MODE_BF16 = 0, MODE_I8 = 1, MODE_F32 = 2 };
+enum { MODE_BF16 = 0, MODE_I8 = 1, MODE_F32 = 2, MODE_BF16X2 = 3 };   // MODE_BF16X2: kernels with prepared operands only (two planes, below)
 
 constexpr int TM = 256, TN = 128, NCHUNK = 4;
 
@@ -69,6 +69,23 @@ __device__ __forceinline__ void split3(float x, uint32_t &hi, uint32_t &mid, uin
     mid = __float_as_uint(r1) & 0xFFFF0000u;
     float r2 = r1 - __uint_as_float(mid);
     lo = __float_as_uint(r2) & 0xFFFF0000u;
+}
+
+// Two-plane form of an fp32 operand, for callers that ask for it: x ~ hi + lo, hi the bf16 nearest to x, lo the bf16 nearest
+// to the rest; |x - hi - lo| <= 2^-16 |x| (two round-to-nearest-even steps of 2^-8 each: a bf16 has 8 significant bits).
+// Two values at a time with the hardware's packed conversion (v_cvt_pk_bf16_f32): `a` lands in the low half of each result,
+// which is also the order of a fragment's elements.  Values beyond the bf16 range (|x| > 3.39e38) round to infinity, as
+// IEEE conversion does, and their products are not finite.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float  f32x2_t  __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pack_nearest(float a, float b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{a, b}, bf16x2_t));
+}
+__device__ __forceinline__ void split2_pk(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    hi = bf16_pack_nearest(a, b);
+    lo = bf16_pack_nearest(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
 }
 
 // The same split for callers that pack the pieces with a byte permute of the upper halves: `lo` keeps its lower 16 bits
@@ -264,6 +281,7 @@ template <> struct Mma<MODE_BF16> {
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
 };
+template <> struct Mma<MODE_BF16X2> : Mma<MODE_BF16> {};
 template <> struct Mma<MODE_I8> {
     static __device__ __forceinline__ void run(const u32x4 &a, const u32x4 &b, i32x16 &c)
     {

@@ -579,8 +579,11 @@ hipError_t launch_conv1x1_dw(const ConvArgs &a, const Conv1x1Plan &pl, const int
     if (!raised) {
         hipError_t e = I8 ? hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_i8_pair_kernel<true>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, FC2I_LDS_BYTES)
-                          : hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel<true>),
+                          : hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel<true, 3>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, FC2_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        if (!I8) e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel<true, 2>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, FC2_LDS_BYTES);
         if (e != hipSuccess) return e;
         raised = true;
     }
@@ -600,7 +603,8 @@ hipError_t launch_conv1x1_dw(const ConvArgs &a, const Conv1x1Plan &pl, const int
     pa.gate = a.gate;
     const int grid = p.n_items < 256 ? p.n_items : 256;
     if constexpr (I8) hipLaunchKernelGGL(fc2_i8_pair_kernel<true>, dim3(grid), dim3(512), FC2I_LDS_BYTES, s, pa);
-    else              hipLaunchKernelGGL(fc2_pair_kernel<true>, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
+    else if (a.two_planes) hipLaunchKernelGGL((fc2_pair_kernel<true, 2>), dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
+    else              hipLaunchKernelGGL((fc2_pair_kernel<true, 3>), dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (pl.n_split > 1) {
@@ -807,7 +811,10 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
         if (use_fc2) {
             static bool raised = false;
             if (!raised) {
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel<false>),
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel<false, 3>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, FC2_LDS_BYTES);
+                if (e != hipSuccess) return e;
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fc2_pair_kernel<false, 2>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, FC2_LDS_BYTES);
                 if (e != hipSuccess) return e;
                 raised = true;
@@ -826,7 +833,8 @@ hipError_t launch_linear_mfma(const LinearArgs &a, hipStream_t s)
             pa.gx = gx; pa.gate = a.gate;
             const int total = pa.prob[0].n_items + pa.prob[1].n_items;
             const int grid = total < 256 ? total : 256;    // persistent: one workgroup per CU (256 whenever gx > 0)
-            hipLaunchKernelGGL(fc2_pair_kernel<false>, dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
+            if (a.two_planes) hipLaunchKernelGGL((fc2_pair_kernel<false, 2>), dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
+            else              hipLaunchKernelGGL((fc2_pair_kernel<false, 3>), dim3(grid), dim3(512), FC2_LDS_BYTES, s, pa);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
             const bool r0 = dx_fast && pdx.n_split > 1, r1 = dw_fast && pdw.n_split > 1;
@@ -970,13 +978,14 @@ hipError_t launch_zero_words(void *p, int64_t n_words, hipStream_t s)
 // ------------------------------------------------------------------------------------------------
 // Convolution (fast dX kernel: any stride; fast dW kernels: stride 1; the generic kernel serves the rest).
 // ------------------------------------------------------------------------------------------------
-template <int MODE_G>
-static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipStream_t s)
+template <int MODE_G, int MODE_K>
+static hipError_t conv_dx_run(const ConvArgs &a, const void *grad, Scale scale, hipStream_t s)
 {
-    // MODE_G: MODE_BF16 (codes, fp32 weights), MODE_I8 (codes, int8 weights) or MODE_F32 (dense).
+    // MODE_G: MODE_BF16 (codes, fp32 weights), MODE_I8 (codes, int8 weights) or MODE_F32 (dense).  MODE_K: the fast kernels'
+    // mode, MODE_G itself or MODE_BF16X2 (fp32 weights in two planes).
     if constexpr (MODE_G != MODE_F32) {
         constexpr bool I8 = MODE_G == MODE_I8;
-        constexpr int PL = I8 ? 1 : 3;
+        constexpr int PL = CdxTraits<MODE_K>::PL;
         auto prepare = [&](int taps, int KG, int Cp, const CdxTapMap *map) {
             const int64_t cells = (int64_t)taps * KG * Cp;
             int pb = (int)((cells + 255) / 256 < 4096 ? (cells + 255) / 256 : 4096);
@@ -988,8 +997,8 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
                 if (map) hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel<true>, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map, job);
                 else     hipLaunchKernelGGL(conv_dx_weight_prep_i8_kernel<false>, dim3(pb), dim3(256), 0, s, a.W8, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{}, job);
             } else {
-                if (map) hipLaunchKernelGGL(conv_dx_weight_prep_kernel<true>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map, job);
-                else     hipLaunchKernelGGL(conv_dx_weight_prep_kernel<false>, dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{}, job);
+                if (map) hipLaunchKernelGGL((conv_dx_weight_prep_kernel<true, PL>), dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, *map, job);
+                else     hipLaunchKernelGGL((conv_dx_weight_prep_kernel<false, PL>), dim3(pb), dim3(256), 0, s, a.W, (uint4 *)a.scratch, (int)a.K, (int)a.C, taps, KG, Cp, rs, CdxTapMap{}, job);
             }
         };
         // The codes as the kernel wants them: planes that start on 4-byte boundaries.  Planes of a size that is not a
@@ -1028,9 +1037,9 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
                         k.code_img = (pad_codes ? a.K : a.kt()) * k.PQ; k.dx_img = a.ct() * k.oPI;
                         k.wp = (const uint4 *)a.scratch + (int64_t)sp.tap_base[i] * KG * PL * Cp;
                     }
-                    if (sp.nb == 7)      hipLaunchKernelGGL((conv_dx_multi_kernel<7, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
-                    else if (sp.nb == 4) hipLaunchKernelGGL((conv_dx_multi_kernel<4, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
-                    else                 hipLaunchKernelGGL((conv_dx_multi_kernel<2, MODE_G>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
+                    if (sp.nb == 7)      hipLaunchKernelGGL((conv_dx_multi_kernel<7, MODE_K>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
+                    else if (sp.nb == 4) hipLaunchKernelGGL((conv_dx_multi_kernel<4, MODE_K>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
+                    else                 hipLaunchKernelGGL((conv_dx_multi_kernel<2, MODE_K>), dim3(sp.grid), dim3(256), sp.lds_bytes, s, sp.multi);
                 }
                 return hipGetLastError();
             }
@@ -1046,13 +1055,13 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
             const bool ring3 = (k.R * k.S) % 3 == 0;
             const dim3 grid(pl.grid), block(256);
             if (ring3) {
-                if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G, true>), grid, block, pl.lds_bytes, s, k);
-                else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G, true>), grid, block, pl.lds_bytes, s, k);
-                else                 hipLaunchKernelGGL((conv_dx_kernel<2, MODE_G, true>), grid, block, pl.lds_bytes, s, k);
+                if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_K, true>), grid, block, pl.lds_bytes, s, k);
+                else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_K, true>), grid, block, pl.lds_bytes, s, k);
+                else                 hipLaunchKernelGGL((conv_dx_kernel<2, MODE_K, true>), grid, block, pl.lds_bytes, s, k);
             } else {
-                if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_G, false>), grid, block, pl.lds_bytes, s, k);
-                else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_G, false>), grid, block, pl.lds_bytes, s, k);
-                else                 hipLaunchKernelGGL((conv_dx_kernel<2, MODE_G, false>), grid, block, pl.lds_bytes, s, k);
+                if (pl.nb == 7)      hipLaunchKernelGGL((conv_dx_kernel<7, MODE_K, false>), grid, block, pl.lds_bytes, s, k);
+                else if (pl.nb == 4) hipLaunchKernelGGL((conv_dx_kernel<4, MODE_K, false>), grid, block, pl.lds_bytes, s, k);
+                else                 hipLaunchKernelGGL((conv_dx_kernel<2, MODE_K, false>), grid, block, pl.lds_bytes, s, k);
             }
             return hipGetLastError();
         }
@@ -1075,6 +1084,15 @@ static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipS
     ConvDxOut om{g.Ct, g.H * g.Wd};
     return run_gemm<MODE_G>(al, bl, om, M, g.C, Kred, k_step<MODE_G>(), scale, (Acc *)a.dX,
                             (char *)a.scratch + rb, a.scratch_bytes - rb, s);
+}
+
+template <int MODE_G>
+static hipError_t conv_dx(const ConvArgs &a, const void *grad, Scale scale, hipStream_t s)
+{
+    if constexpr (MODE_G == MODE_BF16) {
+        if (a.two_planes) return conv_dx_run<MODE_G, MODE_BF16X2>(a, grad, scale, s);
+    }
+    return conv_dx_run<MODE_G, MODE_G>(a, grad, scale, s);
 }
 
 template <int MODE>
@@ -1101,6 +1119,10 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
             ConvDwArgs &k = pl.args;
             k.codes = (const int8_t *)grad; k.X = a.X; k.dW = a.dW; k.partial = (char *)a.scratch + rb; k.scale = scale; k.gate = a.gate;
             k.Ct = (int)a.ct(); k.Kt = (int)a.kt();
+            if constexpr (MODE == MODE_BF16) {
+                if (a.two_planes)
+                    return a.pad == 1 ? launch_conv_dw_fast<MODE_BF16X2, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE_BF16X2, 3, 3, 0, 1>(pl, s);
+            }
             return a.pad == 1 ? launch_conv_dw_fast<MODE, 3, 3, 1, 1>(pl, s) : launch_conv_dw_fast<MODE, 3, 3, 0, 1>(pl, s);
         }
     }
@@ -1142,7 +1164,7 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
             la.B = a.K; la.in = lp.CRS; la.out = lp.NPQ;
             la.dX = (float *)a.dW; la.dW = nullptr;
             la.scratch = col + lp.col_bytes; la.scratch_bytes = lp.fc_bytes;
-            la.stats_job = StatsJob{};
+            la.stats_job = StatsJob{}; la.two_planes = a.two_planes;
             return launch_linear_mfma(la, s);
         }
     }
