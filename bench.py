@@ -87,6 +87,19 @@ def main():
     def med(fn, iters, warm=3):
         return timed(fn, iters, warm)["median"]
 
+    def captured(call):
+        """A HIP graph of call(stream_handle): the library allocates and synchronises nothing, so its calls can be captured; replays
+        save the host's launch work and the gaps between dependent kernels."""
+        side = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            call(side.cuda_stream)                                   # eager first: one-time function attributes are set outside a capture
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            call(torch.cuda.current_stream().cuda_stream)
+        return g
+
     def conv_buffers(p, sets=1):
         N, Cc, H, Wd = p.X.shape
         K, _, R, S = p.W.shape
@@ -106,10 +119,10 @@ def main():
         dims = (N, Cc, H, Wd, K, R, S)
         return out, dims, xd
 
-    def conv_call(b, dims, xd, p, step, path=dbp.PATH_AUTO, dX=True, dW=True):
+    def conv_call(b, dims, xd, p, step, path=dbp.PATH_AUTO, dX=True, dW=True, on=None):
         N, Cc, H, Wd, K, R, S = dims
         dbp.dithered_conv2d_backward(b["d"], b["W"], b["X"], xd, N, Cc, H, Wd, K, R, S, p.stride, p.pad, step, p.seed, 0, b["codes"],
-                                     b["dX"] if dX else None, b["dW"] if dW else None, b["ws"], b["st"], path, stream)
+                                     b["dX"] if dX else None, b["dW"] if dW else None, b["ws"], b["st"], path, stream if on is None else on)
 
     def gate_flag(ws, rows, cols):
         """-1: one family was launched; 0 / 1: both were, and the matrix-core / the gather kernels ran."""
@@ -259,6 +272,9 @@ def main():
                 "1e-4 tolerance); NOT the headline, which multiplies the exact three-plane split",
     }
 
+    graphs5 = [captured(lambda st_, b=b: conv_call(b, dims5, xd5, p5, p5.step, on=st_)) for b in sets5]
+    t_graph5 = med(lambda i: graphs5[i % 2].replay(), max(20, args.steps // 2))
+
     out_line = {
         "metric": "dithered backward dense-equiv TFLOP/s (NSD + dX + dW, one call on config 5: VGG conv3-shaped layer, 8-bit mode)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -272,10 +288,11 @@ def main():
         "ms_per_step_mean": t_mean * 1e3, "ms_per_step_min": min(per_step) * 1e3, "host_wall_ms_per_step": wall * 1e3,
         "kernels_cfg5_us": kernels5,
         "two_plane_operands": two_planes,
+        "hip_graph_replay_ms_per_step": t_graph5 * 1e3,
     }
 
     if not args.headline_only:
-        out_line["configs"] = bench_rows(dbp, workloads, torch, np, med, timed, stream, conv_buffers, conv_call, gate_flag, arm_flag, PATH_NAME,
+        out_line["configs"] = bench_rows(dbp, workloads, torch, np, med, timed, captured, stream, conv_buffers, conv_call, gate_flag, arm_flag, PATH_NAME,
                                          sets5, dims5, xd5, p5)
         out_line["nsd_2^28"] = bench_nsd(dbp, torch, np, med, stream)
 
@@ -349,7 +366,7 @@ def bench_nsd(dbp, torch, np, med, stream):
     return nsd
 
 
-def bench_rows(dbp, workloads, torch, np, med, timed, stream, conv_buffers, conv_call, gate_flag, arm_flag, PATH_NAME, sets5, dims5, xd5, p5):
+def bench_rows(dbp, workloads, torch, np, med, timed, captured, stream, conv_buffers, conv_call, gate_flag, arm_flag, PATH_NAME, sets5, dims5, xd5, p5):
     """Rows for every configuration besides the headline step: dithered vs the same library's dense backward, the sweeps
     over the sparsity, the gather kernels, structured gradients."""
     dev = torch.device("cuda:0")
@@ -450,15 +467,18 @@ def bench_rows(dbp, workloads, torch, np, med, timed, stream, conv_buffers, conv
                     dW=torch.empty((out, in_), dtype=torch.float32, device=dev),
                     ws=torch.zeros(dbp.linear_workspace_bytes(B, in_, out), dtype=torch.uint8, device=dev), st=torch.zeros(32, dtype=torch.uint8, device=dev))
 
-    def linear_call(b, step=None, path=dbp.PATH_AUTO, dX=True, dW=True):
+    def linear_call(b, step=None, path=dbp.PATH_AUTO, dX=True, dW=True, on=None):
         p = b["p"]
         B, in_, out = p.dims
         dbp.dithered_linear_backward(b["d"], b["W"], b["X"], dbp.F32, B, in_, out, p.step if step is None else step, p.seed, 0, b["codes"],
-                                     b["dX"] if dX else None, b["dW"] if dW else None, b["ws"], b["st"], path, stream)
+                                     b["dX"] if dX else None, b["dW"] if dW else None, b["ws"], b["st"], path, stream if on is None else on)
 
     b1 = linear_buffers(workloads.config1())
     t1 = med(lambda i: linear_call(b1), 50)
-    res["cfg1"] = {"us": t1 * 1e6, "sparsity": 1 - dbp.Stats.from_tensor(b1["st"]).nnz / b1["d"].numel(), "note": "launch bound: 3 launches"}
+    g1 = captured(lambda st_: linear_call(b1, on=st_))
+    res["cfg1"] = {"us": t1 * 1e6, "us_hip_graph_replay": med(lambda i: g1.replay(), 50) * 1e6,
+                   "sparsity": 1 - dbp.Stats.from_tensor(b1["st"]).nnz / b1["d"].numel(), "note": "launch bound: 3 launches"}
+    del g1
 
     NSETS = 3
     mlp = {}
@@ -480,6 +500,13 @@ def bench_rows(dbp, workloads, torch, np, med, timed, stream, conv_buffers, conv
             for bq in sets[i % NSETS]:
                 linear_call(bq, path=dbp.PATH_AUTO | dbp.PATH_TWO_PLANES)
         row["ms_auto_two_planes"] = med(step2, 60, warm=5) * 1e3
+        if c == 8.0:
+            def chain(st_, k):
+                for bq in sets[k]:
+                    linear_call(bq, on=st_)
+            gs = [captured(lambda st_, k=k: chain(st_, k)) for k in range(NSETS)]
+            row["ms_auto_hip_graph_replay"] = med(lambda i: gs[i % NSETS].replay(), 60, warm=5) * 1e3
+            del gs
         row["sparsity_per_layer"] = [round(1 - dbp.Stats.from_tensor(bq["st"]).nnz / bq["d"].numel(), 4) for bq in sets[0]]
         row["dense_equiv_tflops_auto"] = dense_flops / (row["ms_auto"] * 1e-3) / 1e12
         # the gather kernels alone on the 4096x4096 layer: the method's own work, 2*nnz*in per product, against the fp32 vector peak
