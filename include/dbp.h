@@ -410,6 +410,10 @@ dbp_status dithered_conv2d_backward_q8(const float *delta, const int8_t *W8, con
 int dbp_plan_check_linear(int64_t B, int64_t in, int64_t out);
 int dbp_plan_check_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
                           int64_t stride, int64_t pad);
+/* The same for the plans of the gather kernels that scan the code planes (3x3 and 1x1 layers): bands, tile sizes, LDS, the
+ * reciprocals that replace divisions, the share of `scratch_bytes` of workspace they would use.  int8_x: X is DBP_I8. */
+int dbp_plan_check_conv2d_gather(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                                 int64_t stride, int64_t pad, int int8_x, size_t scratch_bytes);
 
 #ifdef __cplusplus
 }

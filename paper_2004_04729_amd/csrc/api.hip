@@ -287,7 +287,10 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
         ConvArgs g;
         g.codes = codes; g.dense = nullptr; g.step = step; g.step_dev = step_dev; g.W = W; g.W8 = nullptr; g.X = X; g.x_dtype = x_dtype;
         g.N = N; g.C = C; g.H = H; g.Wd = Wd; g.K = K; g.R = R; g.S = S; g.pad = pad; g.stride = stride;
-        g.dX = dX; g.dW = dW; g.scratch = nullptr; g.scratch_bytes = 0;
+        // the kernels that read the code plane keep prepared weights and partial sums in the workspace; without one the kernels
+        // that walk the format's entries serve
+        const bool ws_ok = workspace && aligned(workspace, 256);
+        g.dX = dX; g.dW = dW; g.scratch = ws_ok ? workspace : nullptr; g.scratch_bytes = ws_ok ? workspace_bytes : 0;
         g.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; g.pending = nullptr; g.gate = gate;
         if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
         return launch_conv_gather(g, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
@@ -580,7 +583,8 @@ dbp_status conv2d_products_grouped(const int8_t *codes, const void *format, floa
     a.dense = nullptr; a.step = step; a.step_dev = nullptr; a.W8 = nullptr; a.x_dtype = x_dtype;
     a.N = N; a.C = Cg; a.H = H; a.Wd = Wd; a.K = Kg; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.Ct = C; a.Kt = K;
-    a.scratch = gather ? nullptr : scratch; a.scratch_bytes = gather ? 0 : scratch_bytes;
+    const bool gather_ws = gather && scratch && aligned(scratch, 256);
+    a.scratch = gather && !gather_ws ? nullptr : scratch; a.scratch_bytes = gather && !gather_ws ? 0 : scratch_bytes;
     a.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; a.pending = nullptr; a.gate = Gate{};
     a.two_planes = path_two_planes(path);
     if (!gather && grouped_as_block_diagonal(C, groups)) {

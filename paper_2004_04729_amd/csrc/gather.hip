@@ -7,8 +7,11 @@
 // columns feeds four multiply-adds, so the staged tile is shared by all rows of the block and the dense operand leaves
 // HBM / L2 once per workgroup.  The one-row-per-workgroup kernels
 // further down serve the shapes it declines (odd strides and alignments, int8 activations).
-// Convolutions: conv_d{x,w}_gather_kernel walk the compacted entries of the tile-sparse format.
+// Convolutions: conv_dw_rows_kernel / conv_dx_rows_kernel (conv_rows_kernel.h: 3x3 and 1x1 layers whose planes are a multiple of
+// 4 bytes; dX: stride 1) read the code plane, lanes = channels; conv_d{x,w}_gather_kernel, which walk the compacted entries of
+// the tile-sparse format with a lane per (channel, tap), serve every other shape.
 #include "common.h"
+#include "conv_rows_kernel.h"
 
 namespace dbp {
 
@@ -530,8 +533,249 @@ bool conv_gather_supported(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t 
     return true;
 }
 
+// ---- host side of conv_rows_kernel.h ---------------------------------------------------------------------
+namespace {
+
+constexpr size_t kRowsLdsTwo = 75 * 1024, kRowsLdsOne = 150 * 1024;     // LDS budget of a workgroup: two per CU, else one
+
+bool rows_shape_ok(const ConvArgs &a, int64_t P, int64_t Q)
+{
+    const bool taps = (a.R == 3 && a.S == 3) || (a.R == 1 && a.S == 1);
+    return taps && (P * Q) % 4 == 0 && (uintptr_t)a.codes % 4 == 0 && Q >= 2 && Q <= 253 && P < 32768 &&
+           a.H * a.Wd < ((int64_t)1 << 24) && a.K * a.C * a.R * a.S < ((int64_t)1 << 31);
+}
+
+struct DwRowsPlan { bool ok; ConvDwRowsArgs k; size_t lds, partial_bytes; int grid; };
+
+// `avail`: bytes of scratch the shares' partial sums may use.
+DwRowsPlan conv_dw_rows_plan(const ConvArgs &a, int64_t P, int64_t Q, size_t avail)
+{
+    DwRowsPlan pl{};
+    if (!rows_shape_ok(a, P, Q)) return pl;
+    const int64_t csb = a.x_dtype == DBP_F32 ? 65 * 4 : 68, st = a.stride;
+    const int64_t Wp = (Q - 1) * st + a.S;
+    int64_t TH = 0;
+    for (size_t budget : {kRowsLdsTwo, kRowsLdsOne}) {
+        int64_t thx = (int64_t)budget / (Wp * csb);
+        if (thx > 64 * CGR_MAX_CHUNKS / Wp) thx = 64 * CGR_MAX_CHUNKS / Wp;
+        if (thx < a.R) continue;
+        TH = (thx - a.R) / st + 1;
+        break;
+    }
+    if (TH > P) TH = P;
+    if (TH > (256 * CGR_MAX_LOADS - 4) / Q) TH = (256 * CGR_MAX_LOADS - 4) / Q;
+    if (TH < 1) return pl;
+    ConvDwRowsArgs &k = pl.k;
+    k.N = (int)a.N; k.C = (int)a.C; k.K = (int)a.K; k.H = (int)a.H; k.Wd = (int)a.Wd; k.P = (int)P; k.Q = (int)Q;
+    k.pad = (int)a.pad; k.st = (int)st; k.Ct = (int)a.ct(); k.Kt = (int)a.kt();
+    k.bands = (int)((P + TH - 1) / TH);
+    k.TH = (int)((P + k.bands - 1) / k.bands);                        // bands of equal height
+    k.THx = (k.TH - 1) * k.st + (int)a.R; k.Wp = (int)Wp;
+    k.cells = k.THx * k.Wp; k.n_chunks = (k.cells + 63) / 64;
+    pl.lds = ((size_t)k.cells * csb + 15) & ~(size_t)15;
+    const int64_t units = a.N * k.bands;
+    if (units >= ((int64_t)1 << 30)) return pl;
+    const int64_t columns = ((a.C + 63) / 64) * ((a.K + CGR_KB - 1) / CGR_KB);
+    const int64_t slots = pl.lds <= kRowsLdsTwo ? 512 : 256;
+    int64_t want = slots / columns < 1 ? 1 : slots / columns;
+    if (want > units) want = units;
+    const size_t dw_bytes = (size_t)(a.K * a.C * a.R * a.S) * 4;
+    if (want > 1 && (size_t)want * dw_bytes > avail) want = (int64_t)(avail / dw_bytes);
+    if (want < 1) want = 1;
+    k.units = (int)units;
+    k.units_per_split = (int)((units + want - 1) / want);
+    k.n_split = (int)((units + k.units_per_split - 1) / k.units_per_split);
+    k.q_magic = (uint32_t)((((uint64_t)1 << 32) / (uint64_t)Q) + 1);
+    k.wp_magic = (uint32_t)((((uint64_t)1 << 32) / (uint64_t)Wp) + 1);
+    pl.partial_bytes = k.n_split > 1 ? (size_t)k.n_split * dw_bytes : 0;
+    if (columns * k.n_split >= ((int64_t)1 << 31)) return pl;
+    pl.grid = (int)(columns * k.n_split);
+    pl.ok = true;
+    return pl;
+}
+
+template <class XT, int R, int S>
+hipError_t launch_conv_dw_rows_as(const DwRowsPlan &pl, hipStream_t s)
+{
+    static bool raised = false;                                       // more than 64 KiB of dynamic LDS: allowed per kernel, once
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dw_rows_kernel<XT, R, S>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kRowsLdsOne);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((conv_dw_rows_kernel<XT, R, S>), dim3(pl.grid), dim3(CGR_WAVES * 64), pl.lds, s, pl.k);
+    return hipGetLastError();
+}
+
+struct DxRowsPlan { bool ok; ConvDxRowsArgs k; size_t lds, prep_bytes; int grid, threads; };
+
+DxRowsPlan conv_dx_rows_plan(const ConvArgs &a, int64_t P, int64_t Q, size_t avail)
+{
+    DxRowsPlan pl{};
+    if (!rows_shape_ok(a, P, Q) || a.stride != 1 || a.Wd < 2) return pl;
+    const int64_t Cp = (a.C + 63) / 64 * 64, Wp = Q + a.S - 1, row_bytes = Wp * 65 * 4, RS = a.R * a.S;
+    const int64_t Kp = (a.K + CGR_KC - 1) / CGR_KC * CGR_KC;
+    pl.prep_bytes = (size_t)(Kp * RS * Cp) * 4;
+    if (pl.prep_bytes > avail || Kp * RS * Cp >= ((int64_t)1 << 31) || (CGR_KC + 1) * P * Q >= ((int64_t)1 << 31)) return pl;
+    // LDS of a workgroup with TH output rows: the rows' accumulators, two chunks of weights, two chunks of code stretches
+    auto threads_of = [](int64_t th) { return th <= 4 ? 256 : th <= 8 ? 512 : 1024; };
+    auto cb_words_of = [&](int64_t th) { const int64_t w = ((th + a.R - 1) * Q + 3 + 3) / 4; return w < 2 ? (int64_t)2 : w; };
+    auto lds_of = [&](int64_t th) { return th * row_bytes + 2 * (CGR_KC * RS * 64 * 4 + CGR_KC * cb_words_of(th) * 4); };
+    auto fits = [&](int64_t th, int64_t budget) { return lds_of(th) <= budget && CGR_KC * cb_words_of(th) <= CGR_DX_CPT * threads_of(th); };
+    const int64_t th_cap = a.H < CGR_DX_MAX_ROWS ? a.H : CGR_DX_MAX_ROWS;
+    int64_t TH = 0;
+    for (int64_t budget : {(int64_t)79 * 1024, (int64_t)158 * 1024}) {           // two workgroups per CU if at least 8 rows (or the image) fit
+        int64_t th = th_cap;
+        while (th >= 1 && !fits(th, budget)) --th;
+        if (th >= 1 && (th >= 8 || th == th_cap || budget > 79 * 1024)) { TH = th; break; }
+    }
+    if (TH < 1) return pl;
+    ConvDxRowsArgs &k = pl.k;
+    k.N = (int)a.N; k.C = (int)a.C; k.K = (int)a.K; k.H = (int)a.H; k.Wd = (int)a.Wd; k.P = (int)P; k.Q = (int)Q;
+    k.pad = (int)a.pad; k.Ct = (int)a.ct(); k.Kt = (int)a.kt(); k.Cp = (int)Cp;
+    k.bands = (int)((a.H + TH - 1) / TH);
+    k.TH = (int)((a.H + k.bands - 1) / k.bands);                      // bands of equal height (never more rows than TH: still fits)
+    k.Wp = (int)Wp;
+    k.cb_words = (int)cb_words_of(k.TH);
+    k.cbw_magic = (uint32_t)((((uint64_t)1 << 32) / (uint64_t)k.cb_words) + 1);
+    k.wd_magic = (uint32_t)((((uint64_t)1 << 32) / (uint64_t)a.Wd) + 1);
+    k.q_magic = (uint32_t)((((uint64_t)1 << 32) / (uint64_t)Q) + 1);
+    pl.lds = ((size_t)lds_of(k.TH) + 15) & ~(size_t)15;
+    const int64_t grid = a.N * k.bands * (Cp / 64);
+    if (grid >= ((int64_t)1 << 31)) return pl;
+    pl.grid = (int)grid; pl.threads = (int)threads_of(k.TH);
+    pl.ok = true;
+    return pl;
+}
+
+template <int R, int S, int NT>
+hipError_t launch_conv_dx_rows_nt(const DxRowsPlan &pl, hipStream_t s)
+{
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dx_rows_kernel<R, S, NT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((conv_dx_rows_kernel<R, S, NT>), dim3(pl.grid), dim3(NT), pl.lds, s, pl.k);
+    return hipGetLastError();
+}
+
+template <int R, int S>
+hipError_t launch_conv_dx_rows_as(const DxRowsPlan &pl, const float *W, hipStream_t s)
+{
+    const int Kp = (pl.k.K + CGR_KC - 1) / CGR_KC * CGR_KC;
+    const int64_t total = (int64_t)Kp * R * S * pl.k.Cp;
+    const int pb = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+    hipLaunchKernelGGL(conv_dx_rows_prep_kernel, dim3(pb), dim3(256), 0, s, W, (float *)pl.k.Wt, pl.k.K, Kp, pl.k.C, R * S, pl.k.Cp, pl.k.gate);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return pl.threads == 256 ? launch_conv_dx_rows_nt<R, S, 256>(pl, s) : pl.threads == 512 ? launch_conv_dx_rows_nt<R, S, 512>(pl, s)
+                                                                                            : launch_conv_dx_rows_nt<R, S, 1024>(pl, s);
+}
+
+}  // namespace
+
+// Host-side walk of the plans above for one layer shape (no GPU call): every limit the kernels rely on, re-derived here from
+// the plan's numbers.  0: consistent (or the shape takes the other kernels); otherwise the number of the violated invariant.
+int check_conv_rows_plans(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
+                          bool int8_x, size_t scratch_bytes)
+{
+    ConvArgs a{};
+    a.codes = nullptr; a.x_dtype = int8_x ? DBP_I8 : DBP_F32;
+    a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
+    const int64_t P = (H + 2 * pad - R) / stride + 1, Q = (Wd + 2 * pad - S) / stride + 1;
+    const DwRowsPlan w = conv_dw_rows_plan(a, P, Q, scratch_bytes);
+    if (w.ok) {
+        const ConvDwRowsArgs &k = w.k;
+        const int64_t csb = int8_x ? 68 : 260;
+        if (k.TH < 1 || (int64_t)k.bands * k.TH < P || (int64_t)(k.bands - 1) * k.TH >= P) return 1;     // the bands cover the code rows, none is empty
+        if (k.THx != (k.TH - 1) * k.st + R || k.Wp != (Q - 1) * stride + S || k.cells != k.THx * k.Wp) return 2;
+        if (k.n_chunks > CGR_MAX_CHUNKS || (int64_t)k.n_chunks * 64 < k.cells) return 3;
+        if ((int64_t)k.TH * Q + 3 > 256 * CGR_MAX_LOADS) return 4;                                   // a band's codes fit the lanes' loads
+        if ((size_t)k.cells * csb > w.lds || w.lds > kRowsLdsOne) return 5;
+        if ((int64_t)k.n_split * k.units_per_split < k.units || (int64_t)(k.n_split - 1) * k.units_per_split >= k.units) return 6;
+        if (w.partial_bytes > scratch_bytes) return 7;
+        // the last X row and column a tile can ask for lie inside the zero halo the stager fills: tile row (TH-1)*st + R-1, column (Q-1)*st + S-1
+        if ((k.TH - 1) * k.st + R - 1 >= k.THx || (Q - 1) * stride + S - 1 >= k.Wp) return 8;
+        for (int64_t x = 0; x < (int64_t)k.TH * Q + 4; ++x)                                          // the reciprocal divides exactly over its range
+            if ((int64_t)(((uint64_t)x * k.q_magic) >> 32) != x / Q) return 9;
+        for (int64_t x = 0; x < (int64_t)k.n_chunks * 64; ++x)
+            if ((int64_t)(((uint64_t)x * k.wp_magic) >> 32) != x / k.Wp) return 10;
+        if ((int64_t)w.grid != ((C + 63) / 64) * ((K + CGR_KB - 1) / CGR_KB) * k.n_split) return 11;
+    }
+    const DxRowsPlan d = conv_dx_rows_plan(a, P, Q, scratch_bytes);
+    if (d.ok) {
+        const ConvDxRowsArgs &k = d.k;
+        if (k.TH < 1 || k.TH > CGR_DX_MAX_ROWS || k.TH * 64 > d.threads || (int64_t)k.bands * k.TH < H || (int64_t)(k.bands - 1) * k.TH >= H) return 21;
+        if (d.threads != 256 && d.threads != 512 && d.threads != 1024) return 22;
+        const int64_t stretch = ((int64_t)k.TH + R - 1) * Q + 3;                                    // bytes of a plane a band can need, with the alignment slack
+        if ((int64_t)k.cb_words * 4 < stretch || k.cb_words < 2) return 23;
+        if ((int64_t)CGR_KC * k.cb_words > (int64_t)CGR_DX_CPT * d.threads) return 24;               // a chunk's codes fit the threads' loads
+        const int64_t lds = (int64_t)k.TH * k.Wp * 65 * 4 + 2 * ((int64_t)CGR_KC * R * S * 64 * 4 + (int64_t)CGR_KC * k.cb_words * 4);
+        if ((size_t)lds > d.lds || d.lds > (size_t)160 * 1024) return 25;
+        if (k.Wp != Q + S - 1 || Wd - 1 + pad >= k.Wp) return 26;                                     // every pixel of a row has its cell
+        if (d.prep_bytes > scratch_bytes || d.prep_bytes < (size_t)((K + CGR_KC - 1) / CGR_KC * CGR_KC * R * S * k.Cp) * 4) return 27;
+        for (int64_t x = 0; x < stretch + 4; ++x)
+            if ((int64_t)(((uint64_t)x * k.q_magic) >> 32) != x / Q) return 28;
+        for (int64_t x = 0; x < (int64_t)CGR_KC * k.cb_words; ++x)
+            if ((int64_t)(((uint64_t)x * k.cbw_magic) >> 32) != x / k.cb_words) return 29;
+        for (int64_t x = 0; x < (int64_t)k.TH * Wd; ++x)
+            if ((int64_t)(((uint64_t)x * k.wd_magic) >> 32) != x / Wd) return 30;
+        if ((int64_t)d.grid != N * k.bands * (k.Cp / 64)) return 31;
+    }
+    return 0;
+}
+
 hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_t s)
 {
+    const int64_t P_ = (a.H + 2 * a.pad - a.R) / a.stride + 1, Q_ = (a.Wd + 2 * a.pad - a.S) / a.stride + 1;
+    const Scale step_{a.step, a.step_dev};
+    // scratch (optional): the dX kernel's prepared weights first, then the dW kernel's partial sums
+    const bool have = a.scratch && (uintptr_t)a.scratch % 256 == 0;
+    size_t used = 0;
+    bool dx_done = false, dw_done = false;
+    // Behind the density gate (flag set: both families are launched and the device picks one) the gather side only runs
+    // beyond ~99.8 % zeros, where the kernels that walk the format's compacted entries have the smaller fixed cost (they touch
+    // nothing but the entries); the kernels that scan the code planes win from there down to ~95 % zeros and serve the
+    // explicit gather path.
+    const bool rows_kernels = a.gate.flag == nullptr;
+    if (a.dX && rows_kernels) {
+        DxRowsPlan pl = conv_dx_rows_plan(a, P_, Q_, have ? a.scratch_bytes : 0);
+        if (pl.ok) {
+            pl.k.codes = a.codes; pl.k.Wt = (const float *)a.scratch; pl.k.dX = a.dX; pl.k.scale = step_; pl.k.gate = a.gate;
+            const hipError_t e = a.R == 3 ? launch_conv_dx_rows_as<3, 3>(pl, a.W, s) : launch_conv_dx_rows_as<1, 1>(pl, a.W, s);
+            if (e != hipSuccess) return e;
+            used = (pl.prep_bytes + 255) & ~(size_t)255;
+            dx_done = true;
+        }
+    }
+    if (a.dW && rows_kernels) {
+        DwRowsPlan pl = conv_dw_rows_plan(a, P_, Q_, have && a.scratch_bytes > used ? a.scratch_bytes - used : 0);
+        if (pl.ok) {
+            ConvDwRowsArgs &k = pl.k;
+            void *partial = have ? (char *)a.scratch + used : nullptr;
+            k.codes = a.codes; k.X = a.X; k.out = k.n_split > 1 ? partial : a.dW; k.scale = step_; k.gate = a.gate;
+            hipError_t e;
+            if (a.x_dtype == DBP_F32) e = a.R == 3 ? launch_conv_dw_rows_as<float, 3, 3>(pl, s) : launch_conv_dw_rows_as<float, 1, 1>(pl, s);
+            else                      e = a.R == 3 ? launch_conv_dw_rows_as<int8_t, 3, 3>(pl, s) : launch_conv_dw_rows_as<int8_t, 1, 1>(pl, s);
+            if (e != hipSuccess) return e;
+            if (k.n_split > 1) {
+                const int64_t n = (int64_t)k.K * k.C * (int)(a.R * a.S);
+                const int rb = (int)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048);
+                if (a.x_dtype == DBP_F32)
+                    hipLaunchKernelGGL(conv_dw_rows_reduce_kernel<float>, dim3(rb), dim3(256), 0, s, (const float *)partial, (float *)a.dW, n, k.n_split, step_, a.gate);
+                else
+                    hipLaunchKernelGGL(conv_dw_rows_reduce_kernel<int32_t>, dim3(rb), dim3(256), 0, s, (const int32_t *)partial, (int32_t *)a.dW, n, k.n_split, step_, a.gate);
+                e = hipGetLastError();
+                if (e != hipSuccess) return e;
+            }
+            dw_done = true;
+        }
+    }
+    if ((dx_done || !a.dX) && (dw_done || !a.dW)) return hipSuccess;
     ConvGatherGeom g;
     g.N = (int)a.N; g.C = (int)a.C; g.H = (int)a.H; g.Wd = (int)a.Wd; g.K = (int)a.K; g.R = (int)a.R; g.S = (int)a.S;
     g.pad = (int)a.pad; g.st = (int)a.stride; g.gate = a.gate;
@@ -539,7 +783,7 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
     g.P = (int)((a.H + 2 * a.pad - a.R) / a.stride + 1); g.Q = (int)((a.Wd + 2 * a.pad - a.S) / a.stride + 1);
     const int RS = g.R * g.S, cpw_max = 64 / RS;
     const Scale step{a.step, a.step_dev};
-    if (a.dX) {
+    if (a.dX && !dx_done) {
         const size_t HW4 = (size_t)g.H * g.Wd * 4, budget = (size_t)150 * 1024 - kConvGatherFixedLds;
         int cpw = cpw_max;
         while (cpw > 1 && (size_t)4 * cpw * HW4 > budget) --cpw;
@@ -557,7 +801,7 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (a.dW) {
+    if (a.dW && !dw_done) {
         g.cpw = cpw_max;
         const dim3 grid((unsigned)((g.C + 4 * g.cpw - 1) / (4 * g.cpw)), (unsigned)g.K);
         if (a.x_dtype == DBP_F32)
@@ -727,3 +971,11 @@ hipError_t launch_linear_gather(const LinearArgs &a, const FormatView &f, hipStr
 }
 
 }  // namespace dbp
+
+extern "C" int dbp_plan_check_conv2d_gather(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride,
+                                            int64_t pad, int int8_x, size_t scratch_bytes)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || Wd <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0 || H + 2 * pad < R || Wd + 2 * pad < S) return -1;
+    if (N > 65535 || C > 65535 || K > 65535 || H > 65535 || Wd > 65535 || R > 255 || S > 255 || pad > 255 || stride > 255) return -1;
+    return dbp::check_conv_rows_plans(N, C, H, Wd, K, R, S, stride, pad, int8_x != 0, scratch_bytes);
+}

@@ -84,6 +84,14 @@ GATHER = [  # N, C, H, Wd, K, R, S, pad, stride: the kernels that walk the nonze
     (4, 64, 28, 28, 40, 3, 3, 1, 2),
     (2, 40, 20, 24, 70, 3, 3, 1, 1),        # planes of more than one 256-pixel tile
     (1, 30, 40, 40, 8, 3, 3, 1, 1),         # input planes too large for seven per wavefront: fewer channels per workgroup
+    # the kernels that scan the code planes (3x3 and 1x1, planes a multiple of 4 bytes; dX: stride 1)
+    (3, 70, 14, 14, 130, 3, 3, 1, 1),       # two channel blocks and five plane blocks, both ragged; dW summed over shares of the images
+    (2, 64, 56, 56, 40, 3, 3, 1, 1),        # several row bands per image on both products
+    (2, 20, 12, 12, 40, 3, 3, 0, 1),        # no padding: the output is smaller than the input
+    (2, 20, 12, 12, 36, 3, 3, 2, 1),        # padding 2: code rows and columns beyond the image on every side
+    (2, 96, 16, 16, 48, 1, 1, 0, 1),        # 1x1
+    (9, 16, 6, 6, 8, 3, 3, 1, 1),           # tiny planes (36 codes): one dword pass covers several rows
+    (2, 24, 20, 100, 8, 3, 3, 1, 1),        # wide rows: two dword passes per plane in the dX kernel
 ]
 
 
@@ -298,3 +306,44 @@ def test_conv_auto_dispatches_by_density_on_the_device(target, expect):
     off = dbp.format_layout(N * K, p.delta.shape[2] * p.delta.shape[3])["scratch_offset"] + 16384 * 16
     assert int(ws[off:off + 4].cpu().numpy().view(np.int32)[0]) == expect
     _check(p, {"codes": codes.cpu().numpy(), "dX": dX.cpu().numpy(), "dW": dW.cpu().numpy(), "stats": dbp.Stats.from_tensor(st)})
+
+
+@pytest.mark.parametrize("target", [0.92, 0.99])
+def test_config4a_gather_kernels_full_size_in_full(target):
+    # the plane-scanning gather kernels in the launch shape the bench times (256 workgroups of 14 output rows for dX; 512
+    # workgroups and a sum over 16 shares of the images for dW): every element against the oracle
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_conv
+    p = workloads.config4a(target)
+    _check(p, run_conv(p, path=dbp.PATH_GATHER))
+
+
+def test_conv_gather_without_a_workspace_and_products_alone():
+    # dbp_conv2d_products with path GATHER: with a workspace the plane-scanning kernels run (prepared weights and partial sums
+    # live there); without one dX runs on the kernel that walks the format's entries and dW unsplit; same oracle, same
+    # tolerance, int8 X bit-exact
+    import torch
+    import paper_2004_04729_amd as dbp
+    from gpu_util import dev, stream, conv_dims, run_nsd, check_products
+    from oracle import oracle as O
+    for i8 in (False, True):
+        p = _problem(3, 40, 14, 14, 48, 3, 3, 1, c=1.0 if i8 else 4.0, i8=i8)
+        N, Cc, H, Wd, K, R, S = conv_dims(p)
+        xd = dbp.I8 if i8 else dbp.F32
+        q = run_nsd(p.delta.reshape(N * K, -1), N * K, H * Wd, p.step, p.seed)
+        k_ref, _ = O.nsd(p.delta, p.step, p.seed)
+        assert np.array_equal(q["codes"].reshape(p.delta.shape), k_ref)
+        Xf = p.X.astype(np.float32)
+        rX, rW, _ = O.conv2d_backward(p.W, Xf, codes=k_ref, step=p.step, stride=1, pad=1)
+        aX, aW, _ = O.conv2d_backward(np.abs(p.W), np.abs(Xf), codes=np.abs(k_ref), step=p.step, stride=1, pad=1)
+        codes = dev(k_ref)
+        for ws in (None, torch.empty(dbp.conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, 1, 1, xd), dtype=torch.uint8, device="cuda:0")):
+            dX = torch.full(p.X.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+            dW = torch.full(p.W.shape, -77, dtype=torch.int32, device="cuda:0") if i8 else torch.full(p.W.shape, float("nan"), device="cuda:0")
+            dbp.conv2d_products(codes, q["fmt_dev"], p.step, dev(p.W), dev(p.X), xd, N, Cc, H, Wd, K, R, S, 1, 1, dX, dW, ws, dbp.PATH_GATHER, stream())
+            torch.cuda.synchronize()
+            check_products(dX.cpu().numpy(), rX, aX, "gather dX, workspace %s" % (ws is not None))
+            if i8:
+                assert np.array_equal(dW.cpu().numpy(), O.conv2d_dw_i8(k_ref, p.X, R, S, 1, 1))
+            else:
+                check_products(dW.cpu().numpy(), rW, aW, "gather dW, workspace %s" % (ws is not None))

@@ -57,3 +57,26 @@ def test_conv_plans_stay_in_bounds():
                 bad.append((N, C_, H, Wd, K, R, st, pad, e))
     assert not bad, bad[:10]
     assert L.dbp_plan_check_conv2d(1, 1, 2, 2, 1, 5, 5, 1, 0) == -1
+
+
+def test_conv_gather_plans_stay_in_bounds():
+    # the gather kernels that scan the code planes: bands, tiles, LDS sizes, the reciprocals that replace divisions
+    L = dbp.lib()
+    L.dbp_plan_check_conv2d_gather.argtypes = [C.c_int64] * 9 + [C.c_int, C.c_size_t]
+    big = 1 << 30
+    for case in CONV:
+        for i8 in (0, 1):
+            for scratch in (0, 1 << 20, big):
+                assert L.dbp_plan_check_conv2d_gather(*case, i8, scratch) == 0, (case, i8, scratch)
+    bad = []
+    for N, C_, H, K, (R, st, pad) in itertools.product([1, 3, 32, 70], [1, 16, 33, 64, 130, 256], [1, 2, 4, 6, 8, 14, 16, 28, 30, 56, 112],
+                                                        [1, 8, 33, 64, 130, 260], [(1, 1, 0), (3, 1, 1), (3, 1, 0), (3, 2, 1), (3, 1, 2), (1, 2, 0)]):
+        for Wd in {H, H + 2, 4 * ((H + 3) // 4), 200, 252}:
+            if H + 2 * pad < R or Wd + 2 * pad < R:
+                continue
+            for i8 in (0, 1):
+                e = L.dbp_plan_check_conv2d_gather(N, C_, H, Wd, K, R, R, st, pad, i8, big)
+                if e:
+                    bad.append((N, C_, H, Wd, K, R, st, pad, i8, e))
+    assert not bad, bad[:10]
+    assert L.dbp_plan_check_conv2d_gather(1, 1, 2, 2, 1, 5, 5, 1, 0, 0, 0) == -1
