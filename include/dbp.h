@@ -212,9 +212,11 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
  * dithered_conv2d_backward_grouped), the convolutional analogue of Eqs. (qdz), (qda), (qdw):
  *   dX[n,c,h,w] = Delta * sum_{k,r,s} code[n,k,p,q] W[k,c,r,s],  h = p*stride+r-pad, w = q*stride+s-pad
  *   dW[k,c,r,s] = Delta * sum_{n,p,q} code[n,k,p,q] X[n,c,p*stride+r-pad,q*stride+s-pad]
- * x_dtype as above.  Errors as above; path == DBP_PATH_GATHER (kernels that walk the nonzero entries, rows of the
+ * x_dtype as above.  Errors as above; path == DBP_PATH_GATHER (kernels that visit the nonzero codes only; rows of the
  * format = the planes (n,k) of P*Q codes) needs R*S <= 64, P, Q < 4096 and, for dX, H*Wd <= 9536 (DBP_ERR_UNSUPPORTED
- * otherwise).  On the matrix-core paths stride 1 runs on the specialised kernels; with another stride dX runs on them as stride*stride
+ * otherwise).  3x3 and 1x1 layers whose planes are a multiple of 4 bytes run on kernels that scan the code planes (dX: stride
+ * 1 only; they keep prepared weights and partial sums in the workspace), every other shape on kernels that walk the format's
+ * entries.  On the matrix-core paths stride 1 runs on the specialised kernels; with another stride dX runs on them as stride*stride
  * stride-1 problems (one per class of output pixels modulo the stride) when stride <= 3, dW as a column-matrix
  * product on the fully connected kernels when the layer is large enough, the rest on the generic implicit-im2col kernel.
  */
