@@ -154,7 +154,10 @@ def main():
             for _ in range(20):
                 dbp.conv2d_products(b["codes"], None, p5.step, b["W"], b["X"], xd5, N, Cc, H, Wd, K, R, S, p5.stride, p5.pad, b["dX"], None,
                                     b["ws"], dbp.PATH_MFMA, stream)
-            what = "20 launches of conv_dx_weight_prep_kernel + conv_dx_kernel on config 5 (90 % zeros)"
+            for _ in range(20):                                            # and the opt-in two-plane form of the same kernel
+                dbp.conv2d_products(b["codes"], None, p5.step, b["W"], b["X"], xd5, N, Cc, H, Wd, K, R, S, p5.stride, p5.pad, b["dX"], None,
+                                    b["ws"], dbp.PATH_MFMA | dbp.PATH_TWO_PLANES, stream)
+            what = "20 launches of conv_dx_weight_prep_kernel + conv_dx_kernel on config 5 (90 % zeros), three planes, then 20 with two planes"
         elif args.probe == "conv_dw":
             b = sets5[0]
             dbp.nsd_quantize(b["d"], N * K, P * Q, p5.step, p5.seed, 0, b["codes"], None, None, stream)
