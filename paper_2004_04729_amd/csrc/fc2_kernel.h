@@ -21,6 +21,7 @@
 namespace dbp {
 
 constexpr int FC2_TM = 256, FC2_TN = 128, FC2_KT = 32;
+constexpr int FC2_SETS = 3;                        // register sets of loads in flight per staging wavefront (K steps ahead; 4 .. 8 measured: no gain)
 constexpr int FC2_MAX_ITEMS = 128;                 // work items of one workgroup (the host checks)
 constexpr int FC2_LDS_BYTES = 2 * (16 + 24) * 1024 + FC2_MAX_ITEMS * 32;
 
@@ -399,25 +400,23 @@ __global__ __launch_bounds__(512, 1) void fc2_pair_kernel(FcPairArgs a)
             }
         };
 
-        // Step g lives in register set g % 3 and LDS stage g % 2.  Barriers: one after step 0 is staged, then
-        // one per step; in the iteration of step g the stagers write step g + 1 and load step g + 4.
+        // Step g lives in register set g % FC2_SETS and LDS stage g % 2.  Barriers: one after step 0 is staged, then
+        // one per step; in the iteration of step g the stagers write step g + 1 and load step g + 1 + FC2_SETS.
         // The loads are unconditional (see issue); only commits and barriers depend on the trip count.
         if (G == 0) { __syncthreads(); if (wave == 7) fc2_side_jobs(a.stats, lane); return; }
-        Fc2Raw r0, r1, r2;
-        issue(r0); issue(r1); issue(r2);
-        commit(r0, stages[0]);
-        issue(r0);
+        Fc2Raw r[FC2_SETS];
+#pragma unroll
+        for (int j = 0; j < FC2_SETS; ++j) issue(r[j]);
+        commit(r[0], stages[0]);
+        issue(r[0]);
         __syncthreads();
-        for (int g = 0; g < G; g += 3) {
-            if (g + 1 < G) commit(r1, stages[(g + 1) & 1]);
-            issue(r1);
-            __syncthreads();
-            if (g + 2 < G) commit(r2, stages[(g + 2) & 1]);
-            issue(r2);
-            if (g + 1 < G) __syncthreads();
-            if (g + 3 < G) commit(r0, stages[(g + 3) & 1]);
-            issue(r0);
-            if (g + 2 < G) __syncthreads();
+        for (int g = 0; g < G; g += FC2_SETS) {
+#pragma unroll
+            for (int j = 1; j <= FC2_SETS; ++j) {                // step g + j: from set j % SETS into stage (g + j) & 1
+                if (g + j < G) commit(r[j % FC2_SETS], stages[(g + j) & 1]);
+                issue(r[j % FC2_SETS]);
+                if (g + j - 1 < G) __syncthreads();
+            }
         }
         if (wave == 7) fc2_side_jobs(a.stats, lane);
         return;
