@@ -6,7 +6,7 @@
 // and everything derived from them are wave-uniform (SGPRs), the 64 lanes are 64 channels c.
 //
 //   conv_dw_rows_kernel   dW[k,c,r,s] = Delta * sum_{n, nonzero (p,q) of plane (n,k)} code * X[n,c,p*st+r-pad,q*st+s-pad]
-//     A workgroup owns 64 channels x 32 code planes (8 wavefronts x 4 planes) and walks a share of the (image, row band)
+//     A workgroup owns 64 channels x 64 code planes (16 wavefronts x 4 planes) and walks a share of the (image, row band)
 //     units.  Per unit it stages the band of X, with its zero halo, in LDS as cells [pixel][64 channels] (one cell = the
 //     64 lanes' operands of one tap: a conflict-free LDS read); per nonzero a lane reads its channel's R*S activations and
 //     adds code * x into the R*S accumulators of that plane -- REGISTERS, because the tap index is static and the plane is
@@ -23,7 +23,7 @@
 
 namespace dbp {
 
-constexpr int CGR_WAVES = 8;                       // dW: wavefronts per workgroup
+constexpr int CGR_WAVES = 16;                      // dW: wavefronts per workgroup (one workgroup per CU; 8 with two per CU staged X twice as often: 3-20 % slower)
 constexpr int CGR_PPW = 4;                         // dW: code planes per wavefront
 constexpr int CGR_KB = CGR_WAVES * CGR_PPW;        // dW: code planes per workgroup
 constexpr int CGR_MAX_CHUNKS = 20;                 // dW: 64-cell chunks of the X tile, at most (1280 cells)
@@ -89,8 +89,8 @@ __global__ __launch_bounds__(CGR_WAVES * 64, 4) void conv_dw_rows_kernel(ConvDwR
             for (int j = 0; j < CGR_MAX_LOADS; ++j) dw[pi][j] = src[min(lane + 64 * j, n_dw - 1)];
         }
         __syncthreads();                                            // the tile of the unit before has been read
-        // ---- stage: wavefront w brings channels 8w .. 8w+7, a lane the same cells of each: four 64-cell chunks x 8 channels =
-        //      32 loads in flight (the loop is bound by their latency), the cells' geometry computed once per chunk ----
+        // ---- stage: wavefront w brings channels 4w .. 4w+3, a lane the same cells of each: four 64-cell chunks x 4 channels =
+        //      16 loads in flight (the loop is bound by their latency), the cells' geometry computed once per chunk ----
         constexpr int CPW = 64 / CGR_WAVES, IB = 4;
         const int ch0 = wave * CPW;
         const XT *xw = Xb + ((int64_t)n * a.Ct + min(c0 + ch0, a.C - 1)) * HW;           // uniform; channel j of the wavefront: + j*HW (clamped below)

@@ -536,7 +536,7 @@ bool conv_gather_supported(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t 
 // ---- host side of conv_rows_kernel.h ---------------------------------------------------------------------
 namespace {
 
-constexpr size_t kRowsLdsTwo = 75 * 1024, kRowsLdsOne = 150 * 1024;     // LDS budget of a workgroup: two per CU, else one
+constexpr size_t kRowsLdsOne = 150 * 1024;                            // LDS budget of the dW kernel's workgroup (one per CU)
 
 bool rows_shape_ok(const ConvArgs &a, int64_t P, int64_t Q)
 {
@@ -555,12 +555,10 @@ DwRowsPlan conv_dw_rows_plan(const ConvArgs &a, int64_t P, int64_t Q, size_t ava
     const int64_t csb = a.x_dtype == DBP_F32 ? 65 * 4 : 68, st = a.stride;
     const int64_t Wp = (Q - 1) * st + a.S;
     int64_t TH = 0;
-    for (size_t budget : {kRowsLdsTwo, kRowsLdsOne}) {
-        int64_t thx = (int64_t)budget / (Wp * csb);
+    {
+        int64_t thx = (int64_t)kRowsLdsOne / (Wp * csb);              // one workgroup per CU: the band may take most of its LDS
         if (thx > 64 * CGR_MAX_CHUNKS / Wp) thx = 64 * CGR_MAX_CHUNKS / Wp;
-        if (thx < a.R) continue;
-        TH = (thx - a.R) / st + 1;
-        break;
+        if (thx >= a.R) TH = (thx - a.R) / st + 1;
     }
     if (TH > P) TH = P;
     if (TH > (256 * CGR_MAX_LOADS - 4) / Q) TH = (256 * CGR_MAX_LOADS - 4) / Q;
@@ -576,7 +574,7 @@ DwRowsPlan conv_dw_rows_plan(const ConvArgs &a, int64_t P, int64_t Q, size_t ava
     const int64_t units = a.N * k.bands;
     if (units >= ((int64_t)1 << 30)) return pl;
     const int64_t columns = ((a.C + 63) / 64) * ((a.K + CGR_KB - 1) / CGR_KB);
-    const int64_t slots = pl.lds <= kRowsLdsTwo ? 512 : 256;
+    const int64_t slots = 256;                                        // one 16-wavefront workgroup per CU
     int64_t want = slots / columns < 1 ? 1 : slots / columns;
     if (want > units) want = units;
     const size_t dw_bytes = (size_t)(a.K * a.C * a.R * a.S) * 4;

@@ -310,8 +310,8 @@ def test_conv_auto_dispatches_by_density_on_the_device(target, expect):
 
 @pytest.mark.parametrize("target", [0.92, 0.99])
 def test_config4a_gather_kernels_full_size_in_full(target):
-    # the plane-scanning gather kernels in the launch shape the bench times (256 workgroups of 14 output rows for dX; 512
-    # workgroups and a sum over 16 shares of the images for dW): every element against the oracle
+    # the plane-scanning gather kernels in the launch shape the bench times (256 workgroups of 14 output rows for dX; 256
+    # workgroups of 64 planes x 64 channels and a sum over 16 shares of the images for dW): every element against the oracle
     import paper_2004_04729_amd as dbp
     from gpu_util import run_conv
     p = workloads.config4a(target)
