@@ -73,14 +73,16 @@ __global__ __launch_bounds__(CGR_WAVES * 64, 4) void conv_dw_rows_kernel(ConvDwR
     const uint32_t row_bytes = (uint32_t)(a.Wp * CSB);              // one tile row further
     const uint32_t lane_off = (uint32_t)(lane * (int)sizeof(XT));
 
-    for (int u = u_a; u < u_b; ++u) {
+    // A unit = (image, band of code rows).  Three steps per unit: its code dwords into registers, its band of X into the LDS
+    // tile, the walk.  (Two tiles of half the size, the next unit staged by each wavefront as soon as its own walk is done, were
+    // measured: equal where a whole image fits either way, 10 % slower where the band has to shrink.)
+    uint32_t dw[CGR_PPW][CGR_MAX_LOADS];
+    auto load_codes = [&](int u) {
         const int n = u / a.bands, band = u - n * a.bands;
         const int p0 = band * a.TH, p1 = min(a.P, p0 + a.TH);
-        const int h0 = p0 * a.st - a.pad;                           // X row of tile row 0; tile column 0 is X column -pad
-        // ---- the unit's codes: all of the wavefront's planes at once, in flight while the tile is staged ----
         const int first = p0 * a.Q, start4 = first & ~3, lo = first - start4;      // bytes [lo, endb) of the loaded stretch are the band's
         const int endb = p1 * a.Q - start4, n_dw = (endb + 3) >> 2;
-        uint32_t dw[CGR_PPW][CGR_MAX_LOADS];
+        (void)lo; (void)endb;
 #pragma unroll
         for (int pi = 0; pi < CGR_PPW; ++pi) {
             const int k = min(k0 + pi, a.K - 1);                     // planes past the tensor repeat the last one; never walked
@@ -88,7 +90,10 @@ __global__ __launch_bounds__(CGR_WAVES * 64, 4) void conv_dw_rows_kernel(ConvDwR
 #pragma unroll
             for (int j = 0; j < CGR_MAX_LOADS; ++j) dw[pi][j] = src[min(lane + 64 * j, n_dw - 1)];
         }
-        __syncthreads();                                            // the tile of the unit before has been read
+    };
+    auto stage = [&](int u, char *tile) {
+        const int n = u / a.bands, band = u - n * a.bands;
+        const int h0 = band * a.TH * a.st - a.pad;                  // X row of tile row 0; tile column 0 is X column -pad
         // ---- stage: wavefront w brings channels 4w .. 4w+3, a lane the same cells of each: four 64-cell chunks x 4 channels =
         //      16 loads in flight (the loop is bound by their latency), the cells' geometry computed once per chunk ----
         constexpr int CPW = 64 / CGR_WAVES, IB = 4;
@@ -120,8 +125,13 @@ __global__ __launch_bounds__(CGR_WAVES * 64, 4) void conv_dw_rows_kernel(ConvDwR
                 }
             }
         }
-        __syncthreads();
-
+    };
+    auto walk = [&](int u, const char *tile) {
+        const int n = u / a.bands, band = u - n * a.bands;
+        const int p0 = band * a.TH, p1 = min(a.P, p0 + a.TH);
+        const int first = p0 * a.Q, start4 = first & ~3, lo = first - start4;      // bytes [lo, endb) of the loaded stretch are the band's
+        const int endb = p1 * a.Q - start4, n_dw = (endb + 3) >> 2;
+        (void)n;
         // ---- the wavefront's planes: nonzeros of the band's code rows p0 .. p1-1 ----
 #pragma unroll
         for (int pi = 0; pi < CGR_PPW; ++pi) {
@@ -172,6 +182,13 @@ __global__ __launch_bounds__(CGR_WAVES * 64, 4) void conv_dw_rows_kernel(ConvDwR
                 }
             }
         }
+    };
+    for (int u = u_a; u < u_b; ++u) {
+        load_codes(u);                                               // in flight while the tile is staged
+        __syncthreads();                                             // the tile of the unit before has been read
+        stage(u, tile);
+        __syncthreads();
+        walk(u, tile);
     }
 
     // ---- out: lane = channel c0 + lane of planes k0 .. k0+PPW-1 ----
