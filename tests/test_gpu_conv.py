@@ -347,3 +347,28 @@ def test_conv_gather_without_a_workspace_and_products_alone():
                 assert np.array_equal(dW.cpu().numpy(), O.conv2d_dw_i8(k_ref, p.X, R, S, 1, 1))
             else:
                 check_products(dW.cpu().numpy(), rW, aW, "gather dW, workspace %s" % (ws is not None))
+
+
+def _random_gather_case(seed):
+    """A small random layer the plane-scanning gather kernels can take (3x3 or 1x1, planes a multiple of 4 bytes)."""
+    rng = np.random.default_rng(7000 + seed)
+    while True:
+        R = int(rng.choice([1, 3])); pad = int(rng.integers(0, 3)); st = int(rng.choice([1, 1, 1, 2]))
+        H = int(rng.integers(2, 41)); Wd = int(rng.integers(2, 61))
+        if H + 2 * pad < R or Wd + 2 * pad < R:
+            continue
+        P, Q = (H + 2 * pad - R) // st + 1, (Wd + 2 * pad - R) // st + 1
+        if (P * Q) % 4 or Q < 2:
+            continue
+        N = int(rng.integers(1, 5)); C = int(rng.integers(1, 141)); K = int(rng.integers(1, 141))
+        return (N, C, H, Wd, K, R, R, pad), st, bool(rng.integers(0, 2)), float(rng.choice([1.0, 4.0, 12.0]))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_conv_gather_random_small_layers(seed):
+    # shapes nobody picked by hand: ragged channel and plane blocks, bands that end inside the image, rows that straddle dwords
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_conv
+    case, st, i8, c = _random_gather_case(seed)
+    p = _problem(*case, c=1.0 if i8 else c, i8=i8, stride=st, seed=seed)
+    _check(p, run_conv(p, path=dbp.PATH_GATHER))
