@@ -372,3 +372,26 @@ def test_conv_gather_random_small_layers(seed):
     case, st, i8, c = _random_gather_case(seed)
     p = _problem(*case, c=1.0 if i8 else c, i8=i8, stride=st, seed=seed)
     _check(p, run_conv(p, path=dbp.PATH_GATHER))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_conv_matrix_core_random_small_layers(seed):
+    # random kernel sizes, strides, paddings, channel counts and operand types over the matrix-core kernels and their fallbacks,
+    # half of them with the two-plane operand split
+    import paper_2004_04729_amd as dbp
+    from gpu_util import run_conv
+    rng = np.random.default_rng(9000 + seed)
+    while True:
+        R = int(rng.choice([1, 3, 3, 3, 5])); S = int(rng.choice([R, R, 3 if R != 3 else 1]))
+        pad = int(rng.integers(0, 3)); st = int(rng.choice([1, 1, 1, 2, 3]))
+        H = int(rng.integers(1, 40)); Wd = int(rng.integers(1, 60))
+        if H + 2 * pad < R or Wd + 2 * pad < S:
+            continue
+        N = int(rng.integers(1, 6)); C = int(rng.integers(1, 200)); K = int(rng.integers(1, 200))
+        i8 = bool(rng.integers(0, 2)); two = bool(rng.integers(0, 2))
+        P, Q = (H + 2 * pad - R) // st + 1, (Wd + 2 * pad - S) // st + 1
+        if i8 and N * P * Q * 127 * 127 >= 2 ** 31:
+            continue
+        break
+    p = _problem(N, C, H, Wd, K, R, S, pad, c=1.0 if i8 else 4.0, i8=i8, stride=st, seed=seed)
+    _check(p, run_conv(p, path=dbp.PATH_MFMA | (dbp.PATH_TWO_PLANES if two else 0)))
