@@ -209,15 +209,39 @@ __global__ __launch_bounds__(CGR_WAVES * 64, 4) void conv_dw_rows_kernel(ConvDwR
     }
 }
 
-// dW = scale * sum of the shares, in share order (fp32), or their exact sum (int32).
+// dW = scale * sum of the shares (fp32: in a fixed order; int32: exact).  `zg` (a power of two, at most 16) threads share an
+// element: thread group g adds the shares g, g + zg, ... in that order, eight loads in flight, and group 0 adds the groups'
+// sums in group order -- with hundreds of shares of a small dW one thread per element would be a chain of dependent loads.
 template <class AccT>
-__global__ __launch_bounds__(256) void conv_dw_rows_reduce_kernel(const AccT *partial, AccT *dW, int64_t n, int n_split, Scale scale, Gate gate)
+__global__ __launch_bounds__(256) void conv_dw_rows_reduce_kernel(const AccT *partial, AccT *dW, int64_t n, int n_split, int zg, Scale scale, Gate gate)
 {
     if (gate.closed()) return;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    __shared__ AccT part[256];
+    const int epb = 256 / zg, e = (int)threadIdx.x & (epb - 1), g = (int)threadIdx.x / epb;
+    for (int64_t base = (int64_t)blockIdx.x * epb; base < n; base += (int64_t)gridDim.x * epb) {     // uniform trip count: barriers inside
+        const int64_t i = base + e;
         AccT s = 0;
-        for (int z = 0; z < n_split; ++z) s += partial[(int64_t)z * n + i];
-        if constexpr (std::is_same<AccT, float>::value) dW[i] = s * scale.get(); else dW[i] = s;
+        if (i < n) {
+            int z = g;
+            for (; z + 7 * zg < n_split; z += 8 * zg) {
+                AccT v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = partial[(int64_t)(z + j * zg) * n + i];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) s += v[j];
+            }
+            for (; z < n_split; z += zg) s += partial[(int64_t)z * n + i];
+        }
+        if (zg > 1) {
+            part[threadIdx.x] = s;
+            __syncthreads();
+            if (g == 0)
+                for (int j = 1; j < zg; ++j) s += part[j * epb + e];
+            __syncthreads();                                          // the next round overwrites part
+        }
+        if (g == 0 && i < n) {
+            if constexpr (std::is_same<AccT, float>::value) dW[i] = s * scale.get(); else dW[i] = s;
+        }
     }
 }
 

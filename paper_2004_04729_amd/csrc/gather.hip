@@ -762,11 +762,14 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
             if (e != hipSuccess) return e;
             if (k.n_split > 1) {
                 const int64_t n = (int64_t)k.K * k.C * (int)(a.R * a.S);
-                const int rb = (int)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048);
+                int zg = 1;                                           // threads per element: more where dW is small and the shares are many
+                while (zg < 16 && k.n_split / (2 * zg) >= 8 && n * zg / 256 < 2048) zg *= 2;
+                const int64_t blocks = (n * zg + 255) / 256;
+                const int rb = (int)(blocks < 2048 ? blocks : 2048);
                 if (a.x_dtype == DBP_F32)
-                    hipLaunchKernelGGL(conv_dw_rows_reduce_kernel<float>, dim3(rb), dim3(256), 0, s, (const float *)partial, (float *)a.dW, n, k.n_split, step_, a.gate);
+                    hipLaunchKernelGGL(conv_dw_rows_reduce_kernel<float>, dim3(rb), dim3(256), 0, s, (const float *)partial, (float *)a.dW, n, k.n_split, zg, step_, a.gate);
                 else
-                    hipLaunchKernelGGL(conv_dw_rows_reduce_kernel<int32_t>, dim3(rb), dim3(256), 0, s, (const int32_t *)partial, (int32_t *)a.dW, n, k.n_split, step_, a.gate);
+                    hipLaunchKernelGGL(conv_dw_rows_reduce_kernel<int32_t>, dim3(rb), dim3(256), 0, s, (const int32_t *)partial, (int32_t *)a.dW, n, k.n_split, zg, step_, a.gate);
                 e = hipGetLastError();
                 if (e != hipSuccess) return e;
             }

@@ -555,7 +555,7 @@ Conv1x1Plan conv1x1_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t
     const int64_t PQ = H * Wd;
     if (!(R == 1 && S == 1 && pad == 0 && stride == 1)) return pl;
     pl.kt = kt;
-    if (K <= FC2_TM / 2 || C < 4 || C % 4 || PQ % 4 || PQ < kt) return pl;          // large row tiles; 16-byte loads and stores
+    if (K < FC2_TM / 4 || C < 4 || C % 4 || PQ % 4 || PQ < kt) return pl;           // row tiles at least a quarter full (lowering costs more than the idle rows); 16-byte loads and stores
     if (C * PQ >= ((int64_t)1 << 29) || K * PQ >= ((int64_t)1 << 31) || K * C >= ((int64_t)1 << 30)) return pl;   // 32-bit lane offsets
     pl.spi = (int)((PQ + kt - 1) / kt);
     if (N * pl.spi >= ((int64_t)1 << 25)) return pl;                              // the reduction axis counts windows of kt
