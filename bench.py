@@ -125,15 +125,18 @@ def main():
                                      b["dX"] if dX else None, b["dW"] if dW else None, b["ws"], b["st"], path, stream if on is None else on)
 
     def gate_flag(ws, rows, cols):
-        """-1: one family was launched; 0 / 1: both were, and the matrix-core / the gather kernels ran."""
+        """-1: one family was launched; else the state the device chose: 0 matrix cores, 1 the gather kernels, 2 matrix
+        cores for dX and the gather kernel for dW (three flags, one of them set)."""
         off = dbp.format_layout(rows, cols)["scratch_offset"] + FLAG_OFFSET
-        return int(ws[off:off + 4].cpu().numpy().view(np.int32)[0])
+        v = ws[off:off + 12].cpu().numpy().view(np.int32)
+        return -1 if v[0] == -1 else 1 if v[0] == 1 else 2 if v[1] == 1 else 0
 
     def arm_flag(ws, rows, cols):
         off = dbp.format_layout(rows, cols)["scratch_offset"] + FLAG_OFFSET
         ws[off:off + 4] = 255                                            # reads back as -1 unless a gated call writes it
 
-    PATH_NAME = {-1: "matrix cores (one family launched)", 0: "matrix cores (device gate)", 1: "gather (device gate)"}
+    PATH_NAME = {-1: "matrix cores (one family launched)", 0: "matrix cores (device gate)", 1: "gather (device gate)",
+                 2: "matrix cores for dX, gather for dW (device gate)"}
 
     # ------------------------------------------------------------------ headline workload: config 5
     p5 = workloads.config5(args.sparsity)

@@ -157,7 +157,12 @@ LayerCarve layer_carve(size_t backward_total, int64_t n, int64_t bias_len)
 // losing family costs its empty launches, which is why shapes where the gather kernels' fixed cost alone is close to the
 // matrix-core time are not dispatched at all.  The estimates below are linear models with constants measured on MI355X
 // (microseconds; flop per microsecond; bytes per microsecond).
-struct AutoPlan { bool dual; uint64_t gather_below; };
+struct AutoPlan {
+    bool dual; uint64_t gather_below;
+    // convolution dW alone on the plane-scanning gather kernel below this many nonzeros (0: never), dX staying on matrix cores
+    uint64_t dw_rows_below = 0;
+    bool gated() const { return dual || dw_rows_below > 0; }
+};
 
 AutoPlan linear_auto_plan(const LinearArgs &call, bool launchable)
 {
@@ -195,12 +200,7 @@ AutoPlan linear_auto_plan(const LinearArgs &call, bool launchable)
 AutoPlan conv_auto_plan(const ConvArgs &call, int64_t P, int64_t Q)
 {
     AutoPlan ap{false, 0};
-    if (!conv_gather_supported(call.N, call.C, call.H, call.Wd, call.K, call.R, call.S, P, Q, call.dX != nullptr)) return ap;
-    // The convolution gather kernels give every workgroup a few channels and let it walk ALL entries of its image (dX) or of
-    // its output channel (dW): with large planes few channels fit a workgroup (their dX planes accumulate in LDS) and the
-    // walk is repeated by many workgroups -- measured on 56x56 planes: 1.0 ms at 99.9 % zeros against 0.41 ms on matrix
-    // cores.  The gate is only worth its empty launches on small planes (14x14: 0.065 against 0.155 ms at 99.9 %).
-    if (call.H * call.Wd > 1024 || P * Q > 1024) return ap;
+    if (!conv_gather_supported(call.N, call.C, call.H, call.Wd, call.K, call.R, call.S, P, Q, false)) return ap;
     ConvArgs probe = call;
     int ungated = 0;
     StatsJob none{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
@@ -209,8 +209,32 @@ AutoPlan conv_auto_plan(const ConvArgs &call, int64_t P, int64_t Q)
     if (ungated) return ap;
     const double crs = (double)(call.C * call.R * call.S), n_codes = (double)(call.N * call.K * P * Q);
     const double flops = 2.0 * n_codes * crs;                                        // one dense product
-    double mfma_us = 0.0;
     const double planes = call.two_planes ? 2.0 : 3.0;
+    // dW alone on the kernel that scans the code planes (fp32 activations: the int8 matrix-core kernel is out of its reach).
+    // Matrix-core dW measured on 13 layer shapes: 25 us + the bf16 planes at 0.95 PFLOP/s, within 22 %.  The gather kernel must
+    // be modelled 15 % faster to be chosen, and the switch must lie above 0.5 % nonzeros to be worth its two empty launches.
+    if (call.dW && call.x_dtype == DBP_F32) {
+        double fixed_us = 0.0, per_nnz_us = 0.0;
+        if (conv_dw_rows_cost(call, P, Q, call.scratch_bytes, &fixed_us, &per_nnz_us)) {
+            const double mfma_dw_us = 25.0 + flops * planes / 0.95e9;
+            const double thr = (0.85 * mfma_dw_us - fixed_us) / per_nnz_us;
+            // every gated launch that returns at once still costs 2.5-4.5 us: the two launches of this state must have at
+            // least 25 us to win at the sparse end, and then stand in for the whole-family state below (whose four launches,
+            // format and separate flag kernel cost 10-14 us at every density, to win only beyond ~99.8 % zeros)
+            if (thr >= 0.005 * n_codes && mfma_dw_us - fixed_us >= 25.0) {
+                ap.dw_rows_below = thr >= n_codes ? (uint64_t)n_codes + 1 : (uint64_t)thr;
+                return ap;
+            }
+        }
+    }
+    // Both products on the gather family.  The kernels that walk the format's entries give every workgroup a few channels and
+    // let it walk ALL entries of its image (dX) or of its output channel (dW): with large planes few channels fit a workgroup
+    // (their dX planes accumulate in LDS) and the walk is repeated by many workgroups -- measured on 56x56 planes: 1.0 ms at
+    // 99.9 % zeros against 0.41 ms on matrix cores.  This side of the gate is only worth its empty launches on small planes
+    // (14x14: 0.065 against 0.155 ms at 99.9 %).
+    if (call.H * call.Wd > 1024 || P * Q > 1024) return ap;
+    if (call.dX && !conv_gather_supported(call.N, call.C, call.H, call.Wd, call.K, call.R, call.S, P, Q, true)) return ap;
+    double mfma_us = 0.0;
     if (call.dX) mfma_us += flops * planes / 0.9e9;
     if (call.dW) mfma_us += call.x_dtype == DBP_I8 ? flops / 1.4e9 : flops * planes / 0.6e9;
     const double x_elems = (double)(call.N * call.C * call.H * call.Wd);
@@ -265,7 +289,8 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
                                dbp_dtype x_dtype, int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
                                int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW,
                                void *workspace, size_t workspace_bytes, dbp_path path, void *stream, const float *step_dev = nullptr,
-                               StatsJob job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}, Gate gate = Gate{})
+                               StatsJob job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}, Gate gate = Gate{},
+                               Gate gate_dw = Gate{}, bool rows_gated = false)
 {
     if (!codes || !W || (!dX && !dW) || (dW && !X)) return DBP_ERR_NULL;
     int64_t P, Q;
@@ -291,7 +316,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
         // that walk the format's entries serve
         const bool ws_ok = workspace && aligned(workspace, 256);
         g.dX = dX; g.dW = dW; g.scratch = ws_ok ? workspace : nullptr; g.scratch_bytes = ws_ok ? workspace_bytes : 0;
-        g.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; g.pending = nullptr; g.gate = gate;
+        g.stats_job = StatsJob{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr}; g.pending = nullptr; g.gate = gate; g.rows_gated = rows_gated;
         if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
         return launch_conv_gather(g, f, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
     }
@@ -301,7 +326,7 @@ dbp_status conv2d_products(const int8_t *codes, const void *format, float step, 
     a.codes = codes; a.dense = nullptr; a.step = step; a.step_dev = step_dev; a.W = W; a.W8 = nullptr; a.X = X; a.x_dtype = x_dtype;
     a.N = N; a.C = C; a.H = H; a.Wd = Wd; a.K = K; a.R = R; a.S = S; a.pad = pad; a.stride = stride;
     a.dX = dX; a.dW = dW; a.scratch = workspace; a.scratch_bytes = workspace_bytes;
-    a.stats_job = job; a.pending = nullptr; a.gate = gate;
+    a.stats_job = job; a.pending = nullptr; a.gate = gate; a.gate_dw = gate_dw;
     a.two_planes = path_two_planes(path);
     return launch_conv_mfma(a, (hipStream_t)stream) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
 }
@@ -313,7 +338,7 @@ dbp_status linear_products_dispatch(const AutoPlan &ap, const int8_t *k, char *w
                                     const float *W, const void *X, dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX,
                                     void *dW, dbp_path path, void *stream, StatsJob job, const float *step_dev)
 {
-    if (!ap.dual)
+    if (!ap.gated())
         return linear_products(k, ws, step, W, X, x_dtype, B, in, out, dX, dW, ws + c.scratch_offset, scratch_bytes, path, stream, job, step_dev);
     int *flag = (int *)(ws + c.fmt.scratch_offset + kNsdFlagOffset);
     job.flag = flag; job.gather_below = ap.gather_below;
@@ -331,18 +356,34 @@ dbp_status conv2d_products_dispatch(const AutoPlan &ap, const int8_t *k, char *w
                                     int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad, float *dX, void *dW, dbp_path path,
                                     void *stream, StatsJob job, const float *step_dev)
 {
-    if (!ap.dual)
+    if (!ap.gated())
         return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset, scratch_bytes,
                                path, stream, step_dev, job);
+    // Three states, one flag each (write_density_flags): everything on matrix cores; dX on matrix cores and dW on the gather
+    // kernel that scans the code planes; everything on the gather kernels that walk the format's entries.
     int *flag = (int *)(ws + c.fmt.scratch_offset + kNsdFlagOffset);
-    job.flag = flag; job.gather_below = ap.gather_below;
-    if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
+    job.flag = flag; job.gather_below = ap.dual ? ap.gather_below : 0; job.dw_rows_below = dW ? ap.dw_rows_below : 0;
+    const bool rows = job.dw_rows_below > 0;
     const StatsJob none{nullptr, 0, nullptr, nullptr, 0, nullptr, 0.0f, nullptr};
+    // The flags must be there before the first gated kernel: the sum that writes them rides in the weight preparation of the
+    // dX kernel as usual (small preparation kernels are not gated), or, without dX, is launched on its own.
+    if (!dX) {
+        if (launch_stats_job(job, (hipStream_t)stream) != hipSuccess) return DBP_ERR_DEVICE;
+        job = none;
+    }
     dbp_status st = conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset,
-                                    scratch_bytes, path_with_flags(DBP_PATH_MFMA, path), stream, step_dev, none, Gate{flag, 0});
+                                    scratch_bytes, path_with_flags(DBP_PATH_MFMA, path), stream, step_dev, job,
+                                    ap.dual ? Gate{flag, 0} : Gate{}, rows ? Gate{flag + 2, 1} : Gate{});
     if (st != DBP_OK) return st;
-    return conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset,
-                           scratch_bytes, DBP_PATH_GATHER, stream, step_dev, none, Gate{flag, 1});
+    if (ap.dual) {
+        st = conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, ws + c.scratch_offset,
+                             scratch_bytes, DBP_PATH_GATHER, stream, step_dev, none, Gate{flag, 1});
+        if (st != DBP_OK) return st;
+    }
+    if (rows)
+        st = conv2d_products(k, ws, step, W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, nullptr, dW, ws + c.scratch_offset,
+                             scratch_bytes, DBP_PATH_GATHER, stream, step_dev, none, Gate{flag + 1, 1}, Gate{}, true);
+    return st;
 }
 
 LinearArgs linear_call(const float *W, const void *X, dbp_dtype x_dtype, int64_t B, int64_t in, int64_t out, float *dX, void *dW,
@@ -481,7 +522,7 @@ dbp_status dithered_linear_backward(const float *delta, const float *W, const vo
     const AutoPlan ap = path_family(path) == DBP_PATH_AUTO
         ? linear_auto_plan(linear_call(W, X, x_dtype, B, in, out, dX, dW, k, ws + c.scratch_offset, workspace_bytes - c.scratch_offset, path_two_planes(path)), true)
         : AutoPlan{false, 0};
-    dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
+    dbp_stats *st_dev = stats ? stats : ap.gated() ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
     StatsJob job;
     st = run_nsd(delta, B, out, step, seed, idx_base, k, ws, &c.fmt, st_dev, (hipStream_t)stream,
                  path_family(path) == DBP_PATH_GATHER, &job);
@@ -523,7 +564,7 @@ dbp_status dithered_conv2d_backward(const float *delta, const float *W, const vo
         ? conv_auto_plan(conv_call(W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, k, ws + c.scratch_offset,
                                    workspace_bytes - c.scratch_offset, path_two_planes(path)), P, Q)
         : AutoPlan{false, 0};
-    dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
+    dbp_stats *st_dev = stats ? stats : ap.gated() ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
     StatsJob job;
     st = run_nsd(delta, N * K, P * Q, step, seed, idx_base, k, ws, &c.fmt, st_dev, (hipStream_t)stream,
                  path_family(path) == DBP_PATH_GATHER || ap.dual, &job);
@@ -926,7 +967,7 @@ dbp_status dithered_linear_layer_backward(const float *delta_a, const float *act
     const AutoPlan ap = path_family(path) == DBP_PATH_AUTO && (dX || dW)
         ? linear_auto_plan(linear_call(W, X, x_dtype, B, in, out, dX, dW, k, ws + c.scratch_offset, c.total - c.scratch_offset, path_two_planes(path)), true)
         : AutoPlan{false, 0};
-    dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
+    dbp_stats *st_dev = stats ? stats : ap.gated() ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
     st = run_nsd(delta_a, B, out, 1.0f, seed, idx_base, k, ws, &c.fmt, st_dev, hs, path_family(path) == DBP_PATH_GATHER, &job, &ex, true, &tree);
     if (st != DBP_OK) return st;
     if (!dX && !dW) return launch_stats_job(job, hs) == hipSuccess ? DBP_OK : DBP_ERR_DEVICE;
@@ -968,7 +1009,7 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
         ? conv_auto_plan(conv_call(W, X, x_dtype, N, C, H, Wd, K, R, S, stride, pad, dX, dW, k, ws + c.scratch_offset,
                                    c.total - c.scratch_offset, path_two_planes(path)), P, Q)
         : AutoPlan{false, 0};
-    dbp_stats *st_dev = stats ? stats : ap.dual ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
+    dbp_stats *st_dev = stats ? stats : ap.gated() ? (dbp_stats *)(ws + c.fmt.scratch_offset + kNsdFlagOffset + 64) : nullptr;
     st = run_nsd(delta_a, N * K, P * Q, 1.0f, seed, idx_base, k, ws, &c.fmt, st_dev, hs, path_family(path) == DBP_PATH_GATHER || ap.dual, &job, &ex,
                  true, &tree);
     if (st != DBP_OK) return st;

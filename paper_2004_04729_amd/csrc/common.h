@@ -73,9 +73,17 @@ struct StatsJob {
     const u32x4 *partials; int n; dbp_stats *out;                  // statistics records -> dbp_stats (n == 0: none)
     const int64_t *bias_sums; int64_t bias_len; float *bias_grad;   // code sums -> fp32 bias gradient (bias_len == 0: none)
     float step; const float *step_dev;
-    // density dispatch: flag[0] = 1 (gather kernels) when fewer than gather_below codes are nonzero, else 0 (matrix cores)
-    int *flag = nullptr; uint64_t gather_below = 0;
+    // density dispatch (write_density_flags): three flags, exactly one of them 1 -- flag[0]: fewer than gather_below codes
+    // are nonzero (the gather family runs); flag[1]: not that, but fewer than dw_rows_below (matrix cores for dX, the
+    // plane-scanning gather kernel for dW); flag[2]: neither (matrix cores for both)
+    int *flag = nullptr; uint64_t gather_below = 0, dw_rows_below = 0;
 };
+__device__ __forceinline__ void write_density_flags(const StatsJob &j, uint64_t nnz)
+{
+    if (!j.flag) return;
+    const int state = nnz < j.gather_below ? 0 : nnz < j.dw_rows_below ? 1 : 2;
+    j.flag[0] = state == 0; j.flag[1] = state == 1; j.flag[2] = state == 2;
+}
 // Launches the quantiser.  With `defer` non-null and statistics kept in records, the final sum is not
 // launched: *defer describes it, and the caller either folds it into a later kernel of the same stream
 // or calls launch_stats_job.
@@ -147,6 +155,8 @@ struct ConvArgs {
     StatsJob      stats_job;   // statistics sum / bias gradient still to be done on this stream (none: n == 0 and bias_len == 0)
     StatsJob     *pending;     // set by launch_conv_mfma: what of stats_job no kernel has taken along yet
     Gate          gate;        // device-side dispatch (the large kernels; the small preparation kernels run regardless)
+    Gate          gate_dw;     // matrix-core family: the dW kernels' gate where it differs from the dX kernels' (flag == nullptr: `gate` serves both)
+    bool          rows_gated = false;    // gather family: the plane-scanning kernels also behind a gate (else a gated call takes the entry-walking kernels)
     int          *plan_only = nullptr;   // non-null: launch nothing, set *plan_only = 1 if a large kernel would run ungated
 };
 size_t     linear_scratch_bytes(int64_t B, int64_t in, int64_t out);
@@ -172,6 +182,9 @@ bool       linear_gather_supported(int64_t B, int64_t in, int64_t out);
 // plane of at most about 37 KiB (four of them accumulate in LDS).
 bool       conv_gather_supported(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t P, int64_t Q, bool want_dx);
 hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_t s);     // honours a.gate
+// Cost model of conv_dw_rows_kernel on this layer with `avail` bytes of scratch (microseconds; constants measured on MI355X):
+// false when the kernel does not take the shape.
+bool       conv_dw_rows_cost(const ConvArgs &a, int64_t P, int64_t Q, size_t avail, double *fixed_us, double *per_nnz_us);
 
 
 }  // namespace dbp

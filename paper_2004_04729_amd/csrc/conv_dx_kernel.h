@@ -109,6 +109,7 @@ __device__ __forceinline__ bool cdx_side_jobs(const StatsJob &job, int &workers)
             job.out->n_nonfinite = s_sum[2][0] + s_sum[2][1] + s_sum[2][2] + s_sum[2][3];
             job.out->max_abs_code = (int32_t)max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3]));
             job.out->reserved = 0;
+            write_density_flags(job, s_sum[0][0] + s_sum[0][1] + s_sum[0][2] + s_sum[0][3]);
         }
     }
     if (job.bias_len > 0) {

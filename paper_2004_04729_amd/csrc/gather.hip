@@ -676,6 +676,24 @@ hipError_t launch_conv_dx_rows_as(const DxRowsPlan &pl, const float *W, hipStrea
 
 }  // namespace
 
+// conv_dw_rows_kernel's time as fixed + nonzeros * per_nnz, from its plan.  Fixed: ~8 us of launches, per unit of a
+// workgroup's share ~2 us plus the X band at ~30 GB/s per CU, and the partial sums written and read at ~5 TB/s; per
+// nonzero 2*64*R*S flop per 64-channel block at ~21 TFLOP/s (3x3; a 1x1 nonzero has one multiply-add per lane to pay for
+// its decoding: ~3 TFLOP/s), scaled by the share of the 256 CUs that have a workgroup.  Measured against 13 layer shapes
+// (8x8 to 56x56 planes, 64 to 1024 channels): the fixed part within 20 % (1x1: overestimated by up to 45 %).
+bool conv_dw_rows_cost(const ConvArgs &a, int64_t P, int64_t Q, size_t avail, double *fixed_us, double *per_nnz_us)
+{
+    const DwRowsPlan pl = conv_dw_rows_plan(a, P, Q, avail);
+    if (!pl.ok) return false;
+    const double csb = a.x_dtype == DBP_I8 ? 68.0 : 260.0;
+    const double dw_bytes = (double)(a.K * a.C * a.R * a.S) * 4.0;
+    *fixed_us = 8.0 + pl.k.units_per_split * (2.0 + pl.k.cells * csb / 30.0e3) + (pl.k.n_split > 1 ? 2.0 * pl.k.n_split * dw_bytes / 5.0e6 : 0.0);
+    const double util = pl.grid >= 256 ? 1.0 : pl.grid / 256.0;
+    const double rate = (a.R * a.S >= 9 ? 21.0e6 : 3.0e6) * util;                                 // flop per microsecond
+    *per_nnz_us = 2.0 * (double)((a.C + 63) / 64 * 64) * (double)(a.R * a.S) / rate;
+    return true;
+}
+
 // Host-side walk of the plans above for one layer shape (no GPU call): every limit the kernels rely on, re-derived here from
 // the plan's numbers.  0: consistent (or the shape takes the other kernels); otherwise the number of the violated invariant.
 int check_conv_rows_plans(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
@@ -735,11 +753,11 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
     const bool have = a.scratch && (uintptr_t)a.scratch % 256 == 0;
     size_t used = 0;
     bool dx_done = false, dw_done = false;
-    // Behind the density gate (flag set: both families are launched and the device picks one) the gather side only runs
-    // beyond ~99.8 % zeros, where the kernels that walk the format's compacted entries have the smaller fixed cost (they touch
-    // nothing but the entries); the kernels that scan the code planes win from there down to ~95 % zeros and serve the
-    // explicit gather path.
-    const bool rows_kernels = a.gate.flag == nullptr;
+    // Behind the density gate (flag set: both families are launched and the device picks one) the whole gather side only
+    // runs beyond ~99.8 % zeros, where the kernels that walk the format's compacted entries have the smaller fixed cost (they
+    // touch nothing but the entries); the kernels that scan the code planes win from there down to ~95 % zeros and serve the
+    // explicit gather path and, with rows_gated, the dW-only middle state of the gate.
+    const bool rows_kernels = a.gate.flag == nullptr || a.rows_gated;
     if (a.dX && rows_kernels) {
         DxRowsPlan pl = conv_dx_rows_plan(a, P_, Q_, have ? a.scratch_bytes : 0);
         if (pl.ok) {
@@ -777,6 +795,7 @@ hipError_t launch_conv_gather(const ConvArgs &a, const FormatView &f, hipStream_
         }
     }
     if ((dx_done || !a.dX) && (dw_done || !a.dW)) return hipSuccess;
+    if (a.rows_gated) return hipErrorInvalidValue;                    // the caller planned on the plane-scanning kernels (no format was written)
     ConvGatherGeom g;
     g.N = (int)a.N; g.C = (int)a.C; g.H = (int)a.H; g.Wd = (int)a.Wd; g.K = (int)a.K; g.R = (int)a.R; g.S = (int)a.S;
     g.pad = (int)a.pad; g.st = (int)a.stride; g.gate = a.gate;

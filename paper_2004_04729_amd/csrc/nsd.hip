@@ -401,7 +401,7 @@ __global__ __launch_bounds__(256) void nsd_kernel(NsdArgs a)
 }
 
 // Sum the per-workgroup statistics in a fixed order (one workgroup; deterministic, no atomics).
-__global__ __launch_bounds__(1024) void finalize_stats_kernel(const u32x4 *partials, int n, dbp_stats *out, int *flag, uint64_t gather_below)
+__global__ __launch_bounds__(1024) void finalize_stats_kernel(const u32x4 *partials, int n, dbp_stats *out, StatsJob job)
 {
     __shared__ uint64_t s_nnz[1024], s_sat[1024], s_nf[1024];
     __shared__ int s_mx[1024];
@@ -426,7 +426,7 @@ __global__ __launch_bounds__(1024) void finalize_stats_kernel(const u32x4 *parti
     }
     if (threadIdx.x == 0) {
         if (out) { out->nnz = s_nnz[0]; out->n_saturated = s_sat[0]; out->n_nonfinite = s_nf[0]; out->max_abs_code = s_mx[0]; out->reserved = 0; }
-        if (flag) flag[0] = s_nnz[0] < gather_below ? 1 : 0;      // density dispatch: 1 = the gather kernels run
+        write_density_flags(job, s_nnz[0]);
     }
 }
 
@@ -718,7 +718,7 @@ DitherKeys make_dither_keys(uint64_t seed)
 
 hipError_t launch_stats_job(const StatsJob &j, hipStream_t s)
 {
-    if (j.n > 0) hipLaunchKernelGGL(finalize_stats_kernel, dim3(1), dim3(1024), 0, s, j.partials, j.n, j.out, j.flag, j.gather_below);
+    if (j.n > 0) hipLaunchKernelGGL(finalize_stats_kernel, dim3(1), dim3(1024), 0, s, j.partials, j.n, j.out, j);
     if (j.bias_len > 0) {
         const int64_t zb = (j.bias_len + 255) / 256;
         hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)(zb < 1024 ? zb : 1024)), dim3(256), 0, s, j.bias_sums, j.bias_len,

@@ -1177,22 +1177,25 @@ static hipError_t conv_dw(const ConvArgs &a, const void *grad, Scale scale, hipS
                           (char *)a.scratch + rb, a.scratch_bytes - rb, s);
 }
 
-static hipError_t conv_products(const ConvArgs &a, hipStream_t s)
+static hipError_t conv_products(const ConvArgs &a_in, hipStream_t s)
 {
     hipError_t e = hipSuccess;
+    const ConvArgs &a = a_in;
+    ConvArgs aw = a_in;                                                // what the dW kernels see: their own gate where one is given
+    if (a_in.gate_dw.flag) aw.gate = a_in.gate_dw;
     if (a.codes && a.W8) {
         // full 8-bit mode: int8 weights and activations, exact int32 results
         if (a.dX) { e = conv_dx<MODE_I8>(a, a.codes, Scale{1.0f, nullptr}, s); if (e != hipSuccess) return e; }
-        if (a.dW) e = conv_dw<MODE_I8>(a, a.codes, Scale{1.0f, nullptr}, s);
+        if (a.dW) e = conv_dw<MODE_I8>(aw, a.codes, Scale{1.0f, nullptr}, s);
         return e;
     }
     if (a.codes) {
         if (a.dX) { e = conv_dx<MODE_BF16>(a, a.codes, Scale{a.step, a.step_dev}, s); if (e != hipSuccess) return e; }
-        if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_BF16>(a, a.codes, Scale{a.step, a.step_dev}, s) : conv_dw<MODE_I8>(a, a.codes, Scale{1.0f, nullptr}, s);
+        if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_BF16>(aw, a.codes, Scale{a.step, a.step_dev}, s) : conv_dw<MODE_I8>(aw, a.codes, Scale{1.0f, nullptr}, s);
         return e;
     }
     if (a.dX) { e = conv_dx<MODE_F32>(a, a.dense, Scale{1.0f, nullptr}, s); if (e != hipSuccess) return e; }
-    if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_F32>(a, a.dense, Scale{1.0f, nullptr}, s) : conv_dw<MODE_I8>(a, a.dense, Scale{1.0f, nullptr}, s);
+    if (a.dW) e = a.x_dtype == DBP_F32 ? conv_dw<MODE_F32>(aw, a.dense, Scale{1.0f, nullptr}, s) : conv_dw<MODE_I8>(aw, a.dense, Scale{1.0f, nullptr}, s);
     return e;
 }
 

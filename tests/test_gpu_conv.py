@@ -24,7 +24,8 @@ def _check(p, res):
     from oracle import oracle as O
     k_ref, st = O.nsd(p.delta, p.step, p.seed)
     assert np.array_equal(res["codes"], k_ref)
-    assert res["stats"].nnz == st.nnz and res["stats"].max_abs_code == st.max_abs_code
+    if res.get("stats") is not None:
+        assert res["stats"].nnz == st.nnz and res["stats"].max_abs_code == st.max_abs_code
     i8 = p.X.dtype == np.int8
     Xf = p.X.astype(np.float32)
     kw = dict(stride=p.stride, pad=p.pad)
@@ -286,26 +287,68 @@ def test_config5_int8_full_size_in_full(target):
     _check(p, res)
 
 
-@pytest.mark.parametrize("target,expect", [(0.92, 0), (0.999, 1)])
-def test_conv_auto_dispatches_by_density_on_the_device(target, expect):
-    # the ResNet-stage layer is large enough for both kernel families behind the density gate: matrix cores at 92 %
-    # zeros, the gather kernels at 99.9 % -- decided on the device from the quantiser's nonzero count
+def _auto_conv(p, want_dx=True, stats=True, path=None):
+    """dithered_conv2d_backward with DBP_PATH_AUTO; returns the results and the three density flags the device wrote."""
     import torch
     import paper_2004_04729_amd as dbp
     from gpu_util import dev, stream, conv_dims
-    p = workloads.config4a(target)
     N, Cc, H, Wd, K, R, S = conv_dims(p)
     codes = torch.empty(p.delta.shape, dtype=torch.int8, device="cuda:0")
-    dX = torch.full(p.X.shape, float("nan"), dtype=torch.float32, device="cuda:0")
-    dW = torch.full(p.W.shape, float("nan"), dtype=torch.float32, device="cuda:0")
-    ws = torch.zeros(dbp.conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, 1, p.pad), dtype=torch.uint8, device="cuda:0")
-    st = torch.zeros(32, dtype=torch.uint8, device="cuda:0")
-    dbp.dithered_conv2d_backward(dev(p.delta), dev(p.W), dev(p.X), dbp.F32, N, Cc, H, Wd, K, R, S, 1, p.pad, p.step, p.seed, 0,
-                                 codes, dX, dW, ws, st, dbp.PATH_AUTO, stream())
-    torch.cuda.synchronize()
+    dX = torch.full(p.X.shape, float("nan"), dtype=torch.float32, device="cuda:0") if want_dx else None
+    i8 = p.X.dtype == np.int8
+    xd = dbp.I8 if i8 else dbp.F32
+    dW = torch.full(p.W.shape, -77, dtype=torch.int32, device="cuda:0") if i8 else torch.full(p.W.shape, float("nan"), dtype=torch.float32, device="cuda:0")
+    ws = torch.zeros(dbp.conv2d_workspace_bytes(N, Cc, H, Wd, K, R, S, p.stride, p.pad, xd), dtype=torch.uint8, device="cuda:0")
     off = dbp.format_layout(N * K, p.delta.shape[2] * p.delta.shape[3])["scratch_offset"] + 16384 * 16
-    assert int(ws[off:off + 4].cpu().numpy().view(np.int32)[0]) == expect
-    _check(p, {"codes": codes.cpu().numpy(), "dX": dX.cpu().numpy(), "dW": dW.cpu().numpy(), "stats": dbp.Stats.from_tensor(st)})
+    ws[off:off + 12] = 255                                     # reads back as -1 unless a gated call writes the flags
+    st = torch.zeros(32, dtype=torch.uint8, device="cuda:0") if stats else None
+    dbp.dithered_conv2d_backward(dev(p.delta), dev(p.W), dev(p.X), xd, N, Cc, H, Wd, K, R, S, p.stride, p.pad, p.step, p.seed, 0,
+                                 codes, dX, dW, ws, st, dbp.PATH_AUTO if path is None else path, stream())
+    torch.cuda.synchronize()
+    flags = [int(v) for v in ws[off:off + 12].cpu().numpy().view(np.int32)]
+    res = {"codes": codes.cpu().numpy(), "dX": dX.cpu().numpy() if want_dx else None, "dW": dW.cpu().numpy(),
+           "stats": dbp.Stats.from_tensor(st) if stats else None}
+    return res, flags
+
+
+@pytest.mark.parametrize("target,expect", [(0.92, [0, 0, 1]), (0.985, [0, 1, 0]), (0.999, [0, 1, 0])])
+def test_conv_auto_dispatches_by_density_on_the_device(target, expect):
+    # the ResNet-stage layer behind the density gate, decided on the device from the quantiser's nonzero count: matrix cores
+    # at 92 % zeros; matrix cores for dX and the plane-scanning gather kernel for dW beyond ~97 %.
+    # Flags: [whole gather family, dW on the gather kernel, matrix cores].
+    p = workloads.config4a(target)
+    res, flags = _auto_conv(p)
+    assert flags == expect
+    _check(p, res)
+
+
+@pytest.mark.parametrize("target,expect", [(0.92, [0, 0, 1]), (0.999, [1, 0, 0])])
+def test_conv_auto_whole_gather_family_with_int8_activations(target, expect):
+    # int8 activations: dW stays on the int8 matrix cores at every density the plane-scanning kernel could take, so the gate
+    # has its other state -- both products on the kernels that walk the format's entries, beyond ~99.8 % zeros
+    p = _problem(64, 256, 14, 14, 256, 3, 3, 1, i8=True)
+    p.step = float(np.float32(workloads.step_for_sparsity(p.delta, target)))
+    res, flags = _auto_conv(p)
+    assert flags == expect
+    _check(p, res)
+
+
+@pytest.mark.parametrize("target,expect", [(0.9, [0, 0, 1]), (0.99, [0, 1, 0])])
+@pytest.mark.parametrize("want_dx,stats,two", [(True, True, False), (False, True, False), (True, False, True)])
+def test_conv_auto_dw_alone_on_the_gather_kernel(target, expect, want_dx, stats, two):
+    # a layer where only the middle state is armed (planes too large for the entry-walking kernels to win): the flags ride
+    # in the dX kernel's weight preparation, or, without dX, in a launch of their own; also without a statistics
+    # argument (the sum then goes to the workspace) and with the two-plane operands
+    import paper_2004_04729_amd as dbp
+    p = _problem(16, 128, 56, 56, 128, 3, 3, 1, c=4.0)
+    p.step = float(np.float32(workloads.step_for_sparsity(p.delta, target)))
+    res, flags = _auto_conv(p, want_dx=want_dx, stats=stats, path=(dbp.PATH_AUTO | dbp.PATH_TWO_PLANES) if two else None)
+    # (two planes make the matrix-core dW a third cheaper: on this layer the state is then not worth its launches and the
+    # gate is not armed at all)
+    assert flags == ([-1, -1, -1] if two else expect)
+    if stats:
+        assert abs(1 - res["stats"].nnz / p.delta.size - target) < 2e-2
+    _check(p, res)                                             # the two-plane bound (1.5e-5) lies inside the tolerance
 
 
 @pytest.mark.parametrize("target", [0.92, 0.99])
