@@ -70,11 +70,14 @@ typedef enum { DBP_F32 = 0, DBP_I8 = 1 } dbp_dtype;
  *           generic kernel that serves odd shapes skips all-zero code fragments).
  *   GATHER  kernels that walk the nonzero codes: work in proportion to the nonzeros (Sec. "Computational complexity",
  *           O(p_nz m k n)) plus the fixed cost of streaming the dense operand and writing the outputs.
- *   AUTO    matrix cores, unless the shape is one where the gather kernels can win by a wide margin at high sparsity; then
- *           BOTH families are launched behind a gate and the device decides: the kernel that sums the quantiser's statistics
- *           compares the nonzero count with a threshold (a linear cost model with constants measured on MI355X) and writes a
- *           flag; the kernels of the family the flag does not name return at once.  No host round trip, no allocation.
- *           Results are those of whichever family ran (both meet the same tolerance; each is deterministic). */
+ *   AUTO    matrix cores, unless the shape is one where gather kernels can win by a wide margin at high sparsity; then
+ *           BOTH candidates are launched behind a gate and the device decides: the kernel that sums the quantiser's statistics
+ *           compares the nonzero count with a threshold (a linear cost model with constants measured on MI355X) and writes
+ *           flags; the kernels the flags do not name return at once.  No host round trip, no allocation.  A layer has at most
+ *           one alternative to "everything on matrix cores": 3x3 convolutions with fp32 activations and 128 channels or
+ *           more the gather kernel for dW alone (dX stays on matrix cores; it wins from ~97 % zeros); fully connected layers
+ *           and other small-plane convolutions the whole gather family (beyond ~98.5-99.8 % zeros).
+ *           Results are those of whichever kernels ran (all meet the same tolerance; each is deterministic). */
 typedef enum {
     DBP_PATH_AUTO = 0,
     DBP_PATH_MFMA = 1,
