@@ -101,3 +101,31 @@ def test_conv_backward_and_static_quantiser_replay_like_the_eager_calls():
     fresh = [[torch.randn((N, K, H, Wd), device=DEV, generator=g) * sc] for sc in (1e-3, 3e-3, 5e-4)]
     d.copy_(fresh[0][0])
     _replay_matches_eager(call, [d], [codes, dX, dW, st, codes2, st2], fresh)
+
+
+def test_conv_backward_with_the_dw_gate_replays_like_the_eager_call():
+    # a layer that arms the middle state of the density gate (dX on matrix cores, dW on the plane-scanning gather kernel):
+    # every candidate kernel is in the captured graph and the flags written inside it pick, replay by replay
+    N, C, H, Wd, K = 64, 256, 14, 14, 256
+    g = torch.Generator(device=DEV)
+    g.manual_seed(9)
+    d = torch.empty((N, K, H, Wd), device=DEV)
+    W = torch.randn((K, C, 3, 3), device=DEV, generator=g) * 0.03
+    X = torch.relu(torch.randn((N, C, H, Wd), device=DEV, generator=g))
+    codes = torch.empty((N, K, H, Wd), dtype=torch.int8, device=DEV)
+    dX = torch.empty_like(X)
+    dW = torch.empty_like(W)
+    st = torch.zeros(32, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(dbp.conv2d_workspace_bytes(N, C, H, Wd, K, 3, 3, 1, 1), dtype=torch.uint8, device=DEV)
+
+    def call(stream):
+        dbp.dithered_conv2d_backward(d, W, X, dbp.F32, N, C, H, Wd, K, 3, 3, 1, 1, 4e-3, 11, 0, codes, dX, dW, ws, st, dbp.PATH_AUTO, stream)
+
+    fresh = [[torch.randn((N, K, H, Wd), device=DEV, generator=g) * sc] for sc in (1e-3, 5e-5, 4e-4)]    # ~20 %, ~1 %, ~8 % nonzeros
+    d.copy_(fresh[0][0])
+    flags = []
+    off = dbp.format_layout(N * K, H * Wd)["scratch_offset"] + 16384 * 16
+    ws[off:off + 12] = 255
+    _replay_matches_eager(call, [d], [codes, dX, dW, st], fresh,
+                          after_replay=lambda rnd: flags.append([int(v) for v in ws[off:off + 12].cpu().numpy().view(np.int32)]))
+    assert flags == [[0, 0, 1], [0, 1, 0], [0, 0, 1]], flags
