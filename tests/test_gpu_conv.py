@@ -59,6 +59,9 @@ CASES = [  # N, C, H, Wd, K, R, S, pad
     (2, 16, 12, 12, 40, 2, 3, 1),       # six taps
     (2, 16, 13, 12, 24, 3, 2, 1),       # six taps the other way round, odd height
     (32, 256, 48, 48, 16, 3, 3, 1),     # 704 workgroups: two rounds over the chip, the second one partly filled
+    (2, 24, 16, 16, 40, 3, 3, 0),       # 14-wide code rows under 16-wide image rows: the dW stager's half-piece path for the codes alone
+    (3, 70, 18, 18, 130, 3, 3, 1),      # 18-wide rows (even, not a multiple of 4): half-piece path for both operands, partial tiles
+    (2, 64, 10, 14, 64, 3, 3, 1),       # the same on whole tiles, more rows than columns
 ]
 
 
