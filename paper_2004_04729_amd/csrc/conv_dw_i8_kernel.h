@@ -70,7 +70,6 @@ __global__ __launch_bounds__(512, 1) void conv_dw_i8_kernel(ConvDwI8Args a)
         // ---- fixed for the kernel: this thread's (row, cell) pair of each operand, its LDS cell, its offset inside the
         // rows of a tile's first channel, and how a partly filled cell is moved into place.  Passes walk the channels.
         const uint32_t dump = (2u * buf_cells + (uint32_t)tid) * 16u;        // a cell of its own for writes that have no place
-        const bool part_rows = (a.Wd & 15) != 0;                             // rows end inside a cell
         const int xch = tid / a.xpairs, xpr = tid - xch * a.xpairs, XCH = 256 / a.xpairs;
         const bool x_own = xch < XCH;
         const int xrow = xpr / a.DC, xcell = xpr - xrow * a.DC;
@@ -127,14 +126,12 @@ __global__ __launch_bounds__(512, 1) void conv_dw_i8_kernel(ConvDwI8Args a)
 
         // 16 loaded bytes -> one cell: a partly filled cell's load started sh dwords early (pixel dword d is loaded dword
         // d + sh, dwords past the row are zero); rows outside the image are cleared; then "dword d = pixels d, d+4, d+8, d+12"
+        // (rows that fill whole cells have sh = 0, m1 = take2 = 0, take0 = ok: the same arithmetic gives v & ok.  A run-time
+        // test for them inside the loop over the passes was two taken branches per cell.)
         auto make_cell = [&](const u32x4 &v, uint32_t m1, uint32_t take2, uint32_t take0, uint32_t ok) {
-            uint32_t w0, w1, w2, w3;
-            if (part_rows) {
-                const uint32_t u0 = (v.y & m1) | (v.x & ~m1), u1 = (v.z & m1) | (v.y & ~m1), u2 = (v.w & m1) | (v.z & ~m1), u3 = v.w & ~m1;
-                w0 = (u2 & take2) | (u0 & take0); w1 = (u3 & take2) | (u1 & take0); w2 = u2 & take0; w3 = u3 & take0;
-            } else {
-                w0 = v.x & ok; w1 = v.y & ok; w2 = v.z & ok; w3 = v.w & ok;
-            }
+            const uint32_t u0 = (v.y & m1) | (v.x & ~m1), u1 = (v.z & m1) | (v.y & ~m1), u2 = (v.w & m1) | (v.z & ~m1), u3 = v.w & ~m1;
+            const uint32_t w0 = (u2 & take2) | (u0 & take0), w1 = (u3 & take2) | (u1 & take0), w2 = u2 & take0, w3 = u3 & take0;
+            (void)ok;
             uint32_t o[4];
             fc2i_transpose(w0, w1, w2, w3, o);
             return uint4{o[0], o[1], o[2], o[3]};
