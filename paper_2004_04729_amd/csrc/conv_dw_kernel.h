@@ -306,21 +306,21 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
                 if (++w == a.Wd) { w = 0; ++h; }
             }
             bool done = false;
-            if constexpr (MODE != MODE_I8) {
-                if (a.row2x && !a.row4x) {
-                    // Rows of an even length that is not a multiple of 4 (14x14 planes ...): a piece may straddle two rows, its
-                    // halves never do, and their places are the same for all channels.  A half with no place in this unit is
-                    // written as zeros into the zero columns behind the unit's first row (PW - Wd >= 2 for such widths), so
-                    // the loop over the channels has no branch: a mask on the value, two fixed offsets.
-                    const uint32_t mA = x_ld && pos[0] >= 0 ? 0xFFFFFFFFu : 0u, mB = x_ld && pos[2] >= 0 ? 0xFFFFFFFFu : 0u;
-                    const uint32_t oA = (uint32_t)((pos[0] >= 0 ? pos[0] : a.Wd) * ESZ), oB = (uint32_t)((pos[2] >= 0 ? pos[2] : a.Wd) * ESZ);
-                    char *row = lds_x + (size_t)xch * a.pitchX * ESZ;
-                    const size_t rstep = (size_t)XCH * a.pitchX * ESZ;
+            if (a.row2x && !a.row4x) {
+                // Rows of an even length that is not a multiple of 4 (14x14 planes ...): a piece may straddle two rows, its
+                // halves never do, and their places are the same for all channels.  A half with no place in this unit is
+                // written as zeros into the zero columns behind the unit's first row (PW - Wd >= 2 for such widths), so
+                // the loop over the channels has no branch: a mask on the value, two fixed offsets.
+                const uint32_t mA = x_ld && pos[0] >= 0 ? 0xFFFFFFFFu : 0u, mB = x_ld && pos[2] >= 0 ? 0xFFFFFFFFu : 0u;
+                const uint32_t oA = (uint32_t)((pos[0] >= 0 ? pos[0] : a.Wd) * ESZ), oB = (uint32_t)((pos[2] >= 0 ? pos[2] : a.Wd) * ESZ);
+                char *row = lds_x + (size_t)xch * a.pitchX * ESZ;
+                const size_t rstep = (size_t)XCH * a.pitchX * ESZ;
 #pragma unroll
-                    for (int j = 0; j < XI; ++j) {
-                        if (j >= xi_n) break;
-                        const uint32_t okm = (whole_tile || c0 + xch + XCH * j < a.C) ? 0xFFFFFFFFu : 0u;
-                        const uint32_t ma = mA & okm, mb = mB & okm;
+                for (int j = 0; j < XI; ++j) {
+                    if (j >= xi_n) break;
+                    const uint32_t okm = (whole_tile || c0 + xch + XCH * j < a.C) ? 0xFFFFFFFFu : 0u;
+                    const uint32_t ma = mA & okm, mb = mB & okm;
+                    if constexpr (MODE != MODE_I8) {
                         uint32_t pa[PL], pb[PL];
                         cdw_planes<PL>(__uint_as_float(xr[j].x & ma), __uint_as_float(xr[j].y & ma), pa);
                         cdw_planes<PL>(__uint_as_float(xr[j].z & mb), __uint_as_float(xr[j].w & mb), pb);
@@ -329,10 +329,13 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
                             *(uint32_t *)(row + oA + pl * x_plane) = pa[pl];
                             *(uint32_t *)(row + oB + pl * x_plane) = pb[pl];
                         }
-                        row += rstep;
+                    } else {
+                        *(uint16_t *)(row + oA) = (uint16_t)(xr[j] & ma);
+                        *(uint16_t *)(row + oB) = (uint16_t)((xr[j] >> 16) & mb);
                     }
-                    done = true;
+                    row += rstep;
                 }
+                done = true;
             }
 #pragma unroll
             for (int j = 0; j < XI; ++j) {
@@ -397,25 +400,28 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
                 if (++q == a.Q) { q = 0; ++p; }
             }
             bool done = false;
-            if constexpr (MODE != MODE_I8) {
-                if (a.row2c && !a.row4c) {
-                    // the same for the codes: a half with no place goes, as zeros, to the zero columns behind the patch's second row
-                    const uint32_t mA = c_ld && pos[0] >= 0 ? 0xFFFFFFFFu : 0u, mB = c_ld && pos[2] >= 0 ? 0xFFFFFFFFu : 0u;
-                    const int spare = a.PW + a.Q + CDW_M8;
-                    const uint32_t oA = (uint32_t)((pos[0] >= 0 ? pos[0] : spare) * ESZ), oB = (uint32_t)((pos[2] >= 0 ? pos[2] : spare) * ESZ);
-                    char *row = lds_c + (size_t)cch * a.pitchC * ESZ;
-                    const size_t rstep = (size_t)CCH * a.pitchC * ESZ;
+            if (a.row2c && !a.row4c) {
+                // the same for the codes: a half with no place goes, as zeros, to the zero columns behind the patch's second row
+                const uint32_t mA = c_ld && pos[0] >= 0 ? 0xFFFFFFFFu : 0u, mB = c_ld && pos[2] >= 0 ? 0xFFFFFFFFu : 0u;
+                const int spare = a.PW + a.Q + CDW_M8;
+                const uint32_t oA = (uint32_t)((pos[0] >= 0 ? pos[0] : spare) * ESZ), oB = (uint32_t)((pos[2] >= 0 ? pos[2] : spare) * ESZ);
+                char *row = lds_c + (size_t)cch * a.pitchC * ESZ;
+                const size_t rstep = (size_t)CCH * a.pitchC * ESZ;
 #pragma unroll
-                    for (int j = 0; j < CI; ++j) {
-                        if (j >= ci_n) break;
-                        const uint32_t okm = (whole_tile || k0 + cch + CCH * j < a.K) ? 0xFFFFFFFFu : 0u;
-                        const uint32_t t = cr[j];
+                for (int j = 0; j < CI; ++j) {
+                    if (j >= ci_n) break;
+                    const uint32_t okm = (whole_tile || k0 + cch + CCH * j < a.K) ? 0xFFFFFFFFu : 0u;
+                    const uint32_t t = cr[j];
+                    if constexpr (MODE != MODE_I8) {
                         *(uint32_t *)(row + oA) = bf16_pair_from_i8((int8_t)t, (int8_t)(t >> 8)) & mA & okm;
                         *(uint32_t *)(row + oB) = bf16_pair_from_i8((int8_t)(t >> 16), (int8_t)(t >> 24)) & mB & okm;
-                        row += rstep;
+                    } else {
+                        *(uint16_t *)(row + oA) = (uint16_t)(t & mA & okm);
+                        *(uint16_t *)(row + oB) = (uint16_t)((t >> 16) & mB & okm);
                     }
-                    done = true;
+                    row += rstep;
                 }
+                done = true;
             }
 #pragma unroll
             for (int j = 0; j < CI; ++j) {
