@@ -126,12 +126,11 @@ __global__ __launch_bounds__(512, 1) void conv_dw_i8_kernel(ConvDwI8Args a)
 
         // 16 loaded bytes -> one cell: a partly filled cell's load started sh dwords early (pixel dword d is loaded dword
         // d + sh, dwords past the row are zero); rows outside the image are cleared; then "dword d = pixels d, d+4, d+8, d+12"
-        // (rows that fill whole cells have sh = 0, m1 = take2 = 0, take0 = ok: the same arithmetic gives v & ok.  A run-time
+        // (rows that fill whole cells have sh = 0, m1 = take2 = 0, take0 = the row's validity mask: the same arithmetic gives v & that mask.  A run-time
         // test for them inside the loop over the passes was two taken branches per cell.)
-        auto make_cell = [&](const u32x4 &v, uint32_t m1, uint32_t take2, uint32_t take0, uint32_t ok) {
+        auto make_cell = [&](const u32x4 &v, uint32_t m1, uint32_t take2, uint32_t take0) {
             const uint32_t u0 = (v.y & m1) | (v.x & ~m1), u1 = (v.z & m1) | (v.y & ~m1), u2 = (v.w & m1) | (v.z & ~m1), u3 = v.w & ~m1;
             const uint32_t w0 = (u2 & take2) | (u0 & take0), w1 = (u3 & take2) | (u1 & take0), w2 = u2 & take0, w3 = u3 & take0;
-            (void)ok;
             uint32_t o[4];
             fc2i_transpose(w0, w1, w2, w3, o);
             return uint4{o[0], o[1], o[2], o[3]};
@@ -147,14 +146,14 @@ __global__ __launch_bounds__(512, 1) void conv_dw_i8_kernel(ConvDwI8Args a)
 #pragma unroll
             for (int j = 0; j < XI; ++j) {
                 if (j >= x_passes) break;
-                *(uint4 *)(lds + (j == x_passes - 1 ? x_llast : cell)) = make_cell(xr[j], xm1, xt2, xt0, xok);
+                *(uint4 *)(lds + (j == x_passes - 1 ? x_llast : cell)) = make_cell(xr[j], xm1, xt2, xt0);
                 cell += x_ls;
             }
             cell = c_l0;
 #pragma unroll
             for (int j = 0; j < CI; ++j) {
                 if (j >= c_passes) break;
-                *(uint4 *)(lds + (j == c_passes - 1 ? c_llast : cell)) = make_cell(cr[j], cm1, ct2, ct0, cok);
+                *(uint4 *)(lds + (j == c_passes - 1 ? c_llast : cell)) = make_cell(cr[j], cm1, ct2, ct0);
                 cell += c_ls;
             }
         };
