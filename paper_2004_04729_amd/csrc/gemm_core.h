@@ -46,8 +46,8 @@ struct RawF32x4  { f32x4 v; };            // 4 fp32
 
 __device__ __forceinline__ uint32_t bf16_pair_from_i8(int a, int b)
 {
-    // small integers are exact in bf16: the upper 16 bits of their fp32 image
-    return (__float_as_uint((float)a) >> 16) | (__float_as_uint((float)b) & 0xFFFF0000u);
+    // small integers are exact in bf16: the upper 16 bits of their fp32 image (one byte permute packs the two upper halves)
+    return __builtin_amdgcn_perm(__float_as_uint((float)b), __float_as_uint((float)a), 0x07060302u);
 }
 
 __device__ __forceinline__ void convert(const RawCodes8 &r, u32x4 (&out)[1])
