@@ -44,7 +44,8 @@ struct ConvDwArgs {
     int tiles_k, tiles_c;
     int pitchX, pitchC, lenC;  // LDS row pitches (elements) and code patch length (elements, multiple of 4)
     int NR;                    // code rows that a unit's patch overlaps
-    int nqx, nqc;              // aligned 4-element pieces per channel that a unit loads (X, codes)
+    int nqx, nqc;              // aligned 4-element pieces per channel that a unit loads (X, codes; c8: pieces of 8 codes)
+    int c8;                    // bf16 modes, code rows of whole 8-code pieces (Q % 8 == 0): the whole-piece path loads the codes 8 bytes at a time
     int xshift, cshift;        // stagers: 2^shift threads along the pieces (>= nq), 256 >> shift channels at a time
     int row4x, row4c;          // Wd % 4 == 0 / Q % 4 == 0: a piece never straddles rows -> one wide LDS write
     int row2x, row2c;          // Wd, Q even: at least its halves never do
@@ -87,9 +88,11 @@ __device__ __forceinline__ u32x4 cdw_funnel(const uint4 &lo, const uint4 &hi)
                       __builtin_amdgcn_alignbyte(d[q + 3], d[q + 2], b), __builtin_amdgcn_alignbyte(d[q + 4], d[q + 3], b)};
 }
 
-template <int MODE, int R, int S, int PAD, int MB, bool ROW4>
+// ROWS: 0 rows of any length; 1 image rows and code rows of whole 4-element pieces; 2 the same with code rows of whole 8-code pieces
+template <int MODE, int R, int S, int PAD, int MB, int ROWS>
 __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
 {
+    constexpr bool ROW4 = ROWS != 0, C8 = ROWS == 2;
     if (a.gate.closed()) return;
     using TR = CdwTraits<MODE>;
     using XT = typename TR::XT;
@@ -126,6 +129,10 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
 
     XRaw xr[XI];                                                     // raw loads of the unit being staged next
     uint32_t cr[CI];
+    // Pieces of 8 codes where rows allow (a wavefront's load costs the CU's address unit the same 16 cycles whether it
+    // moves 256 B or 512 B, and the stagers' loads are what they wait for): half as many code loads.
+    typedef uint32_t u32x2_a4 __attribute__((ext_vector_type(2), aligned(4)));
+    u32x2_a4 cr8[C8 ? CI / 2 : 1];
 
     // Aligned loads of a unit's rows.  Pieces outside the tensor or the channel range read offset 0 of the
     // (uniform) base and are replaced by zero when staged, so the loads are straight-line code.
@@ -161,7 +168,7 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
     // bound by the number of instructions they issue: per piece this path issues an addition, a comparison
     // and a select on either side of the load, where the general path below recomputes positions (two
     // integer divisions per unit), multiplies addresses per piece and branches around every write.
-    const int xrel = 4 * xq, crel = 4 * cq;
+    const int xrel = 4 * xq, crel = (C8 ? 8 : 4) * cq;
     bool x_own = false, c_own = false;
     uint32_t x_lds0 = 0, c_lds0 = 0, x_g0 = 0;
     int c_g0 = 0;
@@ -197,11 +204,20 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
             const uint32_t cm = c_ld ? 0xFFFFFFFFu : 0u, xm = x_ld ? 0xFFFFFFFFu : 0u;
             uint32_t co = (uint32_t)(c_g0 + c_shift) & cm, xo = x_g0 & xm;
             const uint32_t cs = (uint32_t)c_gstep & cm, xs = x_gstep & xm;
+            if constexpr (C8) {
 #pragma unroll
-            for (int j = 0; j < CI; ++j) {
-                if (j >= ci_n) break;
-                cr[j] = *(const uint32_t *)(cb + co);
-                co += cs;
+                for (int j = 0; j < CI / 2; ++j) {
+                    if (j >= ci_n) break;
+                    cr8[j] = *(const u32x2_a4 *)(cb + co);
+                    co += cs;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < CI; ++j) {
+                    if (j >= ci_n) break;
+                    cr[j] = *(const uint32_t *)(cb + co);
+                    co += cs;
+                }
             }
 #pragma unroll
             for (int j = 0; j < XI; ++j) {
@@ -210,11 +226,20 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
                 xo += xs;
             }
         } else {
+            if constexpr (C8) {
 #pragma unroll
-            for (int j = 0; j < CI; ++j) {
-                if (j >= ci_n) break;
-                const bool ok = c_ld && k0 + cch + CCH * j < a.K;
-                cr[j] = *(const uint32_t *)(cb + (ok ? (uint32_t)(c_g0 + c_shift + j * c_gstep) : 0u));
+                for (int j = 0; j < CI / 2; ++j) {
+                    if (j >= ci_n) break;
+                    const bool ok = c_ld && k0 + cch + CCH * j < a.K;
+                    cr8[j] = *(const u32x2_a4 *)(cb + (ok ? (uint32_t)(c_g0 + c_shift + j * c_gstep) : 0u));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < CI; ++j) {
+                    if (j >= ci_n) break;
+                    const bool ok = c_ld && k0 + cch + CCH * j < a.K;
+                    cr[j] = *(const uint32_t *)(cb + (ok ? (uint32_t)(c_g0 + c_shift + j * c_gstep) : 0u));
+                }
             }
 #pragma unroll
             for (int j = 0; j < XI; ++j) {
@@ -247,6 +272,12 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
             *(uint32_t *)d = t;
     };
 
+    auto put_c8 = [&](uint32_t addr, uint32_t t0, uint32_t t1) {          // eight codes -> one 16-byte cell of bf16 (bf16 modes only)
+        *(uint4 *)((char *)cdw_lds + addr) =
+            uint4{bf16_pair_from_i8((int8_t)t0, (int8_t)(t0 >> 8)), bf16_pair_from_i8((int8_t)(t0 >> 16), (int8_t)(t0 >> 24)),
+                  bf16_pair_from_i8((int8_t)t1, (int8_t)(t1 >> 8)), bf16_pair_from_i8((int8_t)(t1 >> 16), (int8_t)(t1 >> 24))};
+    };
+
     auto stage_fast = [&](int unit, uint32_t buf_off) {
         const int n = unit / a.chunks, h_a = (unit - n * a.chunks) * a.RU;
         if (x_own) {
@@ -274,7 +305,15 @@ __global__ __launch_bounds__(512, 1) void conv_dw_kernel(ConvDwArgs a)
             const bool c_ld = crel + c_shift >= 0 && crel + c_shift < PQ;
             const uint32_t cm = c_ld ? 0xFFFFFFFFu : 0u;
             uint32_t addr = buf_off + c_lds0;
-            if (whole_tile) {
+            if constexpr (C8) {
+#pragma unroll
+                for (int j = 0; j < CI / 2; ++j) {
+                    if (j >= ci_n) break;
+                    const uint32_t m = whole_tile || k0 + cch + CCH * j < a.K ? cm : 0u;
+                    put_c8(addr, cr8[j].x & m, cr8[j].y & m);
+                    addr += c_lstep;
+                }
+            } else if (whole_tile) {
 #pragma unroll
                 for (int j = 0; j < CI; ++j) {
                     if (j >= ci_n) break;

@@ -284,6 +284,9 @@ ConvDwPlan conv_dw_plan(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, 
     if (!pl.ok) return pl;
     k.row4x = Wd % 4 == 0; k.row4c = Q % 4 == 0;
     k.row2x = Wd % 2 == 0; k.row2c = Q % 2 == 0;
+    // code rows of whole 8-code pieces under the whole-piece staging path (bf16 modes): half as many, twice as wide code loads
+    k.c8 = !i8 && k.row4x && k.row4c && Q % 8 == 0;
+    if (k.c8) k.nqc = (k.nqc + 1) / 2;
     k.xshift = k.nqx <= 16 ? 4 : k.nqx <= 32 ? 5 : 6;
     k.cshift = k.nqc <= 32 ? 5 : k.nqc <= 64 ? 6 : 7;
     const int TK = 64 * pl.mb;
@@ -370,18 +373,18 @@ hipError_t launch_conv_dw_i8(const ConvDwI8Plan &pl, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int MODE, int R, int S, int PAD, int MB, bool ROW4>
+template <int MODE, int R, int S, int PAD, int MB, int ROWS>
 hipError_t launch_conv_dw_fast_as(const ConvDwPlan &pl, hipStream_t s)
 {
     // more than 64 KiB of dynamic LDS has to be allowed per kernel, once
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dw_kernel<MODE, R, S, PAD, MB, ROW4>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_dw_kernel<MODE, R, S, PAD, MB, ROWS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, CDW_MAX_LDS);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((conv_dw_kernel<MODE, R, S, PAD, MB, ROW4>), dim3(pl.grid), dim3(512), pl.lds_bytes, s, pl.args);
+    hipLaunchKernelGGL((conv_dw_kernel<MODE, R, S, PAD, MB, ROWS>), dim3(pl.grid), dim3(512), pl.lds_bytes, s, pl.args);
     if (pl.args.n_split > 1)
         hipLaunchKernelGGL((conv_dw_reduce_kernel<MODE, R, S, MB>), dim3(pl.reduce_grid), dim3(256), 0, s, pl.args);
     return hipGetLastError();
@@ -391,8 +394,12 @@ template <int MODE, int R, int S, int PAD, int MB>
 hipError_t launch_conv_dw_fast(const ConvDwPlan &pl, hipStream_t s)
 {
     // rows that are whole numbers of aligned 4-element pieces have a staging path of their own
-    return pl.args.row4x && pl.args.row4c ? launch_conv_dw_fast_as<MODE, R, S, PAD, MB, true>(pl, s)
-                                          : launch_conv_dw_fast_as<MODE, R, S, PAD, MB, false>(pl, s);
+    // (and code rows of whole 8-code pieces, bf16 modes, one that loads the codes 8 bytes at a time)
+    if constexpr (MODE != MODE_I8) {
+        if (pl.args.c8) return launch_conv_dw_fast_as<MODE, R, S, PAD, MB, 2>(pl, s);
+    }
+    return pl.args.row4x && pl.args.row4c ? launch_conv_dw_fast_as<MODE, R, S, PAD, MB, 1>(pl, s)
+                                          : launch_conv_dw_fast_as<MODE, R, S, PAD, MB, 0>(pl, s);
 }
 
 // ---- fast fully connected path (fc_kernel.h) -------------------------------------------------------
