@@ -162,6 +162,8 @@ ONE_BY_ONE = [  # N, C, H, Wd, K: 1x1, stride 1, no padding, more than 128 outpu
     (5, 16, 6, 6, 140),         # 36 pixels: the second window repeats 28 indices of the first
     (70, 128, 14, 14, 256),     # the reduction split over groups of images
     (2, 260, 10, 10, 300),      # several column tiles, two row tiles
+    (6, 96, 12, 12, 64),        # 64 output channels: a quarter of the 256-row tile, the fewest this kernel takes
+    (4, 200, 8, 16, 100),       # 100 output channels, ragged against every tile size
 ]
 
 
@@ -180,6 +182,8 @@ ONE_BY_ONE_I8 = [  # the same with int8 activations: windows of 64 pixels
     (70, 128, 14, 14, 256),     # the reduction split over groups of images
     (2, 260, 10, 10, 300),      # several column tiles, two row tiles
     (3, 16, 6, 6, 140),         # 36 pixels, less than a window: the other kernels serve
+    (6, 96, 12, 12, 64),        # 64 output channels: a quarter of the row tile
+    (4, 200, 8, 16, 100),       # 100 output channels
 ]
 
 
