@@ -420,6 +420,16 @@ int dbp_plan_check_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K
 int dbp_plan_check_conv2d_gather(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
                                  int64_t stride, int64_t pad, int int8_x, size_t scratch_bytes);
 
+/* What DBP_PATH_AUTO would set up for dithered_conv2d_backward on this layer, from the host's cost models alone (no GPU
+ * call; see dbp_path): 0 = matrix cores, no gate; 1 = the whole gather family behind the gate, taken when fewer than
+ * *gather_below codes are nonzero; 2 = the gather kernel for dW alone (dX on matrix cores) when fewer than *dw_rows_below
+ * are; -1 for invalid dimensions.  The thresholds not in use are set to 0; either pointer may be NULL.  int8_x: X is
+ * DBP_I8; want_dx / want_dw: which products the call asks for; two_planes: DBP_PATH_TWO_PLANES.  The workspace is taken to
+ * be the size dbp_conv2d_workspace_bytes reports.  For tests and diagnostics. */
+int dbp_plan_auto_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
+                         int64_t stride, int64_t pad, int int8_x, int want_dx, int want_dw, int two_planes,
+                         uint64_t *gather_below, uint64_t *dw_rows_below);
+
 #ifdef __cplusplus
 }
 #endif

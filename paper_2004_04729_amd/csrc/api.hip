@@ -1018,4 +1018,21 @@ dbp_status dithered_conv2d_layer_backward(const float *delta_a, const float *act
                                     path, stream, job, pair);
 }
 
+// The density dispatch a DBP_PATH_AUTO convolution call would set up, from the host's cost models alone (no GPU call).
+int dbp_plan_auto_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S, int64_t stride, int64_t pad,
+                         int int8_x, int want_dx, int want_dw, int two_planes, uint64_t *gather_below, uint64_t *dw_rows_below)
+{
+    int64_t P, Q;
+    if (check_conv_dims(N, C, H, Wd, K, R, S, stride, pad, &P, &Q) != DBP_OK || (!want_dx && !want_dw)) return -1;
+    // stand-ins for the tensors: the planners look at alignment and at which outputs are asked for, and touch nothing
+    char *fake = (char *)(uintptr_t)4096;
+    const ConvArgs call = conv_call((const float *)fake, fake, int8_x ? DBP_I8 : DBP_F32, N, C, H, Wd, K, R, S, stride, pad,
+                                    want_dx ? (float *)fake : nullptr, want_dw ? fake : nullptr, (const int8_t *)fake, fake,
+                                    conv_scratch_bytes(N, C, H, Wd, K, R, S, pad, stride), two_planes != 0);
+    const AutoPlan ap = conv_auto_plan(call, P, Q);
+    if (gather_below) *gather_below = ap.dual ? ap.gather_below : 0;
+    if (dw_rows_below) *dw_rows_below = ap.dw_rows_below;
+    return ap.dual ? 1 : ap.dw_rows_below ? 2 : 0;
+}
+
 }  // extern "C"

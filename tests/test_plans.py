@@ -80,3 +80,37 @@ def test_conv_gather_plans_stay_in_bounds():
                     bad.append((N, C_, H, Wd, K, R, st, pad, i8, e))
     assert not bad, bad[:10]
     assert L.dbp_plan_check_conv2d_gather(1, 1, 2, 2, 1, 5, 5, 1, 0, 0, 0) == -1
+
+
+def test_conv_auto_plan_arms_what_the_measurements_say():
+    """The host's cost models behind DBP_PATH_AUTO on the layer shapes they were calibrated on (measured on MI355X: where the
+    plane-scanning gather kernel for dW beats the matrix cores below 2-4 % nonzeros it is armed, with a threshold in that
+    range; where it never does, or the gate's empty launches would cost more than it can win, nothing is armed)."""
+    L = _lib()
+    L.dbp_plan_auto_conv2d.argtypes = [C.c_int64] * 9 + [C.c_int] * 4 + [C.POINTER(C.c_uint64)] * 2
+    L.dbp_plan_auto_conv2d.restype = C.c_int
+
+    def plan(N, C_, H, K, R, pad, i8=0, dx=1, dw=1, two=0, stride=1):
+        g, d = C.c_uint64(7), C.c_uint64(7)
+        kind = L.dbp_plan_auto_conv2d(N, C_, H, H, K, R, R, stride, pad, i8, dx, dw, two, C.byref(g), C.byref(d))
+        codes = N * K * ((H + 2 * pad - R) // stride + 1) ** 2
+        return kind, g.value / codes, d.value / codes
+
+    # dW alone on the gather kernel: armed, switching between 1.5 % and 5 % nonzeros (measured crossovers: 3-4 %)
+    for shape in [(64, 256, 14, 256), (64, 512, 14, 512), (32, 256, 28, 256), (16, 128, 56, 128), (256, 128, 16, 128)]:
+        kind, g, d = plan(*shape, 3, 1)
+        assert kind == 2 and g == 0 and 0.015 < d < 0.05, (shape, kind, g, d)
+        assert plan(*shape, 3, 1, dx=0)[0] == 2                         # also for a call that asks for dW alone
+        assert plan(*shape, 3, 1, dw=0)[0] in (0, 1)                    # and never for one that asks for dX alone
+    # too little to win (64-channel layers, config 3's shape among them; 1x1 layers): no gate, or the whole-family one
+    for shape, r, pad in [((128, 64, 32, 64), 3, 1), ((32, 64, 56, 64), 3, 1), ((64, 1024, 14, 256), 1, 0), ((32, 512, 28, 128), 1, 0)]:
+        kind, g, d = plan(*shape, r, pad)
+        assert kind in (0, 1) and d == 0, (shape, kind, d)
+    # int8 activations keep dW on the int8 matrix cores: config 5 no gate at all, the 14x14 layer the whole-family gate beyond 99.5 % zeros
+    assert plan(32, 256, 56, 256, 3, 1, i8=1)[0] == 0
+    kind, g, d = plan(64, 256, 14, 256, 3, 1, i8=1)
+    assert kind == 1 and d == 0 and 0 < g < 0.005, (kind, g, d)
+    # shapes the kernels decline (stride 2; 5x5) and invalid ones
+    assert plan(64, 256, 28, 256, 3, 1, stride=2)[0] in (0, 1) and plan(16, 64, 28, 64, 5, 2)[0] in (0, 1)
+    assert L.dbp_plan_auto_conv2d(1, 1, 2, 2, 1, 5, 5, 1, 0, 0, 1, 1, 0, None, None) == -1
+    assert L.dbp_plan_auto_conv2d(4, 8, 8, 8, 8, 3, 3, 1, 1, 0, 0, 0, 0, None, None) == -1
