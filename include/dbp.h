@@ -429,6 +429,10 @@ int dbp_plan_check_conv2d_gather(int64_t N, int64_t C, int64_t H, int64_t Wd, in
 int dbp_plan_auto_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K, int64_t R, int64_t S,
                          int64_t stride, int64_t pad, int int8_x, int want_dx, int want_dw, int two_planes,
                          uint64_t *gather_below, uint64_t *dw_rows_below);
+/* The same for dithered_linear_backward: 0 = matrix cores, no gate; 1 = both families behind the gate, the gather kernels
+ * taken when fewer than *gather_below codes are nonzero (0 otherwise; may be NULL); -1 for invalid dimensions. */
+int dbp_plan_auto_linear(int64_t B, int64_t in, int64_t out, int int8_x, int want_dx, int want_dw, int two_planes,
+                         uint64_t *gather_below);
 
 #ifdef __cplusplus
 }

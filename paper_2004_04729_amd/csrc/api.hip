@@ -1035,4 +1035,16 @@ int dbp_plan_auto_conv2d(int64_t N, int64_t C, int64_t H, int64_t Wd, int64_t K,
     return ap.dual ? 1 : ap.dw_rows_below ? 2 : 0;
 }
 
+// The same for dithered_linear_backward: 0 = matrix cores, no gate; 1 = the gather family below *gather_below nonzero codes.
+int dbp_plan_auto_linear(int64_t B, int64_t in, int64_t out, int int8_x, int want_dx, int want_dw, int two_planes, uint64_t *gather_below)
+{
+    if (check_linear_dims(B, in, out) != DBP_OK || (!want_dx && !want_dw)) return -1;
+    char *fake = (char *)(uintptr_t)4096;
+    const LinearArgs call = linear_call((const float *)fake, fake, int8_x ? DBP_I8 : DBP_F32, B, in, out, want_dx ? (float *)fake : nullptr,
+                                        want_dw ? fake : nullptr, (const int8_t *)fake, fake, linear_scratch_bytes(B, in, out), two_planes != 0);
+    const AutoPlan ap = linear_auto_plan(call, true);
+    if (gather_below) *gather_below = ap.dual ? ap.gather_below : 0;
+    return ap.dual ? 1 : 0;
+}
+
 }  // extern "C"

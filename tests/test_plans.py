@@ -114,3 +114,18 @@ def test_conv_auto_plan_arms_what_the_measurements_say():
     assert plan(64, 256, 28, 256, 3, 1, stride=2)[0] in (0, 1) and plan(16, 64, 28, 64, 5, 2)[0] in (0, 1)
     assert L.dbp_plan_auto_conv2d(1, 1, 2, 2, 1, 5, 5, 1, 0, 0, 1, 1, 0, None, None) == -1
     assert L.dbp_plan_auto_conv2d(4, 8, 8, 8, 8, 3, 3, 1, 1, 0, 0, 0, 0, None, None) == -1
+
+
+def test_fc_auto_plan_arms_the_wide_layer_only():
+    """Fully connected layers: the gather family's fixed cost (streaming the dense operand, writing dW) is what the matrix
+    cores pay too, so the gate is armed only where a layer is wide enough for the nonzero-proportional part to matter:
+    256x4096x16384 (measured: gather wins from ~98.5 % zeros), not the 4096-wide layers of the MLP or 2048^3."""
+    L = _lib()
+    L.dbp_plan_auto_linear.argtypes = [C.c_int64] * 3 + [C.c_int] * 4 + [C.POINTER(C.c_uint64)]
+    L.dbp_plan_auto_linear.restype = C.c_int
+    g = C.c_uint64(7)
+    assert L.dbp_plan_auto_linear(256, 4096, 16384, 0, 1, 1, 0, C.byref(g)) == 1
+    assert 0.005 < g.value / (256 * 16384) < 0.03, g.value
+    for B, in_, out in [(256, 4096, 4096), (256, 784, 4096), (256, 4096, 1000), (2048, 2048, 2048), (64, 784, 300)]:
+        assert L.dbp_plan_auto_linear(B, in_, out, 0, 1, 1, 0, C.byref(g)) == 0 and g.value == 0, (B, in_, out)
+    assert L.dbp_plan_auto_linear(0, 4, 4, 0, 1, 1, 0, None) == -1
