@@ -249,6 +249,18 @@ def test_linear_layer_backward_8bit_and_degenerate():
 @pytest.mark.parametrize("i8", [False, True])
 @pytest.mark.parametrize("path", ["auto", "gather"])
 def test_conv_layer_backward_is_algorithm_1(case, i8, path):
+    _conv_layer_case(case, i8, path, 4.0)
+
+
+@pytest.mark.parametrize("s,flags", [(4.0, [0, 0, 1]), (60.0, [0, 1, 0])])
+def test_conv_layer_backward_through_the_dw_gate(s, flags):
+    # a layer large enough to arm the density gate's dW state: the statistics sum that writes the flags also carries the bias
+    # gradient, and rides in the dX kernel's weight preparation; at s = 60 (> 98 % zeros) dW comes from the gather kernel
+    got = _conv_layer_case((16, 128, 56, 56, 128, 3, 3, 1), False, "auto", s, want_flags=True)
+    assert got == flags
+
+
+def _conv_layer_case(case, i8, path, s_mult, want_flags=False):
     import torch
     import paper_2004_04729_amd as dbp
     from gpu_util import check_products, stream
@@ -270,11 +282,14 @@ def test_conv_layer_backward_is_algorithm_1(case, i8, path):
     pair = torch.zeros(2, dtype=torch.float32, device="cuda:0")
     st = torch.zeros(32, dtype=torch.uint8, device="cuda:0")
     ws = torch.empty(dbp.conv2d_layer_workspace_bytes(N, C, H, Wd, K, R, S, stride, pad, xd), dtype=torch.uint8, device="cuda:0")
-    dbp.dithered_conv2d_layer_backward(_dev(da), _dev(a), _dev(W), _dev(X), xd, N, C, H, Wd, K, R, S, stride, pad, 4.0, 1, 0,
+    off = dbp.format_layout(N * K, P * Q)["scratch_offset"] + 16384 * 16
+    ws[off:off + 12] = 255                                     # the density flags read back as -1 unless a gated call writes them
+    dbp.dithered_conv2d_layer_backward(_dev(da), _dev(a), _dev(W), _dev(X), xd, N, C, H, Wd, K, R, S, stride, pad, s_mult, 1, 0,
                                        codes, dX, dW, db, pair, ws, st, dbp.PATH_AUTO if path == "auto" else dbp.PATH_GATHER, stream())
     torch.cuda.synchronize()
+    flags = [int(v) for v in ws[off:off + 12].cpu().numpy().view(np.int32)]
     dz = O.relu_backward(da, a)
-    step, _ = O.step_size(dz, 4.0)
+    step, _ = O.step_size(dz, s_mult)
     assert pair.cpu().numpy()[0] == np.float32(step)
     k_ref, sref = O.nsd(dz, step, 1)
     assert np.array_equal(codes.cpu().numpy(), k_ref)
@@ -288,3 +303,4 @@ def test_conv_layer_backward_is_algorithm_1(case, i8, path):
         assert np.array_equal(dW.cpu().numpy(), O.conv2d_dw_i8(k_ref, X, R, S, stride=stride, pad=pad))
     else:
         check_products(dW.cpu().numpy(), rW, aW, "conv layer dW")
+    return flags if want_flags else None
